@@ -1,0 +1,194 @@
+/*
+ * dmath.h -- C ABI of the MI355X (gfx950) implementation of one worker's share of dMath's
+ * block-distributed matrix multiply and of convolution lowered to an implicit GEMM.
+ *
+ * Objects (paper, section 2.1 "Managing Persistent Data in the GPUs"): a matrix is split into
+ * non-overlapping dense blocks; the blocks live in GPU memory for the life of the matrix; all
+ * GPU memory comes from a pool so that no driver allocation happens after start-up
+ * (section 1, "pooling of unused GPU memory").  Precisions (section 1, feature d): double,
+ * float, half; half values are widened to float for arithmetic (section 4.2).
+ *
+ * Conventions of every call
+ *   - returns a dmath_status_t, never throws, never aborts; out-parameters are untouched on
+ *     error;
+ *   - "device pointer" = address in GPU memory, "host pointer" = ordinary process memory;
+ *   - compute calls (dmath_gemm, dmath_conv_*) only enqueue work on the context's HIP stream
+ *     and return; argument errors are reported at once, device faults at the next
+ *     synchronising call (dmath_synchronize, dmath_matrix_get) as DMATH_ERR_DEVICE;
+ *   - a context and its handles belong to one host thread.
+ *
+ * Block split rule: a dimension of length n cut into g parts gives part p the index range
+ * [p*ceil(n/g), min(n,(p+1)*ceil(n/g))); a grid that would leave an empty trailing part is
+ * refused (DMATH_ERR_LAYOUT).  Each block is its own pool allocation, dense row-major with
+ * leading dimension equal to its own column count.
+ */
+#ifndef DMATH_H
+#define DMATH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dmath_ctx_s *dmath_ctx_t;       /* opaque, owned by the library */
+typedef struct dmath_matrix_s *dmath_matrix_t; /* opaque, owned by its context */
+
+typedef enum { DMATH_F64 = 0, DMATH_F32 = 1, DMATH_F16 = 2 } dmath_dtype_t;
+typedef enum { DMATH_OP_N = 0, DMATH_OP_T = 1 } dmath_op_t;
+
+typedef enum {
+    DMATH_OK = 0,
+    DMATH_ERR_INVALID_ARG = 1, /* null pointer, bad enum value, non-positive size            */
+    DMATH_ERR_SHAPE = 2,       /* operand shapes do not fit the operation                     */
+    DMATH_ERR_LAYOUT = 3,      /* block grid not allowed (empty trailing block, conv grids)   */
+    DMATH_ERR_DTYPE = 4,       /* precision combination not supported                         */
+    DMATH_ERR_ALIAS = 5,       /* output handle is also an input                              */
+    DMATH_ERR_OOM = 6,         /* the pool cannot satisfy the request                         */
+    DMATH_ERR_UNSUPPORTED = 7, /* valid in principle, not implemented (dilation, groups, ...) */
+    DMATH_ERR_DEVICE = 8       /* a HIP call failed                                           */
+} dmath_status_t;
+
+/*
+ * Context.  `slab` is a device pointer to `slab_bytes` of GPU memory owned by the CALLER (for
+ * example a torch uint8 tensor); the library sub-allocates every block, descriptor table and
+ * workspace from it and never frees or reallocates it (section 1: the pool replaces driver
+ * allocations).  `hip_stream` is the caller's hipStream_t (NULL = the default stream); all
+ * device work of this context is enqueued on it.  dmath_init itself touches neither the slab
+ * nor the device.  The slab must outlive the context.
+ */
+dmath_status_t dmath_init(dmath_ctx_t *ctx, void *slab, size_t slab_bytes, void *hip_stream);
+
+/* Destroys every matrix and cached plan of the context, then the context. */
+dmath_status_t dmath_finalize(dmath_ctx_t ctx);
+
+/*
+ * Creates a rows x cols matrix of `dtype` cut into a grid_rows x grid_cols grid of blocks
+ * (section 2.1).  Contents are uninitialised.  DMATH_ERR_OOM if the pool is exhausted (nothing
+ * is leaked in that case).
+ */
+dmath_status_t dmath_matrix_create(dmath_ctx_t ctx, int64_t rows, int64_t cols, int32_t grid_rows,
+                                   int32_t grid_cols, dmath_dtype_t dtype, dmath_matrix_t *out);
+
+/* Returns the blocks to the pool.  Reuse of that memory is ordered after work already enqueued
+ * on the context's stream.  Cached plans that mention the matrix are dropped. */
+dmath_status_t dmath_matrix_destroy(dmath_matrix_t m);
+
+/*
+ * Copies between a monolithic row-major HOST array (leading dimension ld_elems >= cols, in
+ * elements of the matrix's dtype; fp16 as raw IEEE binary16 bits) and the blocks.  Both calls
+ * run on the context's stream and return after the copy has completed.  Not part of the timed
+ * path: operands are meant to stay resident (section 2.1).
+ */
+dmath_status_t dmath_matrix_set(dmath_matrix_t m, const void *host, int64_t ld_elems);
+dmath_status_t dmath_matrix_get(dmath_matrix_t m, void *host, int64_t ld_elems);
+
+/* Shape and grid of a matrix; any out-pointer may be NULL. */
+dmath_status_t dmath_matrix_info(dmath_matrix_t m, int64_t *rows, int64_t *cols,
+                                 int32_t *grid_rows, int32_t *grid_cols, dmath_dtype_t *dtype);
+
+/* Device pointer, size and leading dimension (elements) of block (bi, bj).  The memory stays
+ * owned by the matrix. */
+dmath_status_t dmath_matrix_block(dmath_matrix_t m, int32_t bi, int32_t bj, void **dev_ptr,
+                                  int64_t *rows, int64_t *cols, int64_t *ld);
+
+/*
+ * C <- alpha * op(A) * op(B) + beta * C            (abstract: "matrix multiplication";
+ * section 1: the back-propagation variants dW = X^T dY (T,N) and dX = dY W^T (N,T))
+ *
+ * op(X) = X or X^T; a transposed operand is never physically transposed: block (i,k) of op(A)
+ * is the transpose of stored block (k,i).  The three block grids are independent of one
+ * another (section 3.2, data distribution independence): where partitions do not line up the
+ * scheduler cuts tiles at every block boundary of every operand.
+ *
+ * Precisions: A and B share a dtype; C has the same dtype, except that F16 inputs may write an
+ * F32 or an F16 C.  F16 products are exact and are accumulated in fp32, alpha/beta applied in
+ * fp32, one final round-to-nearest-even when C is F16 (section 4.2, mixed mode).  F32 uses fp32
+ * FMA, F64 fp64 FMA.  alpha and beta are narrowed to the accumulation type.
+ * beta == 0: the old C is not read (NaNs in it do not propagate); alpha == 0: A and B are not
+ * read.
+ *
+ * Errors: DMATH_ERR_SHAPE (inner/outer sizes differ), DMATH_ERR_DTYPE, DMATH_ERR_ALIAS (C is
+ * A or B), DMATH_ERR_INVALID_ARG (handles of different contexts, bad op), DMATH_ERR_OOM (no
+ * room for the plan tables or a split-K workspace).
+ * Results are bitwise reproducible from run to run (split-K partial sums are reduced in a
+ * fixed order).
+ */
+dmath_status_t dmath_gemm(dmath_ctx_t ctx, dmath_op_t transA, dmath_op_t transB, double alpha,
+                          dmath_matrix_t A, dmath_matrix_t B, double beta, dmath_matrix_t C);
+
+/* What the scheduler decided for a GEMM: filled by dmath_gemm_plan_info without enqueuing
+ * anything (host logic only; usable without a GPU). */
+typedef struct {
+    int64_t m, n, k;
+    int32_t m_segments, n_segments, k_segments; /* after refining against every operand's grid */
+    int32_t tile_m, tile_n, tile_k;
+    int32_t tiles;    /* C tiles                                                       */
+    int32_t split_k;  /* partial sums per C tile (1 = none)                            */
+    int32_t kernel;   /* 0 = guarded generic kernel, >0 = a specialised kernel id      */
+    int32_t cached;   /* 1 if the plan was already in the cache                        */
+    uint64_t workspace_bytes;
+} dmath_plan_info_t;
+
+/* Builds (or finds in the cache) the plan dmath_gemm would use and describes it.  Same
+ * argument checks and errors as dmath_gemm.  Section 3.3: the metadata of an operation is
+ * computed once and remembered. */
+dmath_status_t dmath_gemm_plan_info(dmath_ctx_t ctx, dmath_op_t transA, dmath_op_t transB,
+                                    dmath_matrix_t A, dmath_matrix_t B, dmath_matrix_t C,
+                                    dmath_plan_info_t *info);
+
+/*
+ * Convolution as an implicit GEMM (abstract: "convolutions"; never materialises the lowered
+ * matrix).  Tensors are matrices in the blob view of the Caffe family (section 4): each row is
+ * one image or one filter, NCHW inside the row:
+ *     X, dX : [n x c*h*w]      F, dF : [k x c*r*s]      Y, dY : [n x k*oh*ow]
+ * with oh = (h + 2*pad_h - r)/stride_h + 1, ow likewise.  Cross-correlation, no filter flip:
+ *     Y[n,k,oh,ow] = sum_{c,r,s} X[n,c,oh*stride_h+r-pad_h, ow*stride_w+s-pad_w] * F[k,c,r,s]
+ * with out-of-range input coordinates contributing zero.
+ * Block grids: g x 1 (rows = images or filters split over blocks) for every tensor; a grid
+ * with more than one block column is DMATH_ERR_LAYOUT.  Precisions and alpha/beta as in
+ * dmath_gemm (F16 tensors may produce F32 or F16 results).
+ */
+typedef struct {
+    int32_t n, c, h, w;     /* batch, input channels, input height and width */
+    int32_t k, r, s;        /* output channels, filter height and width      */
+    int32_t pad_h, pad_w, stride_h, stride_w;
+} dmath_conv_desc_t;
+
+/* Y <- alpha * conv(X, F) + beta * Y */
+dmath_status_t dmath_conv_fwd(dmath_ctx_t ctx, const dmath_conv_desc_t *desc, double alpha,
+                              dmath_matrix_t X, dmath_matrix_t F, double beta, dmath_matrix_t Y);
+
+/* dF[k,c,r,s] <- alpha * sum_{n,oh,ow} dY[n,k,oh,ow] * X[n,c,oh*sh+r-ph,ow*sw+s-pw] + beta * dF
+ * (weight gradient of back-propagation, section 1).  Uses a split-K workspace from the pool
+ * with a fixed-order reduction. */
+dmath_status_t dmath_conv_bwd_filter(dmath_ctx_t ctx, const dmath_conv_desc_t *desc, double alpha,
+                                     dmath_matrix_t X, dmath_matrix_t dY, double beta,
+                                     dmath_matrix_t dF);
+
+/* dX[n,c,h,w] <- alpha * sum over (k,r,s,oh,ow) with oh*sh+r-ph == h and ow*sw+s-pw == w of
+ * dY[n,k,oh,ow] * F[k,c,r,s] + beta * dX   (data gradient). */
+dmath_status_t dmath_conv_bwd_data(dmath_ctx_t ctx, const dmath_conv_desc_t *desc, double alpha,
+                                   dmath_matrix_t dY, dmath_matrix_t F, double beta,
+                                   dmath_matrix_t dX);
+
+/* Kernel selection: 0 = automatic (specialised kernels where their preconditions hold),
+ * 1 = always the guarded generic kernel (for testing and debugging).  Drops cached plans. */
+dmath_status_t dmath_set_kernel_policy(dmath_ctx_t ctx, int32_t policy);
+
+/* Waits for all work enqueued on the context's stream. */
+dmath_status_t dmath_synchronize(dmath_ctx_t ctx);
+
+/* Pool accounting in bytes: currently allocated, the maximum ever allocated, slab size; any
+ * out-pointer may be NULL.  The number of driver allocations made by the library is zero. */
+dmath_status_t dmath_pool_stats(dmath_ctx_t ctx, size_t *in_use, size_t *high_water,
+                                size_t *capacity);
+
+/* Static string naming a status code. */
+const char *dmath_status_string(dmath_status_t s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DMATH_H */

@@ -1,0 +1,289 @@
+// C ABI of dmath.h: argument checks, handle bookkeeping, host<->device copies.  All arithmetic
+// of the method runs in the kernels; nothing here computes on matrix elements.
+#include <hip/hip_runtime_api.h>
+
+#include <new>
+
+#include "context.hpp"
+
+using namespace dm;
+
+namespace {
+
+bool valid_dtype(int d) { return d == DMATH_F64 || d == DMATH_F32 || d == DMATH_F16; }
+bool valid_op(int o) { return o == DMATH_OP_N || o == DMATH_OP_T; }
+
+bool owns(dmath_ctx_s* ctx, dmath_matrix_s* m) { return m && ctx && ctx->matrices.count(m); }
+
+// C may equal the input dtype; F16 inputs may also write F32.
+bool dtype_combo_ok(dmath_dtype_t in_a, dmath_dtype_t in_b, dmath_dtype_t out)
+{
+    if (in_a != in_b) return false;
+    if (out == in_a) return true;
+    return in_a == DMATH_F16 && out == DMATH_F32;
+}
+
+dmath_status_t check_gemm(dmath_ctx_s* ctx, int ta, int tb, dmath_matrix_s* A, dmath_matrix_s* B,
+                          dmath_matrix_s* C)
+{
+    if (!ctx || !A || !B || !C || !valid_op(ta) || !valid_op(tb)) return DMATH_ERR_INVALID_ARG;
+    if (!owns(ctx, A) || !owns(ctx, B) || !owns(ctx, C)) return DMATH_ERR_INVALID_ARG;
+    if (C == A || C == B) return DMATH_ERR_ALIAS;
+    if (!dtype_combo_ok(A->dtype, B->dtype, C->dtype)) return DMATH_ERR_DTYPE;
+    int64_t am = ta ? A->cols : A->rows, ak = ta ? A->rows : A->cols;
+    int64_t bk = tb ? B->cols : B->rows, bn = tb ? B->rows : B->cols;
+    if (ak != bk || am != C->rows || bn != C->cols) return DMATH_ERR_SHAPE;
+    return DMATH_OK;
+}
+
+dmath_status_t copy_blocks(dmath_matrix_s* m, void* host, int64_t ld, bool to_device)
+{
+    if (!m || !host) return DMATH_ERR_INVALID_ARG;
+    if (ld < m->cols) return DMATH_ERR_INVALID_ARG;
+    const size_t es = elem_size(m->dtype);
+    hipStream_t st = m->ctx->stream;
+    for (int32_t bi = 0; bi < m->rsplit.g; ++bi)
+        for (int32_t bj = 0; bj < m->csplit.g; ++bj) {
+            int64_t r = m->rsplit.len(bi), c = m->csplit.len(bj);
+            char* h = static_cast<char*>(host) + (m->rsplit.lo(bi) * ld + m->csplit.lo(bj)) * es;
+            void* d = m->block(bi, bj);
+            hipError_t e = to_device
+                               ? hipMemcpy2DAsync(d, c * es, h, ld * es, c * es, r, hipMemcpyHostToDevice, st)
+                               : hipMemcpy2DAsync(h, ld * es, d, c * es, c * es, r, hipMemcpyDeviceToHost, st);
+            if (e != hipSuccess) return DMATH_ERR_DEVICE;
+        }
+    return hipStreamSynchronize(st) == hipSuccess ? DMATH_OK : DMATH_ERR_DEVICE;
+}
+
+dmath_status_t check_conv_desc(const dmath_conv_desc_t* d, int64_t* oh, int64_t* ow)
+{
+    if (!d) return DMATH_ERR_INVALID_ARG;
+    if (d->n <= 0 || d->c <= 0 || d->h <= 0 || d->w <= 0 || d->k <= 0 || d->r <= 0 || d->s <= 0 ||
+        d->pad_h < 0 || d->pad_w < 0 || d->stride_h <= 0 || d->stride_w <= 0)
+        return DMATH_ERR_INVALID_ARG;
+    int64_t hh = (int64_t)d->h + 2 * d->pad_h - d->r, ww = (int64_t)d->w + 2 * d->pad_w - d->s;
+    if (hh < 0 || ww < 0) return DMATH_ERR_SHAPE;
+    *oh = hh / d->stride_h + 1;
+    *ow = ww / d->stride_w + 1;
+    return DMATH_OK;
+}
+
+// in1, in2: the two tensors that are read; res: the tensor that is written.
+dmath_status_t conv_call(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t* d, double alpha,
+                         dmath_matrix_s* X, dmath_matrix_s* F, dmath_matrix_s* Y, double beta)
+{
+    if (!ctx || !X || !F || !Y) return DMATH_ERR_INVALID_ARG;
+    int64_t oh, ow;
+    dmath_status_t st = check_conv_desc(d, &oh, &ow);
+    if (st != DMATH_OK) return st;
+    if (!owns(ctx, X) || !owns(ctx, F) || !owns(ctx, Y)) return DMATH_ERR_INVALID_ARG;
+    if (X == F || X == Y || F == Y) return DMATH_ERR_ALIAS;
+    dmath_matrix_s* res = mode == CONV_FWD ? Y : mode == CONV_BWD_FILTER ? F : X;
+    dmath_matrix_s* in1 = mode == CONV_FWD ? X : mode == CONV_BWD_FILTER ? X : Y;
+    dmath_matrix_s* in2 = mode == CONV_FWD ? F : mode == CONV_BWD_FILTER ? Y : F;
+    if (!dtype_combo_ok(in1->dtype, in2->dtype, res->dtype)) return DMATH_ERR_DTYPE;
+    const int64_t chw = (int64_t)d->c * d->h * d->w, crs = (int64_t)d->c * d->r * d->s;
+    const int64_t kow = (int64_t)d->k * oh * ow;
+    if (X->rows != d->n || X->cols != chw || F->rows != d->k || F->cols != crs ||
+        Y->rows != d->n || Y->cols != kow)
+        return DMATH_ERR_SHAPE;
+    if (X->csplit.g != 1 || F->csplit.g != 1 || Y->csplit.g != 1) return DMATH_ERR_LAYOUT;
+    if (chw >= (1ll << 31) || kow >= (1ll << 31) || crs >= (1ll << 31) ||
+        (int64_t)d->n * oh * ow >= (1ll << 31) || (int64_t)d->n * d->h * d->w >= (1ll << 31))
+        return DMATH_ERR_UNSUPPORTED;
+    ConvPlan* plan = nullptr;
+    st = get_conv_plan(ctx, mode, d, X, F, Y, &plan);
+    if (st != DMATH_OK) return st;
+    return launch_conv(*plan, mode, alpha, beta, ctx->stream) == hipSuccess ? DMATH_OK
+                                                                            : DMATH_ERR_DEVICE;
+}
+
+}  // namespace
+
+extern "C" {
+
+dmath_status_t dmath_init(dmath_ctx_t* ctx, void* slab, size_t slab_bytes, void* hip_stream)
+{
+    if (!ctx || !slab || slab_bytes < Pool::kAlign * 2) return DMATH_ERR_INVALID_ARG;
+    dmath_ctx_s* c = new (std::nothrow) dmath_ctx_s(slab, slab_bytes, static_cast<hipStream_t>(hip_stream));
+    if (!c) return DMATH_ERR_OOM;
+    *ctx = c;
+    return DMATH_OK;
+}
+
+dmath_status_t dmath_finalize(dmath_ctx_t ctx)
+{
+    if (!ctx) return DMATH_ERR_INVALID_ARG;
+    drop_all_plans(ctx);
+    for (dmath_matrix_s* m : ctx->matrices) delete m;
+    delete ctx;
+    return DMATH_OK;
+}
+
+dmath_status_t dmath_matrix_create(dmath_ctx_t ctx, int64_t rows, int64_t cols, int32_t grid_rows,
+                                   int32_t grid_cols, dmath_dtype_t dtype, dmath_matrix_t* out)
+{
+    if (!ctx || !out || rows <= 0 || cols <= 0 || grid_rows <= 0 || grid_cols <= 0 ||
+        !valid_dtype(dtype))
+        return DMATH_ERR_INVALID_ARG;
+    if (rows >= (1ll << 31) || cols >= (1ll << 31)) return DMATH_ERR_UNSUPPORTED;
+    Split rs(rows, grid_rows), cs(cols, grid_cols);
+    if (!rs.valid() || !cs.valid()) return DMATH_ERR_LAYOUT;
+    auto* m = new (std::nothrow) dmath_matrix_s;
+    if (!m) return DMATH_ERR_OOM;
+    m->ctx = ctx;
+    m->rows = rows;
+    m->cols = cols;
+    m->rsplit = rs;
+    m->csplit = cs;
+    m->dtype = dtype;
+    const size_t es = elem_size(dtype);
+    for (int32_t bi = 0; bi < grid_rows; ++bi)
+        for (int32_t bj = 0; bj < grid_cols; ++bj) {
+            void* p = ctx->pool.alloc((size_t)rs.len(bi) * cs.len(bj) * es);
+            if (!p) {
+                for (void* q : m->blocks) ctx->pool.free(q);
+                delete m;
+                return DMATH_ERR_OOM;
+            }
+            m->blocks.push_back(p);
+        }
+    m->id = ctx->next_id++;
+    ctx->matrices.insert(m);
+    *out = m;
+    return DMATH_OK;
+}
+
+dmath_status_t dmath_matrix_destroy(dmath_matrix_t m)
+{
+    if (!m || !m->ctx || !m->ctx->matrices.count(m)) return DMATH_ERR_INVALID_ARG;
+    dmath_ctx_s* ctx = m->ctx;
+    drop_plans_using(ctx, m->id);
+    for (void* p : m->blocks) ctx->pool.free(p);
+    ctx->matrices.erase(m);
+    delete m;
+    return DMATH_OK;
+}
+
+dmath_status_t dmath_matrix_set(dmath_matrix_t m, const void* host, int64_t ld_elems)
+{
+    return copy_blocks(m, const_cast<void*>(host), ld_elems, true);
+}
+
+dmath_status_t dmath_matrix_get(dmath_matrix_t m, void* host, int64_t ld_elems)
+{
+    return copy_blocks(m, host, ld_elems, false);
+}
+
+dmath_status_t dmath_matrix_info(dmath_matrix_t m, int64_t* rows, int64_t* cols, int32_t* grid_rows,
+                                 int32_t* grid_cols, dmath_dtype_t* dtype)
+{
+    if (!m) return DMATH_ERR_INVALID_ARG;
+    if (rows) *rows = m->rows;
+    if (cols) *cols = m->cols;
+    if (grid_rows) *grid_rows = m->rsplit.g;
+    if (grid_cols) *grid_cols = m->csplit.g;
+    if (dtype) *dtype = m->dtype;
+    return DMATH_OK;
+}
+
+dmath_status_t dmath_matrix_block(dmath_matrix_t m, int32_t bi, int32_t bj, void** dev_ptr,
+                                  int64_t* rows, int64_t* cols, int64_t* ld)
+{
+    if (!m || bi < 0 || bj < 0 || bi >= m->rsplit.g || bj >= m->csplit.g)
+        return DMATH_ERR_INVALID_ARG;
+    if (dev_ptr) *dev_ptr = m->block(bi, bj);
+    if (rows) *rows = m->rsplit.len(bi);
+    if (cols) *cols = m->csplit.len(bj);
+    if (ld) *ld = m->csplit.len(bj);
+    return DMATH_OK;
+}
+
+dmath_status_t dmath_gemm(dmath_ctx_t ctx, dmath_op_t transA, dmath_op_t transB, double alpha,
+                          dmath_matrix_t A, dmath_matrix_t B, double beta, dmath_matrix_t C)
+{
+    dmath_status_t st = check_gemm(ctx, transA, transB, A, B, C);
+    if (st != DMATH_OK) return st;
+    GemmPlan* plan = nullptr;
+    st = get_gemm_plan(ctx, transA, transB, A, B, C, true, &plan, nullptr);
+    if (st != DMATH_OK) return st;
+    return launch_gemm(*plan, alpha, beta, ctx->stream) == hipSuccess ? DMATH_OK : DMATH_ERR_DEVICE;
+}
+
+dmath_status_t dmath_gemm_plan_info(dmath_ctx_t ctx, dmath_op_t transA, dmath_op_t transB,
+                                    dmath_matrix_t A, dmath_matrix_t B, dmath_matrix_t C,
+                                    dmath_plan_info_t* info)
+{
+    if (!info) return DMATH_ERR_INVALID_ARG;
+    dmath_status_t st = check_gemm(ctx, transA, transB, A, B, C);
+    if (st != DMATH_OK) return st;
+    GemmPlan* plan = nullptr;
+    bool cached = false;
+    st = get_gemm_plan(ctx, transA, transB, A, B, C, false, &plan, &cached);
+    if (st != DMATH_OK) return st;
+    *info = plan->info;
+    info->cached = cached ? 1 : 0;
+    return DMATH_OK;
+}
+
+dmath_status_t dmath_conv_fwd(dmath_ctx_t ctx, const dmath_conv_desc_t* desc, double alpha,
+                              dmath_matrix_t X, dmath_matrix_t F, double beta, dmath_matrix_t Y)
+{
+    return conv_call(ctx, CONV_FWD, desc, alpha, X, F, Y, beta);
+}
+
+dmath_status_t dmath_conv_bwd_filter(dmath_ctx_t ctx, const dmath_conv_desc_t* desc, double alpha,
+                                     dmath_matrix_t X, dmath_matrix_t dY, double beta,
+                                     dmath_matrix_t dF)
+{
+    return conv_call(ctx, CONV_BWD_FILTER, desc, alpha, X, dF, dY, beta);
+}
+
+dmath_status_t dmath_conv_bwd_data(dmath_ctx_t ctx, const dmath_conv_desc_t* desc, double alpha,
+                                   dmath_matrix_t dY, dmath_matrix_t F, double beta,
+                                   dmath_matrix_t dX)
+{
+    return conv_call(ctx, CONV_BWD_DATA, desc, alpha, dX, F, dY, beta);
+}
+
+dmath_status_t dmath_set_kernel_policy(dmath_ctx_t ctx, int32_t policy)
+{
+    if (!ctx || policy < 0 || policy > 1) return DMATH_ERR_INVALID_ARG;
+    ctx->policy = policy;
+    drop_all_plans(ctx);
+    return DMATH_OK;
+}
+
+dmath_status_t dmath_synchronize(dmath_ctx_t ctx)
+{
+    if (!ctx) return DMATH_ERR_INVALID_ARG;
+    return hipStreamSynchronize(ctx->stream) == hipSuccess ? DMATH_OK : DMATH_ERR_DEVICE;
+}
+
+dmath_status_t dmath_pool_stats(dmath_ctx_t ctx, size_t* in_use, size_t* high_water,
+                                size_t* capacity)
+{
+    if (!ctx) return DMATH_ERR_INVALID_ARG;
+    if (in_use) *in_use = ctx->pool.in_use();
+    if (high_water) *high_water = ctx->pool.high_water();
+    if (capacity) *capacity = ctx->pool.capacity();
+    return DMATH_OK;
+}
+
+const char* dmath_status_string(dmath_status_t s)
+{
+    switch (s) {
+    case DMATH_OK: return "DMATH_OK";
+    case DMATH_ERR_INVALID_ARG: return "DMATH_ERR_INVALID_ARG";
+    case DMATH_ERR_SHAPE: return "DMATH_ERR_SHAPE";
+    case DMATH_ERR_LAYOUT: return "DMATH_ERR_LAYOUT";
+    case DMATH_ERR_DTYPE: return "DMATH_ERR_DTYPE";
+    case DMATH_ERR_ALIAS: return "DMATH_ERR_ALIAS";
+    case DMATH_ERR_OOM: return "DMATH_ERR_OOM";
+    case DMATH_ERR_UNSUPPORTED: return "DMATH_ERR_UNSUPPORTED";
+    case DMATH_ERR_DEVICE: return "DMATH_ERR_DEVICE";
+    }
+    return "DMATH_ERR_UNKNOWN";
+}
+
+}  // extern "C"

@@ -1,0 +1,125 @@
+// Host-side objects behind the opaque handles of dmath.h.
+#pragma once
+#include <hip/hip_runtime_api.h>
+
+#include <cstdint>
+#include <map>
+#include <memory>
+#include <set>
+#include <tuple>
+#include <vector>
+
+#include "../../include/dmath.h"
+#include "pool.hpp"
+#include "tables.hpp"
+
+namespace dm {
+
+inline size_t elem_size(dmath_dtype_t d) { return d == DMATH_F64 ? 8 : d == DMATH_F32 ? 4 : 2; }
+
+// Split rule of a dimension of length n into g parts (see dmath.h).
+struct Split {
+    int64_t n = 0, step = 0;
+    int32_t g = 0;
+    Split() = default;
+    Split(int64_t n_, int32_t g_) : n(n_), step((n_ + g_ - 1) / g_), g(g_) {}
+    bool valid() const { return n > 0 && g > 0 && (int64_t)(g - 1) * step < n; }
+    int64_t lo(int32_t p) const { return (int64_t)p * step; }
+    int64_t hi(int32_t p) const { return lo(p) + step < n ? lo(p) + step : n; }
+    int64_t len(int32_t p) const { return hi(p) - lo(p); }
+    int32_t part(int64_t i) const { return (int32_t)(i / step); }
+};
+
+}  // namespace dm
+
+struct dmath_matrix_s {
+    dmath_ctx_s* ctx = nullptr;
+    uint64_t id = 0;
+    int64_t rows = 0, cols = 0;
+    dm::Split rsplit, csplit;
+    dmath_dtype_t dtype = DMATH_F32;
+    std::vector<void*> blocks;  // grid row-major
+    void* block(int32_t bi, int32_t bj) const { return blocks[(size_t)bi * csplit.g + bj]; }
+};
+
+namespace dm {
+
+enum KernelId : int32_t {
+    KERNEL_GENERIC = 0,
+    KERNEL_F32_128 = 1,
+    KERNEL_F16_256 = 2,
+    KERNEL_F64_128 = 3,
+};
+
+struct GemmPlan {
+    std::vector<uint64_t> uses;  // matrix ids
+    GemmTables t{};
+    void* dev_tables = nullptr;
+    void* workspace = nullptr;
+    dmath_plan_info_t info{};
+    dmath_dtype_t in_dtype = DMATH_F32, out_dtype = DMATH_F32;
+};
+
+enum ConvMode : int32_t { CONV_FWD = 0, CONV_BWD_FILTER = 1, CONV_BWD_DATA = 2 };
+
+struct ConvPlan {
+    std::vector<uint64_t> uses;
+    ConvTables t{};
+    void* dev_tables = nullptr;
+    void* workspace = nullptr;
+    int32_t kernel = 0;
+    dmath_dtype_t in_dtype = DMATH_F16, out_dtype = DMATH_F32;
+};
+
+using GemmKey = std::tuple<uint64_t, uint64_t, uint64_t, int, int>;
+using ConvKey = std::tuple<uint64_t, uint64_t, uint64_t, int, std::vector<int32_t>>;
+
+// Tile shape / kernel / split-K decision for a GEMM whose segments are known.
+struct GemmChoice {
+    int32_t kernel = KERNEL_GENERIC;
+    int32_t tile_m = 64, tile_n = 64, tile_k = 16;
+    int32_t split_k = 1;
+};
+
+}  // namespace dm
+
+struct dmath_ctx_s {
+    dm::Pool pool;
+    hipStream_t stream;
+    uint64_t next_id = 1;
+    int32_t policy = 0;
+    std::set<dmath_matrix_s*> matrices;
+    std::map<dm::GemmKey, std::unique_ptr<dm::GemmPlan>> gemm_plans;
+    std::map<dm::ConvKey, std::unique_ptr<dm::ConvPlan>> conv_plans;
+    dmath_ctx_s(void* slab, size_t bytes, hipStream_t s) : pool(slab, bytes), stream(s) {}
+};
+
+namespace dm {
+
+// plan.cpp
+dmath_status_t get_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_matrix_s* A,
+                             dmath_matrix_s* B, dmath_matrix_s* C, bool upload, GemmPlan** out,
+                             bool* was_cached);
+dmath_status_t get_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t* d,
+                             dmath_matrix_s* X, dmath_matrix_s* F, dmath_matrix_s* Y,
+                             ConvPlan** out);
+void drop_plans_using(dmath_ctx_s* ctx, uint64_t matrix_id);
+void drop_all_plans(dmath_ctx_s* ctx);
+
+// kernels (launch.hip)
+hipError_t launch_gemm(const GemmPlan& p, double alpha, double beta, hipStream_t stream);
+hipError_t launch_conv(const ConvPlan& p, int mode, double alpha, double beta, hipStream_t stream);
+// Picks kernel, tile shape and split-K; written next to the kernels whose preconditions it checks.
+struct SegView {
+    int64_t M, N, K;
+    const std::vector<int64_t>* mlen;
+    const std::vector<int64_t>* nlen;
+    const std::vector<int64_t>* klen;
+    bool a_kcontig, b_kcontig;
+    bool aligned16;  // every panel origin and leading dimension is a multiple of 16 bytes
+    dmath_dtype_t in_dtype, out_dtype;
+    int32_t policy;
+};
+GemmChoice choose_gemm(const SegView& v);
+
+}  // namespace dm

@@ -1,0 +1,406 @@
+// Guarded generic kernels: every precision, every transpose combination, ragged tiles, any
+// alignment, every convolution geometry.  They are the fallback of the specialised kernels
+// and the reference inside the library for them: element-wise guarded loads into LDS, MFMA on
+// 64x64x16 workgroup tiles (4 wavefronts, 32x32 each), fused alpha/beta epilogue.
+//
+// Operation: C <- alpha * op(A) * op(B) + beta * C over block grids (paper abstract and
+// section 2.1), and the convolutions as implicit GEMMs whose A or B operand is gathered from
+// the NCHW tensor on the fly.
+#include <hip/hip_runtime.h>
+
+#include "context.hpp"
+#include "mfma.hpp"
+
+namespace dm {
+
+namespace {
+
+constexpr int GT = 64;   // tile edge
+constexpr int GK = 16;   // k-step
+constexpr int GTHREADS = 256;
+
+template <class T> struct Traits;
+template <> struct Traits<float> {
+    using acc_t = float;
+    static constexpr int kStride = GK + 1;
+    static constexpr int kAccRegs = 16;
+};
+template <> struct Traits<_Float16> {
+    using acc_t = float;
+    static constexpr int kStride = GK + 8;  // rows stay 16-byte aligned
+    static constexpr int kAccRegs = 16;
+};
+template <> struct Traits<double> {
+    using acc_t = double;
+    static constexpr int kStride = GK + 1;
+    static constexpr int kAccRegs = 16;  // 2x2 tiles of 16x16, 4 registers each
+};
+
+template <class T> struct Acc { typename Traits<T>::acc_t v[16]; };
+
+// One k-step of the workgroup tile out of LDS.  As/Bs: [64][kStride], k contiguous.
+__device__ __forceinline__ void mma_step(const float* As, const float* Bs, int wm, int wn, int lane,
+                                         Acc<float>& acc)
+{
+    v16f c;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) c[r] = acc.v[r];
+    const float* ap = As + (wm * 32 + (lane & 31)) * Traits<float>::kStride + (lane >> 5);
+    const float* bp = Bs + (wn * 32 + (lane & 31)) * Traits<float>::kStride + (lane >> 5);
+#pragma unroll
+    for (int s = 0; s < GK / 2; ++s) c = mfma_f32_32x32x2(ap[2 * s], bp[2 * s], c);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc.v[r] = c[r];
+}
+
+__device__ __forceinline__ void mma_step(const _Float16* As, const _Float16* Bs, int wm, int wn,
+                                         int lane, Acc<_Float16>& acc)
+{
+    v16f c;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) c[r] = acc.v[r];
+    const _Float16* ap = As + (wm * 32 + (lane & 31)) * Traits<_Float16>::kStride + 8 * (lane >> 5);
+    const _Float16* bp = Bs + (wn * 32 + (lane & 31)) * Traits<_Float16>::kStride + 8 * (lane >> 5);
+    v8h a = *reinterpret_cast<const v8h*>(ap);
+    v8h b = *reinterpret_cast<const v8h*>(bp);
+    c = mfma_f16_32x32x16(a, b, c);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc.v[r] = c[r];
+}
+
+__device__ __forceinline__ void mma_step(const double* As, const double* Bs, int wm, int wn, int lane,
+                                         Acc<double>& acc)
+{
+#pragma unroll
+    for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+        for (int tj = 0; tj < 2; ++tj) {
+            v4d c;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) c[r] = acc.v[(ti * 2 + tj) * 4 + r];
+            const double* ap = As + (wm * 32 + ti * 16 + (lane & 15)) * Traits<double>::kStride + (lane >> 4);
+            const double* bp = Bs + (wn * 32 + tj * 16 + (lane & 15)) * Traits<double>::kStride + (lane >> 4);
+#pragma unroll
+            for (int s = 0; s < GK / 4; ++s) c = mfma_f64_16x16x4(ap[4 * s], bp[4 * s], c);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc.v[(ti * 2 + tj) * 4 + r] = c[r];
+        }
+}
+
+// (row, column) inside the wavefront's 32x32 tile of accumulator register r.
+template <class T> __device__ __forceinline__ void acc_pos(int lane, int r, int& i, int& j)
+{
+    i = acc32_row(lane, r);
+    j = acc32_col(lane);
+}
+template <> __device__ __forceinline__ void acc_pos<double>(int lane, int r, int& i, int& j)
+{
+    int t = r >> 2, ti = t >> 1, tj = t & 1;
+    i = ti * 16 + acc16d_row(lane, r & 3);
+    j = tj * 16 + acc16d_col(lane);
+}
+
+template <class TC, class AccT>
+__device__ __forceinline__ void epilogue_store(TC* p, AccT acc, AccT alpha, AccT beta)
+{
+    AccT v = alpha * acc;
+    if (beta != AccT(0)) v += beta * static_cast<AccT>(*p);
+    *p = static_cast<TC>(v);
+}
+
+// ---------------------------------------------------------------------------------------
+// GEMM over the segment tables
+// ---------------------------------------------------------------------------------------
+template <class T, class TC>
+__global__ __launch_bounds__(GTHREADS) void gemm_generic_kernel(GemmTables t, double alpha_d,
+                                                                double beta_d)
+{
+    using AccT = typename Traits<T>::acc_t;
+    constexpr int S = Traits<T>::kStride;
+    __shared__ __attribute__((aligned(16))) T As[GT * S];
+    __shared__ __attribute__((aligned(16))) T Bs[GT * S];
+
+    const Tile tile = t.tiles[blockIdx.x];
+    const int split = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
+    Acc<T> acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc.v[r] = AccT(0);
+
+    const int ks0 = t.ksplit[split], ks1 = t.ksplit[split + 1];
+    for (int ks = ks0; ks < ks1; ++ks) {
+        const Panel pa = t.a[tile.mseg * t.n_kseg + ks];
+        const Panel pb = t.b[ks * t.n_nseg + tile.nseg];
+        const T* a = static_cast<const T*>(pa.ptr);
+        const T* b = static_cast<const T*>(pb.ptr);
+        const int64_t a_smn = t.a_kcontig ? pa.ld : 1, a_sk = t.a_kcontig ? 1 : pa.ld;
+        const int64_t b_smn = t.b_kcontig ? pb.ld : 1, b_sk = t.b_kcontig ? 1 : pb.ld;
+        const int kl = t.klen[ks];
+        for (int k0 = 0; k0 < kl; k0 += GK) {
+#pragma unroll
+            for (int q = 0; q < GT * GK / GTHREADS; ++q) {
+                int e = q * GTHREADS + tid;
+                int row, kk;
+                if (t.a_kcontig) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
+                T v = T(0);
+                if (row < tile.m_len && k0 + kk < kl)
+                    v = a[(int64_t)(tile.m_off + row) * a_smn + (int64_t)(k0 + kk) * a_sk];
+                As[row * S + kk] = v;
+                if (t.b_kcontig) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
+                v = T(0);
+                if (row < tile.n_len && k0 + kk < kl)
+                    v = b[(int64_t)(tile.n_off + row) * b_smn + (int64_t)(k0 + kk) * b_sk];
+                Bs[row * S + kk] = v;
+            }
+            __syncthreads();
+            mma_step(As, Bs, wm, wn, lane, acc);
+            __syncthreads();
+        }
+    }
+
+    if (t.split_k > 1) {
+        AccT* ws = static_cast<AccT*>(t.workspace) + (int64_t)split * t.M * t.N;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            int i, j;
+            acc_pos<T>(lane, r, i, j);
+            i += wm * 32;
+            j += wn * 32;
+            if (i < tile.m_len && j < tile.n_len)
+                ws[(int64_t)(tile.m_glob + i) * t.N + tile.n_glob + j] = acc.v[r];
+        }
+        return;
+    }
+    const Panel pc = t.c[tile.mseg * t.n_nseg + tile.nseg];
+    TC* c = static_cast<TC*>(const_cast<void*>(pc.ptr));
+    const AccT alpha = static_cast<AccT>(alpha_d), beta = static_cast<AccT>(beta_d);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        int i, j;
+        acc_pos<T>(lane, r, i, j);
+        i += wm * 32;
+        j += wn * 32;
+        if (i < tile.m_len && j < tile.n_len)
+            epilogue_store(c + (int64_t)(tile.m_off + i) * pc.ld + tile.n_off + j, acc.v[r], alpha, beta);
+    }
+}
+
+// Fixed-order sum of the split-K partials followed by the epilogue; with n_partials == 0 it is
+// the alpha == 0 path (C <- beta * C) that never touches A or B.
+template <class AccT, class TC>
+__global__ __launch_bounds__(GTHREADS) void gemm_reduce_kernel(GemmTables t, int n_partials,
+                                                               double alpha_d, double beta_d)
+{
+    const Tile tile = t.tiles[blockIdx.x];
+    const Panel pc = t.c[tile.mseg * t.n_nseg + tile.nseg];
+    TC* c = static_cast<TC*>(const_cast<void*>(pc.ptr));
+    const AccT* ws = static_cast<const AccT*>(t.workspace);
+    const AccT alpha = static_cast<AccT>(alpha_d), beta = static_cast<AccT>(beta_d);
+    const int count = tile.m_len * tile.n_len;
+    for (int e = threadIdx.x; e < count; e += GTHREADS) {
+        int i = e / tile.n_len, j = e % tile.n_len;
+        AccT sum = AccT(0);
+        for (int s = 0; s < n_partials; ++s)
+            sum += ws[(int64_t)s * t.M * t.N + (int64_t)(tile.m_glob + i) * t.N + tile.n_glob + j];
+        epilogue_store(c + (int64_t)(tile.m_off + i) * pc.ld + tile.n_off + j, sum, alpha, beta);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Convolutions as implicit GEMMs (gathered operands)
+// ---------------------------------------------------------------------------------------
+template <class T> __device__ __forceinline__ T conv_im2col(const ConvTables& t, int m, int kk)
+{
+    // row m = (image, oh, ow), column kk = (c, r, s): X[n, c, oh*sh + r - ph, ow*sw + s - pw]
+    const ConvGeom& g = t.g;
+    int sp_out = g.oh * g.ow;
+    int n = m / sp_out, sp = m % sp_out, oy = sp / g.ow, ox = sp % g.ow;
+    int rs = g.r * g.s;
+    int c = kk / rs, q = kk % rs, fr = q / g.s, fs = q % g.s;
+    int ih = oy * g.stride_h + fr - g.pad_h, iw = ox * g.stride_w + fs - g.pad_w;
+    if (ih < 0 || ih >= g.h || iw < 0 || iw >= g.w) return T(0);
+    return static_cast<const T*>(t.x_rows[n])[(c * g.h + ih) * g.w + iw];
+}
+
+template <class T, int MODE> __device__ __forceinline__ T conv_a(const ConvTables& t, int m, int kk)
+{
+    const ConvGeom& g = t.g;
+    if (MODE == CONV_FWD) return conv_im2col<T>(t, m, kk);
+    if (MODE == CONV_BWD_FILTER) {
+        // A = dY viewed as [k x (n, oh, ow)]
+        int sp_out = g.oh * g.ow;
+        int n = kk / sp_out, sp = kk % sp_out;
+        return static_cast<const T*>(t.y_rows[n])[m * sp_out + sp];
+    }
+    // data gradient: row m = (image, ih, iw), column kk = (k, r, s)
+    int sp_in = g.h * g.w;
+    int n = m / sp_in, sp = m % sp_in, ih = sp / g.w, iw = sp % g.w;
+    int rs = g.r * g.s;
+    int ko = kk / rs, q = kk % rs, fr = q / g.s, fs = q % g.s;
+    int th = ih + g.pad_h - fr, tw = iw + g.pad_w - fs;
+    if (th < 0 || tw < 0 || th % g.stride_h || tw % g.stride_w) return T(0);
+    int oy = th / g.stride_h, ox = tw / g.stride_w;
+    if (oy >= g.oh || ox >= g.ow) return T(0);
+    return static_cast<const T*>(t.y_rows[n])[(ko * g.oh + oy) * g.ow + ox];
+}
+
+template <class T, int MODE> __device__ __forceinline__ T conv_b(const ConvTables& t, int kk, int j)
+{
+    const ConvGeom& g = t.g;
+    if (MODE == CONV_FWD) return static_cast<const T*>(t.f_rows[j])[kk];
+    if (MODE == CONV_BWD_FILTER) return conv_im2col<T>(t, kk, j);
+    int rs = g.r * g.s;
+    int ko = kk / rs, q = kk % rs;
+    return static_cast<const T*>(t.f_rows[ko])[j * rs + q];
+}
+
+template <class TC, int MODE> __device__ __forceinline__ TC* conv_c(const ConvTables& t, int m, int j)
+{
+    const ConvGeom& g = t.g;
+    if (MODE == CONV_FWD) {
+        int sp_out = g.oh * g.ow;
+        int n = m / sp_out, sp = m % sp_out;
+        return static_cast<TC*>(const_cast<void*>(t.y_rows[n])) + j * sp_out + sp;
+    }
+    if (MODE == CONV_BWD_FILTER) return static_cast<TC*>(const_cast<void*>(t.f_rows[m])) + j;
+    int sp_in = g.h * g.w;
+    int n = m / sp_in, sp = m % sp_in;
+    return static_cast<TC*>(const_cast<void*>(t.x_rows[n])) + j * sp_in + sp;
+}
+
+template <class T, class TC, int MODE>
+__global__ __launch_bounds__(GTHREADS) void conv_generic_kernel(ConvTables t, int k_per_split,
+                                                                double alpha_d, double beta_d)
+{
+    using AccT = typename Traits<T>::acc_t;
+    constexpr int S = Traits<T>::kStride;
+    __shared__ __attribute__((aligned(16))) T As[GT * S];
+    __shared__ __attribute__((aligned(16))) T Bs[GT * S];
+    const int tiles_n = (int)((t.N + GT - 1) / GT);
+    const int m0 = (blockIdx.x / tiles_n) * GT, n0 = (blockIdx.x % tiles_n) * GT;
+    const int split = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
+    const int M = (int)t.M, N = (int)t.N, K = (int)t.K;
+    Acc<T> acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc.v[r] = AccT(0);
+    const int kbeg = split * k_per_split;
+    const int kend = min(K, kbeg + k_per_split);
+    // thread -> element maps: unit-stride axis of the gathered tensor goes across lanes
+    constexpr bool a_kfast = (MODE == CONV_BWD_FILTER);
+    constexpr bool b_kfast = (MODE != CONV_BWD_DATA);
+    for (int k0 = kbeg; k0 < kend; k0 += GK) {
+#pragma unroll
+        for (int q = 0; q < GT * GK / GTHREADS; ++q) {
+            int e = q * GTHREADS + tid;
+            int row, kk;
+            if (a_kfast) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
+            T v = T(0);
+            if (m0 + row < M && k0 + kk < kend) v = conv_a<T, MODE>(t, m0 + row, k0 + kk);
+            As[row * S + kk] = v;
+            if (b_kfast) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
+            v = T(0);
+            if (n0 + row < N && k0 + kk < kend) v = conv_b<T, MODE>(t, k0 + kk, n0 + row);
+            Bs[row * S + kk] = v;
+        }
+        __syncthreads();
+        mma_step(As, Bs, wm, wn, lane, acc);
+        __syncthreads();
+    }
+    const AccT alpha = static_cast<AccT>(alpha_d), beta = static_cast<AccT>(beta_d);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        int i, j;
+        acc_pos<T>(lane, r, i, j);
+        i += m0 + wm * 32;
+        j += n0 + wn * 32;
+        if (i < M && j < N) {
+            if (t.split_k > 1)
+                static_cast<AccT*>(t.workspace)[((int64_t)split * M + i) * N + j] = acc.v[r];
+            else
+                epilogue_store(conv_c<TC, MODE>(t, i, j), acc.v[r], alpha, beta);
+        }
+    }
+}
+
+template <class AccT, class TC, int MODE>
+__global__ __launch_bounds__(GTHREADS) void conv_reduce_kernel(ConvTables t, int n_partials,
+                                                               double alpha_d, double beta_d)
+{
+    const int64_t total = t.M * t.N;
+    const AccT alpha = static_cast<AccT>(alpha_d), beta = static_cast<AccT>(beta_d);
+    const AccT* ws = static_cast<const AccT*>(t.workspace);
+    for (int64_t e = (int64_t)blockIdx.x * GTHREADS + threadIdx.x; e < total;
+         e += (int64_t)gridDim.x * GTHREADS) {
+        AccT sum = AccT(0);
+        for (int s = 0; s < n_partials; ++s) sum += ws[(int64_t)s * total + e];
+        epilogue_store(conv_c<TC, MODE>(t, (int)(e / t.N), (int)(e % t.N)), sum, alpha, beta);
+    }
+}
+
+template <class T, class TC>
+hipError_t run_gemm_generic(const GemmPlan& p, double alpha, double beta, hipStream_t st)
+{
+    using AccT = typename Traits<T>::acc_t;
+    const GemmTables& t = p.t;
+    if (alpha == 0.0) {
+        gemm_reduce_kernel<AccT, TC><<<t.n_tiles, GTHREADS, 0, st>>>(t, 0, 0.0, beta);
+        return hipGetLastError();
+    }
+    gemm_generic_kernel<T, TC><<<dim3(t.n_tiles, t.split_k), GTHREADS, 0, st>>>(t, alpha, beta);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || t.split_k == 1) return e;
+    gemm_reduce_kernel<AccT, TC><<<t.n_tiles, GTHREADS, 0, st>>>(t, t.split_k, alpha, beta);
+    return hipGetLastError();
+}
+
+template <class T, class TC, int MODE>
+hipError_t run_conv_generic(const ConvPlan& p, double alpha, double beta, hipStream_t st)
+{
+    using AccT = typename Traits<T>::acc_t;
+    const ConvTables& t = p.t;
+    const int64_t total = t.M * t.N;
+    const int rblocks = (int)std::min<int64_t>((total + GTHREADS - 1) / GTHREADS, 4096);
+    if (alpha == 0.0) {
+        conv_reduce_kernel<AccT, TC, MODE><<<rblocks, GTHREADS, 0, st>>>(t, 0, 0.0, beta);
+        return hipGetLastError();
+    }
+    const int tiles = (int)(((t.M + GT - 1) / GT) * ((t.N + GT - 1) / GT));
+    int per = (int)((t.K + t.split_k - 1) / t.split_k);
+    per = (per + GK - 1) / GK * GK;
+    conv_generic_kernel<T, TC, MODE><<<dim3(tiles, t.split_k), GTHREADS, 0, st>>>(t, per, alpha, beta);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || t.split_k == 1) return e;
+    conv_reduce_kernel<AccT, TC, MODE><<<rblocks, GTHREADS, 0, st>>>(t, t.split_k, alpha, beta);
+    return hipGetLastError();
+}
+
+template <int MODE>
+hipError_t conv_dispatch(const ConvPlan& p, double alpha, double beta, hipStream_t st)
+{
+    if (p.in_dtype == DMATH_F64) return run_conv_generic<double, double, MODE>(p, alpha, beta, st);
+    if (p.in_dtype == DMATH_F32) return run_conv_generic<float, float, MODE>(p, alpha, beta, st);
+    if (p.out_dtype == DMATH_F16) return run_conv_generic<_Float16, _Float16, MODE>(p, alpha, beta, st);
+    return run_conv_generic<_Float16, float, MODE>(p, alpha, beta, st);
+}
+
+}  // namespace
+
+hipError_t launch_gemm_generic(const GemmPlan& p, double alpha, double beta, hipStream_t st)
+{
+    if (p.in_dtype == DMATH_F64) return run_gemm_generic<double, double>(p, alpha, beta, st);
+    if (p.in_dtype == DMATH_F32) return run_gemm_generic<float, float>(p, alpha, beta, st);
+    if (p.out_dtype == DMATH_F16) return run_gemm_generic<_Float16, _Float16>(p, alpha, beta, st);
+    return run_gemm_generic<_Float16, float>(p, alpha, beta, st);
+}
+
+hipError_t launch_conv_generic(const ConvPlan& p, int mode, double alpha, double beta, hipStream_t st)
+{
+    switch (mode) {
+    case CONV_FWD: return conv_dispatch<CONV_FWD>(p, alpha, beta, st);
+    case CONV_BWD_FILTER: return conv_dispatch<CONV_BWD_FILTER>(p, alpha, beta, st);
+    default: return conv_dispatch<CONV_BWD_DATA>(p, alpha, beta, st);
+    }
+}
+
+}  // namespace dm

@@ -1,0 +1,43 @@
+// Thin wrappers over the gfx950 matrix-core (MFMA) builtins and the register layouts of their
+// operands and results.  One wavefront = 64 lanes.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace dm {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+typedef double v4d __attribute__((ext_vector_type(4)));
+
+// 32x32 result tile, 16 registers per lane (f32 accumulators, used by the f32 and f16 paths):
+// register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+__device__ __forceinline__ int acc32_row(int lane, int r) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
+__device__ __forceinline__ int acc32_col(int lane) { return lane & 31; }
+
+// 16x16 fp64 result tile, 4 registers per lane: register r of lane l holds row 4*(l/16) + r,
+// column l%16.
+__device__ __forceinline__ int acc16d_row(int lane, int r) { return 4 * (lane >> 4) + r; }
+__device__ __forceinline__ int acc16d_col(int lane) { return lane & 15; }
+
+// D += A(32x2) * B(2x32), fp32.  Lane l supplies A[l%32][l/32] and B[l/32][l%32].
+__device__ __forceinline__ v16f mfma_f32_32x32x2(float a, float b, v16f c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+
+// D += A(32x16) * B(16x32), fp16 inputs, fp32 accumulate.  Lane l supplies 8 consecutive k of
+// row/column l%32, k-group l/32.
+__device__ __forceinline__ v16f mfma_f16_32x32x16(v8h a, v8h b, v16f c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
+
+// D += A(16x4) * B(4x16), fp64.  Lane l supplies A[l%16][l/16] and B[l/16][l%16].
+__device__ __forceinline__ v4d mfma_f64_16x16x4(double a, double b, v4d c)
+{
+    return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+}
+
+}  // namespace dm

@@ -1,0 +1,378 @@
+// The tile scheduler: turns three independent block grids into the tables the kernels walk.
+//
+// Paper section 2.1: every worker knows the layout of every matrix and works out by itself
+// which blocks it needs; section 3.2: results must not depend on the layout.  Here the one
+// worker owns every block.  Each dimension (m, n, k) is cut at every block boundary of every
+// operand that spans it, so that a (segment x segment) panel lies inside exactly one block of
+// each operand; C tiles are laid inside (m-segment x n-segment) cells and the k-loop walks
+// the k-segments.  Section 3.3: the result is cached per (A, B, C, ops).
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cstring>
+
+#include "context.hpp"
+
+namespace dm {
+
+namespace {
+
+struct Seg {
+    int64_t start, len;
+};
+
+// Union of the cut points of several partitions of [0, n).
+std::vector<Seg> refine(int64_t n, std::initializer_list<const Split*> parts,
+                        const std::vector<int64_t>& extra_cuts = {})
+{
+    std::vector<int64_t> cuts{0, n};
+    for (const Split* s : parts)
+        for (int32_t p = 1; p < s->g; ++p) cuts.push_back(s->lo(p));
+    for (int64_t c : extra_cuts)
+        if (c > 0 && c < n) cuts.push_back(c);
+    std::sort(cuts.begin(), cuts.end());
+    cuts.erase(std::unique(cuts.begin(), cuts.end()), cuts.end());
+    std::vector<Seg> segs;
+    for (size_t i = 0; i + 1 < cuts.size(); ++i) segs.push_back({cuts[i], cuts[i + 1] - cuts[i]});
+    return segs;
+}
+
+// Address of logical element (i, j) of a matrix and the leading dimension of its block.
+Panel locate(const dmath_matrix_s* m, int64_t i, int64_t j)
+{
+    int32_t bi = m->rsplit.part(i), bj = m->csplit.part(j);
+    int64_t ld = m->csplit.len(bj);
+    int64_t off = (i - m->rsplit.lo(bi)) * ld + (j - m->csplit.lo(bj));
+    const char* base = static_cast<const char*>(m->block(bi, bj));
+    return Panel{base + off * (int64_t)elem_size(m->dtype), ld};
+}
+
+template <class T>
+size_t append(std::vector<char>& buf, const std::vector<T>& v)
+{
+    size_t off = (buf.size() + 15) / 16 * 16;
+    buf.resize(off + v.size() * sizeof(T));
+    if (!v.empty()) std::memcpy(buf.data() + off, v.data(), v.size() * sizeof(T));
+    return off;
+}
+
+// Orders tiles so that consecutive workgroups of one XCD (workgroup w runs on XCD w % 8) work
+// on neighbouring tiles: the logical sequence is cut into 8 contiguous runs, one per XCD, and
+// the table is written so that hardware workgroup w gets element (w / 8) of run (w % 8).
+std::vector<Tile> xcd_interleave(const std::vector<Tile>& logical)
+{
+    const size_t n = logical.size(), X = 8;
+    if (n < 2 * X) return logical;
+    // run x has base (+1 if x < rem) tiles, so that position w = j*8 + x exists for every
+    // element j of run x and the table has no holes.
+    const size_t base = n / X, rem = n % X;
+    std::vector<Tile> out(n);
+    size_t start = 0;
+    for (size_t x = 0; x < X; ++x) {
+        size_t len = base + (x < rem ? 1 : 0);
+        for (size_t j = 0; j < len; ++j) out[j * X + x] = logical[start + j];
+        start += len;
+    }
+    return out;
+}
+
+}  // namespace
+
+void drop_plans_using(dmath_ctx_s* ctx, uint64_t id)
+{
+    for (auto it = ctx->gemm_plans.begin(); it != ctx->gemm_plans.end();) {
+        auto& u = it->second->uses;
+        if (std::find(u.begin(), u.end(), id) != u.end()) {
+            if (it->second->dev_tables) ctx->pool.free(it->second->dev_tables);
+            if (it->second->workspace) ctx->pool.free(it->second->workspace);
+            it = ctx->gemm_plans.erase(it);
+        } else
+            ++it;
+    }
+    for (auto it = ctx->conv_plans.begin(); it != ctx->conv_plans.end();) {
+        auto& u = it->second->uses;
+        if (std::find(u.begin(), u.end(), id) != u.end()) {
+            if (it->second->dev_tables) ctx->pool.free(it->second->dev_tables);
+            if (it->second->workspace) ctx->pool.free(it->second->workspace);
+            it = ctx->conv_plans.erase(it);
+        } else
+            ++it;
+    }
+}
+
+void drop_all_plans(dmath_ctx_s* ctx)
+{
+    for (auto& kv : ctx->gemm_plans) {
+        if (kv.second->dev_tables) ctx->pool.free(kv.second->dev_tables);
+        if (kv.second->workspace) ctx->pool.free(kv.second->workspace);
+    }
+    ctx->gemm_plans.clear();
+    for (auto& kv : ctx->conv_plans) {
+        if (kv.second->dev_tables) ctx->pool.free(kv.second->dev_tables);
+        if (kv.second->workspace) ctx->pool.free(kv.second->workspace);
+    }
+    ctx->conv_plans.clear();
+}
+
+static hipError_t upload(dmath_ctx_s* ctx, void* dst, const std::vector<char>& buf)
+{
+    hipError_t e = hipMemcpyAsync(dst, buf.data(), buf.size(), hipMemcpyHostToDevice, ctx->stream);
+    if (e != hipSuccess) return e;
+    return hipStreamSynchronize(ctx->stream);  // buf is pageable and about to go away
+}
+
+dmath_status_t get_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_matrix_s* A,
+                             dmath_matrix_s* B, dmath_matrix_s* C, bool do_upload, GemmPlan** out,
+                             bool* was_cached)
+{
+    GemmKey key{A->id, B->id, C->id, transA, transB};
+    auto found = ctx->gemm_plans.find(key);
+    if (found != ctx->gemm_plans.end() && (found->second->dev_tables || !do_upload)) {
+        *out = found->second.get();
+        if (was_cached) *was_cached = true;
+        return DMATH_OK;
+    }
+    if (was_cached) *was_cached = false;
+    if (found != ctx->gemm_plans.end()) ctx->gemm_plans.erase(found);  // described, never uploaded
+
+    const int64_t M = C->rows, N = C->cols, K = transA ? A->rows : A->cols;
+    const Split& a_m = transA ? A->csplit : A->rsplit;
+    const Split& a_k = transA ? A->rsplit : A->csplit;
+    const Split& b_k = transB ? B->csplit : B->rsplit;
+    const Split& b_n = transB ? B->rsplit : B->csplit;
+
+    // first pass without split-K cuts to let the kernel chooser see the natural segments
+    std::vector<Seg> ms = refine(M, {&a_m, &C->rsplit});
+    std::vector<Seg> ns = refine(N, {&b_n, &C->csplit});
+    std::vector<Seg> ks = refine(K, {&a_k, &b_k});
+
+    const size_t es = elem_size(A->dtype);
+    auto panel_a = [&](const Seg& m, const Seg& k) {
+        return transA ? locate(A, k.start, m.start) : locate(A, m.start, k.start);
+    };
+    auto panel_b = [&](const Seg& k, const Seg& n) {
+        return transB ? locate(B, n.start, k.start) : locate(B, k.start, n.start);
+    };
+    auto aligned = [&](const Panel& p, size_t esz) {
+        return (reinterpret_cast<uintptr_t>(p.ptr) % 16 == 0) && ((p.ld * (int64_t)esz) % 16 == 0);
+    };
+    bool al = true;
+    for (auto& m : ms)
+        for (auto& k : ks) al = al && aligned(panel_a(m, k), es);
+    for (auto& k : ks)
+        for (auto& n : ns) al = al && aligned(panel_b(k, n), es);
+    for (auto& m : ms)
+        for (auto& n : ns) al = al && aligned(locate(C, m.start, n.start), elem_size(C->dtype));
+
+    std::vector<int64_t> mlen, nlen, klen;
+    for (auto& s : ms) mlen.push_back(s.len);
+    for (auto& s : ns) nlen.push_back(s.len);
+    for (auto& s : ks) klen.push_back(s.len);
+    SegView view{M, N, K, &mlen, &nlen, &klen, !transA, (bool)transB, al, A->dtype, C->dtype,
+                 ctx->policy};
+    GemmChoice ch = choose_gemm(view);
+
+    // split-K: extra cuts of the k axis at multiples of 64 (every kernel's k-step divides 64)
+    std::vector<int64_t> split_cuts;
+    if (ch.split_k > 1) {
+        int64_t per = (K + ch.split_k - 1) / ch.split_k;
+        per = (per + 63) / 64 * 64;
+        for (int32_t s = 1; s < ch.split_k; ++s)
+            if (s * per < K) split_cuts.push_back(s * per);
+        ch.split_k = (int32_t)split_cuts.size() + 1;
+        ks = refine(K, {&a_k, &b_k}, split_cuts);
+    }
+    std::vector<int32_t> ksplit{0};
+    for (int64_t c : split_cuts)
+        for (size_t i = 0; i < ks.size(); ++i)
+            if (ks[i].start == c) ksplit.push_back((int32_t)i);
+    ksplit.push_back((int32_t)ks.size());
+
+    std::vector<Panel> pa, pb, pc;
+    for (auto& m : ms)
+        for (auto& k : ks) pa.push_back(panel_a(m, k));
+    for (auto& k : ks)
+        for (auto& n : ns) pb.push_back(panel_b(k, n));
+    for (auto& m : ms)
+        for (auto& n : ns) pc.push_back(locate(C, m.start, n.start));
+    std::vector<int32_t> kl;
+    for (auto& k : ks) kl.push_back((int32_t)k.len);
+
+    // Logical tile order: cells in row-major order, tiles inside a cell in bands of 8 tile-rows
+    // walked column by column, so that a contiguous run of tiles re-uses a narrow set of A row
+    // panels and B column panels out of one L2.
+    std::vector<Tile> tiles;
+    for (size_t mi = 0; mi < ms.size(); ++mi)
+        for (size_t ni = 0; ni < ns.size(); ++ni) {
+            int64_t tm = (ms[mi].len + ch.tile_m - 1) / ch.tile_m;
+            int64_t tn = (ns[ni].len + ch.tile_n - 1) / ch.tile_n;
+            const int64_t band = 8;
+            for (int64_t b0 = 0; b0 < tm; b0 += band)
+                for (int64_t j = 0; j < tn; ++j)
+                    for (int64_t i = b0; i < std::min(tm, b0 + band); ++i) {
+                        Tile t;
+                        t.mseg = (int32_t)mi;
+                        t.nseg = (int32_t)ni;
+                        t.m_off = (int32_t)(i * ch.tile_m);
+                        t.n_off = (int32_t)(j * ch.tile_n);
+                        t.m_len = (int32_t)std::min<int64_t>(ch.tile_m, ms[mi].len - t.m_off);
+                        t.n_len = (int32_t)std::min<int64_t>(ch.tile_n, ns[ni].len - t.n_off);
+                        t.m_glob = (int32_t)(ms[mi].start + t.m_off);
+                        t.n_glob = (int32_t)(ns[ni].start + t.n_off);
+                        tiles.push_back(t);
+                    }
+        }
+    tiles = xcd_interleave(tiles);
+
+    auto plan = std::make_unique<GemmPlan>();
+    plan->uses = {A->id, B->id, C->id};
+    plan->in_dtype = A->dtype;
+    plan->out_dtype = C->dtype;
+    dmath_plan_info_t& info = plan->info;
+    info.m = M;
+    info.n = N;
+    info.k = K;
+    info.m_segments = (int32_t)ms.size();
+    info.n_segments = (int32_t)ns.size();
+    info.k_segments = (int32_t)ks.size();
+    info.tile_m = ch.tile_m;
+    info.tile_n = ch.tile_n;
+    info.tile_k = ch.tile_k;
+    info.tiles = (int32_t)tiles.size();
+    info.split_k = ch.split_k;
+    info.kernel = ch.kernel;
+    const size_t acc_size = A->dtype == DMATH_F64 ? 8 : 4;
+    info.workspace_bytes = ch.split_k > 1 ? (uint64_t)ch.split_k * M * N * acc_size : 0;
+
+    GemmTables& t = plan->t;
+    t.n_mseg = (int32_t)ms.size();
+    t.n_nseg = (int32_t)ns.size();
+    t.n_kseg = (int32_t)ks.size();
+    t.n_tiles = (int32_t)tiles.size();
+    t.split_k = ch.split_k;
+    t.a_kcontig = !transA;
+    t.b_kcontig = transB ? 1 : 0;
+    t.M = M;
+    t.N = N;
+
+    if (do_upload) {
+        std::vector<char> buf;
+        size_t oa = append(buf, pa), ob = append(buf, pb), oc = append(buf, pc);
+        size_t ok = append(buf, kl), os = append(buf, ksplit), ot = append(buf, tiles);
+        void* dev = ctx->pool.alloc(buf.size());
+        if (!dev) return DMATH_ERR_OOM;
+        void* ws = nullptr;
+        if (info.workspace_bytes) {
+            ws = ctx->pool.alloc(info.workspace_bytes);
+            if (!ws) {
+                ctx->pool.free(dev);
+                return DMATH_ERR_OOM;
+            }
+        }
+        if (upload(ctx, dev, buf) != hipSuccess) {
+            ctx->pool.free(dev);
+            if (ws) ctx->pool.free(ws);
+            return DMATH_ERR_DEVICE;
+        }
+        char* d = static_cast<char*>(dev);
+        t.a = reinterpret_cast<const Panel*>(d + oa);
+        t.b = reinterpret_cast<const Panel*>(d + ob);
+        t.c = reinterpret_cast<const Panel*>(d + oc);
+        t.klen = reinterpret_cast<const int32_t*>(d + ok);
+        t.ksplit = reinterpret_cast<const int32_t*>(d + os);
+        t.tiles = reinterpret_cast<const Tile*>(d + ot);
+        t.workspace = ws;
+        plan->dev_tables = dev;
+        plan->workspace = ws;
+    }
+    *out = plan.get();
+    ctx->gemm_plans[key] = std::move(plan);
+    return DMATH_OK;
+}
+
+dmath_status_t get_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t* d,
+                             dmath_matrix_s* X, dmath_matrix_s* F, dmath_matrix_s* Y,
+                             ConvPlan** out)
+{
+    std::vector<int32_t> geom{d->n, d->c, d->h, d->w, d->k, d->r, d->s,
+                              d->pad_h, d->pad_w, d->stride_h, d->stride_w};
+    ConvKey key{X->id, F->id, Y->id, mode, geom};
+    auto found = ctx->conv_plans.find(key);
+    if (found != ctx->conv_plans.end()) {
+        *out = found->second.get();
+        return DMATH_OK;
+    }
+    auto plan = std::make_unique<ConvPlan>();
+    plan->uses = {X->id, F->id, Y->id};
+    ConvTables& t = plan->t;
+    ConvGeom& g = t.g;
+    g.n = d->n; g.c = d->c; g.h = d->h; g.w = d->w; g.k = d->k; g.r = d->r; g.s = d->s;
+    g.pad_h = d->pad_h; g.pad_w = d->pad_w; g.stride_h = d->stride_h; g.stride_w = d->stride_w;
+    g.oh = (d->h + 2 * d->pad_h - d->r) / d->stride_h + 1;
+    g.ow = (d->w + 2 * d->pad_w - d->s) / d->stride_w + 1;
+    const int64_t sp_out = (int64_t)g.oh * g.ow, sp_in = (int64_t)g.h * g.w;
+    const int64_t crs = (int64_t)g.c * g.r * g.s;
+    dmath_matrix_s* result = nullptr;
+    switch (mode) {
+    case CONV_FWD:
+        t.M = g.n * sp_out; t.N = g.k; t.K = crs; result = Y;
+        break;
+    case CONV_BWD_FILTER:
+        t.M = g.k; t.N = crs; t.K = g.n * sp_out; result = F;
+        break;
+    default:
+        t.M = g.n * sp_in; t.N = g.c; t.K = (int64_t)g.k * g.r * g.s; result = X;
+        break;
+    }
+    plan->in_dtype = (mode == CONV_FWD) ? X->dtype : Y->dtype;
+    plan->out_dtype = result->dtype;
+
+    // split-K for the weight gradient: few C tiles, very deep K
+    t.split_k = 1;
+    if (mode == CONV_BWD_FILTER) {
+        int64_t tiles = ((t.M + 63) / 64) * ((t.N + 63) / 64);
+        int64_t want = std::max<int64_t>(1, 1024 / std::max<int64_t>(1, tiles));
+        int64_t max_by_k = std::max<int64_t>(1, t.K / 512);
+        t.split_k = (int32_t)std::min<int64_t>({want, max_by_k, 64});
+    }
+
+    auto row_ptrs = [](const dmath_matrix_s* m) {
+        std::vector<const void*> v((size_t)m->rows);
+        for (int64_t i = 0; i < m->rows; ++i) {
+            int32_t bi = m->rsplit.part(i);
+            v[(size_t)i] = static_cast<const char*>(m->block(bi, 0)) +
+                           (i - m->rsplit.lo(bi)) * m->cols * (int64_t)elem_size(m->dtype);
+        }
+        return v;
+    };
+    std::vector<char> buf;
+    size_t ox = append(buf, row_ptrs(X)), of = append(buf, row_ptrs(F)), oy = append(buf, row_ptrs(Y));
+    void* dev = ctx->pool.alloc(buf.size());
+    if (!dev) return DMATH_ERR_OOM;
+    void* ws = nullptr;
+    if (t.split_k > 1) {
+        size_t acc = plan->in_dtype == DMATH_F64 ? 8 : 4;
+        ws = ctx->pool.alloc((size_t)t.split_k * t.M * t.N * acc);
+        if (!ws) {
+            ctx->pool.free(dev);
+            return DMATH_ERR_OOM;
+        }
+    }
+    if (upload(ctx, dev, buf) != hipSuccess) {
+        ctx->pool.free(dev);
+        if (ws) ctx->pool.free(ws);
+        return DMATH_ERR_DEVICE;
+    }
+    char* dp = static_cast<char*>(dev);
+    t.x_rows = reinterpret_cast<const void* const*>(dp + ox);
+    t.f_rows = reinterpret_cast<const void* const*>(dp + of);
+    t.y_rows = reinterpret_cast<const void* const*>(dp + oy);
+    t.workspace = ws;
+    plan->dev_tables = dev;
+    plan->workspace = ws;
+    *out = plan.get();
+    ctx->conv_plans[key] = std::move(plan);
+    return DMATH_OK;
+}
+
+}  // namespace dm

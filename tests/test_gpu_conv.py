@@ -1,0 +1,134 @@
+"""GPU parity of the implicit-GEMM convolutions against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+import paper_1611_07819_amd as dm
+from paper_1611_07819_amd import synth
+from gpu_util import TOL, make_context, rel_fro
+
+pytestmark = pytest.mark.gpu
+NP = {dm.F64: np.float64, dm.F32: np.float32, dm.F16: np.float16}
+
+GEOMS = [
+    dict(n=3, c=5, h=9, w=7, k=6, r=3, s=3, pad_h=1, pad_w=1),
+    dict(n=2, c=4, h=12, w=10, k=70, r=3, s=2, pad_h=0, pad_w=1, stride_h=2, stride_w=1),
+    dict(n=4, c=16, h=6, w=6, k=8, r=1, s=1),
+    dict(n=2, c=3, h=11, w=9, k=5, r=5, s=3, pad_h=2, pad_w=0, stride_h=2, stride_w=3),
+    dict(n=5, c=24, h=14, w=14, k=40, r=3, s=3, pad_h=1, pad_w=1),
+]
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = make_context(3.0)
+    yield c
+    c.close()
+
+
+def tensors(g, dt, seed, ints=False):
+    d = dm.ConvDesc(**g)
+    oh = (d.h + 2 * d.pad_h - d.r) // d.stride_h + 1
+    ow = (d.w + 2 * d.pad_w - d.s) // d.stride_w + 1
+    r = np.random.default_rng(seed)
+    shapes = {"X": (d.n, d.c * d.h * d.w), "F": (d.k, d.c * d.r * d.s), "Y": (d.n, d.k * oh * ow)}
+    if ints:
+        t = {k: r.integers(-2, 3, s).astype(NP[dt]) for k, s in shapes.items()}
+    else:
+        t = {"X": r.uniform(0, 1, shapes["X"]).astype(NP[dt]),
+             "F": r.normal(0, 0.2, shapes["F"]).astype(NP[dt]),
+             "Y": r.normal(0, 0.1, shapes["Y"]).astype(NP[dt])}
+    return d, t
+
+
+def three_modes(ctx, oracle, g, dt, out_dt, alpha, beta, grids, ints=False, policy=0):
+    d, t = tensors(g, dt, 300, ints)
+    od = oracle.ConvDesc(**g)
+    ctx.set_kernel_policy(policy)
+    res = {}
+    for mode in ("fwd", "bwd_filter", "bwd_data"):
+        out_name = {"fwd": "Y", "bwd_filter": "F", "bwd_data": "X"}[mode]
+        host = {k: (v.astype(NP[out_dt]) if k == out_name else v) for k, v in t.items()}
+        dev = {k: ctx.from_host(v, grids[k]) for k, v in host.items()}
+        blk = {k: oracle.BlockMatrix(v, grids[k]) for k, v in host.items()}
+        if mode == "fwd":
+            dm.conv_fwd(ctx, d, alpha, dev["X"], dev["F"], beta, dev["Y"])
+            ref = oracle.conv_fwd(od, alpha, blk["X"], blk["F"], beta, blk["Y"])
+        elif mode == "bwd_filter":
+            dm.conv_bwd_filter(ctx, d, alpha, dev["X"], dev["Y"], beta, dev["F"])
+            ref = oracle.conv_bwd_filter(od, alpha, blk["X"], blk["Y"], beta, blk["F"])
+        else:
+            dm.conv_bwd_data(ctx, d, alpha, dev["Y"], dev["F"], beta, dev["X"])
+            ref = oracle.conv_bwd_data(od, alpha, blk["Y"], blk["F"], beta, blk["X"])
+        res[mode] = (dev[out_name].get(), ref)
+        for m in dev.values():
+            m.destroy()
+    return res
+
+
+@pytest.mark.parametrize("policy", [0, 1])
+@pytest.mark.parametrize("g", GEOMS)
+@pytest.mark.parametrize("dt,out", [(dm.F64, dm.F64), (dm.F32, dm.F32), (dm.F16, dm.F32), (dm.F16, dm.F16)])
+def test_geometries_all_modes(ctx, oracle, g, dt, out, policy):
+    grids = {"X": (1, 1), "F": (1, 1), "Y": (1, 1)}
+    for mode, (got, ref) in three_modes(ctx, oracle, g, dt, out, 1.5, -0.5, grids, policy=policy).items():
+        assert rel_fro(got, ref) <= TOL[dt], mode
+
+
+@pytest.mark.parametrize("g", GEOMS[:2] + GEOMS[4:])
+@pytest.mark.parametrize("dt,out", [(dm.F64, dm.F64), (dm.F32, dm.F32), (dm.F16, dm.F32), (dm.F16, dm.F16)])
+def test_integer_inputs_bitwise_with_row_blocked_tensors(ctx, oracle, g, dt, out):
+    # |values| <= 2, at most c*r*s*4 <= 2048 per output in these geometries for the forward
+    # pass; the weight gradient sums n*oh*ow*4 terms, also below 2048 here.
+    grids = {"X": (g["n"], 1), "F": (2, 1), "Y": (2, 1)}
+    for mode, (got, ref) in three_modes(ctx, oracle, g, dt, out, 1.0, 1.0, grids, ints=True).items():
+        if out == dm.F16 and np.abs(ref).max() > 2048:
+            assert rel_fro(got, ref) <= TOL[dt], mode
+        else:
+            assert np.array_equal(got.astype(np.float64), ref), mode
+
+
+def test_delta_filters_fix_the_convention(ctx):
+    g = dict(n=2, c=4, h=8, w=9, k=4, r=3, s=3, pad_h=1, pad_w=1)
+    d = dm.ConvDesc(**g)
+    X = np.random.default_rng(301).uniform(0, 1, (2, 4 * 72)).astype(np.float16)
+    F = np.zeros((4, 4, 3, 3), np.float16)
+    for k in range(4):
+        F[k, k, 0, 2] = 1
+    dX, dF = ctx.from_host(X), ctx.from_host(F.reshape(4, 36))
+    dY = ctx.matrix(2, 4 * 72, (1, 1), dm.F16)
+    dm.conv_fwd(ctx, d, 1.0, dX, dF, 0.0, dY)
+    got = dY.get().reshape(2, 4, 8, 9)
+    x = X.reshape(2, 4, 8, 9)
+    want = np.zeros_like(x)
+    want[:, :, 1:, :-1] = x[:, :, :-1, 1:]      # Y[oh,ow] = X[oh-1, ow+1]
+    assert np.array_equal(got, want)
+    for m in (dX, dF, dY):
+        m.destroy()
+
+
+@pytest.mark.parametrize("out", ["f32", "f16"])
+def test_config5_reduced_whole_result(ctx, oracle, out):
+    w = synth.config5(out, batch=4, channels=64, hw=28)
+    _config5(ctx, oracle, w, None, None)
+
+
+@pytest.mark.parametrize("out", ["f32", "f16"])
+def test_config5_full_size_sampled(ctx, oracle, out):
+    w = synth.config5(out)
+    _config5(ctx, oracle, w, [0, 37, 63], [1, 200])
+
+
+def _config5(ctx, oracle, w, images, filters):
+    d = dm.ConvDesc(**w.conv)
+    od = oracle.ConvDesc(**w.conv)
+    dev = {k: ctx.from_host(v) for k, v in w.mats.items()}
+    dm.conv_fwd(ctx, d, 1.0, dev["X"], dev["F"], 0.0, dev["Y"])
+    got = dev["Y"].get()
+    ref = oracle.conv_fwd(od, 1.0, w.mats["X"], w.mats["F"], images=images)
+    assert rel_fro(got if images is None else got[images], ref) <= TOL[dm.F16]
+    dm.conv_bwd_filter(ctx, d, 1.0, dev["X"], dev["dY"], 0.0, dev["dF"])
+    got = dev["dF"].get()
+    ref = oracle.conv_bwd_filter(od, 1.0, w.mats["X"], w.mats["dY"], filters=filters)
+    assert rel_fro(got if filters is None else got[filters], ref) <= TOL[dm.F16]
+    for m in dev.values():
+        m.destroy()

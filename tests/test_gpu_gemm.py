@@ -1,0 +1,232 @@
+"""GPU parity of dmath_gemm against the CPU oracle, through the C ABI (needs an MI355X).
+
+Bars (relative Frobenius error over the whole result, by input precision): 1e-12 fp64,
+1e-5 fp32, 2e-3 fp16 inputs with fp32 accumulation (either output type); bitwise equality on
+small-integer inputs, where every summation order gives the same bits."""
+import itertools
+
+import numpy as np
+import pytest
+
+import paper_1611_07819_amd as dm
+from paper_1611_07819_amd import synth
+from gpu_util import TOL, CODE, make_context, rel_fro
+
+pytestmark = pytest.mark.gpu
+
+NP = {dm.F64: np.float64, dm.F32: np.float32, dm.F16: np.float16}
+OPS = list(itertools.product([0, 1], repeat=2))
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = make_context(6.0)
+    yield c
+    c.close()
+
+
+def stored(op_mat, trans):
+    return np.ascontiguousarray(op_mat.T if trans else op_mat)
+
+
+def run_gemm(ctx, oracle, ta, tb, alpha, opA, opB, beta, C0, grids, out_dtype=None, rows=None,
+             policy=0):
+    """op(A) = opA, op(B) = opB are given logically; they are stored transposed when ta/tb."""
+    A, B = stored(opA, ta), stored(opB, tb)
+    ga, gb, gc = grids
+    ctx.set_kernel_policy(policy)
+    dA, dB = ctx.from_host(A, ga), ctx.from_host(B, gb)
+    C0 = C0 if out_dtype is None else C0.astype(NP[out_dtype])
+    dC = ctx.from_host(C0, gc)
+    dm.gemm(ctx, ta, tb, alpha, dA, dB, beta, dC)
+    got = dC.get()
+    ref = oracle.gemm(bool(ta), bool(tb), alpha, oracle.BlockMatrix(A, ga), oracle.BlockMatrix(B, gb),
+                      beta, oracle.BlockMatrix(C0, gc), rows=rows)
+    for m in (dA, dB, dC):
+        m.destroy()
+    return got if rows is None else got[rows], ref
+
+
+@pytest.mark.parametrize("policy", [0, 1])
+@pytest.mark.parametrize("dt", [dm.F64, dm.F32, dm.F16])
+@pytest.mark.parametrize("ta,tb", OPS)
+def test_ragged_multi_tile_all_ops(ctx, oracle, dt, ta, tb, policy):
+    # several tiles in every direction, ragged tails, grids that do not line up
+    r = np.random.default_rng(100 + dt)
+    M, N, K = 150, 203, 117
+    opA = r.uniform(-1, 1, (M, K)).astype(NP[dt])
+    opB = r.uniform(-1, 1, (K, N)).astype(NP[dt])
+    C0 = r.uniform(-1, 1, (M, N)).astype(NP[dt])
+    for grids in [((1, 1), (1, 1), (1, 1)), ((2, 3), (2, 2), (3, 2))]:
+        got, ref = run_gemm(ctx, oracle, ta, tb, 1.5, opA, opB, -0.5, C0, grids, policy=policy)
+        assert rel_fro(got, ref) <= TOL[dt]
+        assert np.abs(got.astype(np.float64) - ref).max() <= 50 * TOL[dt] * np.abs(ref).max()
+
+
+@pytest.mark.parametrize("policy", [0, 1])
+@pytest.mark.parametrize("dt,out", [(dm.F64, dm.F64), (dm.F32, dm.F32), (dm.F16, dm.F32), (dm.F16, dm.F16)])
+@pytest.mark.parametrize("ta,tb", OPS)
+def test_small_integers_are_bitwise_exact(ctx, oracle, dt, out, ta, tb, policy):
+    # entries in {-3..3}: all partial sums are exactly representable, so any summation order,
+    # tiling or split-K must reproduce the oracle bit for bit.  |result| <= 2048 for fp16 out.
+    r = np.random.default_rng(200)
+    M, N, K = 192, 130, 96
+    opA = r.integers(-3, 4, (M, K)).astype(NP[dt])
+    opB = r.integers(-3, 4, (K, N)).astype(NP[dt])
+    C0 = r.integers(-3, 4, (M, N)).astype(NP[out])
+    for grids in [((1, 1), (1, 1), (1, 1)), ((3, 2), (2, 2), (2, 2)), ((4, 3), (3, 5), (5, 4))]:
+        got, ref = run_gemm(ctx, oracle, ta, tb, 2.0, opA, opB, 1.0, C0, grids, out_dtype=out,
+                            policy=policy)
+        assert np.array_equal(got.astype(np.float64), ref)
+
+
+@pytest.mark.parametrize("dt", [dm.F64, dm.F32, dm.F16])
+def test_deep_k_uses_split_k_and_stays_exact(ctx, oracle, dt):
+    r = np.random.default_rng(201)
+    M, N, K = 96, 80, 8192
+    opA = r.integers(-1, 2, (M, K)).astype(NP[dt])
+    opB = r.integers(-1, 2, (K, N)).astype(NP[dt])
+    C0 = r.integers(-3, 4, (M, N)).astype(NP[dt])
+    dA, dB, dC = ctx.from_host(opA, (1, 3)), ctx.from_host(opB, (2, 1)), ctx.from_host(C0, (1, 1))
+    info = dm.gemm_plan_info(ctx, 0, 0, dA, dB, dC)
+    assert info["split_k"] > 1 and info["workspace_bytes"] > 0
+    dm.gemm(ctx, 0, 0, 1.0, dA, dB, 1.0, dC)
+    got = dC.get()
+    ref = oracle.gemm(False, False, 1.0, opA, opB, 1.0, C0)
+    assert np.array_equal(got.astype(np.float64), ref)
+    for m in (dA, dB, dC):
+        m.destroy()
+
+
+@pytest.mark.parametrize("dt", [dm.F64, dm.F32, dm.F16])
+def test_identity_and_alpha_beta_rules(ctx, oracle, dt):
+    r = np.random.default_rng(202)
+    n = 100
+    A = r.uniform(-1, 1, (n, n)).astype(NP[dt])
+    I = np.eye(n, dtype=NP[dt])
+    C0 = r.uniform(-1, 1, (n, n)).astype(NP[dt])
+    got, _ = run_gemm(ctx, oracle, 0, 0, 1.0, A, I, 0.0, C0, ((2, 2), (2, 2), (2, 2)))
+    assert np.array_equal(got, A)
+    got, _ = run_gemm(ctx, oracle, 1, 0, 1.0, A, I, 0.0, C0, ((2, 2), (2, 2), (2, 2)))
+    assert np.array_equal(got, A)                      # op(A) was given logically
+    nan = np.full((n, n), np.nan, NP[dt])
+    got, ref = run_gemm(ctx, oracle, 0, 0, 1.0, A, I, 0.0, nan, ((1, 1),) * 3)
+    assert np.array_equal(got, A)                      # beta == 0: old C not read
+    got, ref = run_gemm(ctx, oracle, 0, 0, 0.0, nan, I, 2.0, C0, ((1, 1),) * 3)
+    assert np.array_equal(got.astype(np.float64), ref) # alpha == 0: A not read; C = 2*C0 exactly
+    got, ref = run_gemm(ctx, oracle, 0, 0, 0.0, nan, nan, 0.0, nan, ((1, 1),) * 3)
+    assert np.array_equal(got, np.zeros((n, n), NP[dt]))
+    for (al, be) in [(1.0, 1.0), (1.5, -0.5)]:
+        got, ref = run_gemm(ctx, oracle, 0, 0, al, A, A, be, C0, ((2, 1), (1, 2), (2, 2)))
+        assert rel_fro(got, ref) <= TOL[dt]
+
+
+def test_run_to_run_bitwise_reproducible(ctx):
+    r = np.random.default_rng(203)
+    A = r.uniform(-1, 1, (96, 4096)).astype(np.float32)
+    B = r.uniform(-1, 1, (4096, 64)).astype(np.float32)
+    dA, dB = ctx.from_host(A), ctx.from_host(B)
+    outs = []
+    for _ in range(3):
+        dC = ctx.matrix(96, 64, (1, 1), dm.F32)
+        dm.gemm(ctx, 0, 0, 1.0, dA, dB, 0.0, dC)
+        outs.append(dC.get())
+        dC.destroy()
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+
+
+def test_config1_full(ctx, oracle):
+    w = synth.config1()
+    m = w.mats
+    got, ref = run_gemm(ctx, oracle, 0, 0, 1.0, m["A"], m["B"], 1.0, m["C"], (w.grid,) * 3)
+    assert rel_fro(got, ref) <= TOL[dm.F32]
+
+
+def _fc_workload(ctx, oracle, w, in_dt, out_dt, rows_per_call, policy=0):
+    ctx.set_kernel_policy(policy)
+    dev = {k: ctx.from_host(v, w.grid) for k, v in w.mats.items()}
+    r = np.random.default_rng(7)
+    for call in w.calls:
+        dm.gemm(ctx, int(call.transA), int(call.transB), call.alpha, dev[call.a], dev[call.b],
+                call.beta, dev[call.c])
+        got = dev[call.c].get()
+        M = got.shape[0]
+        rows = None if rows_per_call is None or rows_per_call >= M else \
+            np.sort(r.choice(M, rows_per_call, replace=False))
+        ref = oracle.gemm(call.transA, call.transB, call.alpha,
+                          oracle.BlockMatrix(w.mats[call.a], w.grid),
+                          oracle.BlockMatrix(w.mats[call.b], w.grid), call.beta,
+                          oracle.BlockMatrix(w.mats[call.c], w.grid), rows=rows)
+        g = got if rows is None else got[rows]
+        err = rel_fro(g, ref)
+        assert err <= TOL[in_dt], (w.name, call.name, err)
+    for m in dev.values():
+        m.destroy()
+
+
+@pytest.mark.parametrize("policy", [0, 1])
+def test_config2_scaled_whole_result(ctx, oracle, policy):
+    _fc_workload(ctx, oracle, synth.config2(scale=8), dm.F32, dm.F32, None, policy)
+
+
+def test_config2_full_size_sampled_rows(ctx, oracle):
+    _fc_workload(ctx, oracle, synth.config2(), dm.F32, dm.F32, 48)
+
+
+@pytest.mark.parametrize("out", ["f32", "f16"])
+@pytest.mark.parametrize("policy", [0, 1])
+def test_config3_scaled_whole_result(ctx, oracle, out, policy):
+    _fc_workload(ctx, oracle, synth.config3(out, scale=8), dm.F16, None, None, policy)
+
+
+@pytest.mark.parametrize("out", ["f32", "f16"])
+def test_config3_full_size_sampled_rows(ctx, oracle, out):
+    _fc_workload(ctx, oracle, synth.config3(out), dm.F16, None, 96)
+
+
+@pytest.mark.parametrize("policy", [0, 1])
+def test_config4_scaled_whole_result(ctx, oracle, policy):
+    w = synth.config4(scale=16)
+    m = w.mats
+    got, ref = run_gemm(ctx, oracle, 0, 0, 1.5, m["A"], m["B"], -0.5, m["C"], (w.grid,) * 3,
+                        policy=policy)
+    assert rel_fro(got, ref) <= TOL[dm.F64]
+
+
+def test_config4_full_size_sampled_rows(ctx, oracle):
+    w = synth.config4()
+    m = w.mats
+    rows = np.sort(np.random.default_rng(8).choice(8192, 24, replace=False))
+    got, ref = run_gemm(ctx, oracle, 0, 0, 1.5, m["A"], m["B"], -0.5, m["C"], (w.grid,) * 3,
+                        rows=rows)
+    assert rel_fro(got, ref) <= TOL[dm.F64]
+
+
+def test_fp16_path_agrees_with_fp32_path(ctx):
+    # section 4.2: half mode "performs at par" with float.  Same fp16-representable data through
+    # both paths: the only difference is the summation order of exact products.
+    r = np.random.default_rng(204)
+    A = r.uniform(0, 1, (256, 512)).astype(np.float16)
+    B = r.normal(0, 1 / 16, (512, 128)).astype(np.float16)
+    outs = []
+    for dt in (np.float16, np.float32):
+        dA, dB = ctx.from_host(A.astype(dt), (2, 2)), ctx.from_host(B.astype(dt), (2, 2))
+        dC = ctx.matrix(256, 128, (2, 2), dm.F32)
+        dm.gemm(ctx, 0, 0, 1.0, dA, dB, 0.0, dC)
+        outs.append(dC.get())
+        for m in (dA, dB, dC):
+            m.destroy()
+    assert rel_fro(outs[0], outs[1]) <= 1e-5
+
+
+def test_pool_is_the_only_allocator(ctx):
+    import torch
+    before = torch.cuda.memory_allocated()
+    A = ctx.from_host(np.ones((300, 300), np.float32), (2, 2))
+    B = ctx.from_host(np.ones((300, 300), np.float32), (2, 2))
+    C = ctx.matrix(300, 300, (2, 2), dm.F32)
+    dm.gemm(ctx, 0, 0, 1.0, A, B, 0.0, C)
+    assert np.array_equal(C.get(), np.full((300, 300), 300, np.float32))
+    assert torch.cuda.memory_allocated() == before
+    for m in (A, B, C):
+        m.destroy()

@@ -1,0 +1,176 @@
+"""CPU-only tests of the library's host side: the C ABI exports what the header declares, the
+pool, the block split rule, argument checks, and the tile scheduler (no kernel is launched)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1611_07819_amd as dm
+from paper_1611_07819_amd import dmath as binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE_SLAB = 0x7F0000000100      # never dereferenced by host logic
+
+
+@pytest.fixture()
+def ctx():
+    c = dm.Context(FAKE_SLAB, 1 << 30)
+    yield c
+    c.close()
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "dmath.h")).read()
+    names = set(re.findall(r"\b(dmath_[a-z_0-9]+)\s*\(", header))
+    assert {"dmath_init", "dmath_matrix_create", "dmath_gemm", "dmath_conv_fwd",
+            "dmath_conv_bwd_filter", "dmath_conv_bwd_data"} <= names
+    lib = ctypes.CDLL(os.path.join(ROOT, "paper_1611_07819_amd", "libdmath.so"))
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings():
+    assert binding.status_string(0) == "DMATH_OK"
+    assert binding.status_string(6) == "DMATH_ERR_OOM"
+    assert binding.status_string(99) == "DMATH_ERR_UNKNOWN"
+
+
+def test_pool_accounting_alignment_and_reuse(ctx):
+    s0 = ctx.pool_stats()
+    assert s0["in_use"] == 0 and s0["capacity"] == 1 << 30
+    odd = dm.Context(FAKE_SLAB + 8, 1 << 20)         # unaligned slab: the head is given up
+    assert odd.pool_stats()["capacity"] == (1 << 20) - 256
+    assert odd.matrix(4, 4, (1, 1), dm.F32).block(0, 0)["ptr"] == FAKE_SLAB + 256
+    odd.close()
+    a = ctx.matrix(100, 100, (2, 2), dm.F32)        # 4 blocks of 50*50*4 = 10000 -> 10240 each
+    assert ctx.pool_stats()["in_use"] == 4 * 10240
+    ptrs = [a.block(i, j)["ptr"] for i in range(2) for j in range(2)]
+    assert all(p % 256 == 0 for p in ptrs) and len(set(ptrs)) == 4
+    b = ctx.matrix(10, 10, (1, 1), dm.F64)
+    a.destroy()
+    assert ctx.pool_stats()["in_use"] == 1024
+    c = ctx.matrix(100, 100, (2, 2), dm.F32)        # first fit: reuses the hole left by a
+    assert sorted(c.block(i, j)["ptr"] for i in range(2) for j in range(2)) == sorted(ptrs)
+    assert ctx.pool_stats()["high_water"] == 4 * 10240 + 1024
+    b.destroy()
+    c.destroy()
+    assert ctx.pool_stats()["in_use"] == 0
+    big = ctx.matrix(16384, 16383, (1, 1), dm.F32)  # coalescing gave back one contiguous range
+    big.destroy()
+
+
+def test_pool_exhaustion_is_an_error_and_leaks_nothing():
+    c = dm.Context(FAKE_SLAB, 1 << 20)
+    with pytest.raises(dm.DmathError) as e:
+        c.matrix(1024, 1024, (2, 2), dm.F32)         # 4 MiB > 1 MiB
+    assert e.value.code == 6
+    assert c.pool_stats()["in_use"] == 0
+    c.close()
+
+
+def test_split_rule_and_block_shapes(ctx):
+    m = ctx.matrix(10, 7, (3, 2), dm.F16)
+    assert [m.block(i, 0)["rows"] for i in range(3)] == [4, 4, 2]
+    assert [m.block(0, j)["cols"] for j in range(2)] == [4, 3]
+    assert m.block(2, 1)["ld"] == 3
+    assert m.info() == {"rows": 10, "cols": 7, "grid": (3, 2), "dtype": dm.F16}
+    with pytest.raises(dm.DmathError) as e:
+        ctx.matrix(9, 4, (4, 1), dm.F32)             # ceil(9/4) = 3 leaves the 4th part empty
+    assert e.value.code == 3
+    for bad in [(0, 4, (1, 1)), (4, 4, (0, 1)), (4, -1, (1, 1))]:
+        with pytest.raises(dm.DmathError) as e:
+            ctx.matrix(bad[0], bad[1], bad[2], dm.F32)
+        assert e.value.code == 1
+    with pytest.raises(dm.DmathError):
+        ctx.matrix(4, 4, (1, 1), 7)
+
+
+def test_gemm_argument_checks(ctx):
+    A = ctx.matrix(8, 6, (2, 2), dm.F32)
+    B = ctx.matrix(6, 4, (1, 2), dm.F32)
+    C = ctx.matrix(8, 4, (2, 1), dm.F32)
+    assert dm.gemm_plan_info(ctx, 0, 0, A, B, C)["k"] == 6
+
+    def code(fn):
+        with pytest.raises(dm.DmathError) as e:
+            fn()
+        return e.value.code
+    assert code(lambda: dm.gemm_plan_info(ctx, 1, 0, A, B, C)) == 2          # shape
+    assert code(lambda: dm.gemm_plan_info(ctx, 0, 0, A, B, A)) == 5          # alias
+    assert code(lambda: dm.gemm_plan_info(ctx, 0, 2, A, B, C)) == 1          # bad op
+    Ch = ctx.matrix(8, 4, (1, 1), dm.F16)
+    assert code(lambda: dm.gemm_plan_info(ctx, 0, 0, A, B, Ch)) == 4         # f32 in, f16 out
+    Ah = ctx.matrix(8, 6, (1, 1), dm.F16)
+    Bh = ctx.matrix(6, 4, (1, 1), dm.F16)
+    assert dm.gemm_plan_info(ctx, 0, 0, Ah, Bh, C)["m"] == 8                 # f16 in, f32 out
+    assert dm.gemm_plan_info(ctx, 0, 0, Ah, Bh, Ch)["m"] == 8                # f16 in, f16 out
+    assert code(lambda: dm.gemm_plan_info(ctx, 0, 0, Ah, B, C)) == 4         # mixed inputs
+    other = dm.Context(FAKE_SLAB + (1 << 31), 1 << 20)
+    Co = other.matrix(8, 4, (1, 1), dm.F32)
+    assert code(lambda: dm.gemm_plan_info(ctx, 0, 0, A, B, Co)) == 1         # foreign handle
+    # the same checks guard the launching call; errors come back before any device work
+    assert code(lambda: dm.gemm(ctx, 1, 0, 1.0, A, B, 0.0, C)) == 2
+    assert code(lambda: dm.gemm(ctx, 0, 0, 1.0, A, B, 0.0, A)) == 5
+    other.close()
+
+
+def test_scheduler_refines_against_every_grid(ctx):
+    # section 3.2: the grids of A, B and C need not agree.
+    A = ctx.matrix(10, 7, (3, 2), dm.F32)   # rows cut at 4, 8; cols at 4
+    B = ctx.matrix(7, 5, (2, 2), dm.F32)    # rows cut at 4;    cols at 3
+    C = ctx.matrix(10, 5, (2, 1), dm.F32)   # rows cut at 5
+    p = dm.gemm_plan_info(ctx, 0, 0, A, B, C)
+    assert (p["m_segments"], p["n_segments"], p["k_segments"]) == (4, 2, 2)
+    assert p["tiles"] == 8 and p["cached"] == 0
+    assert dm.gemm_plan_info(ctx, 0, 0, A, B, C)["cached"] == 1
+    B3 = ctx.matrix(7, 5, (3, 1), dm.F32)   # rows cut at 3, 6 -> k cuts {3,4,6}
+    p = dm.gemm_plan_info(ctx, 0, 0, A, B3, C)
+    assert (p["n_segments"], p["k_segments"]) == (1, 4)
+    # transposed operands: op(A) = A^T swaps the roles of the two grids of A
+    At = ctx.matrix(7, 10, (2, 3), dm.F32)
+    p = dm.gemm_plan_info(ctx, 1, 0, At, B, C)
+    assert (p["m_segments"], p["k_segments"]) == (4, 2)
+    # destroying an operand drops the cached plan
+    B.destroy()
+    B = ctx.matrix(7, 5, (2, 2), dm.F32)
+    assert dm.gemm_plan_info(ctx, 0, 0, A, B, C)["cached"] == 0
+
+
+def test_scheduler_on_the_benchmark_configs(ctx):
+    big = dm.Context(FAKE_SLAB, 8 << 30)
+    X = big.matrix(1024, 9216, (4, 4), dm.F32)
+    W = big.matrix(9216, 4096, (4, 4), dm.F32)
+    Y = big.matrix(1024, 4096, (4, 4), dm.F32)
+    dW = big.matrix(9216, 4096, (4, 4), dm.F32)
+    dX = big.matrix(1024, 9216, (4, 4), dm.F32)
+    for (ta, tb, a, b, c, mnk) in [(0, 0, X, W, Y, (1024, 4096, 9216)),
+                                   (1, 0, X, Y, dW, (9216, 4096, 1024)),
+                                   (0, 1, Y, W, dX, (1024, 9216, 4096))]:
+        p = dm.gemm_plan_info(big, ta, tb, a, b, c)
+        assert (p["m"], p["n"], p["k"]) == mnk
+        assert (p["m_segments"], p["n_segments"], p["k_segments"]) == (4, 4, 4)
+        assert p["tiles"] * p["tile_m"] * p["tile_n"] == mnk[0] * mnk[1]
+    big.close()
+
+
+def test_conv_argument_checks(ctx):
+    d = dm.ConvDesc(n=4, c=3, h=8, w=8, k=5, r=3, s=3, pad_h=1, pad_w=1)
+    X = ctx.matrix(4, 3 * 64, (2, 1), dm.F16)
+    F = ctx.matrix(5, 27, (1, 1), dm.F16)
+    Y = ctx.matrix(4, 5 * 64, (1, 1), dm.F32)
+
+    def code(fn):
+        with pytest.raises(dm.DmathError) as e:
+            fn()
+        return e.value.code
+    Ybad = ctx.matrix(4, 5 * 63, (1, 1), dm.F32)
+    assert code(lambda: dm.conv_fwd(ctx, d, 1.0, X, F, 0.0, Ybad)) == 2
+    Xcols = ctx.matrix(4, 3 * 64, (1, 2), dm.F16)
+    assert code(lambda: dm.conv_fwd(ctx, d, 1.0, Xcols, F, 0.0, Y)) == 3
+    Y64 = ctx.matrix(4, 5 * 64, (1, 1), dm.F64)
+    assert code(lambda: dm.conv_fwd(ctx, d, 1.0, X, F, 0.0, Y64)) == 4
+    assert code(lambda: dm.conv_fwd(ctx, dm.ConvDesc(4, 3, 8, 8, 5, 3, 3, 1, 1, 0, 1), 1.0, X, F, 0.0, Y)) == 1
+    assert code(lambda: dm.conv_fwd(ctx, dm.ConvDesc(4, 3, 2, 2, 5, 5, 5), 1.0, X, F, 0.0, Y)) == 2
+    assert code(lambda: dm.conv_bwd_filter(ctx, d, 1.0, X, X, 0.0, F)) in (2, 5)
