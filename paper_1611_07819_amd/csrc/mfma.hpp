@@ -16,9 +16,9 @@ typedef double v4d __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ int acc32_row(int lane, int r) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 __device__ __forceinline__ int acc32_col(int lane) { return lane & 31; }
 
-// 16x16 fp64 result tile, 4 registers per lane: register r of lane l holds row 4*(l/16) + r,
-// column l%16.
-__device__ __forceinline__ int acc16d_row(int lane, int r) { return 4 * (lane >> 4) + r; }
+// 16x16 fp64 result tile, 4 registers per lane: register r of lane l holds row 4*r + l/16,
+// column l%16 (checked on the hardware with one-hot operands).
+__device__ __forceinline__ int acc16d_row(int lane, int r) { return 4 * r + (lane >> 4); }
 __device__ __forceinline__ int acc16d_col(int lane) { return lane & 15; }
 
 // D += A(32x2) * B(2x32), fp32.  Lane l supplies A[l%32][l/32] and B[l/32][l%32].
