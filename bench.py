@@ -1,0 +1,164 @@
+"""Benchmark of the hot path on one MI355X.
+
+One step = one pass of configuration 2 (the fp32 fully connected layer of the paper's AlexNet
+workload at its batch of 1024): forward Y = X*W (N,N), weight gradient dW = X^T*dY (T,N) and
+data gradient dX = dY*W^T (N,T), operands resident in HBM as 4x4 block grids.  The reported
+value is TFLOP/s over whole steps; the other configurations are timed per call and listed under
+"calls".  The CPU oracle is timed on a bounded sample of the same workload as a reported
+baseline.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"f16": 2516.6, "f32": 157.3, "f64": 78.6}   # dense MFMA peaks of MI355X
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only-main", action="store_true", help="skip the per-call side table")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run three 1 GiB device-to-device copies (calibrates HBM counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+                 "use --gpus 1")
+
+    import numpy as np
+    import torch
+    import paper_1611_07819_amd as dm
+    from paper_1611_07819_amd import synth
+
+    dm.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+    slab = torch.empty(8 << 30, dtype=torch.uint8, device="cuda:0")
+    ctx = dm.Context(slab, stream=stream.cuda_stream)
+
+    def time_calls(fns, steps, warmup):
+        """ms per pass over fns, HIP events on the stream the kernels are launched on."""
+        for _ in range(warmup):
+            for f in fns:
+                f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for _ in range(steps):
+            for f in fns:
+                f()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3 / steps
+        return e0.elapsed_time(e1) / steps, wall
+
+    # ---------------- main workload: configuration 2 ----------------
+    w = synth.config2()
+    dev = {k: ctx.from_host(v, w.grid) for k, v in w.mats.items()}
+    fns, flops = [], []
+    for c in w.calls:
+        fns.append(lambda c=c: dm.gemm(ctx, int(c.transA), int(c.transB), c.alpha, dev[c.a],
+                                       dev[c.b], c.beta, dev[c.c]))
+        M, N, K = c.mnk(w.mats)
+        flops.append(2.0 * M * N * K)
+    ms_step, wall_ms = time_calls(fns, args.steps, args.warmup)
+    value = sum(flops) / (ms_step * 1e-3) / 1e12
+    # dominant kernel = the GEMM main loop; one launch per call, three launches per step, each
+    # doing the same 2*M*N*K = 77.31 GFLOP.
+    avg_launch_ms = ms_step / len(fns)
+    achieved = (sum(flops) / len(fns)) / (avg_launch_ms * 1e-3) / 1e12
+    calls = {}
+    if not args.only_main:
+        for c, f, fl in zip(w.calls, fns, flops):
+            ms, _ = time_calls([f], max(5, args.steps // 2), 3)
+            calls[f"cfg2.{c.name}"] = {"ms": round(ms, 4), "tflops": round(fl / ms / 1e9, 2),
+                                       "frac_peak": round(fl / ms / 1e9 / PEAK_TFLOPS["f32"], 4)}
+    info = dm.gemm_plan_info(ctx, 0, 0, dev["X"], dev["W"], dev["Y"])
+    for m in dev.values():
+        m.destroy()
+
+    # ---------------- side table: the other configurations, per call ----------------
+    if not args.only_main:
+        def bench_workload(wl, tag, dtype_key):
+            d = {k: ctx.from_host(v, wl.grid) for k, v in wl.mats.items()}
+            for c in wl.calls:
+                M, N, K = c.mnk(wl.mats)
+                fl = 2.0 * M * N * K
+                f = lambda c=c: dm.gemm(ctx, int(c.transA), int(c.transB), c.alpha, d[c.a], d[c.b],
+                                        c.beta, d[c.c])
+                ms, _ = time_calls([f], 10, 3)
+                calls[f"{tag}.{c.name}"] = {"ms": round(ms, 4), "tflops": round(fl / ms / 1e9, 2),
+                                            "frac_peak": round(fl / ms / 1e9 / PEAK_TFLOPS[dtype_key], 4)}
+            for m in d.values():
+                m.destroy()
+        bench_workload(synth.config1(), "cfg1", "f32")
+        bench_workload(synth.config3("f32"), "cfg3_f32out", "f16")
+        bench_workload(synth.config3("f16"), "cfg3_f16out", "f16")
+        bench_workload(synth.config4(), "cfg4", "f64")
+        w5 = synth.config5("f32")
+        d5 = {k: ctx.from_host(v) for k, v in w5.mats.items()}
+        desc = dm.ConvDesc(**w5.conv)
+        fl5 = 2.0 * 50176 * 256 * 2304
+        for name, f in [("fwd", lambda: dm.conv_fwd(ctx, desc, 1.0, d5["X"], d5["F"], 0.0, d5["Y"])),
+                        ("bwd_filter", lambda: dm.conv_bwd_filter(ctx, desc, 1.0, d5["X"], d5["dY"], 0.0, d5["dF"]))]:
+            ms, _ = time_calls([f], 5, 2)
+            calls[f"cfg5.{name}"] = {"ms": round(ms, 4), "tflops": round(fl5 / ms / 1e9, 2),
+                                     "frac_peak": round(fl5 / ms / 1e9 / PEAK_TFLOPS["f16"], 4)}
+        for m in d5.values():
+            m.destroy()
+
+    # ---------------- CPU oracle on a bounded sample (reported baseline only) ----------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import cpu_oracle as oracle
+        blk = {k: oracle.BlockMatrix(v, w.grid) for k, v in w.mats.items()}
+        t0 = time.perf_counter()
+        for c in w.calls:       # the whole step, every output row: a few seconds of CPU work
+            oracle.gemm(c.transA, c.transB, c.alpha, blk[c.a], blk[c.b], c.beta, blk[c.c])
+        t = time.perf_counter() - t0
+        cpu = {"value": round(sum(flops) / t / 1e12, 5), "unit": "TFLOP/s",
+               "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"one whole cfg2 step (all three GEMMs, all rows, 231.9 GFLOP) in {t:.1f} s "
+                         f"including the exact widening of the operands to fp64"}
+
+    if args.copy_probe:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
+    ctx.close()
+    out = {
+        "metric": "GEMM TFLOP/s per shape/precision and % of MI355X MFMA peak (1 GPU)",
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "configs[1]: fp32 FC layer fwd (NN) + dW (TN) + dX (NT), "
+                               "X[1024x9216] W[9216x4096], 4x4 block grids, alpha=1 beta=0",
+                   "gflop_per_step": round(sum(flops) / 1e9, 2), "kernel": info["kernel"],
+                   "tile": [info["tile_m"], info["tile_n"], info["tile_k"]],
+                   "wall_ms_per_step": round(wall_ms, 4)},
+        "frac_of_peak": round(value / PEAK_TFLOPS["f32"], 4),
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 3), "peak": PEAK_TFLOPS["f32"],
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_TFLOPS["f32"], 4),
+                     "traffic": None},
+        "cpu_baseline": cpu,
+        "calls": calls,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
