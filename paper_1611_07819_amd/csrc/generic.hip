@@ -394,6 +394,19 @@ hipError_t launch_gemm_generic(const GemmPlan& p, double alpha, double beta, hip
     return run_gemm_generic<_Float16, float>(p, alpha, beta, st);
 }
 
+// C <- beta * C without reading A or B (alpha == 0), for any tile shape.
+hipError_t launch_gemm_scale_only(const GemmPlan& p, double beta, hipStream_t st)
+{
+    const GemmTables& t = p.t;
+    if (p.in_dtype == DMATH_F64)
+        gemm_reduce_kernel<double, double><<<t.n_tiles, GTHREADS, 0, st>>>(t, 0, 0.0, beta);
+    else if (p.out_dtype == DMATH_F32)
+        gemm_reduce_kernel<float, float><<<t.n_tiles, GTHREADS, 0, st>>>(t, 0, 0.0, beta);
+    else
+        gemm_reduce_kernel<float, _Float16><<<t.n_tiles, GTHREADS, 0, st>>>(t, 0, 0.0, beta);
+    return hipGetLastError();
+}
+
 hipError_t launch_conv_generic(const ConvPlan& p, int mode, double alpha, double beta, hipStream_t st)
 {
     switch (mode) {

@@ -2,21 +2,75 @@
 // preconditions (tile shapes, k-step divisibility, 16-byte alignment).
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+#include <cstring>
+
 #include "context.hpp"
 
 namespace dm {
 
 hipError_t launch_gemm_generic(const GemmPlan& p, double alpha, double beta, hipStream_t st);
+hipError_t launch_gemm_scale_only(const GemmPlan& p, double beta, hipStream_t st);
 hipError_t launch_conv_generic(const ConvPlan& p, int mode, double alpha, double beta, hipStream_t st);
+hipError_t launch_gemm_f32(const GemmPlan& p, double alpha, double beta, hipStream_t st);
+bool gemm_f32_has_shape(int bm, int bn);
+
+namespace {
+
+constexpr int kCUs = 256;
+
+bool all_multiple(const std::vector<int64_t>& v, int64_t q)
+{
+    for (int64_t x : v)
+        if (x % q) return false;
+    return true;
+}
+
+int64_t count_tiles(const SegView& v, int bm, int bn)
+{
+    int64_t tiles = 0;
+    for (int64_t m : *v.mlen)
+        for (int64_t n : *v.nlen) tiles += ((m + bm - 1) / bm) * ((n + bn - 1) / bn);
+    return tiles;
+}
+
+// Optional "BMxBN" override for experiments, e.g. DMATH_TILE=128x64.
+bool env_tile(int* bm, int* bn)
+{
+    const char* e = std::getenv("DMATH_TILE");
+    if (!e) return false;
+    return std::sscanf(e, "%dx%d", bm, bn) == 2;
+}
+
+}  // namespace
 
 GemmChoice choose_gemm(const SegView& v)
 {
     GemmChoice ch;  // generic 64x64x16
-    // Few C tiles and a deep K: split K so that the chip is filled.  The partial sums are
-    // reduced in a fixed order by a second kernel.
-    int64_t tiles = 0;
-    for (int64_t m : *v.mlen)
-        for (int64_t n : *v.nlen) tiles += ((m + ch.tile_m - 1) / ch.tile_m) * ((n + ch.tile_n - 1) / ch.tile_n);
+    if (v.policy == 0 && v.aligned16 && v.in_dtype == DMATH_F32 && all_multiple(*v.klen, 32)) {
+        // candidate shapes, larger first; take the one with the least serialised work per CU
+        const int shapes[][2] = {{128, 128}, {128, 64}};
+        int64_t best_cost = -1;
+        int ebm = 0, ebn = 0;
+        const bool forced = env_tile(&ebm, &ebn);
+        for (auto& s : shapes) {
+            if (forced && (s[0] != ebm || s[1] != ebn)) continue;
+            if (!all_multiple(*v.mlen, s[0]) || !all_multiple(*v.nlen, s[1])) continue;
+            int64_t tiles = count_tiles(v, s[0], s[1]);
+            int64_t cost = ((tiles + kCUs - 1) / kCUs) * s[0] * s[1];
+            if (best_cost < 0 || cost < best_cost) {
+                best_cost = cost;
+                ch.kernel = KERNEL_F32_128;
+                ch.tile_m = s[0];
+                ch.tile_n = s[1];
+                ch.tile_k = 32;
+            }
+        }
+        if (ch.kernel != KERNEL_GENERIC) return ch;
+    }
+    // Generic kernel.  Few C tiles and a deep K: split K so that the chip is filled.  The
+    // partial sums are reduced in a fixed order by a second kernel.
+    int64_t tiles = count_tiles(v, ch.tile_m, ch.tile_n);
     if (tiles < 128 && v.K >= 2048) {
         int64_t want = (512 + tiles - 1) / tiles;
         int64_t max_by_k = v.K / 512;
@@ -27,7 +81,11 @@ GemmChoice choose_gemm(const SegView& v)
 
 hipError_t launch_gemm(const GemmPlan& p, double alpha, double beta, hipStream_t st)
 {
-    return launch_gemm_generic(p, alpha, beta, st);
+    if (alpha == 0.0) return launch_gemm_scale_only(p, beta, st);
+    switch (p.info.kernel) {
+    case KERNEL_F32_128: return launch_gemm_f32(p, alpha, beta, st);
+    default: return launch_gemm_generic(p, alpha, beta, st);
+    }
 }
 
 hipError_t launch_conv(const ConvPlan& p, int mode, double alpha, double beta, hipStream_t st)

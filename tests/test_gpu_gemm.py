@@ -230,3 +230,45 @@ def test_pool_is_the_only_allocator(ctx):
     assert torch.cuda.memory_allocated() == before
     for m in (A, B, C):
         m.destroy()
+
+
+FAST_CASES = [
+    # dtype, (M, N, K), grids (A-as-op, B-as-op, C) chosen so that every segment is a whole
+    # number of tiles and every k-segment a multiple of the k-step of the specialised kernels
+    (dm.F32, (256, 384, 320), ((2, 2), (2, 2), (2, 2))),
+    (dm.F32, (512, 256, 256), ((1, 1), (1, 1), (1, 1))),
+    (dm.F32, (384, 256, 384), ((3, 2), (3, 2), (1, 2))),
+]
+
+
+@pytest.mark.parametrize("dt,mnk,grids", FAST_CASES)
+@pytest.mark.parametrize("ta,tb", OPS)
+def test_specialised_kernels_whole_result(ctx, oracle, dt, mnk, grids, ta, tb):
+    """Sizes that satisfy the preconditions of the specialised kernels: the plan must pick one,
+    the result must match the oracle within the precision's bar, and integer inputs must match
+    bit for bit."""
+    M, N, K = mnk
+    r = np.random.default_rng(400 + M + N + K)
+    ga, gb, gc = grids
+    ga = ga[::-1] if ta else ga          # grids are given for op(A), op(B)
+    gb = gb[::-1] if tb else gb
+    for ints in (False, True):
+        if ints:
+            opA = r.integers(-3, 4, (M, K)).astype(NP[dt])
+            opB = r.integers(-3, 4, (K, N)).astype(NP[dt])
+            C0 = r.integers(-3, 4, (M, N)).astype(NP[dt])
+        else:
+            opA = r.uniform(-1, 1, (M, K)).astype(NP[dt])
+            opB = r.uniform(-1, 1, (K, N)).astype(NP[dt])
+            C0 = r.uniform(-1, 1, (M, N)).astype(NP[dt])
+        ctx.set_kernel_policy(0)
+        dA, dB, dC = ctx.from_host(stored(opA, ta), ga), ctx.from_host(stored(opB, tb), gb), ctx.from_host(C0, gc)
+        assert dm.gemm_plan_info(ctx, ta, tb, dA, dB, dC)["kernel"] != 0
+        for m in (dA, dB, dC):
+            m.destroy()
+        got, ref = run_gemm(ctx, oracle, ta, tb, 1.5 if not ints else 2.0, opA, opB,
+                            -0.5 if not ints else 1.0, C0, (ga, gb, gc))
+        if ints:
+            assert np.array_equal(got.astype(np.float64), ref)
+        else:
+            assert rel_fro(got, ref) <= TOL[dt]
