@@ -177,6 +177,16 @@ dmath_status_t dmath_conv_bwd_data(dmath_ctx_t ctx, const dmath_conv_desc_t *des
  * 1 = always the guarded generic kernel (for testing and debugging).  Drops cached plans. */
 dmath_status_t dmath_set_kernel_policy(dmath_ctx_t ctx, int32_t policy);
 
+/*
+ * Measurement aid (not part of the paper's method): enqueues a register-only kernel in which
+ * every wavefront issues independent chains of the MFMA instruction the GEMM kernels of
+ * `dtype` use, `iters` times 16 instructions per wavefront, and returns in *flops the number
+ * of floating-point operations it performs.  Timing it gives the matrix-core rate the chip
+ * sustains at its clocks under load, to be read beside the nominal peak.
+ */
+dmath_status_t dmath_mfma_peak_probe(dmath_ctx_t ctx, dmath_dtype_t dtype, int32_t iters,
+                                     double *flops);
+
 /* Waits for all work enqueued on the context's stream. */
 dmath_status_t dmath_synchronize(dmath_ctx_t ctx);
 

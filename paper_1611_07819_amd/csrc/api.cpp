@@ -254,6 +254,19 @@ dmath_status_t dmath_set_kernel_policy(dmath_ctx_t ctx, int32_t policy)
     return DMATH_OK;
 }
 
+dmath_status_t dmath_mfma_peak_probe(dmath_ctx_t ctx, dmath_dtype_t dtype, int32_t iters, double* flops)
+{
+    if (!ctx || !flops || !valid_dtype(dtype) || iters <= 0) return DMATH_ERR_INVALID_ARG;
+    void* scratch = ctx->pool.alloc(256);
+    if (!scratch) return DMATH_ERR_OOM;
+    double f = 0;
+    hipError_t e = launch_mfma_peak(dtype, iters, scratch, ctx->stream, &f);
+    ctx->pool.free(scratch);  // the kernel practically never writes; reuse is stream-ordered anyway
+    if (e != hipSuccess) return DMATH_ERR_DEVICE;
+    *flops = f;
+    return DMATH_OK;
+}
+
 dmath_status_t dmath_synchronize(dmath_ctx_t ctx)
 {
     if (!ctx) return DMATH_ERR_INVALID_ARG;

@@ -109,6 +109,7 @@ void drop_all_plans(dmath_ctx_s* ctx);
 // kernels (launch.hip)
 hipError_t launch_gemm(const GemmPlan& p, double alpha, double beta, hipStream_t stream);
 hipError_t launch_conv(const ConvPlan& p, int mode, double alpha, double beta, hipStream_t stream);
+hipError_t launch_mfma_peak(dmath_dtype_t dt, int iters, void* scratch, hipStream_t st, double* flops);
 // Picks kernel, tile shape and split-K; written next to the kernels whose preconditions it checks.
 struct SegView {
     int64_t M, N, K;

@@ -187,9 +187,6 @@ hipError_t launch_shape(const GemmPlan& p, float alpha, float beta, hipStream_t 
 
 }  // namespace
 
-// Tile shapes this file provides.
-bool gemm_f32_has_shape(int bm, int bn) { return (bm == 128 && bn == 128) || (bm == 128 && bn == 64); }
-
 hipError_t launch_gemm_f32(const GemmPlan& p, double alpha, double beta, hipStream_t st)
 {
     const int bm = p.info.tile_m, bn = p.info.tile_n;

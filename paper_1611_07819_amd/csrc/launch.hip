@@ -13,7 +13,7 @@ hipError_t launch_gemm_generic(const GemmPlan& p, double alpha, double beta, hip
 hipError_t launch_gemm_scale_only(const GemmPlan& p, double beta, hipStream_t st);
 hipError_t launch_conv_generic(const ConvPlan& p, int mode, double alpha, double beta, hipStream_t st);
 hipError_t launch_gemm_f32(const GemmPlan& p, double alpha, double beta, hipStream_t st);
-bool gemm_f32_has_shape(int bm, int bn);
+hipError_t launch_gemm_f64(const GemmPlan& p, double alpha, double beta, hipStream_t st);
 
 namespace {
 
@@ -47,9 +47,12 @@ bool env_tile(int* bm, int* bn)
 GemmChoice choose_gemm(const SegView& v)
 {
     GemmChoice ch;  // generic 64x64x16
-    if (v.policy == 0 && v.aligned16 && v.in_dtype == DMATH_F32 && all_multiple(*v.klen, 32)) {
-        // candidate shapes, larger first; take the one with the least serialised work per CU
-        const int shapes[][2] = {{128, 128}, {128, 64}};
+    const bool f32 = v.in_dtype == DMATH_F32 && all_multiple(*v.klen, 32);
+    const bool f64 = v.in_dtype == DMATH_F64 && all_multiple(*v.klen, 16);
+    if (v.policy == 0 && v.aligned16 && (f32 || f64)) {
+        // candidate shapes; take the one with the least serialised work per CU (the first of
+        // equals: measured, the smaller tile is never slower at these sizes)
+        const int shapes[][2] = {{128, 64}, {128, 128}};
         int64_t best_cost = -1;
         int ebm = 0, ebn = 0;
         const bool forced = env_tile(&ebm, &ebn);
@@ -60,10 +63,10 @@ GemmChoice choose_gemm(const SegView& v)
             int64_t cost = ((tiles + kCUs - 1) / kCUs) * s[0] * s[1];
             if (best_cost < 0 || cost < best_cost) {
                 best_cost = cost;
-                ch.kernel = KERNEL_F32_128;
+                ch.kernel = f32 ? KERNEL_F32_128 : KERNEL_F64_128;
                 ch.tile_m = s[0];
                 ch.tile_n = s[1];
-                ch.tile_k = 32;
+                ch.tile_k = f32 ? 32 : 16;
             }
         }
         if (ch.kernel != KERNEL_GENERIC) return ch;
@@ -84,6 +87,7 @@ hipError_t launch_gemm(const GemmPlan& p, double alpha, double beta, hipStream_t
     if (alpha == 0.0) return launch_gemm_scale_only(p, beta, st);
     switch (p.info.kernel) {
     case KERNEL_F32_128: return launch_gemm_f32(p, alpha, beta, st);
+    case KERNEL_F64_128: return launch_gemm_f64(p, alpha, beta, st);
     default: return launch_gemm_generic(p, alpha, beta, st);
     }
 }

@@ -88,6 +88,7 @@ def load_library(build_if_missing: bool = True):
         "dmath_conv_bwd_data": [vp, P(_ConvDesc), dbl, vp, vp, dbl, vp],
         "dmath_set_kernel_policy": [vp, i32],
         "dmath_synchronize": [vp],
+        "dmath_mfma_peak_probe": [vp, ctypes.c_int, i32, P(dbl)],
         "dmath_pool_stats": [vp, P(sz), P(sz), P(sz)],
     }
     for name, args in sig.items():
@@ -136,6 +137,13 @@ class Context:
 
     def set_kernel_policy(self, policy: int):
         _check(self._lib.dmath_set_kernel_policy(self._h, policy), "dmath_set_kernel_policy")
+
+    def mfma_peak_probe(self, dtype: int, iters: int) -> float:
+        """Enqueues the MFMA-only micro-kernel; returns the flops it performs."""
+        f = ctypes.c_double()
+        _check(self._lib.dmath_mfma_peak_probe(self._h, dtype, iters, ctypes.byref(f)),
+               "dmath_mfma_peak_probe")
+        return f.value
 
     def synchronize(self):
         _check(self._lib.dmath_synchronize(self._h), "dmath_synchronize")
