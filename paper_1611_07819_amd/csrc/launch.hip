@@ -14,6 +14,7 @@ hipError_t launch_gemm_scale_only(const GemmPlan& p, double beta, hipStream_t st
 hipError_t launch_conv_generic(const ConvPlan& p, int mode, double alpha, double beta, hipStream_t st);
 hipError_t launch_gemm_f32(const GemmPlan& p, double alpha, double beta, hipStream_t st);
 hipError_t launch_gemm_f64(const GemmPlan& p, double alpha, double beta, hipStream_t st);
+hipError_t launch_gemm_f16(const GemmPlan& p, double alpha, double beta, hipStream_t st);
 
 namespace {
 
@@ -71,6 +72,26 @@ GemmChoice choose_gemm(const SegView& v)
         }
         if (ch.kernel != KERNEL_GENERIC) return ch;
     }
+    if (v.policy == 0 && v.aligned16 && v.in_dtype == DMATH_F16 && all_multiple(*v.klen, 64)) {
+        const int shapes[][2] = {{256, 128}, {128, 128}};
+        int64_t best_cost = -1;
+        int ebm = 0, ebn = 0;
+        const bool forced = env_tile(&ebm, &ebn);
+        for (auto& s : shapes) {
+            if (forced && (s[0] != ebm || s[1] != ebn)) continue;
+            if (!all_multiple(*v.mlen, s[0]) || !all_multiple(*v.nlen, s[1])) continue;
+            int64_t tiles = count_tiles(v, s[0], s[1]);
+            int64_t cost = ((tiles + kCUs - 1) / kCUs) * s[0] * s[1];
+            if (best_cost < 0 || cost < best_cost) {
+                best_cost = cost;
+                ch.kernel = KERNEL_F16_256;
+                ch.tile_m = s[0];
+                ch.tile_n = s[1];
+                ch.tile_k = 64;
+            }
+        }
+        if (ch.kernel != KERNEL_GENERIC) return ch;
+    }
     // Generic kernel.  Few C tiles and a deep K: split K so that the chip is filled.  The
     // partial sums are reduced in a fixed order by a second kernel.
     int64_t tiles = count_tiles(v, ch.tile_m, ch.tile_n);
@@ -88,6 +109,7 @@ hipError_t launch_gemm(const GemmPlan& p, double alpha, double beta, hipStream_t
     switch (p.info.kernel) {
     case KERNEL_F32_128: return launch_gemm_f32(p, alpha, beta, st);
     case KERNEL_F64_128: return launch_gemm_f64(p, alpha, beta, st);
+    case KERNEL_F16_256: return launch_gemm_f16(p, alpha, beta, st);
     default: return launch_gemm_generic(p, alpha, beta, st);
     }
 }

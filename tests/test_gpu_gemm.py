@@ -238,6 +238,9 @@ FAST_CASES = [
     (dm.F32, (256, 384, 320), ((2, 2), (2, 2), (2, 2))),
     (dm.F32, (512, 256, 256), ((1, 1), (1, 1), (1, 1))),
     (dm.F32, (384, 256, 384), ((3, 2), (3, 2), (1, 2))),
+    (dm.F16, (512, 256, 384), ((2, 2), (2, 2), (2, 2))),
+    (dm.F16, (256, 384, 192), ((1, 3), (3, 1), (1, 1))),
+    (dm.F16, (768, 256, 128), ((3, 1), (1, 2), (3, 2))),
     (dm.F64, (256, 384, 160), ((2, 2), (2, 2), (2, 2))),
     (dm.F64, (256, 128, 208), ((1, 1), (1, 1), (1, 1))),
     (dm.F64, (384, 256, 192), ((3, 2), (2, 2), (1, 2))),
