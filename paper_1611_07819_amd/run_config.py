@@ -1,0 +1,75 @@
+"""Runs the calls of one benchmark configuration a few times and prints per-call timings.
+
+    python -m paper_1611_07819_amd.run_config <1|2|3|3h|4|5|5h> [--iters N] [--only CALL]
+        [--copy-probe]
+
+Meant as the target of a profiler (`rocprofv3 ... -- python3 -m paper_1611_07819_amd.run_config 3`):
+inputs are the seeded synthetic recipes of ``synth.py``; nothing is checked here.
+``--copy-probe`` appends three 1 GiB device-to-device copies (a kernel of known traffic that
+calibrates the HBM byte counters)."""
+import argparse
+import os
+import sys
+
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("config")
+    ap.add_argument("--iters", type=int, default=20)
+    ap.add_argument("--only", default=None)
+    ap.add_argument("--copy-probe", action="store_true")
+    args = ap.parse_args()
+    import torch
+    import paper_1611_07819_amd as dm
+    from paper_1611_07819_amd import synth
+
+    make = {"1": synth.config1, "2": synth.config2, "3": lambda: synth.config3("f32"),
+            "3h": lambda: synth.config3("f16"), "4": synth.config4,
+            "5": lambda: synth.config5("f32"), "5h": lambda: synth.config5("f16")}[args.config]
+    w = make()
+    slab = torch.empty(6 << 30, dtype=torch.uint8, device="cuda:0")
+    st = torch.cuda.current_stream()
+    ctx = dm.Context(slab, stream=st.cuda_stream)
+    dev = {k: ctx.from_host(v, w.grid) for k, v in w.mats.items()}
+    calls = []
+    for c in w.calls:
+        M, N, K = c.mnk(w.mats)
+        info = dm.gemm_plan_info(ctx, int(c.transA), int(c.transB), dev[c.a], dev[c.b], dev[c.c])
+        desc = f"kernel {info['kernel']} tile {info['tile_m']}x{info['tile_n']} tiles {info['tiles']} split {info['split_k']}"
+        calls.append((c.name, 2.0 * M * N * K, desc,
+                      lambda c=c: dm.gemm(ctx, int(c.transA), int(c.transB), c.alpha, dev[c.a],
+                                          dev[c.b], c.beta, dev[c.c])))
+    if w.conv:
+        d = dm.ConvDesc(**w.conv)
+        g = w.conv
+        fl = 2.0 * g["n"] * g["h"] * g["w"] * g["k"] * g["c"] * g["r"] * g["s"]
+        calls.append(("conv_fwd", fl, "", lambda: dm.conv_fwd(ctx, d, 1.0, dev["X"], dev["F"], 0.0, dev["Y"])))
+        calls.append(("conv_bwd_filter", fl, "",
+                      lambda: dm.conv_bwd_filter(ctx, d, 1.0, dev["X"], dev["dY"], 0.0, dev["dF"])))
+    for name, fl, desc, f in calls:
+        if args.only and args.only != name:
+            continue
+        for _ in range(3):
+            f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        for _ in range(args.iters):
+            f()
+        e1.record(st)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.iters
+        print(f"{w.name} {name}: {desc}: {ms * 1e3:.1f} us  {fl / ms / 1e9:.1f} TFLOP/s", flush=True)
+    if args.copy_probe:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()
