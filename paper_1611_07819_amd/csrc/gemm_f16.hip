@@ -38,7 +38,6 @@ namespace {
 
 constexpr int BK = 64;
 constexpr int NT = 256;
-constexpr int STAGES = 3;
 typedef short v4s __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) char lds_char;
 
@@ -132,7 +131,7 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int BM, int BN, bool AKC, bool BKC, class TC>
+template <int BM, int BN, int STAGES, bool AKC, bool BKC, class TC>
 __global__ __launch_bounds__(NT) void gemm_f16_kernel(GemmTables t, float alpha, float beta)
 {
     using TA = OperandTile<BM, AKC>;
@@ -243,13 +242,19 @@ __global__ __launch_bounds__(NT) void gemm_f16_kernel(GemmTables t, float alpha,
 #pragma unroll
                 for (int j = 0; j < NTL; ++j) {
                     const int m = i * NTL + j;
+#ifndef DM_DBG_NO_MFMA
                     acc[i][j] = mfma_f16_32x32x16(fa[cur][i], fb[cur][j], acc[i][j]);
+#else
+                    acc[i][j][0] += (float)fa[cur][i][0] * (float)fb[cur][j][0];
+#endif
                     __builtin_amdgcn_sched_barrier(0);
                     if (s + 1 < kSteps && m < kReads) read_frag(cur ^ 1, m, s + 1);
                     // spread kPerTile loads evenly over the kSteps * kMfma slots
                     const int slot = s * kMfma + m;
                     if (PREFETCH && issued < kPerTile && slot * kPerTile >= issued * (kSteps * kMfma)) {
+#ifndef DM_DBG_NO_DMA
                         issue_one(nbase, ab, bb, issued);
+#endif
                         ++issued;
                     }
                     __builtin_amdgcn_sched_barrier(0);
@@ -258,22 +263,40 @@ __global__ __launch_bounds__(NT) void gemm_f16_kernel(GemmTables t, float alpha,
         if (PREFETCH) advance();
     };
 
-    issue_all(0);
-    if (n_ktiles > 1) issue_all(1);
+#ifdef DM_DBG_TIMING
+    uint64_t dbg_t0 = __builtin_amdgcn_s_memtime(), dbg_r0 = __builtin_amdgcn_s_memrealtime();
+    uint64_t dbg_wait = 0, dbg_tw;
+#define DBG_W0 dbg_tw = __builtin_amdgcn_s_memtime();
+#define DBG_W1 dbg_wait += __builtin_amdgcn_s_memtime() - dbg_tw;
+#else
+#define DBG_W0
+#define DBG_W1
+#endif
+    // Prologue: STAGES-1 tiles in flight.
+#pragma unroll
+    for (int p = 0; p < STAGES - 1; ++p)
+        if (p < n_ktiles) issue_all(p);
+#ifdef DM_DBG_TIMING
+    uint64_t dbg_t1 = __builtin_amdgcn_s_memtime();
+#endif
 
-    // k-tile kt is multiplied from stage kt % 3.  Before that, its loads must have landed
-    // (at most the loads of tile kt+1 still outstanding) and every wavefront must be past tile
-    // kt-1, whose stage then receives tile kt+2.
+    // k-tile kt is multiplied from stage kt % STAGES.  Before that, its loads must have landed
+    // (only the loads of the STAGES-2 younger tiles may still be outstanding) and every
+    // wavefront must be past tile kt-1, whose stage then receives tile kt+STAGES-1.
     int stage = 0;
-    for (int kt = 0; kt + 2 < n_ktiles; ++kt) {
-        wait_vmcnt<kPerTile>();
+    int kt = 0;
+    for (; kt + STAGES - 1 < n_ktiles; ++kt) {
+        DBG_W0
+        wait_vmcnt<kPerTile * (STAGES - 2)>();
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        multiply(stage, stage == 0 ? 2 : stage - 1, std::true_type{});
+        DBG_W1
+        multiply(stage, stage == 0 ? STAGES - 1 : stage - 1, std::true_type{});
         asm volatile("" ::: "memory");
         stage = stage == STAGES - 1 ? 0 : stage + 1;
     }
-    if (n_ktiles > 1) {
+    // drain: no more loads to issue; the number of younger tiles in flight shrinks to zero
+    if (STAGES == 3 && kt + 1 < n_ktiles) {
         wait_vmcnt<kPerTile>();
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
@@ -285,6 +308,9 @@ __global__ __launch_bounds__(NT) void gemm_f16_kernel(GemmTables t, float alpha,
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     multiply(stage, 0, std::false_type{});
+#ifdef DM_DBG_TIMING
+    uint64_t dbg_t2 = __builtin_amdgcn_s_memtime();
+#endif
 
     const Panel pc = t.c[tile.mseg * t.n_nseg + tile.nseg];
     TC* c = static_cast<TC*>(const_cast<void*>(pc.ptr));
@@ -301,13 +327,26 @@ __global__ __launch_bounds__(NT) void gemm_f16_kernel(GemmTables t, float alpha,
                 if (beta != 0.f) v += beta * (float)*p;
                 *p = to_out<TC>(v);
             }
+#ifdef DM_DBG_TIMING
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    uint64_t dbg_t3 = __builtin_amdgcn_s_memtime(), dbg_r3 = __builtin_amdgcn_s_memrealtime();
+    if (tid == 0 && tile.m_off == 0 && tile.n_off == 0 && tile.mseg == 0 && tile.nseg == 0) {
+        float* o = reinterpret_cast<float*>(c);
+        o[0] = (float)(dbg_t1 - dbg_t0);  // prologue issue
+        o[1] = (float)(dbg_t2 - dbg_t1);  // main loop
+        o[2] = (float)(dbg_t3 - dbg_t2);  // epilogue
+        o[3] = (float)dbg_wait;           // wait + barrier inside the loop
+        o[4] = (float)(dbg_r3 - dbg_r0);  // 100 MHz ticks
+        o[5] = (float)n_ktiles;
+    }
+#endif
 }
 
-template <int BM, int BN, bool AKC, bool BKC, class TC>
+template <int BM, int BN, int STAGES, bool AKC, bool BKC, class TC>
 hipError_t launch_one(const GemmTables& t, float alpha, float beta, hipStream_t st)
 {
     constexpr int lds_bytes = STAGES * (BM + BN) * BK * 2;
-    auto kern = gemm_f16_kernel<BM, BN, AKC, BKC, TC>;
+    auto kern = gemm_f16_kernel<BM, BN, STAGES, AKC, BKC, TC>;
     static bool configured = false;
     if (!configured) {  // more than 64 KiB of LDS has to be asked for once per kernel
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -319,22 +358,25 @@ hipError_t launch_one(const GemmTables& t, float alpha, float beta, hipStream_t 
     return hipGetLastError();
 }
 
-template <int BM, int BN, class TC>
+template <int BM, int BN, int STAGES, class TC>
 hipError_t launch_shape(const GemmPlan& p, float alpha, float beta, hipStream_t st)
 {
     const GemmTables& t = p.t;
-    if (t.a_kcontig && t.b_kcontig) return launch_one<BM, BN, true, true, TC>(t, alpha, beta, st);
-    if (t.a_kcontig && !t.b_kcontig) return launch_one<BM, BN, true, false, TC>(t, alpha, beta, st);
-    if (!t.a_kcontig && t.b_kcontig) return launch_one<BM, BN, false, true, TC>(t, alpha, beta, st);
-    return launch_one<BM, BN, false, false, TC>(t, alpha, beta, st);
+    if (t.a_kcontig && t.b_kcontig) return launch_one<BM, BN, STAGES, true, true, TC>(t, alpha, beta, st);
+    if (t.a_kcontig && !t.b_kcontig) return launch_one<BM, BN, STAGES, true, false, TC>(t, alpha, beta, st);
+    if (!t.a_kcontig && t.b_kcontig) return launch_one<BM, BN, STAGES, false, true, TC>(t, alpha, beta, st);
+    return launch_one<BM, BN, STAGES, false, false, TC>(t, alpha, beta, st);
 }
 
+// Tile shapes: 256x256 (two 64 KiB stages), 256x128 (three 48 KiB stages), 128x128 (two 32 KiB
+// stages, so that two workgroups share a CU).
 template <class TC>
 hipError_t launch_out(const GemmPlan& p, float alpha, float beta, hipStream_t st)
 {
     const int bm = p.info.tile_m, bn = p.info.tile_n;
-    if (bm == 256 && bn == 128) return launch_shape<256, 128, TC>(p, alpha, beta, st);
-    if (bm == 128 && bn == 128) return launch_shape<128, 128, TC>(p, alpha, beta, st);
+    if (bm == 256 && bn == 256) return launch_shape<256, 256, 2, TC>(p, alpha, beta, st);
+    if (bm == 256 && bn == 128) return launch_shape<256, 128, 3, TC>(p, alpha, beta, st);
+    if (bm == 128 && bn == 128) return launch_shape<128, 128, 2, TC>(p, alpha, beta, st);
     return hipErrorInvalidValue;
 }
 

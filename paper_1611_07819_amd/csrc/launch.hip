@@ -73,7 +73,7 @@ GemmChoice choose_gemm(const SegView& v)
         if (ch.kernel != KERNEL_GENERIC) return ch;
     }
     if (v.policy == 0 && v.aligned16 && v.in_dtype == DMATH_F16 && all_multiple(*v.klen, 64)) {
-        const int shapes[][2] = {{256, 128}, {128, 128}};
+        const int shapes[][2] = {{256, 256}, {256, 128}, {128, 128}};
         int64_t best_cost = -1;
         int ebm = 0, ebn = 0;
         const bool forced = env_tile(&ebm, &ebn);

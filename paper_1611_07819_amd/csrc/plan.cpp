@@ -198,30 +198,56 @@ dmath_status_t get_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_mat
     std::vector<int32_t> kl;
     for (auto& k : ks) kl.push_back((int32_t)k.len);
 
-    // Logical tile order: cells in row-major order, tiles inside a cell in bands of 8 tile-rows
-    // walked column by column, so that a contiguous run of tiles re-uses a narrow set of A row
-    // panels and B column panels out of one L2.
-    std::vector<Tile> tiles;
-    for (size_t mi = 0; mi < ms.size(); ++mi)
-        for (size_t ni = 0; ni < ns.size(); ++ni) {
-            int64_t tm = (ms[mi].len + ch.tile_m - 1) / ch.tile_m;
-            int64_t tn = (ns[ni].len + ch.tile_n - 1) / ch.tile_n;
-            const int64_t band = 8;
-            for (int64_t b0 = 0; b0 < tm; b0 += band)
-                for (int64_t j = 0; j < tn; ++j)
-                    for (int64_t i = b0; i < std::min(tm, b0 + band); ++i) {
-                        Tile t;
-                        t.mseg = (int32_t)mi;
-                        t.nseg = (int32_t)ni;
-                        t.m_off = (int32_t)(i * ch.tile_m);
-                        t.n_off = (int32_t)(j * ch.tile_n);
-                        t.m_len = (int32_t)std::min<int64_t>(ch.tile_m, ms[mi].len - t.m_off);
-                        t.n_len = (int32_t)std::min<int64_t>(ch.tile_n, ns[ni].len - t.n_off);
-                        t.m_glob = (int32_t)(ms[mi].start + t.m_off);
-                        t.n_glob = (int32_t)(ns[ni].start + t.n_off);
-                        tiles.push_back(t);
-                    }
+    // Tiles of all cells form one global grid (every cell of a segment row has the same m
+    // cuts, every cell of a segment column the same n cuts).  Logical order: super-blocks of
+    // SR x SC tiles holding about one XCD's worth of workgroups (32), R/C chosen so that the A row
+    // panels and B column panels a super-block touches are as few bytes as possible; xcd_interleave
+    // then hands contiguous runs of the order to the XCDs, so the workgroups resident on one XCD
+    // at a time share operand panels out of that XCD's L2.
+    struct Cut {
+        int32_t seg, off, len, glob;
+    };
+    auto cuts_of = [](const std::vector<Seg>& segs, int32_t tile) {
+        std::vector<Cut> v;
+        for (size_t si = 0; si < segs.size(); ++si)
+            for (int64_t o = 0; o < segs[si].len; o += tile)
+                v.push_back({(int32_t)si, (int32_t)o, (int32_t)std::min<int64_t>(tile, segs[si].len - o),
+                             (int32_t)(segs[si].start + o)});
+        return v;
+    };
+    const std::vector<Cut> mt = cuts_of(ms, ch.tile_m), nt = cuts_of(ns, ch.tile_n);
+    const int64_t Mt = (int64_t)mt.size(), Nt = (int64_t)nt.size();
+    int64_t SR = 1;
+    {
+        const int64_t P = 32;
+        int64_t best = -1;
+        for (int64_t r = 1; r <= P; r *= 2) {
+            int64_t rr = std::min(r, Mt), cc = std::min((P + rr - 1) / rr, Nt);
+            int64_t cost = (rr * ch.tile_m + cc * ch.tile_n) * 1024 / (rr * cc);  // bytes per tile
+            if (best < 0 || cost < best) {
+                best = cost;
+                SR = rr;
+            }
         }
+    }
+    const int64_t SC = std::min<int64_t>(std::max<int64_t>(1, (32 + SR - 1) / SR), Nt);
+    std::vector<Tile> tiles;
+    tiles.reserve((size_t)(Mt * Nt));
+    for (int64_t i0 = 0; i0 < Mt; i0 += SR)
+        for (int64_t j0 = 0; j0 < Nt; j0 += SC)
+            for (int64_t i = i0; i < std::min(Mt, i0 + SR); ++i)
+                for (int64_t j = j0; j < std::min(Nt, j0 + SC); ++j) {
+                    Tile t;
+                    t.mseg = mt[i].seg;
+                    t.nseg = nt[j].seg;
+                    t.m_off = mt[i].off;
+                    t.n_off = nt[j].off;
+                    t.m_len = mt[i].len;
+                    t.n_len = nt[j].len;
+                    t.m_glob = mt[i].glob;
+                    t.n_glob = nt[j].glob;
+                    tiles.push_back(t);
+                }
     tiles = xcd_interleave(tiles);
 
     auto plan = std::make_unique<GemmPlan>();

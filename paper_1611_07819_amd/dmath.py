@@ -9,7 +9,8 @@ from dataclasses import dataclass
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libdmath.so")
+# DMATH_LIBRARY may point at another build of the same library (debug variants)
+_LIB_PATH = os.environ.get("DMATH_LIBRARY") or os.path.join(_HERE, "libdmath.so")
 
 F64, F32, F16 = 0, 1, 2
 OP_N, OP_T = 0, 1

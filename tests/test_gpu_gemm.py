@@ -278,3 +278,33 @@ def test_specialised_kernels_whole_result(ctx, oracle, dt, mnk, grids, ta, tb):
             assert np.array_equal(got.astype(np.float64), ref)
         else:
             assert rel_fro(got, ref) <= TOL[dt]
+
+
+@pytest.mark.parametrize("dt,shape", [(dm.F16, "256x256"), (dm.F16, "256x128"), (dm.F16, "128x128"),
+                                      (dm.F32, "128x128"), (dm.F32, "128x64"),
+                                      (dm.F64, "128x128"), (dm.F64, "128x64")])
+@pytest.mark.parametrize("ta,tb", OPS)
+def test_every_tile_shape_of_the_specialised_kernels(ctx, oracle, dt, shape, ta, tb, monkeypatch):
+    """The scheduler normally picks the tile shape by cost; DMATH_TILE pins it, so that every
+    compiled shape is checked bit for bit on integer inputs (several k-tiles, several tiles,
+    k-segments of different blocks)."""
+    monkeypatch.setenv("DMATH_TILE", shape)
+    r = np.random.default_rng(500)
+    M, N, K = 512, 768, 448 if dt != dm.F16 else 448 + 64 * 3
+    opA = r.integers(-2, 3, (M, K)).astype(NP[dt])
+    opB = r.integers(-2, 3, (K, N)).astype(NP[dt])
+    C0 = r.integers(-3, 4, (M, N)).astype(NP[dt])
+    ga, gb, gc = (2, 1), (1, 3), (1, 1)
+    ga = ga[::-1] if ta else ga
+    gb = gb[::-1] if tb else gb
+    ctx.set_kernel_policy(0)
+    dA, dB, dC = ctx.from_host(stored(opA, ta), ga), ctx.from_host(stored(opB, tb), gb), ctx.from_host(C0, gc)
+    info = dm.gemm_plan_info(ctx, ta, tb, dA, dB, dC)
+    assert f"{info['tile_m']}x{info['tile_n']}" == shape and info["kernel"] != 0
+    dm.gemm(ctx, ta, tb, 1.0, dA, dB, 1.0, dC)
+    got = dC.get()
+    ref = oracle.gemm(bool(ta), bool(tb), 1.0, oracle.BlockMatrix(stored(opA, ta), ga),
+                      oracle.BlockMatrix(stored(opB, tb), gb), 1.0, oracle.BlockMatrix(C0, gc))
+    assert np.array_equal(got.astype(np.float64), ref)
+    for m in (dA, dB, dC):
+        m.destroy()
