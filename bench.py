@@ -18,6 +18,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"f16": 2516.6, "f32": 157.3, "f64": 78.6}   # dense MFMA peaks of MI355X
+# HBM bytes per launch of the dominant kernel (mean over the three cfg2 GEMMs), from the two
+# rocprofv3 --pmc runs summarised in profiles/gemm_f32_cfg2_hbm_traffic.txt; None until measured.
+MEASURED_TRAFFIC_BYTES = 649041863
 
 
 def main():
@@ -118,6 +121,18 @@ def main():
         for m in d5.values():
             m.destroy()
 
+    # ---------------- MFMA-only probe: what the matrix cores sustain at their clocks under load
+    sustained = {}
+    for key, code, iters in (("f32", dm.F32, 4000), ("f16", dm.F16, 8000), ("f64", dm.F64, 4000)):
+        ctx.mfma_peak_probe(code, 200)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        fl = ctx.mfma_peak_probe(code, iters)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        sustained[key] = round(fl / e0.elapsed_time(e1) / 1e9, 1)
+
     # ---------------- CPU oracle on a bounded sample (reported baseline only) ----------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -153,8 +168,10 @@ def main():
         "frac_of_peak": round(value / PEAK_TFLOPS["f32"], 4),
         "roofline": {"bound": "mfma", "achieved": round(achieved, 3), "peak": PEAK_TFLOPS["f32"],
                      "unit": "TFLOP/s", "frac": round(achieved / PEAK_TFLOPS["f32"], 4),
-                     "traffic": None},
+                     "traffic": MEASURED_TRAFFIC_BYTES},
         "cpu_baseline": cpu,
+        "sustained_mfma_tflops": sustained,
+        "frac_of_sustained": round(value / sustained["f32"], 4),
         "calls": calls,
     }
     print(json.dumps(out))
