@@ -1,23 +1,27 @@
-// Specialised fp32 GEMM for gfx950: C <- alpha * op(A) * op(B) + beta * C on full tiles.
+// Specialised fp32 GEMM for gfx950 on v_mfma_f32_32x32x2_f32:
+// C <- alpha * op(A) * op(B) + beta * C on full tiles (paper abstract: matrix multiplication;
+// section 2.1: blocks; section 1: the transposed variants of back-propagation).
 //
-// One workgroup (256 threads = 4 wavefronts in a 2 x 2 arrangement) owns one BM x BN tile of C
-// that lies inside one block of C, and walks the k-panels of its block row / block column
-// (paper section 2.1: blocks; section 1: the transposed variants of back-propagation).
-// Per k-tile of 32: 128-bit global loads into registers (issued one tile ahead), 128-bit
-// stores into a double-buffered LDS stage, fragments read back in the order the
-// v_mfma_f32_32x32x2_f32 instruction wants them, fused alpha/beta epilogue.
+// One workgroup of 4 wavefronts (2 x 2) per BM x BN tile of C inside one block; the k-panels of
+// the block row / block column are walked 32 at a time through a three-stage LDS ring that is
+// filled by global_load_lds_dwordx4 (16 bytes per lane straight into LDS at M0 + 16*lane, no
+// registers), two tiles in flight while a third is multiplied.  The loads are inline assembly
+// with explicit s_waitcnt vmcnt(); inside a k-tile the instruction order is pinned so that
+// between two MFMAs there is at most one fragment read and one load.
 //
-// LDS layouts (both conflict-free for the accesses used):
-//   operand whose unit-stride axis is k  : [mn][32 k], 16-byte chunks XOR-swizzled by (mn & 7);
-//                                          a lane reads 4 consecutive k with one 128-bit read
-//   operand whose unit-stride axis is m/n: [k][mn] as in memory; a lane reads one value per
-//                                          MFMA with lanes on consecutive addresses
-// The k index inside a group of 8 is permuted identically for A and B (lanes 0-31 take
-// k = 8u+j, lanes 32-63 take k = 8u+4+j at step j), which the sum over k does not notice.
+// LDS layouts, both as the operand lies in memory:
+//   k unit-stride operand  : [mn][32 k], 128-byte rows, 16-byte chunk index XOR
+//                            ((mn ^ (mn>>3)) & 7) (applied by choosing which global chunk a lane
+//                            fetches); one ds_read_b128 gives a lane 4 consecutive k = 4 MFMAs
+//   m/n unit-stride operand: [k][mn]; one ds_read_b32 per MFMA, lanes on consecutive addresses
+// Inside a group of 8 k the order is permuted identically for A and B (lanes 0-31 supply
+// k = 8u+j, lanes 32-63 k = 8u+4+j at step j), which the sum over k does not notice.
 //
-// Preconditions (checked by the chooser): every tile is full, every k-segment is a multiple of
-// 32, every panel origin and leading dimension is 16-byte aligned.
+// Preconditions (checked by the chooser): full tiles, k-segments multiples of 32, 16-byte
+// aligned panel origins and leading dimensions, blocks smaller than 4 GiB.
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 
 #include "context.hpp"
 #include "mfma.hpp"
@@ -28,65 +32,96 @@ namespace {
 
 constexpr int BK = 32;
 constexpr int NT = 256;
+constexpr int STAGES = 3;
+typedef __attribute__((address_space(3))) char lds_char;
+
+__device__ __forceinline__ int swz(int mn) { return (mn ^ (mn >> 3)) & 7; }
+
+__device__ __forceinline__ const char* uniform_ptr(const char* p)
+{
+    uint64_t v = reinterpret_cast<uint64_t>(p);
+    uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const char*>(((uint64_t)hi << 32) | lo);
+}
+
+// One direct global->LDS load: lane fetches 16 bytes at (sbase + voff), lands at m0 + 16*lane.
+__device__ __forceinline__ void dma16(uint32_t lds_addr, const void* sbase, uint32_t voff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(sbase)
+                 : "memory");
+}
+
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
 template <int BMN, bool KC> struct OperandTile {
-    // number of 128-bit loads per thread and k-tile
-    static constexpr int kLoads = BMN * BK / 4 / NT;
-    static constexpr int kChunksPerRow = KC ? BK / 4 : BMN / 4;
-    static constexpr int kRowsPerPass = NT / kChunksPerRow;
+    static constexpr int kInstr = BMN / 32;      // 1 KiB segments per wavefront and k-tile
+    static constexpr int kBytes = BMN * BK * 4;  // one stage of this operand
+    static constexpr int kChunksPerRow = KC ? 8 : BMN / 4;
+    static constexpr int kRowsPerSeg = 64 / kChunksPerRow;
+    static constexpr int kReadsPerFrag = KC ? 1 : 4;
 
-    // global -> registers.  base points at the panel origin (element (0,0) of the panel);
-    // mn0 = offset of the tile inside the panel, k0 = offset of the k-tile inside the panel.
-    __device__ __forceinline__ static void load(const float* base, int64_t ld, int mn0, int k0,
-                                                int tid, v4f (&r)[kLoads])
+    // byte offsets (relative to the panel origin) of the chunks this lane fetches at k-tile 0
+    __device__ __forceinline__ static void offsets(int64_t ld, int mn0, int wave, int lane,
+                                                   uint32_t (&off)[kInstr])
     {
-        const int chunk = tid % kChunksPerRow, row0 = tid / kChunksPerRow;
 #pragma unroll
-        for (int q = 0; q < kLoads; ++q) {
-            const int row = row0 + q * kRowsPerPass;
-            const float* p = KC ? base + (int64_t)(mn0 + row) * ld + k0 + chunk * 4
-                                : base + (int64_t)(k0 + row) * ld + mn0 + chunk * 4;
-            r[q] = *reinterpret_cast<const v4f*>(p);
+        for (int q = 0; q < kInstr; ++q) {
+            const int seg = q * 4 + wave;
+            const int row = seg * kRowsPerSeg + lane / kChunksPerRow;
+            const int cpos = lane % kChunksPerRow;
+            if (KC)
+                off[q] = (uint32_t)((((int64_t)(mn0 + row)) * ld + (cpos ^ swz(row)) * 4) * 4);
+            else
+                off[q] = (uint32_t)(((int64_t)row * ld + mn0 + cpos * 4) * 4);
         }
     }
+    __device__ __forceinline__ static int64_t step(int64_t ld) { return KC ? BK * 4 : BK * 4 * ld; }
 
-    // registers -> LDS stage
-    __device__ __forceinline__ static void store(float* lds, int tid, const v4f (&r)[kLoads])
+    // Part `part` of the fragment of group u (4 MFMA steps) for the lane whose row/column is mn.
+    // k unit-stride: the whole fragment in one read (part 0); otherwise one value per part.
+    __device__ __forceinline__ static void read(const lds_char* tile, int mn, int h, int u, int part,
+                                                v4f& frag)
     {
-        const int chunk = tid % kChunksPerRow, row0 = tid / kChunksPerRow;
-#pragma unroll
-        for (int q = 0; q < kLoads; ++q) {
-            const int row = row0 + q * kRowsPerPass;
-            float* p = KC ? lds + row * BK + ((chunk ^ (row & 7)) << 2) : lds + row * BMN + chunk * 4;
-            *reinterpret_cast<v4f*>(p) = r[q];
+        if (KC) {
+            frag = *reinterpret_cast<const __attribute__((address_space(3))) v4f*>(
+                tile + mn * 128 + ((((u << 1) + h) ^ swz(mn)) << 4));
+        } else {
+            frag[part] = *reinterpret_cast<const __attribute__((address_space(3))) float*>(
+                tile + ((8 * u + 4 * h + part) * BMN + mn) * 4);
         }
-    }
-
-    // The four values (steps j = 0..3 of group u) that lane (mn, h) feeds to the MFMA.
-    __device__ __forceinline__ static v4f fragment(const float* lds, int mn, int h, int u)
-    {
-        if (KC) return *reinterpret_cast<const v4f*>(lds + mn * BK + ((((u << 1) + h) ^ (mn & 7)) << 2));
-        v4f f;
-        const float* p = lds + (8 * u + 4 * h) * BMN + mn;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) f[j] = p[j * BMN];
-        return f;
     }
 };
 
-template <int BM, int BN, bool AKC, bool BKC>
+template <int BMN, bool KC> struct KCheck {
+    static constexpr bool ok = KC || (64 % (BMN / 4) == 0);
+};
+
+// WVM x WVN = 4: arrangement of the wavefronts over the tile.
+template <int BM, int BN, int WVM, bool AKC, bool BKC>
 __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmTables t, float alpha, float beta)
 {
     using TA = OperandTile<BM, AKC>;
     using TB = OperandTile<BN, BKC>;
-    constexpr int WM = BM / 2, WN = BN / 2;  // wavefront tile
+    constexpr int WVN = 4 / WVM;
+    constexpr int WM = BM / WVM, WN = BN / WVN;  // wavefront tile
+    static_assert(KCheck<BM, AKC>::ok && KCheck<BN, BKC>::ok, "m/n-major tiles must fill whole LDS segments");
     constexpr int MT = WM / 32, NTL = WN / 32;
-    __shared__ __attribute__((aligned(16))) float lds_a[2][BM * BK];
-    __shared__ __attribute__((aligned(16))) float lds_b[2][BN * BK];
+    constexpr int kStage = TA::kBytes + TB::kBytes;
+    constexpr int kPerTile = TA::kInstr + TB::kInstr;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const lds_char* lds = (const lds_char*)smem;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
 
     const Tile tile = t.tiles[blockIdx.x];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1, h = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WVN, wn = wave % WVN, h = lane >> 5, l32 = lane & 31;
 
     v16f acc[MT][NTL];
 #pragma unroll
@@ -96,60 +131,150 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmTables t, float alpha,
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // walk of the k-panels: position of the next k-tile to fetch
+    // walk of the k-panels by the loader
     const int ks_end = t.n_kseg;
-    int ks = 0, k0 = 0;
+    int ks = 0, kleft;
     int n_ktiles = 0;
     for (int s = 0; s < ks_end; ++s) n_ktiles += t.klen[s] / BK;
     Panel pa = t.a[tile.mseg * t.n_kseg], pb = t.b[tile.nseg];
-    int klen = t.klen[0];
+    kleft = t.klen[0] / BK;
+    const char* abase = static_cast<const char*>(pa.ptr);
+    const char* bbase = static_cast<const char*>(pb.ptr);
+    uint32_t aoff[TA::kInstr], boff[TB::kInstr];
+    TA::offsets(pa.ld, tile.m_off, wave, lane, aoff);
+    TB::offsets(pb.ld, tile.n_off, wave, lane, boff);
 
-    v4f ra[TA::kLoads], rb[TB::kLoads];
-    auto fetch = [&]() {
-        TA::load(static_cast<const float*>(pa.ptr), pa.ld, tile.m_off, k0, tid, ra);
-        TB::load(static_cast<const float*>(pb.ptr), pb.ld, tile.n_off, k0, tid, rb);
-        k0 += BK;
-        if (k0 >= klen && ks + 1 < ks_end) {
+    auto issue_one = [&](uint32_t sbase, const char* ab, const char* bb, int idx) {
+        if (idx < TA::kInstr)
+            dma16(sbase + (idx * 4 + wave) * 1024, ab, aoff[idx]);
+        else
+            dma16(sbase + TA::kBytes + ((idx - TA::kInstr) * 4 + wave) * 1024, bb, boff[idx - TA::kInstr]);
+    };
+    auto advance = [&]() {
+        abase += TA::step(pa.ld);
+        bbase += TB::step(pb.ld);
+        if (--kleft == 0 && ks + 1 < ks_end) {
             ++ks;
-            k0 = 0;
             pa = t.a[tile.mseg * t.n_kseg + ks];
             pb = t.b[ks * t.n_nseg + tile.nseg];
-            klen = t.klen[ks];
+            kleft = t.klen[ks] / BK;
+            abase = static_cast<const char*>(pa.ptr);
+            bbase = static_cast<const char*>(pb.ptr);
+            TA::offsets(pa.ld, tile.m_off, wave, lane, aoff);
+            TB::offsets(pb.ld, tile.n_off, wave, lane, boff);
         }
     };
+    auto issue_all = [&](int stage) {
+        const uint32_t sbase = lds0 + stage * kStage;
+        const char* ab = uniform_ptr(abase);
+        const char* bb = uniform_ptr(bbase);
+#pragma unroll
+        for (int idx = 0; idx < kPerTile; ++idx) issue_one(sbase, ab, bb, idx);
+        advance();
+    };
 
-    fetch();
-    TA::store(lds_a[0], tid, ra);
-    TB::store(lds_b[0], tid, rb);
-    __syncthreads();
-    if (n_ktiles > 1) fetch();
-
-    for (int kt = 0; kt < n_ktiles; ++kt) {
-        const int cur = kt & 1;
-        const float* sa = lds_a[cur];
-        const float* sb = lds_b[cur];
+    // Multiplies the tile in `stage`: 4 groups of 8 k, each group 4 MFMA steps on every pair of
+    // fragments.  While group u is multiplied the fragments of group u+1 are read (register
+    // double buffer), one read unit after each MFMA, and -- when PREFETCH -- the loads of the
+    // tile two ahead are spread over the MFMA slots.
+    auto multiply = [&](int stage, int next_stage, auto prefetch) {
+        constexpr bool PREFETCH = decltype(prefetch)::value;
+        constexpr int kGroups = BK / 8, kMfma = 4 * MT * NTL;
+        constexpr int kUnitsA = MT * TA::kReadsPerFrag, kUnits = kUnitsA + NTL * TB::kReadsPerFrag;
+        constexpr int kPerSlot = (kUnits + kMfma - 1) / kMfma;
+        static_assert(kGroups * kMfma >= kPerTile, "not enough slots to spread the loads");
+        const lds_char* sa = lds + stage * kStage;
+        const lds_char* sb = sa + TA::kBytes;
+        const uint32_t nbase = lds0 + next_stage * kStage;
+        const char* ab = uniform_ptr(abase);
+        const char* bb = uniform_ptr(bbase);
+        v4f fa[2][MT], fb[2][NTL];
+        auto read_unit = [&](int buf, int r, int u) {
+            if (r < kUnitsA)
+                TA::read(sa, wm * WM + (r / TA::kReadsPerFrag) * 32 + l32, h, u, r % TA::kReadsPerFrag,
+                         fa[buf][r / TA::kReadsPerFrag]);
+            else
+                TB::read(sb, wn * WN + ((r - kUnitsA) / TB::kReadsPerFrag) * 32 + l32, h, u,
+                         (r - kUnitsA) % TB::kReadsPerFrag, fb[buf][(r - kUnitsA) / TB::kReadsPerFrag]);
+        };
 #pragma unroll
-        for (int u = 0; u < BK / 8; ++u) {
-            v4f fa[MT], fb[NTL];
+        for (int r = 0; r < kUnits; ++r) read_unit(0, r, 0);
+        int issued = 0;
 #pragma unroll
-            for (int i = 0; i < MT; ++i) fa[i] = TA::fragment(sa, wm * WM + i * 32 + l32, h, u);
-#pragma unroll
-            for (int j = 0; j < NTL; ++j) fb[j] = TB::fragment(sb, wn * WN + j * 32 + l32, h, u);
+        for (int u = 0; u < kGroups; ++u) {
+            const int cur = u & 1;
 #pragma unroll
             for (int s = 0; s < 4; ++s)
 #pragma unroll
                 for (int i = 0; i < MT; ++i)
 #pragma unroll
-                    for (int j = 0; j < NTL; ++j)
-                        acc[i][j] = mfma_f32_32x32x2(fa[i][s], fb[j][s], acc[i][j]);
+                    for (int j = 0; j < NTL; ++j) {
+                        const int m = (s * MT + i) * NTL + j;
+                        acc[i][j] = mfma_f32_32x32x2(fa[cur][i][s], fb[cur][j][s], acc[i][j]);
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (u + 1 < kGroups) {
+#pragma unroll
+                            for (int q = 0; q < kPerSlot; ++q)
+                                if (m * kPerSlot + q < kUnits) read_unit(cur ^ 1, m * kPerSlot + q, u + 1);
+                        }
+                        const int slot = u * kMfma + m;
+                        if (PREFETCH && issued < kPerTile && slot * kPerTile >= issued * (kGroups * kMfma)) {
+                            issue_one(nbase, ab, bb, issued);
+                            ++issued;
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
         }
-        if (kt + 1 < n_ktiles) {
-            TA::store(lds_a[cur ^ 1], tid, ra);
-            TB::store(lds_b[cur ^ 1], tid, rb);
-            __syncthreads();
-            if (kt + 2 < n_ktiles) fetch();
-        }
+        if (PREFETCH) advance();
+    };
+
+#ifdef DM_DBG_TIMING
+    uint64_t dbg_t0 = __builtin_amdgcn_s_memtime(), dbg_r0 = __builtin_amdgcn_s_memrealtime();
+    uint64_t dbg_wait = 0, dbg_tw;
+#define DBG_W0 dbg_tw = __builtin_amdgcn_s_memtime();
+#define DBG_W1 dbg_wait += __builtin_amdgcn_s_memtime() - dbg_tw;
+#else
+#define DBG_W0
+#define DBG_W1
+#endif
+    // Prologue: STAGES-1 tiles in flight.
+#pragma unroll
+    for (int p = 0; p < STAGES - 1; ++p)
+        if (p < n_ktiles) issue_all(p);
+#ifdef DM_DBG_TIMING
+    uint64_t dbg_t1 = __builtin_amdgcn_s_memtime();
+#endif
+
+    // k-tile kt is multiplied from stage kt % STAGES.  Before that, its loads must have landed
+    // (only the loads of the younger tile may still be outstanding) and every wavefront must be
+    // past tile kt-1, whose stage then receives tile kt+2.
+    int stage = 0;
+    int kt = 0;
+    for (; kt + STAGES - 1 < n_ktiles; ++kt) {
+        DBG_W0
+        wait_vmcnt<kPerTile>();
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        DBG_W1
+        multiply(stage, stage == 0 ? STAGES - 1 : stage - 1, std::true_type{});
+        asm volatile("" ::: "memory");
+        stage = stage == STAGES - 1 ? 0 : stage + 1;
     }
+    if (kt + 1 < n_ktiles) {
+        wait_vmcnt<kPerTile>();
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        multiply(stage, 0, std::false_type{});
+        asm volatile("" ::: "memory");
+        stage = stage == STAGES - 1 ? 0 : stage + 1;
+    }
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    multiply(stage, 0, std::false_type{});
+#ifdef DM_DBG_TIMING
+    uint64_t dbg_t2 = __builtin_amdgcn_s_memtime();
+#endif
 
     // epilogue: register r of a 32x32 result tile holds row 8*(r/4) + 4*h + r%4, column l32
     const Panel pc = t.c[tile.mseg * t.n_nseg + tile.nseg];
@@ -167,31 +292,59 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmTables t, float alpha,
                 if (beta != 0.f) v += beta * *p;
                 *p = v;
             }
+#ifdef DM_DBG_TIMING
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    uint64_t dbg_t3 = __builtin_amdgcn_s_memtime(), dbg_r3 = __builtin_amdgcn_s_memrealtime();
+    if (tid == 0 && tile.m_off == 0 && tile.n_off == 0 && tile.mseg == 0 && tile.nseg == 0) {
+        c[0] = (float)(dbg_t1 - dbg_t0);
+        c[1] = (float)(dbg_t2 - dbg_t1);
+        c[2] = (float)(dbg_t3 - dbg_t2);
+        c[3] = (float)dbg_wait;
+        c[4] = (float)(dbg_r3 - dbg_r0);
+        c[5] = (float)n_ktiles;
+    }
+#endif
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int WVM, bool AKC, bool BKC>
+hipError_t launch_one(const GemmTables& t, float alpha, float beta, hipStream_t st)
+{
+    constexpr int lds_bytes = STAGES * (BM + BN) * BK * 4;
+    auto kern = gemm_f32_kernel<BM, BN, WVM, AKC, BKC>;
+    static bool configured = false;
+    if (!configured) {  // more than 64 KiB of LDS has to be asked for once per kernel
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    kern<<<dim3(t.n_tiles), dim3(NT), lds_bytes, st>>>(t, alpha, beta);
+    return hipGetLastError();
+}
+
+template <int BM, int BN, int WVM>
 hipError_t launch_shape(const GemmPlan& p, float alpha, float beta, hipStream_t st)
 {
     const GemmTables& t = p.t;
-    dim3 grid(t.n_tiles), block(NT);
-    if (t.a_kcontig && t.b_kcontig)
-        gemm_f32_kernel<BM, BN, true, true><<<grid, block, 0, st>>>(t, alpha, beta);
-    else if (t.a_kcontig && !t.b_kcontig)
-        gemm_f32_kernel<BM, BN, true, false><<<grid, block, 0, st>>>(t, alpha, beta);
-    else if (!t.a_kcontig && t.b_kcontig)
-        gemm_f32_kernel<BM, BN, false, true><<<grid, block, 0, st>>>(t, alpha, beta);
-    else
-        gemm_f32_kernel<BM, BN, false, false><<<grid, block, 0, st>>>(t, alpha, beta);
-    return hipGetLastError();
+    if (t.a_kcontig && t.b_kcontig) return launch_one<BM, BN, WVM, true, true>(t, alpha, beta, st);
+    if (!t.a_kcontig && t.b_kcontig) return launch_one<BM, BN, WVM, false, true>(t, alpha, beta, st);
+    if constexpr (64 % (BN / 4) == 0) {  // an m/n-major B tile must fill whole 1 KiB LDS segments
+        if (t.a_kcontig) return launch_one<BM, BN, WVM, true, false>(t, alpha, beta, st);
+        return launch_one<BM, BN, WVM, false, false>(t, alpha, beta, st);
+    }
+    return hipErrorInvalidValue;
 }
 
 }  // namespace
 
+// 128x96 (wavefronts 4 x 1) exists for outputs whose tile count would otherwise leave the last
+// round of workgroups mostly empty; it needs a k-major B.
 hipError_t launch_gemm_f32(const GemmPlan& p, double alpha, double beta, hipStream_t st)
 {
     const int bm = p.info.tile_m, bn = p.info.tile_n;
-    if (bm == 128 && bn == 128) return launch_shape<128, 128>(p, (float)alpha, (float)beta, st);
-    if (bm == 128 && bn == 64) return launch_shape<128, 64>(p, (float)alpha, (float)beta, st);
+    if (bm == 128 && bn == 128) return launch_shape<128, 128, 2>(p, (float)alpha, (float)beta, st);
+    if (bm == 128 && bn == 64) return launch_shape<128, 64, 2>(p, (float)alpha, (float)beta, st);
+    if (bm == 128 && bn == 96) return launch_shape<128, 96, 4>(p, (float)alpha, (float)beta, st);
     return hipErrorInvalidValue;
 }
 

@@ -7,7 +7,7 @@
 // (BM/2) x (BN/2) tile as a grid of 16 x 16 result tiles.
 //
 // LDS layouts:
-//   k unit-stride operand  : [mn][16 k], 16-byte chunks (2 doubles) XOR-swizzled by (mn & 7);
+//   k unit-stride operand  : [mn][16 k], 16-byte chunks (2 doubles) XOR-swizzled by ((mn ^ (mn >> 3)) & 7);
 //                            one 128-bit read gives a lane its values for two MFMA steps
 //   m/n unit-stride operand: [k][mn]; one 64-bit read per MFMA step, lanes on consecutive
 //                            addresses
@@ -27,6 +27,10 @@ namespace {
 
 constexpr int BK = 16;
 constexpr int NT = 256;
+
+// XOR applied to the 16-byte chunk index of row mn: rows 8 apart differ too, so that the 16 lanes
+// served per LDS cycle never meet in a bank.
+__device__ __forceinline__ int swz(int mn) { return (mn ^ (mn >> 3)) & 7; }
 typedef double v2d __attribute__((ext_vector_type(2)));
 
 template <int BMN, bool KC> struct OperandTile {
@@ -53,7 +57,7 @@ template <int BMN, bool KC> struct OperandTile {
 #pragma unroll
         for (int q = 0; q < kLoads; ++q) {
             const int row = row0 + q * kRowsPerPass;
-            double* p = KC ? lds + row * BK + ((chunk ^ (row & 7)) << 1) : lds + row * BMN + chunk * 2;
+            double* p = KC ? lds + row * BK + ((chunk ^ swz(row)) << 1) : lds + row * BMN + chunk * 2;
             *reinterpret_cast<v2d*>(p) = r[q];
         }
     }
@@ -61,7 +65,7 @@ template <int BMN, bool KC> struct OperandTile {
     // values of steps j = 0, 1 of group u for lane (mn, g)
     __device__ __forceinline__ static v2d fragment(const double* lds, int mn, int g, int u)
     {
-        if (KC) return *reinterpret_cast<const v2d*>(lds + mn * BK + ((((u << 2) + g) ^ (mn & 7)) << 1));
+        if (KC) return *reinterpret_cast<const v2d*>(lds + mn * BK + ((((u << 2) + g) ^ swz(mn)) << 1));
         v2d f;
         const double* p = lds + (8 * u + 2 * g) * BMN + mn;
         f[0] = p[0];

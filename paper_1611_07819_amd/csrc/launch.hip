@@ -51,22 +51,29 @@ GemmChoice choose_gemm(const SegView& v)
     const bool f32 = v.in_dtype == DMATH_F32 && all_multiple(*v.klen, 32);
     const bool f64 = v.in_dtype == DMATH_F64 && all_multiple(*v.klen, 16);
     if (v.policy == 0 && v.aligned16 && (f32 || f64)) {
-        // candidate shapes; take the one with the least serialised work per CU (the first of
-        // equals: measured, the smaller tile is never slower at these sizes)
-        const int shapes[][2] = {{128, 64}, {128, 128}};
-        int64_t best_cost = -1;
+        // Candidate shapes; take the one with the least serialised work per CU.  Smaller tiles
+        // move more bytes per flop, which costs clock at the power limit: 3 % handicap
+        // (measured on configuration 2: 128x128 beats 128x64 when both fill the chip evenly).
+        struct Shape {
+            int bm, bn;
+            bool needs_b_kcontig, f32_only;
+        };
+        const Shape shapes[] = {{128, 128, false, false}, {128, 64, false, false}, {128, 96, true, true}};
+        double best_cost = -1;
         int ebm = 0, ebn = 0;
         const bool forced = env_tile(&ebm, &ebn);
         for (auto& s : shapes) {
-            if (forced && (s[0] != ebm || s[1] != ebn)) continue;
-            if (!all_multiple(*v.mlen, s[0]) || !all_multiple(*v.nlen, s[1])) continue;
-            int64_t tiles = count_tiles(v, s[0], s[1]);
-            int64_t cost = ((tiles + kCUs - 1) / kCUs) * s[0] * s[1];
+            if (forced && (s.bm != ebm || s.bn != ebn)) continue;
+            if ((s.needs_b_kcontig && !v.b_kcontig) || (s.f32_only && !f32)) continue;
+            if (!all_multiple(*v.mlen, s.bm) || !all_multiple(*v.nlen, s.bn)) continue;
+            int64_t tiles = count_tiles(v, s.bm, s.bn);
+            double cost = (double)((tiles + kCUs - 1) / kCUs) * s.bm * s.bn;
+            if (s.bm * s.bn < 128 * 128) cost *= 1.03;
             if (best_cost < 0 || cost < best_cost) {
                 best_cost = cost;
                 ch.kernel = f32 ? KERNEL_F32_128 : KERNEL_F64_128;
-                ch.tile_m = s[0];
-                ch.tile_n = s[1];
+                ch.tile_m = s.bm;
+                ch.tile_n = s.bn;
                 ch.tile_k = f32 ? 32 : 16;
             }
         }

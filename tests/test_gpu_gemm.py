@@ -281,16 +281,18 @@ def test_specialised_kernels_whole_result(ctx, oracle, dt, mnk, grids, ta, tb):
 
 
 @pytest.mark.parametrize("dt,shape", [(dm.F16, "256x256"), (dm.F16, "256x128"), (dm.F16, "128x128"),
-                                      (dm.F32, "128x128"), (dm.F32, "128x64"),
+                                      (dm.F32, "128x128"), (dm.F32, "128x64"), (dm.F32, "128x96"),
                                       (dm.F64, "128x128"), (dm.F64, "128x64")])
 @pytest.mark.parametrize("ta,tb", OPS)
 def test_every_tile_shape_of_the_specialised_kernels(ctx, oracle, dt, shape, ta, tb, monkeypatch):
     """The scheduler normally picks the tile shape by cost; DMATH_TILE pins it, so that every
     compiled shape is checked bit for bit on integer inputs (several k-tiles, several tiles,
     k-segments of different blocks)."""
+    if shape == "128x96" and not tb:
+        pytest.skip("the 128x96 fp32 tile needs a k-major B (transB = T)")
     monkeypatch.setenv("DMATH_TILE", shape)
     r = np.random.default_rng(500)
-    M, N, K = 512, 768, 448 if dt != dm.F16 else 448 + 64 * 3
+    M, N, K = 512, (576 if shape == "128x96" else 768), 448 if dt != dm.F16 else 448 + 64 * 3
     opA = r.integers(-2, 3, (M, K)).astype(NP[dt])
     opB = r.integers(-2, 3, (K, N)).astype(NP[dt])
     C0 = r.integers(-3, 4, (M, N)).astype(NP[dt])
