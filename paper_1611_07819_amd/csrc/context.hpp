@@ -67,7 +67,11 @@ struct ConvPlan {
     ConvTables t{};
     void* dev_tables = nullptr;
     void* workspace = nullptr;
-    int32_t kernel = 0;
+    // specialised fp16 path: channels-last copies kept in the pool (rewritten by every call)
+    void* xp = nullptr;  // [n][h+2ph][w+2pw][c], zero border
+    void* fp = nullptr;  // [k][(r,s,c)]
+    void* yt = nullptr;  // [n*oh*ow][k]
+    int32_t kernel = 0;  // 0 generic, 1 specialised fp16
     dmath_dtype_t in_dtype = DMATH_F16, out_dtype = DMATH_F32;
 };
 
@@ -109,6 +113,9 @@ void drop_all_plans(dmath_ctx_s* ctx);
 // kernels (launch.hip)
 hipError_t launch_gemm(const GemmPlan& p, double alpha, double beta, hipStream_t stream);
 hipError_t launch_conv(const ConvPlan& p, int mode, double alpha, double beta, hipStream_t stream);
+bool conv_f16_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype);
+int conv_f16_wgrad_split(const ConvGeom& g);
+hipError_t launch_conv_f16(const ConvPlan& p, int mode, double alpha, double beta, hipStream_t st);
 hipError_t launch_mfma_peak(dmath_dtype_t dt, int iters, void* scratch, hipStream_t st, double* flops);
 // Picks kernel, tile shape and split-K; written next to the kernels whose preconditions it checks.
 struct SegView {

@@ -1,0 +1,400 @@
+// Specialised fp16 convolution kernels for gfx950 (stride 1): forward and weight gradient as
+// implicit GEMMs on the MFMA pipeline of f16_pipeline.hpp (paper abstract: convolutions;
+// section 1: data reorganisation to support a series of operations).
+//
+// NCHW keeps pixels, not channels, contiguous, and the 3x3 taps shift the pixel index by +-1,
+// which no 16-byte load can follow.  So every call first rewrites its activations into a
+// zero-bordered channels-last copy in the pool,
+//     Xp[n][h + 2*pad_h][w + 2*pad_w][c]          (borders zeroed once, when the plan is made)
+// after which row (n, oh, ow) of the lowered matrix for tap (r, s) is the contiguous c-vector
+// at Xp[n][oh + r][ow + s][:]: a k unit-stride operand whose rows are gathered, with K ordered
+// (r, s, c) and no masks.  The filter is permuted to the same K order, Fp[k][(r,s,c)].
+//   forward        : Y[m, k]   = sum_K  Xp-rows[m, K] * Fp[k, K]          (N,T)-like, M = n*oh*ow
+//   weight gradient: dF[k, K]  = sum_m  Yt[m, k] * Xp-rows[m, K]          (T,N)-like, deep sum over
+//                    m, split over workgroups, fixed-order reduction; Yt = dY rewritten
+//                    channels-last, [m][k].
+// The rewrites are part of every call (activations change every step); their cost is inside
+// the timed region.
+#include <hip/hip_runtime.h>
+
+#include "context.hpp"
+#include "f16_pipeline.hpp"
+
+namespace dm {
+
+namespace {
+
+using namespace f16p;
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+
+// ------------------------------------------------------------------------------------------
+// layout rewrites
+// ------------------------------------------------------------------------------------------
+
+// src rows: image n -> [ch][hw] halfs (NCHW inside a row).  dst: [n][HP][WP][ch] with the image
+// placed at (ph, pw).  One workgroup moves 64 channels of one image through LDS: fully
+// coalesced 16-byte reads of the 64 planes, 128-byte writes per pixel.
+__global__ __launch_bounds__(256) void to_channels_last_kernel(const void* const* src_rows, int ch,
+                                                               int h, int w, int ph, int pw, int hp,
+                                                               int wp, _Float16* dst)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    _Float16* planes = reinterpret_cast<_Float16*>(smem);  // [64][hw + 8]
+    const int hw = h * w, stride = hw + 8;                 // +8 halfs: planes start on different banks
+    const int chunks_c = ch / 64;
+    const int n = blockIdx.x / chunks_c, c0 = (blockIdx.x % chunks_c) * 64;
+    const _Float16* src = static_cast<const _Float16*>(src_rows[n]) + (int64_t)c0 * hw;
+    const int vec_per_plane = hw / 8;
+    for (int e = threadIdx.x; e < 64 * vec_per_plane; e += 256) {
+        const int c = e / vec_per_plane, v = e % vec_per_plane;
+        *reinterpret_cast<v4u*>(planes + c * stride + v * 8) =
+            *reinterpret_cast<const v4u*>(src + (int64_t)c * hw + v * 8);
+    }
+    __syncthreads();
+    _Float16* out = dst + ((int64_t)n * hp * wp) * ch + c0;
+    for (int e = threadIdx.x; e < hw * 8; e += 256) {
+        const int pix = e >> 3, cg = e & 7;  // 8 channels per lane
+        const int y = pix / w, x = pix % w;
+        v8h v;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = planes[(cg * 8 + i) * stride + pix];
+        *reinterpret_cast<v8h*>(out + ((int64_t)(y + ph) * wp + (x + pw)) * ch + cg * 8) = v;
+    }
+}
+
+// F[k][c][r][s] -> Fp[k][(r,s,c)]
+__global__ __launch_bounds__(256) void filter_to_rsc_kernel(const void* const* f_rows, int c, int rs,
+                                                            int k, _Float16* fp)
+{
+    const int64_t total = (int64_t)k * c * rs;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        const int kk = (int)(e / (c * rs)), rem = (int)(e % (c * rs));
+        const int q = rem / c, cc = rem % c;  // destination order (rs, c)
+        fp[e] = static_cast<const _Float16*>(f_rows[kk])[cc * rs + q];
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// forward
+// ------------------------------------------------------------------------------------------
+struct FastConv {
+    ConvGeom g;
+    int hp, wp;
+    const void* const* y_rows;  // forward: output rows (images)
+    const void* const* f_rows;  // weight gradient: output rows (filters)
+    const _Float16* xp;
+    const _Float16* fp;
+    const _Float16* yt;
+    float* ws;
+    int split, ktiles_per_split;
+};
+
+// byte offset of pixel m = (n, oh, ow) in Xp (tap (0,0), channel 0)
+__device__ __forceinline__ uint32_t pixel_offset(const FastConv& p, int m)
+{
+    const int sp_out = p.g.oh * p.g.ow;
+    const int n = m / sp_out, sp = m % sp_out, oy = sp / p.g.ow, ox = sp % p.g.ow;
+    return (uint32_t)((((int64_t)n * p.hp + oy) * p.wp + ox) * p.g.c * 2);
+}
+
+template <int BM, int BN> struct FwdWalk {
+    using TA = OperandTile<BM, true>;
+    using TB = OperandTile<BN, true>;
+    const char *abase, *bbase, *xp;
+    uint32_t aoff[TA::kInstr], boff[TB::kInstr];
+    int c, wp, s_taps, cchunks, r, s, cc;
+
+    __device__ __forceinline__ FwdWalk(const FastConv& p, int m0, int n0, int wave, int lane)
+    {
+        xp = reinterpret_cast<const char*>(p.xp);
+        c = p.g.c; wp = p.wp; s_taps = p.g.s; cchunks = p.g.c / 64;
+        r = s = cc = 0;
+        abase = xp;
+        bbase = reinterpret_cast<const char*>(p.fp);
+#pragma unroll
+        for (int q = 0; q < TA::kInstr; ++q) {
+            int row, chunk;
+            TA::lane_slot(q, wave, lane, row, chunk);
+            aoff[q] = pixel_offset(p, m0 + row) + chunk * 16;
+        }
+        TB::offsets((int64_t)p.g.c * p.g.r * p.g.s, n0, wave, lane, boff);
+    }
+    __device__ __forceinline__ void advance()
+    {
+        bbase += BK * 2;
+        if (++cc == cchunks) {
+            cc = 0;
+            if (++s == s_taps) {
+                s = 0;
+                ++r;
+            }
+        }
+        abase = xp + ((int64_t)(r * wp + s) * c + cc * 64) * 2;
+    }
+};
+
+// workgroup w of n: XCD w % 8 gets a contiguous run of the logical order
+__device__ __forceinline__ int xcd_logical(int w, int n)
+{
+    const int base = n / 8, rem = n % 8, x = w % 8, j = w / 8;
+    if (n < 16) return w;
+    return x * base + min(x, rem) + j;
+}
+
+template <int BM, int BN, class TC>
+__global__ __launch_bounds__(NT) void conv_fwd_f16_kernel(FastConv p, float alpha, float beta)
+{
+    using TS = TileShape<BM, BN>;
+    constexpr int WM = TS::WM, WN = TS::WN, MT = TS::MT, NTL = TS::NTL;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const int tiles_n = p.g.k / BN;
+    const int idx = xcd_logical(blockIdx.x, gridDim.x);
+    const int m0 = (idx / tiles_n) * BM, n0 = (idx % tiles_n) * BN;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1, h = lane >> 5, l32 = lane & 31;
+
+    v16f acc[MT][NTL];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NTL; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    FwdWalk<BM, BN> walk(p, m0, n0, wave, lane);
+    const int n_ktiles = p.g.r * p.g.s * (p.g.c / 64);
+    run<BM, BN, 3, true, true>(walk, n_ktiles, smem, acc);
+
+    // epilogue: four consecutive registers are four consecutive pixels of one output plane
+    const int sp_out = p.g.oh * p.g.ow;
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const int m = m0 + wm * WM + i * 32 + 8 * q4 + 4 * h;
+            const int n_img = m / sp_out, sp = m % sp_out;
+            TC* yrow = static_cast<TC*>(const_cast<void*>(p.y_rows[n_img]));
+#pragma unroll
+            for (int j = 0; j < NTL; ++j) {
+                const int ko = n0 + wn * WN + j * 32 + l32;
+                TC* dst = yrow + (int64_t)ko * sp_out + sp;
+                typedef TC out4 __attribute__((ext_vector_type(4)));
+                out4 o;
+                if (beta != 0.f) o = *reinterpret_cast<out4*>(dst);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float v = alpha * acc[i][j][q4 * 4 + e];
+                    if (beta != 0.f) v += beta * (float)o[e];
+                    o[e] = to_out<TC>(v);
+                }
+                *reinterpret_cast<out4*>(dst) = o;
+            }
+        }
+}
+
+// ------------------------------------------------------------------------------------------
+// weight gradient
+// ------------------------------------------------------------------------------------------
+template <int BM, int BN> struct WgradWalk {
+    using TA = OperandTile<BM, false>;
+    using TB = OperandTile<BN, false>;
+    const char *abase, *bbase;
+    uint32_t aoff[TA::kInstr], boff[TB::kInstr];
+    // pixel (n, oy, ox) fetched by this lane for each B segment, and the geometry to step it
+    int pn[TB::kInstr], py[TB::kInstr], px[TB::kInstr], chunk16[TB::kInstr];
+    int oh, ow, hp, wp, c, d_oy, d_ox;
+    int64_t astep;
+
+    __device__ __forceinline__ WgradWalk(const FastConv& p, int k0_pixels, int n0_cols, int wave, int lane)
+    {
+        oh = p.g.oh; ow = p.g.ow; hp = p.hp; wp = p.wp; c = p.g.c;
+        d_oy = BK / ow; d_ox = BK % ow;
+        // A' = Yt[m][k]: dense, m/n (= k_out) unit-stride, all of k_out in the tile
+        TA::offsets(p.g.k, 0, wave, lane, aoff);
+        astep = TA::step(p.g.k);
+        abase = reinterpret_cast<const char*>(p.yt) + (int64_t)k0_pixels * p.g.k * 2;
+        // B' columns n0 .. n0+BN of (r, s, c): one tap, BN consecutive channels
+        const int tap = n0_cols / c, c0 = n0_cols % c, r = tap / p.g.s, s = tap % p.g.s;
+        bbase = reinterpret_cast<const char*>(p.xp) + ((int64_t)(r * wp + s) * c + c0) * 2;
+        const int sp_out = oh * ow;
+#pragma unroll
+        for (int q = 0; q < TB::kInstr; ++q) {
+            int row, chunk;
+            TB::lane_slot(q, wave, lane, row, chunk);
+            const int m = k0_pixels + row;
+            pn[q] = m / sp_out;
+            const int sp = m % sp_out;
+            py[q] = sp / ow;
+            px[q] = sp % ow;
+            chunk16[q] = chunk * 16;
+        }
+        set_boff();
+    }
+    __device__ __forceinline__ void set_boff()
+    {
+#pragma unroll
+        for (int q = 0; q < TB::kInstr; ++q)
+            boff[q] = (uint32_t)((((int64_t)pn[q] * hp + py[q]) * wp + px[q]) * c * 2) + chunk16[q];
+    }
+    __device__ __forceinline__ void advance()
+    {
+        abase += astep;
+#pragma unroll
+        for (int q = 0; q < TB::kInstr; ++q) {  // pixel index += 64
+            px[q] += d_ox;
+            py[q] += d_oy;
+            if (px[q] >= ow) { px[q] -= ow; ++py[q]; }
+            if (py[q] >= oh) { py[q] -= oh; ++pn[q]; }
+            if (py[q] >= oh) { py[q] -= oh; ++pn[q]; }
+        }
+        set_boff();
+    }
+};
+
+template <int BM, int BN>
+__global__ __launch_bounds__(NT) void conv_wgrad_f16_kernel(FastConv p)
+{
+    using TS = TileShape<BM, BN>;
+    constexpr int WM = TS::WM, WN = TS::WN, MT = TS::MT, NTL = TS::NTL;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const int ncols = p.g.c * p.g.r * p.g.s, tiles_n = ncols / BN;
+    const int idx = xcd_logical(blockIdx.x, gridDim.x);
+    const int split = idx / tiles_n, n0 = (idx % tiles_n) * BN;  // split-major: same pixels, same XCD
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31;
+
+    v16f acc[MT][NTL];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NTL; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    WgradWalk<BM, BN> walk(p, split * p.ktiles_per_split * BK, n0, wave, lane);
+    run<BM, BN, 3, false, false>(walk, p.ktiles_per_split, smem, acc);
+
+    float* ws = p.ws + (int64_t)split * p.g.k * ncols;
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NTL; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = wm * WM + i * 32 + acc32_row(lane, r);
+                const int col = n0 + wn * WN + j * 32 + l32;
+                ws[(int64_t)row * ncols + col] = acc[i][j][r];
+            }
+}
+
+// dF[k][c][r][s] <- alpha * sum over splits (ascending) + beta * dF; the partials are [k][(r,s,c)].
+template <class TC>
+__global__ __launch_bounds__(256) void conv_wgrad_reduce_kernel(FastConv p, float alpha, float beta)
+{
+    const int rs = p.g.r * p.g.s, c = p.g.c, ncols = rs * c;
+    const int64_t total = (int64_t)p.g.k * ncols;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        float sum = 0.f;
+        for (int s = 0; s < p.split; ++s) sum += p.ws[(int64_t)s * total + e];
+        const int kk = (int)(e / ncols), col = (int)(e % ncols), q = col / c, cc = col % c;
+        TC* dst = static_cast<TC*>(const_cast<void*>(p.f_rows[kk])) + cc * rs + q;
+        float v = alpha * sum;
+        if (beta != 0.f) v += beta * (float)*dst;
+        *dst = to_out<TC>(v);
+    }
+}
+
+template <class K> hipError_t set_lds(K kern, int bytes)
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+}  // namespace
+
+// Geometry the specialised kernels accept (everything else runs on the generic kernels).
+bool conv_f16_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype)
+{
+    if (in_dtype != DMATH_F16 || g.stride_h != 1 || g.stride_w != 1) return false;
+    const int64_t sp_out = (int64_t)g.oh * g.ow, m = (int64_t)g.n * sp_out;
+    if (g.c % 64 || (g.h * g.w) % 8 || (int64_t)64 * (g.h * g.w + 8) * 2 > 150 * 1024) return false;
+    if (sp_out < 64) return false;
+    if (mode == CONV_FWD) return g.k % 128 == 0 && m % 256 == 0 && sp_out % 4 == 0;
+    if (mode == CONV_BWD_FILTER)
+        return g.k == 256 && g.c % 128 == 0 && m % 64 == 0 && g.k % 64 == 0 && sp_out % 8 == 0 &&
+               (int64_t)64 * (sp_out + 8) * 2 <= 150 * 1024;
+    return false;
+}
+
+// Split count for the weight gradient: enough workgroups to fill the chip, dividing the k-tiles.
+int conv_f16_wgrad_split(const ConvGeom& g)
+{
+    const int64_t ktiles = (int64_t)g.n * g.oh * g.ow / 64;
+    const int64_t tiles = (int64_t)g.c * g.r * g.s / 128;
+    int best = 1;
+    for (int s = 1; s <= 64; ++s)
+        if (ktiles % s == 0 && tiles * s <= 256 && ktiles / s >= 8) best = s;
+    return best;
+}
+
+hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double beta, hipStream_t st)
+{
+    const ConvTables& t = plan.t;
+    const ConvGeom& g = t.g;
+    FastConv p{};
+    p.g = g;
+    p.hp = g.h + 2 * g.pad_h;
+    p.wp = g.w + 2 * g.pad_w;
+    p.y_rows = t.y_rows;
+    p.f_rows = t.f_rows;
+    p.xp = static_cast<const _Float16*>(plan.xp);
+    p.fp = static_cast<const _Float16*>(plan.fp);
+    p.yt = static_cast<const _Float16*>(plan.yt);
+    p.ws = static_cast<float*>(t.workspace);
+    p.split = t.split_k;
+    if (!plan.xp || (mode == CONV_FWD && !plan.fp) || (mode == CONV_BWD_FILTER && (!plan.yt || !p.ws)))
+        return hipErrorInvalidValue;  // the plan was not made for this path
+
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = set_lds(to_channels_last_kernel, 150 * 1024);
+        if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 128, float>, 3 * 384 * 128);
+        if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 128, _Float16>, 3 * 384 * 128);
+        if (e == hipSuccess) e = set_lds(conv_wgrad_f16_kernel<256, 128>, 3 * 384 * 128);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    // activations -> zero-bordered channels-last copy (borders were zeroed when the plan was made)
+    {
+        const int lds = 64 * (g.h * g.w + 8) * 2;
+        to_channels_last_kernel<<<g.n * (g.c / 64), 256, lds, st>>>(t.x_rows, g.c, g.h, g.w, g.pad_h, g.pad_w,
+                                                                     p.hp, p.wp, static_cast<_Float16*>(plan.xp));
+    }
+    if (mode == CONV_FWD) {
+        filter_to_rsc_kernel<<<512, 256, 0, st>>>(t.f_rows, g.c, g.r * g.s, g.k, static_cast<_Float16*>(plan.fp));
+        const int tiles = (int)((int64_t)g.n * g.oh * g.ow / 256) * (g.k / 128);
+        if (plan.out_dtype == DMATH_F16)
+            conv_fwd_f16_kernel<256, 128, _Float16><<<tiles, NT, 3 * 384 * 128, st>>>(p, (float)alpha, (float)beta);
+        else
+            conv_fwd_f16_kernel<256, 128, float><<<tiles, NT, 3 * 384 * 128, st>>>(p, (float)alpha, (float)beta);
+        return hipGetLastError();
+    }
+    // weight gradient: dY -> channels-last [m][k], split GEMM, fixed-order reduction
+    {
+        const int lds = 64 * (g.oh * g.ow + 8) * 2;
+        to_channels_last_kernel<<<g.n * (g.k / 64), 256, lds, st>>>(t.y_rows, g.k, g.oh, g.ow, 0, 0, g.oh, g.ow,
+                                                                     static_cast<_Float16*>(plan.yt));
+    }
+    p.ktiles_per_split = (int)((int64_t)g.n * g.oh * g.ow / 64 / t.split_k);
+    const int tiles = (g.c * g.r * g.s / 128) * t.split_k;
+    conv_wgrad_f16_kernel<256, 128><<<tiles, NT, 3 * 384 * 128, st>>>(p);
+    if (plan.out_dtype == DMATH_F16)
+        conv_wgrad_reduce_kernel<_Float16><<<1024, 256, 0, st>>>(p, (float)alpha, (float)beta);
+    else
+        conv_wgrad_reduce_kernel<float><<<1024, 256, 0, st>>>(p, (float)alpha, (float)beta);
+    return hipGetLastError();
+}
+
+}  // namespace dm

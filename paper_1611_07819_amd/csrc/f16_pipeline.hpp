@@ -1,0 +1,264 @@
+// The fp16-input / fp32-accumulate MFMA pipeline shared by the GEMM and the implicit-GEMM
+// convolution kernels (v_mfma_f32_32x32x16_f16, gfx950).
+//
+// A workgroup of 4 wavefronts (2 x 2) multiplies a BM x BN tile; k is walked 64 at a time
+// through a ring of STAGES LDS stages.
+//
+// Global -> LDS without registers: every wavefront issues global_load_lds_dwordx4, which
+// writes the 16 bytes fetched by lane p to (LDS base in M0) + 16*p.  A 1 KiB LDS segment is
+// filled per instruction; the swizzles below are applied by choosing WHICH global chunk each
+// lane fetches.  The loads are inline assembly with explicit s_waitcnt vmcnt(), so that the
+// compiler neither sees nor serialises them; STAGES-1 tiles are in flight while one is
+// multiplied.
+//
+// LDS layouts, both as the operand lies in memory:
+//   k unit-stride operand  : [mn][64 k], 128-byte rows, 16-byte chunk index XOR ((mn^(mn>>3))&7);
+//                            the MFMA fragment of a lane (8 consecutive k of one row) is one
+//                            ds_read_b128, conflict-free
+//   m/n unit-stride operand: [k][mn], 16-byte chunk index XOR ((k&3)<<1); fragments come from
+//                            two ds_read_b64_tr_b16 (the gfx950 transposing LDS read: inside a
+//                            16-lane group, lane i receives element i%4 of the 8 bytes fetched
+//                            by lanes i/4, i/4+4, i/4+8, i/4+12), so a group fetches a 4(k) x
+//                            16(mn) patch and every lane ends up with 4 consecutive k of its
+//                            own column; the XOR spreads the four k rows over the banks
+//
+// What a kernel supplies is a "walk": for the k-tile about to be fetched, a wavefront-uniform
+// base pointer and one 32-bit byte offset per lane and 1 KiB segment for each operand, plus
+// advance() to move to the next k-tile.  Operand rows need not be equidistant (the convolution
+// gathers them), only 16-byte aligned and 128 bytes long per k-tile.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "mfma.hpp"
+
+namespace dm {
+namespace f16p {
+
+constexpr int BK = 64;
+constexpr int NT = 256;
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) char lds_char;
+
+__device__ __forceinline__ int swz(int mn) { return (mn ^ (mn >> 3)) & 7; }
+
+// Forces a wavefront-uniform pointer into scalar registers.
+__device__ __forceinline__ const char* uniform_ptr(const char* p)
+{
+    uint64_t v = reinterpret_cast<uint64_t>(p);
+    uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const char*>(((uint64_t)hi << 32) | lo);
+}
+
+// One direct global->LDS load: lane fetches 16 bytes at (sbase + voff), lands at m0 + 16*lane.
+__device__ __forceinline__ void dma16(uint32_t lds_addr, const void* sbase, uint32_t voff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(sbase)
+                 : "memory");
+}
+
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int BMN, bool KC> struct OperandTile {
+    static constexpr int kInstr = BMN / 32;      // 1 KiB segments per wavefront and k-tile
+    static constexpr int kBytes = BMN * BK * 2;  // one stage of this operand
+    static constexpr int kChunksPerRow = KC ? 8 : BMN / 8;
+    static constexpr int kRowsPerSeg = 64 / kChunksPerRow;
+
+    // Row (k unit-stride: m/n index; otherwise: k index) inside the tile, and 16-byte chunk of
+    // that row in memory, which this lane fetches with segment q.
+    __device__ __forceinline__ static void lane_slot(int q, int wave, int lane, int& row, int& chunk)
+    {
+        const int seg = q * 4 + wave;
+        row = seg * kRowsPerSeg + lane / kChunksPerRow;
+        const int cpos = lane % kChunksPerRow;
+        chunk = KC ? (cpos ^ swz(row)) : (cpos ^ ((row & 3) << 1));
+    }
+
+    // byte offsets (relative to the panel origin) for a dense panel with leading dimension ld
+    __device__ __forceinline__ static void offsets(int64_t ld, int mn0, int wave, int lane,
+                                                   uint32_t (&off)[kInstr])
+    {
+#pragma unroll
+        for (int q = 0; q < kInstr; ++q) {
+            int row, chunk;
+            lane_slot(q, wave, lane, row, chunk);
+            if (KC)
+                off[q] = (uint32_t)((((int64_t)(mn0 + row)) * ld + chunk * 8) * 2);
+            else
+                off[q] = (uint32_t)(((int64_t)row * ld + mn0 + chunk * 8) * 2);
+        }
+    }
+    // bytes a dense panel pointer advances per k-tile
+    __device__ __forceinline__ static int64_t step(int64_t ld) { return KC ? BK * 2 : BK * 2 * ld; }
+
+    // Per-lane LDS byte offset (inside the operand's stage) of the fragment for k-step 0 of the
+    // 32-row tile starting at mn_base.
+    __device__ __forceinline__ static uint32_t frag_base(int mn_base, int lane)
+    {
+        if (KC) return (uint32_t)((mn_base + (lane & 31)) * 128);
+        const int g = lane >> 4, i = lane & 15;
+        const int row = 8 * (g >> 1) + (i >> 2);
+        const int col = mn_base + 16 * (g & 1) + 4 * (i & 3);
+        return (uint32_t)(row * (BMN * 2) + (((col >> 3) ^ ((row & 3) << 1)) << 4) + (col & 7) * 2);
+    }
+
+    __device__ __forceinline__ static v8h fragment(const lds_char* tile, uint32_t fb, int mn_row,
+                                                   int h, int s)
+    {
+        if (KC) {
+            const int chunk = ((s << 1) + h) ^ swz(mn_row);
+            return *reinterpret_cast<const __attribute__((address_space(3))) v8h*>(tile + fb + (chunk << 4));
+        }
+        const lds_char* p = tile + fb + s * (16 * BMN * 2);
+        v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4s __attribute__((address_space(3)))*)p);
+        v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4s __attribute__((address_space(3)))*)(p + 4 * BMN * 2));
+        typedef short v8s __attribute__((ext_vector_type(8)));
+        v8s both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(v8h, both);
+    }
+};
+
+template <class TC> __device__ __forceinline__ TC to_out(float v);
+template <> __device__ __forceinline__ float to_out<float>(float v) { return v; }
+template <> __device__ __forceinline__ _Float16 to_out<_Float16>(float v) { return (_Float16)v; }
+
+template <int BM, int BN> struct TileShape {
+    static constexpr int WM = BM / 2, WN = BN / 2;  // wavefront tile
+    static constexpr int MT = WM / 32, NTL = WN / 32;
+};
+
+// Runs the whole k-loop of one workgroup tile.  `walk` must provide
+//   const char *abase, *bbase;  uint32_t aoff[BM/32], boff[BN/32];  void advance();
+// describing the k-tile that is fetched next.  acc must be zeroed by the caller.
+template <int BM, int BN, int STAGES, bool AKC, bool BKC, class Walk>
+__device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
+                                    v16f (&acc)[TileShape<BM, BN>::MT][TileShape<BM, BN>::NTL])
+{
+    using TA = OperandTile<BM, AKC>;
+    using TB = OperandTile<BN, BKC>;
+    using TS = TileShape<BM, BN>;
+    constexpr int WM = TS::WM, WN = TS::WN, MT = TS::MT, NTL = TS::NTL;
+    constexpr int kStage = TA::kBytes + TB::kBytes;
+    constexpr int kPerTile = TA::kInstr + TB::kInstr;  // loads per wavefront and k-tile
+    static_assert(STAGES == 2 || STAGES == 3, "ring of two or three stages");
+    const lds_char* lds = (const lds_char*)smem;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1, h = lane >> 5, l32 = lane & 31;
+
+    uint32_t fa_base[MT], fb_base[NTL];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) fa_base[i] = TA::frag_base(wm * WM + i * 32, lane);
+#pragma unroll
+    for (int j = 0; j < NTL; ++j) fb_base[j] = TB::frag_base(wn * WN + j * 32, lane);
+
+    // The loads of one k-tile are numbered 0 .. kPerTile-1 (A segments first).
+    auto issue_one = [&](uint32_t sbase, const char* ab, const char* bb, int idx) {
+        if (idx < TA::kInstr)
+            dma16(sbase + (idx * 4 + wave) * 1024, ab, walk.aoff[idx]);
+        else
+            dma16(sbase + TA::kBytes + ((idx - TA::kInstr) * 4 + wave) * 1024, bb, walk.boff[idx - TA::kInstr]);
+    };
+    auto issue_all = [&](int stage) {
+        const uint32_t sbase = lds0 + stage * kStage;
+        const char* ab = uniform_ptr(walk.abase);
+        const char* bb = uniform_ptr(walk.bbase);
+#pragma unroll
+        for (int idx = 0; idx < kPerTile; ++idx) issue_one(sbase, ab, bb, idx);
+        walk.advance();
+    };
+
+    // Multiplies the tile in `stage`.  The instruction order is pinned: after every MFMA comes
+    // one fragment read for the NEXT k-step (register double buffer) and, when PREFETCH, every
+    // few MFMAs one load of the tile STAGES-1 ahead into `next_stage` -- so neither the LDS nor
+    // the memory pipeline ever holds up the matrix instructions queued behind it.
+    auto multiply = [&](int stage, int next_stage, auto prefetch) {
+        constexpr bool PREFETCH = decltype(prefetch)::value;
+        constexpr int kSteps = BK / 16, kMfma = MT * NTL, kReads = MT + NTL;
+        static_assert(kReads <= kMfma, "one fragment read per MFMA slot");
+        static_assert(kSteps * kMfma >= kPerTile, "not enough slots to spread the loads");
+        const lds_char* sa = lds + stage * kStage;
+        const lds_char* sb = sa + TA::kBytes;
+        const uint32_t nbase = lds0 + next_stage * kStage;
+        const char* ab = uniform_ptr(walk.abase);
+        const char* bb = uniform_ptr(walk.bbase);
+        v8h fa[2][MT], fb[2][NTL];
+        // read order: what the first MFMAs need comes first (A0, all B, then the other A)
+        auto read_frag = [&](int buf, int r, int s) {
+            if (r == 0)
+                fa[buf][0] = TA::fragment(sa, fa_base[0], wm * WM + l32, h, s);
+            else if (r <= NTL)
+                fb[buf][r - 1] = TB::fragment(sb, fb_base[r - 1], wn * WN + (r - 1) * 32 + l32, h, s);
+            else
+                fa[buf][r - NTL] = TA::fragment(sa, fa_base[r - NTL], wm * WM + (r - NTL) * 32 + l32, h, s);
+        };
+#pragma unroll
+        for (int r = 0; r < kReads; ++r) read_frag(0, r, 0);
+        int issued = 0;
+#pragma unroll
+        for (int s = 0; s < kSteps; ++s) {
+            const int cur = s & 1;
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NTL; ++j) {
+                    const int m = i * NTL + j;
+                    acc[i][j] = mfma_f16_32x32x16(fa[cur][i], fb[cur][j], acc[i][j]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (s + 1 < kSteps && m < kReads) read_frag(cur ^ 1, m, s + 1);
+                    // spread kPerTile loads evenly over the kSteps * kMfma slots
+                    const int slot = s * kMfma + m;
+                    if (PREFETCH && issued < kPerTile && slot * kPerTile >= issued * (kSteps * kMfma)) {
+                        issue_one(nbase, ab, bb, issued);
+                        ++issued;
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+        }
+        if (PREFETCH) walk.advance();
+    };
+
+    // Prologue: STAGES-1 tiles in flight.
+#pragma unroll
+    for (int p = 0; p < STAGES - 1; ++p)
+        if (p < n_ktiles) issue_all(p);
+
+    // k-tile kt is multiplied from stage kt % STAGES.  Before that, its loads must have landed
+    // (only the loads of the STAGES-2 younger tiles may still be outstanding) and every
+    // wavefront must be past tile kt-1, whose stage then receives tile kt+STAGES-1.
+    int stage = 0;
+    int kt = 0;
+    for (; kt + STAGES - 1 < n_ktiles; ++kt) {
+        wait_vmcnt<kPerTile*(STAGES - 2)>();
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        multiply(stage, stage == 0 ? STAGES - 1 : stage - 1, std::true_type{});
+        asm volatile("" ::: "memory");
+        stage = stage == STAGES - 1 ? 0 : stage + 1;
+    }
+    // drain: no more loads to issue; the number of younger tiles in flight shrinks to zero
+    if (STAGES == 3 && kt + 1 < n_ktiles) {
+        wait_vmcnt<kPerTile>();
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        multiply(stage, 0, std::false_type{});
+        asm volatile("" ::: "memory");
+        stage = stage == STAGES - 1 ? 0 : stage + 1;
+    }
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    multiply(stage, 0, std::false_type{});
+}
+
+}  // namespace f16p
+}  // namespace dm

@@ -78,6 +78,15 @@ std::vector<Tile> xcd_interleave(const std::vector<Tile>& logical)
 
 }  // namespace
 
+static void free_conv_plan(dmath_ctx_s* ctx, ConvPlan& p)
+{
+    for (void** q : {&p.dev_tables, &p.workspace, &p.xp, &p.fp, &p.yt})
+        if (*q) {
+            ctx->pool.free(*q);
+            *q = nullptr;
+        }
+}
+
 void drop_plans_using(dmath_ctx_s* ctx, uint64_t id)
 {
     for (auto it = ctx->gemm_plans.begin(); it != ctx->gemm_plans.end();) {
@@ -92,8 +101,7 @@ void drop_plans_using(dmath_ctx_s* ctx, uint64_t id)
     for (auto it = ctx->conv_plans.begin(); it != ctx->conv_plans.end();) {
         auto& u = it->second->uses;
         if (std::find(u.begin(), u.end(), id) != u.end()) {
-            if (it->second->dev_tables) ctx->pool.free(it->second->dev_tables);
-            if (it->second->workspace) ctx->pool.free(it->second->workspace);
+            free_conv_plan(ctx, *it->second);
             it = ctx->conv_plans.erase(it);
         } else
             ++it;
@@ -107,10 +115,7 @@ void drop_all_plans(dmath_ctx_s* ctx)
         if (kv.second->workspace) ctx->pool.free(kv.second->workspace);
     }
     ctx->gemm_plans.clear();
-    for (auto& kv : ctx->conv_plans) {
-        if (kv.second->dev_tables) ctx->pool.free(kv.second->dev_tables);
-        if (kv.second->workspace) ctx->pool.free(kv.second->workspace);
-    }
+    for (auto& kv : ctx->conv_plans) free_conv_plan(ctx, *kv.second);
     ctx->conv_plans.clear();
 }
 
@@ -353,13 +358,19 @@ dmath_status_t get_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t
     plan->in_dtype = (mode == CONV_FWD) ? X->dtype : Y->dtype;
     plan->out_dtype = result->dtype;
 
+    const bool fast = ctx->policy == 0 && mode != CONV_BWD_DATA && conv_f16_fast_ok(mode, g, plan->in_dtype);
+    plan->kernel = fast ? 1 : 0;
     // split-K for the weight gradient: few C tiles, very deep K
     t.split_k = 1;
     if (mode == CONV_BWD_FILTER) {
-        int64_t tiles = ((t.M + 63) / 64) * ((t.N + 63) / 64);
-        int64_t want = std::max<int64_t>(1, 1024 / std::max<int64_t>(1, tiles));
-        int64_t max_by_k = std::max<int64_t>(1, t.K / 512);
-        t.split_k = (int32_t)std::min<int64_t>({want, max_by_k, 64});
+        if (fast) {
+            t.split_k = conv_f16_wgrad_split(g);
+        } else {
+            int64_t tiles = ((t.M + 63) / 64) * ((t.N + 63) / 64);
+            int64_t want = std::max<int64_t>(1, 1024 / std::max<int64_t>(1, tiles));
+            int64_t max_by_k = std::max<int64_t>(1, t.K / 512);
+            t.split_k = (int32_t)std::min<int64_t>({want, max_by_k, 64});
+        }
     }
 
     auto row_ptrs = [](const dmath_matrix_s* m) {
@@ -376,7 +387,9 @@ dmath_status_t get_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t
     void* dev = ctx->pool.alloc(buf.size());
     if (!dev) return DMATH_ERR_OOM;
     void* ws = nullptr;
-    if (t.split_k > 1) {
+    // the specialised weight-gradient kernel always goes through the partial-sum workspace,
+    // also with a single split
+    if (t.split_k > 1 || (fast && mode == CONV_BWD_FILTER)) {
         size_t acc = plan->in_dtype == DMATH_F64 ? 8 : 4;
         ws = ctx->pool.alloc((size_t)t.split_k * t.M * t.N * acc);
         if (!ws) {
@@ -384,9 +397,28 @@ dmath_status_t get_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t
             return DMATH_ERR_OOM;
         }
     }
+    if (fast) {
+        const size_t xp_bytes = (size_t)g.n * (g.h + 2 * g.pad_h) * (g.w + 2 * g.pad_w) * g.c * 2;
+        plan->xp = ctx->pool.alloc(xp_bytes);
+        if (mode == CONV_FWD) plan->fp = ctx->pool.alloc((size_t)g.k * crs * 2);
+        if (mode == CONV_BWD_FILTER) plan->yt = ctx->pool.alloc((size_t)g.n * sp_out * g.k * 2);
+        plan->dev_tables = dev;
+        plan->workspace = ws;
+        bool ok = plan->xp && (mode != CONV_FWD || plan->fp) && (mode != CONV_BWD_FILTER || plan->yt);
+        // the zero border of the padded copy is written once; every call rewrites the interior
+        if (ok && hipMemsetAsync(plan->xp, 0, xp_bytes, ctx->stream) != hipSuccess) {
+            free_conv_plan(ctx, *plan);
+            return DMATH_ERR_DEVICE;
+        }
+        if (!ok) {
+            free_conv_plan(ctx, *plan);
+            return DMATH_ERR_OOM;
+        }
+    }
     if (upload(ctx, dev, buf) != hipSuccess) {
-        ctx->pool.free(dev);
-        if (ws) ctx->pool.free(ws);
+        plan->dev_tables = dev;
+        plan->workspace = ws;
+        free_conv_plan(ctx, *plan);
         return DMATH_ERR_DEVICE;
     }
     char* dp = static_cast<char*>(dev);

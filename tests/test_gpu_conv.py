@@ -132,3 +132,67 @@ def _config5(ctx, oracle, w, images, filters):
     assert rel_fro(got if filters is None else got[filters], ref) <= TOL[dm.F16]
     for m in dev.values():
         m.destroy()
+
+
+FAST_GEOMS = [
+    # geometries that satisfy the preconditions of the specialised fp16 kernels (stride 1,
+    # channels a multiple of 64/128, n*oh*ow a multiple of 256)
+    dict(n=4, c=128, h=16, w=16, k=256, r=3, s=3, pad_h=1, pad_w=1),
+    dict(n=8, c=128, h=16, w=8, k=256, r=1, s=1),
+    dict(n=2, c=256, h=16, w=16, k=256, r=5, s=3, pad_h=2, pad_w=1),
+    dict(n=16, c=128, h=12, w=12, k=256, r=3, s=3, pad_h=1, pad_w=1),
+]
+
+
+@pytest.mark.parametrize("g", FAST_GEOMS)
+@pytest.mark.parametrize("out", [dm.F32, dm.F16])
+def test_specialised_fp16_conv_whole_result(ctx, oracle, g, out):
+    """Forward and weight gradient on the specialised path against the oracle: within the fp16
+    bar on random data (alpha/beta exercised) and bit for bit on small-integer data with a
+    row-blocked layout of every tensor."""
+    grids = {"X": (1, 1), "F": (1, 1), "Y": (1, 1)}
+    res = three_modes(ctx, oracle, g, dm.F16, out, 1.5, -0.5, grids, policy=0)
+    for mode in ("fwd", "bwd_filter"):
+        got, ref = res[mode]
+        assert rel_fro(got, ref) <= TOL[dm.F16], mode
+    d, t = tensors(g, dm.F16, 300, ints=True)
+    t = {k: np.sign(v).astype(np.float16) if k != "F" else v for k, v in t.items()}   # keep sums small
+    od = oracle.ConvDesc(**g)
+    grids = {"X": (g["n"], 1), "F": (2, 1), "Y": (2, 1)}
+    ctx.set_kernel_policy(0)
+    for mode in ("fwd", "bwd_filter"):
+        out_name = "Y" if mode == "fwd" else "F"
+        host = {k: (v.astype(NP[out]) if k == out_name else v) for k, v in t.items()}
+        dev = {k: ctx.from_host(v, grids[k]) for k, v in host.items()}
+        if mode == "fwd":
+            dm.conv_fwd(ctx, d, 1.0, dev["X"], dev["F"], 1.0, dev["Y"])
+            ref = oracle.conv_fwd(od, 1.0, host["X"], host["F"], 1.0, host["Y"])
+        else:
+            dm.conv_bwd_filter(ctx, d, 1.0, dev["X"], dev["Y"], 1.0, dev["F"])
+            ref = oracle.conv_bwd_filter(od, 1.0, host["X"], host["Y"], 1.0, host["F"])
+        got = dev[out_name].get().astype(np.float64)
+        if out == dm.F16 and np.abs(ref).max() > 2048:
+            assert rel_fro(got, ref) <= TOL[dm.F16], mode
+        else:
+            assert np.array_equal(got, ref), mode
+        for m in dev.values():
+            m.destroy()
+
+
+def test_repeated_calls_rewrite_the_channels_last_copy(ctx, oracle):
+    # the specialised path keeps a channels-last copy of X in the pool; a second call with new
+    # contents of X must not see the old copy
+    g = FAST_GEOMS[0]
+    d, t = tensors(g, dm.F16, 301)
+    od = oracle.ConvDesc(**g)
+    dX, dF = ctx.from_host(t["X"]), ctx.from_host(t["F"])
+    dY = ctx.matrix(*t["Y"].shape, (1, 1), dm.F32)
+    dm.conv_fwd(ctx, d, 1.0, dX, dF, 0.0, dY)
+    first = dY.get()
+    x2 = (1 - t["X"].astype(np.float32)).astype(np.float16)
+    dX.set(x2)
+    dm.conv_fwd(ctx, d, 1.0, dX, dF, 0.0, dY)
+    assert rel_fro(dY.get(), oracle.conv_fwd(od, 1.0, x2, t["F"])) <= TOL[dm.F16]
+    assert rel_fro(first, oracle.conv_fwd(od, 1.0, t["X"], t["F"])) <= TOL[dm.F16]
+    for m in (dX, dF, dY):
+        m.destroy()
