@@ -17,6 +17,9 @@
 // the timed region.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+#include <cstring>
+
 #include "context.hpp"
 #include "f16_pipeline.hpp"
 
@@ -32,29 +35,37 @@ typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 // ------------------------------------------------------------------------------------------
 
 // src rows: image n -> [ch][hw] halfs (NCHW inside a row).  dst: [n][HP][WP][ch] with the image
-// placed at (ph, pw).  One workgroup moves 64 channels of one image through LDS: fully
-// coalesced 16-byte reads of the 64 planes, 128-byte writes per pixel.
-__global__ __launch_bounds__(256) void to_channels_last_kernel(const void* const* src_rows, int ch,
-                                                               int h, int w, int ph, int pw, int hp,
-                                                               int wp, _Float16* dst)
+// placed at (ph, pw).  One workgroup of 1024 threads moves 64 channels of one image through
+// LDS: fully coalesced 16-byte reads of the 64 planes, 128-byte writes per pixel.  The plane
+// stride (hw + pad, pad chosen so that the stride is 4 mod 16 halfs) keeps the transposed
+// 16-bit reads at two lanes per bank.
+constexpr int kTclThreads = 1024;
+__host__ __device__ inline int tcl_stride(int hw) { return hw + ((20 - hw % 16) % 16); }
+
+__global__ __launch_bounds__(kTclThreads) void to_channels_last_kernel(const void* const* src_rows, int ch,
+                                                                       int h, int w, int ph, int pw, int hp,
+                                                                       int wp, _Float16* dst)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    _Float16* planes = reinterpret_cast<_Float16*>(smem);  // [64][hw + 8]
-    const int hw = h * w, stride = hw + 8;                 // +8 halfs: planes start on different banks
+    _Float16* planes = reinterpret_cast<_Float16*>(smem);  // [64][stride]
+    typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+    const int hw = h * w, stride = tcl_stride(hw);
     const int chunks_c = ch / 64;
     const int n = blockIdx.x / chunks_c, c0 = (blockIdx.x % chunks_c) * 64;
     const _Float16* src = static_cast<const _Float16*>(src_rows[n]) + (int64_t)c0 * hw;
     const int vec_per_plane = hw / 8;
-    for (int e = threadIdx.x; e < 64 * vec_per_plane; e += 256) {
-        const int c = e / vec_per_plane, v = e % vec_per_plane;
-        *reinterpret_cast<v4u*>(planes + c * stride + v * 8) =
-            *reinterpret_cast<const v4u*>(src + (int64_t)c * hw + v * 8);
+    for (int e = threadIdx.x; e < 64 * vec_per_plane; e += kTclThreads) {
+        const int c = e / vec_per_plane, v = e - c * vec_per_plane;
+        const v4u d = *reinterpret_cast<const v4u*>(src + (int64_t)c * hw + v * 8);
+        v2u* q = reinterpret_cast<v2u*>(planes + c * stride + v * 8);  // rows are 8-byte aligned
+        q[0] = v2u{d[0], d[1]};
+        q[1] = v2u{d[2], d[3]};
     }
     __syncthreads();
     _Float16* out = dst + ((int64_t)n * hp * wp) * ch + c0;
-    for (int e = threadIdx.x; e < hw * 8; e += 256) {
+    for (int e = threadIdx.x; e < hw * 8; e += kTclThreads) {
         const int pix = e >> 3, cg = e & 7;  // 8 channels per lane
-        const int y = pix / w, x = pix % w;
+        const int y = pix / w, x = pix - y * w;
         v8h v;
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] = planes[(cg * 8 + i) * stride + pix];
@@ -141,7 +152,7 @@ __device__ __forceinline__ int xcd_logical(int w, int n)
     return x * base + min(x, rem) + j;
 }
 
-template <int BM, int BN, class TC>
+template <int BM, int BN, int STAGES, class TC>
 __global__ __launch_bounds__(NT) void conv_fwd_f16_kernel(FastConv p, float alpha, float beta)
 {
     using TS = TileShape<BM, BN>;
@@ -164,7 +175,7 @@ __global__ __launch_bounds__(NT) void conv_fwd_f16_kernel(FastConv p, float alph
 
     FwdWalk<BM, BN> walk(p, m0, n0, wave, lane);
     const int n_ktiles = p.g.r * p.g.s * (p.g.c / 64);
-    run<BM, BN, 3, true, true>(walk, n_ktiles, smem, acc);
+    run<BM, BN, STAGES, true, true>(walk, n_ktiles, smem, acc);
 
     // epilogue: four consecutive registers are four consecutive pixels of one output plane
     const int sp_out = p.g.oh * p.g.ow;
@@ -289,20 +300,25 @@ __global__ __launch_bounds__(NT) void conv_wgrad_f16_kernel(FastConv p)
             }
 }
 
-// dF[k][c][r][s] <- alpha * sum over splits (ascending) + beta * dF; the partials are [k][(r,s,c)].
+// dF[k][c][r][s] <- alpha * sum over splits (ascending) + beta * dF; the partials are
+// [k][(r,s,c)], read four channels at a time.
 template <class TC>
 __global__ __launch_bounds__(256) void conv_wgrad_reduce_kernel(FastConv p, float alpha, float beta)
 {
     const int rs = p.g.r * p.g.s, c = p.g.c, ncols = rs * c;
-    const int64_t total = (int64_t)p.g.k * ncols;
-    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-        float sum = 0.f;
-        for (int s = 0; s < p.split; ++s) sum += p.ws[(int64_t)s * total + e];
+    const int64_t total = (int64_t)p.g.k * ncols, quads = total / 4;
+    for (int64_t e4 = (int64_t)blockIdx.x * 256 + threadIdx.x; e4 < quads; e4 += (int64_t)gridDim.x * 256) {
+        const int64_t e = e4 * 4;
+        v4f sum = {0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < p.split; ++s) sum += *reinterpret_cast<const v4f*>(p.ws + (int64_t)s * total + e);
         const int kk = (int)(e / ncols), col = (int)(e % ncols), q = col / c, cc = col % c;
         TC* dst = static_cast<TC*>(const_cast<void*>(p.f_rows[kk])) + cc * rs + q;
-        float v = alpha * sum;
-        if (beta != 0.f) v += beta * (float)*dst;
-        *dst = to_out<TC>(v);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float v = alpha * sum[i];
+            if (beta != 0.f) v += beta * (float)dst[i * rs];
+            dst[i * rs] = to_out<TC>(v);
+        }
     }
 }
 
@@ -319,12 +335,12 @@ bool conv_f16_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype)
 {
     if (in_dtype != DMATH_F16 || g.stride_h != 1 || g.stride_w != 1) return false;
     const int64_t sp_out = (int64_t)g.oh * g.ow, m = (int64_t)g.n * sp_out;
-    if (g.c % 64 || (g.h * g.w) % 8 || (int64_t)64 * (g.h * g.w + 8) * 2 > 150 * 1024) return false;
+    if (g.c % 64 || (g.h * g.w) % 8 || (int64_t)64 * tcl_stride(g.h * g.w) * 2 > 150 * 1024) return false;
     if (sp_out < 64) return false;
     if (mode == CONV_FWD) return g.k % 128 == 0 && m % 256 == 0 && sp_out % 4 == 0;
     if (mode == CONV_BWD_FILTER)
         return g.k == 256 && g.c % 128 == 0 && m % 64 == 0 && g.k % 64 == 0 && sp_out % 8 == 0 &&
-               (int64_t)64 * (sp_out + 8) * 2 <= 150 * 1024;
+               (int64_t)64 * tcl_stride((int)sp_out) * 2 <= 150 * 1024;
     return false;
 }
 
@@ -360,31 +376,46 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
     static bool configured = false;
     if (!configured) {
         hipError_t e = set_lds(to_channels_last_kernel, 150 * 1024);
-        if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 128, float>, 3 * 384 * 128);
-        if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 128, _Float16>, 3 * 384 * 128);
+        if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 128, 3, float>, 3 * 384 * 128);
+        if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 128, 3, _Float16>, 3 * 384 * 128);
+        if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 256, 2, float>, 2 * 512 * 128);
+        if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 256, 2, _Float16>, 2 * 512 * 128);
         if (e == hipSuccess) e = set_lds(conv_wgrad_f16_kernel<256, 128>, 3 * 384 * 128);
         if (e != hipSuccess) return e;
         configured = true;
     }
     // activations -> zero-bordered channels-last copy (borders were zeroed when the plan was made)
     {
-        const int lds = 64 * (g.h * g.w + 8) * 2;
-        to_channels_last_kernel<<<g.n * (g.c / 64), 256, lds, st>>>(t.x_rows, g.c, g.h, g.w, g.pad_h, g.pad_w,
+        const int lds = 64 * tcl_stride(g.h * g.w) * 2;
+        to_channels_last_kernel<<<g.n * (g.c / 64), kTclThreads, lds, st>>>(t.x_rows, g.c, g.h, g.w, g.pad_h, g.pad_w,
                                                                      p.hp, p.wp, static_cast<_Float16*>(plan.xp));
     }
     if (mode == CONV_FWD) {
         filter_to_rsc_kernel<<<512, 256, 0, st>>>(t.f_rows, g.c, g.r * g.s, g.k, static_cast<_Float16*>(plan.fp));
-        const int tiles = (int)((int64_t)g.n * g.oh * g.ow / 256) * (g.k / 128);
-        if (plan.out_dtype == DMATH_F16)
-            conv_fwd_f16_kernel<256, 128, _Float16><<<tiles, NT, 3 * 384 * 128, st>>>(p, (float)alpha, (float)beta);
-        else
-            conv_fwd_f16_kernel<256, 128, float><<<tiles, NT, 3 * 384 * 128, st>>>(p, (float)alpha, (float)beta);
+        // 256x128 tiles unless they would need a second, mostly empty round of workgroups while
+        // 256x256 tiles fit in one
+        const int mt = (int)((int64_t)g.n * g.oh * g.ow / 256);
+        const int t128 = mt * (g.k / 128), t256 = mt * (g.k / 256);
+        const char* force = std::getenv("DMATH_CONV_TILE");
+        bool wide = g.k % 256 == 0 && t128 > 256 && t256 <= 256;
+        if (force) wide = g.k % 256 == 0 && std::strcmp(force, "256x256") == 0;
+        if (wide) {
+            if (plan.out_dtype == DMATH_F16)
+                conv_fwd_f16_kernel<256, 256, 2, _Float16><<<t256, NT, 2 * 512 * 128, st>>>(p, (float)alpha, (float)beta);
+            else
+                conv_fwd_f16_kernel<256, 256, 2, float><<<t256, NT, 2 * 512 * 128, st>>>(p, (float)alpha, (float)beta);
+        } else {
+            if (plan.out_dtype == DMATH_F16)
+                conv_fwd_f16_kernel<256, 128, 3, _Float16><<<t128, NT, 3 * 384 * 128, st>>>(p, (float)alpha, (float)beta);
+            else
+                conv_fwd_f16_kernel<256, 128, 3, float><<<t128, NT, 3 * 384 * 128, st>>>(p, (float)alpha, (float)beta);
+        }
         return hipGetLastError();
     }
     // weight gradient: dY -> channels-last [m][k], split GEMM, fixed-order reduction
     {
-        const int lds = 64 * (g.oh * g.ow + 8) * 2;
-        to_channels_last_kernel<<<g.n * (g.k / 64), 256, lds, st>>>(t.y_rows, g.k, g.oh, g.ow, 0, 0, g.oh, g.ow,
+        const int lds = 64 * tcl_stride(g.oh * g.ow) * 2;
+        to_channels_last_kernel<<<g.n * (g.k / 64), kTclThreads, lds, st>>>(t.y_rows, g.k, g.oh, g.ow, 0, 0, g.oh, g.ow,
                                                                      static_cast<_Float16*>(plan.yt));
     }
     p.ktiles_per_split = (int)((int64_t)g.n * g.oh * g.ow / 64 / t.split_k);
