@@ -177,36 +177,63 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
         walk.advance();
     };
 
-    // Multiplies the tile in `stage`.  The instruction order is pinned: after every MFMA comes
-    // one fragment read for the NEXT k-step (register double buffer) and, when PREFETCH, every
-    // few MFMAs one load of the tile STAGES-1 ahead into `next_stage` -- so neither the LDS nor
-    // the memory pipeline ever holds up the matrix instructions queued behind it.
-    auto multiply = [&](int stage, int next_stage, auto prefetch) {
-        constexpr bool PREFETCH = decltype(prefetch)::value;
-        constexpr int kSteps = BK / 16, kMfma = MT * NTL, kReads = MT + NTL;
-        static_assert(kReads <= kMfma, "one fragment read per MFMA slot");
-        static_assert(kSteps * kMfma >= kPerTile, "not enough slots to spread the loads");
-        const lds_char* sa = lds + stage * kStage;
+    // Ring protocol.  k-tile kt lives in stage kt % STAGES and is multiplied in 4 k-steps; the
+    // fragments of step s+1 are read from LDS while step s is multiplied (register double
+    // buffer).  Before the LAST step of tile kt every wavefront
+    //   - waits until its own loads of tile kt+1 have landed (s_waitcnt vmcnt),
+    //   - waits for its last fragment reads of tile kt (s_waitcnt lgkmcnt(0)),
+    //   - meets the others at the workgroup barrier.
+    // After that barrier tile kt+1 is visible to everybody and nobody reads tile kt's stage
+    // any more.  So the last step of tile kt already prefetches the first fragments of tile
+    // kt+1 (no LDS latency is exposed at tile boundaries), and the stage of tile kt is free:
+    //   STAGES == 3: tile kt+2 is fetched during steps 0..2 of iteration kt into the stage of
+    //                tile kt-1 (freed by the barrier of iteration kt-1); at the barrier only
+    //                those loads may still be outstanding;
+    //   STAGES == 2: tile kt+2 is fetched during the last step of iteration kt into the stage
+    //                of tile kt itself; at the barrier nothing may be outstanding.
+    // The instruction order inside a step is pinned: after every MFMA one fragment read and at
+    // most one load, so neither LDS nor the memory pipeline holds up the matrix instructions.
+    constexpr int kSteps = BK / 16, kMfma = MT * NTL, kReads = MT + NTL;
+    static_assert(kReads <= kMfma, "one fragment read per MFMA slot");
+    constexpr int kDmaSlots = (STAGES == 3 ? (kSteps - 1) : 1) * kMfma;
+    constexpr int kDmaPerSlot = (kPerTile + kDmaSlots - 1) / kDmaSlots;
+
+    v8h fa[2][MT], fb[2][NTL];
+    // read order: what the first MFMAs need comes first (A0, all B, then the other A)
+    auto read_frag = [&](const lds_char* sa, int buf, int r, int s) {
         const lds_char* sb = sa + TA::kBytes;
-        const uint32_t nbase = lds0 + next_stage * kStage;
+        if (r == 0)
+            fa[buf][0] = TA::fragment(sa, fa_base[0], wm * WM + l32, h, s);
+        else if (r <= NTL)
+            fb[buf][r - 1] = TB::fragment(sb, fb_base[r - 1], wn * WN + (r - 1) * 32 + l32, h, s);
+        else
+            fa[buf][r - NTL] = TA::fragment(sa, fa_base[r - NTL], wm * WM + (r - NTL) * 32 + l32, h, s);
+    };
+
+    // One iteration.  HAS_NEXT: tile kt+1 exists; HAS_DMA: tile kt+2 exists and is fetched.
+    auto iteration = [&](int stage, auto has_next, auto has_dma) {
+        constexpr bool HAS_NEXT = decltype(has_next)::value, HAS_DMA = decltype(has_dma)::value;
+        const int stage1 = stage + 1 == STAGES ? 0 : stage + 1;               // tile kt+1
+        const int stage2 = STAGES == 3 ? (stage == 0 ? 2 : stage - 1) : stage;  // tile kt+2
+        const lds_char* sa = lds + stage * kStage;
+        const lds_char* sa1 = lds + stage1 * kStage;
+        const uint32_t dbase = lds0 + stage2 * kStage;
         const char* ab = uniform_ptr(walk.abase);
         const char* bb = uniform_ptr(walk.bbase);
-        v8h fa[2][MT], fb[2][NTL];
-        // read order: what the first MFMAs need comes first (A0, all B, then the other A)
-        auto read_frag = [&](int buf, int r, int s) {
-            if (r == 0)
-                fa[buf][0] = TA::fragment(sa, fa_base[0], wm * WM + l32, h, s);
-            else if (r <= NTL)
-                fb[buf][r - 1] = TB::fragment(sb, fb_base[r - 1], wn * WN + (r - 1) * 32 + l32, h, s);
-            else
-                fa[buf][r - NTL] = TA::fragment(sa, fa_base[r - NTL], wm * WM + (r - NTL) * 32 + l32, h, s);
-        };
-#pragma unroll
-        for (int r = 0; r < kReads; ++r) read_frag(0, r, 0);
         int issued = 0;
 #pragma unroll
         for (int s = 0; s < kSteps; ++s) {
             const int cur = s & 1;
+            if (s == kSteps - 1 && HAS_NEXT) {
+                if (HAS_DMA && STAGES == 3)
+                    wait_vmcnt<kPerTile>();
+                else
+                    wait_vmcnt<0>();
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
+            }
 #pragma unroll
             for (int i = 0; i < MT; ++i)
 #pragma unroll
@@ -214,50 +241,52 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
                     const int m = i * NTL + j;
                     acc[i][j] = mfma_f16_32x32x16(fa[cur][i], fb[cur][j], acc[i][j]);
                     __builtin_amdgcn_sched_barrier(0);
-                    if (s + 1 < kSteps && m < kReads) read_frag(cur ^ 1, m, s + 1);
-                    // spread kPerTile loads evenly over the kSteps * kMfma slots
-                    const int slot = s * kMfma + m;
-                    if (PREFETCH && issued < kPerTile && slot * kPerTile >= issued * (kSteps * kMfma)) {
-                        issue_one(nbase, ab, bb, issued);
-                        ++issued;
+                    if (m < kReads) {
+                        if (s + 1 < kSteps)
+                            read_frag(sa, cur ^ 1, m, s + 1);
+                        else if (HAS_NEXT)
+                            read_frag(sa1, cur ^ 1, m, 0);
+                    }
+                    if (HAS_DMA) {
+                        const bool window = STAGES == 3 ? (s < kSteps - 1) : (s == kSteps - 1);
+                        const int slot = (STAGES == 3 ? s : 0) * kMfma + m;
+#pragma unroll
+                        for (int q = 0; q < kDmaPerSlot; ++q)
+                            if (window && issued < kPerTile && (slot + 1) * kPerTile > issued * kDmaSlots) {
+                                issue_one(dbase, ab, bb, issued);
+                                ++issued;
+                            }
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
         }
-        if (PREFETCH) walk.advance();
+        if (HAS_DMA) walk.advance();
     };
 
-    // Prologue: STAGES-1 tiles in flight.
-#pragma unroll
-    for (int p = 0; p < STAGES - 1; ++p)
-        if (p < n_ktiles) issue_all(p);
-
-    // k-tile kt is multiplied from stage kt % STAGES.  Before that, its loads must have landed
-    // (only the loads of the STAGES-2 younger tiles may still be outstanding) and every
-    // wavefront must be past tile kt-1, whose stage then receives tile kt+STAGES-1.
-    int stage = 0;
-    int kt = 0;
-    for (; kt + STAGES - 1 < n_ktiles; ++kt) {
-        wait_vmcnt<kPerTile*(STAGES - 2)>();
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        multiply(stage, stage == 0 ? STAGES - 1 : stage - 1, std::true_type{});
-        asm volatile("" ::: "memory");
-        stage = stage == STAGES - 1 ? 0 : stage + 1;
-    }
-    // drain: no more loads to issue; the number of younger tiles in flight shrinks to zero
-    if (STAGES == 3 && kt + 1 < n_ktiles) {
+    // Prologue: tiles 0 and 1 in flight, tile 0 landed and visible, its first fragments read.
+    issue_all(0);
+    if (n_ktiles > 1) {
+        issue_all(1);
         wait_vmcnt<kPerTile>();
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        multiply(stage, 0, std::false_type{});
-        asm volatile("" ::: "memory");
-        stage = stage == STAGES - 1 ? 0 : stage + 1;
+    } else {
+        wait_vmcnt<0>();
     }
-    wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    multiply(stage, 0, std::false_type{});
+#pragma unroll
+    for (int r = 0; r < kReads; ++r) read_frag(lds, 0, r, 0);
+
+    int stage = 0;
+    int kt = 0;
+    for (; kt + 2 < n_ktiles; ++kt) {
+        iteration(stage, std::true_type{}, std::true_type{});
+        stage = stage + 1 == STAGES ? 0 : stage + 1;
+    }
+    if (kt + 1 < n_ktiles) {
+        iteration(stage, std::true_type{}, std::false_type{});
+        stage = stage + 1 == STAGES ? 0 : stage + 1;
+    }
+    iteration(stage, std::false_type{}, std::false_type{});
 }
 
 }  // namespace f16p
