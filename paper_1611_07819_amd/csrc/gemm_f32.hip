@@ -228,22 +228,10 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmTables t, float alpha,
         if (PREFETCH) advance();
     };
 
-#ifdef DM_DBG_TIMING
-    uint64_t dbg_t0 = __builtin_amdgcn_s_memtime(), dbg_r0 = __builtin_amdgcn_s_memrealtime();
-    uint64_t dbg_wait = 0, dbg_tw;
-#define DBG_W0 dbg_tw = __builtin_amdgcn_s_memtime();
-#define DBG_W1 dbg_wait += __builtin_amdgcn_s_memtime() - dbg_tw;
-#else
-#define DBG_W0
-#define DBG_W1
-#endif
     // Prologue: STAGES-1 tiles in flight.
 #pragma unroll
     for (int p = 0; p < STAGES - 1; ++p)
         if (p < n_ktiles) issue_all(p);
-#ifdef DM_DBG_TIMING
-    uint64_t dbg_t1 = __builtin_amdgcn_s_memtime();
-#endif
 
     // k-tile kt is multiplied from stage kt % STAGES.  Before that, its loads must have landed
     // (only the loads of the younger tile may still be outstanding) and every wavefront must be
@@ -251,11 +239,9 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmTables t, float alpha,
     int stage = 0;
     int kt = 0;
     for (; kt + STAGES - 1 < n_ktiles; ++kt) {
-        DBG_W0
         wait_vmcnt<kPerTile>();
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        DBG_W1
         multiply(stage, stage == 0 ? STAGES - 1 : stage - 1, std::true_type{});
         asm volatile("" ::: "memory");
         stage = stage == STAGES - 1 ? 0 : stage + 1;
@@ -272,9 +258,6 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmTables t, float alpha,
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     multiply(stage, 0, std::false_type{});
-#ifdef DM_DBG_TIMING
-    uint64_t dbg_t2 = __builtin_amdgcn_s_memtime();
-#endif
 
     // epilogue: register r of a 32x32 result tile holds row 8*(r/4) + 4*h + r%4, column l32
     const Panel pc = t.c[tile.mseg * t.n_nseg + tile.nseg];
@@ -292,18 +275,6 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmTables t, float alpha,
                 if (beta != 0.f) v += beta * *p;
                 *p = v;
             }
-#ifdef DM_DBG_TIMING
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    uint64_t dbg_t3 = __builtin_amdgcn_s_memtime(), dbg_r3 = __builtin_amdgcn_s_memrealtime();
-    if (tid == 0 && tile.m_off == 0 && tile.n_off == 0 && tile.mseg == 0 && tile.nseg == 0) {
-        c[0] = (float)(dbg_t1 - dbg_t0);
-        c[1] = (float)(dbg_t2 - dbg_t1);
-        c[2] = (float)(dbg_t3 - dbg_t2);
-        c[3] = (float)dbg_wait;
-        c[4] = (float)(dbg_r3 - dbg_r0);
-        c[5] = (float)n_ktiles;
-    }
-#endif
 }
 
 template <int BM, int BN, int WVM, bool AKC, bool BKC>

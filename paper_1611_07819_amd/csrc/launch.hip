@@ -51,9 +51,11 @@ GemmChoice choose_gemm(const SegView& v)
     const bool f32 = v.in_dtype == DMATH_F32 && all_multiple(*v.klen, 32);
     const bool f64 = v.in_dtype == DMATH_F64 && all_multiple(*v.klen, 16);
     if (v.policy == 0 && v.aligned16 && (f32 || f64)) {
-        // Candidate shapes; take the one with the least serialised work per CU.  Smaller tiles
-        // move more bytes per flop, which costs clock at the power limit: 3 % handicap
+        // Candidate shapes; take the one with the least serialised work per CU.  fp32: smaller
+        // tiles move more bytes per flop, which costs clock at the power limit: 3 % handicap
         // (measured on configuration 2: 128x128 beats 128x64 when both fill the chip evenly).
+        // fp64: the register-staged kernel runs two 128x64 workgroups per CU and is 14 % faster
+        // that way on configuration 4, so there the larger tile carries the handicap.
         struct Shape {
             int bm, bn;
             bool needs_b_kcontig, f32_only;
@@ -68,7 +70,8 @@ GemmChoice choose_gemm(const SegView& v)
             if (!all_multiple(*v.mlen, s.bm) || !all_multiple(*v.nlen, s.bn)) continue;
             int64_t tiles = count_tiles(v, s.bm, s.bn);
             double cost = (double)((tiles + kCUs - 1) / kCUs) * s.bm * s.bn;
-            if (s.bm * s.bn < 128 * 128) cost *= 1.03;
+            if (f32 && s.bm * s.bn < 128 * 128) cost *= 1.03;
+            if (f64 && s.bm * s.bn >= 128 * 128) cost *= 1.03;
             if (best_cost < 0 || cost < best_cost) {
                 best_cost = cost;
                 ch.kernel = f32 ? KERNEL_F32_128 : KERNEL_F64_128;
