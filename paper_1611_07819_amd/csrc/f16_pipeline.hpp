@@ -15,12 +15,14 @@
 //   k unit-stride operand  : [mn][64 k], 128-byte rows, 16-byte chunk index XOR ((mn^(mn>>3))&7);
 //                            the MFMA fragment of a lane (8 consecutive k of one row) is one
 //                            ds_read_b128, conflict-free
-//   m/n unit-stride operand: [k][mn], 16-byte chunk index XOR ((k&3)<<1); fragments come from
+//   m/n unit-stride operand: [k][mn], 16-byte chunk index XOR ((k&3)<<2); fragments come from
 //                            two ds_read_b64_tr_b16 (the gfx950 transposing LDS read: inside a
 //                            16-lane group, lane i receives element i%4 of the 8 bytes fetched
 //                            by lanes i/4, i/4+4, i/4+8, i/4+12), so a group fetches a 4(k) x
 //                            16(mn) patch and every lane ends up with 4 consecutive k of its
-//                            own column; the XOR spreads the four k rows over the banks
+//                            own column; the XOR puts the four k rows x two 16-column groups
+//                            that 32 lanes fetch together into eight different 32-byte bank
+//                            groups
 //
 // What a kernel supplies is a "walk": for the k-tile about to be fetched, a wavefront-uniform
 // base pointer and one 32-bit byte offset per lane and 1 KiB segment for each operand, plus
@@ -79,7 +81,7 @@ template <int BMN, bool KC> struct OperandTile {
         const int seg = q * 4 + wave;
         row = seg * kRowsPerSeg + lane / kChunksPerRow;
         const int cpos = lane % kChunksPerRow;
-        chunk = KC ? (cpos ^ swz(row)) : (cpos ^ ((row & 3) << 1));
+        chunk = KC ? (cpos ^ swz(row)) : (cpos ^ ((row & 3) << 2));
     }
 
     // byte offsets (relative to the panel origin) for a dense panel with leading dimension ld
@@ -107,7 +109,7 @@ template <int BMN, bool KC> struct OperandTile {
         const int g = lane >> 4, i = lane & 15;
         const int row = 8 * (g >> 1) + (i >> 2);
         const int col = mn_base + 16 * (g & 1) + 4 * (i & 3);
-        return (uint32_t)(row * (BMN * 2) + (((col >> 3) ^ ((row & 3) << 1)) << 4) + (col & 7) * 2);
+        return (uint32_t)(row * (BMN * 2) + (((col >> 3) ^ ((row & 3) << 2)) << 4) + (col & 7) * 2);
     }
 
     __device__ __forceinline__ static v8h fragment(const lds_char* tile, uint32_t fb, int mn_row,
