@@ -25,13 +25,15 @@ template <int BM, int BN, bool AKC, bool BKC> struct PanelWalk {
     using TB = OperandTile<BN, BKC>;
     const GemmTables& t;
     const Tile& tile;
-    int wave, lane, ks, kleft;
+    int wave, lane, ks, ks_end, kleft;
     Panel pa, pb;
     const char *abase, *bbase;
     uint32_t aoff[TA::kInstr], boff[TB::kInstr];
 
-    __device__ __forceinline__ PanelWalk(const GemmTables& t_, const Tile& tile_, int wave_, int lane_)
-        : t(t_), tile(tile_), wave(wave_), lane(lane_), ks(0)
+    // walks the k-segments [ks_begin, ks_end_) (one split of a split-K plan, or all of them)
+    __device__ __forceinline__ PanelWalk(const GemmTables& t_, const Tile& tile_, int wave_, int lane_,
+                                         int ks_begin, int ks_end_)
+        : t(t_), tile(tile_), wave(wave_), lane(lane_), ks(ks_begin), ks_end(ks_end_)
     {
         load_panel();
     }
@@ -49,7 +51,7 @@ template <int BM, int BN, bool AKC, bool BKC> struct PanelWalk {
     {
         abase += TA::step(pa.ld);
         bbase += TB::step(pb.ld);
-        if (--kleft == 0 && ks + 1 < t.n_kseg) {
+        if (--kleft == 0 && ks + 1 < ks_end) {
             ++ks;
             load_panel();
         }
@@ -76,10 +78,26 @@ __global__ __launch_bounds__(NT) void gemm_f16_kernel(GemmTables t, float alpha,
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+    const int split = blockIdx.y, ks0 = t.ksplit[split], ks1 = t.ksplit[split + 1];
     int n_ktiles = 0;
-    for (int s = 0; s < t.n_kseg; ++s) n_ktiles += t.klen[s] / BK;
-    PanelWalk<BM, BN, AKC, BKC> walk(t, tile, wave, lane);
+    for (int s = ks0; s < ks1; ++s) n_ktiles += t.klen[s] / BK;
+    PanelWalk<BM, BN, AKC, BKC> walk(t, tile, wave, lane, ks0, ks1);
     run<BM, BN, STAGES, AKC, BKC>(walk, n_ktiles, smem, acc);
+
+    if (t.split_k > 1) {  // partial sums; the fixed-order reduction kernel finishes the job
+        float* ws = static_cast<float*>(t.workspace) + (int64_t)split * t.M * t.N;
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NTL; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = tile.m_glob + wm * WM + i * 32 + acc32_row(lane, r);
+                    const int col = tile.n_glob + wn * WN + j * 32 + l32;
+                    ws[(int64_t)row * t.N + col] = acc[i][j][r];
+                }
+        return;
+    }
 
     // epilogue: register r of a 32x32 result tile holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
     const Panel pc = t.c[tile.mseg * t.n_nseg + tile.nseg];
@@ -111,7 +129,7 @@ hipError_t launch_one(const GemmTables& t, float alpha, float beta, hipStream_t 
         if (e != hipSuccess) return e;
         configured = true;
     }
-    kern<<<dim3(t.n_tiles), dim3(NT), lds_bytes, st>>>(t, alpha, beta);
+    kern<<<dim3(t.n_tiles, t.split_k), dim3(NT), lds_bytes, st>>>(t, alpha, beta);
     return hipGetLastError();
 }
 

@@ -132,12 +132,14 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmTables t, float alpha,
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     // walk of the k-panels by the loader
-    const int ks_end = t.n_kseg;
-    int ks = 0, kleft;
+    // split-K: blockIdx.y owns the k-segments [ksplit[y], ksplit[y+1])
+    const int split = blockIdx.y;
+    const int ks_end = t.ksplit[split + 1];
+    int ks = t.ksplit[split], kleft;
     int n_ktiles = 0;
-    for (int s = 0; s < ks_end; ++s) n_ktiles += t.klen[s] / BK;
-    Panel pa = t.a[tile.mseg * t.n_kseg], pb = t.b[tile.nseg];
-    kleft = t.klen[0] / BK;
+    for (int s = ks; s < ks_end; ++s) n_ktiles += t.klen[s] / BK;
+    Panel pa = t.a[tile.mseg * t.n_kseg + ks], pb = t.b[ks * t.n_nseg + tile.nseg];
+    kleft = t.klen[ks] / BK;
     const char* abase = static_cast<const char*>(pa.ptr);
     const char* bbase = static_cast<const char*>(pb.ptr);
     uint32_t aoff[TA::kInstr], boff[TB::kInstr];
@@ -259,6 +261,20 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmTables t, float alpha,
     asm volatile("" ::: "memory");
     multiply(stage, 0, std::false_type{});
 
+    if (t.split_k > 1) {  // partial sums; the fixed-order reduction kernel finishes the job
+        float* ws = static_cast<float*>(t.workspace) + (int64_t)split * t.M * t.N;
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NTL; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = tile.m_glob + wm * WM + i * 32 + acc32_row(lane, r);
+                    const int col = tile.n_glob + wn * WN + j * 32 + l32;
+                    ws[(int64_t)row * t.N + col] = acc[i][j][r];
+                }
+        return;
+    }
     // epilogue: register r of a 32x32 result tile holds row 8*(r/4) + 4*h + r%4, column l32
     const Panel pc = t.c[tile.mseg * t.n_nseg + tile.nseg];
     float* c = static_cast<float*>(const_cast<void*>(pc.ptr));
@@ -289,7 +305,7 @@ hipError_t launch_one(const GemmTables& t, float alpha, float beta, hipStream_t 
         if (e != hipSuccess) return e;
         configured = true;
     }
-    kern<<<dim3(t.n_tiles), dim3(NT), lds_bytes, st>>>(t, alpha, beta);
+    kern<<<dim3(t.n_tiles, t.split_k), dim3(NT), lds_bytes, st>>>(t, alpha, beta);
     return hipGetLastError();
 }
 

@@ -133,12 +133,14 @@ __global__ __launch_bounds__(NT) void gemm_f64_kernel(GemmTables t, double alpha
             for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0;
 
     // walk of the k-panels by the loader
-    const int ks_end = t.n_kseg;
-    int ks = 0, kleft;
+    // split-K: blockIdx.y owns the k-segments [ksplit[y], ksplit[y+1])
+    const int split = blockIdx.y;
+    const int ks_end = t.ksplit[split + 1];
+    int ks = t.ksplit[split], kleft;
     int n_ktiles = 0;
-    for (int s = 0; s < ks_end; ++s) n_ktiles += t.klen[s] / BK;
-    Panel pa = t.a[tile.mseg * t.n_kseg], pb = t.b[tile.nseg];
-    kleft = t.klen[0] / BK;
+    for (int s = ks; s < ks_end; ++s) n_ktiles += t.klen[s] / BK;
+    Panel pa = t.a[tile.mseg * t.n_kseg + ks], pb = t.b[ks * t.n_nseg + tile.nseg];
+    kleft = t.klen[ks] / BK;
     const char* abase = static_cast<const char*>(pa.ptr);
     const char* bbase = static_cast<const char*>(pb.ptr);
     uint32_t aoff[TA::kInstr], boff[TB::kInstr];
@@ -260,6 +262,20 @@ __global__ __launch_bounds__(NT) void gemm_f64_kernel(GemmTables t, double alpha
     asm volatile("" ::: "memory");
     multiply(stage, 0, std::false_type{});
 
+    if (t.split_k > 1) {  // partial sums; the fixed-order reduction kernel finishes the job
+        double* ws = static_cast<double*>(t.workspace) + (int64_t)split * t.M * t.N;
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NTL; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int row = tile.m_glob + wm * WM + i * 16 + acc16d_row(lane, r);
+                    const int col = tile.n_glob + wn * WN + j * 16 + l32;
+                    ws[(int64_t)row * t.N + col] = acc[i][j][r];
+                }
+        return;
+    }
     // epilogue: register r of a 16x16 result tile holds row 4*r + lane/16, column lane%16
     const Panel pc = t.c[tile.mseg * t.n_nseg + tile.nseg];
     double* c = static_cast<double*>(const_cast<void*>(pc.ptr));
@@ -290,7 +306,7 @@ hipError_t launch_one(const GemmTables& t, double alpha, double beta, hipStream_
         if (e != hipSuccess) return e;
         configured = true;
     }
-    kern<<<dim3(t.n_tiles), dim3(NT), lds_bytes, st>>>(t, alpha, beta);
+    kern<<<dim3(t.n_tiles, t.split_k), dim3(NT), lds_bytes, st>>>(t, alpha, beta);
     return hipGetLastError();
 }
 

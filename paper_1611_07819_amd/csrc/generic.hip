@@ -186,22 +186,34 @@ __global__ __launch_bounds__(GTHREADS) void gemm_generic_kernel(GemmTables t, do
 }
 
 // Fixed-order sum of the split-K partials followed by the epilogue; with n_partials == 0 it is
-// the alpha == 0 path (C <- beta * C) that never touches A or B.
+// the alpha == 0 path (C <- beta * C) that never touches A or B.  Grid: (tiles, row chunks of
+// kReduceRows rows), so that few large tiles still fill the chip.
+constexpr int kReduceRows = 8;
 template <class AccT, class TC>
 __global__ __launch_bounds__(GTHREADS) void gemm_reduce_kernel(GemmTables t, int n_partials,
                                                                double alpha_d, double beta_d)
 {
     const Tile tile = t.tiles[blockIdx.x];
+    const int r0 = blockIdx.y * kReduceRows;
+    if (r0 >= tile.m_len) return;
+    const int rows = min(kReduceRows, tile.m_len - r0);
     const Panel pc = t.c[tile.mseg * t.n_nseg + tile.nseg];
     TC* c = static_cast<TC*>(const_cast<void*>(pc.ptr));
     const AccT* ws = static_cast<const AccT*>(t.workspace);
     const AccT alpha = static_cast<AccT>(alpha_d), beta = static_cast<AccT>(beta_d);
-    const int count = tile.m_len * tile.n_len;
+    const int64_t slice = t.M * t.N;
+    const int count = rows * tile.n_len;
     for (int e = threadIdx.x; e < count; e += GTHREADS) {
-        int i = e / tile.n_len, j = e % tile.n_len;
+        const int i = r0 + e / tile.n_len, j = e % tile.n_len;
+        const AccT* p = ws + (int64_t)(tile.m_glob + i) * t.N + tile.n_glob + j;
         AccT sum = AccT(0);
-        for (int s = 0; s < n_partials; ++s)
-            sum += ws[(int64_t)s * t.M * t.N + (int64_t)(tile.m_glob + i) * t.N + tile.n_glob + j];
+        int s = 0;
+        for (; s + 4 <= n_partials; s += 4) {  // four loads in flight, added in ascending order
+            const AccT p0 = p[(int64_t)s * slice], p1 = p[(int64_t)(s + 1) * slice];
+            const AccT p2 = p[(int64_t)(s + 2) * slice], p3 = p[(int64_t)(s + 3) * slice];
+            sum = (((sum + p0) + p1) + p2) + p3;
+        }
+        for (; s < n_partials; ++s) sum += p[(int64_t)s * slice];
         epilogue_store(c + (int64_t)(tile.m_off + i) * pc.ld + tile.n_off + j, sum, alpha, beta);
     }
 }
@@ -338,19 +350,24 @@ __global__ __launch_bounds__(GTHREADS) void conv_reduce_kernel(ConvTables t, int
     }
 }
 
+dim3 reduce_grid(const GemmPlan& p)
+{
+    return dim3(p.t.n_tiles, (p.info.tile_m + kReduceRows - 1) / kReduceRows);
+}
+
 template <class T, class TC>
 hipError_t run_gemm_generic(const GemmPlan& p, double alpha, double beta, hipStream_t st)
 {
     using AccT = typename Traits<T>::acc_t;
     const GemmTables& t = p.t;
     if (alpha == 0.0) {
-        gemm_reduce_kernel<AccT, TC><<<t.n_tiles, GTHREADS, 0, st>>>(t, 0, 0.0, beta);
+        gemm_reduce_kernel<AccT, TC><<<reduce_grid(p), GTHREADS, 0, st>>>(t, 0, 0.0, beta);
         return hipGetLastError();
     }
     gemm_generic_kernel<T, TC><<<dim3(t.n_tiles, t.split_k), GTHREADS, 0, st>>>(t, alpha, beta);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || t.split_k == 1) return e;
-    gemm_reduce_kernel<AccT, TC><<<t.n_tiles, GTHREADS, 0, st>>>(t, t.split_k, alpha, beta);
+    gemm_reduce_kernel<AccT, TC><<<reduce_grid(p), GTHREADS, 0, st>>>(t, t.split_k, alpha, beta);
     return hipGetLastError();
 }
 
@@ -394,16 +411,17 @@ hipError_t launch_gemm_generic(const GemmPlan& p, double alpha, double beta, hip
     return run_gemm_generic<_Float16, float>(p, alpha, beta, st);
 }
 
-// C <- beta * C without reading A or B (alpha == 0), for any tile shape.
-hipError_t launch_gemm_scale_only(const GemmPlan& p, double beta, hipStream_t st)
+// C <- alpha * (sum of the first n_partials split-K partials, ascending) + beta * C, for any
+// tile shape.  n_partials == 0 is the alpha == 0 path: A and B are never read.
+hipError_t launch_gemm_reduce(const GemmPlan& p, int n_partials, double alpha, double beta, hipStream_t st)
 {
     const GemmTables& t = p.t;
     if (p.in_dtype == DMATH_F64)
-        gemm_reduce_kernel<double, double><<<t.n_tiles, GTHREADS, 0, st>>>(t, 0, 0.0, beta);
+        gemm_reduce_kernel<double, double><<<reduce_grid(p), GTHREADS, 0, st>>>(t, n_partials, alpha, beta);
     else if (p.out_dtype == DMATH_F32)
-        gemm_reduce_kernel<float, float><<<t.n_tiles, GTHREADS, 0, st>>>(t, 0, 0.0, beta);
+        gemm_reduce_kernel<float, float><<<reduce_grid(p), GTHREADS, 0, st>>>(t, n_partials, alpha, beta);
     else
-        gemm_reduce_kernel<float, _Float16><<<t.n_tiles, GTHREADS, 0, st>>>(t, 0, 0.0, beta);
+        gemm_reduce_kernel<float, _Float16><<<reduce_grid(p), GTHREADS, 0, st>>>(t, n_partials, alpha, beta);
     return hipGetLastError();
 }
 

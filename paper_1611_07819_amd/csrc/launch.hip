@@ -10,7 +10,7 @@
 namespace dm {
 
 hipError_t launch_gemm_generic(const GemmPlan& p, double alpha, double beta, hipStream_t st);
-hipError_t launch_gemm_scale_only(const GemmPlan& p, double beta, hipStream_t st);
+hipError_t launch_gemm_reduce(const GemmPlan& p, int n_partials, double alpha, double beta, hipStream_t st);
 hipError_t launch_conv_generic(const ConvPlan& p, int mode, double alpha, double beta, hipStream_t st);
 hipError_t launch_gemm_f32(const GemmPlan& p, double alpha, double beta, hipStream_t st);
 hipError_t launch_gemm_f64(const GemmPlan& p, double alpha, double beta, hipStream_t st);
@@ -19,6 +19,15 @@ hipError_t launch_gemm_f16(const GemmPlan& p, double alpha, double beta, hipStre
 namespace {
 
 constexpr int kCUs = 256;
+
+// Few tiles and a deep K: split K over workgroups so that the chip is filled; every split keeps
+// at least 8 k-steps of 64.  The partial sums are reduced in a fixed order by a second kernel.
+int32_t split_for(int64_t tiles, int64_t K)
+{
+    if (tiles * 2 > kCUs || K < 1024) return 1;
+    int64_t want = kCUs / tiles, max_by_k = K / 512;
+    return (int32_t)std::max<int64_t>(1, std::min<int64_t>({want, max_by_k, 32}));
+}
 
 bool all_multiple(const std::vector<int64_t>& v, int64_t q)
 {
@@ -78,6 +87,7 @@ GemmChoice choose_gemm(const SegView& v)
                 ch.tile_m = s.bm;
                 ch.tile_n = s.bn;
                 ch.tile_k = f32 ? 32 : 16;
+                ch.split_k = split_for(tiles, v.K);
             }
         }
         if (ch.kernel != KERNEL_GENERIC) return ch;
@@ -98,6 +108,7 @@ GemmChoice choose_gemm(const SegView& v)
                 ch.tile_m = s[0];
                 ch.tile_n = s[1];
                 ch.tile_k = 64;
+                ch.split_k = split_for(tiles, v.K);
             }
         }
         if (ch.kernel != KERNEL_GENERIC) return ch;
@@ -115,13 +126,16 @@ GemmChoice choose_gemm(const SegView& v)
 
 hipError_t launch_gemm(const GemmPlan& p, double alpha, double beta, hipStream_t st)
 {
-    if (alpha == 0.0) return launch_gemm_scale_only(p, beta, st);
+    if (alpha == 0.0) return launch_gemm_reduce(p, 0, 0.0, beta, st);
+    hipError_t e;
     switch (p.info.kernel) {
-    case KERNEL_F32_128: return launch_gemm_f32(p, alpha, beta, st);
-    case KERNEL_F64_128: return launch_gemm_f64(p, alpha, beta, st);
-    case KERNEL_F16_256: return launch_gemm_f16(p, alpha, beta, st);
-    default: return launch_gemm_generic(p, alpha, beta, st);
+    case KERNEL_F32_128: e = launch_gemm_f32(p, alpha, beta, st); break;
+    case KERNEL_F64_128: e = launch_gemm_f64(p, alpha, beta, st); break;
+    case KERNEL_F16_256: e = launch_gemm_f16(p, alpha, beta, st); break;
+    default: return launch_gemm_generic(p, alpha, beta, st);  // does its own reduction
     }
+    if (e != hipSuccess || p.t.split_k == 1) return e;
+    return launch_gemm_reduce(p, p.t.split_k, alpha, beta, st);
 }
 
 hipError_t launch_conv(const ConvPlan& p, int mode, double alpha, double beta, hipStream_t st)

@@ -310,3 +310,34 @@ def test_every_tile_shape_of_the_specialised_kernels(ctx, oracle, dt, shape, ta,
     assert np.array_equal(got.astype(np.float64), ref)
     for m in (dA, dB, dC):
         m.destroy()
+
+
+@pytest.mark.parametrize("dt,out", [(dm.F64, dm.F64), (dm.F32, dm.F32), (dm.F16, dm.F32), (dm.F16, dm.F16)])
+@pytest.mark.parametrize("ta,tb", [(0, 0), (1, 0), (0, 1)])
+def test_specialised_kernels_with_split_k(ctx, oracle, dt, out, ta, tb):
+    """Few C tiles, deep K: the specialised kernels split K over workgroups and a second kernel
+    adds the partial sums in a fixed order.  Integer inputs: bit-for-bit; two runs: identical."""
+    r = np.random.default_rng(600)
+    M, N, K = 256, 384, 4096
+    opA = r.integers(-1, 2, (M, K)).astype(NP[dt])
+    opB = r.integers(-1, 2, (K, N)).astype(NP[dt])
+    C0 = r.integers(-3, 4, (M, N)).astype(NP[out])
+    ga, gb, gc = (1, 2), (2, 1), (1, 1)
+    ga = ga[::-1] if ta else ga
+    gb = gb[::-1] if tb else gb
+    ctx.set_kernel_policy(0)
+    dA, dB = ctx.from_host(stored(opA, ta), ga), ctx.from_host(stored(opB, tb), gb)
+    ref = oracle.gemm(bool(ta), bool(tb), 1.0, oracle.BlockMatrix(stored(opA, ta), ga),
+                      oracle.BlockMatrix(stored(opB, tb), gb), 1.0, oracle.BlockMatrix(C0, gc))
+    outs = []
+    for _ in range(2):
+        dC = ctx.from_host(C0, gc)
+        info = dm.gemm_plan_info(ctx, ta, tb, dA, dB, dC)
+        assert info["kernel"] != 0 and info["split_k"] > 1 and info["workspace_bytes"] > 0
+        dm.gemm(ctx, ta, tb, 1.0, dA, dB, 1.0, dC)
+        outs.append(dC.get())
+        dC.destroy()
+    assert np.array_equal(outs[0].astype(np.float64), ref)
+    assert np.array_equal(outs[0], outs[1])
+    for m in (dA, dB):
+        m.destroy()
