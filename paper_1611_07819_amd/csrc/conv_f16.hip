@@ -13,6 +13,9 @@
 //   weight gradient: dF[k, K]  = sum_m  Yt[m, k] * Xp-rows[m, K]          (T,N)-like, deep sum over
 //                    m, split over workgroups, fixed-order reduction; Yt = dY rewritten
 //                    channels-last, [m][k].
+//   data gradient  : the forward kernel again, over the zero-bordered channels-last copy of dY
+//                    (padding r-1-pad) with the filter rotated by 180 degrees and its channel
+//                    roles swapped, Gp[c][(r',s',k)].
 // The rewrites are part of every call (activations change every step); their cost is inside
 // the timed region.
 #include <hip/hip_runtime.h>
@@ -82,6 +85,21 @@ __global__ __launch_bounds__(256) void filter_to_rsc_kernel(const void* const* f
         const int kk = (int)(e / (c * rs)), rem = (int)(e % (c * rs));
         const int q = rem / c, cc = rem % c;  // destination order (rs, c)
         fp[e] = static_cast<const _Float16*>(f_rows[kk])[cc * rs + q];
+    }
+}
+
+// F[k][c][r][s] -> Gp[c][(r',s',k)] with r' = R-1-r, s' = S-1-s: the filter of the forward
+// convolution (over dY, channels k) that computes the data gradient.
+__global__ __launch_bounds__(256) void filter_to_rsk_rotated_kernel(const void* const* f_rows, int c, int r,
+                                                                    int s, int k, _Float16* gp)
+{
+    const int rs = r * s;
+    const int64_t total = (int64_t)c * rs * k;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        const int cc = (int)(e / (rs * k)), rem = (int)(e % (rs * k));
+        const int q = rem / k, kk = rem % k;  // destination order (r', s', k)
+        const int rr = r - 1 - q / s, ss = s - 1 - q % s;
+        gp[e] = static_cast<const _Float16*>(f_rows[kk])[cc * rs + rr * s + ss];
     }
 }
 
@@ -335,13 +353,20 @@ bool conv_f16_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype)
 {
     if (in_dtype != DMATH_F16 || g.stride_h != 1 || g.stride_w != 1) return false;
     const int64_t sp_out = (int64_t)g.oh * g.ow, m = (int64_t)g.n * sp_out;
-    if (g.c % 64 || (g.h * g.w) % 8 || (int64_t)64 * tcl_stride(g.h * g.w) * 2 > 150 * 1024) return false;
+    if (mode != CONV_BWD_DATA &&
+        (g.c % 64 || (g.h * g.w) % 8 || (int64_t)64 * tcl_stride(g.h * g.w) * 2 > 150 * 1024))
+        return false;
     if (sp_out < 64) return false;
     if (mode == CONV_FWD) return g.k % 128 == 0 && m % 256 == 0 && sp_out % 4 == 0;
     if (mode == CONV_BWD_FILTER)
         return g.k == 256 && g.c % 128 == 0 && m % 64 == 0 && g.k % 64 == 0 && sp_out % 8 == 0 &&
                (int64_t)64 * tcl_stride((int)sp_out) * 2 <= 150 * 1024;
-    return false;
+    // data gradient = forward convolution of dY (k channels) with the rotated filter and
+    // padding r-1-pad: needs that padding to be non-negative
+    const int64_t m_in = (int64_t)g.n * g.h * g.w;
+    return g.pad_h <= g.r - 1 && g.pad_w <= g.s - 1 && g.k % 64 == 0 && g.c % 128 == 0 && m_in % 256 == 0 &&
+           (g.h * g.w) % 4 == 0 && g.h * g.w >= 64 && sp_out % 8 == 0 &&
+           (int64_t)64 * tcl_stride((int)sp_out) * 2 <= 150 * 1024;
 }
 
 // Split count for the weight gradient: enough workgroups to fill the chip, dividing the k-tiles.
@@ -370,7 +395,7 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
     p.yt = static_cast<const _Float16*>(plan.yt);
     p.ws = static_cast<float*>(t.workspace);
     p.split = t.split_k;
-    if (!plan.xp || (mode == CONV_FWD && !plan.fp) || (mode == CONV_BWD_FILTER && (!plan.yt || !p.ws)))
+    if (!plan.xp || (mode != CONV_BWD_FILTER && !plan.fp) || (mode == CONV_BWD_FILTER && (!plan.yt || !p.ws)))
         return hipErrorInvalidValue;  // the plan was not made for this path
 
     static bool configured = false;
@@ -383,6 +408,37 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
         if (e == hipSuccess) e = set_lds(conv_wgrad_f16_kernel<256, 128>, 3 * 384 * 128);
         if (e != hipSuccess) return e;
         configured = true;
+    }
+    if (mode == CONV_BWD_DATA) {
+        // forward convolution over dY: input channels k, spatial oh x ow, padding r-1-pad,
+        // rotated filter, output channels c, output spatial h x w, output rows = images of dX
+        FastConv q = p;
+        const int pph = g.r - 1 - g.pad_h, ppw = g.s - 1 - g.pad_w;
+        q.g.c = g.k; q.g.k = g.c;
+        q.g.h = g.oh; q.g.w = g.ow; q.g.oh = g.h; q.g.ow = g.w;
+        q.g.pad_h = pph; q.g.pad_w = ppw;
+        q.hp = g.oh + 2 * pph;
+        q.wp = g.ow + 2 * ppw;
+        q.y_rows = t.x_rows;
+        const int lds = 64 * tcl_stride(g.oh * g.ow) * 2;
+        to_channels_last_kernel<<<g.n * (g.k / 64), kTclThreads, lds, st>>>(t.y_rows, g.k, g.oh, g.ow, pph, ppw,
+                                                                             q.hp, q.wp, static_cast<_Float16*>(plan.xp));
+        filter_to_rsk_rotated_kernel<<<512, 256, 0, st>>>(t.f_rows, g.c, g.r, g.s, g.k, static_cast<_Float16*>(plan.fp));
+        const int mt = (int)((int64_t)g.n * g.h * g.w / 256);
+        const int t128 = mt * (g.c / 128), t256 = mt * (g.c / 256);
+        const bool wide = g.c % 256 == 0 && t128 > 256 && t256 <= 256;
+        if (wide) {
+            if (plan.out_dtype == DMATH_F16)
+                conv_fwd_f16_kernel<256, 256, 2, _Float16><<<t256, NT, 2 * 512 * 128, st>>>(q, (float)alpha, (float)beta);
+            else
+                conv_fwd_f16_kernel<256, 256, 2, float><<<t256, NT, 2 * 512 * 128, st>>>(q, (float)alpha, (float)beta);
+        } else {
+            if (plan.out_dtype == DMATH_F16)
+                conv_fwd_f16_kernel<256, 128, 3, _Float16><<<t128, NT, 3 * 384 * 128, st>>>(q, (float)alpha, (float)beta);
+            else
+                conv_fwd_f16_kernel<256, 128, 3, float><<<t128, NT, 3 * 384 * 128, st>>>(q, (float)alpha, (float)beta);
+        }
+        return hipGetLastError();
     }
     // activations -> zero-bordered channels-last copy (borders were zeroed when the plan was made)
     {

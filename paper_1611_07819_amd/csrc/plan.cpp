@@ -358,7 +358,7 @@ dmath_status_t get_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t
     plan->in_dtype = (mode == CONV_FWD) ? X->dtype : Y->dtype;
     plan->out_dtype = result->dtype;
 
-    const bool fast = ctx->policy == 0 && mode != CONV_BWD_DATA && conv_f16_fast_ok(mode, g, plan->in_dtype);
+    const bool fast = ctx->policy == 0 && conv_f16_fast_ok(mode, g, plan->in_dtype);
     plan->kernel = fast ? 1 : 0;
     // split-K for the weight gradient: few C tiles, very deep K
     t.split_k = 1;
@@ -398,13 +398,18 @@ dmath_status_t get_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t
         }
     }
     if (fast) {
-        const size_t xp_bytes = (size_t)g.n * (g.h + 2 * g.pad_h) * (g.w + 2 * g.pad_w) * g.c * 2;
+        // padded channels-last copy of the gathered tensor: X for forward / weight gradient, dY
+        // (padding r-1-pad) for the data gradient
+        const size_t xp_bytes =
+            mode == CONV_BWD_DATA
+                ? (size_t)g.n * (g.oh + 2 * (g.r - 1 - g.pad_h)) * (g.ow + 2 * (g.s - 1 - g.pad_w)) * g.k * 2
+                : (size_t)g.n * (g.h + 2 * g.pad_h) * (g.w + 2 * g.pad_w) * g.c * 2;
         plan->xp = ctx->pool.alloc(xp_bytes);
-        if (mode == CONV_FWD) plan->fp = ctx->pool.alloc((size_t)g.k * crs * 2);
+        if (mode != CONV_BWD_FILTER) plan->fp = ctx->pool.alloc((size_t)g.k * crs * 2);
         if (mode == CONV_BWD_FILTER) plan->yt = ctx->pool.alloc((size_t)g.n * sp_out * g.k * 2);
         plan->dev_tables = dev;
         plan->workspace = ws;
-        bool ok = plan->xp && (mode != CONV_FWD || plan->fp) && (mode != CONV_BWD_FILTER || plan->yt);
+        bool ok = plan->xp && (mode == CONV_BWD_FILTER || plan->fp) && (mode != CONV_BWD_FILTER || plan->yt);
         // the zero border of the padded copy is written once; every call rewrites the interior
         if (ok && hipMemsetAsync(plan->xp, 0, xp_bytes, ctx->stream) != hipSuccess) {
             free_conv_plan(ctx, *plan);

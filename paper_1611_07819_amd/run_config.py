@@ -48,6 +48,9 @@ def main():
         calls.append(("conv_fwd", fl, "", lambda: dm.conv_fwd(ctx, d, 1.0, dev["X"], dev["F"], 0.0, dev["Y"])))
         calls.append(("conv_bwd_filter", fl, "",
                       lambda: dm.conv_bwd_filter(ctx, d, 1.0, dev["X"], dev["dY"], 0.0, dev["dF"])))
+        dev["dX"] = ctx.matrix(dev["X"].rows, dev["X"].cols, (1, 1), dev["Y"].dtype)
+        calls.append(("conv_bwd_data", fl, "",
+                      lambda: dm.conv_bwd_data(ctx, d, 1.0, dev["dY"], dev["F"], 0.0, dev["dX"])))
     for name, fl, desc, f in calls:
         if args.only and args.only != name:
             continue

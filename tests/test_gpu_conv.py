@@ -152,7 +152,7 @@ def test_specialised_fp16_conv_whole_result(ctx, oracle, g, out):
     row-blocked layout of every tensor."""
     grids = {"X": (1, 1), "F": (1, 1), "Y": (1, 1)}
     res = three_modes(ctx, oracle, g, dm.F16, out, 1.5, -0.5, grids, policy=0)
-    for mode in ("fwd", "bwd_filter"):
+    for mode in ("fwd", "bwd_filter", "bwd_data"):
         got, ref = res[mode]
         assert rel_fro(got, ref) <= TOL[dm.F16], mode
     d, t = tensors(g, dm.F16, 300, ints=True)
@@ -160,16 +160,19 @@ def test_specialised_fp16_conv_whole_result(ctx, oracle, g, out):
     od = oracle.ConvDesc(**g)
     grids = {"X": (g["n"], 1), "F": (2, 1), "Y": (2, 1)}
     ctx.set_kernel_policy(0)
-    for mode in ("fwd", "bwd_filter"):
-        out_name = "Y" if mode == "fwd" else "F"
+    for mode in ("fwd", "bwd_filter", "bwd_data"):
+        out_name = {"fwd": "Y", "bwd_filter": "F", "bwd_data": "X"}[mode]
         host = {k: (v.astype(NP[out]) if k == out_name else v) for k, v in t.items()}
         dev = {k: ctx.from_host(v, grids[k]) for k, v in host.items()}
         if mode == "fwd":
             dm.conv_fwd(ctx, d, 1.0, dev["X"], dev["F"], 1.0, dev["Y"])
             ref = oracle.conv_fwd(od, 1.0, host["X"], host["F"], 1.0, host["Y"])
-        else:
+        elif mode == "bwd_filter":
             dm.conv_bwd_filter(ctx, d, 1.0, dev["X"], dev["Y"], 1.0, dev["F"])
             ref = oracle.conv_bwd_filter(od, 1.0, host["X"], host["Y"], 1.0, host["F"])
+        else:
+            dm.conv_bwd_data(ctx, d, 1.0, dev["Y"], dev["F"], 1.0, dev["X"])
+            ref = oracle.conv_bwd_data(od, 1.0, host["Y"], host["F"], 1.0, host["X"])
         got = dev[out_name].get().astype(np.float64)
         if out == dm.F16 and np.abs(ref).max() > 2048:
             assert rel_fro(got, ref) <= TOL[dm.F16], mode
