@@ -94,6 +94,15 @@ dmath_status_t dmath_matrix_block(dmath_matrix_t m, int32_t bi, int32_t bj, void
                                   int64_t *rows, int64_t *cols, int64_t *ld);
 
 /*
+ * dst <- src element by element, for any two block grids and any two precisions (section 3.3:
+ * "reshape (including a change of ... layout) ... and/or change precision during reshape").
+ * Shapes must be equal (DMATH_ERR_SHAPE); src and dst must differ (DMATH_ERR_ALIAS).  Widening is
+ * exact; narrowing rounds to nearest even in ONE step (also double -> half), overflow gives
+ * +-Inf, NaN stays NaN.  Runs on the context's stream; asynchronous.
+ */
+dmath_status_t dmath_matrix_reblock(dmath_ctx_t ctx, dmath_matrix_t src, dmath_matrix_t dst);
+
+/*
  * C <- alpha * op(A) * op(B) + beta * C            (abstract: "matrix multiplication";
  * section 1: the back-propagation variants dW = X^T dY (T,N) and dX = dY W^T (N,T))
  *

@@ -203,6 +203,13 @@ def conv_bwd_data(d: ConvDesc, alpha, dY, F, beta=0.0, dX=None, images=None):
                       d.c * d.h * d.w)
 
 
+def convert(dense, dtype):
+    """Re-layout with precision change (section 3.3, "change precision during reshape"): the
+    values are unchanged when widening and rounded once, to nearest even, when narrowing.  The
+    block grid does not enter: a matrix is the same matrix however it is cut (section 3.2)."""
+    return np.asarray(dense).astype(dtype)
+
+
 def rel_frobenius(got, ref) -> float:
     """||got - ref||_F / ||ref||_F in fp64; if ref is all zero, returns ||got||_F."""
     got = np.asarray(got, dtype=np.float64)

@@ -2,7 +2,9 @@
 // of the method runs in the kernels; nothing here computes on matrix elements.
 #include <hip/hip_runtime_api.h>
 
+#include <algorithm>
 #include <new>
+#include <vector>
 
 #include "context.hpp"
 
@@ -197,6 +199,54 @@ dmath_status_t dmath_matrix_block(dmath_matrix_t m, int32_t bi, int32_t bj, void
     if (cols) *cols = m->csplit.len(bj);
     if (ld) *ld = m->csplit.len(bj);
     return DMATH_OK;
+}
+
+dmath_status_t dmath_matrix_reblock(dmath_ctx_t ctx, dmath_matrix_t src, dmath_matrix_t dst)
+{
+    if (!ctx || !owns(ctx, src) || !owns(ctx, dst)) return DMATH_ERR_INVALID_ARG;
+    if (src == dst) return DMATH_ERR_ALIAS;
+    if (src->rows != dst->rows || src->cols != dst->cols) return DMATH_ERR_SHAPE;
+    // cut rows and columns at every block boundary of either matrix
+    auto cuts = [](const Split& a, const Split& b) {
+        std::vector<int64_t> c{0, a.n};
+        for (int32_t p = 1; p < a.g; ++p) c.push_back(a.lo(p));
+        for (int32_t p = 1; p < b.g; ++p) c.push_back(b.lo(p));
+        std::sort(c.begin(), c.end());
+        c.erase(std::unique(c.begin(), c.end()), c.end());
+        return c;
+    };
+    const std::vector<int64_t> rc = cuts(src->rsplit, dst->rsplit), cc = cuts(src->csplit, dst->csplit);
+    const int64_t ses = elem_size(src->dtype), des = elem_size(dst->dtype);
+    std::vector<CopyCell> cells;
+    int max_rows = 0;
+    for (size_t i = 0; i + 1 < rc.size(); ++i)
+        for (size_t j = 0; j + 1 < cc.size(); ++j) {
+            const int64_t r = rc[i], c = cc[j];
+            const int32_t sbi = src->rsplit.part(r), sbj = src->csplit.part(c);
+            const int32_t dbi = dst->rsplit.part(r), dbj = dst->csplit.part(c);
+            CopyCell cell;
+            cell.src_ld = src->csplit.len(sbj);
+            cell.dst_ld = dst->csplit.len(dbj);
+            cell.src = static_cast<const char*>(src->block(sbi, sbj)) +
+                       ((r - src->rsplit.lo(sbi)) * cell.src_ld + (c - src->csplit.lo(sbj))) * ses;
+            cell.dst = static_cast<char*>(dst->block(dbi, dbj)) +
+                       ((r - dst->rsplit.lo(dbi)) * cell.dst_ld + (c - dst->csplit.lo(dbj))) * des;
+            cell.rows = (int32_t)(rc[i + 1] - r);
+            cell.cols = (int32_t)(cc[j + 1] - c);
+            max_rows = std::max(max_rows, cell.rows);
+            cells.push_back(cell);
+        }
+    const size_t bytes = cells.size() * sizeof(CopyCell);
+    void* dev = ctx->pool.alloc(bytes);
+    if (!dev) return DMATH_ERR_OOM;
+    // the table is pageable host memory: copy, wait, then it may go; the kernel itself is asynchronous
+    hipError_t e = hipMemcpyAsync(dev, cells.data(), bytes, hipMemcpyHostToDevice, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    if (e == hipSuccess)
+        e = launch_reblock(src->dtype, dst->dtype, static_cast<const CopyCell*>(dev), (int)cells.size(),
+                           max_rows, ctx->stream);
+    ctx->pool.free(dev);  // reuse of the table's memory is ordered after the kernel by the stream
+    return e == hipSuccess ? DMATH_OK : DMATH_ERR_DEVICE;
 }
 
 dmath_status_t dmath_gemm(dmath_ctx_t ctx, dmath_op_t transA, dmath_op_t transB, double alpha,

@@ -113,6 +113,8 @@ void drop_all_plans(dmath_ctx_s* ctx);
 // kernels (launch.hip)
 hipError_t launch_gemm(const GemmPlan& p, double alpha, double beta, hipStream_t stream);
 hipError_t launch_conv(const ConvPlan& p, int mode, double alpha, double beta, hipStream_t stream);
+hipError_t launch_reblock(dmath_dtype_t sd, dmath_dtype_t dd, const CopyCell* cells, int n_cells,
+                          int max_rows, hipStream_t st);
 bool conv_f16_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype);
 int conv_f16_wgrad_split(const ConvGeom& g);
 hipError_t launch_conv_f16(const ConvPlan& p, int mode, double alpha, double beta, hipStream_t st);

@@ -35,6 +35,14 @@ struct GemmTables {
     int64_t M, N;
 };
 
+// One rectangle of a re-layout: it lies inside one block of the source and one of the destination.
+struct CopyCell {
+    const void* src;
+    void* dst;
+    int64_t src_ld, dst_ld;
+    int32_t rows, cols;
+};
+
 struct ConvGeom {
     int32_t n, c, h, w, k, r, s, pad_h, pad_w, stride_h, stride_w, oh, ow;
 };

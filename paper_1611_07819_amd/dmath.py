@@ -82,6 +82,7 @@ def load_library(build_if_missing: bool = True):
         "dmath_matrix_get": [vp, vp, i64],
         "dmath_matrix_info": [vp, P(i64), P(i64), P(i32), P(i32), P(ctypes.c_int)],
         "dmath_matrix_block": [vp, i32, i32, P(vp), P(i64), P(i64), P(i64)],
+        "dmath_matrix_reblock": [vp, vp, vp],
         "dmath_gemm": [vp, ctypes.c_int, ctypes.c_int, dbl, vp, vp, dbl, vp],
         "dmath_gemm_plan_info": [vp, ctypes.c_int, ctypes.c_int, vp, vp, vp, P(_PlanInfo)],
         "dmath_conv_fwd": [vp, P(_ConvDesc), dbl, vp, vp, dbl, vp],
@@ -203,6 +204,11 @@ class Matrix:
         if self._h:
             _check(self.ctx._lib.dmath_matrix_destroy(self._h), "dmath_matrix_destroy")
             self._h = ctypes.c_void_p()
+
+
+def reblock(ctx: Context, src: Matrix, dst: Matrix):
+    """dst <- src across block grids and precisions."""
+    _check(ctx._lib.dmath_matrix_reblock(ctx._h, src._h, dst._h), "dmath_matrix_reblock")
 
 
 def gemm(ctx: Context, transA, transB, alpha, A: Matrix, B: Matrix, beta, C: Matrix):

@@ -292,3 +292,24 @@ def test_fp64_accuracy_on_deep_k(oracle):
     got = oracle.gemm(False, False, 1.0, A, B, 0.0)
     want = np.array([[math.fsum(A[i] * B[:, j]) for j in range(3)] for i in range(2)])
     assert np.abs(got - want).max() <= 1e-13 * np.abs(want).max() + 1e-13
+
+
+def test_convert_rounds_once_to_nearest_even(oracle):
+    # ties and a double-rounding trap, checked against hand-computed binary16 / binary32 values
+    h = np.float64
+    ulp16 = 2.0 ** -10                       # spacing of binary16 in [1, 2)
+    src = np.array([[1 + ulp16 / 2,          # tie -> even (1.0)
+                     1 + 3 * ulp16 / 2,      # tie -> even (1 + 2 ulp)
+                     1 + ulp16 / 2 + 2.0 ** -40,   # just above the tie: must round UP (a detour over
+                                                   # binary32 would first land on the tie, then go down)
+                     65504.0, 65520.0, 1e-8, -2.0 ** -25]], dtype=h)
+    with np.errstate(over="ignore"):
+        got = oracle.convert(src, np.float16).astype(h)
+    want = np.array([[1.0, 1 + 2 * ulp16, 1 + ulp16, 65504.0, np.inf, 0.0, -0.0]])
+    assert np.array_equal(got, want)
+    assert np.signbit(got[0, 6])
+    f = oracle.convert(np.array([[1 + 2.0 ** -24, 1 + 3 * 2.0 ** -24]]), np.float32).astype(h)
+    assert np.array_equal(f, np.array([[1.0, 1 + 2.0 ** -22]]))
+    # widening is exact
+    x = np.random.default_rng(30).uniform(-1, 1, (5, 7)).astype(np.float16)
+    assert np.array_equal(oracle.convert(x, np.float64), x.astype(np.float64))
