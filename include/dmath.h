@@ -182,6 +182,26 @@ dmath_status_t dmath_conv_bwd_data(dmath_ctx_t ctx, const dmath_conv_desc_t *des
                                    dmath_matrix_t dY, dmath_matrix_t F, double beta,
                                    dmath_matrix_t dX);
 
+/*
+ * Pipeline replay (section 3.3: with fixed pipelines the workers "remember the entire forward
+ * and backward computations", and one cached identifier replaces the per-operation metadata).
+ *   dmath_pipeline_begin : from now on dmath_gemm / dmath_conv_* calls of this context are
+ *                          recorded (HIP stream capture) instead of executed.  The context's
+ *                          stream must not be the default (NULL) stream.
+ *   dmath_pipeline_end   : stops recording and returns the identifier of the recorded sequence.
+ *   dmath_pipeline_replay: enqueues the whole sequence with one launch; same results, same
+ *                          order, on the same matrices (their contents are read at replay time).
+ * Every operation that is recorded must have been executed once before on the same handles,
+ * because building a plan copies tables and synchronises: otherwise the call returns
+ * DMATH_ERR_UNSUPPORTED (and recording continues).  dmath_matrix_set/get/reblock/create/destroy
+ * are refused while recording (DMATH_ERR_UNSUPPORTED).  Destroying a matrix that a pipeline
+ * uses invalidates the pipeline (the caller must not replay it).
+ */
+dmath_status_t dmath_pipeline_begin(dmath_ctx_t ctx);
+dmath_status_t dmath_pipeline_end(dmath_ctx_t ctx, int32_t *pipeline_id);
+dmath_status_t dmath_pipeline_replay(dmath_ctx_t ctx, int32_t pipeline_id);
+dmath_status_t dmath_pipeline_destroy(dmath_ctx_t ctx, int32_t pipeline_id);
+
 /* Kernel selection: 0 = automatic (specialised kernels where their preconditions hold),
  * 1 = always the guarded generic kernel (for testing and debugging).  Drops cached plans. */
 dmath_status_t dmath_set_kernel_policy(dmath_ctx_t ctx, int32_t policy);

@@ -41,6 +41,7 @@ dmath_status_t check_gemm(dmath_ctx_s* ctx, int ta, int tb, dmath_matrix_s* A, d
 dmath_status_t copy_blocks(dmath_matrix_s* m, void* host, int64_t ld, bool to_device)
 {
     if (!m || !host) return DMATH_ERR_INVALID_ARG;
+    if (m->ctx->recording) return DMATH_ERR_UNSUPPORTED;
     if (ld < m->cols) return DMATH_ERR_INVALID_ARG;
     const size_t es = elem_size(m->dtype);
     hipStream_t st = m->ctx->stream;
@@ -116,6 +117,12 @@ dmath_status_t dmath_init(dmath_ctx_t* ctx, void* slab, size_t slab_bytes, void*
 dmath_status_t dmath_finalize(dmath_ctx_t ctx)
 {
     if (!ctx) return DMATH_ERR_INVALID_ARG;
+    if (ctx->recording) {
+        hipGraph_t g = nullptr;
+        (void)hipStreamEndCapture(ctx->stream, &g);
+        if (g) (void)hipGraphDestroy(g);
+    }
+    for (auto& kv : ctx->pipelines) (void)hipGraphExecDestroy(kv.second);
     drop_all_plans(ctx);
     for (dmath_matrix_s* m : ctx->matrices) delete m;
     delete ctx;
@@ -128,6 +135,7 @@ dmath_status_t dmath_matrix_create(dmath_ctx_t ctx, int64_t rows, int64_t cols, 
     if (!ctx || !out || rows <= 0 || cols <= 0 || grid_rows <= 0 || grid_cols <= 0 ||
         !valid_dtype(dtype))
         return DMATH_ERR_INVALID_ARG;
+    if (ctx->recording) return DMATH_ERR_UNSUPPORTED;
     if (rows >= (1ll << 31) || cols >= (1ll << 31)) return DMATH_ERR_UNSUPPORTED;
     Split rs(rows, grid_rows), cs(cols, grid_cols);
     if (!rs.valid() || !cs.valid()) return DMATH_ERR_LAYOUT;
@@ -160,6 +168,7 @@ dmath_status_t dmath_matrix_destroy(dmath_matrix_t m)
 {
     if (!m || !m->ctx || !m->ctx->matrices.count(m)) return DMATH_ERR_INVALID_ARG;
     dmath_ctx_s* ctx = m->ctx;
+    if (ctx->recording) return DMATH_ERR_UNSUPPORTED;
     drop_plans_using(ctx, m->id);
     for (void* p : m->blocks) ctx->pool.free(p);
     ctx->matrices.erase(m);
@@ -206,6 +215,7 @@ dmath_status_t dmath_matrix_reblock(dmath_ctx_t ctx, dmath_matrix_t src, dmath_m
     if (!ctx || !owns(ctx, src) || !owns(ctx, dst)) return DMATH_ERR_INVALID_ARG;
     if (src == dst) return DMATH_ERR_ALIAS;
     if (src->rows != dst->rows || src->cols != dst->cols) return DMATH_ERR_SHAPE;
+    if (ctx->recording) return DMATH_ERR_UNSUPPORTED;
     // cut rows and columns at every block boundary of either matrix
     auto cuts = [](const Split& a, const Split& b) {
         std::vector<int64_t> c{0, a.n};
@@ -296,9 +306,53 @@ dmath_status_t dmath_conv_bwd_data(dmath_ctx_t ctx, const dmath_conv_desc_t* des
     return conv_call(ctx, CONV_BWD_DATA, desc, alpha, dX, F, dY, beta);
 }
 
+dmath_status_t dmath_pipeline_begin(dmath_ctx_t ctx)
+{
+    if (!ctx || ctx->recording) return DMATH_ERR_INVALID_ARG;
+    if (!ctx->stream) return DMATH_ERR_UNSUPPORTED;  // the default stream cannot be captured
+    if (hipStreamBeginCapture(ctx->stream, hipStreamCaptureModeThreadLocal) != hipSuccess)
+        return DMATH_ERR_DEVICE;
+    ctx->recording = true;
+    return DMATH_OK;
+}
+
+dmath_status_t dmath_pipeline_end(dmath_ctx_t ctx, int32_t* pipeline_id)
+{
+    if (!ctx || !pipeline_id || !ctx->recording) return DMATH_ERR_INVALID_ARG;
+    ctx->recording = false;
+    hipGraph_t graph = nullptr;
+    if (hipStreamEndCapture(ctx->stream, &graph) != hipSuccess || !graph) return DMATH_ERR_DEVICE;
+    hipGraphExec_t exec = nullptr;
+    hipError_t e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(graph);
+    if (e != hipSuccess || !exec) return DMATH_ERR_DEVICE;
+    *pipeline_id = ctx->next_pipeline++;
+    ctx->pipelines[*pipeline_id] = exec;
+    return DMATH_OK;
+}
+
+dmath_status_t dmath_pipeline_replay(dmath_ctx_t ctx, int32_t pipeline_id)
+{
+    if (!ctx || ctx->recording) return DMATH_ERR_INVALID_ARG;
+    auto it = ctx->pipelines.find(pipeline_id);
+    if (it == ctx->pipelines.end()) return DMATH_ERR_INVALID_ARG;
+    return hipGraphLaunch(it->second, ctx->stream) == hipSuccess ? DMATH_OK : DMATH_ERR_DEVICE;
+}
+
+dmath_status_t dmath_pipeline_destroy(dmath_ctx_t ctx, int32_t pipeline_id)
+{
+    if (!ctx) return DMATH_ERR_INVALID_ARG;
+    auto it = ctx->pipelines.find(pipeline_id);
+    if (it == ctx->pipelines.end()) return DMATH_ERR_INVALID_ARG;
+    (void)hipGraphExecDestroy(it->second);
+    ctx->pipelines.erase(it);
+    return DMATH_OK;
+}
+
 dmath_status_t dmath_set_kernel_policy(dmath_ctx_t ctx, int32_t policy)
 {
     if (!ctx || policy < 0 || policy > 1) return DMATH_ERR_INVALID_ARG;
+    if (ctx->recording) return DMATH_ERR_UNSUPPORTED;
     ctx->policy = policy;
     drop_all_plans(ctx);
     return DMATH_OK;

@@ -95,6 +95,9 @@ struct dmath_ctx_s {
     std::set<dmath_matrix_s*> matrices;
     std::map<dm::GemmKey, std::unique_ptr<dm::GemmPlan>> gemm_plans;
     std::map<dm::ConvKey, std::unique_ptr<dm::ConvPlan>> conv_plans;
+    bool recording = false;                      // between dmath_pipeline_begin and _end
+    std::map<int32_t, hipGraphExec_t> pipelines;  // recorded sequences
+    int32_t next_pipeline = 1;
     dmath_ctx_s(void* slab, size_t bytes, hipStream_t s) : pool(slab, bytes), stream(s) {}
 };
 

@@ -138,6 +138,7 @@ dmath_status_t get_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_mat
         return DMATH_OK;
     }
     if (was_cached) *was_cached = false;
+    if (do_upload && ctx->recording) return DMATH_ERR_UNSUPPORTED;  // uploading synchronises
     if (found != ctx->gemm_plans.end()) ctx->gemm_plans.erase(found);  // described, never uploaded
 
     const int64_t M = C->rows, N = C->cols, K = transA ? A->rows : A->cols;
@@ -333,6 +334,7 @@ dmath_status_t get_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t
         *out = found->second.get();
         return DMATH_OK;
     }
+    if (ctx->recording) return DMATH_ERR_UNSUPPORTED;  // building a plan synchronises
     auto plan = std::make_unique<ConvPlan>();
     plan->uses = {X->id, F->id, Y->id};
     ConvTables& t = plan->t;

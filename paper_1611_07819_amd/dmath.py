@@ -89,6 +89,10 @@ def load_library(build_if_missing: bool = True):
         "dmath_conv_bwd_filter": [vp, P(_ConvDesc), dbl, vp, vp, dbl, vp],
         "dmath_conv_bwd_data": [vp, P(_ConvDesc), dbl, vp, vp, dbl, vp],
         "dmath_set_kernel_policy": [vp, i32],
+        "dmath_pipeline_begin": [vp],
+        "dmath_pipeline_end": [vp, P(i32)],
+        "dmath_pipeline_replay": [vp, i32],
+        "dmath_pipeline_destroy": [vp, i32],
         "dmath_synchronize": [vp],
         "dmath_mfma_peak_probe": [vp, ctypes.c_int, i32, P(dbl)],
         "dmath_pool_stats": [vp, P(sz), P(sz), P(sz)],
@@ -146,6 +150,20 @@ class Context:
         _check(self._lib.dmath_mfma_peak_probe(self._h, dtype, iters, ctypes.byref(f)),
                "dmath_mfma_peak_probe")
         return f.value
+
+    def pipeline_begin(self):
+        _check(self._lib.dmath_pipeline_begin(self._h), "dmath_pipeline_begin")
+
+    def pipeline_end(self) -> int:
+        pid = ctypes.c_int32()
+        _check(self._lib.dmath_pipeline_end(self._h, ctypes.byref(pid)), "dmath_pipeline_end")
+        return pid.value
+
+    def pipeline_replay(self, pid: int):
+        _check(self._lib.dmath_pipeline_replay(self._h, pid), "dmath_pipeline_replay")
+
+    def pipeline_destroy(self, pid: int):
+        _check(self._lib.dmath_pipeline_destroy(self._h, pid), "dmath_pipeline_destroy")
 
     def synchronize(self):
         _check(self._lib.dmath_synchronize(self._h), "dmath_synchronize")

@@ -1,0 +1,92 @@
+"""Pipeline record / replay (paper section 3.3: a fixed forward+backward sequence is remembered
+and re-issued through one identifier): every replay must equal the eager result for the
+contents the matrices hold at replay time."""
+import numpy as np
+import pytest
+
+import paper_1611_07819_amd as dm
+from gpu_util import TOL, rel_fro
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    import torch
+    stream = torch.cuda.Stream()          # capture needs a non-default stream (default priority)
+    slab = torch.empty(2 << 30, dtype=torch.uint8, device="cuda:0")
+    torch.cuda.synchronize()
+    c = dm.Context(slab, stream=stream.cuda_stream)
+    yield c
+    c.close()
+
+
+def test_replay_equals_eager_on_current_contents(ctx, oracle):
+    r = np.random.default_rng(800)
+    b, i, o = 512, 1024, 768
+    X = r.uniform(0, 1, (b, i)).astype(np.float16)
+    W = r.normal(0, 1 / 32, (i, o)).astype(np.float16)
+    dY = r.normal(0, 0.1, (b, o)).astype(np.float16)
+    g = (2, 2)
+    dX_, dW_, ddY = ctx.from_host(X, g), ctx.from_host(W, g), ctx.from_host(dY, g)
+    Y, gW, gX = ctx.matrix(b, o, g, dm.F32), ctx.matrix(i, o, g, dm.F32), ctx.matrix(b, i, g, dm.F32)
+    # a small convolution rides along in the same pipeline
+    geo = dict(n=4, c=128, h=16, w=16, k=256, r=3, s=3, pad_h=1, pad_w=1)
+    cd = dm.ConvDesc(**geo)
+    cx = r.uniform(0, 1, (4, 128 * 256)).astype(np.float16)
+    cf = r.normal(0, 0.05, (256, 128 * 9)).astype(np.float16)
+    dcx, dcf = ctx.from_host(cx), ctx.from_host(cf)
+    dcy = ctx.matrix(4, 256 * 256, (1, 1), dm.F32)
+
+    def step():
+        dm.gemm(ctx, 0, 0, 1.0, dX_, dW_, 0.0, Y)
+        dm.gemm(ctx, 1, 0, 1.0, dX_, ddY, 0.0, gW)
+        dm.gemm(ctx, 0, 1, 1.0, ddY, dW_, 0.0, gX)
+        dm.conv_fwd(ctx, cd, 1.0, dcx, dcf, 0.0, dcy)
+
+    def outputs():
+        return [m.get() for m in (Y, gW, gX, dcy)]
+
+    step()                                   # eager: builds the plans
+    eager0 = outputs()
+    ctx.pipeline_begin()
+    with pytest.raises(dm.DmathError) as e:  # not allowed while recording
+        dX_.set(X)
+    assert e.value.code == 7
+    step()
+    pid = ctx.pipeline_end()
+    for rep in range(3):
+        # new contents each time, eager work and synchronisation between the replays
+        X2 = r.uniform(0, 1, (b, i)).astype(np.float16)
+        cx2 = r.uniform(0, 1, cx.shape).astype(np.float16)
+        dX_.set(X2)
+        dcx.set(cx2)
+        for m in (Y, gW, gX, dcy):
+            m.set(np.full((m.rows, m.cols), np.nan, np.float32))
+        ctx.pipeline_replay(pid)
+        replayed = outputs()
+        step()
+        eager = outputs()
+        for a, bb in zip(replayed, eager):
+            assert np.array_equal(a, bb)     # same kernels, same order: bitwise
+        assert rel_fro(replayed[0], oracle.gemm(False, False, 1.0, X2, W, 0.0)) <= TOL[dm.F16]
+        assert rel_fro(replayed[3], oracle.conv_fwd(oracle.ConvDesc(**geo), 1.0, cx2, cf)) <= TOL[dm.F16]
+    assert not np.array_equal(eager0[0], replayed[0])
+    ctx.pipeline_destroy(pid)
+    with pytest.raises(dm.DmathError):
+        ctx.pipeline_replay(pid)
+
+
+def test_recording_an_operation_without_a_plan_is_refused(ctx):
+    A = ctx.from_host(np.ones((128, 128), np.float32))
+    B = ctx.from_host(np.ones((128, 128), np.float32))
+    C = ctx.matrix(128, 128, (1, 1), dm.F32)
+    ctx.pipeline_begin()
+    with pytest.raises(dm.DmathError) as e:
+        dm.gemm(ctx, 0, 0, 1.0, A, B, 0.0, C)    # never run eagerly: no plan
+    assert e.value.code == 7
+    pid = ctx.pipeline_end()                       # an empty pipeline is fine
+    ctx.pipeline_replay(pid)
+    ctx.pipeline_destroy(pid)
+    dm.gemm(ctx, 0, 0, 1.0, A, B, 0.0, C)
+    assert np.array_equal(C.get(), np.full((128, 128), 128, np.float32))

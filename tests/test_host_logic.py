@@ -174,3 +174,22 @@ def test_conv_argument_checks(ctx):
     assert code(lambda: dm.conv_fwd(ctx, dm.ConvDesc(4, 3, 8, 8, 5, 3, 3, 1, 1, 0, 1), 1.0, X, F, 0.0, Y)) == 1
     assert code(lambda: dm.conv_fwd(ctx, dm.ConvDesc(4, 3, 2, 2, 5, 5, 5), 1.0, X, F, 0.0, Y)) == 2
     assert code(lambda: dm.conv_bwd_filter(ctx, d, 1.0, X, X, 0.0, F)) in (2, 5)
+
+
+def test_pipeline_calls_without_a_capturable_stream(ctx):
+    # the fixture's context uses the default stream, which cannot be captured
+    with pytest.raises(dm.DmathError) as e:
+        ctx.pipeline_begin()
+    assert e.value.code == 7
+    with pytest.raises(dm.DmathError) as e:
+        ctx.pipeline_end()
+    assert e.value.code == 1
+    with pytest.raises(dm.DmathError) as e:
+        ctx.pipeline_replay(3)
+    assert e.value.code == 1
+
+
+def test_size_limits(ctx):
+    with pytest.raises(dm.DmathError) as e:
+        ctx.matrix(1 << 31, 1, (1, 1), dm.F16)
+    assert e.value.code == 7
