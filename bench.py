@@ -45,8 +45,12 @@ def main():
     dm.load_library()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    stream = torch.cuda.current_stream()
+    # one dedicated stream (default priority) for every launch and every timing event; a
+    # non-default stream is also what pipeline recording needs
+    stream = torch.cuda.Stream()
+    torch.cuda.set_stream(stream)
     slab = torch.empty(8 << 30, dtype=torch.uint8, device="cuda:0")
+    torch.cuda.synchronize()
     ctx = dm.Context(slab, stream=stream.cuda_stream)
 
     def time_calls(fns, steps, warmup):
@@ -105,7 +109,28 @@ def main():
                                             "frac_peak": round(fl / ms / 1e9 / PEAK_TFLOPS[dtype_key], 4)}
             for m in d.values():
                 m.destroy()
+        def bench_step(wl, tag, dtype_key):
+            """Whole forward+backward step of a configuration, issued call by call and as one
+            recorded pipeline replay."""
+            d = {k: ctx.from_host(v, wl.grid) for k, v in wl.mats.items()}
+            fl = sum(2.0 * np.prod(c.mnk(wl.mats)) for c in wl.calls)
+
+            def step():
+                for c in wl.calls:
+                    dm.gemm(ctx, int(c.transA), int(c.transB), c.alpha, d[c.a], d[c.b], c.beta, d[c.c])
+            step()
+            ctx.pipeline_begin()
+            step()
+            pid = ctx.pipeline_end()
+            for name, f in (("step_eager", step), ("step_replay", lambda: ctx.pipeline_replay(pid))):
+                ms, _ = time_calls([f], 20, 5)
+                calls[f"{tag}.{name}"] = {"ms": round(ms, 4), "tflops": round(fl / ms / 1e9, 2),
+                                          "frac_peak": round(fl / ms / 1e9 / PEAK_TFLOPS[dtype_key], 4)}
+            ctx.pipeline_destroy(pid)
+            for m in d.values():
+                m.destroy()
         bench_workload(synth.config1(), "cfg1", "f32")
+        bench_step(synth.config3("f32"), "cfg3_f32out", "f16")
         bench_workload(synth.config3("f32"), "cfg3_f32out", "f16")
         bench_workload(synth.config3("f16"), "cfg3_f16out", "f16")
         bench_workload(synth.config4(), "cfg4", "f64")
@@ -113,9 +138,11 @@ def main():
         d5 = {k: ctx.from_host(v) for k, v in w5.mats.items()}
         desc = dm.ConvDesc(**w5.conv)
         fl5 = 2.0 * 50176 * 256 * 2304
+        d5["dX"] = ctx.matrix(d5["X"].rows, d5["X"].cols, (1, 1), dm.F32)
         for name, f in [("fwd", lambda: dm.conv_fwd(ctx, desc, 1.0, d5["X"], d5["F"], 0.0, d5["Y"])),
-                        ("bwd_filter", lambda: dm.conv_bwd_filter(ctx, desc, 1.0, d5["X"], d5["dY"], 0.0, d5["dF"]))]:
-            ms, _ = time_calls([f], 5, 2)
+                        ("bwd_filter", lambda: dm.conv_bwd_filter(ctx, desc, 1.0, d5["X"], d5["dY"], 0.0, d5["dF"])),
+                        ("bwd_data", lambda: dm.conv_bwd_data(ctx, desc, 1.0, d5["dY"], d5["F"], 0.0, d5["dX"]))]:
+            ms, _ = time_calls([f], 10, 3)
             calls[f"cfg5.{name}"] = {"ms": round(ms, 4), "tflops": round(fl5 / ms / 1e9, 2),
                                      "frac_peak": round(fl5 / ms / 1e9 / PEAK_TFLOPS["f16"], 4)}
         for m in d5.values():

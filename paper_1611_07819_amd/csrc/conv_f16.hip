@@ -146,7 +146,7 @@ template <int BM, int BN> struct FwdWalk {
             TA::lane_slot(q, wave, lane, row, chunk);
             aoff[q] = pixel_offset(p, m0 + row) + chunk * 16;
         }
-        TB::offsets((int64_t)p.g.c * p.g.r * p.g.s, n0, wave, lane, boff);
+        TB::offsets((int64_t)p.g.c * p.g.r * p.g.s, n0, BN, wave, lane, boff);
     }
     __device__ __forceinline__ void advance()
     {
@@ -240,7 +240,7 @@ template <int BM, int BN> struct WgradWalk {
         oh = p.g.oh; ow = p.g.ow; hp = p.hp; wp = p.wp; c = p.g.c;
         d_oy = BK / ow; d_ox = BK % ow;
         // A' = Yt[m][k]: dense, m/n (= k_out) unit-stride, all of k_out in the tile
-        TA::offsets(p.g.k, 0, wave, lane, aoff);
+        TA::offsets(p.g.k, 0, BM, wave, lane, aoff);
         astep = TA::step(p.g.k);
         abase = reinterpret_cast<const char*>(p.yt) + (int64_t)k0_pixels * p.g.k * 2;
         // B' columns n0 .. n0+BN of (r, s, c): one tap, BN consecutive channels

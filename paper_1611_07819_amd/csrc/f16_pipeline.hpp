@@ -84,8 +84,12 @@ template <int BMN, bool KC> struct OperandTile {
         chunk = KC ? (cpos ^ swz(row)) : (cpos ^ ((row & 3) << 2));
     }
 
-    // byte offsets (relative to the panel origin) for a dense panel with leading dimension ld
-    __device__ __forceinline__ static void offsets(int64_t ld, int mn0, int wave, int lane,
+    // byte offsets (relative to the panel origin) for a dense panel with leading dimension ld.
+    // Only `len` (<= BMN) rows/columns of the tile exist (ragged last tile of a segment): loads
+    // for the rest are redirected to the last existing row / 16-byte chunk, so every address
+    // stays inside the operand; what they bring in only reaches accumulators that the
+    // epilogue does not store.
+    __device__ __forceinline__ static void offsets(int64_t ld, int mn0, int len, int wave, int lane,
                                                    uint32_t (&off)[kInstr])
     {
 #pragma unroll
@@ -93,9 +97,9 @@ template <int BMN, bool KC> struct OperandTile {
             int row, chunk;
             lane_slot(q, wave, lane, row, chunk);
             if (KC)
-                off[q] = (uint32_t)((((int64_t)(mn0 + row)) * ld + chunk * 8) * 2);
+                off[q] = (uint32_t)((((int64_t)(mn0 + min(row, len - 1))) * ld + chunk * 8) * 2);
             else
-                off[q] = (uint32_t)(((int64_t)row * ld + mn0 + chunk * 8) * 2);
+                off[q] = (uint32_t)(((int64_t)row * ld + mn0 + min(chunk, (len - 1) >> 3) * 8) * 2);
         }
     }
     // bytes a dense panel pointer advances per k-tile

@@ -6,7 +6,7 @@
 // column (paper section 2.1) are walked by the loader below and multiplied by the shared
 // pipeline of f16_pipeline.hpp (direct global->LDS loads, LDS ring, pinned MFMA schedule).
 //
-// Preconditions (checked by the chooser): full tiles, k-segments multiples of 64, 16-byte
+// Preconditions (checked by the chooser): k-segments multiples of 64, 16-byte
 // aligned panel origins and leading dimensions, blocks smaller than 4 GiB.
 #include <hip/hip_runtime.h>
 
@@ -44,8 +44,8 @@ template <int BM, int BN, bool AKC, bool BKC> struct PanelWalk {
         kleft = t.klen[ks] / BK;
         abase = static_cast<const char*>(pa.ptr);
         bbase = static_cast<const char*>(pb.ptr);
-        TA::offsets(pa.ld, tile.m_off, wave, lane, aoff);
-        TB::offsets(pb.ld, tile.n_off, wave, lane, boff);
+        TA::offsets(pa.ld, tile.m_off, tile.m_len, wave, lane, aoff);
+        TB::offsets(pb.ld, tile.n_off, tile.n_len, wave, lane, boff);
     }
     __device__ __forceinline__ void advance()
     {
@@ -92,9 +92,10 @@ __global__ __launch_bounds__(NT) void gemm_f16_kernel(GemmTables t, float alpha,
             for (int j = 0; j < NTL; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int row = tile.m_glob + wm * WM + i * 32 + acc32_row(lane, r);
-                    const int col = tile.n_glob + wn * WN + j * 32 + l32;
-                    ws[(int64_t)row * t.N + col] = acc[i][j][r];
+                    const int row = wm * WM + i * 32 + acc32_row(lane, r);
+                    const int col = wn * WN + j * 32 + l32;
+                    if (row < tile.m_len && col < tile.n_len)
+                        ws[(int64_t)(tile.m_glob + row) * t.N + tile.n_glob + col] = acc[i][j][r];
                 }
         return;
     }
@@ -108,9 +109,10 @@ __global__ __launch_bounds__(NT) void gemm_f16_kernel(GemmTables t, float alpha,
         for (int j = 0; j < NTL; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int row = tile.m_off + wm * WM + i * 32 + acc32_row(lane, r);
-                const int col = tile.n_off + wn * WN + j * 32 + l32;
-                TC* p = c + (int64_t)row * pc.ld + col;
+                const int row = wm * WM + i * 32 + acc32_row(lane, r);
+                const int col = wn * WN + j * 32 + l32;
+                if (row >= tile.m_len || col >= tile.n_len) continue;  // ragged last tile
+                TC* p = c + (int64_t)(tile.m_off + row) * pc.ld + tile.n_off + col;
                 float v = alpha * acc[i][j][r];
                 if (beta != 0.f) v += beta * (float)*p;
                 *p = to_out<TC>(v);

@@ -17,7 +17,7 @@
 // Inside a group of 8 k the order is permuted identically for A and B (lanes 0-31 supply
 // k = 8u+j, lanes 32-63 k = 8u+4+j at step j), which the sum over k does not notice.
 //
-// Preconditions (checked by the chooser): full tiles, k-segments multiples of 32, 16-byte
+// Preconditions (checked by the chooser): k-segments multiples of 32, 16-byte
 // aligned panel origins and leading dimensions, blocks smaller than 4 GiB.
 #include <hip/hip_runtime.h>
 
@@ -67,7 +67,10 @@ template <int BMN, bool KC> struct OperandTile {
     static constexpr int kReadsPerFrag = KC ? 1 : 4;
 
     // byte offsets (relative to the panel origin) of the chunks this lane fetches at k-tile 0
-    __device__ __forceinline__ static void offsets(int64_t ld, int mn0, int wave, int lane,
+    // Only `len` (<= BMN) rows/columns of the tile exist (ragged last tile): loads for the rest are
+    // redirected to the last existing row / 16-byte chunk, so every address stays inside the
+    // operand; what they bring in only reaches accumulators that the epilogue does not store.
+    __device__ __forceinline__ static void offsets(int64_t ld, int mn0, int len, int wave, int lane,
                                                    uint32_t (&off)[kInstr])
     {
 #pragma unroll
@@ -76,9 +79,9 @@ template <int BMN, bool KC> struct OperandTile {
             const int row = seg * kRowsPerSeg + lane / kChunksPerRow;
             const int cpos = lane % kChunksPerRow;
             if (KC)
-                off[q] = (uint32_t)((((int64_t)(mn0 + row)) * ld + (cpos ^ swz(row)) * 4) * 4);
+                off[q] = (uint32_t)((((int64_t)(mn0 + min(row, len - 1))) * ld + (cpos ^ swz(row)) * 4) * 4);
             else
-                off[q] = (uint32_t)(((int64_t)row * ld + mn0 + cpos * 4) * 4);
+                off[q] = (uint32_t)(((int64_t)row * ld + mn0 + min(cpos, (len - 1) >> 2) * 4) * 4);
         }
     }
     __device__ __forceinline__ static int64_t step(int64_t ld) { return KC ? BK * 4 : BK * 4 * ld; }
@@ -143,8 +146,8 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmTables t, float alpha,
     const char* abase = static_cast<const char*>(pa.ptr);
     const char* bbase = static_cast<const char*>(pb.ptr);
     uint32_t aoff[TA::kInstr], boff[TB::kInstr];
-    TA::offsets(pa.ld, tile.m_off, wave, lane, aoff);
-    TB::offsets(pb.ld, tile.n_off, wave, lane, boff);
+    TA::offsets(pa.ld, tile.m_off, tile.m_len, wave, lane, aoff);
+    TB::offsets(pb.ld, tile.n_off, tile.n_len, wave, lane, boff);
 
     auto issue_one = [&](uint32_t sbase, const char* ab, const char* bb, int idx) {
         if (idx < TA::kInstr)
@@ -162,8 +165,8 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmTables t, float alpha,
             kleft = t.klen[ks] / BK;
             abase = static_cast<const char*>(pa.ptr);
             bbase = static_cast<const char*>(pb.ptr);
-            TA::offsets(pa.ld, tile.m_off, wave, lane, aoff);
-            TB::offsets(pb.ld, tile.n_off, wave, lane, boff);
+            TA::offsets(pa.ld, tile.m_off, tile.m_len, wave, lane, aoff);
+            TB::offsets(pb.ld, tile.n_off, tile.n_len, wave, lane, boff);
         }
     };
     auto issue_all = [&](int stage) {
@@ -269,9 +272,10 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmTables t, float alpha,
             for (int j = 0; j < NTL; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int row = tile.m_glob + wm * WM + i * 32 + acc32_row(lane, r);
-                    const int col = tile.n_glob + wn * WN + j * 32 + l32;
-                    ws[(int64_t)row * t.N + col] = acc[i][j][r];
+                    const int row = wm * WM + i * 32 + acc32_row(lane, r);
+                    const int col = wn * WN + j * 32 + l32;
+                    if (row < tile.m_len && col < tile.n_len)
+                        ws[(int64_t)(tile.m_glob + row) * t.N + tile.n_glob + col] = acc[i][j][r];
                 }
         return;
     }
@@ -284,9 +288,10 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmTables t, float alpha,
         for (int j = 0; j < NTL; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int row = tile.m_off + wm * WM + i * 32 + acc32_row(lane, r);
-                const int col = tile.n_off + wn * WN + j * 32 + l32;
-                float* p = c + (int64_t)row * pc.ld + col;
+                const int row = wm * WM + i * 32 + acc32_row(lane, r);
+                const int col = wn * WN + j * 32 + l32;
+                if (row >= tile.m_len || col >= tile.n_len) continue;  // ragged last tile
+                float* p = c + (int64_t)(tile.m_off + row) * pc.ld + tile.n_off + col;
                 float v = alpha * acc[i][j][r];
                 if (beta != 0.f) v += beta * *p;
                 *p = v;

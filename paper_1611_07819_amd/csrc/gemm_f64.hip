@@ -17,7 +17,7 @@
 // Inside a group of 8 k the order is permuted identically for A and B: lane group g = lane/16
 // supplies k = 8u + 2g + j at step j of group u.
 //
-// Preconditions (checked by the chooser): full tiles, k-segments multiples of 16, 16-byte
+// Preconditions (checked by the chooser): k-segments multiples of 16, 16-byte
 // aligned panel origins and leading dimensions, blocks smaller than 4 GiB.
 #include <hip/hip_runtime.h>
 
@@ -68,7 +68,10 @@ template <int BMN, bool KC> struct OperandTile {
     static constexpr int kReadsPerFrag = KC ? 1 : 2;
 
     // byte offsets (relative to the panel origin) of the chunks this lane fetches at k-tile 0
-    __device__ __forceinline__ static void offsets(int64_t ld, int mn0, int wave, int lane,
+    // Only `len` (<= BMN) rows/columns of the tile exist (ragged last tile): loads for the rest are
+    // redirected to the last existing row / 16-byte chunk, so every address stays inside the
+    // operand; what they bring in only reaches accumulators that the epilogue does not store.
+    __device__ __forceinline__ static void offsets(int64_t ld, int mn0, int len, int wave, int lane,
                                                    uint32_t (&off)[kInstr])
     {
 #pragma unroll
@@ -77,9 +80,9 @@ template <int BMN, bool KC> struct OperandTile {
             const int row = seg * kRowsPerSeg + lane / kChunksPerRow;
             const int cpos = lane % kChunksPerRow;
             if (KC)
-                off[q] = (uint32_t)((((int64_t)(mn0 + row)) * ld + (cpos ^ swz(row)) * 2) * 8);
+                off[q] = (uint32_t)((((int64_t)(mn0 + min(row, len - 1))) * ld + (cpos ^ swz(row)) * 2) * 8);
             else
-                off[q] = (uint32_t)(((int64_t)row * ld + mn0 + cpos * 2) * 8);
+                off[q] = (uint32_t)(((int64_t)row * ld + mn0 + min(cpos, (len - 1) >> 1) * 2) * 8);
         }
     }
     __device__ __forceinline__ static int64_t step(int64_t ld) { return KC ? BK * 8 : BK * 8 * ld; }
@@ -144,8 +147,8 @@ __global__ __launch_bounds__(NT) void gemm_f64_kernel(GemmTables t, double alpha
     const char* abase = static_cast<const char*>(pa.ptr);
     const char* bbase = static_cast<const char*>(pb.ptr);
     uint32_t aoff[TA::kInstr], boff[TB::kInstr];
-    TA::offsets(pa.ld, tile.m_off, wave, lane, aoff);
-    TB::offsets(pb.ld, tile.n_off, wave, lane, boff);
+    TA::offsets(pa.ld, tile.m_off, tile.m_len, wave, lane, aoff);
+    TB::offsets(pb.ld, tile.n_off, tile.n_len, wave, lane, boff);
 
     auto issue_one = [&](uint32_t sbase, const char* ab, const char* bb, int idx) {
         if (idx < TA::kInstr)
@@ -163,8 +166,8 @@ __global__ __launch_bounds__(NT) void gemm_f64_kernel(GemmTables t, double alpha
             kleft = t.klen[ks] / BK;
             abase = static_cast<const char*>(pa.ptr);
             bbase = static_cast<const char*>(pb.ptr);
-            TA::offsets(pa.ld, tile.m_off, wave, lane, aoff);
-            TB::offsets(pb.ld, tile.n_off, wave, lane, boff);
+            TA::offsets(pa.ld, tile.m_off, tile.m_len, wave, lane, aoff);
+            TB::offsets(pb.ld, tile.n_off, tile.n_len, wave, lane, boff);
         }
     };
     auto issue_all = [&](int stage) {
@@ -270,9 +273,10 @@ __global__ __launch_bounds__(NT) void gemm_f64_kernel(GemmTables t, double alpha
             for (int j = 0; j < NTL; ++j)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int row = tile.m_glob + wm * WM + i * 16 + acc16d_row(lane, r);
-                    const int col = tile.n_glob + wn * WN + j * 16 + l32;
-                    ws[(int64_t)row * t.N + col] = acc[i][j][r];
+                    const int row = wm * WM + i * 16 + acc16d_row(lane, r);
+                    const int col = wn * WN + j * 16 + l32;
+                    if (row < tile.m_len && col < tile.n_len)
+                        ws[(int64_t)(tile.m_glob + row) * t.N + tile.n_glob + col] = acc[i][j][r];
                 }
         return;
     }
@@ -285,9 +289,10 @@ __global__ __launch_bounds__(NT) void gemm_f64_kernel(GemmTables t, double alpha
         for (int j = 0; j < NTL; ++j)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int row = tile.m_off + wm * WM + i * 16 + acc16d_row(lane, r);
-                const int col = tile.n_off + wn * WN + j * 16 + l32;
-                double* p = c + (int64_t)row * pc.ld + col;
+                const int row = wm * WM + i * 16 + acc16d_row(lane, r);
+                const int col = wn * WN + j * 16 + l32;
+                if (row >= tile.m_len || col >= tile.n_len) continue;  // ragged last tile
+                double* p = c + (int64_t)(tile.m_off + row) * pc.ld + tile.n_off + col;
                 double v = alpha * acc[i][j][r];
                 if (beta != 0.0) v += beta * *p;
                 *p = v;

@@ -76,8 +76,7 @@ GemmChoice choose_gemm(const SegView& v)
         for (auto& s : shapes) {
             if (forced && (s.bm != ebm || s.bn != ebn)) continue;
             if ((s.needs_b_kcontig && !v.b_kcontig) || (s.f32_only && !f32)) continue;
-            if (!all_multiple(*v.mlen, s.bm) || !all_multiple(*v.nlen, s.bn)) continue;
-            int64_t tiles = count_tiles(v, s.bm, s.bn);
+            int64_t tiles = count_tiles(v, s.bm, s.bn);  // ragged last tiles count as whole ones
             double cost = (double)((tiles + kCUs - 1) / kCUs) * s.bm * s.bn;
             if (f32 && s.bm * s.bn < 128 * 128) cost *= 1.03;
             if (f64 && s.bm * s.bn >= 128 * 128) cost *= 1.03;
@@ -99,7 +98,6 @@ GemmChoice choose_gemm(const SegView& v)
         const bool forced = env_tile(&ebm, &ebn);
         for (auto& s : shapes) {
             if (forced && (s[0] != ebm || s[1] != ebn)) continue;
-            if (!all_multiple(*v.mlen, s[0]) || !all_multiple(*v.nlen, s[1])) continue;
             int64_t tiles = count_tiles(v, s[0], s[1]);
             int64_t cost = ((tiles + kCUs - 1) / kCUs) * s[0] * s[1];
             if (best_cost < 0 || cost < best_cost) {

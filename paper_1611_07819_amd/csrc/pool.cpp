@@ -10,7 +10,9 @@ Pool::Pool(void* base, size_t bytes)
     uintptr_t aligned = round_up(b, kAlign);
     size_t lost = aligned - b;
     base_ = aligned;
-    cap_ = bytes > lost ? (bytes - lost) / kAlign * kAlign : 0;
+    // the last kAlign bytes of the slab are never handed out: a 16-byte load that starts inside
+    // the last allocation may run a few bytes past its end and must still hit owned memory
+    cap_ = bytes > lost + kAlign ? (bytes - lost - kAlign) / kAlign * kAlign : 0;
     if (cap_) free_[0] = cap_;
 }
 

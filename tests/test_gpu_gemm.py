@@ -341,3 +341,37 @@ def test_specialised_kernels_with_split_k(ctx, oracle, dt, out, ta, tb):
     assert np.array_equal(outs[0], outs[1])
     for m in (dA, dB):
         m.destroy()
+
+
+@pytest.mark.parametrize("dt,out", [(dm.F64, dm.F64), (dm.F32, dm.F32), (dm.F16, dm.F32), (dm.F16, dm.F16)])
+@pytest.mark.parametrize("ta,tb", OPS)
+def test_specialised_kernels_on_ragged_tiles(ctx, oracle, dt, out, ta, tb):
+    """M and N that are not multiples of any tile (but keep 16-byte alignment), K a multiple of the
+    k-step: the specialised kernels run with a ragged last tile row/column.  Integer inputs:
+    bit for bit; NaN-filled C with beta = 0 must not leak; neighbours of C must stay untouched."""
+    r = np.random.default_rng(900)
+    M, N, K = 152, 200, 192
+    opA = r.integers(-2, 3, (M, K)).astype(NP[dt])
+    opB = r.integers(-2, 3, (K, N)).astype(NP[dt])
+    C0 = r.integers(-3, 4, (M, N)).astype(NP[out])
+    ctx.set_kernel_policy(0)
+    for grids in [((1, 1), (1, 1), (1, 1)), ((1, 3), (3, 1), (1, 1))]:
+        ga, gb, gc = grids
+        ga = ga[::-1] if ta else ga
+        gb = gb[::-1] if tb else gb
+        dA, dB, dC = ctx.from_host(stored(opA, ta), ga), ctx.from_host(stored(opB, tb), gb), ctx.from_host(C0, gc)
+        guard = ctx.from_host(np.full((4, 64), 7, NP[out]))          # allocated right after C
+        info = dm.gemm_plan_info(ctx, ta, tb, dA, dB, dC)
+        assert info["kernel"] != 0, grids
+        dm.gemm(ctx, ta, tb, 2.0, dA, dB, 1.0, dC)
+        got = dC.get().astype(np.float64)
+        ref = oracle.gemm(bool(ta), bool(tb), 2.0, oracle.BlockMatrix(stored(opA, ta), ga),
+                          oracle.BlockMatrix(stored(opB, tb), gb), 1.0, oracle.BlockMatrix(C0, gc))
+        assert np.array_equal(got, ref), grids
+        dC.set(np.full((M, N), np.nan, NP[out]))
+        dm.gemm(ctx, ta, tb, 1.0, dA, dB, 0.0, dC)
+        ref0 = oracle.gemm(bool(ta), bool(tb), 1.0, stored(opA, ta), stored(opB, tb), 0.0)
+        assert np.array_equal(dC.get().astype(np.float64), ref0), grids
+        assert np.array_equal(guard.get(), np.full((4, 64), 7, NP[out]))
+        for m in (dA, dB, dC, guard):
+            m.destroy()
