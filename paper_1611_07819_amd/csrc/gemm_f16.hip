@@ -10,6 +10,8 @@
 // aligned panel origins and leading dimensions, blocks smaller than 4 GiB.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "context.hpp"
 #include "f16_pipeline.hpp"
 
@@ -103,20 +105,26 @@ __global__ __launch_bounds__(NT) void gemm_f16_kernel(GemmTables t, float alpha,
     // epilogue: register r of a 32x32 result tile holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
     const Panel pc = t.c[tile.mseg * t.n_nseg + tile.nseg];
     TC* c = static_cast<TC*>(const_cast<void*>(pc.ptr));
+    // full tiles (the common case) store unmasked; a ragged last tile masks every element
+    auto store = [&](auto ragged) {
 #pragma unroll
-    for (int i = 0; i < MT; ++i)
+        for (int i = 0; i < MT; ++i)
 #pragma unroll
-        for (int j = 0; j < NTL; ++j)
+            for (int j = 0; j < NTL; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = wm * WM + i * 32 + acc32_row(lane, r);
-                const int col = wn * WN + j * 32 + l32;
-                if (row >= tile.m_len || col >= tile.n_len) continue;  // ragged last tile
-                TC* p = c + (int64_t)(tile.m_off + row) * pc.ld + tile.n_off + col;
-                float v = alpha * acc[i][j][r];
-                if (beta != 0.f) v += beta * (float)*p;
-                *p = to_out<TC>(v);
-            }
+                for (int r = 0; r < 16; ++r) {
+                    const int row = wm * WM + i * 32 + acc32_row(lane, r);
+                    const int col = wn * WN + j * 32 + l32;
+                    if constexpr (decltype(ragged)::value)
+                        if (row >= tile.m_len || col >= tile.n_len) continue;
+                    TC* p = c + (int64_t)(tile.m_off + row) * pc.ld + tile.n_off + col;
+                    float v = alpha * acc[i][j][r];
+                    if (beta != 0.f) v += beta * (float)*p;
+                    *p = to_out<TC>(v);
+                }
+    };
+    if (tile.m_len == BM && tile.n_len == BN) store(std::false_type{});
+    else store(std::true_type{});
 }
 
 template <int BM, int BN, int STAGES, bool AKC, bool BKC, class TC>

@@ -283,20 +283,26 @@ __global__ __launch_bounds__(NT) void gemm_f64_kernel(GemmTables t, double alpha
     // epilogue: register r of a 16x16 result tile holds row 4*r + lane/16, column lane%16
     const Panel pc = t.c[tile.mseg * t.n_nseg + tile.nseg];
     double* c = static_cast<double*>(const_cast<void*>(pc.ptr));
+    // full tiles (the common case) store unmasked; a ragged last tile masks every element
+    auto store = [&](auto ragged) {
 #pragma unroll
-    for (int i = 0; i < MT; ++i)
+        for (int i = 0; i < MT; ++i)
 #pragma unroll
-        for (int j = 0; j < NTL; ++j)
+            for (int j = 0; j < NTL; ++j)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int row = wm * WM + i * 16 + acc16d_row(lane, r);
-                const int col = wn * WN + j * 16 + l32;
-                if (row >= tile.m_len || col >= tile.n_len) continue;  // ragged last tile
-                double* p = c + (int64_t)(tile.m_off + row) * pc.ld + tile.n_off + col;
-                double v = alpha * acc[i][j][r];
-                if (beta != 0.0) v += beta * *p;
-                *p = v;
-            }
+                for (int r = 0; r < 4; ++r) {
+                    const int row = wm * WM + i * 16 + acc16d_row(lane, r);
+                    const int col = wn * WN + j * 16 + l32;
+                    if constexpr (decltype(ragged)::value)
+                        if (row >= tile.m_len || col >= tile.n_len) continue;
+                    double* p = c + (int64_t)(tile.m_off + row) * pc.ld + tile.n_off + col;
+                    double v = alpha * acc[i][j][r];
+                    if (beta != 0.0) v += beta * *p;
+                    *p = v;
+                }
+    };
+    if (tile.m_len == BM && tile.n_len == BN) store(std::false_type{});
+    else store(std::true_type{});
 }
 
 template <int BM, int BN, int WVM, bool AKC, bool BKC>
