@@ -139,12 +139,30 @@ def main():
         desc = dm.ConvDesc(**w5.conv)
         fl5 = 2.0 * 50176 * 256 * 2304
         d5["dX"] = ctx.matrix(d5["X"].rows, d5["X"].cols, (1, 1), dm.F32)
+        # per-call figures: every call re-lays-out its operands (no copy kept from the call
+        # before, which would take work out of the timed region)
+        ctx.set_relayout_reuse(False)
         for name, f in [("fwd", lambda: dm.conv_fwd(ctx, desc, 1.0, d5["X"], d5["F"], 0.0, d5["Y"])),
                         ("bwd_filter", lambda: dm.conv_bwd_filter(ctx, desc, 1.0, d5["X"], d5["dY"], 0.0, d5["dF"])),
                         ("bwd_data", lambda: dm.conv_bwd_data(ctx, desc, 1.0, d5["dY"], d5["F"], 0.0, d5["dX"]))]:
             ms, _ = time_calls([f], 10, 3)
             calls[f"cfg5.{name}"] = {"ms": round(ms, 4), "tflops": round(fl5 / ms / 1e9, 2),
                                      "frac_peak": round(fl5 / ms / 1e9 / PEAK_TFLOPS["f16"], 4)}
+        # one training step of the layer: new activations, new gradient and an updated filter
+        # arrive (declared with touch), then forward + weight gradient + data gradient; with
+        # copies kept, X is re-laid-out once for the two calls that read it
+        def step5():
+            for k in ("X", "dY", "F"):
+                d5[k].touch()
+            dm.conv_fwd(ctx, desc, 1.0, d5["X"], d5["F"], 0.0, d5["Y"])
+            dm.conv_bwd_filter(ctx, desc, 1.0, d5["X"], d5["dY"], 0.0, d5["dF"])
+            dm.conv_bwd_data(ctx, desc, 1.0, d5["dY"], d5["F"], 0.0, d5["dX"])
+        for name, keep in (("step_rewrite_all", False), ("step_copies_kept", True)):
+            ctx.set_relayout_reuse(keep)
+            ms, _ = time_calls([step5], 10, 3)
+            calls[f"cfg5.{name}"] = {"ms": round(ms, 4), "tflops": round(3 * fl5 / ms / 1e9, 2),
+                                     "frac_peak": round(3 * fl5 / ms / 1e9 / PEAK_TFLOPS["f16"], 4)}
+        ctx.set_relayout_reuse(True)
         for m in d5.values():
             m.destroy()
 

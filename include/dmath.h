@@ -195,12 +195,38 @@ dmath_status_t dmath_conv_bwd_data(dmath_ctx_t ctx, const dmath_conv_desc_t *des
  * because building a plan copies tables and synchronises: otherwise the call returns
  * DMATH_ERR_UNSUPPORTED (and recording continues).  dmath_matrix_set/get/reblock/create/destroy
  * are refused while recording (DMATH_ERR_UNSUPPORTED).  Destroying a matrix that a pipeline
- * uses invalidates the pipeline (the caller must not replay it).
+ * uses, or changing the kernel policy, destroys the pipeline: its identifier is then unknown
+ * (DMATH_ERR_INVALID_ARG from replay and destroy).
  */
 dmath_status_t dmath_pipeline_begin(dmath_ctx_t ctx);
 dmath_status_t dmath_pipeline_end(dmath_ctx_t ctx, int32_t *pipeline_id);
 dmath_status_t dmath_pipeline_replay(dmath_ctx_t ctx, int32_t pipeline_id);
 dmath_status_t dmath_pipeline_destroy(dmath_ctx_t ctx, int32_t pipeline_id);
+
+/*
+ * Re-layout copies that are kept (section 1: the cache of shared objects, "keep what you've
+ * seen", switched off where memory is the limit; section 3.3: data reorganised once for the
+ * operations that follow).  The specialised convolution kernels read channels-last copies of
+ * their activations and permuted copies of their filters, which live in the pool beside the
+ * matrices.  A copy is reused, and its rewrite skipped, while the matrix it was made from has not
+ * been written since: every library call that writes a matrix (set, reblock, the result of a
+ * gemm or convolution, a replayed pipeline) marks it changed.  The activations copied for the
+ * forward pass so serve the weight gradient of the same step, and a constant filter is permuted
+ * once.  Results are bit-identical with and without reuse.
+ *   dmath_set_relayout_reuse: 1 (default) reuse current copies, 0 rewrite them in every call
+ *                             (the memory held is the same: the kernels need the copies).
+ *   dmath_relayout_stats    : rewrites skipped / done so far, bytes of pool memory the copies hold.
+ *                             Any output pointer may be NULL.
+ *   dmath_matrix_touch      : declares that the matrix's elements changed without the library
+ *                             seeing it.  A matrix whose block pointers were handed out by
+ *                             dmath_matrix_block is treated as changed before every use.
+ * Nothing is reused across dmath_pipeline_begin / _end / _replay; inside one recording a copy
+ * made by a recorded call serves the recorded calls after it.
+ */
+dmath_status_t dmath_set_relayout_reuse(dmath_ctx_t ctx, int32_t enable);
+dmath_status_t dmath_relayout_stats(dmath_ctx_t ctx, uint64_t *reused, uint64_t *written,
+                                    size_t *bytes_held);
+dmath_status_t dmath_matrix_touch(dmath_matrix_t m);
 
 /* Kernel selection: 0 = automatic (specialised kernels where their preconditions hold),
  * 1 = always the guarded generic kernel (for testing and debugging).  Drops cached plans. */

@@ -38,6 +38,9 @@ dmath_status_t check_gemm(dmath_ctx_s* ctx, int ta, int tb, dmath_matrix_s* A, d
     return DMATH_OK;
 }
 
+// Every path that changes a matrix's elements ends here.
+void wrote(dmath_ctx_s*, dmath_matrix_s* m) { ++m->version; }
+
 dmath_status_t copy_blocks(dmath_matrix_s* m, void* host, int64_t ld, bool to_device)
 {
     if (!m || !host) return DMATH_ERR_INVALID_ARG;
@@ -55,6 +58,7 @@ dmath_status_t copy_blocks(dmath_matrix_s* m, void* host, int64_t ld, bool to_de
                                : hipMemcpy2DAsync(h, ld * es, d, c * es, c * es, r, hipMemcpyDeviceToHost, st);
             if (e != hipSuccess) return DMATH_ERR_DEVICE;
         }
+    if (to_device) wrote(m->ctx, m);
     return hipStreamSynchronize(st) == hipSuccess ? DMATH_OK : DMATH_ERR_DEVICE;
 }
 
@@ -97,8 +101,35 @@ dmath_status_t conv_call(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t* d,
     ConvPlan* plan = nullptr;
     st = get_conv_plan(ctx, mode, d, X, F, Y, &plan);
     if (st != DMATH_OK) return st;
-    return launch_conv(*plan, mode, alpha, beta, ctx->stream) == hipSuccess ? DMATH_OK
-                                                                            : DMATH_ERR_DEVICE;
+    // which re-layout copies are still current (same version of their matrix, same epoch)
+    unsigned rewrite = 0;
+    struct Use { Relayout* copy; dmath_matrix_s* src; unsigned bit; };
+    const Use used[3] = {{plan->xp, mode == CONV_BWD_DATA ? Y : X, REWRITE_X},
+                         {plan->fp, F, REWRITE_F},
+                         {plan->yt, Y, REWRITE_Y}};
+    const bool specialised = plan->kernel == 1 && alpha != 0.0;
+    if (specialised)
+        for (const Use& u : used) {
+            if (!u.copy) continue;
+            const bool current = ctx->reuse_relayouts && !u.src->exposed &&
+                                 u.copy->version == u.src->version && u.copy->epoch == ctx->epoch;
+            if (current) {
+                ++ctx->relayouts_reused;
+            } else {
+                rewrite |= u.bit;
+                ++ctx->relayouts_written;
+            }
+        }
+    if (launch_conv(*plan, mode, alpha, beta, rewrite, ctx->stream) != hipSuccess) return DMATH_ERR_DEVICE;
+    if (specialised)
+        for (const Use& u : used)
+            if (u.copy && (rewrite & u.bit)) {
+                u.copy->version = u.src->version;
+                u.copy->epoch = ctx->epoch;
+            }
+    wrote(ctx, res);
+    if (ctx->recording) ctx->recording_uses.insert({X->id, F->id, Y->id});
+    return DMATH_OK;
 }
 
 }  // namespace
@@ -122,8 +153,7 @@ dmath_status_t dmath_finalize(dmath_ctx_t ctx)
         (void)hipStreamEndCapture(ctx->stream, &g);
         if (g) (void)hipGraphDestroy(g);
     }
-    for (auto& kv : ctx->pipelines) (void)hipGraphExecDestroy(kv.second);
-    drop_all_plans(ctx);
+    drop_all_plans(ctx);  // recorded sequences included
     for (dmath_matrix_s* m : ctx->matrices) delete m;
     delete ctx;
     return DMATH_OK;
@@ -203,7 +233,11 @@ dmath_status_t dmath_matrix_block(dmath_matrix_t m, int32_t bi, int32_t bj, void
 {
     if (!m || bi < 0 || bj < 0 || bi >= m->rsplit.g || bj >= m->csplit.g)
         return DMATH_ERR_INVALID_ARG;
-    if (dev_ptr) *dev_ptr = m->block(bi, bj);
+    if (dev_ptr) {
+        *dev_ptr = m->block(bi, bj);
+        m->exposed = true;  // the caller may now write behind the library's back
+        wrote(m->ctx, m);
+    }
     if (rows) *rows = m->rsplit.len(bi);
     if (cols) *cols = m->csplit.len(bj);
     if (ld) *ld = m->csplit.len(bj);
@@ -256,6 +290,7 @@ dmath_status_t dmath_matrix_reblock(dmath_ctx_t ctx, dmath_matrix_t src, dmath_m
         e = launch_reblock(src->dtype, dst->dtype, static_cast<const CopyCell*>(dev), (int)cells.size(),
                            max_rows, ctx->stream);
     ctx->pool.free(dev);  // reuse of the table's memory is ordered after the kernel by the stream
+    wrote(ctx, dst);
     return e == hipSuccess ? DMATH_OK : DMATH_ERR_DEVICE;
 }
 
@@ -267,7 +302,10 @@ dmath_status_t dmath_gemm(dmath_ctx_t ctx, dmath_op_t transA, dmath_op_t transB,
     GemmPlan* plan = nullptr;
     st = get_gemm_plan(ctx, transA, transB, A, B, C, true, &plan, nullptr);
     if (st != DMATH_OK) return st;
-    return launch_gemm(*plan, alpha, beta, ctx->stream) == hipSuccess ? DMATH_OK : DMATH_ERR_DEVICE;
+    if (launch_gemm(*plan, alpha, beta, ctx->stream) != hipSuccess) return DMATH_ERR_DEVICE;
+    wrote(ctx, C);
+    if (ctx->recording) ctx->recording_uses.insert({A->id, B->id, C->id});
+    return DMATH_OK;
 }
 
 dmath_status_t dmath_gemm_plan_info(dmath_ctx_t ctx, dmath_op_t transA, dmath_op_t transB,
@@ -313,6 +351,8 @@ dmath_status_t dmath_pipeline_begin(dmath_ctx_t ctx)
     if (hipStreamBeginCapture(ctx->stream, hipStreamCaptureModeThreadLocal) != hipSuccess)
         return DMATH_ERR_DEVICE;
     ctx->recording = true;
+    ctx->recording_uses.clear();
+    ++ctx->epoch;  // a copy made before the recording is not rewritten by its replays
     return DMATH_OK;
 }
 
@@ -320,6 +360,7 @@ dmath_status_t dmath_pipeline_end(dmath_ctx_t ctx, int32_t* pipeline_id)
 {
     if (!ctx || !pipeline_id || !ctx->recording) return DMATH_ERR_INVALID_ARG;
     ctx->recording = false;
+    ++ctx->epoch;
     hipGraph_t graph = nullptr;
     if (hipStreamEndCapture(ctx->stream, &graph) != hipSuccess || !graph) return DMATH_ERR_DEVICE;
     hipGraphExec_t exec = nullptr;
@@ -327,7 +368,9 @@ dmath_status_t dmath_pipeline_end(dmath_ctx_t ctx, int32_t* pipeline_id)
     (void)hipGraphDestroy(graph);
     if (e != hipSuccess || !exec) return DMATH_ERR_DEVICE;
     *pipeline_id = ctx->next_pipeline++;
-    ctx->pipelines[*pipeline_id] = exec;
+    Pipeline& p = ctx->pipelines[*pipeline_id];
+    p.exec = exec;
+    p.uses.swap(ctx->recording_uses);
     return DMATH_OK;
 }
 
@@ -336,7 +379,11 @@ dmath_status_t dmath_pipeline_replay(dmath_ctx_t ctx, int32_t pipeline_id)
     if (!ctx || ctx->recording) return DMATH_ERR_INVALID_ARG;
     auto it = ctx->pipelines.find(pipeline_id);
     if (it == ctx->pipelines.end()) return DMATH_ERR_INVALID_ARG;
-    return hipGraphLaunch(it->second, ctx->stream) == hipSuccess ? DMATH_OK : DMATH_ERR_DEVICE;
+    // the replay rewrites matrices and re-layout copies that the host-side versions do not follow
+    ++ctx->epoch;
+    for (dmath_matrix_s* m : ctx->matrices)
+        if (it->second.uses.count(m->id)) wrote(ctx, m);
+    return hipGraphLaunch(it->second.exec, ctx->stream) == hipSuccess ? DMATH_OK : DMATH_ERR_DEVICE;
 }
 
 dmath_status_t dmath_pipeline_destroy(dmath_ctx_t ctx, int32_t pipeline_id)
@@ -344,8 +391,36 @@ dmath_status_t dmath_pipeline_destroy(dmath_ctx_t ctx, int32_t pipeline_id)
     if (!ctx) return DMATH_ERR_INVALID_ARG;
     auto it = ctx->pipelines.find(pipeline_id);
     if (it == ctx->pipelines.end()) return DMATH_ERR_INVALID_ARG;
-    (void)hipGraphExecDestroy(it->second);
+    (void)hipGraphExecDestroy(it->second.exec);
     ctx->pipelines.erase(it);
+    return DMATH_OK;
+}
+
+dmath_status_t dmath_set_relayout_reuse(dmath_ctx_t ctx, int32_t enable)
+{
+    if (!ctx || enable < 0 || enable > 1) return DMATH_ERR_INVALID_ARG;
+    if (ctx->recording) return DMATH_ERR_UNSUPPORTED;
+    ctx->reuse_relayouts = enable != 0;
+    return DMATH_OK;
+}
+
+dmath_status_t dmath_relayout_stats(dmath_ctx_t ctx, uint64_t* reused, uint64_t* written, size_t* bytes_held)
+{
+    if (!ctx) return DMATH_ERR_INVALID_ARG;
+    if (reused) *reused = ctx->relayouts_reused;
+    if (written) *written = ctx->relayouts_written;
+    if (bytes_held) {
+        size_t b = 0;
+        for (const auto& kv : ctx->relayouts) b += kv.second.bytes;
+        *bytes_held = b;
+    }
+    return DMATH_OK;
+}
+
+dmath_status_t dmath_matrix_touch(dmath_matrix_t m)
+{
+    if (!m || !m->ctx || !m->ctx->matrices.count(m)) return DMATH_ERR_INVALID_ARG;
+    wrote(m->ctx, m);
     return DMATH_OK;
 }
 

@@ -39,6 +39,10 @@ struct dmath_matrix_s {
     dm::Split rsplit, csplit;
     dmath_dtype_t dtype = DMATH_F32;
     std::vector<void*> blocks;  // grid row-major
+    // Bumped by every call that writes the matrix; re-layout copies remember the value they were
+    // made from.  A matrix whose block pointers were handed out can change unseen: never reused.
+    uint64_t version = 1;
+    bool exposed = false;
     void* block(int32_t bi, int32_t bj) const { return blocks[(size_t)bi * csplit.g + bj]; }
 };
 
@@ -62,21 +66,44 @@ struct GemmPlan {
 
 enum ConvMode : int32_t { CONV_FWD = 0, CONV_BWD_FILTER = 1, CONV_BWD_DATA = 2 };
 
+// A re-laid-out copy of one matrix, kept in the pool beside it (paper section 1, the cache of
+// objects already seen; section 3.3, reorganised data kept for the operations that follow).  It
+// is current while the source's version and the context's epoch are the ones it was written at.
+enum RelayoutKind : int32_t {
+    RELAYOUT_CHANNELS_LAST = 0,   // [n][h+2ph][w+2pw][ch], zero border; geometry {ch, h, w, ph, pw}
+    RELAYOUT_FILTER_RSC = 1,      // [k][(r,s,c)];                       geometry {c, r, s, k}
+    RELAYOUT_FILTER_ROTATED = 2,  // [c][(r',s',k)], taps reversed;      geometry {c, r, s, k}
+};
+struct Relayout {
+    void* buf = nullptr;
+    size_t bytes = 0;
+    uint64_t version = 0;  // of the source when the copy was last written (0: never)
+    uint64_t epoch = 0;
+};
+using RelayoutKey = std::tuple<uint64_t, int32_t, std::vector<int32_t>>;  // matrix id, kind, geometry
+
 struct ConvPlan {
     std::vector<uint64_t> uses;
     ConvTables t{};
     void* dev_tables = nullptr;
     void* workspace = nullptr;
-    // specialised fp16 path: channels-last copies kept in the pool (rewritten by every call)
-    void* xp = nullptr;  // [n][h+2ph][w+2pw][c], zero border
-    void* fp = nullptr;  // [k][(r,s,c)]
-    void* yt = nullptr;  // [n*oh*ow][k]
+    // specialised fp16 path: the copies it reads (owned by the context's table of re-layouts)
+    Relayout* xp = nullptr;  // gathered activations, channels-last with zero border
+    Relayout* fp = nullptr;  // permuted filter
+    Relayout* yt = nullptr;  // weight gradient: dY channels-last, [n*oh*ow][k]
     int32_t kernel = 0;  // 0 generic, 1 specialised fp16
     dmath_dtype_t in_dtype = DMATH_F16, out_dtype = DMATH_F32;
 };
 
 using GemmKey = std::tuple<uint64_t, uint64_t, uint64_t, int, int>;
 using ConvKey = std::tuple<uint64_t, uint64_t, uint64_t, int, std::vector<int32_t>>;
+
+// A recorded sequence and the matrices its kernels read or write (destroying one of them
+// destroys the sequence).
+struct Pipeline {
+    hipGraphExec_t exec = nullptr;
+    std::set<uint64_t> uses;
+};
 
 // Tile shape / kernel / split-K decision for a GEMM whose segments are known.
 struct GemmChoice {
@@ -95,9 +122,16 @@ struct dmath_ctx_s {
     std::set<dmath_matrix_s*> matrices;
     std::map<dm::GemmKey, std::unique_ptr<dm::GemmPlan>> gemm_plans;
     std::map<dm::ConvKey, std::unique_ptr<dm::ConvPlan>> conv_plans;
-    bool recording = false;                      // between dmath_pipeline_begin and _end
-    std::map<int32_t, hipGraphExec_t> pipelines;  // recorded sequences
+    bool recording = false;  // between dmath_pipeline_begin and _end
+    std::set<uint64_t> recording_uses;  // matrices touched by the sequence being recorded
+    std::map<int32_t, dm::Pipeline> pipelines;  // recorded sequences
     int32_t next_pipeline = 1;
+    // re-layout copies: reused while current unless switched off; the epoch moves at every
+    // recording boundary and replay, so nothing is reused across them
+    std::map<dm::RelayoutKey, dm::Relayout> relayouts;
+    bool reuse_relayouts = true;
+    uint64_t epoch = 1;
+    uint64_t relayouts_reused = 0, relayouts_written = 0;
     dmath_ctx_s(void* slab, size_t bytes, hipStream_t s) : pool(slab, bytes), stream(s) {}
 };
 
@@ -112,15 +146,22 @@ dmath_status_t get_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t
                              ConvPlan** out);
 void drop_plans_using(dmath_ctx_s* ctx, uint64_t matrix_id);
 void drop_all_plans(dmath_ctx_s* ctx);
+void drop_pipelines_using(dmath_ctx_s* ctx, uint64_t matrix_id);
+void drop_all_pipelines(dmath_ctx_s* ctx);
 
 // kernels (launch.hip)
 hipError_t launch_gemm(const GemmPlan& p, double alpha, double beta, hipStream_t stream);
-hipError_t launch_conv(const ConvPlan& p, int mode, double alpha, double beta, hipStream_t stream);
+// rewrite: bit 0 the gathered activations, bit 1 the filter, bit 2 dY of the weight gradient have
+// to be re-laid-out before the multiplication (specialised path only)
+enum : unsigned { REWRITE_X = 1, REWRITE_F = 2, REWRITE_Y = 4 };
+hipError_t launch_conv(const ConvPlan& p, int mode, double alpha, double beta, unsigned rewrite,
+                       hipStream_t stream);
 hipError_t launch_reblock(dmath_dtype_t sd, dmath_dtype_t dd, const CopyCell* cells, int n_cells,
                           int max_rows, hipStream_t st);
 bool conv_f16_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype);
 int conv_f16_wgrad_split(const ConvGeom& g);
-hipError_t launch_conv_f16(const ConvPlan& p, int mode, double alpha, double beta, hipStream_t st);
+hipError_t launch_conv_f16(const ConvPlan& p, int mode, double alpha, double beta, unsigned rewrite,
+                           hipStream_t st);
 hipError_t launch_mfma_peak(dmath_dtype_t dt, int iters, void* scratch, hipStream_t st, double* flops);
 // Picks kernel, tile shape and split-K; written next to the kernels whose preconditions it checks.
 struct SegView {

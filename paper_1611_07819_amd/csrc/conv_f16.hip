@@ -16,8 +16,8 @@
 //   data gradient  : the forward kernel again, over the zero-bordered channels-last copy of dY
 //                    (padding r-1-pad) with the filter rotated by 180 degrees and its channel
 //                    roles swapped, Gp[c][(r',s',k)].
-// The rewrites are part of every call (activations change every step); their cost is inside
-// the timed region.
+// A rewrite is skipped when the caller says the copy is still current (the context keeps the
+// copies and the version of the matrix each was made from); otherwise it is part of the call.
 #include <hip/hip_runtime.h>
 
 #include <cstdlib>
@@ -380,7 +380,8 @@ int conv_f16_wgrad_split(const ConvGeom& g)
     return best;
 }
 
-hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double beta, hipStream_t st)
+hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double beta, unsigned rewrite,
+                           hipStream_t st)
 {
     const ConvTables& t = plan.t;
     const ConvGeom& g = t.g;
@@ -390,12 +391,15 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
     p.wp = g.w + 2 * g.pad_w;
     p.y_rows = t.y_rows;
     p.f_rows = t.f_rows;
-    p.xp = static_cast<const _Float16*>(plan.xp);
-    p.fp = static_cast<const _Float16*>(plan.fp);
-    p.yt = static_cast<const _Float16*>(plan.yt);
+    _Float16* const xp = plan.xp ? static_cast<_Float16*>(plan.xp->buf) : nullptr;
+    _Float16* const fp = plan.fp ? static_cast<_Float16*>(plan.fp->buf) : nullptr;
+    _Float16* const yt = plan.yt ? static_cast<_Float16*>(plan.yt->buf) : nullptr;
+    p.xp = xp;
+    p.fp = fp;
+    p.yt = yt;
     p.ws = static_cast<float*>(t.workspace);
     p.split = t.split_k;
-    if (!plan.xp || (mode != CONV_BWD_FILTER && !plan.fp) || (mode == CONV_BWD_FILTER && (!plan.yt || !p.ws)))
+    if (!xp || (mode != CONV_BWD_FILTER && !fp) || (mode == CONV_BWD_FILTER && (!yt || !p.ws)))
         return hipErrorInvalidValue;  // the plan was not made for this path
 
     static bool configured = false;
@@ -421,9 +425,11 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
         q.wp = g.ow + 2 * ppw;
         q.y_rows = t.x_rows;
         const int lds = 64 * tcl_stride(g.oh * g.ow) * 2;
-        to_channels_last_kernel<<<g.n * (g.k / 64), kTclThreads, lds, st>>>(t.y_rows, g.k, g.oh, g.ow, pph, ppw,
-                                                                             q.hp, q.wp, static_cast<_Float16*>(plan.xp));
-        filter_to_rsk_rotated_kernel<<<512, 256, 0, st>>>(t.f_rows, g.c, g.r, g.s, g.k, static_cast<_Float16*>(plan.fp));
+        if (rewrite & REWRITE_X)
+            to_channels_last_kernel<<<g.n * (g.k / 64), kTclThreads, lds, st>>>(t.y_rows, g.k, g.oh, g.ow, pph, ppw,
+                                                                                 q.hp, q.wp, xp);
+        if (rewrite & REWRITE_F)
+            filter_to_rsk_rotated_kernel<<<512, 256, 0, st>>>(t.f_rows, g.c, g.r, g.s, g.k, fp);
         const int mt = (int)((int64_t)g.n * g.h * g.w / 256);
         const int t128 = mt * (g.c / 128), t256 = mt * (g.c / 256);
         const bool wide = g.c % 256 == 0 && t128 > 256 && t256 <= 256;
@@ -440,14 +446,14 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
         }
         return hipGetLastError();
     }
-    // activations -> zero-bordered channels-last copy (borders were zeroed when the plan was made)
-    {
+    // activations -> zero-bordered channels-last copy (borders were zeroed when the copy was allocated)
+    if (rewrite & REWRITE_X) {
         const int lds = 64 * tcl_stride(g.h * g.w) * 2;
         to_channels_last_kernel<<<g.n * (g.c / 64), kTclThreads, lds, st>>>(t.x_rows, g.c, g.h, g.w, g.pad_h, g.pad_w,
-                                                                     p.hp, p.wp, static_cast<_Float16*>(plan.xp));
+                                                                     p.hp, p.wp, xp);
     }
     if (mode == CONV_FWD) {
-        filter_to_rsc_kernel<<<512, 256, 0, st>>>(t.f_rows, g.c, g.r * g.s, g.k, static_cast<_Float16*>(plan.fp));
+        if (rewrite & REWRITE_F) filter_to_rsc_kernel<<<512, 256, 0, st>>>(t.f_rows, g.c, g.r * g.s, g.k, fp);
         // 256x128 tiles unless they would need a second, mostly empty round of workgroups while
         // 256x256 tiles fit in one
         const int mt = (int)((int64_t)g.n * g.oh * g.ow / 256);
@@ -469,10 +475,10 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
         return hipGetLastError();
     }
     // weight gradient: dY -> channels-last [m][k], split GEMM, fixed-order reduction
-    {
+    if (rewrite & REWRITE_Y) {
         const int lds = 64 * tcl_stride(g.oh * g.ow) * 2;
         to_channels_last_kernel<<<g.n * (g.k / 64), kTclThreads, lds, st>>>(t.y_rows, g.k, g.oh, g.ow, 0, 0, g.oh, g.ow,
-                                                                     static_cast<_Float16*>(plan.yt));
+                                                                     yt);
     }
     p.ktiles_per_split = (int)((int64_t)g.n * g.oh * g.ow / 64 / t.split_k);
     const int tiles = (g.c * g.r * g.s / 128) * t.split_k;

@@ -136,9 +136,9 @@ hipError_t launch_gemm(const GemmPlan& p, double alpha, double beta, hipStream_t
     return launch_gemm_reduce(p, p.t.split_k, alpha, beta, st);
 }
 
-hipError_t launch_conv(const ConvPlan& p, int mode, double alpha, double beta, hipStream_t st)
+hipError_t launch_conv(const ConvPlan& p, int mode, double alpha, double beta, unsigned rewrite, hipStream_t st)
 {
-    if (p.kernel == 1 && alpha != 0.0) return launch_conv_f16(p, mode, alpha, beta, st);
+    if (p.kernel == 1 && alpha != 0.0) return launch_conv_f16(p, mode, alpha, beta, rewrite, st);
     return launch_conv_generic(p, mode, alpha, beta, st);
 }
 

@@ -80,15 +80,65 @@ std::vector<Tile> xcd_interleave(const std::vector<Tile>& logical)
 
 static void free_conv_plan(dmath_ctx_s* ctx, ConvPlan& p)
 {
-    for (void** q : {&p.dev_tables, &p.workspace, &p.xp, &p.fp, &p.yt})
+    for (void** q : {&p.dev_tables, &p.workspace})
         if (*q) {
             ctx->pool.free(*q);
             *q = nullptr;
         }
+    p.xp = p.fp = p.yt = nullptr;  // the copies belong to the context's table
 }
 
+// The copy of matrix `src` in the given layout: found, or allocated (zeroed once: the border of a
+// padded copy is never written again).  Null when the pool is full.
+static Relayout* get_relayout(dmath_ctx_s* ctx, const dmath_matrix_s* src, int32_t kind,
+                              std::vector<int32_t> geom, size_t bytes)
+{
+    RelayoutKey key{src->id, kind, std::move(geom)};
+    auto it = ctx->relayouts.find(key);
+    if (it != ctx->relayouts.end()) return &it->second;
+    void* buf = ctx->pool.alloc(bytes);
+    if (!buf) return nullptr;
+    if (hipMemsetAsync(buf, 0, bytes, ctx->stream) != hipSuccess) {
+        ctx->pool.free(buf);
+        return nullptr;
+    }
+    Relayout r;
+    r.buf = buf;
+    r.bytes = bytes;
+    return &(ctx->relayouts[key] = r);
+}
+
+static void drop_relayouts_of(dmath_ctx_s* ctx, uint64_t id)
+{
+    for (auto it = ctx->relayouts.begin(); it != ctx->relayouts.end();)
+        if (std::get<0>(it->first) == id) {
+            ctx->pool.free(it->second.buf);
+            it = ctx->relayouts.erase(it);
+        } else
+            ++it;
+}
+
+void drop_pipelines_using(dmath_ctx_s* ctx, uint64_t id)
+{
+    for (auto it = ctx->pipelines.begin(); it != ctx->pipelines.end();)
+        if (it->second.uses.count(id)) {
+            (void)hipGraphExecDestroy(it->second.exec);
+            it = ctx->pipelines.erase(it);
+        } else
+            ++it;
+}
+
+void drop_all_pipelines(dmath_ctx_s* ctx)
+{
+    for (auto& kv : ctx->pipelines) (void)hipGraphExecDestroy(kv.second.exec);
+    ctx->pipelines.clear();
+}
+
+// Everything derived from matrix `id` goes: recorded sequences first (their kernels hold the
+// addresses of the tables and copies freed next).
 void drop_plans_using(dmath_ctx_s* ctx, uint64_t id)
 {
+    drop_pipelines_using(ctx, id);
     for (auto it = ctx->gemm_plans.begin(); it != ctx->gemm_plans.end();) {
         auto& u = it->second->uses;
         if (std::find(u.begin(), u.end(), id) != u.end()) {
@@ -106,10 +156,12 @@ void drop_plans_using(dmath_ctx_s* ctx, uint64_t id)
         } else
             ++it;
     }
+    drop_relayouts_of(ctx, id);
 }
 
 void drop_all_plans(dmath_ctx_s* ctx)
 {
+    drop_all_pipelines(ctx);
     for (auto& kv : ctx->gemm_plans) {
         if (kv.second->dev_tables) ctx->pool.free(kv.second->dev_tables);
         if (kv.second->workspace) ctx->pool.free(kv.second->workspace);
@@ -117,6 +169,8 @@ void drop_all_plans(dmath_ctx_s* ctx)
     ctx->gemm_plans.clear();
     for (auto& kv : ctx->conv_plans) free_conv_plan(ctx, *kv.second);
     ctx->conv_plans.clear();
+    for (auto& kv : ctx->relayouts) ctx->pool.free(kv.second.buf);
+    ctx->relayouts.clear();
 }
 
 static hipError_t upload(dmath_ctx_s* ctx, void* dst, const std::vector<char>& buf)
@@ -400,23 +454,26 @@ dmath_status_t get_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t
         }
     }
     if (fast) {
-        // padded channels-last copy of the gathered tensor: X for forward / weight gradient, dY
-        // (padding r-1-pad) for the data gradient
-        const size_t xp_bytes =
-            mode == CONV_BWD_DATA
-                ? (size_t)g.n * (g.oh + 2 * (g.r - 1 - g.pad_h)) * (g.ow + 2 * (g.s - 1 - g.pad_w)) * g.k * 2
-                : (size_t)g.n * (g.h + 2 * g.pad_h) * (g.w + 2 * g.pad_w) * g.c * 2;
-        plan->xp = ctx->pool.alloc(xp_bytes);
-        if (mode != CONV_BWD_FILTER) plan->fp = ctx->pool.alloc((size_t)g.k * crs * 2);
-        if (mode == CONV_BWD_FILTER) plan->yt = ctx->pool.alloc((size_t)g.n * sp_out * g.k * 2);
+        // copies this plan reads; a copy is shared by every plan that wants the same layout of
+        // the same matrix (the activations of the forward pass serve the weight gradient too)
         plan->dev_tables = dev;
         plan->workspace = ws;
-        bool ok = plan->xp && (mode == CONV_BWD_FILTER || plan->fp) && (mode != CONV_BWD_FILTER || plan->yt);
-        // the zero border of the padded copy is written once; every call rewrites the interior
-        if (ok && hipMemsetAsync(plan->xp, 0, xp_bytes, ctx->stream) != hipSuccess) {
-            free_conv_plan(ctx, *plan);
-            return DMATH_ERR_DEVICE;
+        const int32_t pph = g.r - 1 - g.pad_h, ppw = g.s - 1 - g.pad_w;
+        if (mode == CONV_BWD_DATA) {
+            // dY gathered with padding r-1-pad, filter rotated with its channel roles swapped
+            plan->xp = get_relayout(ctx, Y, RELAYOUT_CHANNELS_LAST, {g.k, g.oh, g.ow, pph, ppw},
+                                    (size_t)g.n * (g.oh + 2 * pph) * (g.ow + 2 * ppw) * g.k * 2);
+            plan->fp = get_relayout(ctx, F, RELAYOUT_FILTER_ROTATED, {g.c, g.r, g.s, g.k}, (size_t)g.k * crs * 2);
+        } else {
+            plan->xp = get_relayout(ctx, X, RELAYOUT_CHANNELS_LAST, {g.c, g.h, g.w, g.pad_h, g.pad_w},
+                                    (size_t)g.n * (g.h + 2 * g.pad_h) * (g.w + 2 * g.pad_w) * g.c * 2);
+            if (mode == CONV_FWD)
+                plan->fp = get_relayout(ctx, F, RELAYOUT_FILTER_RSC, {g.c, g.r, g.s, g.k}, (size_t)g.k * crs * 2);
+            else
+                plan->yt = get_relayout(ctx, Y, RELAYOUT_CHANNELS_LAST, {g.k, g.oh, g.ow, 0, 0},
+                                        (size_t)g.n * sp_out * g.k * 2);
         }
+        const bool ok = plan->xp && (mode == CONV_BWD_FILTER ? plan->yt != nullptr : plan->fp != nullptr);
         if (!ok) {
             free_conv_plan(ctx, *plan);
             return DMATH_ERR_OOM;

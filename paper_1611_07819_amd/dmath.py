@@ -89,6 +89,9 @@ def load_library(build_if_missing: bool = True):
         "dmath_conv_bwd_filter": [vp, P(_ConvDesc), dbl, vp, vp, dbl, vp],
         "dmath_conv_bwd_data": [vp, P(_ConvDesc), dbl, vp, vp, dbl, vp],
         "dmath_set_kernel_policy": [vp, i32],
+        "dmath_set_relayout_reuse": [vp, i32],
+        "dmath_relayout_stats": [vp, P(ctypes.c_uint64), P(ctypes.c_uint64), P(sz)],
+        "dmath_matrix_touch": [vp],
         "dmath_pipeline_begin": [vp],
         "dmath_pipeline_end": [vp, P(i32)],
         "dmath_pipeline_replay": [vp, i32],
@@ -143,6 +146,15 @@ class Context:
 
     def set_kernel_policy(self, policy: int):
         _check(self._lib.dmath_set_kernel_policy(self._h, policy), "dmath_set_kernel_policy")
+
+    def set_relayout_reuse(self, enable: bool):
+        _check(self._lib.dmath_set_relayout_reuse(self._h, 1 if enable else 0), "dmath_set_relayout_reuse")
+
+    def relayout_stats(self):
+        a, b, c = ctypes.c_uint64(), ctypes.c_uint64(), ctypes.c_size_t()
+        _check(self._lib.dmath_relayout_stats(self._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)),
+               "dmath_relayout_stats")
+        return {"reused": a.value, "written": b.value, "bytes_held": c.value}
 
     def mfma_peak_probe(self, dtype: int, iters: int) -> float:
         """Enqueues the MFMA-only micro-kernel; returns the flops it performs."""
@@ -210,6 +222,9 @@ class Matrix:
         _check(self.ctx._lib.dmath_matrix_block(self._h, bi, bj, ctypes.byref(p), ctypes.byref(r),
                                                 ctypes.byref(c), ctypes.byref(ld)), "dmath_matrix_block")
         return {"ptr": p.value, "rows": r.value, "cols": c.value, "ld": ld.value}
+
+    def touch(self):
+        _check(self.ctx._lib.dmath_matrix_touch(self._h), "dmath_matrix_touch")
 
     def info(self):
         r, c, gr, gc, dt = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int()

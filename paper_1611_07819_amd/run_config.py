@@ -32,6 +32,7 @@ def main():
     slab = torch.empty(6 << 30, dtype=torch.uint8, device="cuda:0")
     st = torch.cuda.current_stream()
     ctx = dm.Context(slab, stream=st.cuda_stream)
+    ctx.set_relayout_reuse(False)     # every call shows all of its kernels in the trace
     dev = {k: ctx.from_host(v, w.grid) for k, v in w.mats.items()}
     calls = []
     for c in w.calls:

@@ -1,0 +1,161 @@
+"""Re-layout copies that are kept between calls (paper section 1: the cache of objects already
+seen; section 3.3: data reorganised once for the operations that follow).  A copy may only be
+reused while the matrix it was made from is unchanged: every way of writing a matrix is checked
+to invalidate it, against the CPU oracle on the new contents, and reuse itself must not change
+a single bit of any result."""
+import numpy as np
+import pytest
+
+import paper_1611_07819_amd as dm
+from gpu_util import TOL, rel_fro
+
+pytestmark = pytest.mark.gpu
+
+GEO = dict(n=4, c=128, h=16, w=16, k=256, r=3, s=3, pad_h=1, pad_w=1)   # specialised fp16 path
+
+
+@pytest.fixture()
+def ctx():
+    import torch
+    stream = torch.cuda.Stream()          # non-default stream (default priority): recordable
+    slab = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+    torch.cuda.synchronize()
+    c = dm.Context(slab, stream=stream.cuda_stream)
+    yield c
+    c.close()
+
+
+def host_tensors(seed):
+    r = np.random.default_rng(seed)
+    g = GEO
+    return {"X": r.uniform(0, 1, (g["n"], g["c"] * g["h"] * g["w"])).astype(np.float16),
+            "F": r.normal(0, 0.05, (g["k"], g["c"] * g["r"] * g["s"])).astype(np.float16),
+            "dY": r.normal(0, 0.1, (g["n"], g["k"] * g["h"] * g["w"])).astype(np.float16)}
+
+
+def delta(ctx, before):
+    now = ctx.relayout_stats()
+    return now["reused"] - before["reused"], now["written"] - before["written"]
+
+
+def test_reuse_skips_rewrites_and_changes_no_bit(ctx, oracle):
+    d, od = dm.ConvDesc(**GEO), oracle.ConvDesc(**GEO)
+    t = host_tensors(1000)
+    X, F, dY = ctx.from_host(t["X"]), ctx.from_host(t["F"]), ctx.from_host(t["dY"])
+    Y = ctx.matrix(*t["dY"].shape, (1, 1), dm.F32)
+    dF = ctx.matrix(*t["F"].shape, (1, 1), dm.F32)
+    dX = ctx.matrix(*t["X"].shape, (1, 1), dm.F32)
+
+    def step():
+        dm.conv_fwd(ctx, d, 1.0, X, F, 0.0, Y)
+        dm.conv_bwd_filter(ctx, d, 1.0, X, dY, 0.0, dF)
+        dm.conv_bwd_data(ctx, d, 1.0, dY, F, 0.0, dX)
+        return [m.get() for m in (Y, dF, dX)]
+
+    s0 = ctx.relayout_stats()
+    first = step()
+    # forward: X and F copied; weight gradient: X's copy serves again, dY copied; data gradient:
+    # dY with its own padding and the rotated filter, both new
+    assert delta(ctx, s0) == (1, 5)
+    s1 = ctx.relayout_stats()
+    second = step()                                   # nothing changed: every copy is current
+    assert delta(ctx, s1) == (6, 0)
+    ctx.set_relayout_reuse(False)
+    s2 = ctx.relayout_stats()
+    third = step()
+    assert delta(ctx, s2) == (0, 6)
+    ctx.set_relayout_reuse(True)
+    for a, b, c in zip(first, second, third):
+        assert np.array_equal(a, b) and np.array_equal(a, c)
+    assert rel_fro(first[0], oracle.conv_fwd(od, 1.0, t["X"], t["F"])) <= TOL[dm.F16]
+    assert rel_fro(first[1], oracle.conv_bwd_filter(od, 1.0, t["X"], t["dY"])) <= TOL[dm.F16]
+    assert rel_fro(first[2], oracle.conv_bwd_data(od, 1.0, t["dY"], t["F"])) <= TOL[dm.F16]
+    assert ctx.relayout_stats()["bytes_held"] > 0
+
+
+def test_every_kind_of_write_invalidates_the_copy(ctx, oracle):
+    d, od = dm.ConvDesc(**GEO), oracle.ConvDesc(**GEO)
+    t = host_tensors(1001)
+    X, F = ctx.from_host(t["X"]), ctx.from_host(t["F"])
+    Y = ctx.matrix(GEO["n"], GEO["k"] * 256, (1, 1), dm.F32)
+
+    def fwd_matches(x, f):
+        dm.conv_fwd(ctx, d, 1.0, X, F, 0.0, Y)
+        assert rel_fro(Y.get(), oracle.conv_fwd(od, 1.0, x, f)) <= TOL[dm.F16]
+
+    fwd_matches(t["X"], t["F"])
+    # 1. host upload
+    x1 = (1 - t["X"].astype(np.float32)).astype(np.float16)
+    X.set(x1)
+    s = ctx.relayout_stats()
+    fwd_matches(x1, t["F"])
+    assert delta(ctx, s) == (1, 1)                      # F reused, X rewritten
+    # 2. result of a GEMM (fp16 output): F <- P * Q
+    r = np.random.default_rng(1002)
+    P = r.normal(0, 0.2, (GEO["k"], 64)).astype(np.float16)
+    Q = r.normal(0, 0.2, (64, t["F"].shape[1])).astype(np.float16)
+    dP, dQ = ctx.from_host(P), ctx.from_host(Q)
+    dm.gemm(ctx, 0, 0, 1.0, dP, dQ, 0.0, F)
+    f2 = F.get()
+    assert not np.array_equal(f2, t["F"])
+    s = ctx.relayout_stats()
+    fwd_matches(x1, f2)
+    assert delta(ctx, s) == (1, 1)                      # X reused, F rewritten
+    # 3. result of a convolution (data gradient written into X, fp16 output)
+    dY = ctx.from_host(host_tensors(1003)["dY"])
+    dm.conv_bwd_data(ctx, d, 1.0, dY, F, 0.0, X)
+    x3 = X.get()
+    assert not np.array_equal(x3, x1)
+    fwd_matches(x3, f2)
+    # 4. re-blocking into X from a matrix with another grid and precision
+    x4 = r.uniform(0, 1, t["X"].shape).astype(np.float32)
+    src = ctx.from_host(x4, (2, 2))
+    dm.reblock(ctx, src, X)
+    fwd_matches(x4.astype(np.float16), f2)
+    # 5. a declared outside change: rewritten although the contents are the same
+    X.touch()
+    s = ctx.relayout_stats()
+    fwd_matches(x4.astype(np.float16), f2)
+    assert delta(ctx, s) == (1, 1)
+    # 6. handing out a block pointer: from then on the copy of that matrix is never trusted
+    X.block(0, 0)
+    for _ in range(2):
+        s = ctx.relayout_stats()
+        fwd_matches(x4.astype(np.float16), f2)
+        assert delta(ctx, s) == (1, 1)
+
+
+def test_recorded_sequences_rewrite_their_copies_on_every_replay(ctx, oracle):
+    d, od = dm.ConvDesc(**GEO), oracle.ConvDesc(**GEO)
+    t = host_tensors(1004)
+    X, F, dY = ctx.from_host(t["X"]), ctx.from_host(t["F"]), ctx.from_host(t["dY"])
+    Y = ctx.matrix(*t["dY"].shape, (1, 1), dm.F32)
+    dF = ctx.matrix(*t["F"].shape, (1, 1), dm.F32)
+
+    def step():
+        dm.conv_fwd(ctx, d, 1.0, X, F, 0.0, Y)
+        dm.conv_bwd_filter(ctx, d, 1.0, X, dY, 0.0, dF)
+
+    step()                                              # plans and current copies exist now
+    s = ctx.relayout_stats()
+    ctx.pipeline_begin()
+    step()
+    pid = ctx.pipeline_end()
+    # copies made before the recording are not trusted inside it; the copy of X made by the
+    # recorded forward pass serves the recorded weight gradient
+    assert delta(ctx, s) == (1, 3)
+    for seed in (1005, 1006):
+        t2 = host_tensors(seed)
+        X.set(t2["X"]); F.set(t2["F"]); dY.set(t2["dY"])
+        ctx.pipeline_replay(pid)
+        assert rel_fro(Y.get(), oracle.conv_fwd(od, 1.0, t2["X"], t2["F"])) <= TOL[dm.F16]
+        assert rel_fro(dF.get(), oracle.conv_bwd_filter(od, 1.0, t2["X"], t2["dY"])) <= TOL[dm.F16]
+        s = ctx.relayout_stats()
+        step()                                          # eager after a replay: nothing is trusted
+        assert delta(ctx, s) == (1, 3)
+        assert rel_fro(Y.get(), oracle.conv_fwd(od, 1.0, t2["X"], t2["F"])) <= TOL[dm.F16]
+    # destroying a matrix that the sequence uses destroys the sequence
+    dY.destroy()
+    with pytest.raises(dm.DmathError) as err:
+        ctx.pipeline_replay(pid)
+    assert err.value.code == 1                          # DMATH_ERR_INVALID_ARG
