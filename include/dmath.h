@@ -228,6 +228,43 @@ dmath_status_t dmath_relayout_stats(dmath_ctx_t ctx, uint64_t *reused, uint64_t 
                                     size_t *bytes_held);
 dmath_status_t dmath_matrix_touch(dmath_matrix_t m);
 
+/*
+ * Selection from timing samples (section 4.1: at start-up the library picks the convolution
+ * algorithm from timing samples within the system's memory constraints).  Without tuning, the
+ * kernel family, tile shape and split-K count come from a cost model.  The tuners time every
+ * configuration the operation admits on the given handles (one warm-up launch, then `trials`
+ * launches between two events; the call blocks), leave out those that need more pool memory
+ * beyond the operands than `workspace_limit` bytes (split-K partial sums; for convolutions also
+ * the re-layout copies the specialised kernels read) or than the pool can give, and remember the
+ * fastest under the operation's layout signature (ops, precisions, shapes, block grids,
+ * convolution geometry): every later plan with that signature uses it, whichever matrices it is
+ * built for.  The result matrix is overwritten (alpha = 1, beta = 0).  Results stay within the
+ * same tolerances whatever is chosen (summation order may differ between configurations).
+ *   dmath_conv_tune: mode 0 forward, 1 weight gradient, 2 data gradient; X, F, Y are the
+ *     tensors in the shapes of dmath_conv_fwd (X or dX, F or dF, Y or dY).
+ *   dmath_tune_reset: forgets every choice and drops all plans.
+ * Errors: DMATH_ERR_UNSUPPORTED while recording or under kernel policy 1; DMATH_ERR_OOM if no
+ * configuration fits; the argument errors of the operation itself.
+ */
+typedef struct dmath_tune_result {
+    int32_t candidates;       /* configurations timed */
+    int32_t skipped;          /* configurations left out for memory */
+    int32_t kernel;           /* chosen: kernel family (0 generic), */
+    int32_t tile_m, tile_n;   /*   tile shape, */
+    int32_t split_k;          /*   split-K parts, */
+    uint64_t workspace_bytes; /*   pool memory beyond the operands */
+    double chosen_us;         /* time per call of the chosen configuration */
+    double default_us;        /* time per call of the cost model's choice (0: it did not fit) */
+} dmath_tune_result_t;
+
+dmath_status_t dmath_gemm_tune(dmath_ctx_t ctx, dmath_op_t transA, dmath_op_t transB,
+                               dmath_matrix_t A, dmath_matrix_t B, dmath_matrix_t C,
+                               size_t workspace_limit, int32_t trials, dmath_tune_result_t *result);
+dmath_status_t dmath_conv_tune(dmath_ctx_t ctx, int32_t mode, const dmath_conv_desc_t *desc,
+                               dmath_matrix_t X, dmath_matrix_t F, dmath_matrix_t Y,
+                               size_t workspace_limit, int32_t trials, dmath_tune_result_t *result);
+dmath_status_t dmath_tune_reset(dmath_ctx_t ctx);
+
 /* Kernel selection: 0 = automatic (specialised kernels where their preconditions hold),
  * 1 = always the guarded generic kernel (for testing and debugging).  Drops cached plans. */
 dmath_status_t dmath_set_kernel_policy(dmath_ctx_t ctx, int32_t policy);

@@ -75,9 +75,9 @@ dmath_status_t check_conv_desc(const dmath_conv_desc_t* d, int64_t* oh, int64_t*
     return DMATH_OK;
 }
 
-// in1, in2: the two tensors that are read; res: the tensor that is written.
-dmath_status_t conv_call(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t* d, double alpha,
-                         dmath_matrix_s* X, dmath_matrix_s* F, dmath_matrix_s* Y, double beta)
+// Argument checks shared by the convolution calls and their tuner.
+dmath_status_t check_conv(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t* d, dmath_matrix_s* X,
+                          dmath_matrix_s* F, dmath_matrix_s* Y)
 {
     if (!ctx || !X || !F || !Y) return DMATH_ERR_INVALID_ARG;
     int64_t oh, ow;
@@ -98,6 +98,16 @@ dmath_status_t conv_call(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t* d,
     if (chw >= (1ll << 31) || kow >= (1ll << 31) || crs >= (1ll << 31) ||
         (int64_t)d->n * oh * ow >= (1ll << 31) || (int64_t)d->n * d->h * d->w >= (1ll << 31))
         return DMATH_ERR_UNSUPPORTED;
+    return DMATH_OK;
+}
+
+// in1, in2: the two tensors that are read; res: the tensor that is written.
+dmath_status_t conv_call(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t* d, double alpha,
+                         dmath_matrix_s* X, dmath_matrix_s* F, dmath_matrix_s* Y, double beta)
+{
+    dmath_status_t st = check_conv(ctx, mode, d, X, F, Y);
+    if (st != DMATH_OK) return st;
+    dmath_matrix_s* res = mode == CONV_FWD ? Y : mode == CONV_BWD_FILTER ? F : X;
     ConvPlan* plan = nullptr;
     st = get_conv_plan(ctx, mode, d, X, F, Y, &plan);
     if (st != DMATH_OK) return st;
@@ -131,6 +141,33 @@ dmath_status_t conv_call(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t* d,
     if (ctx->recording) ctx->recording_uses.insert({X->id, F->id, Y->id});
     return DMATH_OK;
 }
+
+}  // namespace
+
+namespace {
+
+// Average time of `trials` launches after one warm-up launch, in microseconds (negative: error).
+template <class Launch> double sample_us(dmath_ctx_s* ctx, hipEvent_t e0, hipEvent_t e1, int trials, Launch&& launch)
+{
+    if (launch() != hipSuccess) return -1;
+    if (hipEventRecord(e0, ctx->stream) != hipSuccess) return -1;
+    for (int i = 0; i < trials; ++i)
+        if (launch() != hipSuccess) return -1;
+    if (hipEventRecord(e1, ctx->stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) return -1;
+    float ms = 0;
+    if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) return -1;
+    return (double)ms * 1e3 / trials;
+}
+
+struct Events {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    bool ok() { return hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess; }
+    ~Events()
+    {
+        if (e0) (void)hipEventDestroy(e0);
+        if (e1) (void)hipEventDestroy(e1);
+    }
+};
 
 }  // namespace
 
@@ -393,6 +430,182 @@ dmath_status_t dmath_pipeline_destroy(dmath_ctx_t ctx, int32_t pipeline_id)
     if (it == ctx->pipelines.end()) return DMATH_ERR_INVALID_ARG;
     (void)hipGraphExecDestroy(it->second.exec);
     ctx->pipelines.erase(it);
+    return DMATH_OK;
+}
+
+dmath_status_t dmath_gemm_tune(dmath_ctx_t ctx, dmath_op_t transA, dmath_op_t transB, dmath_matrix_t A,
+                               dmath_matrix_t B, dmath_matrix_t C, size_t workspace_limit, int32_t trials,
+                               dmath_tune_result_t* result)
+{
+    if (!result || trials <= 0) return DMATH_ERR_INVALID_ARG;
+    dmath_status_t st = check_gemm(ctx, transA, transB, A, B, C);
+    if (st != DMATH_OK) return st;
+    if (ctx->recording || ctx->policy != 0) return DMATH_ERR_UNSUPPORTED;
+    // the cost model's own choice and the list of candidates
+    const std::vector<int64_t> sig = gemm_signature(transA, transB, A, B, C);
+    ctx->tuned_gemm.erase(sig);
+    std::unique_ptr<GemmPlan> described;
+    std::vector<GemmChoice> cands;
+    st = make_gemm_plan(ctx, transA, transB, A, B, C, false, nullptr, &described, &cands);
+    if (st != DMATH_OK) return st;
+    const dmath_plan_info_t model = described->info;
+    Events ev;
+    if (!ev.ok()) return DMATH_ERR_DEVICE;
+    *result = dmath_tune_result_t{};
+    const size_t acc = A->dtype == DMATH_F64 ? 8 : 4;
+    double best = -1;
+    GemmChoice best_choice;
+    for (const GemmChoice& c : cands) {
+        const size_t need = c.split_k > 1 ? (size_t)c.split_k * C->rows * C->cols * acc : 0;
+        if (need > workspace_limit) {
+            ++result->skipped;
+            continue;
+        }
+        std::unique_ptr<GemmPlan> plan;
+        st = make_gemm_plan(ctx, transA, transB, A, B, C, true, &c, &plan, nullptr);
+        if (st == DMATH_ERR_OOM) {  // the pool cannot hold it now: as good as over the limit
+            ++result->skipped;
+            continue;
+        }
+        if (st != DMATH_OK) return st;
+        const double us = sample_us(ctx, ev.e0, ev.e1, trials,
+                                    [&] { return launch_gemm(*plan, 1.0, 0.0, ctx->stream); });
+        const dmath_plan_info_t info = plan->info;
+        free_gemm_plan(ctx, *plan);  // stream order: the samples have completed (event wait)
+        if (us < 0) return DMATH_ERR_DEVICE;
+        ++result->candidates;
+        const bool is_model = info.kernel == model.kernel && info.tile_m == model.tile_m &&
+                              info.tile_n == model.tile_n && info.split_k == model.split_k;
+        if (is_model) result->default_us = us;
+        if (best < 0 || us < best) {
+            best = us;
+            best_choice = c;
+            result->kernel = info.kernel;
+            result->tile_m = info.tile_m;
+            result->tile_n = info.tile_n;
+            result->split_k = info.split_k;
+            result->workspace_bytes = info.workspace_bytes;
+            result->chosen_us = us;
+        }
+    }
+    wrote(ctx, C);
+    if (best < 0) return DMATH_ERR_OOM;  // nothing fitted
+    ctx->tuned_gemm[sig] = best_choice;
+    // plans made before for matrices laid out like these were built on the cost model's choice
+    for (auto it = ctx->gemm_plans.begin(); it != ctx->gemm_plans.end();) {
+        const auto& u = it->second->uses;
+        dmath_matrix_s *a = nullptr, *b = nullptr, *c = nullptr;
+        for (dmath_matrix_s* m : ctx->matrices) {
+            if (m->id == u[0]) a = m;
+            if (m->id == u[1]) b = m;
+            if (m->id == u[2]) c = m;
+        }
+        const bool same = a && b && c &&
+                          gemm_signature(std::get<3>(it->first), std::get<4>(it->first), a, b, c) == sig;
+        if (same) {
+            for (uint64_t id : u) drop_pipelines_using(ctx, id);
+            free_gemm_plan(ctx, *it->second);
+            it = ctx->gemm_plans.erase(it);
+        } else
+            ++it;
+    }
+    return DMATH_OK;
+}
+
+dmath_status_t dmath_conv_tune(dmath_ctx_t ctx, int32_t mode, const dmath_conv_desc_t* desc, dmath_matrix_t X,
+                               dmath_matrix_t F, dmath_matrix_t Y, size_t workspace_limit, int32_t trials,
+                               dmath_tune_result_t* result)
+{
+    if (!ctx || !result || trials <= 0 || mode < CONV_FWD || mode > CONV_BWD_DATA || !X || !F || !Y)
+        return DMATH_ERR_INVALID_ARG;
+    dmath_status_t st = check_conv(ctx, mode, desc, X, F, Y);
+    if (st != DMATH_OK) return st;
+    if (ctx->recording || ctx->policy != 0) return DMATH_ERR_UNSUPPORTED;
+    const std::vector<int64_t> sig = conv_signature(mode, desc, X, F, Y);
+    ctx->tuned_conv.erase(sig);
+    // plans of this signature go first: their re-layout copies would otherwise be counted as held
+    auto drop_same = [&] {
+        for (auto it = ctx->conv_plans.begin(); it != ctx->conv_plans.end();) {
+            const auto& u = it->second->uses;
+            dmath_matrix_s *x = nullptr, *f = nullptr, *y = nullptr;
+            for (dmath_matrix_s* m : ctx->matrices) {
+                if (m->id == u[0]) x = m;
+                if (m->id == u[1]) f = m;
+                if (m->id == u[2]) y = m;
+            }
+            const std::vector<int32_t>& gv = std::get<4>(it->first);
+            dmath_conv_desc_t d{gv[0], gv[1], gv[2], gv[3], gv[4], gv[5], gv[6], gv[7], gv[8], gv[9], gv[10]};
+            if (x && f && y && conv_signature(std::get<3>(it->first), &d, x, f, y) == sig) {
+                for (uint64_t id : u) drop_pipelines_using(ctx, id);
+                free_conv_plan(ctx, *it->second);
+                it = ctx->conv_plans.erase(it);
+            } else
+                ++it;
+        }
+    };
+    drop_same();
+    dmath_matrix_s* res = mode == CONV_FWD ? Y : mode == CONV_BWD_FILTER ? F : X;
+    const dmath_dtype_t in_dtype = mode == CONV_FWD ? X->dtype : Y->dtype;
+    std::unique_ptr<ConvPlan> probe;
+    ConvChoice none;
+    st = make_conv_plan(ctx, mode, desc, X, F, Y, &none, &probe);  // generic, unsplit: only for the geometry
+    if (st != DMATH_OK) return st;
+    const ConvGeom g = probe->t.g;
+    free_conv_plan(ctx, *probe);
+    const ConvChoice model = choose_conv(mode, g, in_dtype, ctx->policy);
+    Events ev;
+    if (!ev.ok()) return DMATH_ERR_DEVICE;
+    *result = dmath_tune_result_t{};
+    double best = -1;
+    ConvChoice best_choice;
+    for (const ConvChoice& c : conv_candidates(mode, g, in_dtype, ctx->policy)) {
+        const size_t need = conv_choice_bytes(mode, g, c, in_dtype);
+        if (need > workspace_limit) {
+            ++result->skipped;
+            continue;
+        }
+        std::unique_ptr<ConvPlan> plan;
+        st = make_conv_plan(ctx, mode, desc, X, F, Y, &c, &plan);
+        if (st == DMATH_ERR_OOM) {
+            ++result->skipped;
+            continue;
+        }
+        if (st != DMATH_OK) return st;
+        const double us = sample_us(ctx, ev.e0, ev.e1, trials, [&] {
+            return launch_conv(*plan, mode, 1.0, 0.0, REWRITE_X | REWRITE_F | REWRITE_Y, ctx->stream);
+        });
+        for (Relayout* r : {plan->xp, plan->fp, plan->yt})
+            if (r) r->version = 0;  // written outside the version bookkeeping: never trusted
+        free_conv_plan(ctx, *plan);
+        if (us < 0) return DMATH_ERR_DEVICE;
+        ++result->candidates;
+        if (c.kernel == model.kernel && c.tile_n == model.tile_n && c.split_k == model.split_k)
+            result->default_us = us;
+        if (best < 0 || us < best) {
+            best = us;
+            best_choice = c;
+            result->kernel = c.kernel;
+            result->tile_m = c.kernel == 1 ? 256 : 64;
+            result->tile_n = c.kernel == 1 ? (mode == CONV_BWD_FILTER ? 128 : c.tile_n) : 64;
+            result->split_k = c.split_k;
+            result->workspace_bytes = need;
+            result->chosen_us = us;
+        }
+    }
+    wrote(ctx, res);
+    drop_unused_relayouts(ctx);  // what only a rejected candidate needed goes back to the pool
+    if (best < 0) return DMATH_ERR_OOM;
+    ctx->tuned_conv[sig] = best_choice;
+    return DMATH_OK;
+}
+
+dmath_status_t dmath_tune_reset(dmath_ctx_t ctx)
+{
+    if (!ctx) return DMATH_ERR_INVALID_ARG;
+    if (ctx->recording) return DMATH_ERR_UNSUPPORTED;
+    ctx->tuned_gemm.clear();
+    ctx->tuned_conv.clear();
+    drop_all_plans(ctx);
     return DMATH_OK;
 }
 

@@ -92,7 +92,13 @@ struct ConvPlan {
     Relayout* fp = nullptr;  // permuted filter
     Relayout* yt = nullptr;  // weight gradient: dY channels-last, [n*oh*ow][k]
     int32_t kernel = 0;  // 0 generic, 1 specialised fp16
+    int32_t tile_n = 0;  // specialised forward / data gradient: 128 or 256 output channels per tile
     dmath_dtype_t in_dtype = DMATH_F16, out_dtype = DMATH_F32;
+};
+
+// Kernel / tile / split-K decision for a convolution.
+struct ConvChoice {
+    int32_t kernel = 0, tile_n = 0, split_k = 1;
 };
 
 using GemmKey = std::tuple<uint64_t, uint64_t, uint64_t, int, int>;
@@ -129,6 +135,9 @@ struct dmath_ctx_s {
     // re-layout copies: reused while current unless switched off; the epoch moves at every
     // recording boundary and replay, so nothing is reused across them
     std::map<dm::RelayoutKey, dm::Relayout> relayouts;
+    // choices found by timing samples (dmath_gemm_tune / dmath_conv_tune), by layout signature
+    std::map<std::vector<int64_t>, dm::GemmChoice> tuned_gemm;
+    std::map<std::vector<int64_t>, dm::ConvChoice> tuned_conv;
     bool reuse_relayouts = true;
     uint64_t epoch = 1;
     uint64_t relayouts_reused = 0, relayouts_written = 0;
@@ -148,6 +157,7 @@ void drop_plans_using(dmath_ctx_s* ctx, uint64_t matrix_id);
 void drop_all_plans(dmath_ctx_s* ctx);
 void drop_pipelines_using(dmath_ctx_s* ctx, uint64_t matrix_id);
 void drop_all_pipelines(dmath_ctx_s* ctx);
+void drop_unused_relayouts(dmath_ctx_s* ctx);
 
 // kernels (launch.hip)
 hipError_t launch_gemm(const GemmPlan& p, double alpha, double beta, hipStream_t stream);
@@ -175,5 +185,23 @@ struct SegView {
     int32_t policy;
 };
 GemmChoice choose_gemm(const SegView& v);
+std::vector<GemmChoice> gemm_candidates(const SegView& v);
+// conv_f16.hip / launch.hip: the cost model's choice and everything worth a timing sample
+ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int32_t policy);
+std::vector<ConvChoice> conv_candidates(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int32_t policy);
+// plan.cpp: plans outside the cache, built for one given choice (timing samples)
+dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_matrix_s* A, dmath_matrix_s* B,
+                              dmath_matrix_s* C, bool upload, const GemmChoice* forced,
+                              std::unique_ptr<GemmPlan>* out, std::vector<GemmChoice>* candidates);
+void free_gemm_plan(dmath_ctx_s* ctx, GemmPlan& p);
+dmath_status_t make_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t* d, dmath_matrix_s* X,
+                              dmath_matrix_s* F, dmath_matrix_s* Y, const ConvChoice* forced,
+                              std::unique_ptr<ConvPlan>* out);
+void free_conv_plan(dmath_ctx_s* ctx, ConvPlan& p);
+std::vector<int64_t> gemm_signature(int transA, int transB, const dmath_matrix_s* A, const dmath_matrix_s* B,
+                                    const dmath_matrix_s* C);
+std::vector<int64_t> conv_signature(int mode, const dmath_conv_desc_t* d, const dmath_matrix_s* X,
+                                    const dmath_matrix_s* F, const dmath_matrix_s* Y);
+size_t conv_choice_bytes(int mode, const ConvGeom& g, const ConvChoice& c, dmath_dtype_t in_dtype);
 
 }  // namespace dm

@@ -20,8 +20,10 @@
 // copies and the version of the matrix each was made from); otherwise it is part of the call.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdlib>
 #include <cstring>
+#include <vector>
 
 #include "context.hpp"
 #include "f16_pipeline.hpp"
@@ -380,6 +382,79 @@ int conv_f16_wgrad_split(const ConvGeom& g)
     return best;
 }
 
+// Generic weight gradient: few C tiles and a very deep K.
+static int32_t generic_wgrad_split(const ConvGeom& g)
+{
+    const int64_t M = g.k, N = (int64_t)g.c * g.r * g.s, K = (int64_t)g.n * g.oh * g.ow;
+    const int64_t tiles = ((M + 63) / 64) * ((N + 63) / 64);
+    const int64_t want = std::max<int64_t>(1, 1024 / std::max<int64_t>(1, tiles));
+    const int64_t max_by_k = std::max<int64_t>(1, K / 512);
+    return (int32_t)std::min<int64_t>({want, max_by_k, 64});
+}
+
+// The cost model: the specialised kernels wherever their preconditions hold; forward and data
+// gradient on 256x128 tiles unless those would need a second, mostly empty round of workgroups
+// while 256x256 tiles fit in one.
+ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int32_t policy)
+{
+    ConvChoice ch;
+    if (policy != 0 || !conv_f16_fast_ok(mode, g, in_dtype)) {
+        if (mode == CONV_BWD_FILTER) ch.split_k = generic_wgrad_split(g);
+        return ch;
+    }
+    ch.kernel = 1;
+    if (mode == CONV_BWD_FILTER) {
+        ch.split_k = conv_f16_wgrad_split(g);
+        return ch;
+    }
+    const int64_t m = mode == CONV_FWD ? (int64_t)g.n * g.oh * g.ow : (int64_t)g.n * g.h * g.w;
+    const int n_out = mode == CONV_FWD ? g.k : g.c;
+    const int64_t t128 = m / 256 * (n_out / 128), t256 = m / 256 * (n_out / 256);
+    bool wide = n_out % 256 == 0 && t128 > 256 && t256 <= 256;
+    if (const char* force = std::getenv("DMATH_CONV_TILE")) wide = n_out % 256 == 0 && std::strcmp(force, "256x256") == 0;
+    ch.tile_n = wide ? 256 : 128;
+    return ch;
+}
+
+// Everything worth a timing sample: the generic kernel (weight gradient: unsplit and with its
+// own split), and where the specialised kernels apply, both tile widths (forward, data
+// gradient) or every split count that divides the k-tiles evenly, keeps at least 8 of them per
+// part and at most two rounds of workgroups (weight gradient).
+std::vector<ConvChoice> conv_candidates(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int32_t policy)
+{
+    std::vector<ConvChoice> out;
+    ConvChoice c;
+    out.push_back(c);
+    if (mode == CONV_BWD_FILTER && generic_wgrad_split(g) > 1) {
+        c.split_k = generic_wgrad_split(g);
+        out.push_back(c);
+    }
+    if (policy != 0 || !conv_f16_fast_ok(mode, g, in_dtype)) return out;
+    c = ConvChoice{};
+    c.kernel = 1;
+    if (mode == CONV_BWD_FILTER) {
+        const int64_t ktiles = (int64_t)g.n * g.oh * g.ow / 64, tiles = (int64_t)g.c * g.r * g.s / 128;
+        for (int s = 1; s <= 64; ++s)
+            if (ktiles % s == 0 && tiles * s <= 512 && ktiles / s >= 8) {
+                c.split_k = s;
+                out.push_back(c);
+            }
+        if (out.back().kernel != 1) {  // no split passes the filter: the cost model's own
+            c.split_k = conv_f16_wgrad_split(g);
+            out.push_back(c);
+        }
+        return out;
+    }
+    const int n_out = mode == CONV_FWD ? g.k : g.c;
+    c.tile_n = 128;
+    out.push_back(c);
+    if (n_out % 256 == 0) {
+        c.tile_n = 256;
+        out.push_back(c);
+    }
+    return out;
+}
+
 hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double beta, unsigned rewrite,
                            hipStream_t st)
 {
@@ -401,6 +476,9 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
     p.split = t.split_k;
     if (!xp || (mode != CONV_BWD_FILTER && !fp) || (mode == CONV_BWD_FILTER && (!yt || !p.ws)))
         return hipErrorInvalidValue;  // the plan was not made for this path
+    const int n_out = mode == CONV_BWD_DATA ? g.c : g.k;
+    if (mode != CONV_BWD_FILTER && !(plan.tile_n == 128 || (plan.tile_n == 256 && n_out % 256 == 0)))
+        return hipErrorInvalidValue;
 
     static bool configured = false;
     if (!configured) {
@@ -432,7 +510,7 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
             filter_to_rsk_rotated_kernel<<<512, 256, 0, st>>>(t.f_rows, g.c, g.r, g.s, g.k, fp);
         const int mt = (int)((int64_t)g.n * g.h * g.w / 256);
         const int t128 = mt * (g.c / 128), t256 = mt * (g.c / 256);
-        const bool wide = g.c % 256 == 0 && t128 > 256 && t256 <= 256;
+        const bool wide = plan.tile_n == 256;
         if (wide) {
             if (plan.out_dtype == DMATH_F16)
                 conv_fwd_f16_kernel<256, 256, 2, _Float16><<<t256, NT, 2 * 512 * 128, st>>>(q, (float)alpha, (float)beta);
@@ -454,13 +532,9 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
     }
     if (mode == CONV_FWD) {
         if (rewrite & REWRITE_F) filter_to_rsc_kernel<<<512, 256, 0, st>>>(t.f_rows, g.c, g.r * g.s, g.k, fp);
-        // 256x128 tiles unless they would need a second, mostly empty round of workgroups while
-        // 256x256 tiles fit in one
         const int mt = (int)((int64_t)g.n * g.oh * g.ow / 256);
         const int t128 = mt * (g.k / 128), t256 = mt * (g.k / 256);
-        const char* force = std::getenv("DMATH_CONV_TILE");
-        bool wide = g.k % 256 == 0 && t128 > 256 && t256 <= 256;
-        if (force) wide = g.k % 256 == 0 && std::strcmp(force, "256x256") == 0;
+        const bool wide = plan.tile_n == 256;
         if (wide) {
             if (plan.out_dtype == DMATH_F16)
                 conv_fwd_f16_kernel<256, 256, 2, _Float16><<<t256, NT, 2 * 512 * 128, st>>>(p, (float)alpha, (float)beta);

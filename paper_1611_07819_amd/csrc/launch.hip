@@ -54,72 +54,102 @@ bool env_tile(int* bm, int* bn)
 
 }  // namespace
 
+namespace {
+
+struct Shape {
+    int32_t kernel, bm, bn, bk;
+};
+
+// Tile shapes of the specialised kernels whose preconditions this GEMM meets.
+std::vector<Shape> specialised_shapes(const SegView& v)
+{
+    std::vector<Shape> out;
+    if (v.policy != 0 || !v.aligned16) return out;
+    const bool f32 = v.in_dtype == DMATH_F32 && all_multiple(*v.klen, 32);
+    const bool f64 = v.in_dtype == DMATH_F64 && all_multiple(*v.klen, 16);
+    const bool f16 = v.in_dtype == DMATH_F16 && all_multiple(*v.klen, 64);
+    if (f32 || f64) {
+        const int32_t kern = f32 ? KERNEL_F32_128 : KERNEL_F64_128, bk = f32 ? 32 : 16;
+        out.push_back({kern, 128, 128, bk});
+        out.push_back({kern, 128, 64, bk});
+        if (f32 && v.b_kcontig) out.push_back({kern, 128, 96, bk});  // wavefronts 4x1, k-major B only
+    }
+    if (f16) {
+        out.push_back({KERNEL_F16_256, 256, 256, 64});
+        out.push_back({KERNEL_F16_256, 256, 128, 64});
+        out.push_back({KERNEL_F16_256, 128, 128, 64});
+    }
+    return out;
+}
+
+// Generic kernel.  Few C tiles and a deep K: split K so that the chip is filled.
+int32_t generic_split(const SegView& v)
+{
+    const int64_t tiles = count_tiles(v, 64, 64);
+    if (tiles >= 128 || v.K < 2048) return 1;
+    const int64_t want = (512 + tiles - 1) / tiles, max_by_k = v.K / 512;
+    return (int32_t)std::max<int64_t>(1, std::min<int64_t>({want, max_by_k, 32}));
+}
+
+}  // namespace
+
+// The cost model: among the specialised shapes the one with the least serialised work per CU.
+// fp32: smaller tiles move more bytes per flop, which costs clock at the power limit: 3 %
+// handicap (measured on configuration 2: 128x128 beats 128x64 when both fill the chip evenly).
+// fp64: 128x64 runs two workgroups per CU and is faster on configuration 4, so there the larger
+// tile carries the handicap.  Ragged last tiles count as whole ones.
 GemmChoice choose_gemm(const SegView& v)
 {
     GemmChoice ch;  // generic 64x64x16
-    const bool f32 = v.in_dtype == DMATH_F32 && all_multiple(*v.klen, 32);
-    const bool f64 = v.in_dtype == DMATH_F64 && all_multiple(*v.klen, 16);
-    if (v.policy == 0 && v.aligned16 && (f32 || f64)) {
-        // Candidate shapes; take the one with the least serialised work per CU.  fp32: smaller
-        // tiles move more bytes per flop, which costs clock at the power limit: 3 % handicap
-        // (measured on configuration 2: 128x128 beats 128x64 when both fill the chip evenly).
-        // fp64: the register-staged kernel runs two 128x64 workgroups per CU and is 14 % faster
-        // that way on configuration 4, so there the larger tile carries the handicap.
-        struct Shape {
-            int bm, bn;
-            bool needs_b_kcontig, f32_only;
-        };
-        const Shape shapes[] = {{128, 128, false, false}, {128, 64, false, false}, {128, 96, true, true}};
-        double best_cost = -1;
-        int ebm = 0, ebn = 0;
-        const bool forced = env_tile(&ebm, &ebn);
-        for (auto& s : shapes) {
-            if (forced && (s.bm != ebm || s.bn != ebn)) continue;
-            if ((s.needs_b_kcontig && !v.b_kcontig) || (s.f32_only && !f32)) continue;
-            int64_t tiles = count_tiles(v, s.bm, s.bn);  // ragged last tiles count as whole ones
-            double cost = (double)((tiles + kCUs - 1) / kCUs) * s.bm * s.bn;
-            if (f32 && s.bm * s.bn < 128 * 128) cost *= 1.03;
-            if (f64 && s.bm * s.bn >= 128 * 128) cost *= 1.03;
-            if (best_cost < 0 || cost < best_cost) {
-                best_cost = cost;
-                ch.kernel = f32 ? KERNEL_F32_128 : KERNEL_F64_128;
-                ch.tile_m = s.bm;
-                ch.tile_n = s.bn;
-                ch.tile_k = f32 ? 32 : 16;
-                ch.split_k = split_for(tiles, v.K);
-            }
+    double best_cost = -1;
+    int ebm = 0, ebn = 0;
+    const bool forced = env_tile(&ebm, &ebn);
+    for (const Shape& s : specialised_shapes(v)) {
+        if (forced && (s.bm != ebm || s.bn != ebn)) continue;
+        const int64_t tiles = count_tiles(v, s.bm, s.bn);
+        double cost = (double)((tiles + kCUs - 1) / kCUs) * s.bm * s.bn;
+        if (s.kernel == KERNEL_F32_128 && s.bm * s.bn < 128 * 128) cost *= 1.03;
+        if (s.kernel == KERNEL_F64_128 && s.bm * s.bn >= 128 * 128) cost *= 1.03;
+        if (best_cost < 0 || cost < best_cost) {
+            best_cost = cost;
+            ch.kernel = s.kernel;
+            ch.tile_m = s.bm;
+            ch.tile_n = s.bn;
+            ch.tile_k = s.bk;
+            ch.split_k = split_for(tiles, v.K);
         }
-        if (ch.kernel != KERNEL_GENERIC) return ch;
     }
-    if (v.policy == 0 && v.aligned16 && v.in_dtype == DMATH_F16 && all_multiple(*v.klen, 64)) {
-        const int shapes[][2] = {{256, 256}, {256, 128}, {128, 128}};
-        int64_t best_cost = -1;
-        int ebm = 0, ebn = 0;
-        const bool forced = env_tile(&ebm, &ebn);
-        for (auto& s : shapes) {
-            if (forced && (s[0] != ebm || s[1] != ebn)) continue;
-            int64_t tiles = count_tiles(v, s[0], s[1]);
-            int64_t cost = ((tiles + kCUs - 1) / kCUs) * s[0] * s[1];
-            if (best_cost < 0 || cost < best_cost) {
-                best_cost = cost;
-                ch.kernel = KERNEL_F16_256;
-                ch.tile_m = s[0];
-                ch.tile_n = s[1];
-                ch.tile_k = 64;
-                ch.split_k = split_for(tiles, v.K);
-            }
-        }
-        if (ch.kernel != KERNEL_GENERIC) return ch;
-    }
-    // Generic kernel.  Few C tiles and a deep K: split K so that the chip is filled.  The
-    // partial sums are reduced in a fixed order by a second kernel.
-    int64_t tiles = count_tiles(v, ch.tile_m, ch.tile_n);
-    if (tiles < 128 && v.K >= 2048) {
-        int64_t want = (512 + tiles - 1) / tiles;
-        int64_t max_by_k = v.K / 512;
-        ch.split_k = (int32_t)std::max<int64_t>(1, std::min<int64_t>({want, max_by_k, 32}));
-    }
+    if (ch.kernel == KERNEL_GENERIC) ch.split_k = generic_split(v);
     return ch;
+}
+
+// Every configuration worth a timing sample: each shape unsplit, with the cost model's split,
+// and with the power-of-two splits that keep at least 512 of K per part and at most two rounds
+// of workgroups; the generic kernel unsplit and with its own split.
+std::vector<GemmChoice> gemm_candidates(const SegView& v)
+{
+    std::vector<GemmChoice> out;
+    auto add = [&](int32_t kernel, int bm, int bn, int bk, int32_t split) {
+        for (const GemmChoice& c : out)
+            if (c.kernel == kernel && c.tile_m == bm && c.tile_n == bn && c.split_k == split) return;
+        GemmChoice c;
+        c.kernel = kernel;
+        c.tile_m = bm;
+        c.tile_n = bn;
+        c.tile_k = bk;
+        c.split_k = split;
+        out.push_back(c);
+    };
+    for (const Shape& s : specialised_shapes(v)) {
+        const int64_t tiles = count_tiles(v, s.bm, s.bn);
+        add(s.kernel, s.bm, s.bn, s.bk, 1);
+        add(s.kernel, s.bm, s.bn, s.bk, split_for(tiles, v.K));
+        for (int32_t sp = 2; sp <= 32; sp *= 2)
+            if (v.K / sp >= 512 && tiles * sp <= 2 * kCUs) add(s.kernel, s.bm, s.bn, s.bk, sp);
+    }
+    add(KERNEL_GENERIC, 64, 64, 16, 1);
+    add(KERNEL_GENERIC, 64, 64, 16, generic_split(v));
+    return out;
 }
 
 hipError_t launch_gemm(const GemmPlan& p, double alpha, double beta, hipStream_t st)

@@ -78,7 +78,7 @@ std::vector<Tile> xcd_interleave(const std::vector<Tile>& logical)
 
 }  // namespace
 
-static void free_conv_plan(dmath_ctx_s* ctx, ConvPlan& p)
+void free_conv_plan(dmath_ctx_s* ctx, ConvPlan& p)
 {
     for (void** q : {&p.dev_tables, &p.workspace})
         if (*q) {
@@ -112,6 +112,21 @@ static void drop_relayouts_of(dmath_ctx_s* ctx, uint64_t id)
 {
     for (auto it = ctx->relayouts.begin(); it != ctx->relayouts.end();)
         if (std::get<0>(it->first) == id) {
+            ctx->pool.free(it->second.buf);
+            it = ctx->relayouts.erase(it);
+        } else
+            ++it;
+}
+
+// Copies that no plan reads any more (their plans were replaced) give their memory back.
+void drop_unused_relayouts(dmath_ctx_s* ctx)
+{
+    std::set<const Relayout*> used;
+    for (auto& kv : ctx->conv_plans)
+        for (const Relayout* r : {kv.second->xp, kv.second->fp, kv.second->yt})
+            if (r) used.insert(r);
+    for (auto it = ctx->relayouts.begin(); it != ctx->relayouts.end();)
+        if (!used.count(&it->second)) {
             ctx->pool.free(it->second.buf);
             it = ctx->relayouts.erase(it);
         } else
@@ -180,6 +195,26 @@ static hipError_t upload(dmath_ctx_s* ctx, void* dst, const std::vector<char>& b
     return hipStreamSynchronize(ctx->stream);  // buf is pageable and about to go away
 }
 
+// What the choice of kernel depends on besides the device addresses: ops, precisions, shapes
+// and block grids.  Choices found by timing samples are stored under this key, so that they
+// serve every set of matrices laid out the same way.
+std::vector<int64_t> gemm_signature(int transA, int transB, const dmath_matrix_s* A, const dmath_matrix_s* B,
+                                    const dmath_matrix_s* C)
+{
+    std::vector<int64_t> sig{transA, transB};
+    for (const dmath_matrix_s* m : {A, B, C})
+        for (int64_t x : {(int64_t)m->dtype, m->rows, m->cols, (int64_t)m->rsplit.g, (int64_t)m->csplit.g})
+            sig.push_back(x);
+    return sig;
+}
+
+void free_gemm_plan(dmath_ctx_s* ctx, GemmPlan& p)
+{
+    if (p.dev_tables) ctx->pool.free(p.dev_tables);
+    if (p.workspace) ctx->pool.free(p.workspace);
+    p.dev_tables = p.workspace = nullptr;
+}
+
 dmath_status_t get_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_matrix_s* A,
                              dmath_matrix_s* B, dmath_matrix_s* C, bool do_upload, GemmPlan** out,
                              bool* was_cached)
@@ -194,7 +229,21 @@ dmath_status_t get_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_mat
     if (was_cached) *was_cached = false;
     if (do_upload && ctx->recording) return DMATH_ERR_UNSUPPORTED;  // uploading synchronises
     if (found != ctx->gemm_plans.end()) ctx->gemm_plans.erase(found);  // described, never uploaded
+    const GemmChoice* forced = nullptr;
+    auto tuned = ctx->tuned_gemm.find(gemm_signature(transA, transB, A, B, C));
+    if (tuned != ctx->tuned_gemm.end() && ctx->policy == 0) forced = &tuned->second;
+    std::unique_ptr<GemmPlan> plan;
+    dmath_status_t st = make_gemm_plan(ctx, transA, transB, A, B, C, do_upload, forced, &plan, nullptr);
+    if (st != DMATH_OK) return st;
+    *out = plan.get();
+    ctx->gemm_plans[key] = std::move(plan);
+    return DMATH_OK;
+}
 
+dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_matrix_s* A, dmath_matrix_s* B,
+                              dmath_matrix_s* C, bool do_upload, const GemmChoice* forced,
+                              std::unique_ptr<GemmPlan>* out, std::vector<GemmChoice>* candidates)
+{
     const int64_t M = C->rows, N = C->cols, K = transA ? A->rows : A->cols;
     const Split& a_m = transA ? A->csplit : A->rsplit;
     const Split& a_k = transA ? A->rsplit : A->csplit;
@@ -230,7 +279,8 @@ dmath_status_t get_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_mat
     for (auto& s : ks) klen.push_back(s.len);
     SegView view{M, N, K, &mlen, &nlen, &klen, !transA, (bool)transB, al, A->dtype, C->dtype,
                  ctx->policy};
-    GemmChoice ch = choose_gemm(view);
+    GemmChoice ch = forced ? *forced : choose_gemm(view);
+    if (candidates) *candidates = gemm_candidates(view);
 
     // split-K: extra cuts of the k axis at multiples of 64 (every kernel's k-step divides 64)
     std::vector<int64_t> split_cuts;
@@ -371,8 +421,7 @@ dmath_status_t get_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_mat
         plan->dev_tables = dev;
         plan->workspace = ws;
     }
-    *out = plan.get();
-    ctx->gemm_plans[key] = std::move(plan);
+    *out = std::move(plan);
     return DMATH_OK;
 }
 
@@ -389,14 +438,65 @@ dmath_status_t get_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t
         return DMATH_OK;
     }
     if (ctx->recording) return DMATH_ERR_UNSUPPORTED;  // building a plan synchronises
-    auto plan = std::make_unique<ConvPlan>();
-    plan->uses = {X->id, F->id, Y->id};
-    ConvTables& t = plan->t;
-    ConvGeom& g = t.g;
+    const ConvChoice* forced = nullptr;
+    auto tuned = ctx->tuned_conv.find(conv_signature(mode, d, X, F, Y));
+    if (tuned != ctx->tuned_conv.end() && ctx->policy == 0) forced = &tuned->second;
+    std::unique_ptr<ConvPlan> plan;
+    dmath_status_t st = make_conv_plan(ctx, mode, d, X, F, Y, forced, &plan);
+    if (st != DMATH_OK) return st;
+    *out = plan.get();
+    ctx->conv_plans[key] = std::move(plan);
+    return DMATH_OK;
+}
+
+std::vector<int64_t> conv_signature(int mode, const dmath_conv_desc_t* d, const dmath_matrix_s* X,
+                                    const dmath_matrix_s* F, const dmath_matrix_s* Y)
+{
+    std::vector<int64_t> sig{mode, d->n, d->c, d->h, d->w, d->k, d->r, d->s,
+                             d->pad_h, d->pad_w, d->stride_h, d->stride_w};
+    for (const dmath_matrix_s* m : {X, F, Y})
+        for (int64_t x : {(int64_t)m->dtype, (int64_t)m->rsplit.g}) sig.push_back(x);
+    return sig;
+}
+
+static ConvGeom geometry_of(const dmath_conv_desc_t* d)
+{
+    ConvGeom g;
     g.n = d->n; g.c = d->c; g.h = d->h; g.w = d->w; g.k = d->k; g.r = d->r; g.s = d->s;
     g.pad_h = d->pad_h; g.pad_w = d->pad_w; g.stride_h = d->stride_h; g.stride_w = d->stride_w;
     g.oh = (d->h + 2 * d->pad_h - d->r) / d->stride_h + 1;
     g.ow = (d->w + 2 * d->pad_w - d->s) / d->stride_w + 1;
+    return g;
+}
+
+// Pool memory a choice needs beyond the tensors: split-K partial sums and, for the specialised
+// kernels, the re-layout copies they read.
+size_t conv_choice_bytes(int mode, const ConvGeom& g, const ConvChoice& c, dmath_dtype_t in_dtype)
+{
+    const size_t sp_out = (size_t)g.oh * g.ow, crs = (size_t)g.c * g.r * g.s;
+    size_t bytes = 0;
+    if (mode == CONV_BWD_FILTER && (c.split_k > 1 || c.kernel == 1))
+        bytes += (size_t)c.split_k * g.k * crs * (in_dtype == DMATH_F64 ? 8 : 4);
+    if (c.kernel == 1) {
+        const size_t pph = g.r - 1 - g.pad_h, ppw = g.s - 1 - g.pad_w;
+        if (mode == CONV_BWD_DATA)
+            bytes += (size_t)g.n * (g.oh + 2 * pph) * (g.ow + 2 * ppw) * g.k * 2 + (size_t)g.k * crs * 2;
+        else
+            bytes += (size_t)g.n * (g.h + 2 * g.pad_h) * (g.w + 2 * g.pad_w) * g.c * 2 +
+                     (mode == CONV_FWD ? (size_t)g.k * crs * 2 : (size_t)g.n * sp_out * g.k * 2);
+    }
+    return bytes;
+}
+
+dmath_status_t make_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t* d, dmath_matrix_s* X,
+                              dmath_matrix_s* F, dmath_matrix_s* Y, const ConvChoice* forced,
+                              std::unique_ptr<ConvPlan>* out)
+{
+    auto plan = std::make_unique<ConvPlan>();
+    plan->uses = {X->id, F->id, Y->id};
+    ConvTables& t = plan->t;
+    ConvGeom& g = t.g;
+    g = geometry_of(d);
     const int64_t sp_out = (int64_t)g.oh * g.ow, sp_in = (int64_t)g.h * g.w;
     const int64_t crs = (int64_t)g.c * g.r * g.s;
     dmath_matrix_s* result = nullptr;
@@ -414,20 +514,11 @@ dmath_status_t get_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t
     plan->in_dtype = (mode == CONV_FWD) ? X->dtype : Y->dtype;
     plan->out_dtype = result->dtype;
 
-    const bool fast = ctx->policy == 0 && conv_f16_fast_ok(mode, g, plan->in_dtype);
-    plan->kernel = fast ? 1 : 0;
-    // split-K for the weight gradient: few C tiles, very deep K
-    t.split_k = 1;
-    if (mode == CONV_BWD_FILTER) {
-        if (fast) {
-            t.split_k = conv_f16_wgrad_split(g);
-        } else {
-            int64_t tiles = ((t.M + 63) / 64) * ((t.N + 63) / 64);
-            int64_t want = std::max<int64_t>(1, 1024 / std::max<int64_t>(1, tiles));
-            int64_t max_by_k = std::max<int64_t>(1, t.K / 512);
-            t.split_k = (int32_t)std::min<int64_t>({want, max_by_k, 64});
-        }
-    }
+    const ConvChoice ch = forced ? *forced : choose_conv(mode, g, plan->in_dtype, ctx->policy);
+    const bool fast = ch.kernel == 1;
+    plan->kernel = ch.kernel;
+    plan->tile_n = ch.tile_n;
+    t.split_k = ch.split_k;  // weight gradient only: few C tiles, very deep K
 
     auto row_ptrs = [](const dmath_matrix_s* m) {
         std::vector<const void*> v((size_t)m->rows);
@@ -492,8 +583,7 @@ dmath_status_t get_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t
     t.workspace = ws;
     plan->dev_tables = dev;
     plan->workspace = ws;
-    *out = plan.get();
-    ctx->conv_plans[key] = std::move(plan);
+    *out = std::move(plan);
     return DMATH_OK;
 }
 

@@ -24,6 +24,16 @@ class DmathError(RuntimeError):
         super().__init__(f"{where}: {status_string(code)}")
 
 
+class _TuneResult(ctypes.Structure):
+    _fields_ = [("candidates", ctypes.c_int32), ("skipped", ctypes.c_int32), ("kernel", ctypes.c_int32),
+                ("tile_m", ctypes.c_int32), ("tile_n", ctypes.c_int32), ("split_k", ctypes.c_int32),
+                ("workspace_bytes", ctypes.c_uint64), ("chosen_us", ctypes.c_double),
+                ("default_us", ctypes.c_double)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
 class _PlanInfo(ctypes.Structure):
     _fields_ = [("m", ctypes.c_int64), ("n", ctypes.c_int64), ("k", ctypes.c_int64),
                 ("m_segments", ctypes.c_int32), ("n_segments", ctypes.c_int32),
@@ -89,6 +99,9 @@ def load_library(build_if_missing: bool = True):
         "dmath_conv_bwd_filter": [vp, P(_ConvDesc), dbl, vp, vp, dbl, vp],
         "dmath_conv_bwd_data": [vp, P(_ConvDesc), dbl, vp, vp, dbl, vp],
         "dmath_set_kernel_policy": [vp, i32],
+        "dmath_gemm_tune": [vp, ctypes.c_int, ctypes.c_int, vp, vp, vp, sz, i32, P(_TuneResult)],
+        "dmath_conv_tune": [vp, i32, P(_ConvDesc), vp, vp, vp, sz, i32, P(_TuneResult)],
+        "dmath_tune_reset": [vp],
         "dmath_set_relayout_reuse": [vp, i32],
         "dmath_relayout_stats": [vp, P(ctypes.c_uint64), P(ctypes.c_uint64), P(sz)],
         "dmath_matrix_touch": [vp],
@@ -146,6 +159,9 @@ class Context:
 
     def set_kernel_policy(self, policy: int):
         _check(self._lib.dmath_set_kernel_policy(self._h, policy), "dmath_set_kernel_policy")
+
+    def tune_reset(self):
+        _check(self._lib.dmath_tune_reset(self._h), "dmath_tune_reset")
 
     def set_relayout_reuse(self, enable: bool):
         _check(self._lib.dmath_set_relayout_reuse(self._h, 1 if enable else 0), "dmath_set_relayout_reuse")
@@ -272,3 +288,20 @@ def conv_bwd_data(ctx: Context, desc: ConvDesc, alpha, dY: Matrix, F: Matrix, be
     d = desc._c()
     _check(ctx._lib.dmath_conv_bwd_data(ctx._h, ctypes.byref(d), float(alpha), dY._h, F._h,
                                         float(beta), dX._h), "dmath_conv_bwd_data")
+
+
+def gemm_tune(ctx: Context, transA, transB, A: Matrix, B: Matrix, C: Matrix, workspace_limit: int,
+              trials: int = 5) -> dict:
+    r = _TuneResult()
+    _check(ctx._lib.dmath_gemm_tune(ctx._h, int(transA), int(transB), A._h, B._h, C._h,
+                                    int(workspace_limit), int(trials), ctypes.byref(r)), "dmath_gemm_tune")
+    return r.as_dict()
+
+
+def conv_tune(ctx: Context, mode: int, desc: ConvDesc, X: Matrix, F: Matrix, Y: Matrix,
+              workspace_limit: int, trials: int = 5) -> dict:
+    r = _TuneResult()
+    d = desc._c()
+    _check(ctx._lib.dmath_conv_tune(ctx._h, int(mode), ctypes.byref(d), X._h, F._h, Y._h,
+                                    int(workspace_limit), int(trials), ctypes.byref(r)), "dmath_conv_tune")
+    return r.as_dict()
