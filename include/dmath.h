@@ -232,8 +232,9 @@ dmath_status_t dmath_matrix_touch(dmath_matrix_t m);
  * Selection from timing samples (section 4.1: at start-up the library picks the convolution
  * algorithm from timing samples within the system's memory constraints).  Without tuning, the
  * kernel family, tile shape and split-K count come from a cost model.  The tuners time every
- * configuration the operation admits on the given handles (one warm-up launch, then `trials`
- * launches between two events; the call blocks), leave out those that need more pool memory
+ * configuration the operation admits on the given handles (3 ms of warm-up launches, 20 ms before the first sample, then
+ * `trials` launches between two events; the call blocks; a configuration replaces the cost
+ * model's choice only if it is more than 2 % faster), leave out those that need more pool memory
  * beyond the operands than `workspace_limit` bytes (split-K partial sums; for convolutions also
  * the re-layout copies the specialised kernels read) or than the pool can give, and remember the
  * fastest under the operation's layout signature (ops, precisions, shapes, block grids,

@@ -95,7 +95,9 @@ int32_t generic_split(const SegView& v)
 
 // The cost model: among the specialised shapes the one with the least serialised work per CU.
 // fp32: smaller tiles move more bytes per flop, which costs clock at the power limit: 3 %
-// handicap (measured on configuration 2: 128x128 beats 128x64 when both fill the chip evenly).
+// handicap (measured on configuration 2: 128x128 beats 128x64 when both fill the chip evenly),
+// except when neither operand is k unit-stride (TN): there every fragment is a 4-byte LDS read
+// per MFMA, two 128x64 workgroups per CU hide those better and win by 2 %.
 // fp64: 128x64 runs two workgroups per CU and is faster on configuration 4, so there the larger
 // tile carries the handicap.  Ragged last tiles count as whole ones.
 GemmChoice choose_gemm(const SegView& v)
@@ -108,7 +110,8 @@ GemmChoice choose_gemm(const SegView& v)
         if (forced && (s.bm != ebm || s.bn != ebn)) continue;
         const int64_t tiles = count_tiles(v, s.bm, s.bn);
         double cost = (double)((tiles + kCUs - 1) / kCUs) * s.bm * s.bn;
-        if (s.kernel == KERNEL_F32_128 && s.bm * s.bn < 128 * 128) cost *= 1.03;
+        const bool f32_strided = !v.a_kcontig && !v.b_kcontig;
+        if (s.kernel == KERNEL_F32_128 && (s.bm * s.bn < 128 * 128) != f32_strided) cost *= 1.03;
         if (s.kernel == KERNEL_F64_128 && s.bm * s.bn >= 128 * 128) cost *= 1.03;
         if (best_cost < 0 || cost < best_cost) {
             best_cost = cost;
