@@ -181,6 +181,7 @@ struct SegView {
     const std::vector<int64_t>* klen;
     bool a_kcontig, b_kcontig;
     bool aligned16;  // every panel origin and leading dimension is a multiple of 16 bytes
+    bool offsets32;  // every block of A and B is smaller than 4 GiB (the kernels' 32-bit lane offsets)
     dmath_dtype_t in_dtype, out_dtype;
     int32_t policy;
 };

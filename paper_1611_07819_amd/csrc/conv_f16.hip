@@ -355,6 +355,12 @@ bool conv_f16_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype)
 {
     if (in_dtype != DMATH_F16 || g.stride_h != 1 || g.stride_w != 1) return false;
     const int64_t sp_out = (int64_t)g.oh * g.ow, m = (int64_t)g.n * sp_out;
+    // 32-bit lane offsets into the re-layout copies: each copy has to stay below 4 GiB
+    const int64_t pph = g.r - 1 - g.pad_h, ppw = g.s - 1 - g.pad_w, limit = 1ll << 32;
+    const int64_t copy_x = (int64_t)g.n * (g.h + 2 * g.pad_h) * (g.w + 2 * g.pad_w) * g.c * 2;
+    const int64_t copy_dy = (int64_t)g.n * (g.oh + 2 * pph) * (g.ow + 2 * ppw) * g.k * 2;
+    const int64_t copy_f = (int64_t)g.k * g.c * g.r * g.s * 2;
+    if (copy_f >= limit || (mode == CONV_BWD_DATA ? copy_dy : copy_x) >= limit || m * g.k * 2 >= limit) return false;
     if (mode != CONV_BWD_DATA &&
         (g.c % 64 || (g.h * g.w) % 8 || (int64_t)64 * tcl_stride(g.h * g.w) * 2 > 150 * 1024))
         return false;

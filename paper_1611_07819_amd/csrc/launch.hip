@@ -64,7 +64,7 @@ struct Shape {
 std::vector<Shape> specialised_shapes(const SegView& v)
 {
     std::vector<Shape> out;
-    if (v.policy != 0 || !v.aligned16) return out;
+    if (v.policy != 0 || !v.aligned16 || !v.offsets32) return out;
     const bool f32 = v.in_dtype == DMATH_F32 && all_multiple(*v.klen, 32);
     const bool f64 = v.in_dtype == DMATH_F64 && all_multiple(*v.klen, 16);
     const bool f16 = v.in_dtype == DMATH_F16 && all_multiple(*v.klen, 64);

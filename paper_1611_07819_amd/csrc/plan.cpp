@@ -277,7 +277,10 @@ dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_ma
     for (auto& s : ms) mlen.push_back(s.len);
     for (auto& s : ns) nlen.push_back(s.len);
     for (auto& s : ks) klen.push_back(s.len);
-    SegView view{M, N, K, &mlen, &nlen, &klen, !transA, (bool)transB, al, A->dtype, C->dtype,
+    bool small = true;  // the specialised kernels address a block through 32-bit byte offsets
+    for (const dmath_matrix_s* m : {A, B})
+        small = small && (uint64_t)m->rsplit.step * (uint64_t)m->csplit.step * elem_size(m->dtype) < (1ull << 32);
+    SegView view{M, N, K, &mlen, &nlen, &klen, !transA, (bool)transB, al, small, A->dtype, C->dtype,
                  ctx->policy};
     GemmChoice ch = forced ? *forced : choose_gemm(view);
     if (candidates) *candidates = gemm_candidates(view);

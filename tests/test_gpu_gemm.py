@@ -375,3 +375,33 @@ def test_specialised_kernels_on_ragged_tiles(ctx, oracle, dt, out, ta, tb):
         assert np.array_equal(guard.get(), np.full((4, 64), 7, NP[out]))
         for m in (dA, dB, dC, guard):
             m.destroy()
+
+
+def test_block_beyond_4_gib_is_addressed_in_64_bits(ctx, oracle):
+    """One block of B holds 4.6 GB: beyond the 32-bit lane offsets of the specialised kernels, so
+    the plan must fall back to the kernel that indexes in 64 bits.  Small-integer data: rows of
+    the result checked bit for bit, including k rows of B that lie beyond the 4 GiB mark."""
+    M, K, N = 64, 8192, 278528
+    assert K * N * 2 > 1 << 32
+    A = ((np.arange(M * K, dtype=np.int64).reshape(M, K) * 7 + 3) % 5 - 2).astype(np.float16)
+    B = np.empty((K, N), np.float16)
+    col = (np.arange(N, dtype=np.int64) % 3 - 1).astype(np.float16)
+    for k0 in range(0, K, 1024):                       # built in slices: no 18 GB int64 temporary
+        kk = np.arange(k0, k0 + 1024, dtype=np.int64)
+        B[k0:k0 + 1024] = ((kk % 4) - 1).astype(np.float16)[:, None] * col[None, :]
+    ctx.set_kernel_policy(0)
+    dA, dB = ctx.from_host(A), ctx.from_host(B)
+    dC = ctx.matrix(M, N, (1, 1), dm.F32)
+    info = dm.gemm_plan_info(ctx, 0, 0, dA, dB, dC)
+    assert info["kernel"] == 0
+    dm.gemm(ctx, 0, 0, 1.0, dA, dB, 0.0, dC)
+    got = dC.get()
+    rows = [0, 37, 63]
+    ref = oracle.gemm(False, False, 1.0, A, B, 0.0, rows=rows)
+    assert np.array_equal(got[rows].astype(np.float64), ref)
+    # the same product restricted to the k rows beyond 4 GiB must not vanish (they are read)
+    k_far = (1 << 32) // (N * 2) + 1
+    far = A[rows][:, k_far:].astype(np.float64) @ B[k_far:, :4096].astype(np.float64)
+    assert np.abs(far).max() > 0
+    for m in (dA, dB, dC):
+        m.destroy()
