@@ -229,6 +229,11 @@ dmath_status_t dmath_relayout_stats(dmath_ctx_t ctx, uint64_t *reused, uint64_t 
 dmath_status_t dmath_matrix_touch(dmath_matrix_t m);
 
 /*
+ * Memory decides first: when the pool cannot hold what the preferred configuration needs beyond
+ * the operands (split-K partial sums, re-layout copies), a gemm or convolution call falls back
+ * to the configuration that needs none (same results within tolerance, slower) instead of
+ * failing; DMATH_ERR_OOM is returned only if not even the plan's tables fit.
+ *
  * Selection from timing samples (section 4.1: at start-up the library picks the convolution
  * algorithm from timing samples within the system's memory constraints).  Without tuning, the
  * kernel family, tile shape and split-K count come from a cost model.  The tuners time every

@@ -193,7 +193,8 @@ std::vector<ConvChoice> conv_candidates(int mode, const ConvGeom& g, dmath_dtype
 // plan.cpp: plans outside the cache, built for one given choice (timing samples)
 dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_matrix_s* A, dmath_matrix_s* B,
                               dmath_matrix_s* C, bool upload, const GemmChoice* forced,
-                              std::unique_ptr<GemmPlan>* out, std::vector<GemmChoice>* candidates);
+                              std::unique_ptr<GemmPlan>* out, std::vector<GemmChoice>* candidates,
+                              bool unsplit = false);
 void free_gemm_plan(dmath_ctx_s* ctx, GemmPlan& p);
 dmath_status_t make_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t* d, dmath_matrix_s* X,
                               dmath_matrix_s* F, dmath_matrix_s* Y, const ConvChoice* forced,

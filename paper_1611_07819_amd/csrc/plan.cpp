@@ -234,6 +234,10 @@ dmath_status_t get_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_mat
     if (tuned != ctx->tuned_gemm.end() && ctx->policy == 0) forced = &tuned->second;
     std::unique_ptr<GemmPlan> plan;
     dmath_status_t st = make_gemm_plan(ctx, transA, transB, A, B, C, do_upload, forced, &plan, nullptr);
+    // the pool cannot hold the split-K partial sums: same kernel and tiles, unsplit (slower, but
+    // memory decides, as in the paper's choice of algorithm under memory constraints, section 4.1)
+    if (st == DMATH_ERR_OOM)
+        st = make_gemm_plan(ctx, transA, transB, A, B, C, do_upload, forced, &plan, nullptr, true);
     if (st != DMATH_OK) return st;
     *out = plan.get();
     ctx->gemm_plans[key] = std::move(plan);
@@ -242,7 +246,7 @@ dmath_status_t get_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_mat
 
 dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_matrix_s* A, dmath_matrix_s* B,
                               dmath_matrix_s* C, bool do_upload, const GemmChoice* forced,
-                              std::unique_ptr<GemmPlan>* out, std::vector<GemmChoice>* candidates)
+                              std::unique_ptr<GemmPlan>* out, std::vector<GemmChoice>* candidates, bool unsplit)
 {
     const int64_t M = C->rows, N = C->cols, K = transA ? A->rows : A->cols;
     const Split& a_m = transA ? A->csplit : A->rsplit;
@@ -283,6 +287,7 @@ dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_ma
     SegView view{M, N, K, &mlen, &nlen, &klen, !transA, (bool)transB, al, small, A->dtype, C->dtype,
                  ctx->policy};
     GemmChoice ch = forced ? *forced : choose_gemm(view);
+    if (unsplit) ch.split_k = 1;
     if (candidates) *candidates = gemm_candidates(view);
 
     // split-K: extra cuts of the k axis at multiples of 64 (every kernel's k-step divides 64)
@@ -446,6 +451,13 @@ dmath_status_t get_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t
     if (tuned != ctx->tuned_conv.end() && ctx->policy == 0) forced = &tuned->second;
     std::unique_ptr<ConvPlan> plan;
     dmath_status_t st = make_conv_plan(ctx, mode, d, X, F, Y, forced, &plan);
+    if (st == DMATH_ERR_OOM) {
+        // no room for the re-layout copies or the partial sums: the generic kernel, unsplit,
+        // needs neither (section 4.1: a slower algorithm where memory is the constraint)
+        const ConvChoice frugal;
+        drop_unused_relayouts(ctx);
+        st = make_conv_plan(ctx, mode, d, X, F, Y, &frugal, &plan);
+    }
     if (st != DMATH_OK) return st;
     *out = plan.get();
     ctx->conv_plans[key] = std::move(plan);

@@ -138,3 +138,56 @@ def test_tune_argument_errors(ctx):
         dm.gemm_tune(ctx, 0, 0, A, B, C, 0, trials=1)
     assert e.value.code == 7
     ctx.pipeline_destroy(ctx.pipeline_end())
+
+
+def test_full_pool_falls_back_to_configurations_without_workspace(oracle):
+    """Section 4.1's other half: where memory is the constraint a slower configuration is taken.
+    A pool that cannot hold the split-K partial sums, or the convolution's re-layout copies, must
+    still give the result (unsplit kernel, generic convolution kernel)."""
+    import torch
+    stream = torch.cuda.Stream()
+    slab = torch.empty(64 << 20, dtype=torch.uint8, device="cuda:0")
+    torch.cuda.synchronize()
+    ctx = dm.Context(slab, stream=stream.cuda_stream)
+    r = np.random.default_rng(1102)
+
+    def fill_pool(leave):
+        st = ctx.pool_stats()
+        n = (st["capacity"] - st["in_use"] - leave) // 256 * 256
+        return ctx.matrix(1, n // 4, (1, 1), dm.F32)
+
+    # GEMM: 4 tiles, K = 16384: the cost model wants 32 splits = 8 MB of partial sums
+    M, N, K = 256, 256, 16384
+    A = r.uniform(-1, 1, (M, K)).astype(np.float32)
+    B = r.uniform(-1, 1, (K, N)).astype(np.float32)
+    dA, dB, dC = ctx.from_host(A), ctx.from_host(B), ctx.matrix(M, N, (1, 1), dm.F32)
+    assert dm.gemm_plan_info(ctx, 0, 0, dA, dB, dC)["split_k"] > 1
+    filler = fill_pool(1 << 20)
+    dm.gemm(ctx, 0, 0, 1.0, dA, dB, 0.0, dC)
+    info = dm.gemm_plan_info(ctx, 0, 0, dA, dB, dC)
+    assert info["split_k"] == 1 and info["workspace_bytes"] == 0 and info["kernel"] != 0
+    assert rel_fro(dC.get(), oracle.gemm(False, False, 1.0, A, B, 0.0)) <= TOL[dm.F32]
+    for m in (filler, dA, dB, dC):
+        m.destroy()
+
+    # convolution: the specialised kernels need ~0.9 MB of copies; 256 KiB are left
+    d, od = dm.ConvDesc(**GEO), oracle.ConvDesc(**GEO)
+    hx = r.uniform(0, 1, (4, 128 * 256)).astype(np.float16)
+    hf = r.normal(0, 0.05, (256, 128 * 9)).astype(np.float16)
+    hy = r.normal(0, 0.1, (4, 256 * 256)).astype(np.float16)
+    X, F, dY = ctx.from_host(hx), ctx.from_host(hf), ctx.from_host(hy)
+    Y = ctx.matrix(4, 256 * 256, (1, 1), dm.F32)
+    dF = ctx.matrix(256, 128 * 9, (1, 1), dm.F32)
+    filler = fill_pool(256 << 10)
+    dm.conv_fwd(ctx, d, 1.0, X, F, 0.0, Y)
+    dm.conv_bwd_filter(ctx, d, 1.0, X, dY, 0.0, dF)
+    assert ctx.relayout_stats()["bytes_held"] == 0
+    assert rel_fro(Y.get(), oracle.conv_fwd(od, 1.0, hx, hf)) <= TOL[dm.F16]
+    assert rel_fro(dF.get(), oracle.conv_bwd_filter(od, 1.0, hx, hy)) <= TOL[dm.F16]
+    # with room again (and fresh plans) the specialised path comes back
+    filler.destroy()
+    ctx.tune_reset()
+    dm.conv_fwd(ctx, d, 1.0, X, F, 0.0, Y)
+    assert ctx.relayout_stats()["bytes_held"] > 0
+    assert rel_fro(Y.get(), oracle.conv_fwd(od, 1.0, hx, hf)) <= TOL[dm.F16]
+    ctx.close()
