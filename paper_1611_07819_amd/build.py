@@ -9,6 +9,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdmath.so")
+# measurement build: the fp16 GEMM kernel counts its own cycles (dmath_cycle_probe_read)
+OBJ_PROBE = os.path.join(HERE, "_build_probe")
+LIB_PROBE = os.path.join(HERE, "libdmath_probe.so")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 
 # -packed-fp32-ops off: packed fp32 instructions are not to be generated on the test machines.
@@ -27,29 +30,31 @@ def _newest_header():
     return max(os.path.getmtime(h) for h in hs)
 
 
-def _compile(src, force):
-    obj = os.path.join(OBJ, src + ".o")
+def _compile(src, force, probe=False):
+    obj = os.path.join(OBJ_PROBE if probe else OBJ, src + ".o")
     path = os.path.join(CSRC, src)
     if (not force and os.path.exists(obj) and os.path.getmtime(obj) >= os.path.getmtime(path)
             and os.path.getmtime(obj) >= _newest_header()):
         return obj, False
-    cmd = ["hipcc"] + HIP_FLAGS + (["-x", "hip"] if src.endswith(".hip") else []) + ["-c", path, "-o", obj]
+    cmd = (["hipcc"] + HIP_FLAGS + (["-DDMATH_CYCLE_PROBE"] if probe else []) +
+           (["-x", "hip"] if src.endswith(".hip") else []) + ["-c", path, "-o", obj])
     subprocess.run(cmd, check=True)
     return obj, True
 
 
-def build(force: bool = False, verbose: bool = False) -> str:
-    os.makedirs(OBJ, exist_ok=True)
+def build(force: bool = False, verbose: bool = False, probe: bool = False) -> str:
+    lib = LIB_PROBE if probe else LIB
+    os.makedirs(OBJ_PROBE if probe else OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=8) as ex:
-        res = list(ex.map(lambda s: _compile(s, force), sources()))
-    if force or any(changed for _, changed in res) or not os.path.exists(LIB):
-        cmd = ["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + [o for o, _ in res]
+        res = list(ex.map(lambda s: _compile(s, force, probe), sources()))
+    if force or any(changed for _, changed in res) or not os.path.exists(lib):
+        cmd = ["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", lib] + [o for o, _ in res]
         subprocess.run(cmd, check=True)
         if verbose:
-            print("linked", LIB)
-    return LIB
+            print("linked", lib)
+    return lib
 
 
 if __name__ == "__main__":
     import sys
-    build(force="--force" in sys.argv, verbose=True)
+    build(force="--force" in sys.argv, verbose=True, probe="--probe" in sys.argv)

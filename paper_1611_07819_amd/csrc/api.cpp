@@ -672,6 +672,14 @@ dmath_status_t dmath_mfma_peak_probe(dmath_ctx_t ctx, dmath_dtype_t dtype, int32
     return DMATH_OK;
 }
 
+dmath_status_t dmath_cycle_probe_read(dmath_ctx_t ctx, uint64_t* out6)
+{
+    if (!ctx || !out6) return DMATH_ERR_INVALID_ARG;
+    if (ctx->recording) return DMATH_ERR_UNSUPPORTED;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) return DMATH_ERR_DEVICE;
+    return read_cycle_probe(out6) ? DMATH_OK : DMATH_ERR_UNSUPPORTED;
+}
+
 dmath_status_t dmath_synchronize(dmath_ctx_t ctx)
 {
     if (!ctx) return DMATH_ERR_INVALID_ARG;

@@ -172,6 +172,7 @@ bool conv_f16_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype);
 int conv_f16_wgrad_split(const ConvGeom& g);
 hipError_t launch_conv_f16(const ConvPlan& p, int mode, double alpha, double beta, unsigned rewrite,
                            hipStream_t st);
+bool read_cycle_probe(uint64_t* out6);  // gemm_f16.hip; false unless built with the cycle probe
 hipError_t launch_mfma_peak(dmath_dtype_t dt, int iters, void* scratch, hipStream_t st, double* flops);
 // Picks kernel, tile shape and split-K; written next to the kernels whose preconditions it checks.
 struct SegView {

@@ -141,12 +141,20 @@ template <int BM, int BN> struct TileShape {
     static constexpr int MT = WM / 32, NTL = WN / 32;
 };
 
+// Measurement hooks of run(): nothing by default.  CycleProbe (gemm_f16.hip, opt-in build) reads
+// the shader clock at these points.
+struct NoProbe {
+    __device__ __forceinline__ void prologue_done() {}
+    __device__ __forceinline__ void wait_begin() {}
+    __device__ __forceinline__ void wait_end() {}
+};
+
 // Runs the whole k-loop of one workgroup tile.  `walk` must provide
 //   const char *abase, *bbase;  uint32_t aoff[BM/32], boff[BN/32];  void advance();
 // describing the k-tile that is fetched next.  acc must be zeroed by the caller.
-template <int BM, int BN, int STAGES, bool AKC, bool BKC, class Walk>
+template <int BM, int BN, int STAGES, bool AKC, bool BKC, class Walk, class Probe>
 __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
-                                    v16f (&acc)[TileShape<BM, BN>::MT][TileShape<BM, BN>::NTL])
+                                    v16f (&acc)[TileShape<BM, BN>::MT][TileShape<BM, BN>::NTL], Probe& probe)
 {
     using TA = OperandTile<BM, AKC>;
     using TB = OperandTile<BN, BKC>;
@@ -231,6 +239,7 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
         for (int s = 0; s < kSteps; ++s) {
             const int cur = s & 1;
             if (s == kSteps - 1 && HAS_NEXT) {
+                probe.wait_begin();
                 if (HAS_DMA && STAGES == 3)
                     wait_vmcnt<kPerTile>();
                 else
@@ -238,6 +247,7 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
+                probe.wait_end();
                 __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
@@ -282,6 +292,7 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
 #pragma unroll
     for (int r = 0; r < kReads; ++r) read_frag(lds, 0, r, 0);
 
+    probe.prologue_done();
     int stage = 0;
     int kt = 0;
     for (; kt + 2 < n_ktiles; ++kt) {
@@ -293,6 +304,14 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
         stage = stage + 1 == STAGES ? 0 : stage + 1;
     }
     iteration(stage, std::false_type{}, std::false_type{});
+}
+
+template <int BM, int BN, int STAGES, bool AKC, bool BKC, class Walk>
+__device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
+                                    v16f (&acc)[TileShape<BM, BN>::MT][TileShape<BM, BN>::NTL])
+{
+    NoProbe none;
+    run<BM, BN, STAGES, AKC, BKC>(walk, n_ktiles, smem, acc, none);
 }
 
 }  // namespace f16p

@@ -17,9 +17,37 @@
 
 namespace dm {
 
+// Opt-in cycle probe (a separate build with -DDMATH_CYCLE_PROBE, never the product library): the
+// workgroup that owns the C tile at (0, 0) records, for wavefront 0, the shader-clock cycles of
+// its prologue (until the first k-tile is in registers), k-loop and epilogue, the cycles spent
+// waiting at the per-k-tile barrier, and the elapsed 100 MHz reference ticks, from which the
+// clock the kernel really ran at follows.
+#ifdef DMATH_CYCLE_PROBE
+__device__ uint64_t g_cycle_probe[6];
+#endif
+
+bool read_cycle_probe(uint64_t* out6)
+{
+#ifdef DMATH_CYCLE_PROBE
+    return hipMemcpyFromSymbol(out6, HIP_SYMBOL(g_cycle_probe), 6 * sizeof(uint64_t)) == hipSuccess;
+#else
+    (void)out6;
+    return false;
+#endif
+}
+
 namespace {
 
 using namespace f16p;
+
+#ifdef DMATH_CYCLE_PROBE
+struct CycleProbe {
+    uint64_t t_prologue = 0, t_wait = 0, w0 = 0;
+    __device__ __forceinline__ void prologue_done() { t_prologue = __builtin_amdgcn_s_memtime(); }
+    __device__ __forceinline__ void wait_begin() { w0 = __builtin_amdgcn_s_memtime(); }
+    __device__ __forceinline__ void wait_end() { t_wait += __builtin_amdgcn_s_memtime() - w0; }
+};
+#endif
 
 // Walks the k-panels of one C tile: dense panels, pointer + leading dimension per k-segment.
 template <int BM, int BN, bool AKC, bool BKC> struct PanelWalk {
@@ -84,7 +112,14 @@ __global__ __launch_bounds__(NT) void gemm_f16_kernel(GemmTables t, float alpha,
     int n_ktiles = 0;
     for (int s = ks0; s < ks1; ++s) n_ktiles += t.klen[s] / BK;
     PanelWalk<BM, BN, AKC, BKC> walk(t, tile, wave, lane, ks0, ks1);
+#ifdef DMATH_CYCLE_PROBE
+    const uint64_t t_start = __builtin_amdgcn_s_memtime(), r_start = __builtin_amdgcn_s_memrealtime();
+    CycleProbe probe;
+    run<BM, BN, STAGES, AKC, BKC>(walk, n_ktiles, smem, acc, probe);
+    const uint64_t t_loop_end = __builtin_amdgcn_s_memtime();
+#else
     run<BM, BN, STAGES, AKC, BKC>(walk, n_ktiles, smem, acc);
+#endif
 
     if (t.split_k > 1) {  // partial sums; the fixed-order reduction kernel finishes the job
         float* ws = static_cast<float*>(t.workspace) + (int64_t)split * t.M * t.N;
@@ -125,6 +160,18 @@ __global__ __launch_bounds__(NT) void gemm_f16_kernel(GemmTables t, float alpha,
     };
     if (tile.m_len == BM && tile.n_len == BN) store(std::false_type{});
     else store(std::true_type{});
+#ifdef DMATH_CYCLE_PROBE
+    __syncthreads();
+    if (tid == 0 && tile.m_glob == 0 && tile.n_glob == 0) {
+        const uint64_t t_end = __builtin_amdgcn_s_memtime(), r_end = __builtin_amdgcn_s_memrealtime();
+        g_cycle_probe[0] = probe.t_prologue - t_start;
+        g_cycle_probe[1] = t_loop_end - probe.t_prologue;
+        g_cycle_probe[2] = t_end - t_loop_end;
+        g_cycle_probe[3] = probe.t_wait;
+        g_cycle_probe[4] = r_end - r_start;
+        g_cycle_probe[5] = (uint64_t)n_ktiles;
+    }
+#endif
 }
 
 template <int BM, int BN, int STAGES, bool AKC, bool BKC, class TC>

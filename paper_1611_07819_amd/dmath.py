@@ -110,6 +110,7 @@ def load_library(build_if_missing: bool = True):
         "dmath_pipeline_replay": [vp, i32],
         "dmath_pipeline_destroy": [vp, i32],
         "dmath_synchronize": [vp],
+        "dmath_cycle_probe_read": [vp, P(ctypes.c_uint64)],
         "dmath_mfma_peak_probe": [vp, ctypes.c_int, i32, P(dbl)],
         "dmath_pool_stats": [vp, P(sz), P(sz), P(sz)],
     }
@@ -192,6 +193,13 @@ class Context:
 
     def pipeline_destroy(self, pid: int):
         _check(self._lib.dmath_pipeline_destroy(self._h, pid), "dmath_pipeline_destroy")
+
+    def cycle_probe_read(self):
+        """Cycle counts of the last specialised fp16 GEMM (probe builds of the library only)."""
+        out = (ctypes.c_uint64 * 6)()
+        _check(self._lib.dmath_cycle_probe_read(self._h, out), "dmath_cycle_probe_read")
+        keys = ("prologue", "loop", "epilogue", "barrier_wait", "ticks_100mhz", "ktiles")
+        return dict(zip(keys, [int(v) for v in out]))
 
     def synchronize(self):
         _check(self._lib.dmath_synchronize(self._h), "dmath_synchronize")

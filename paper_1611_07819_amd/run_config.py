@@ -20,6 +20,9 @@ def main():
     ap.add_argument("--iters", type=int, default=20)
     ap.add_argument("--only", default=None)
     ap.add_argument("--copy-probe", action="store_true")
+    ap.add_argument("--cycle-probe", action="store_true",
+                    help="print the fp16 GEMM kernel's own cycle counts (needs the probe build of the "
+                         "library: python -m paper_1611_07819_amd.build --probe, then DMATH_LIBRARY=...)")
     args = ap.parse_args()
     import torch
     import paper_1611_07819_amd as dm
@@ -66,6 +69,14 @@ def main():
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / args.iters
         print(f"{w.name} {name}: {desc}: {ms * 1e3:.1f} us  {fl / ms / 1e9:.1f} TFLOP/s", flush=True)
+        if args.cycle_probe and name.startswith(("fwd", "dW", "dX", "nn")):
+            c = ctx.cycle_probe_read()
+            cyc = c["prologue"] + c["loop"] + c["epilogue"]
+            ghz = cyc / (c["ticks_100mhz"] / 100e6) / 1e9
+            print(f"    workgroup of tile (0,0): prologue {c['prologue']} + loop {c['loop']} "
+                  f"({c['loop'] / c['ktiles']:.0f} per k-tile) + epilogue {c['epilogue']} cycles, "
+                  f"{c['barrier_wait'] / max(c['ktiles'] - 1, 1):.0f} per k-tile waiting at the barrier; "
+                  f"{c['ticks_100mhz'] / 100:.1f} us -> {ghz:.2f} GHz in the kernel", flush=True)
     if args.copy_probe:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
         dst = torch.empty_like(src)

@@ -405,3 +405,9 @@ def test_block_beyond_4_gib_is_addressed_in_64_bits(ctx, oracle):
     assert np.abs(far).max() > 0
     for m in (dA, dB, dC):
         m.destroy()
+
+
+def test_cycle_probe_is_absent_from_the_product_library(ctx):
+    with pytest.raises(dm.DmathError) as e:
+        ctx.cycle_probe_read()
+    assert e.value.code == 7                      # DMATH_ERR_UNSUPPORTED
