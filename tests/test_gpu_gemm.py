@@ -244,6 +244,13 @@ FAST_CASES = [
     (dm.F64, (256, 384, 160), ((2, 2), (2, 2), (2, 2))),
     (dm.F64, (256, 128, 208), ((1, 1), (1, 1), (1, 1))),
     (dm.F64, (384, 256, 192), ((3, 2), (2, 2), (1, 2))),
+    # K of one and two k-steps of the kernel: the load ring never fills (prologue and drain only)
+    (dm.F32, (256, 256, 32), ((1, 1), (1, 1), (1, 1))),
+    (dm.F32, (128, 256, 64), ((1, 2), (2, 1), (1, 1))),
+    (dm.F16, (256, 256, 64), ((1, 1), (1, 1), (1, 1))),
+    (dm.F16, (512, 256, 128), ((1, 2), (2, 1), (1, 1))),
+    (dm.F64, (128, 128, 16), ((1, 1), (1, 1), (1, 1))),
+    (dm.F64, (256, 128, 32), ((1, 2), (2, 1), (1, 1))),
 ]
 
 
