@@ -199,3 +199,36 @@ def test_repeated_calls_rewrite_the_channels_last_copy(ctx, oracle):
     assert rel_fro(first, oracle.conv_fwd(od, 1.0, t["X"], t["F"])) <= TOL[dm.F16]
     for m in (dX, dF, dY):
         m.destroy()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_geometries_against_oracle(ctx, oracle, seed):
+    """Seeded sweep over geometries (filter sizes 1..5, strides 1..3, pads up to the filter size
+    minus one, odd channel counts; every third case a stride-1 geometry with channel counts that
+    the specialised fp16 kernels accept), row-blocked tensors, all three modes, small-integer data
+    compared bit for bit."""
+    r = np.random.default_rng(8000 + seed)
+    ctx.set_kernel_policy(0)
+    for case in range(3):
+        if case == 2:
+            rr, ss = int(r.integers(1, 4)), int(r.integers(1, 4))
+            hw = [(8, 8), (16, 8), (16, 16), (12, 12)][int(r.integers(0, 4))]
+            g = dict(n=int(r.integers(1, 4)) * 4, c=int(r.integers(1, 3)) * 128, h=hw[0], w=hw[1], k=256, r=rr, s=ss,
+                     pad_h=(rr - 1) // 2, pad_w=(ss - 1) // 2)
+            if rr % 2 == 0 or ss % 2 == 0:       # even filters shrink the output: keep n*oh*ow a multiple of 256
+                g["pad_h"], g["pad_w"] = rr // 2, ss // 2
+            dt, out = dm.F16, [dm.F32, dm.F16][int(r.integers(0, 2))]
+        else:
+            rr, ss = int(r.integers(1, 6)), int(r.integers(1, 6))
+            g = dict(n=int(r.integers(1, 5)), c=int(r.integers(1, 20)), h=int(r.integers(rr, rr + 12)),
+                     w=int(r.integers(ss, ss + 12)), k=int(r.integers(1, 70)), r=rr, s=ss,
+                     pad_h=int(r.integers(0, rr)), pad_w=int(r.integers(0, ss)),
+                     stride_h=int(r.integers(1, 4)), stride_w=int(r.integers(1, 4)))
+            dt, out = [(dm.F64, dm.F64), (dm.F32, dm.F32), (dm.F16, dm.F32), (dm.F16, dm.F16)][int(r.integers(0, 4))]
+        grids = {"X": (min(2, g["n"]), 1), "F": (min(3, g["k"]), 1), "Y": (1, 1)}
+        for mode, (got, ref) in three_modes(ctx, oracle, g, dt, out, 1.0, 1.0, grids, ints=True).items():
+            what = (seed, case, mode, g, dt, out)
+            if out == dm.F16 and np.abs(ref).max() > 2048:
+                assert rel_fro(got, ref) <= TOL[dt], what
+            else:
+                assert np.array_equal(got.astype(np.float64), ref), what

@@ -418,3 +418,48 @@ def test_cycle_probe_is_absent_from_the_product_library(ctx):
     with pytest.raises(dm.DmathError) as e:
         ctx.cycle_probe_read()
     assert e.value.code == 7                      # DMATH_ERR_UNSUPPORTED
+
+
+def _valid_grid(r, n):
+    """A random part count g for a dimension of length n that leaves no empty trailing part."""
+    while True:
+        g = int(r.integers(1, 5))
+        step = -(-n // g)
+        if (g - 1) * step < n:
+            return g
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shapes_grids_ops_against_oracle(ctx, oracle, seed):
+    """Seeded sweep over shapes (half of them multiples of 64 so that the specialised kernels and
+    their ragged tiles are drawn, the rest arbitrary), independent random block grids for A, B
+    and C, all ops, all precisions, random alpha and beta: small-integer data, bit for bit."""
+    r = np.random.default_rng(7000 + seed)
+    ctx.set_kernel_policy(0)
+    for case in range(6):
+        dt, out = [(dm.F64, dm.F64), (dm.F32, dm.F32), (dm.F16, dm.F32), (dm.F16, dm.F16)][int(r.integers(0, 4))]
+        if r.integers(0, 2):
+            M, N, K = (int(r.integers(1, 7)) * 64 + int(r.integers(0, 2)) * 8 for _ in range(3))
+            K = K // 64 * 64
+        else:
+            M, N, K = (int(r.integers(1, 300)) for _ in range(3))
+        ta, tb = int(r.integers(0, 2)), int(r.integers(0, 2))
+        opA = r.integers(-2, 3, (M, K)).astype(NP[dt])
+        opB = r.integers(-2, 3, (K, N)).astype(NP[dt])
+        C0 = r.integers(-2, 3, (M, N)).astype(NP[out])
+        A_st, B_st = stored(opA, ta), stored(opB, tb)
+        ga = (_valid_grid(r, A_st.shape[0]), _valid_grid(r, A_st.shape[1]))
+        gb = (_valid_grid(r, B_st.shape[0]), _valid_grid(r, B_st.shape[1]))
+        gc = (_valid_grid(r, M), _valid_grid(r, N))
+        alpha, beta = float(r.integers(-2, 3)), float(r.integers(-1, 2))
+        dA, dB, dC = ctx.from_host(A_st, ga), ctx.from_host(B_st, gb), ctx.from_host(C0, gc)
+        dm.gemm(ctx, ta, tb, alpha, dA, dB, beta, dC)
+        ref = oracle.gemm(bool(ta), bool(tb), alpha, oracle.BlockMatrix(A_st, ga), oracle.BlockMatrix(B_st, gb),
+                          beta, oracle.BlockMatrix(C0, gc))
+        what = (seed, case, dt, out, (M, N, K), (ta, tb), ga, gb, gc, alpha, beta)
+        if out == dm.F16 and np.abs(ref).max() > 2048:
+            assert rel_fro(dC.get(), ref) <= TOL[dt], what
+        else:
+            assert np.array_equal(dC.get().astype(np.float64), ref), what
+        for m in (dA, dB, dC):
+            m.destroy()
