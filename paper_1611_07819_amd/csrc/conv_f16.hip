@@ -237,12 +237,13 @@ template <int BM, int BN> struct WgradWalk {
     int oh, ow, hp, wp, c, d_oy, d_ox;
     int64_t astep;
 
-    __device__ __forceinline__ WgradWalk(const FastConv& p, int k0_pixels, int n0_cols, int wave, int lane)
+    __device__ __forceinline__ WgradWalk(const FastConv& p, int k0_pixels, int m0_filters, int n0_cols, int wave,
+                                         int lane)
     {
         oh = p.g.oh; ow = p.g.ow; hp = p.hp; wp = p.wp; c = p.g.c;
         d_oy = BK / ow; d_ox = BK % ow;
-        // A' = Yt[m][k]: dense, m/n (= k_out) unit-stride, all of k_out in the tile
-        TA::offsets(p.g.k, 0, BM, wave, lane, aoff);
+        // A' = Yt[m][k]: dense, m/n (= k_out) unit-stride, filters m0 .. m0+BM of the tile
+        TA::offsets(p.g.k, m0_filters, BM, wave, lane, aoff);
         astep = TA::step(p.g.k);
         abase = reinterpret_cast<const char*>(p.yt) + (int64_t)k0_pixels * p.g.k * 2;
         // B' columns n0 .. n0+BN of (r, s, c): one tap, BN consecutive channels
@@ -289,9 +290,10 @@ __global__ __launch_bounds__(NT) void conv_wgrad_f16_kernel(FastConv p)
     using TS = TileShape<BM, BN>;
     constexpr int WM = TS::WM, WN = TS::WN, MT = TS::MT, NTL = TS::NTL;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
-    const int ncols = p.g.c * p.g.r * p.g.s, tiles_n = ncols / BN;
+    const int ncols = p.g.c * p.g.r * p.g.s, tiles_n = ncols / BN, tiles_mn = (p.g.k / BM) * tiles_n;
     const int idx = xcd_logical(blockIdx.x, gridDim.x);
-    const int split = idx / tiles_n, n0 = (idx % tiles_n) * BN;  // split-major: same pixels, same XCD
+    const int split = idx / tiles_mn, mn = idx % tiles_mn;  // split-major: same pixels, same XCD
+    const int m0 = (mn / tiles_n) * BM, n0 = (mn % tiles_n) * BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31;
@@ -304,7 +306,7 @@ __global__ __launch_bounds__(NT) void conv_wgrad_f16_kernel(FastConv p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    WgradWalk<BM, BN> walk(p, split * p.ktiles_per_split * BK, n0, wave, lane);
+    WgradWalk<BM, BN> walk(p, split * p.ktiles_per_split * BK, m0, n0, wave, lane);
     run<BM, BN, 3, false, false>(walk, p.ktiles_per_split, smem, acc);
 
     float* ws = p.ws + (int64_t)split * p.g.k * ncols;
@@ -314,7 +316,7 @@ __global__ __launch_bounds__(NT) void conv_wgrad_f16_kernel(FastConv p)
         for (int j = 0; j < NTL; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int row = wm * WM + i * 32 + acc32_row(lane, r);
+                const int row = m0 + wm * WM + i * 32 + acc32_row(lane, r);
                 const int col = n0 + wn * WN + j * 32 + l32;
                 ws[(int64_t)row * ncols + col] = acc[i][j][r];
             }
@@ -367,7 +369,7 @@ bool conv_f16_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype)
     if (sp_out < 64) return false;
     if (mode == CONV_FWD) return g.k % 128 == 0 && m % 256 == 0 && sp_out % 4 == 0;
     if (mode == CONV_BWD_FILTER)
-        return g.k == 256 && g.c % 128 == 0 && m % 64 == 0 && g.k % 64 == 0 && sp_out % 8 == 0 &&
+        return (g.k % 256 == 0 || g.k == 128) && g.c % 128 == 0 && m % 64 == 0 && sp_out % 8 == 0 &&
                (int64_t)64 * tcl_stride((int)sp_out) * 2 <= 150 * 1024;
     // data gradient = forward convolution of dY (k channels) with the rotated filter and
     // padding r-1-pad: needs that padding to be non-negative
@@ -377,11 +379,17 @@ bool conv_f16_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype)
            (int64_t)64 * tcl_stride((int)sp_out) * 2 <= 150 * 1024;
 }
 
+// C tiles of the weight gradient: 256 (or, for 128 filters, 128) filters x 128 columns of (r,s,c).
+static int64_t wgrad_tiles(const ConvGeom& g)
+{
+    return (int64_t)(g.k == 128 ? 1 : g.k / 256) * ((int64_t)g.c * g.r * g.s / 128);
+}
+
 // Split count for the weight gradient: enough workgroups to fill the chip, dividing the k-tiles.
 int conv_f16_wgrad_split(const ConvGeom& g)
 {
     const int64_t ktiles = (int64_t)g.n * g.oh * g.ow / 64;
-    const int64_t tiles = (int64_t)g.c * g.r * g.s / 128;
+    const int64_t tiles = wgrad_tiles(g);
     int best = 1;
     for (int s = 1; s <= 64; ++s)
         if (ktiles % s == 0 && tiles * s <= 256 && ktiles / s >= 8) best = s;
@@ -439,7 +447,7 @@ std::vector<ConvChoice> conv_candidates(int mode, const ConvGeom& g, dmath_dtype
     c = ConvChoice{};
     c.kernel = 1;
     if (mode == CONV_BWD_FILTER) {
-        const int64_t ktiles = (int64_t)g.n * g.oh * g.ow / 64, tiles = (int64_t)g.c * g.r * g.s / 128;
+        const int64_t ktiles = (int64_t)g.n * g.oh * g.ow / 64, tiles = wgrad_tiles(g);
         for (int s = 1; s <= 64; ++s)
             if (ktiles % s == 0 && tiles * s <= 512 && ktiles / s >= 8) {
                 c.split_k = s;
@@ -494,6 +502,7 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
         if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 256, 2, float>, 2 * 512 * 128);
         if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 256, 2, _Float16>, 2 * 512 * 128);
         if (e == hipSuccess) e = set_lds(conv_wgrad_f16_kernel<256, 128>, 3 * 384 * 128);
+        if (e == hipSuccess) e = set_lds(conv_wgrad_f16_kernel<128, 128>, 3 * 256 * 128);
         if (e != hipSuccess) return e;
         configured = true;
     }
@@ -561,8 +570,11 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
                                                                      yt);
     }
     p.ktiles_per_split = (int)((int64_t)g.n * g.oh * g.ow / 64 / t.split_k);
-    const int tiles = (g.c * g.r * g.s / 128) * t.split_k;
-    conv_wgrad_f16_kernel<256, 128><<<tiles, NT, 3 * 384 * 128, st>>>(p);
+    const int tiles = (int)wgrad_tiles(g) * t.split_k;
+    if (g.k == 128)
+        conv_wgrad_f16_kernel<128, 128><<<tiles, NT, 3 * 256 * 128, st>>>(p);
+    else
+        conv_wgrad_f16_kernel<256, 128><<<tiles, NT, 3 * 384 * 128, st>>>(p);
     if (plan.out_dtype == DMATH_F16)
         conv_wgrad_reduce_kernel<_Float16><<<1024, 256, 0, st>>>(p, (float)alpha, (float)beta);
     else

@@ -141,6 +141,8 @@ FAST_GEOMS = [
     dict(n=8, c=128, h=16, w=8, k=256, r=1, s=1),
     dict(n=2, c=256, h=16, w=16, k=256, r=5, s=3, pad_h=2, pad_w=1),
     dict(n=16, c=128, h=12, w=12, k=256, r=3, s=3, pad_h=1, pad_w=1),
+    dict(n=4, c=128, h=16, w=16, k=512, r=3, s=3, pad_h=1, pad_w=1),      # two row tiles of filters
+    dict(n=4, c=256, h=16, w=16, k=128, r=3, s=3, pad_h=1, pad_w=1),      # 128 filters: 128x128 tiles
 ]
 
 
@@ -151,7 +153,10 @@ def test_specialised_fp16_conv_whole_result(ctx, oracle, g, out):
     bar on random data (alpha/beta exercised) and bit for bit on small-integer data with a
     row-blocked layout of every tensor."""
     grids = {"X": (1, 1), "F": (1, 1), "Y": (1, 1)}
+    before = ctx.relayout_stats()["written"]
     res = three_modes(ctx, oracle, g, dm.F16, out, 1.5, -0.5, grids, policy=0)
+    # every mode went through the specialised kernels: each re-laid-out its two operands
+    assert ctx.relayout_stats()["written"] - before == 6
     for mode in ("fwd", "bwd_filter", "bwd_data"):
         got, ref = res[mode]
         assert rel_fro(got, ref) <= TOL[dm.F16], mode
