@@ -47,6 +47,8 @@ typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 constexpr int kTclThreads = 1024;
 __host__ __device__ inline int tcl_stride(int hw) { return hw + ((20 - hw % 16) % 16); }
 
+// VEC: halfs per global read, 8 where a plane is a multiple of 16 bytes, else 4.
+template <int VEC>
 __global__ __launch_bounds__(kTclThreads) void to_channels_last_kernel(const void* const* src_rows, int ch,
                                                                        int h, int w, int ph, int pw, int hp,
                                                                        int wp, _Float16* dst)
@@ -58,13 +60,17 @@ __global__ __launch_bounds__(kTclThreads) void to_channels_last_kernel(const voi
     const int chunks_c = ch / 64;
     const int n = blockIdx.x / chunks_c, c0 = (blockIdx.x % chunks_c) * 64;
     const _Float16* src = static_cast<const _Float16*>(src_rows[n]) + (int64_t)c0 * hw;
-    const int vec_per_plane = hw / 8;
+    const int vec_per_plane = hw / VEC;
     for (int e = threadIdx.x; e < 64 * vec_per_plane; e += kTclThreads) {
         const int c = e / vec_per_plane, v = e - c * vec_per_plane;
-        const v4u d = *reinterpret_cast<const v4u*>(src + (int64_t)c * hw + v * 8);
-        v2u* q = reinterpret_cast<v2u*>(planes + c * stride + v * 8);  // rows are 8-byte aligned
-        q[0] = v2u{d[0], d[1]};
-        q[1] = v2u{d[2], d[3]};
+        v2u* q = reinterpret_cast<v2u*>(planes + c * stride + v * VEC);  // rows are 8-byte aligned
+        if (VEC == 8) {
+            const v4u d = *reinterpret_cast<const v4u*>(src + (int64_t)c * hw + v * 8);
+            q[0] = v2u{d[0], d[1]};
+            q[1] = v2u{d[2], d[3]};
+        } else {
+            q[0] = *reinterpret_cast<const v2u*>(src + (int64_t)c * hw + v * 4);
+        }
     }
     __syncthreads();
     _Float16* out = dst + ((int64_t)n * hp * wp) * ch + c0;
@@ -76,6 +82,17 @@ __global__ __launch_bounds__(kTclThreads) void to_channels_last_kernel(const voi
         for (int i = 0; i < 8; ++i) v[i] = planes[(cg * 8 + i) * stride + pix];
         *reinterpret_cast<v8h*>(out + ((int64_t)(y + ph) * wp + (x + pw)) * ch + cg * 8) = v;
     }
+}
+
+// NCHW rows -> zero-bordered channels-last copy, on stream st.
+static void to_channels_last(const void* const* src_rows, int n, int ch, int h, int w, int ph, int pw, int hp, int wp,
+                             _Float16* dst, hipStream_t st)
+{
+    const int lds = 64 * tcl_stride(h * w) * 2;
+    if ((h * w) % 8 == 0)
+        to_channels_last_kernel<8><<<n * (ch / 64), kTclThreads, lds, st>>>(src_rows, ch, h, w, ph, pw, hp, wp, dst);
+    else
+        to_channels_last_kernel<4><<<n * (ch / 64), kTclThreads, lds, st>>>(src_rows, ch, h, w, ph, pw, hp, wp, dst);
 }
 
 // F[k][c][r][s] -> Fp[k][(r,s,c)]
@@ -142,11 +159,14 @@ template <int BM, int BN> struct FwdWalk {
         r = s = cc = 0;
         abase = xp;
         bbase = reinterpret_cast<const char*>(p.fp);
+        // rows past the last pixel (ragged last tile) fetch the last pixel again: in bounds, and
+        // what they bring in only reaches accumulators that the epilogue does not store
+        const int m_last = p.g.n * p.g.oh * p.g.ow - 1;
 #pragma unroll
         for (int q = 0; q < TA::kInstr; ++q) {
             int row, chunk;
             TA::lane_slot(q, wave, lane, row, chunk);
-            aoff[q] = pixel_offset(p, m0 + row) + chunk * 16;
+            aoff[q] = pixel_offset(p, min(m0 + row, m_last)) + chunk * 16;
         }
         TB::offsets((int64_t)p.g.c * p.g.r * p.g.s, n0, BN, wave, lane, boff);
     }
@@ -198,12 +218,13 @@ __global__ __launch_bounds__(NT) void conv_fwd_f16_kernel(FastConv p, float alph
     run<BM, BN, STAGES, true, true>(walk, n_ktiles, smem, acc);
 
     // epilogue: four consecutive registers are four consecutive pixels of one output plane
-    const int sp_out = p.g.oh * p.g.ow;
+    const int sp_out = p.g.oh * p.g.ow, m_end = p.g.n * sp_out;  // a multiple of 4, as sp_out is
 #pragma unroll
     for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
             const int m = m0 + wm * WM + i * 32 + 8 * q4 + 4 * h;
+            if (m >= m_end) continue;  // ragged last tile
             const int n_img = m / sp_out, sp = m % sp_out;
             TC* yrow = static_cast<TC*>(const_cast<void*>(p.y_rows[n_img]));
 #pragma unroll
@@ -364,18 +385,17 @@ bool conv_f16_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype)
     const int64_t copy_f = (int64_t)g.k * g.c * g.r * g.s * 2;
     if (copy_f >= limit || (mode == CONV_BWD_DATA ? copy_dy : copy_x) >= limit || m * g.k * 2 >= limit) return false;
     if (mode != CONV_BWD_DATA &&
-        (g.c % 64 || (g.h * g.w) % 8 || (int64_t)64 * tcl_stride(g.h * g.w) * 2 > 150 * 1024))
+        (g.c % 64 || (g.h * g.w) % 4 || (int64_t)64 * tcl_stride(g.h * g.w) * 2 > 150 * 1024))
         return false;
     if (sp_out < 64) return false;
-    if (mode == CONV_FWD) return g.k % 128 == 0 && m % 256 == 0 && sp_out % 4 == 0;
+    if (mode == CONV_FWD) return g.k % 128 == 0 && sp_out % 4 == 0;
     if (mode == CONV_BWD_FILTER)
-        return (g.k % 256 == 0 || g.k == 128) && g.c % 128 == 0 && m % 64 == 0 && sp_out % 8 == 0 &&
+        return (g.k % 256 == 0 || g.k == 128) && g.c % 128 == 0 && m % 64 == 0 && sp_out % 4 == 0 &&
                (int64_t)64 * tcl_stride((int)sp_out) * 2 <= 150 * 1024;
     // data gradient = forward convolution of dY (k channels) with the rotated filter and
     // padding r-1-pad: needs that padding to be non-negative
-    const int64_t m_in = (int64_t)g.n * g.h * g.w;
-    return g.pad_h <= g.r - 1 && g.pad_w <= g.s - 1 && g.k % 64 == 0 && g.c % 128 == 0 && m_in % 256 == 0 &&
-           (g.h * g.w) % 4 == 0 && g.h * g.w >= 64 && sp_out % 8 == 0 &&
+    return g.pad_h <= g.r - 1 && g.pad_w <= g.s - 1 && g.k % 64 == 0 && g.c % 128 == 0 &&
+           (g.h * g.w) % 4 == 0 && g.h * g.w >= 64 && sp_out % 4 == 0 &&
            (int64_t)64 * tcl_stride((int)sp_out) * 2 <= 150 * 1024;
 }
 
@@ -423,7 +443,7 @@ ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int3
     }
     const int64_t m = mode == CONV_FWD ? (int64_t)g.n * g.oh * g.ow : (int64_t)g.n * g.h * g.w;
     const int n_out = mode == CONV_FWD ? g.k : g.c;
-    const int64_t t128 = m / 256 * (n_out / 128), t256 = m / 256 * (n_out / 256);
+    const int64_t t128 = (m + 255) / 256 * (n_out / 128), t256 = (m + 255) / 256 * (n_out / 256);
     bool wide = n_out % 256 == 0 && t128 > 256 && t256 <= 256;
     if (const char* force = std::getenv("DMATH_CONV_TILE")) wide = n_out % 256 == 0 && std::strcmp(force, "256x256") == 0;
     ch.tile_n = wide ? 256 : 128;
@@ -496,7 +516,8 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
 
     static bool configured = false;
     if (!configured) {
-        hipError_t e = set_lds(to_channels_last_kernel, 150 * 1024);
+        hipError_t e = set_lds(to_channels_last_kernel<8>, 150 * 1024);
+        if (e == hipSuccess) e = set_lds(to_channels_last_kernel<4>, 150 * 1024);
         if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 128, 3, float>, 3 * 384 * 128);
         if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 128, 3, _Float16>, 3 * 384 * 128);
         if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 256, 2, float>, 2 * 512 * 128);
@@ -517,13 +538,10 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
         q.hp = g.oh + 2 * pph;
         q.wp = g.ow + 2 * ppw;
         q.y_rows = t.x_rows;
-        const int lds = 64 * tcl_stride(g.oh * g.ow) * 2;
-        if (rewrite & REWRITE_X)
-            to_channels_last_kernel<<<g.n * (g.k / 64), kTclThreads, lds, st>>>(t.y_rows, g.k, g.oh, g.ow, pph, ppw,
-                                                                                 q.hp, q.wp, xp);
+        if (rewrite & REWRITE_X) to_channels_last(t.y_rows, g.n, g.k, g.oh, g.ow, pph, ppw, q.hp, q.wp, xp, st);
         if (rewrite & REWRITE_F)
             filter_to_rsk_rotated_kernel<<<512, 256, 0, st>>>(t.f_rows, g.c, g.r, g.s, g.k, fp);
-        const int mt = (int)((int64_t)g.n * g.h * g.w / 256);
+        const int mt = (int)(((int64_t)g.n * g.h * g.w + 255) / 256);
         const int t128 = mt * (g.c / 128), t256 = mt * (g.c / 256);
         const bool wide = plan.tile_n == 256;
         if (wide) {
@@ -540,14 +558,10 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
         return hipGetLastError();
     }
     // activations -> zero-bordered channels-last copy (borders were zeroed when the copy was allocated)
-    if (rewrite & REWRITE_X) {
-        const int lds = 64 * tcl_stride(g.h * g.w) * 2;
-        to_channels_last_kernel<<<g.n * (g.c / 64), kTclThreads, lds, st>>>(t.x_rows, g.c, g.h, g.w, g.pad_h, g.pad_w,
-                                                                     p.hp, p.wp, xp);
-    }
+    if (rewrite & REWRITE_X) to_channels_last(t.x_rows, g.n, g.c, g.h, g.w, g.pad_h, g.pad_w, p.hp, p.wp, xp, st);
     if (mode == CONV_FWD) {
         if (rewrite & REWRITE_F) filter_to_rsc_kernel<<<512, 256, 0, st>>>(t.f_rows, g.c, g.r * g.s, g.k, fp);
-        const int mt = (int)((int64_t)g.n * g.oh * g.ow / 256);
+        const int mt = (int)(((int64_t)g.n * g.oh * g.ow + 255) / 256);
         const int t128 = mt * (g.k / 128), t256 = mt * (g.k / 256);
         const bool wide = plan.tile_n == 256;
         if (wide) {
@@ -564,11 +578,7 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
         return hipGetLastError();
     }
     // weight gradient: dY -> channels-last [m][k], split GEMM, fixed-order reduction
-    if (rewrite & REWRITE_Y) {
-        const int lds = 64 * tcl_stride(g.oh * g.ow) * 2;
-        to_channels_last_kernel<<<g.n * (g.k / 64), kTclThreads, lds, st>>>(t.y_rows, g.k, g.oh, g.ow, 0, 0, g.oh, g.ow,
-                                                                     yt);
-    }
+    if (rewrite & REWRITE_Y) to_channels_last(t.y_rows, g.n, g.k, g.oh, g.ow, 0, 0, g.oh, g.ow, yt, st);
     p.ktiles_per_split = (int)((int64_t)g.n * g.oh * g.ow / 64 / t.split_k);
     const int tiles = (int)wgrad_tiles(g) * t.split_k;
     if (g.k == 128)

@@ -217,7 +217,7 @@ def test_random_geometries_against_oracle(ctx, oracle, seed):
     for case in range(3):
         if case == 2:
             rr, ss = int(r.integers(1, 4)), int(r.integers(1, 4))
-            hw = [(8, 8), (16, 8), (16, 16), (12, 12)][int(r.integers(0, 4))]
+            hw = [(8, 8), (16, 8), (16, 16), (12, 12), (14, 14), (10, 10)][int(r.integers(0, 6))]
             g = dict(n=int(r.integers(1, 4)) * 4, c=int(r.integers(1, 3)) * 128, h=hw[0], w=hw[1], k=256, r=rr, s=ss,
                      pad_h=(rr - 1) // 2, pad_w=(ss - 1) // 2)
             if rr % 2 == 0 or ss % 2 == 0:       # even filters shrink the output: keep n*oh*ow a multiple of 256
@@ -237,3 +237,21 @@ def test_random_geometries_against_oracle(ctx, oracle, seed):
                 assert rel_fro(got, ref) <= TOL[dt], what
             else:
                 assert np.array_equal(got.astype(np.float64), ref), what
+
+
+@pytest.mark.parametrize("g", [dict(n=3, c=128, h=14, w=14, k=256, r=3, s=3, pad_h=1, pad_w=1),
+                               dict(n=5, c=256, h=12, w=6, k=128, r=1, s=1)])
+@pytest.mark.parametrize("out", [dm.F32, dm.F16])
+def test_specialised_fp16_conv_ragged_last_row_tile(ctx, oracle, g, out):
+    """n*oh*ow is not a multiple of the 256-row tile: the last tile of the forward and of the data
+    gradient is ragged (clamped gathers, masked stores); the weight gradient of such a geometry
+    runs on the generic kernel.  Small-integer data, bit for bit, NaN-free neighbours."""
+    grids = {"X": (g["n"], 1), "F": (2, 1), "Y": (1, 1)}
+    before = ctx.relayout_stats()["written"]
+    res = three_modes(ctx, oracle, g, dm.F16, out, 1.0, 1.0, grids, ints=True, policy=0)
+    assert ctx.relayout_stats()["written"] - before == 4       # forward and data gradient: two copies each
+    for mode, (got, ref) in res.items():
+        if out == dm.F16 and np.abs(ref).max() > 2048:
+            assert rel_fro(got, ref) <= TOL[dm.F16], mode
+        else:
+            assert np.array_equal(got.astype(np.float64), ref), mode
