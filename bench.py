@@ -144,6 +144,24 @@ def main():
         bench_workload(synth.config3("f32"), "cfg3_f32out", "f16")
         bench_workload(synth.config3("f16"), "cfg3_f16out", "f16")
         bench_workload(synth.config4(), "cfg4", "f64")
+        # small batch against the configuration-2/3 weight matrices: bound by streaming W from HBM
+        # (fp16) or by the matrix instructions on a 64-row tile (fp32, fp64), not by the MFMA peak
+        rs = np.random.default_rng(16110781)
+        for tag, code, npdt, (M, N, K) in (("f16", dm.F16, np.float16, (64, 4096, 4096)),
+                                           ("f16", dm.F16, np.float16, (64, 4096, 9216)),
+                                           ("f32", dm.F32, np.float32, (64, 4096, 9216))):
+            sa = ctx.from_host(rs.uniform(0, 1, (M, K)).astype(npdt))
+            sb = ctx.from_host(rs.normal(0, 0.01, (K, N)).astype(npdt))
+            sc = ctx.matrix(M, N, (1, 1), dm.F32)
+            ms, _ = time_calls([lambda: dm.gemm(ctx, 0, 0, 1.0, sa, sb, 0.0, sc)], 20, 5)
+            byt = (M * K + K * N) * npdt().itemsize + M * N * 4
+            pinfo = dm.gemm_plan_info(ctx, 0, 0, sa, sb, sc)
+            calls[f"skinny_{tag}.M{M}_N{N}_K{K}"] = {
+                "ms": round(ms, 4), "tflops": round(2.0 * M * N * K / ms / 1e9, 2),
+                "hbm_tb_s": round(byt / ms / 1e9, 3), "frac_hbm_peak": round(byt / ms / 1e9 / 8.0, 4),
+                "tile": [pinfo["tile_m"], pinfo["tile_n"], pinfo["split_k"]]}
+            for m in (sa, sb, sc):
+                m.destroy()
         w5 = synth.config5("f32")
         d5 = {k: ctx.from_host(v) for k, v in w5.mats.items()}
         desc = dm.ConvDesc(**w5.conv)

@@ -343,6 +343,8 @@ hipError_t launch_gemm_f32(const GemmPlan& p, double alpha, double beta, hipStre
     if (bm == 128 && bn == 128) return launch_shape<128, 128, 2>(p, (float)alpha, (float)beta, st);
     if (bm == 128 && bn == 64) return launch_shape<128, 64, 2>(p, (float)alpha, (float)beta, st);
     if (bm == 128 && bn == 96) return launch_shape<128, 96, 4>(p, (float)alpha, (float)beta, st);
+    if (bm == 64 && bn == 256) return launch_shape<64, 256, 2>(p, (float)alpha, (float)beta, st);
+    if (bm == 64 && bn == 128) return launch_shape<64, 128, 2>(p, (float)alpha, (float)beta, st);
     return hipErrorInvalidValue;
 }
 

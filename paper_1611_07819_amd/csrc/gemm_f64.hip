@@ -341,6 +341,7 @@ hipError_t launch_gemm_f64(const GemmPlan& p, double alpha, double beta, hipStre
     const int bm = p.info.tile_m, bn = p.info.tile_n;
     if (bm == 128 && bn == 128) return launch_shape<128, 128, 2>(p, alpha, beta, st);
     if (bm == 128 && bn == 64) return launch_shape<128, 64, 2>(p, alpha, beta, st);
+    if (bm == 64 && bn == 128) return launch_shape<64, 128, 2>(p, alpha, beta, st);
     return hipErrorInvalidValue;
 }
 

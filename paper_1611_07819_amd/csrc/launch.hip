@@ -29,6 +29,14 @@ int32_t split_for(int64_t tiles, int64_t K)
     return (int32_t)std::max<int64_t>(1, std::min<int64_t>({want, max_by_k, 32}));
 }
 
+// Few rows (a small batch against a large weight matrix): every m-segment fits a 64-row tile.
+bool few_rows(const SegView& v)
+{
+    for (int64_t m : *v.mlen)
+        if (m > 64) return false;
+    return true;
+}
+
 bool all_multiple(const std::vector<int64_t>& v, int64_t q)
 {
     for (int64_t x : v)
@@ -73,6 +81,11 @@ std::vector<Shape> specialised_shapes(const SegView& v)
         out.push_back({kern, 128, 128, bk});
         out.push_back({kern, 128, 64, bk});
         if (f32 && v.b_kcontig) out.push_back({kern, 128, 96, bk});  // wavefronts 4x1, k-major B only
+        // few rows: 64-row tiles do half the matrix instructions of 128-row ones on padding
+        if (few_rows(v)) {
+            out.push_back({kern, 64, 128, bk});
+            if (f32) out.push_back({kern, 64, 256, bk});
+        }
     }
     if (f16) {
         out.push_back({KERNEL_F16_256, 256, 256, 64});
@@ -113,6 +126,11 @@ GemmChoice choose_gemm(const SegView& v)
         const bool f32_strided = !v.a_kcontig && !v.b_kcontig;
         if (s.kernel == KERNEL_F32_128 && (s.bm * s.bn < 128 * 128) != f32_strided) cost *= 1.03;
         if (s.kernel == KERNEL_F64_128 && s.bm * s.bn >= 128 * 128) cost *= 1.03;
+        // few rows: a 128-row tile multiplies 64 rows of padding (one or two workgroups per CU
+        // measured the same, so the split stays at one round: half the partial sums)
+        const bool short_tile = s.bm == 64;
+        if (few_rows(v) && !short_tile) cost *= 2;
+        if (short_tile && s.bn > 128) cost *= 1.03;
         if (best_cost < 0 || cost < best_cost) {
             best_cost = cost;
             ch.kernel = s.kernel;
