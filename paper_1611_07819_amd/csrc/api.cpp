@@ -310,6 +310,8 @@ dmath_status_t dmath_matrix_reblock(dmath_ctx_t ctx, dmath_matrix_t src, dmath_m
     const int64_t ses = elem_size(src->dtype), des = elem_size(dst->dtype);
     std::vector<CopyCell> cells;
     int max_rows = 0;
+    const int64_t vec = reblock_vector_width(src->dtype, dst->dtype);
+    bool vectors = true;  // every cell: origins, leading dimensions and width multiples of the vector
     for (size_t i = 0; i + 1 < rc.size(); ++i)
         for (size_t j = 0; j + 1 < cc.size(); ++j) {
             const int64_t r = rc[i], c = cc[j];
@@ -325,6 +327,9 @@ dmath_status_t dmath_matrix_reblock(dmath_ctx_t ctx, dmath_matrix_t src, dmath_m
             cell.rows = (int32_t)(rc[i + 1] - r);
             cell.cols = (int32_t)(cc[j + 1] - c);
             max_rows = std::max(max_rows, cell.rows);
+            vectors = vectors && cell.cols % vec == 0 && cell.src_ld % vec == 0 && cell.dst_ld % vec == 0 &&
+                      reinterpret_cast<uintptr_t>(cell.src) % (vec * ses) == 0 &&
+                      reinterpret_cast<uintptr_t>(cell.dst) % (vec * des) == 0;
             cells.push_back(cell);
         }
     const size_t bytes = cells.size() * sizeof(CopyCell);
@@ -335,7 +340,7 @@ dmath_status_t dmath_matrix_reblock(dmath_ctx_t ctx, dmath_matrix_t src, dmath_m
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
     if (e == hipSuccess)
         e = launch_reblock(src->dtype, dst->dtype, static_cast<const CopyCell*>(dev), (int)cells.size(),
-                           max_rows, ctx->stream);
+                           max_rows, vectors, ctx->stream);
     ctx->pool.free(dev);  // reuse of the table's memory is ordered after the kernel by the stream
     wrote(ctx, dst);
     return e == hipSuccess ? DMATH_OK : DMATH_ERR_DEVICE;

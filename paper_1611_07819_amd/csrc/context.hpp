@@ -167,7 +167,8 @@ enum : unsigned { REWRITE_X = 1, REWRITE_F = 2, REWRITE_Y = 4 };
 hipError_t launch_conv(const ConvPlan& p, int mode, double alpha, double beta, unsigned rewrite,
                        hipStream_t stream);
 hipError_t launch_reblock(dmath_dtype_t sd, dmath_dtype_t dd, const CopyCell* cells, int n_cells,
-                          int max_rows, hipStream_t st);
+                          int max_rows, bool vectors, hipStream_t st);
+int reblock_vector_width(dmath_dtype_t sd, dmath_dtype_t dd);
 bool conv_f16_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype);
 int conv_f16_wgrad_split(const ConvGeom& g);
 hipError_t launch_conv_f16(const ConvPlan& p, int mode, double alpha, double beta, unsigned rewrite,
