@@ -273,8 +273,8 @@ dmath_status_t dmath_tune_reset(dmath_ctx_t ctx);
 
 /*
  * Measurement aid, for builds of the library made with -DDMATH_CYCLE_PROBE only (the product
- * library returns DMATH_ERR_UNSUPPORTED): after a specialised fp16 dmath_gemm (unsplit), waits for
- * the stream and returns what wavefront 0 of the workgroup owning C tile (0,0) counted:
+ * library returns DMATH_ERR_UNSUPPORTED): after a specialised fp16 dmath_gemm, waits for
+ * the stream and returns what wavefront 0 of the workgroup owning C tile (0,0) (first k-split) counted:
  * out6[0..2] shader-clock cycles of prologue, k-loop, epilogue; out6[3] cycles waiting at the
  * per-k-tile barrier; out6[4] elapsed ticks of the 100 MHz reference clock; out6[5] k-tiles.
  * (cycles / ticks * 100 MHz = the clock the kernel ran at.)

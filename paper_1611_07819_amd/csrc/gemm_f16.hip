@@ -121,6 +121,20 @@ __global__ __launch_bounds__(NT) void gemm_f16_kernel(GemmTables t, float alpha,
     run<BM, BN, STAGES, AKC, BKC>(walk, n_ktiles, smem, acc);
 #endif
 
+#ifdef DMATH_CYCLE_PROBE
+    auto record_probe = [&] {
+        __syncthreads();
+        if (tid == 0 && tile.m_glob == 0 && tile.n_glob == 0 && blockIdx.y == 0) {
+            const uint64_t t_end = __builtin_amdgcn_s_memtime(), r_end = __builtin_amdgcn_s_memrealtime();
+            g_cycle_probe[0] = probe.t_prologue - t_start;
+            g_cycle_probe[1] = t_loop_end - probe.t_prologue;
+            g_cycle_probe[2] = t_end - t_loop_end;
+            g_cycle_probe[3] = probe.t_wait;
+            g_cycle_probe[4] = r_end - r_start;
+            g_cycle_probe[5] = (uint64_t)n_ktiles;
+        }
+    };
+#endif
     if (t.split_k > 1) {  // partial sums; the fixed-order reduction kernel finishes the job
         float* ws = static_cast<float*>(t.workspace) + (int64_t)split * t.M * t.N;
 #pragma unroll
@@ -134,6 +148,9 @@ __global__ __launch_bounds__(NT) void gemm_f16_kernel(GemmTables t, float alpha,
                     if (row < tile.m_len && col < tile.n_len)
                         ws[(int64_t)(tile.m_glob + row) * t.N + tile.n_glob + col] = acc[i][j][r];
                 }
+#ifdef DMATH_CYCLE_PROBE
+        record_probe();
+#endif
         return;
     }
 
@@ -161,16 +178,7 @@ __global__ __launch_bounds__(NT) void gemm_f16_kernel(GemmTables t, float alpha,
     if (tile.m_len == BM && tile.n_len == BN) store(std::false_type{});
     else store(std::true_type{});
 #ifdef DMATH_CYCLE_PROBE
-    __syncthreads();
-    if (tid == 0 && tile.m_glob == 0 && tile.n_glob == 0) {
-        const uint64_t t_end = __builtin_amdgcn_s_memtime(), r_end = __builtin_amdgcn_s_memrealtime();
-        g_cycle_probe[0] = probe.t_prologue - t_start;
-        g_cycle_probe[1] = t_loop_end - probe.t_prologue;
-        g_cycle_probe[2] = t_end - t_loop_end;
-        g_cycle_probe[3] = probe.t_wait;
-        g_cycle_probe[4] = r_end - r_start;
-        g_cycle_probe[5] = (uint64_t)n_ktiles;
-    }
+    record_probe();
 #endif
 }
 
