@@ -1,11 +1,11 @@
-// Specialised fp16 convolution kernels for gfx950 (stride 1): forward and weight gradient as
-// implicit GEMMs on the MFMA pipeline of f16_pipeline.hpp (paper abstract: convolutions;
+// Specialised fp16 convolution kernels for gfx950 (stride 1): forward, weight gradient and data
+// gradient as implicit GEMMs on the MFMA pipeline of f16_pipeline.hpp (paper abstract: convolutions;
 // section 1: data reorganisation to support a series of operations).
 //
 // NCHW keeps pixels, not channels, contiguous, and the 3x3 taps shift the pixel index by +-1,
-// which no 16-byte load can follow.  So every call first rewrites its activations into a
+// which no 16-byte load can follow.  So the activations are first rewritten into a
 // zero-bordered channels-last copy in the pool,
-//     Xp[n][h + 2*pad_h][w + 2*pad_w][c]          (borders zeroed once, when the plan is made)
+//     Xp[n][h + 2*pad_h][w + 2*pad_w][c]          (borders zeroed once, when the copy is allocated)
 // after which row (n, oh, ow) of the lowered matrix for tap (r, s) is the contiguous c-vector
 // at Xp[n][oh + r][ow + s][:]: a k unit-stride operand whose rows are gathered, with K ordered
 // (r, s, c) and no masks.  The filter is permuted to the same K order, Fp[k][(r,s,c)].
