@@ -596,14 +596,15 @@ dmath_status_t dmath_conv_tune(dmath_ctx_t ctx, int32_t mode, const dmath_conv_d
         free_conv_plan(ctx, *plan);
         if (us < 0) return DMATH_ERR_DEVICE;
         ++result->candidates;
-        const bool is_model = c.kernel == model.kernel && c.tile_n == model.tile_n && c.split_k == model.split_k;
+        const bool is_model = c.kernel == model.kernel && c.tile_m == model.tile_m && c.tile_n == model.tile_n &&
+                              c.split_k == model.split_k;
         if (is_model) result->default_us = us;
         const double handicap = is_model ? 0.98 : 1.0;
         if (best < 0 || us * handicap < best) {
             best = us * handicap;
             best_choice = c;
             result->kernel = c.kernel;
-            result->tile_m = c.kernel == 1 ? 256 : 64;
+            result->tile_m = c.kernel == 1 ? (c.tile_m ? c.tile_m : 256) : 64;
             result->tile_n = c.kernel == 1 ? (mode == CONV_BWD_FILTER ? 128 : c.tile_n) : 64;
             result->split_k = c.split_k;
             result->workspace_bytes = need;

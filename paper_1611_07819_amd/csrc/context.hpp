@@ -93,12 +93,13 @@ struct ConvPlan {
     Relayout* yt = nullptr;  // weight gradient: dY channels-last, [n*oh*ow][k]
     int32_t kernel = 0;  // 0 generic, 1 specialised fp16
     int32_t tile_n = 0;  // specialised forward / data gradient: 128 or 256 output channels per tile
+    int32_t tile_m = 0;  //   and 256 or 224 pixels
     dmath_dtype_t in_dtype = DMATH_F16, out_dtype = DMATH_F32;
 };
 
 // Kernel / tile / split-K decision for a convolution.
 struct ConvChoice {
-    int32_t kernel = 0, tile_n = 0, split_k = 1;
+    int32_t kernel = 0, tile_m = 0, tile_n = 0, split_k = 1;
 };
 
 using GemmKey = std::tuple<uint64_t, uint64_t, uint64_t, int, int>;

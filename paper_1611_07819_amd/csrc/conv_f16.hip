@@ -203,7 +203,7 @@ __global__ __launch_bounds__(NT) void conv_fwd_f16_kernel(FastConv p, float alph
     const int m0 = (idx / tiles_n) * BM, n0 = (idx % tiles_n) * BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1, h = lane >> 5, l32 = lane & 31;
+    const int wm = TS::wm(wave), wn = TS::wn(wave), h = lane >> 5, l32 = lane & 31;
 
     v16f acc[MT][NTL];
 #pragma unroll
@@ -317,7 +317,7 @@ __global__ __launch_bounds__(NT) void conv_wgrad_f16_kernel(FastConv p)
     const int m0 = (mn / tiles_n) * BM, n0 = (mn % tiles_n) * BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31;
+    const int wm = TS::wm(wave), wn = TS::wn(wave), l32 = lane & 31;
 
     v16f acc[MT][NTL];
 #pragma unroll
@@ -447,6 +447,13 @@ ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int3
     bool wide = n_out % 256 == 0 && t128 > 256 && t256 <= 256;
     if (const char* force = std::getenv("DMATH_CONV_TILE")) wide = n_out % 256 == 0 && std::strcmp(force, "256x256") == 0;
     ch.tile_n = wide ? 256 : 128;
+    // 224-row tiles where they shorten the longest chain of tiles a CU works through (50176
+    // pixels: 224 tiles of 224 rows instead of 196 of 256, both one round)
+    ch.tile_m = 256;
+    if (wide) {
+        const int64_t t224 = (m + 223) / 224 * (n_out / 256);
+        if (((t224 + 255) / 256) * 224 < ((t256 + 255) / 256) * 256) ch.tile_m = 224;
+    }
     return ch;
 }
 
@@ -481,12 +488,36 @@ std::vector<ConvChoice> conv_candidates(int mode, const ConvGeom& g, dmath_dtype
     }
     const int n_out = mode == CONV_FWD ? g.k : g.c;
     c.tile_n = 128;
+    c.tile_m = 256;
     out.push_back(c);
     if (n_out % 256 == 0) {
         c.tile_n = 256;
         out.push_back(c);
+        c.tile_m = 224;
+        out.push_back(c);
     }
     return out;
+}
+
+// Launches the forward kernel (also the data gradient's) on tiles of tile_m x tile_n.
+template <int BM, int BN, int STAGES>
+static void launch_fwd_shape(const FastConv& p, dmath_dtype_t out, float alpha, float beta, hipStream_t st)
+{
+    const int64_t m = (int64_t)p.g.n * p.g.oh * p.g.ow;
+    const int tiles = (int)((m + BM - 1) / BM) * (p.g.k / BN);
+    constexpr int lds = STAGES * (BM + BN) * 128;
+    if (out == DMATH_F16)
+        conv_fwd_f16_kernel<BM, BN, STAGES, _Float16><<<tiles, NT, lds, st>>>(p, alpha, beta);
+    else
+        conv_fwd_f16_kernel<BM, BN, STAGES, float><<<tiles, NT, lds, st>>>(p, alpha, beta);
+}
+
+static void launch_fwd(const FastConv& p, int tile_m, int tile_n, dmath_dtype_t out, float alpha, float beta,
+                       hipStream_t st)
+{
+    if (tile_n == 256 && tile_m == 224) launch_fwd_shape<224, 256, 2>(p, out, alpha, beta, st);
+    else if (tile_n == 256) launch_fwd_shape<256, 256, 2>(p, out, alpha, beta, st);
+    else launch_fwd_shape<256, 128, 3>(p, out, alpha, beta, st);
 }
 
 hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double beta, unsigned rewrite,
@@ -522,6 +553,8 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
         if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 128, 3, _Float16>, 3 * 384 * 128);
         if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 256, 2, float>, 2 * 512 * 128);
         if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 256, 2, _Float16>, 2 * 512 * 128);
+        if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<224, 256, 2, float>, 2 * 480 * 128);
+        if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<224, 256, 2, _Float16>, 2 * 480 * 128);
         if (e == hipSuccess) e = set_lds(conv_wgrad_f16_kernel<256, 128>, 3 * 384 * 128);
         if (e == hipSuccess) e = set_lds(conv_wgrad_f16_kernel<128, 128>, 3 * 256 * 128);
         if (e != hipSuccess) return e;
@@ -541,40 +574,14 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
         if (rewrite & REWRITE_X) to_channels_last(t.y_rows, g.n, g.k, g.oh, g.ow, pph, ppw, q.hp, q.wp, xp, st);
         if (rewrite & REWRITE_F)
             filter_to_rsk_rotated_kernel<<<512, 256, 0, st>>>(t.f_rows, g.c, g.r, g.s, g.k, fp);
-        const int mt = (int)(((int64_t)g.n * g.h * g.w + 255) / 256);
-        const int t128 = mt * (g.c / 128), t256 = mt * (g.c / 256);
-        const bool wide = plan.tile_n == 256;
-        if (wide) {
-            if (plan.out_dtype == DMATH_F16)
-                conv_fwd_f16_kernel<256, 256, 2, _Float16><<<t256, NT, 2 * 512 * 128, st>>>(q, (float)alpha, (float)beta);
-            else
-                conv_fwd_f16_kernel<256, 256, 2, float><<<t256, NT, 2 * 512 * 128, st>>>(q, (float)alpha, (float)beta);
-        } else {
-            if (plan.out_dtype == DMATH_F16)
-                conv_fwd_f16_kernel<256, 128, 3, _Float16><<<t128, NT, 3 * 384 * 128, st>>>(q, (float)alpha, (float)beta);
-            else
-                conv_fwd_f16_kernel<256, 128, 3, float><<<t128, NT, 3 * 384 * 128, st>>>(q, (float)alpha, (float)beta);
-        }
+        launch_fwd(q, plan.tile_m, plan.tile_n, plan.out_dtype, (float)alpha, (float)beta, st);
         return hipGetLastError();
     }
     // activations -> zero-bordered channels-last copy (borders were zeroed when the copy was allocated)
     if (rewrite & REWRITE_X) to_channels_last(t.x_rows, g.n, g.c, g.h, g.w, g.pad_h, g.pad_w, p.hp, p.wp, xp, st);
     if (mode == CONV_FWD) {
         if (rewrite & REWRITE_F) filter_to_rsc_kernel<<<512, 256, 0, st>>>(t.f_rows, g.c, g.r * g.s, g.k, fp);
-        const int mt = (int)(((int64_t)g.n * g.oh * g.ow + 255) / 256);
-        const int t128 = mt * (g.k / 128), t256 = mt * (g.k / 256);
-        const bool wide = plan.tile_n == 256;
-        if (wide) {
-            if (plan.out_dtype == DMATH_F16)
-                conv_fwd_f16_kernel<256, 256, 2, _Float16><<<t256, NT, 2 * 512 * 128, st>>>(p, (float)alpha, (float)beta);
-            else
-                conv_fwd_f16_kernel<256, 256, 2, float><<<t256, NT, 2 * 512 * 128, st>>>(p, (float)alpha, (float)beta);
-        } else {
-            if (plan.out_dtype == DMATH_F16)
-                conv_fwd_f16_kernel<256, 128, 3, _Float16><<<t128, NT, 3 * 384 * 128, st>>>(p, (float)alpha, (float)beta);
-            else
-                conv_fwd_f16_kernel<256, 128, 3, float><<<t128, NT, 3 * 384 * 128, st>>>(p, (float)alpha, (float)beta);
-        }
+        launch_fwd(p, plan.tile_m, plan.tile_n, plan.out_dtype, (float)alpha, (float)beta, st);
         return hipGetLastError();
     }
     // weight gradient: dY -> channels-last [m][k], split GEMM, fixed-order reduction

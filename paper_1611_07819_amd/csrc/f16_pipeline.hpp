@@ -1,7 +1,7 @@
 // The fp16-input / fp32-accumulate MFMA pipeline shared by the GEMM and the implicit-GEMM
 // convolution kernels (v_mfma_f32_32x32x16_f16, gfx950).
 //
-// A workgroup of 4 wavefronts (2 x 2) multiplies a BM x BN tile; k is walked 64 at a time
+// A workgroup of 4 wavefronts (2 x 2, or 1 x 4 for the 224-row tile) multiplies a BM x BN tile; k is walked 64 at a time
 // through a ring of STAGES LDS stages.
 //
 // Global -> LDS without registers: every wavefront issues global_load_lds_dwordx4, which
@@ -136,9 +136,14 @@ template <class TC> __device__ __forceinline__ TC to_out(float v);
 template <> __device__ __forceinline__ float to_out<float>(float v) { return v; }
 template <> __device__ __forceinline__ _Float16 to_out<_Float16>(float v) { return (_Float16)v; }
 
+// The four wavefronts tile BM x BN as 2 x 2, or as 1 x 4 where BM is not a multiple of 64
+// (224 rows: seven 32-row blocks per wavefront).
 template <int BM, int BN> struct TileShape {
-    static constexpr int WM = BM / 2, WN = BN / 2;  // wavefront tile
+    static constexpr int WVM = BM % 64 == 0 ? 2 : 1, WVN = 4 / WVM;  // wavefronts along m and n
+    static constexpr int WM = BM / WVM, WN = BN / WVN;               // wavefront tile
     static constexpr int MT = WM / 32, NTL = WN / 32;
+    __device__ __forceinline__ static int wm(int wave) { return wave / WVN; }
+    __device__ __forceinline__ static int wn(int wave) { return wave % WVN; }
 };
 
 // Measurement hooks of run(): nothing by default.  CycleProbe (gemm_f16.hip, opt-in build) reads
@@ -167,7 +172,7 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1, h = lane >> 5, l32 = lane & 31;
+    const int wm = TS::wm(wave), wn = TS::wn(wave), h = lane >> 5, l32 = lane & 31;
 
     uint32_t fa_base[MT], fb_base[NTL];
 #pragma unroll

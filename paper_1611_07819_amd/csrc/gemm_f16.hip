@@ -98,7 +98,7 @@ __global__ __launch_bounds__(NT) void gemm_f16_kernel(GemmTables t, float alpha,
     const Tile tile = t.tiles[blockIdx.x];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31;
+    const int wm = TS::wm(wave), wn = TS::wn(wave), l32 = lane & 31;
 
     v16f acc[MT][NTL];
 #pragma unroll

@@ -533,6 +533,7 @@ dmath_status_t make_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_
     const bool fast = ch.kernel == 1;
     plan->kernel = ch.kernel;
     plan->tile_n = ch.tile_n;
+    plan->tile_m = ch.tile_m;
     t.split_k = ch.split_k;  // weight gradient only: few C tiles, very deep K
 
     auto row_ptrs = [](const dmath_matrix_s* m) {
