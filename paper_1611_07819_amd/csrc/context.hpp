@@ -62,6 +62,9 @@ struct GemmPlan {
     void* workspace = nullptr;
     dmath_plan_info_t info{};
     dmath_dtype_t in_dtype = DMATH_F32, out_dtype = DMATH_F32;
+    // the reduction / beta-only kernel may move 16 bytes per lane: every n-segment a multiple of
+    // 4, every C panel and the workspace rows 16-byte aligned
+    bool reduce_vectors = false;
 };
 
 enum ConvMode : int32_t { CONV_FWD = 0, CONV_BWD_FILTER = 1, CONV_BWD_DATA = 2 };

@@ -13,6 +13,8 @@
 
 namespace dm {
 
+hipError_t launch_gemm_reduce(const GemmPlan& p, int n_partials, double alpha, double beta, hipStream_t st);
+
 namespace {
 
 constexpr int GT = 64;   // tile edge
@@ -188,11 +190,20 @@ __global__ __launch_bounds__(GTHREADS) void gemm_generic_kernel(GemmTables t, do
 // Fixed-order sum of the split-K partials followed by the epilogue; with n_partials == 0 it is
 // the alpha == 0 path (C <- beta * C) that never touches A or B.  Grid: (tiles, row chunks of
 // kReduceRows rows), so that few large tiles still fill the chip.
+template <class T, int N> struct VecOf {
+    typedef T type __attribute__((ext_vector_type(N)));
+};
+
+// VEC consecutive columns per lane (16 bytes of the accumulation type) where the plan says that
+// every tile's width, origin and the leading dimensions allow it: the loads of all partials of
+// a lane's columns are then in flight together.
 constexpr int kReduceRows = 8;
-template <class AccT, class TC>
+template <class AccT, class TC, int VEC>
 __global__ __launch_bounds__(GTHREADS) void gemm_reduce_kernel(GemmTables t, int n_partials,
                                                                double alpha_d, double beta_d)
 {
+    typedef typename VecOf<AccT, VEC>::type vacc;
+    typedef typename VecOf<TC, VEC>::type vout;
     const Tile tile = t.tiles[blockIdx.x];
     const int r0 = blockIdx.y * kReduceRows;
     if (r0 >= tile.m_len) return;
@@ -202,19 +213,33 @@ __global__ __launch_bounds__(GTHREADS) void gemm_reduce_kernel(GemmTables t, int
     const AccT* ws = static_cast<const AccT*>(t.workspace);
     const AccT alpha = static_cast<AccT>(alpha_d), beta = static_cast<AccT>(beta_d);
     const int64_t slice = t.M * t.N;
-    const int count = rows * tile.n_len;
+    const int vcols = tile.n_len / VEC;
+    const int count = rows * vcols;
     for (int e = threadIdx.x; e < count; e += GTHREADS) {
-        const int i = r0 + e / tile.n_len, j = e % tile.n_len;
+        const int i = r0 + e / vcols, j = (e % vcols) * VEC;
         const AccT* p = ws + (int64_t)(tile.m_glob + i) * t.N + tile.n_glob + j;
-        AccT sum = AccT(0);
+        vacc sum;
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) sum[q] = AccT(0);
         int s = 0;
         for (; s + 4 <= n_partials; s += 4) {  // four loads in flight, added in ascending order
-            const AccT p0 = p[(int64_t)s * slice], p1 = p[(int64_t)(s + 1) * slice];
-            const AccT p2 = p[(int64_t)(s + 2) * slice], p3 = p[(int64_t)(s + 3) * slice];
+            const vacc p0 = *reinterpret_cast<const vacc*>(p + (int64_t)s * slice);
+            const vacc p1 = *reinterpret_cast<const vacc*>(p + (int64_t)(s + 1) * slice);
+            const vacc p2 = *reinterpret_cast<const vacc*>(p + (int64_t)(s + 2) * slice);
+            const vacc p3 = *reinterpret_cast<const vacc*>(p + (int64_t)(s + 3) * slice);
             sum = (((sum + p0) + p1) + p2) + p3;
         }
-        for (; s < n_partials; ++s) sum += p[(int64_t)s * slice];
-        epilogue_store(c + (int64_t)(tile.m_off + i) * pc.ld + tile.n_off + j, sum, alpha, beta);
+        for (; s < n_partials; ++s) sum += *reinterpret_cast<const vacc*>(p + (int64_t)s * slice);
+        TC* dst = c + (int64_t)(tile.m_off + i) * pc.ld + tile.n_off + j;
+        vout o;
+        if (beta != AccT(0)) o = *reinterpret_cast<const vout*>(dst);
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) {
+            AccT v = alpha * sum[q];
+            if (beta != AccT(0)) v += beta * static_cast<AccT>(o[q]);
+            o[q] = static_cast<TC>(v);
+        }
+        *reinterpret_cast<vout*>(dst) = o;
     }
 }
 
@@ -361,14 +386,12 @@ hipError_t run_gemm_generic(const GemmPlan& p, double alpha, double beta, hipStr
     using AccT = typename Traits<T>::acc_t;
     const GemmTables& t = p.t;
     if (alpha == 0.0) {
-        gemm_reduce_kernel<AccT, TC><<<reduce_grid(p), GTHREADS, 0, st>>>(t, 0, 0.0, beta);
-        return hipGetLastError();
+        return launch_gemm_reduce(p, 0, 0.0, beta, st);
     }
     gemm_generic_kernel<T, TC><<<dim3(t.n_tiles, t.split_k), GTHREADS, 0, st>>>(t, alpha, beta);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || t.split_k == 1) return e;
-    gemm_reduce_kernel<AccT, TC><<<reduce_grid(p), GTHREADS, 0, st>>>(t, t.split_k, alpha, beta);
-    return hipGetLastError();
+    return launch_gemm_reduce(p, t.split_k, alpha, beta, st);
 }
 
 template <class T, class TC, int MODE>
@@ -413,15 +436,24 @@ hipError_t launch_gemm_generic(const GemmPlan& p, double alpha, double beta, hip
 
 // C <- alpha * (sum of the first n_partials split-K partials, ascending) + beta * C, for any
 // tile shape.  n_partials == 0 is the alpha == 0 path: A and B are never read.
+template <class AccT, class TC>
+static void reduce_launch(const GemmPlan& p, int n_partials, double alpha, double beta, hipStream_t st)
+{
+    constexpr int kVec = 16 / sizeof(AccT);
+    if (p.reduce_vectors)
+        gemm_reduce_kernel<AccT, TC, kVec><<<reduce_grid(p), GTHREADS, 0, st>>>(p.t, n_partials, alpha, beta);
+    else
+        gemm_reduce_kernel<AccT, TC, 1><<<reduce_grid(p), GTHREADS, 0, st>>>(p.t, n_partials, alpha, beta);
+}
+
 hipError_t launch_gemm_reduce(const GemmPlan& p, int n_partials, double alpha, double beta, hipStream_t st)
 {
-    const GemmTables& t = p.t;
     if (p.in_dtype == DMATH_F64)
-        gemm_reduce_kernel<double, double><<<reduce_grid(p), GTHREADS, 0, st>>>(t, n_partials, alpha, beta);
+        reduce_launch<double, double>(p, n_partials, alpha, beta, st);
     else if (p.out_dtype == DMATH_F32)
-        gemm_reduce_kernel<float, float><<<reduce_grid(p), GTHREADS, 0, st>>>(t, n_partials, alpha, beta);
+        reduce_launch<float, float>(p, n_partials, alpha, beta, st);
     else
-        gemm_reduce_kernel<float, _Float16><<<reduce_grid(p), GTHREADS, 0, st>>>(t, n_partials, alpha, beta);
+        reduce_launch<float, _Float16>(p, n_partials, alpha, beta, st);
     return hipGetLastError();
 }
 

@@ -372,6 +372,14 @@ dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_ma
     plan->uses = {A->id, B->id, C->id};
     plan->in_dtype = A->dtype;
     plan->out_dtype = C->dtype;
+    plan->reduce_vectors = N % 4 == 0;
+    for (auto& n : ns) plan->reduce_vectors = plan->reduce_vectors && n.len % 4 == 0 && n.start % 4 == 0;
+    for (auto& m : ms)
+        for (auto& n : ns) {
+            const Panel pc_ = locate(C, m.start, n.start);
+            plan->reduce_vectors = plan->reduce_vectors && reinterpret_cast<uintptr_t>(pc_.ptr) % 16 == 0 &&
+                                   pc_.ld % 8 == 0;
+        }
     dmath_plan_info_t& info = plan->info;
     info.m = M;
     info.n = N;
