@@ -90,3 +90,44 @@ def test_recording_an_operation_without_a_plan_is_refused(ctx):
     ctx.pipeline_destroy(pid)
     dm.gemm(ctx, 0, 0, 1.0, A, B, 0.0, C)
     assert np.array_equal(C.get(), np.full((128, 128), 128, np.float32))
+
+
+def test_replay_with_workspaces_split_k_and_weight_gradient(ctx, oracle):
+    """Operations that go through pool workspaces (split-K partial sums and their reduction
+    kernel, the weight gradient's partial sums, accumulation with beta = 1) replayed three times
+    on changing inputs: every replay must equal the eager run bit for bit and the oracle."""
+    r = np.random.default_rng(801)
+    M, N, K = 64, 512, 4096                       # few tiles, deep K: split-K + reduction kernel
+    A = r.integers(-2, 3, (M, K)).astype(np.float16)
+    B = r.integers(-2, 3, (K, N)).astype(np.float16)
+    dA, dB, dC = ctx.from_host(A), ctx.from_host(B), ctx.matrix(M, N, (1, 1), dm.F32)
+    assert dm.gemm_plan_info(ctx, 0, 0, dA, dB, dC)["split_k"] > 1
+    geo = dict(n=4, c=128, h=16, w=16, k=256, r=3, s=3, pad_h=1, pad_w=1)
+    cd, od = dm.ConvDesc(**geo), oracle.ConvDesc(**geo)
+    hx = r.integers(-1, 2, (4, 128 * 256)).astype(np.float16)
+    hy = r.integers(-1, 2, (4, 256 * 256)).astype(np.float16)
+    dX, dY = ctx.from_host(hx), ctx.from_host(hy)
+    dF = ctx.matrix(256, 128 * 9, (1, 1), dm.F32)
+
+    def step():
+        dm.gemm(ctx, 0, 0, 1.0, dA, dB, 1.0, dC)                 # accumulates into C
+        dm.conv_bwd_filter(ctx, cd, 1.0, dX, dY, 0.0, dF)
+
+    dC.set(np.zeros((M, N), np.float32))
+    step()
+    ctx.pipeline_begin()
+    step()
+    pid = ctx.pipeline_end()
+    for rep in range(3):
+        A2 = r.integers(-2, 3, (M, K)).astype(np.float16)
+        x2 = r.integers(-1, 2, hx.shape).astype(np.float16)
+        c0 = r.integers(-3, 4, (M, N)).astype(np.float32)
+        dA.set(A2); dX.set(x2); dC.set(c0)
+        ctx.pipeline_replay(pid)
+        got_c, got_f = dC.get(), dF.get()
+        assert np.array_equal(got_c.astype(np.float64), oracle.gemm(False, False, 1.0, A2, B, 1.0, c0))
+        assert np.array_equal(got_f.astype(np.float64), oracle.conv_bwd_filter(od, 1.0, x2, hy))
+        dC.set(c0)
+        step()
+        assert np.array_equal(dC.get(), got_c) and np.array_equal(dF.get(), got_f)
+    ctx.pipeline_destroy(pid)
