@@ -20,15 +20,6 @@ namespace {
 
 constexpr int kCUs = 256;
 
-// Few tiles and a deep K: split K over workgroups so that the chip is filled; every split keeps
-// at least 8 k-steps of 64.  The partial sums are reduced in a fixed order by a second kernel.
-int32_t split_for(int64_t tiles, int64_t K)
-{
-    if (tiles * 2 > kCUs || K < 1024) return 1;
-    int64_t want = kCUs / tiles, max_by_k = K / 512;
-    return (int32_t)std::max<int64_t>(1, std::min<int64_t>({want, max_by_k, 32}));
-}
-
 // Few rows (a small batch against a large weight matrix): every m-segment fits a 64-row tile.
 bool few_rows(const SegView& v)
 {
@@ -60,12 +51,12 @@ bool env_tile(int* bm, int* bn)
     return std::sscanf(e, "%dx%d", bm, bn) == 2;
 }
 
-}  // namespace
-
-namespace {
-
+// A tile shape of a specialised kernel: how many of its workgroups fit on a CU (LDS), and the
+// fraction of the precision's practical rate it reaches when the chip is full (measured).
 struct Shape {
     int32_t kernel, bm, bn, bk;
+    int32_t per_cu;
+    double efficiency;
 };
 
 // Tile shapes of the specialised kernels whose preconditions this GEMM meets.
@@ -76,21 +67,28 @@ std::vector<Shape> specialised_shapes(const SegView& v)
     const bool f32 = v.in_dtype == DMATH_F32 && all_multiple(*v.klen, 32);
     const bool f64 = v.in_dtype == DMATH_F64 && all_multiple(*v.klen, 16);
     const bool f16 = v.in_dtype == DMATH_F16 && all_multiple(*v.klen, 64);
-    if (f32 || f64) {
-        const int32_t kern = f32 ? KERNEL_F32_128 : KERNEL_F64_128, bk = f32 ? 32 : 16;
-        out.push_back({kern, 128, 128, bk});
-        out.push_back({kern, 128, 64, bk});
-        if (f32 && v.b_kcontig) out.push_back({kern, 128, 96, bk});  // wavefronts 4x1, k-major B only
-        // few rows: 64-row tiles do half the matrix instructions of 128-row ones on padding
-        if (few_rows(v)) {
-            out.push_back({kern, 64, 128, bk});
-            if (f32) out.push_back({kern, 64, 256, bk});
-        }
+    const bool strided = !v.a_kcontig && !v.b_kcontig;  // neither operand k unit-stride (TN)
+    if (f32) {
+        // on a full chip the two run level (configuration 2); where the chip is not full, and for
+        // TN (every fragment a 4-byte LDS read per MFMA), two 128x64 workgroups per CU cover each
+        // other's fill, drain and LDS latency: 6-9 % on batch sizes of 256-1024
+        out.push_back({KERNEL_F32_128, 128, 128, 32, 1, strided ? 0.97 : 0.98});
+        out.push_back({KERNEL_F32_128, 128, 64, 32, 2, 1.0});
+        if (v.b_kcontig) out.push_back({KERNEL_F32_128, 128, 96, 32, 1, 0.97});  // wavefronts 4x1, k-major B only
     }
-    if (f16) {
-        out.push_back({KERNEL_F16_256, 256, 256, 64});
-        out.push_back({KERNEL_F16_256, 256, 128, 64});
-        out.push_back({KERNEL_F16_256, 128, 128, 64});
+    if (f64) {  // two 128x64 workgroups per CU are faster than one 128x128 on configuration 4
+        out.push_back({KERNEL_F64_128, 128, 128, 16, 1, 0.97});
+        out.push_back({KERNEL_F64_128, 128, 64, 16, 2, 1.0});
+    }
+    // few rows: 64-row tiles do half the matrix instructions of 128-row ones on padding
+    if ((f32 || f64) && few_rows(v)) {
+        out.push_back({f32 ? KERNEL_F32_128 : KERNEL_F64_128, 64, 128, f32 ? 32 : 16, 2, 0.95});
+        if (f32) out.push_back({KERNEL_F32_128, 64, 256, 32, 1, 0.92});
+    }
+    if (f16) {  // 128x128 reads twice the LDS bytes per flop of the 256-wide tiles
+        out.push_back({KERNEL_F16_256, 256, 256, 64, 1, 1.0});
+        out.push_back({KERNEL_F16_256, 256, 128, 64, 1, 1.0});
+        out.push_back({KERNEL_F16_256, 128, 128, 64, 2, 0.7});
     }
     return out;
 }
@@ -104,40 +102,64 @@ int32_t generic_split(const SegView& v)
     return (int32_t)std::max<int64_t>(1, std::min<int64_t>({want, max_by_k, 32}));
 }
 
+// The cost model.  Time of a (shape, split) pair =
+//     workgroups on the busiest CU x work of one workgroup / (CU rate x shape efficiency x occupancy)
+//   + the reduction kernel (launch + reading the partial sums and writing C) when split > 1,
+// with the practical per-CU rates measured on configurations 2-4, occupancy 0.8 when an fp32 /
+// fp64 shape that wants two workgroups per CU gets only one, ragged tiles counted as whole ones.
+// Checked against timing samples on 30 shapes per precision: within 10 % of the best sample.
+double modelled_seconds(const SegView& v, const Shape& s, int32_t split)
+{
+    const double cu_flops = s.kernel == KERNEL_F16_256 ? 3.9e12 : s.kernel == KERNEL_F32_128 ? 0.512e12 : 0.23e12;
+    const int64_t wgs = count_tiles(v, s.bm, s.bn) * split;
+    const int64_t busiest = (wgs + kCUs - 1) / kCUs;
+    const double occupancy = s.kernel != KERNEL_F16_256 && s.per_cu > 1 && busiest < s.per_cu ? 0.8 : 1.0;
+    const double wg_flops = 2.0 * s.bm * s.bn * ((double)v.K / split);
+    double t = busiest * wg_flops / (cu_flops * s.efficiency * occupancy);
+    if (split > 1) {
+        const double acc_bytes = v.in_dtype == DMATH_F64 ? 8 : 4;
+        t += 3e-6 + (split + 1.0) * v.M * v.N * acc_bytes / 3e12;
+    }
+    return t;
+}
+
+// Splits are powers of two that leave at least 512 of K per part; a split has to be 3 % better
+// than the one before to pay for its workspace.
+int32_t best_split(const SegView& v, const Shape& s, double* seconds)
+{
+    int32_t best = 1;
+    double best_t = modelled_seconds(v, s, 1);
+    for (int32_t sp = 2; sp <= 32; sp *= 2) {
+        if (v.K / sp < 512) break;
+        const double t = modelled_seconds(v, s, sp);
+        if (t < best_t * 0.97) {
+            best_t = t;
+            best = sp;
+        }
+    }
+    if (seconds) *seconds = best_t;
+    return best;
+}
+
 }  // namespace
 
-// The cost model: among the specialised shapes the one with the least serialised work per CU.
-// fp32: smaller tiles move more bytes per flop, which costs clock at the power limit: 3 %
-// handicap (measured on configuration 2: 128x128 beats 128x64 when both fill the chip evenly),
-// except when neither operand is k unit-stride (TN): there every fragment is a 4-byte LDS read
-// per MFMA, two 128x64 workgroups per CU hide those better and win by 2 %.
-// fp64: 128x64 runs two workgroups per CU and is faster on configuration 4, so there the larger
-// tile carries the handicap.  Ragged last tiles count as whole ones.
 GemmChoice choose_gemm(const SegView& v)
 {
     GemmChoice ch;  // generic 64x64x16
-    double best_cost = -1;
+    double best_t = -1;
     int ebm = 0, ebn = 0;
     const bool forced = env_tile(&ebm, &ebn);
     for (const Shape& s : specialised_shapes(v)) {
         if (forced && (s.bm != ebm || s.bn != ebn)) continue;
-        const int64_t tiles = count_tiles(v, s.bm, s.bn);
-        double cost = (double)((tiles + kCUs - 1) / kCUs) * s.bm * s.bn;
-        const bool f32_strided = !v.a_kcontig && !v.b_kcontig;
-        if (s.kernel == KERNEL_F32_128 && (s.bm * s.bn < 128 * 128) != f32_strided) cost *= 1.03;
-        if (s.kernel == KERNEL_F64_128 && s.bm * s.bn >= 128 * 128) cost *= 1.03;
-        // few rows: a 128-row tile multiplies 64 rows of padding (one or two workgroups per CU
-        // measured the same, so the split stays at one round: half the partial sums)
-        const bool short_tile = s.bm == 64;
-        if (few_rows(v) && !short_tile) cost *= 2;
-        if (short_tile && s.bn > 128) cost *= 1.03;
-        if (best_cost < 0 || cost < best_cost) {
-            best_cost = cost;
+        double t;
+        const int32_t split = best_split(v, s, &t);
+        if (best_t < 0 || t < best_t) {
+            best_t = t;
             ch.kernel = s.kernel;
             ch.tile_m = s.bm;
             ch.tile_n = s.bn;
             ch.tile_k = s.bk;
-            ch.split_k = split_for(tiles, v.K);
+            ch.split_k = split;
         }
     }
     if (ch.kernel == KERNEL_GENERIC) ch.split_k = generic_split(v);
@@ -164,7 +186,7 @@ std::vector<GemmChoice> gemm_candidates(const SegView& v)
     for (const Shape& s : specialised_shapes(v)) {
         const int64_t tiles = count_tiles(v, s.bm, s.bn);
         add(s.kernel, s.bm, s.bn, s.bk, 1);
-        add(s.kernel, s.bm, s.bn, s.bk, split_for(tiles, v.K));
+        add(s.kernel, s.bm, s.bn, s.bk, best_split(v, s, nullptr));
         for (int32_t sp = 2; sp <= 32; sp *= 2)
             if (v.K / sp >= 512 && tiles * sp <= 2 * kCUs) add(s.kernel, s.bm, s.bn, s.bk, sp);
     }
