@@ -112,7 +112,9 @@ double modelled_seconds(const SegView& v, const Shape& s, int32_t split)
 {
     const double cu_flops = s.kernel == KERNEL_F16_256 ? 3.9e12 : s.kernel == KERNEL_F32_128 ? 0.512e12 : 0.23e12;
     const int64_t wgs = count_tiles(v, s.bm, s.bn) * split;
-    const int64_t busiest = (wgs + kCUs - 1) / kCUs;
+    // workgroups are dispatched in rounds that fill every slot of the chip (per_cu per CU)
+    const int64_t slots = (int64_t)kCUs * s.per_cu;
+    const int64_t busiest = wgs <= kCUs ? 1 : (wgs + slots - 1) / slots * s.per_cu;
     const double occupancy = s.kernel != KERNEL_F16_256 && s.per_cu > 1 && busiest < s.per_cu ? 0.8 : 1.0;
     const double wg_flops = 2.0 * s.bm * s.bn * ((double)v.K / split);
     double t = busiest * wg_flops / (cu_flops * s.efficiency * occupancy);
