@@ -405,14 +405,21 @@ static int64_t wgrad_tiles(const ConvGeom& g)
     return (int64_t)(g.k == 128 ? 1 : g.k / 256) * ((int64_t)g.c * g.r * g.s / 128);
 }
 
-// Split count for the weight gradient: enough workgroups to fill the chip, dividing the k-tiles.
+// Split count for the weight gradient: a divisor s of the k-tiles with at most one round of
+// workgroups that minimises (k-tiles per part + s): the parts shorten with s, the partial sums
+// written and read back grow with it (the balance point sqrt(k-tiles) matches the timing
+// samples on 1x1 and 3x3 layers of 14x14 and 28x28 pixels).
 int conv_f16_wgrad_split(const ConvGeom& g)
 {
     const int64_t ktiles = (int64_t)g.n * g.oh * g.ow / 64;
     const int64_t tiles = wgrad_tiles(g);
     int best = 1;
-    for (int s = 1; s <= 64; ++s)
-        if (ktiles % s == 0 && tiles * s <= 256 && ktiles / s >= 8) best = s;
+    int64_t best_cost = ktiles + 1;
+    for (int s = 2; s <= 64; ++s)
+        if (ktiles % s == 0 && tiles * s <= 256 && ktiles / s >= 8 && ktiles / s + s < best_cost) {
+            best_cost = ktiles / s + s;
+            best = s;
+        }
     return best;
 }
 
@@ -443,16 +450,23 @@ ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int3
     }
     const int64_t m = mode == CONV_FWD ? (int64_t)g.n * g.oh * g.ow : (int64_t)g.n * g.h * g.w;
     const int n_out = mode == CONV_FWD ? g.k : g.c;
-    const int64_t t128 = (m + 255) / 256 * (n_out / 128), t256 = (m + 255) / 256 * (n_out / 256);
-    bool wide = n_out % 256 == 0 && t128 > 256 && t256 <= 256;
-    if (const char* force = std::getenv("DMATH_CONV_TILE")) wide = n_out % 256 == 0 && std::strcmp(force, "256x256") == 0;
-    ch.tile_n = wide ? 256 : 128;
-    // 224-row tiles where they shorten the longest chain of tiles a CU works through (50176
-    // pixels: 224 tiles of 224 rows instead of 196 of 256, both one round)
-    ch.tile_m = 256;
-    if (wide) {
-        const int64_t t224 = (m + 223) / 224 * (n_out / 256);
-        if (((t224 + 255) / 256) * 224 < ((t256 + 255) / 256) * 256) ch.tile_m = 224;
+    // the tile shape whose longest chain of tiles on one CU is shortest: rounds of 256
+    // workgroups x tile area (50176 pixels x 256 channels: 224 tiles of 224x256, one round,
+    // against 196 of 256x256 or two rounds of 256x128); wider tiles win ties (half the LDS
+    // reads per flop)
+    const int shapes[3][2] = {{256, 256}, {224, 256}, {256, 128}};
+    int64_t best = -1;
+    const char* force = std::getenv("DMATH_CONV_TILE");
+    for (auto& sh : shapes) {
+        if (n_out % sh[1]) continue;
+        if (force && !(sh[0] == 256 && sh[1] == (std::strcmp(force, "256x256") == 0 ? 256 : 128))) continue;
+        const int64_t tiles = (m + sh[0] - 1) / sh[0] * (n_out / sh[1]);
+        const int64_t cost = (tiles + 255) / 256 * sh[0] * sh[1];
+        if (best < 0 || cost < best) {
+            best = cost;
+            ch.tile_m = sh[0];
+            ch.tile_n = sh[1];
+        }
     }
     return ch;
 }
