@@ -604,8 +604,8 @@ dmath_status_t dmath_conv_tune(dmath_ctx_t ctx, int32_t mode, const dmath_conv_d
             best = us * handicap;
             best_choice = c;
             result->kernel = c.kernel;
-            result->tile_m = c.kernel == 1 ? (c.tile_m ? c.tile_m : 256) : 64;
-            result->tile_n = c.kernel == 1 ? (mode == CONV_BWD_FILTER ? 128 : c.tile_n) : 64;
+            result->tile_m = c.kernel == 1 ? c.tile_m : 64;
+            result->tile_n = c.kernel == 1 ? c.tile_n : 64;
             result->split_k = c.split_k;
             result->workspace_bytes = need;
             result->chosen_us = us;

@@ -40,11 +40,12 @@ typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 // ------------------------------------------------------------------------------------------
 
 // src rows: image n -> [ch][hw] halfs (NCHW inside a row).  dst: [n][HP][WP][ch] with the image
-// placed at (ph, pw).  One workgroup of 1024 threads moves 64 channels of one image through
-// LDS: fully coalesced 16-byte reads of the 64 planes, 128-byte writes per pixel.  The plane
-// stride (hw + pad, pad chosen so that the stride is 4 mod 16 halfs) keeps the transposed
-// 16-bit reads at two lanes per bank.
+// placed at (ph, pw).  One workgroup of 1024 threads moves 64 channels of one image (of up to
+// kTclPixels pixels of it: blockIdx.y) through LDS: fully coalesced 16-byte reads of the 64
+// planes, 128-byte writes per pixel.  The plane stride (pixels + pad, pad chosen so that the
+// stride is 4 mod 16 halfs) keeps the transposed 16-bit reads at two lanes per bank.
 constexpr int kTclThreads = 1024;
+constexpr int kTclPixels = 1024;  // 64 planes x 1024 pixels x 2 bytes = 128 KiB of LDS
 __host__ __device__ inline int tcl_stride(int hw) { return hw + ((20 - hw % 16) % 16); }
 
 // VEC: halfs per global read, 8 where a plane is a multiple of 16 bytes, else 4.
@@ -56,11 +57,13 @@ __global__ __launch_bounds__(kTclThreads) void to_channels_last_kernel(const voi
     extern __shared__ __attribute__((aligned(16))) char smem[];
     _Float16* planes = reinterpret_cast<_Float16*>(smem);  // [64][stride]
     typedef uint32_t v2u __attribute__((ext_vector_type(2)));
-    const int hw = h * w, stride = tcl_stride(hw);
+    const int hw = h * w;
+    const int p0 = blockIdx.y * kTclPixels, pixels = min(kTclPixels, hw - p0);  // this workgroup's pixels
+    const int stride = tcl_stride(min(kTclPixels, hw));
     const int chunks_c = ch / 64;
     const int n = blockIdx.x / chunks_c, c0 = (blockIdx.x % chunks_c) * 64;
-    const _Float16* src = static_cast<const _Float16*>(src_rows[n]) + (int64_t)c0 * hw;
-    const int vec_per_plane = hw / VEC;
+    const _Float16* src = static_cast<const _Float16*>(src_rows[n]) + (int64_t)c0 * hw + p0;
+    const int vec_per_plane = pixels / VEC;
     for (int e = threadIdx.x; e < 64 * vec_per_plane; e += kTclThreads) {
         const int c = e / vec_per_plane, v = e - c * vec_per_plane;
         v2u* q = reinterpret_cast<v2u*>(planes + c * stride + v * VEC);  // rows are 8-byte aligned
@@ -74,9 +77,9 @@ __global__ __launch_bounds__(kTclThreads) void to_channels_last_kernel(const voi
     }
     __syncthreads();
     _Float16* out = dst + ((int64_t)n * hp * wp) * ch + c0;
-    for (int e = threadIdx.x; e < hw * 8; e += kTclThreads) {
+    for (int e = threadIdx.x; e < pixels * 8; e += kTclThreads) {
         const int pix = e >> 3, cg = e & 7;  // 8 channels per lane
-        const int y = pix / w, x = pix - y * w;
+        const int y = (p0 + pix) / w, x = (p0 + pix) - y * w;
         v8h v;
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] = planes[(cg * 8 + i) * stride + pix];
@@ -88,11 +91,12 @@ __global__ __launch_bounds__(kTclThreads) void to_channels_last_kernel(const voi
 static void to_channels_last(const void* const* src_rows, int n, int ch, int h, int w, int ph, int pw, int hp, int wp,
                              _Float16* dst, hipStream_t st)
 {
-    const int lds = 64 * tcl_stride(h * w) * 2;
-    if ((h * w) % 8 == 0)
-        to_channels_last_kernel<8><<<n * (ch / 64), kTclThreads, lds, st>>>(src_rows, ch, h, w, ph, pw, hp, wp, dst);
+    const int hw = h * w, lds = 64 * tcl_stride(std::min(kTclPixels, hw)) * 2;
+    const dim3 grid(n * (ch / 64), (hw + kTclPixels - 1) / kTclPixels);
+    if (hw % 8 == 0)
+        to_channels_last_kernel<8><<<grid, kTclThreads, lds, st>>>(src_rows, ch, h, w, ph, pw, hp, wp, dst);
     else
-        to_channels_last_kernel<4><<<n * (ch / 64), kTclThreads, lds, st>>>(src_rows, ch, h, w, ph, pw, hp, wp, dst);
+        to_channels_last_kernel<4><<<grid, kTclThreads, lds, st>>>(src_rows, ch, h, w, ph, pw, hp, wp, dst);
 }
 
 // F[k][c][r][s] -> Fp[k][(r,s,c)]
@@ -385,24 +389,26 @@ bool conv_f16_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype)
     const int64_t copy_f = (int64_t)g.k * g.c * g.r * g.s * 2;
     if (copy_f >= limit || (mode == CONV_BWD_DATA ? copy_dy : copy_x) >= limit || m * g.k * 2 >= limit) return false;
     if (mode != CONV_BWD_DATA &&
-        (g.c % 64 || (g.h * g.w) % 4 || (int64_t)64 * tcl_stride(g.h * g.w) * 2 > 150 * 1024))
+        (g.c % 64 || (g.h * g.w) % 4))
         return false;
     if (sp_out < 64) return false;
-    if (mode == CONV_FWD) return g.k % 128 == 0 && sp_out % 4 == 0;
+    if (mode == CONV_FWD) return g.k % 64 == 0 && sp_out % 4 == 0;
     if (mode == CONV_BWD_FILTER)
-        return (g.k % 256 == 0 || g.k == 128) && g.c % 128 == 0 && m % 64 == 0 && sp_out % 4 == 0 &&
-               (int64_t)64 * tcl_stride((int)sp_out) * 2 <= 150 * 1024;
+        return (g.k % 256 == 0 || g.k == 128 || g.k == 64) && g.c % 64 == 0 && m % 64 == 0 && sp_out % 4 == 0;
     // data gradient = forward convolution of dY (k channels) with the rotated filter and
     // padding r-1-pad: needs that padding to be non-negative
-    return g.pad_h <= g.r - 1 && g.pad_w <= g.s - 1 && g.k % 64 == 0 && g.c % 128 == 0 &&
-           (g.h * g.w) % 4 == 0 && g.h * g.w >= 64 && sp_out % 4 == 0 &&
-           (int64_t)64 * tcl_stride((int)sp_out) * 2 <= 150 * 1024;
+    return g.pad_h <= g.r - 1 && g.pad_w <= g.s - 1 && g.k % 64 == 0 && g.c % 64 == 0 &&
+           (g.h * g.w) % 4 == 0 && g.h * g.w >= 64 && sp_out % 4 == 0;
 }
 
-// C tiles of the weight gradient: 256 (or, for 128 filters, 128) filters x 128 columns of (r,s,c).
+// C tiles of the weight gradient: 256 filters (all of them where there are 128 or 64) x 128
+// columns of (r,s,c) (64 where the channel count is not a multiple of 128: a tile's columns are
+// consecutive channels of one tap).
+static int wgrad_tile_m(const ConvGeom& g) { return g.k < 256 ? g.k : 256; }
+static int wgrad_tile_n(const ConvGeom& g) { return g.c % 128 == 0 ? 128 : 64; }
 static int64_t wgrad_tiles(const ConvGeom& g)
 {
-    return (int64_t)(g.k == 128 ? 1 : g.k / 256) * ((int64_t)g.c * g.r * g.s / 128);
+    return (int64_t)(g.k / wgrad_tile_m(g)) * ((int64_t)g.c * g.r * g.s / wgrad_tile_n(g));
 }
 
 // Split count for the weight gradient: a divisor s of the k-tiles with at most one round of
@@ -445,6 +451,8 @@ ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int3
     }
     ch.kernel = 1;
     if (mode == CONV_BWD_FILTER) {
+        ch.tile_m = wgrad_tile_m(g);
+        ch.tile_n = wgrad_tile_n(g);
         ch.split_k = conv_f16_wgrad_split(g);
         return ch;
     }
@@ -454,12 +462,10 @@ ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int3
     // workgroups x tile area (50176 pixels x 256 channels: 224 tiles of 224x256, one round,
     // against 196 of 256x256 or two rounds of 256x128); wider tiles win ties (half the LDS
     // reads per flop)
-    const int shapes[3][2] = {{256, 256}, {224, 256}, {256, 128}};
+    const int shapes[4][2] = {{256, 256}, {224, 256}, {256, 128}, {256, 64}};
     int64_t best = -1;
-    const char* force = std::getenv("DMATH_CONV_TILE");
     for (auto& sh : shapes) {
         if (n_out % sh[1]) continue;
-        if (force && !(sh[0] == 256 && sh[1] == (std::strcmp(force, "256x256") == 0 ? 256 : 128))) continue;
         const int64_t tiles = (m + sh[0] - 1) / sh[0] * (n_out / sh[1]);
         const int64_t cost = (tiles + 255) / 256 * sh[0] * sh[1];
         if (best < 0 || cost < best) {
@@ -489,6 +495,8 @@ std::vector<ConvChoice> conv_candidates(int mode, const ConvGeom& g, dmath_dtype
     c.kernel = 1;
     if (mode == CONV_BWD_FILTER) {
         const int64_t ktiles = (int64_t)g.n * g.oh * g.ow / 64, tiles = wgrad_tiles(g);
+        c.tile_m = wgrad_tile_m(g);
+        c.tile_n = wgrad_tile_n(g);
         for (int s = 1; s <= 64; ++s)
             if (ktiles % s == 0 && tiles * s <= 512 && ktiles / s >= 8) {
                 c.split_k = s;
@@ -501,8 +509,11 @@ std::vector<ConvChoice> conv_candidates(int mode, const ConvGeom& g, dmath_dtype
         return out;
     }
     const int n_out = mode == CONV_FWD ? g.k : g.c;
-    c.tile_n = 128;
     c.tile_m = 256;
+    c.tile_n = 64;
+    out.push_back(c);
+    if (n_out % 128) return out;
+    c.tile_n = 128;
     out.push_back(c);
     if (n_out % 256 == 0) {
         c.tile_n = 256;
@@ -531,7 +542,8 @@ static void launch_fwd(const FastConv& p, int tile_m, int tile_n, dmath_dtype_t 
 {
     if (tile_n == 256 && tile_m == 224) launch_fwd_shape<224, 256, 2>(p, out, alpha, beta, st);
     else if (tile_n == 256) launch_fwd_shape<256, 256, 2>(p, out, alpha, beta, st);
-    else launch_fwd_shape<256, 128, 3>(p, out, alpha, beta, st);
+    else if (tile_n == 128) launch_fwd_shape<256, 128, 3>(p, out, alpha, beta, st);
+    else launch_fwd_shape<256, 64, 3>(p, out, alpha, beta, st);
 }
 
 hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double beta, unsigned rewrite,
@@ -556,7 +568,7 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
     if (!xp || (mode != CONV_BWD_FILTER && !fp) || (mode == CONV_BWD_FILTER && (!yt || !p.ws)))
         return hipErrorInvalidValue;  // the plan was not made for this path
     const int n_out = mode == CONV_BWD_DATA ? g.c : g.k;
-    if (mode != CONV_BWD_FILTER && !(plan.tile_n == 128 || (plan.tile_n == 256 && n_out % 256 == 0)))
+    if (mode != CONV_BWD_FILTER && !((plan.tile_n == 64 || plan.tile_n == 128 || plan.tile_n == 256) && n_out % plan.tile_n == 0))
         return hipErrorInvalidValue;
 
     static bool configured = false;
@@ -569,8 +581,14 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
         if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 256, 2, _Float16>, 2 * 512 * 128);
         if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<224, 256, 2, float>, 2 * 480 * 128);
         if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<224, 256, 2, _Float16>, 2 * 480 * 128);
+        if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 64, 3, float>, 3 * 320 * 128);
+        if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 64, 3, _Float16>, 3 * 320 * 128);
         if (e == hipSuccess) e = set_lds(conv_wgrad_f16_kernel<256, 128>, 3 * 384 * 128);
         if (e == hipSuccess) e = set_lds(conv_wgrad_f16_kernel<128, 128>, 3 * 256 * 128);
+        if (e == hipSuccess) e = set_lds(conv_wgrad_f16_kernel<64, 128>, 3 * 192 * 128);
+        if (e == hipSuccess) e = set_lds(conv_wgrad_f16_kernel<256, 64>, 3 * 320 * 128);
+        if (e == hipSuccess) e = set_lds(conv_wgrad_f16_kernel<128, 64>, 3 * 192 * 128);
+        if (e == hipSuccess) e = set_lds(conv_wgrad_f16_kernel<64, 64>, 3 * 128 * 128);
         if (e != hipSuccess) return e;
         configured = true;
     }
@@ -602,10 +620,13 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
     if (rewrite & REWRITE_Y) to_channels_last(t.y_rows, g.n, g.k, g.oh, g.ow, 0, 0, g.oh, g.ow, yt, st);
     p.ktiles_per_split = (int)((int64_t)g.n * g.oh * g.ow / 64 / t.split_k);
     const int tiles = (int)wgrad_tiles(g) * t.split_k;
-    if (g.k == 128)
-        conv_wgrad_f16_kernel<128, 128><<<tiles, NT, 3 * 256 * 128, st>>>(p);
-    else
-        conv_wgrad_f16_kernel<256, 128><<<tiles, NT, 3 * 384 * 128, st>>>(p);
+    const int bm = wgrad_tile_m(g), bn = wgrad_tile_n(g);
+    if (bm == 256 && bn == 128) conv_wgrad_f16_kernel<256, 128><<<tiles, NT, 3 * 384 * 128, st>>>(p);
+    else if (bm == 128 && bn == 128) conv_wgrad_f16_kernel<128, 128><<<tiles, NT, 3 * 256 * 128, st>>>(p);
+    else if (bm == 64 && bn == 128) conv_wgrad_f16_kernel<64, 128><<<tiles, NT, 3 * 192 * 128, st>>>(p);
+    else if (bm == 256) conv_wgrad_f16_kernel<256, 64><<<tiles, NT, 3 * 320 * 128, st>>>(p);
+    else if (bm == 128) conv_wgrad_f16_kernel<128, 64><<<tiles, NT, 3 * 192 * 128, st>>>(p);
+    else conv_wgrad_f16_kernel<64, 64><<<tiles, NT, 3 * 128 * 128, st>>>(p);
     if (plan.out_dtype == DMATH_F16)
         conv_wgrad_reduce_kernel<_Float16><<<1024, 256, 0, st>>>(p, (float)alpha, (float)beta);
     else

@@ -15,7 +15,8 @@
 //   k unit-stride operand  : [mn][64 k], 128-byte rows, 16-byte chunk index XOR ((mn^(mn>>3))&7);
 //                            the MFMA fragment of a lane (8 consecutive k of one row) is one
 //                            ds_read_b128, conflict-free
-//   m/n unit-stride operand: [k][mn], 16-byte chunk index XOR ((k&3)<<2); fragments come from
+//   m/n unit-stride operand: [k][mn], 16-byte chunk index XOR ((k&3)<<2) (64-column tiles:
+//                            XOR (((k>>1)&1)<<2)); fragments come from
 //                            two ds_read_b64_tr_b16 (the gfx950 transposing LDS read: inside a
 //                            16-lane group, lane i receives element i%4 of the 8 bytes fetched
 //                            by lanes i/4, i/4+4, i/4+8, i/4+12), so a group fetches a 4(k) x
@@ -74,6 +75,15 @@ template <int BMN, bool KC> struct OperandTile {
     static constexpr int kChunksPerRow = KC ? 8 : BMN / 8;
     static constexpr int kRowsPerSeg = 64 / kChunksPerRow;
 
+    // Chunk XOR of an m/n unit-stride tile for k row `row`: rows of 256 bytes or more all start
+    // on the same bank, so the four rows a transposing read touches are spread by two chunk bits;
+    // 128-byte rows (64 columns) alternate between two bank halves already and need one bit,
+    // taken from the row pair.  Both are the same for rows 4 and 16 apart.
+    __device__ __forceinline__ static int mswz(int row)
+    {
+        return BMN >= 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
+    }
+
     // Row (k unit-stride: m/n index; otherwise: k index) inside the tile, and 16-byte chunk of
     // that row in memory, which this lane fetches with segment q.
     __device__ __forceinline__ static void lane_slot(int q, int wave, int lane, int& row, int& chunk)
@@ -81,7 +91,7 @@ template <int BMN, bool KC> struct OperandTile {
         const int seg = q * 4 + wave;
         row = seg * kRowsPerSeg + lane / kChunksPerRow;
         const int cpos = lane % kChunksPerRow;
-        chunk = KC ? (cpos ^ swz(row)) : (cpos ^ ((row & 3) << 2));
+        chunk = KC ? (cpos ^ swz(row)) : (cpos ^ mswz(row));
     }
 
     // byte offsets (relative to the panel origin) for a dense panel with leading dimension ld.
@@ -113,7 +123,7 @@ template <int BMN, bool KC> struct OperandTile {
         const int g = lane >> 4, i = lane & 15;
         const int row = 8 * (g >> 1) + (i >> 2);
         const int col = mn_base + 16 * (g & 1) + 4 * (i & 3);
-        return (uint32_t)(row * (BMN * 2) + (((col >> 3) ^ ((row & 3) << 2)) << 4) + (col & 7) * 2);
+        return (uint32_t)(row * (BMN * 2) + (((col >> 3) ^ mswz(row)) << 4) + (col & 7) * 2);
     }
 
     __device__ __forceinline__ static v8h fragment(const lds_char* tile, uint32_t fb, int mn_row,
@@ -210,10 +220,11 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
     //                those loads may still be outstanding;
     //   STAGES == 2: tile kt+2 is fetched during the last step of iteration kt into the stage
     //                of tile kt itself; at the barrier nothing may be outstanding.
-    // The instruction order inside a step is pinned: after every MFMA one fragment read and at
-    // most one load, so neither LDS nor the memory pipeline holds up the matrix instructions.
+    // The instruction order inside a step is pinned: after every MFMA one fragment read (two in
+    // the narrow tiles, which have more fragments than MFMAs per step) and at most one load, so
+    // neither LDS nor the memory pipeline holds up the matrix instructions.
     constexpr int kSteps = BK / 16, kMfma = MT * NTL, kReads = MT + NTL;
-    static_assert(kReads <= kMfma, "one fragment read per MFMA slot");
+    constexpr int kReadsPerSlot = (kReads + kMfma - 1) / kMfma;  // 1 except for the narrow tiles
     constexpr int kDmaSlots = (STAGES == 3 ? (kSteps - 1) : 1) * kMfma;
     constexpr int kDmaPerSlot = (kPerTile + kDmaSlots - 1) / kDmaSlots;
 
@@ -262,11 +273,15 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
                     const int m = i * NTL + j;
                     acc[i][j] = mfma_f16_32x32x16(fa[cur][i], fb[cur][j], acc[i][j]);
                     __builtin_amdgcn_sched_barrier(0);
-                    if (m < kReads) {
-                        if (s + 1 < kSteps)
-                            read_frag(sa, cur ^ 1, m, s + 1);
-                        else if (HAS_NEXT)
-                            read_frag(sa1, cur ^ 1, m, 0);
+#pragma unroll
+                    for (int q = 0; q < kReadsPerSlot; ++q) {
+                        const int r = m * kReadsPerSlot + q;
+                        if (r < kReads) {
+                            if (s + 1 < kSteps)
+                                read_frag(sa, cur ^ 1, r, s + 1);
+                            else if (HAS_NEXT)
+                                read_frag(sa1, cur ^ 1, r, 0);
+                        }
                     }
                     if (HAS_DMA) {
                         const bool window = STAGES == 3 ? (s < kSteps - 1) : (s == kSteps - 1);

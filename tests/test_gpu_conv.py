@@ -143,6 +143,11 @@ FAST_GEOMS = [
     dict(n=16, c=128, h=12, w=12, k=256, r=3, s=3, pad_h=1, pad_w=1),
     dict(n=4, c=128, h=16, w=16, k=512, r=3, s=3, pad_h=1, pad_w=1),      # two row tiles of filters
     dict(n=4, c=256, h=16, w=16, k=128, r=3, s=3, pad_h=1, pad_w=1),      # 128 filters: 128x128 tiles
+    dict(n=4, c=64, h=16, w=16, k=64, r=3, s=3, pad_h=1, pad_w=1),        # 64 channels and filters: narrow tiles
+    dict(n=4, c=192, h=16, w=16, k=128, r=5, s=5, pad_h=2, pad_w=2),      # channels a multiple of 64 only
+    dict(n=8, c=64, h=8, w=8, k=256, r=1, s=1),
+    dict(n=2, c=64, h=40, w=40, k=64, r=3, s=3, pad_h=1, pad_w=1),        # planes of more than 1024 pixels
+    dict(n=16, c=64, h=34, w=34, k=64, r=1, s=1),                         # ... whose size is 4 mod 8
 ]
 
 
