@@ -39,8 +39,9 @@ typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 // layout rewrites
 // ------------------------------------------------------------------------------------------
 
-// src rows: image n -> [ch][hw] halfs (NCHW inside a row).  dst: [n][HP][WP][ch] with the image
-// placed at (ph, pw).  One workgroup of 1024 threads moves 64 channels of one image (of up to
+// src rows: image n -> [ch][hw] halfs (NCHW inside a row).  dst: [n][HP][WP][ch] with pixel
+// (y, x) of the image placed at (ph + y*sy, pw + x*sx); sy = sx = 1 except for the data gradient
+// of a strided convolution, which reads dY spread out with zeros between its pixels.  One workgroup of 1024 threads moves 64 channels of one image (of up to
 // kTclPixels pixels of it: blockIdx.y) through LDS: fully coalesced 16-byte reads of the 64
 // planes, 128-byte writes per pixel.  The plane stride (pixels + pad, pad chosen so that the
 // stride is 4 mod 16 halfs) keeps the transposed 16-bit reads at two lanes per bank.
@@ -51,8 +52,8 @@ __host__ __device__ inline int tcl_stride(int hw) { return hw + ((20 - hw % 16) 
 // VEC: halfs per global read, 8 where a plane is a multiple of 16 bytes, else 4.
 template <int VEC>
 __global__ __launch_bounds__(kTclThreads) void to_channels_last_kernel(const void* const* src_rows, int ch,
-                                                                       int h, int w, int ph, int pw, int hp,
-                                                                       int wp, _Float16* dst)
+                                                                       int h, int w, int ph, int pw, int sy,
+                                                                       int sx, int hp, int wp, _Float16* dst)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     _Float16* planes = reinterpret_cast<_Float16*>(smem);  // [64][stride]
@@ -83,20 +84,20 @@ __global__ __launch_bounds__(kTclThreads) void to_channels_last_kernel(const voi
         v8h v;
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] = planes[(cg * 8 + i) * stride + pix];
-        *reinterpret_cast<v8h*>(out + ((int64_t)(y + ph) * wp + (x + pw)) * ch + cg * 8) = v;
+        *reinterpret_cast<v8h*>(out + ((int64_t)(y * sy + ph) * wp + (x * sx + pw)) * ch + cg * 8) = v;
     }
 }
 
 // NCHW rows -> zero-bordered channels-last copy, on stream st.
-static void to_channels_last(const void* const* src_rows, int n, int ch, int h, int w, int ph, int pw, int hp, int wp,
-                             _Float16* dst, hipStream_t st)
+static void to_channels_last(const void* const* src_rows, int n, int ch, int h, int w, int ph, int pw, int sy, int sx,
+                             int hp, int wp, _Float16* dst, hipStream_t st)
 {
     const int hw = h * w, lds = 64 * tcl_stride(std::min(kTclPixels, hw)) * 2;
     const dim3 grid(n * (ch / 64), (hw + kTclPixels - 1) / kTclPixels);
     if (hw % 8 == 0)
-        to_channels_last_kernel<8><<<grid, kTclThreads, lds, st>>>(src_rows, ch, h, w, ph, pw, hp, wp, dst);
+        to_channels_last_kernel<8><<<grid, kTclThreads, lds, st>>>(src_rows, ch, h, w, ph, pw, sy, sx, hp, wp, dst);
     else
-        to_channels_last_kernel<4><<<grid, kTclThreads, lds, st>>>(src_rows, ch, h, w, ph, pw, hp, wp, dst);
+        to_channels_last_kernel<4><<<grid, kTclThreads, lds, st>>>(src_rows, ch, h, w, ph, pw, sy, sx, hp, wp, dst);
 }
 
 // F[k][c][r][s] -> Fp[k][(r,s,c)]
@@ -146,7 +147,7 @@ __device__ __forceinline__ uint32_t pixel_offset(const FastConv& p, int m)
 {
     const int sp_out = p.g.oh * p.g.ow;
     const int n = m / sp_out, sp = m % sp_out, oy = sp / p.g.ow, ox = sp % p.g.ow;
-    return (uint32_t)((((int64_t)n * p.hp + oy) * p.wp + ox) * p.g.c * 2);
+    return (uint32_t)((((int64_t)n * p.hp + oy * p.g.stride_h) * p.wp + ox * p.g.stride_w) * p.g.c * 2);
 }
 
 template <int BM, int BN> struct FwdWalk {
@@ -259,13 +260,13 @@ template <int BM, int BN> struct WgradWalk {
     uint32_t aoff[TA::kInstr], boff[TB::kInstr];
     // pixel (n, oy, ox) fetched by this lane for each B segment, and the geometry to step it
     int pn[TB::kInstr], py[TB::kInstr], px[TB::kInstr], chunk16[TB::kInstr];
-    int oh, ow, hp, wp, c, d_oy, d_ox;
+    int oh, ow, hp, wp, c, d_oy, d_ox, sh, sw;
     int64_t astep;
 
     __device__ __forceinline__ WgradWalk(const FastConv& p, int k0_pixels, int m0_filters, int n0_cols, int wave,
                                          int lane)
     {
-        oh = p.g.oh; ow = p.g.ow; hp = p.hp; wp = p.wp; c = p.g.c;
+        oh = p.g.oh; ow = p.g.ow; hp = p.hp; wp = p.wp; c = p.g.c; sh = p.g.stride_h; sw = p.g.stride_w;
         d_oy = BK / ow; d_ox = BK % ow;
         // A' = Yt[m][k]: dense, m/n (= k_out) unit-stride, filters m0 .. m0+BM of the tile
         TA::offsets(p.g.k, m0_filters, BM, wave, lane, aoff);
@@ -292,7 +293,7 @@ template <int BM, int BN> struct WgradWalk {
     {
 #pragma unroll
         for (int q = 0; q < TB::kInstr; ++q)
-            boff[q] = (uint32_t)((((int64_t)pn[q] * hp + py[q]) * wp + px[q]) * c * 2) + chunk16[q];
+            boff[q] = (uint32_t)((((int64_t)pn[q] * hp + py[q] * sh) * wp + px[q] * sw) * c * 2) + chunk16[q];
     }
     __device__ __forceinline__ void advance()
     {
@@ -380,12 +381,12 @@ template <class K> hipError_t set_lds(K kern, int bytes)
 // Geometry the specialised kernels accept (everything else runs on the generic kernels).
 bool conv_f16_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype)
 {
-    if (in_dtype != DMATH_F16 || g.stride_h != 1 || g.stride_w != 1) return false;
+    if (in_dtype != DMATH_F16) return false;
     const int64_t sp_out = (int64_t)g.oh * g.ow, m = (int64_t)g.n * sp_out;
     // 32-bit lane offsets into the re-layout copies: each copy has to stay below 4 GiB
-    const int64_t pph = g.r - 1 - g.pad_h, ppw = g.s - 1 - g.pad_w, limit = 1ll << 32;
+    const int64_t limit = 1ll << 32;
     const int64_t copy_x = (int64_t)g.n * (g.h + 2 * g.pad_h) * (g.w + 2 * g.pad_w) * g.c * 2;
-    const int64_t copy_dy = (int64_t)g.n * (g.oh + 2 * pph) * (g.ow + 2 * ppw) * g.k * 2;
+    const int64_t copy_dy = (int64_t)g.n * (g.h + g.r - 1) * (g.w + g.s - 1) * g.k * 2;
     const int64_t copy_f = (int64_t)g.k * g.c * g.r * g.s * 2;
     if (copy_f >= limit || (mode == CONV_BWD_DATA ? copy_dy : copy_x) >= limit || m * g.k * 2 >= limit) return false;
     if (mode != CONV_BWD_DATA &&
@@ -439,9 +440,9 @@ static int32_t generic_wgrad_split(const ConvGeom& g)
     return (int32_t)std::min<int64_t>({want, max_by_k, 64});
 }
 
-// The cost model: the specialised kernels wherever their preconditions hold; forward and data
-// gradient on 256x128 tiles unless those would need a second, mostly empty round of workgroups
-// while 256x256 tiles fit in one.
+// The cost model: the specialised kernels wherever their preconditions hold; the tile shape of
+// the forward pass and the data gradient from a cycle count per round of workgroups, the split
+// of the weight gradient from conv_f16_wgrad_split.
 ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int32_t policy)
 {
     ConvChoice ch;
@@ -458,17 +459,22 @@ ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int3
     }
     const int64_t m = mode == CONV_FWD ? (int64_t)g.n * g.oh * g.ow : (int64_t)g.n * g.h * g.w;
     const int n_out = mode == CONV_FWD ? g.k : g.c;
-    // the tile shape whose longest chain of tiles on one CU is shortest: rounds of 256
-    // workgroups x tile area (50176 pixels x 256 channels: 224 tiles of 224x256, one round,
-    // against 196 of 256x256 or two rounds of 256x128); wider tiles win ties (half the LDS
-    // reads per flop)
+    // the tile shape whose longest chain of tiles on one CU takes the fewest cycles: rounds of 256
+    // workgroups x (k-tiles x the slower of the tile's matrix instructions, 32.5 cycles each over
+    // four SIMDs, and its operand loads at 60 bytes per cycle and CU, + the tile's stores at
+    // 10 bytes per cycle and CU).  50176 pixels x 256 channels: 224 tiles of 224x256 are one
+    // round, against 196 of 256x256 or two rounds of 256x128; 64-wide tiles are load-bound and
+    // win only where they save whole rounds.  A narrower tile has to win by 3 %.
     const int shapes[4][2] = {{256, 256}, {224, 256}, {256, 128}, {256, 64}};
-    int64_t best = -1;
+    const int64_t ktiles = (int64_t)g.r * g.s * (mode == CONV_FWD ? g.c : g.k) / 64;
+    double best = -1;
     for (auto& sh : shapes) {
         if (n_out % sh[1]) continue;
         const int64_t tiles = (m + sh[0] - 1) / sh[0] * (n_out / sh[1]);
-        const int64_t cost = (tiles + 255) / 256 * sh[0] * sh[1];
-        if (best < 0 || cost < best) {
+        const double area = (double)sh[0] * sh[1];
+        const double per_ktile = std::max(area / 1024 * 32.5, (sh[0] + sh[1]) * 128 / 60.0);
+        const double cost = (double)((tiles + 255) / 256) * (ktiles * per_ktile + 0.4 * area);
+        if (best < 0 || cost < 0.97 * best) {
             best = cost;
             ch.tile_m = sh[0];
             ch.tile_n = sh[1];
@@ -593,31 +599,33 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
         configured = true;
     }
     if (mode == CONV_BWD_DATA) {
-        // forward convolution over dY: input channels k, spatial oh x ow, padding r-1-pad,
-        // rotated filter, output channels c, output spatial h x w, output rows = images of dX
+        // forward convolution (stride 1) over dY with its pixels spread out by the stride: input
+        // channels k, padding r-1-pad in front, rotated filter, output channels c, output
+        // spatial h x w (so the copy has h+r-1 x w+s-1 pixels), output rows = images of dX
         FastConv q = p;
         const int pph = g.r - 1 - g.pad_h, ppw = g.s - 1 - g.pad_w;
         q.g.c = g.k; q.g.k = g.c;
         q.g.h = g.oh; q.g.w = g.ow; q.g.oh = g.h; q.g.ow = g.w;
         q.g.pad_h = pph; q.g.pad_w = ppw;
-        q.hp = g.oh + 2 * pph;
-        q.wp = g.ow + 2 * ppw;
+        q.g.stride_h = q.g.stride_w = 1;
+        q.hp = g.h + g.r - 1;
+        q.wp = g.w + g.s - 1;
         q.y_rows = t.x_rows;
-        if (rewrite & REWRITE_X) to_channels_last(t.y_rows, g.n, g.k, g.oh, g.ow, pph, ppw, q.hp, q.wp, xp, st);
+        if (rewrite & REWRITE_X) to_channels_last(t.y_rows, g.n, g.k, g.oh, g.ow, pph, ppw, g.stride_h, g.stride_w, q.hp, q.wp, xp, st);
         if (rewrite & REWRITE_F)
             filter_to_rsk_rotated_kernel<<<512, 256, 0, st>>>(t.f_rows, g.c, g.r, g.s, g.k, fp);
         launch_fwd(q, plan.tile_m, plan.tile_n, plan.out_dtype, (float)alpha, (float)beta, st);
         return hipGetLastError();
     }
     // activations -> zero-bordered channels-last copy (borders were zeroed when the copy was allocated)
-    if (rewrite & REWRITE_X) to_channels_last(t.x_rows, g.n, g.c, g.h, g.w, g.pad_h, g.pad_w, p.hp, p.wp, xp, st);
+    if (rewrite & REWRITE_X) to_channels_last(t.x_rows, g.n, g.c, g.h, g.w, g.pad_h, g.pad_w, 1, 1, p.hp, p.wp, xp, st);
     if (mode == CONV_FWD) {
         if (rewrite & REWRITE_F) filter_to_rsc_kernel<<<512, 256, 0, st>>>(t.f_rows, g.c, g.r * g.s, g.k, fp);
         launch_fwd(p, plan.tile_m, plan.tile_n, plan.out_dtype, (float)alpha, (float)beta, st);
         return hipGetLastError();
     }
     // weight gradient: dY -> channels-last [m][k], split GEMM, fixed-order reduction
-    if (rewrite & REWRITE_Y) to_channels_last(t.y_rows, g.n, g.k, g.oh, g.ow, 0, 0, g.oh, g.ow, yt, st);
+    if (rewrite & REWRITE_Y) to_channels_last(t.y_rows, g.n, g.k, g.oh, g.ow, 0, 0, 1, 1, g.oh, g.ow, yt, st);
     p.ktiles_per_split = (int)((int64_t)g.n * g.oh * g.ow / 64 / t.split_k);
     const int tiles = (int)wgrad_tiles(g) * t.split_k;
     const int bm = wgrad_tile_m(g), bn = wgrad_tile_n(g);

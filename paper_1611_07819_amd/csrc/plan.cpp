@@ -501,9 +501,8 @@ size_t conv_choice_bytes(int mode, const ConvGeom& g, const ConvChoice& c, dmath
     if (mode == CONV_BWD_FILTER && (c.split_k > 1 || c.kernel == 1))
         bytes += (size_t)c.split_k * g.k * crs * (in_dtype == DMATH_F64 ? 8 : 4);
     if (c.kernel == 1) {
-        const size_t pph = g.r - 1 - g.pad_h, ppw = g.s - 1 - g.pad_w;
         if (mode == CONV_BWD_DATA)
-            bytes += (size_t)g.n * (g.oh + 2 * pph) * (g.ow + 2 * ppw) * g.k * 2 + (size_t)g.k * crs * 2;
+            bytes += (size_t)g.n * (g.h + g.r - 1) * (g.w + g.s - 1) * g.k * 2 + (size_t)g.k * crs * 2;
         else
             bytes += (size_t)g.n * (g.h + 2 * g.pad_h) * (g.w + 2 * g.pad_w) * g.c * 2 +
                      (mode == CONV_FWD ? (size_t)g.k * crs * 2 : (size_t)g.n * sp_out * g.k * 2);
@@ -575,9 +574,11 @@ dmath_status_t make_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_
         plan->workspace = ws;
         const int32_t pph = g.r - 1 - g.pad_h, ppw = g.s - 1 - g.pad_w;
         if (mode == CONV_BWD_DATA) {
-            // dY gathered with padding r-1-pad, filter rotated with its channel roles swapped
-            plan->xp = get_relayout(ctx, Y, RELAYOUT_CHANNELS_LAST, {g.k, g.oh, g.ow, pph, ppw},
-                                    (size_t)g.n * (g.oh + 2 * pph) * (g.ow + 2 * ppw) * g.k * 2);
+            // dY gathered with padding r-1-pad and its pixels spread out by the stride (the zeros
+            // between them are those of the allocation), filter rotated with its channel roles swapped
+            plan->xp = get_relayout(ctx, Y, RELAYOUT_CHANNELS_LAST,
+                                    {g.k, g.oh, g.ow, pph, ppw, g.stride_h, g.stride_w, g.h + g.r - 1, g.w + g.s - 1},
+                                    (size_t)g.n * (g.h + g.r - 1) * (g.w + g.s - 1) * g.k * 2);
             plan->fp = get_relayout(ctx, F, RELAYOUT_FILTER_ROTATED, {g.c, g.r, g.s, g.k}, (size_t)g.k * crs * 2);
         } else {
             plan->xp = get_relayout(ctx, X, RELAYOUT_CHANNELS_LAST, {g.c, g.h, g.w, g.pad_h, g.pad_w},

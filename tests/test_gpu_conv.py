@@ -135,8 +135,8 @@ def _config5(ctx, oracle, w, images, filters):
 
 
 FAST_GEOMS = [
-    # geometries that satisfy the preconditions of the specialised fp16 kernels (stride 1,
-    # channels a multiple of 64/128, n*oh*ow a multiple of 256)
+    # geometries that satisfy the preconditions of the specialised fp16 kernels (channels and
+    # filters multiples of 64, n*oh*ow a multiple of 64, planes a multiple of 4 pixels)
     dict(n=4, c=128, h=16, w=16, k=256, r=3, s=3, pad_h=1, pad_w=1),
     dict(n=8, c=128, h=16, w=8, k=256, r=1, s=1),
     dict(n=2, c=256, h=16, w=16, k=256, r=5, s=3, pad_h=2, pad_w=1),
@@ -148,6 +148,11 @@ FAST_GEOMS = [
     dict(n=8, c=64, h=8, w=8, k=256, r=1, s=1),
     dict(n=2, c=64, h=40, w=40, k=64, r=3, s=3, pad_h=1, pad_w=1),        # planes of more than 1024 pixels
     dict(n=16, c=64, h=34, w=34, k=64, r=1, s=1),                         # ... whose size is 4 mod 8
+    # strides: rows and columns left over at the end (22+2-3 and 16+2-3 are odd), 1x1 filter, mixed
+    dict(n=8, c=64, h=22, w=16, k=64, r=3, s=3, pad_h=1, pad_w=1, stride_h=2, stride_w=2),
+    dict(n=4, c=128, h=16, w=16, k=256, r=1, s=1, stride_h=2, stride_w=2),
+    dict(n=4, c=64, h=16, w=32, k=128, r=3, s=5, pad_h=1, pad_w=2, stride_h=1, stride_w=2),
+    dict(n=4, c=64, h=24, w=24, k=64, r=5, s=5, pad_h=2, pad_w=2, stride_h=3, stride_w=3),
 ]
 
 
