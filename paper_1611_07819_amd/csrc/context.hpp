@@ -173,6 +173,15 @@ hipError_t launch_conv(const ConvPlan& p, int mode, double alpha, double beta, u
 hipError_t launch_reblock(dmath_dtype_t sd, dmath_dtype_t dd, const CopyCell* cells, int n_cells,
                           int max_rows, bool vectors, hipStream_t st);
 int reblock_vector_width(dmath_dtype_t sd, dmath_dtype_t dd);
+// Extents and sizes of the copies the specialised fp16 convolution kernels read: channel and
+// filter counts rounded up to multiples of 64, images in the channels-last copy of X (one more,
+// all zeros, where n*oh*ow is not a multiple of 64), bytes of the activation copy (x), the
+// permuted filter (f; 0 for the weight gradient) and the channels-last dY (y; weight gradient only).
+struct ConvF16Layout {
+    int32_t cp, kp;
+    int64_t x_images, x_bytes, f_bytes, y_bytes;
+};
+ConvF16Layout conv_f16_layout(int mode, const ConvGeom& g);
 bool conv_f16_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype);
 int conv_f16_wgrad_split(const ConvGeom& g);
 hipError_t launch_conv_f16(const ConvPlan& p, int mode, double alpha, double beta, unsigned rewrite,

@@ -1,4 +1,4 @@
-// Specialised fp16 convolution kernels for gfx950 (stride 1): forward, weight gradient and data
+// Specialised fp16 convolution kernels for gfx950: forward, weight gradient and data
 // gradient as implicit GEMMs on the MFMA pipeline of f16_pipeline.hpp (paper abstract: convolutions;
 // section 1: data reorganisation to support a series of operations).
 //
@@ -16,6 +16,10 @@
 //   data gradient  : the forward kernel again, over the zero-bordered channels-last copy of dY
 //                    (padding r-1-pad) with the filter rotated by 180 degrees and its channel
 //                    roles swapped, Gp[c][(r',s',k)].
+// Channel and filter counts that are not multiples of 64 are rounded up in the copies (the pad
+// channels stay zero, as the allocation left them; stores skip the pad filters), and a pixel count
+// n*oh*ow that is not a multiple of 64 reads zeros past its end (an extra, never-written image in
+// Xp, extra rows in Yt).
 // A rewrite is skipped when the caller says the copy is still current (the context keeps the
 // copies and the version of the matrix each was made from); otherwise it is part of the call.
 #include <hip/hip_runtime.h>
@@ -44,16 +48,18 @@ typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 // of a strided convolution, which reads dY spread out with zeros between its pixels.  One workgroup of 1024 threads moves 64 channels of one image (of up to
 // kTclPixels pixels of it: blockIdx.y) through LDS: fully coalesced 16-byte reads of the 64
 // planes, 128-byte writes per pixel.  The plane stride (pixels + pad, pad chosen so that the
-// stride is 4 mod 16 halfs) keeps the transposed 16-bit reads at two lanes per bank.
+// stride is 4 mod 16 halfs) keeps the transposed 16-bit reads at two lanes per bank.  dst has
+// chd >= ch channels per pixel (a multiple of 64); channels ch .. chd-1 are written as zeros.
 constexpr int kTclThreads = 1024;
 constexpr int kTclPixels = 1024;  // 64 planes x 1024 pixels x 2 bytes = 128 KiB of LDS
 __host__ __device__ inline int tcl_stride(int hw) { return hw + ((20 - hw % 16) % 16); }
 
-// VEC: halfs per global read, 8 where a plane is a multiple of 16 bytes, else 4.
+// VEC: halfs per global read: 8 where a plane is a multiple of 16 bytes, 4 where of 8, else 1.
 template <int VEC>
 __global__ __launch_bounds__(kTclThreads) void to_channels_last_kernel(const void* const* src_rows, int ch,
-                                                                       int h, int w, int ph, int pw, int sy,
-                                                                       int sx, int hp, int wp, _Float16* dst)
+                                                                       int chd, int h, int w, int ph, int pw,
+                                                                       int sy, int sx, int hp, int wp,
+                                                                       _Float16* dst)
 {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     _Float16* planes = reinterpret_cast<_Float16*>(smem);  // [64][stride]
@@ -61,69 +67,81 @@ __global__ __launch_bounds__(kTclThreads) void to_channels_last_kernel(const voi
     const int hw = h * w;
     const int p0 = blockIdx.y * kTclPixels, pixels = min(kTclPixels, hw - p0);  // this workgroup's pixels
     const int stride = tcl_stride(min(kTclPixels, hw));
-    const int chunks_c = ch / 64;
+    const int chunks_c = chd / 64;
     const int n = blockIdx.x / chunks_c, c0 = (blockIdx.x % chunks_c) * 64;
+    const int planes_here = min(64, ch - c0);  // the last group of a padded channel count is short
     const _Float16* src = static_cast<const _Float16*>(src_rows[n]) + (int64_t)c0 * hw + p0;
     const int vec_per_plane = pixels / VEC;
     for (int e = threadIdx.x; e < 64 * vec_per_plane; e += kTclThreads) {
         const int c = e / vec_per_plane, v = e - c * vec_per_plane;
+        const bool real = c < planes_here;
+        if (VEC == 1) {
+            planes[c * stride + v] = real ? src[(int64_t)c * hw + v] : (_Float16)0.f;
+            continue;
+        }
         v2u* q = reinterpret_cast<v2u*>(planes + c * stride + v * VEC);  // rows are 8-byte aligned
         if (VEC == 8) {
-            const v4u d = *reinterpret_cast<const v4u*>(src + (int64_t)c * hw + v * 8);
+            v4u d = {0u, 0u, 0u, 0u};
+            if (real) d = *reinterpret_cast<const v4u*>(src + (int64_t)c * hw + v * 8);
             q[0] = v2u{d[0], d[1]};
             q[1] = v2u{d[2], d[3]};
         } else {
-            q[0] = *reinterpret_cast<const v2u*>(src + (int64_t)c * hw + v * 4);
+            v2u d = {0u, 0u};
+            if (real) d = *reinterpret_cast<const v2u*>(src + (int64_t)c * hw + v * 4);
+            q[0] = d;
         }
     }
     __syncthreads();
-    _Float16* out = dst + ((int64_t)n * hp * wp) * ch + c0;
+    _Float16* out = dst + ((int64_t)n * hp * wp) * chd + c0;
     for (int e = threadIdx.x; e < pixels * 8; e += kTclThreads) {
         const int pix = e >> 3, cg = e & 7;  // 8 channels per lane
         const int y = (p0 + pix) / w, x = (p0 + pix) - y * w;
         v8h v;
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] = planes[(cg * 8 + i) * stride + pix];
-        *reinterpret_cast<v8h*>(out + ((int64_t)(y * sy + ph) * wp + (x * sx + pw)) * ch + cg * 8) = v;
+        *reinterpret_cast<v8h*>(out + ((int64_t)(y * sy + ph) * wp + (x * sx + pw)) * chd + cg * 8) = v;
     }
 }
 
 // NCHW rows -> zero-bordered channels-last copy, on stream st.
-static void to_channels_last(const void* const* src_rows, int n, int ch, int h, int w, int ph, int pw, int sy, int sx,
-                             int hp, int wp, _Float16* dst, hipStream_t st)
+static void to_channels_last(const void* const* src_rows, int n, int ch, int chd, int h, int w, int ph, int pw,
+                             int sy, int sx, int hp, int wp, _Float16* dst, hipStream_t st)
 {
     const int hw = h * w, lds = 64 * tcl_stride(std::min(kTclPixels, hw)) * 2;
-    const dim3 grid(n * (ch / 64), (hw + kTclPixels - 1) / kTclPixels);
+    const dim3 grid(n * (chd / 64), (hw + kTclPixels - 1) / kTclPixels);
     if (hw % 8 == 0)
-        to_channels_last_kernel<8><<<grid, kTclThreads, lds, st>>>(src_rows, ch, h, w, ph, pw, sy, sx, hp, wp, dst);
+        to_channels_last_kernel<8><<<grid, kTclThreads, lds, st>>>(src_rows, ch, chd, h, w, ph, pw, sy, sx, hp, wp, dst);
+    else if (hw % 4 == 0)
+        to_channels_last_kernel<4><<<grid, kTclThreads, lds, st>>>(src_rows, ch, chd, h, w, ph, pw, sy, sx, hp, wp, dst);
     else
-        to_channels_last_kernel<4><<<grid, kTclThreads, lds, st>>>(src_rows, ch, h, w, ph, pw, sy, sx, hp, wp, dst);
+        to_channels_last_kernel<1><<<grid, kTclThreads, lds, st>>>(src_rows, ch, chd, h, w, ph, pw, sy, sx, hp, wp, dst);
 }
 
-// F[k][c][r][s] -> Fp[k][(r,s,c)]
-__global__ __launch_bounds__(256) void filter_to_rsc_kernel(const void* const* f_rows, int c, int rs,
+// F[k][c][r][s] -> Fp[k][(r,s,cp)], cp >= c channels per tap (the pad channels written as zeros)
+__global__ __launch_bounds__(256) void filter_to_rsc_kernel(const void* const* f_rows, int c, int cp, int rs,
                                                             int k, _Float16* fp)
 {
-    const int64_t total = (int64_t)k * c * rs;
+    const int64_t total = (int64_t)k * cp * rs;
     for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-        const int kk = (int)(e / (c * rs)), rem = (int)(e % (c * rs));
-        const int q = rem / c, cc = rem % c;  // destination order (rs, c)
-        fp[e] = static_cast<const _Float16*>(f_rows[kk])[cc * rs + q];
+        const int kk = (int)(e / (cp * rs)), rem = (int)(e % (cp * rs));
+        const int q = rem / cp, cc = rem % cp;  // destination order (rs, cp)
+        fp[e] = cc < c ? static_cast<const _Float16*>(f_rows[kk])[cc * rs + q] : (_Float16)0.f;
     }
 }
 
-// F[k][c][r][s] -> Gp[c][(r',s',k)] with r' = R-1-r, s' = S-1-s: the filter of the forward
-// convolution (over dY, channels k) that computes the data gradient.
+// F[k][c][r][s] -> Gp[c][(r',s',kp)] with r' = R-1-r, s' = S-1-s: the filter of the forward
+// convolution (over dY, channels k) that computes the data gradient; kp >= k filters per tap
+// (the pad filters written as zeros).
 __global__ __launch_bounds__(256) void filter_to_rsk_rotated_kernel(const void* const* f_rows, int c, int r,
-                                                                    int s, int k, _Float16* gp)
+                                                                    int s, int k, int kp, _Float16* gp)
 {
     const int rs = r * s;
-    const int64_t total = (int64_t)c * rs * k;
+    const int64_t total = (int64_t)c * rs * kp;
     for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-        const int cc = (int)(e / (rs * k)), rem = (int)(e % (rs * k));
-        const int q = rem / k, kk = rem % k;  // destination order (r', s', k)
+        const int cc = (int)(e / (rs * kp)), rem = (int)(e % (rs * kp));
+        const int q = rem / kp, kk = rem % kp;  // destination order (r', s', kp)
         const int rr = r - 1 - q / s, ss = s - 1 - q % s;
-        gp[e] = static_cast<const _Float16*>(f_rows[kk])[cc * rs + rr * s + ss];
+        gp[e] = kk < k ? static_cast<const _Float16*>(f_rows[kk])[cc * rs + rr * s + ss] : (_Float16)0.f;
     }
 }
 
@@ -131,7 +149,8 @@ __global__ __launch_bounds__(256) void filter_to_rsk_rotated_kernel(const void* 
 // forward
 // ------------------------------------------------------------------------------------------
 struct FastConv {
-    ConvGeom g;
+    ConvGeom g;  // c and k rounded up to multiples of 64: the extents of the copies
+    int c_real, k_real;  // what the tensors hold (forward, data gradient: k_real = output channels stored)
     int hp, wp;
     const void* const* y_rows;  // forward: output rows (images)
     const void* const* f_rows;  // weight gradient: output rows (filters)
@@ -139,7 +158,7 @@ struct FastConv {
     const _Float16* fp;
     const _Float16* yt;
     float* ws;
-    int split, ktiles_per_split;
+    int split, ktiles, ktiles_per_split;  // weight gradient: parts, 64-pixel tiles in all and per part
 };
 
 // byte offset of pixel m = (n, oh, ow) in Xp (tap (0,0), channel 0)
@@ -223,18 +242,41 @@ __global__ __launch_bounds__(NT) void conv_fwd_f16_kernel(FastConv p, float alph
     run<BM, BN, STAGES, true, true>(walk, n_ktiles, smem, acc);
 
     // epilogue: four consecutive registers are four consecutive pixels of one output plane
-    const int sp_out = p.g.oh * p.g.ow, m_end = p.g.n * sp_out;  // a multiple of 4, as sp_out is
+    const int sp_out = p.g.oh * p.g.ow, m_end = p.g.n * sp_out;
+    if (sp_out % 4 != 0) {
+        // planes that 4-pixel groups straddle: one element at a time
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                if (m >= m_end) continue;
+                const int n_img = m / sp_out, sp = m % sp_out;
+                TC* yrow = static_cast<TC*>(const_cast<void*>(p.y_rows[n_img]));
+#pragma unroll
+                for (int j = 0; j < NTL; ++j) {
+                    const int ko = n0 + wn * WN + j * 32 + l32;
+                    if (ko >= p.k_real) continue;
+                    TC* dst = yrow + (int64_t)ko * sp_out + sp;
+                    float v = alpha * acc[i][j][r];
+                    if (beta != 0.f) v += beta * (float)*dst;
+                    *dst = to_out<TC>(v);
+                }
+            }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
             const int m = m0 + wm * WM + i * 32 + 8 * q4 + 4 * h;
-            if (m >= m_end) continue;  // ragged last tile
+            if (m >= m_end) continue;  // ragged last tile (m_end is a multiple of 4, as sp_out is)
             const int n_img = m / sp_out, sp = m % sp_out;
             TC* yrow = static_cast<TC*>(const_cast<void*>(p.y_rows[n_img]));
 #pragma unroll
             for (int j = 0; j < NTL; ++j) {
                 const int ko = n0 + wn * WN + j * 32 + l32;
+                if (ko >= p.k_real) continue;  // pad filters
                 TC* dst = yrow + (int64_t)ko * sp_out + sp;
                 typedef TC out4 __attribute__((ext_vector_type(4)));
                 out4 o;
@@ -303,8 +345,7 @@ template <int BM, int BN> struct WgradWalk {
             px[q] += d_ox;
             py[q] += d_oy;
             if (px[q] >= ow) { px[q] -= ow; ++py[q]; }
-            if (py[q] >= oh) { py[q] -= oh; ++pn[q]; }
-            if (py[q] >= oh) { py[q] -= oh; ++pn[q]; }
+            while (py[q] >= oh) { py[q] -= oh; ++pn[q]; }  // planes of fewer than 64 pixels: several images
         }
         set_boff();
     }
@@ -332,8 +373,10 @@ __global__ __launch_bounds__(NT) void conv_wgrad_f16_kernel(FastConv p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    WgradWalk<BM, BN> walk(p, split * p.ktiles_per_split * BK, m0, n0, wave, lane);
-    run<BM, BN, 3, false, false>(walk, p.ktiles_per_split, smem, acc);
+    // the last part may be shorter; pixels past n*oh*ow (last k-tile) read zeros on both sides
+    const int kt0 = split * p.ktiles_per_split;
+    WgradWalk<BM, BN> walk(p, kt0 * BK, m0, n0, wave, lane);
+    run<BM, BN, 3, false, false>(walk, min(p.ktiles_per_split, p.ktiles - kt0), smem, acc);
 
     float* ws = p.ws + (int64_t)split * p.g.k * ncols;
 #pragma unroll
@@ -357,12 +400,14 @@ __global__ __launch_bounds__(256) void conv_wgrad_reduce_kernel(FastConv p, floa
     const int64_t total = (int64_t)p.g.k * ncols, quads = total / 4;
     for (int64_t e4 = (int64_t)blockIdx.x * 256 + threadIdx.x; e4 < quads; e4 += (int64_t)gridDim.x * 256) {
         const int64_t e = e4 * 4;
+        const int kk = (int)(e / ncols), col = (int)(e % ncols), q = col / c, cc = col % c;
+        if (kk >= p.k_real || cc >= p.c_real) continue;  // pad filters, pad channels
         v4f sum = {0.f, 0.f, 0.f, 0.f};
         for (int s = 0; s < p.split; ++s) sum += *reinterpret_cast<const v4f*>(p.ws + (int64_t)s * total + e);
-        const int kk = (int)(e / ncols), col = (int)(e % ncols), q = col / c, cc = col % c;
         TC* dst = static_cast<TC*>(const_cast<void*>(p.f_rows[kk])) + cc * rs + q;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
+            if (cc + i >= p.c_real) break;
             float v = alpha * sum[i];
             if (beta != 0.f) v += beta * (float)dst[i * rs];
             dst[i * rs] = to_out<TC>(v);
@@ -378,55 +423,84 @@ template <class K> hipError_t set_lds(K kern, int bytes)
 
 }  // namespace
 
-// Geometry the specialised kernels accept (everything else runs on the generic kernels).
+static int round64(int v) { return (v + 63) / 64 * 64; }
+
+// Sizes of the copies that the specialised kernels read.
+ConvF16Layout conv_f16_layout(int mode, const ConvGeom& g)
+{
+    ConvF16Layout l{};
+    l.cp = round64(g.c);
+    l.kp = round64(g.k);
+    const int64_t m = (int64_t)g.n * g.oh * g.ow, crs_p = (int64_t)g.r * g.s * l.cp;
+    // one more (all-zero) image where the weight gradient's last 64-pixel tile is not full
+    l.x_images = g.n + (m % 64 ? 1 : 0);
+    if (mode == CONV_BWD_DATA) {
+        l.x_bytes = (int64_t)g.n * (g.h + g.r - 1) * (g.w + g.s - 1) * l.kp * 2;
+        l.f_bytes = (int64_t)l.cp * g.r * g.s * l.kp * 2;
+    } else {
+        l.x_bytes = (int64_t)l.x_images * (g.h + 2 * g.pad_h) * (g.w + 2 * g.pad_w) * l.cp * 2;
+        l.f_bytes = mode == CONV_FWD ? (int64_t)l.kp * crs_p * 2 : 0;
+        l.y_bytes = mode == CONV_BWD_FILTER ? (m + 63) / 64 * 64 * l.kp * 2 : 0;
+    }
+    return l;
+}
+
+// Geometry the specialised kernels accept (everything else runs on the generic kernels): fp16,
+// every copy below 4 GiB (32-bit lane offsets), at most four times the work from rounding the
+// channel and filter counts up to multiples of 64 (the matrix pipeline is more than ten times
+// faster than the generic kernel), and for the data gradient (a forward
+// convolution of dY with padding r-1-pad) a padding that does not exceed the filter.
 bool conv_f16_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype)
 {
     if (in_dtype != DMATH_F16) return false;
-    const int64_t sp_out = (int64_t)g.oh * g.ow, m = (int64_t)g.n * sp_out;
-    // 32-bit lane offsets into the re-layout copies: each copy has to stay below 4 GiB
+    const ConvF16Layout l = conv_f16_layout(mode, g);
     const int64_t limit = 1ll << 32;
-    const int64_t copy_x = (int64_t)g.n * (g.h + 2 * g.pad_h) * (g.w + 2 * g.pad_w) * g.c * 2;
-    const int64_t copy_dy = (int64_t)g.n * (g.h + g.r - 1) * (g.w + g.s - 1) * g.k * 2;
-    const int64_t copy_f = (int64_t)g.k * g.c * g.r * g.s * 2;
-    if (copy_f >= limit || (mode == CONV_BWD_DATA ? copy_dy : copy_x) >= limit || m * g.k * 2 >= limit) return false;
-    if (mode != CONV_BWD_DATA &&
-        (g.c % 64 || (g.h * g.w) % 4))
-        return false;
-    if (sp_out < 64) return false;
-    if (mode == CONV_FWD) return g.k % 64 == 0 && sp_out % 4 == 0;
-    if (mode == CONV_BWD_FILTER)
-        return (g.k % 256 == 0 || g.k == 128 || g.k == 64) && g.c % 64 == 0 && m % 64 == 0 && sp_out % 4 == 0;
-    // data gradient = forward convolution of dY (k channels) with the rotated filter and
-    // padding r-1-pad: needs that padding to be non-negative
-    return g.pad_h <= g.r - 1 && g.pad_w <= g.s - 1 && g.k % 64 == 0 && g.c % 64 == 0 &&
-           (g.h * g.w) % 4 == 0 && g.h * g.w >= 64 && sp_out % 4 == 0;
+    if (l.x_bytes >= limit || l.f_bytes >= limit || l.y_bytes >= limit) return false;
+    if ((int64_t)g.n * g.oh * g.ow >= (1ll << 31) - 256 || (int64_t)g.n * g.h * g.w >= (1ll << 31) - 256) return false;
+    if ((int64_t)l.cp * l.kp > (int64_t)g.c * g.k * 4) return false;
+    if (mode == CONV_BWD_DATA) return g.pad_h <= g.r - 1 && g.pad_w <= g.s - 1;
+    return true;
 }
 
-// C tiles of the weight gradient: 256 filters (all of them where there are 128 or 64) x 128
-// columns of (r,s,c) (64 where the channel count is not a multiple of 128: a tile's columns are
-// consecutive channels of one tap).
-static int wgrad_tile_m(const ConvGeom& g) { return g.k < 256 ? g.k : 256; }
-static int wgrad_tile_n(const ConvGeom& g) { return g.c % 128 == 0 ? 128 : 64; }
+// C tiles of the weight gradient: 256, 128 or 64 filters x 128 columns of (r,s,c) (64 where the
+// channel count is not a multiple of 128: a tile's columns are consecutive channels of one tap).
+static int wgrad_tile_m(const ConvGeom& g)
+{
+    const int kp = round64(g.k);
+    return kp % 256 == 0 ? 256 : kp % 128 == 0 ? 128 : 64;
+}
+static int wgrad_tile_n(const ConvGeom& g) { return round64(g.c) % 128 == 0 ? 128 : 64; }
 static int64_t wgrad_tiles(const ConvGeom& g)
 {
-    return (int64_t)(g.k / wgrad_tile_m(g)) * ((int64_t)g.c * g.r * g.s / wgrad_tile_n(g));
+    return (int64_t)(round64(g.k) / wgrad_tile_m(g)) * ((int64_t)round64(g.c) * g.r * g.s / wgrad_tile_n(g));
+}
+static int64_t wgrad_ktiles(const ConvGeom& g) { return ((int64_t)g.n * g.oh * g.ow + 63) / 64; }
+
+// A split count is usable when no part is empty.
+static bool wgrad_split_ok(int64_t ktiles, int s)
+{
+    const int64_t per = (ktiles + s - 1) / s;
+    return (s - 1) * per < ktiles;
 }
 
-// Split count for the weight gradient: a divisor s of the k-tiles with at most one round of
-// workgroups that minimises (k-tiles per part + s): the parts shorten with s, the partial sums
-// written and read back grow with it (the balance point sqrt(k-tiles) matches the timing
-// samples on 1x1 and 3x3 layers of 14x14 and 28x28 pixels).
+// Split count for the weight gradient: the number of parts s (each of ceil(k-tiles / s) 64-pixel
+// tiles, the last one possibly shorter) with at most one round of workgroups that minimises
+// (k-tiles per part + s): the parts shorten with s, the partial sums written and read back
+// grow with it (the balance point sqrt(k-tiles) matches the timing samples on 1x1 and 3x3
+// layers of 14x14 and 28x28 pixels).
 int conv_f16_wgrad_split(const ConvGeom& g)
 {
-    const int64_t ktiles = (int64_t)g.n * g.oh * g.ow / 64;
+    const int64_t ktiles = wgrad_ktiles(g);
     const int64_t tiles = wgrad_tiles(g);
     int best = 1;
     int64_t best_cost = ktiles + 1;
-    for (int s = 2; s <= 64; ++s)
-        if (ktiles % s == 0 && tiles * s <= 256 && ktiles / s >= 8 && ktiles / s + s < best_cost) {
-            best_cost = ktiles / s + s;
+    for (int s = 2; s <= 64; ++s) {
+        const int64_t per = (ktiles + s - 1) / s;
+        if (wgrad_split_ok(ktiles, s) && tiles * s <= 256 && per >= 8 && per + s < best_cost) {
+            best_cost = per + s;
             best = s;
         }
+    }
     return best;
 }
 
@@ -458,7 +532,7 @@ ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int3
         return ch;
     }
     const int64_t m = mode == CONV_FWD ? (int64_t)g.n * g.oh * g.ow : (int64_t)g.n * g.h * g.w;
-    const int n_out = mode == CONV_FWD ? g.k : g.c;
+    const int n_out = round64(mode == CONV_FWD ? g.k : g.c);
     // the tile shape whose longest chain of tiles on one CU takes the fewest cycles: rounds of 256
     // workgroups x (k-tiles x the slower of the tile's matrix instructions, 32.5 cycles each over
     // four SIMDs, and its operand loads at 60 bytes per cycle and CU, + the tile's stores at
@@ -466,7 +540,7 @@ ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int3
     // round, against 196 of 256x256 or two rounds of 256x128; 64-wide tiles are load-bound and
     // win only where they save whole rounds.  A narrower tile has to win by 3 %.
     const int shapes[4][2] = {{256, 256}, {224, 256}, {256, 128}, {256, 64}};
-    const int64_t ktiles = (int64_t)g.r * g.s * (mode == CONV_FWD ? g.c : g.k) / 64;
+    const int64_t ktiles = (int64_t)g.r * g.s * round64(mode == CONV_FWD ? g.c : g.k) / 64;
     double best = -1;
     for (auto& sh : shapes) {
         if (n_out % sh[1]) continue;
@@ -500,21 +574,18 @@ std::vector<ConvChoice> conv_candidates(int mode, const ConvGeom& g, dmath_dtype
     c = ConvChoice{};
     c.kernel = 1;
     if (mode == CONV_BWD_FILTER) {
-        const int64_t ktiles = (int64_t)g.n * g.oh * g.ow / 64, tiles = wgrad_tiles(g);
+        const int64_t ktiles = wgrad_ktiles(g), tiles = wgrad_tiles(g);
+        const int model = conv_f16_wgrad_split(g);
         c.tile_m = wgrad_tile_m(g);
         c.tile_n = wgrad_tile_n(g);
         for (int s = 1; s <= 64; ++s)
-            if (ktiles % s == 0 && tiles * s <= 512 && ktiles / s >= 8) {
+            if (s == model || (ktiles % s == 0 && tiles * s <= 512 && ktiles / s >= 8)) {
                 c.split_k = s;
                 out.push_back(c);
             }
-        if (out.back().kernel != 1) {  // no split passes the filter: the cost model's own
-            c.split_k = conv_f16_wgrad_split(g);
-            out.push_back(c);
-        }
         return out;
     }
-    const int n_out = mode == CONV_FWD ? g.k : g.c;
+    const int n_out = round64(mode == CONV_FWD ? g.k : g.c);
     c.tile_m = 256;
     c.tile_n = 64;
     out.push_back(c);
@@ -557,8 +628,13 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
 {
     const ConvTables& t = plan.t;
     const ConvGeom& g = t.g;
+    const int cp = round64(g.c), kp = round64(g.k);
     FastConv p{};
     p.g = g;
+    p.g.c = cp;
+    p.g.k = kp;
+    p.c_real = g.c;
+    p.k_real = g.k;
     p.hp = g.h + 2 * g.pad_h;
     p.wp = g.w + 2 * g.pad_w;
     p.y_rows = t.y_rows;
@@ -573,7 +649,7 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
     p.split = t.split_k;
     if (!xp || (mode != CONV_BWD_FILTER && !fp) || (mode == CONV_BWD_FILTER && (!yt || !p.ws)))
         return hipErrorInvalidValue;  // the plan was not made for this path
-    const int n_out = mode == CONV_BWD_DATA ? g.c : g.k;
+    const int n_out = mode == CONV_BWD_DATA ? cp : kp;
     if (mode != CONV_BWD_FILTER && !((plan.tile_n == 64 || plan.tile_n == 128 || plan.tile_n == 256) && n_out % plan.tile_n == 0))
         return hipErrorInvalidValue;
 
@@ -581,6 +657,7 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
     if (!configured) {
         hipError_t e = set_lds(to_channels_last_kernel<8>, 150 * 1024);
         if (e == hipSuccess) e = set_lds(to_channels_last_kernel<4>, 150 * 1024);
+        if (e == hipSuccess) e = set_lds(to_channels_last_kernel<1>, 150 * 1024);
         if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 128, 3, float>, 3 * 384 * 128);
         if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 128, 3, _Float16>, 3 * 384 * 128);
         if (e == hipSuccess) e = set_lds(conv_fwd_f16_kernel<256, 256, 2, float>, 2 * 512 * 128);
@@ -604,29 +681,32 @@ hipError_t launch_conv_f16(const ConvPlan& plan, int mode, double alpha, double 
         // spatial h x w (so the copy has h+r-1 x w+s-1 pixels), output rows = images of dX
         FastConv q = p;
         const int pph = g.r - 1 - g.pad_h, ppw = g.s - 1 - g.pad_w;
-        q.g.c = g.k; q.g.k = g.c;
+        q.g.c = kp; q.g.k = cp;
+        q.k_real = g.c;
         q.g.h = g.oh; q.g.w = g.ow; q.g.oh = g.h; q.g.ow = g.w;
         q.g.pad_h = pph; q.g.pad_w = ppw;
         q.g.stride_h = q.g.stride_w = 1;
         q.hp = g.h + g.r - 1;
         q.wp = g.w + g.s - 1;
         q.y_rows = t.x_rows;
-        if (rewrite & REWRITE_X) to_channels_last(t.y_rows, g.n, g.k, g.oh, g.ow, pph, ppw, g.stride_h, g.stride_w, q.hp, q.wp, xp, st);
+        if (rewrite & REWRITE_X) to_channels_last(t.y_rows, g.n, g.k, kp, g.oh, g.ow, pph, ppw, g.stride_h, g.stride_w, q.hp, q.wp, xp, st);
         if (rewrite & REWRITE_F)
-            filter_to_rsk_rotated_kernel<<<512, 256, 0, st>>>(t.f_rows, g.c, g.r, g.s, g.k, fp);
+            filter_to_rsk_rotated_kernel<<<512, 256, 0, st>>>(t.f_rows, g.c, g.r, g.s, g.k, kp, fp);
         launch_fwd(q, plan.tile_m, plan.tile_n, plan.out_dtype, (float)alpha, (float)beta, st);
         return hipGetLastError();
     }
     // activations -> zero-bordered channels-last copy (borders were zeroed when the copy was allocated)
-    if (rewrite & REWRITE_X) to_channels_last(t.x_rows, g.n, g.c, g.h, g.w, g.pad_h, g.pad_w, 1, 1, p.hp, p.wp, xp, st);
+    if (rewrite & REWRITE_X) to_channels_last(t.x_rows, g.n, g.c, cp, g.h, g.w, g.pad_h, g.pad_w, 1, 1, p.hp, p.wp, xp, st);
     if (mode == CONV_FWD) {
-        if (rewrite & REWRITE_F) filter_to_rsc_kernel<<<512, 256, 0, st>>>(t.f_rows, g.c, g.r * g.s, g.k, fp);
+        if (rewrite & REWRITE_F) filter_to_rsc_kernel<<<512, 256, 0, st>>>(t.f_rows, g.c, cp, g.r * g.s, g.k, fp);
         launch_fwd(p, plan.tile_m, plan.tile_n, plan.out_dtype, (float)alpha, (float)beta, st);
         return hipGetLastError();
     }
     // weight gradient: dY -> channels-last [m][k], split GEMM, fixed-order reduction
-    if (rewrite & REWRITE_Y) to_channels_last(t.y_rows, g.n, g.k, g.oh, g.ow, 0, 0, 1, 1, g.oh, g.ow, yt, st);
-    p.ktiles_per_split = (int)((int64_t)g.n * g.oh * g.ow / 64 / t.split_k);
+    if (rewrite & REWRITE_Y) to_channels_last(t.y_rows, g.n, g.k, kp, g.oh, g.ow, 0, 0, 1, 1, g.oh, g.ow, yt, st);
+    p.ktiles = (int)wgrad_ktiles(g);
+    p.ktiles_per_split = (p.ktiles + t.split_k - 1) / t.split_k;
+    if (!wgrad_split_ok(p.ktiles, t.split_k)) return hipErrorInvalidValue;  // a part without pixels
     const int tiles = (int)wgrad_tiles(g) * t.split_k;
     const int bm = wgrad_tile_m(g), bn = wgrad_tile_n(g);
     if (bm == 256 && bn == 128) conv_wgrad_f16_kernel<256, 128><<<tiles, NT, 3 * 384 * 128, st>>>(p);

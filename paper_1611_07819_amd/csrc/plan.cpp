@@ -498,14 +498,15 @@ size_t conv_choice_bytes(int mode, const ConvGeom& g, const ConvChoice& c, dmath
 {
     const size_t sp_out = (size_t)g.oh * g.ow, crs = (size_t)g.c * g.r * g.s;
     size_t bytes = 0;
-    if (mode == CONV_BWD_FILTER && (c.split_k > 1 || c.kernel == 1))
+    if (c.kernel == 1 && mode == CONV_BWD_FILTER) {
+        const ConvF16Layout l = conv_f16_layout(mode, g);
+        bytes += (size_t)c.split_k * l.kp * l.cp * g.r * g.s * 4;
+    } else if (mode == CONV_BWD_FILTER && c.split_k > 1) {
         bytes += (size_t)c.split_k * g.k * crs * (in_dtype == DMATH_F64 ? 8 : 4);
+    }
     if (c.kernel == 1) {
-        if (mode == CONV_BWD_DATA)
-            bytes += (size_t)g.n * (g.h + g.r - 1) * (g.w + g.s - 1) * g.k * 2 + (size_t)g.k * crs * 2;
-        else
-            bytes += (size_t)g.n * (g.h + 2 * g.pad_h) * (g.w + 2 * g.pad_w) * g.c * 2 +
-                     (mode == CONV_FWD ? (size_t)g.k * crs * 2 : (size_t)g.n * sp_out * g.k * 2);
+        const ConvF16Layout l = conv_f16_layout(mode, g);
+        bytes += (size_t)(l.x_bytes + l.f_bytes + l.y_bytes);
     }
     return bytes;
 }
@@ -559,9 +560,12 @@ dmath_status_t make_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_
     void* ws = nullptr;
     // the specialised weight-gradient kernel always goes through the partial-sum workspace,
     // also with a single split
+    const ConvF16Layout lay = fast ? conv_f16_layout(mode, g) : ConvF16Layout{};
     if (t.split_k > 1 || (fast && mode == CONV_BWD_FILTER)) {
         size_t acc = plan->in_dtype == DMATH_F64 ? 8 : 4;
-        ws = ctx->pool.alloc((size_t)t.split_k * t.M * t.N * acc);
+        // the specialised kernel's partial sums have the padded extents of its copies
+        const size_t elems = fast ? (size_t)lay.kp * lay.cp * g.r * g.s : (size_t)(t.M * t.N);
+        ws = ctx->pool.alloc((size_t)t.split_k * elems * acc);
         if (!ws) {
             ctx->pool.free(dev);
             return DMATH_ERR_OOM;
@@ -578,16 +582,15 @@ dmath_status_t make_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_
             // between them are those of the allocation), filter rotated with its channel roles swapped
             plan->xp = get_relayout(ctx, Y, RELAYOUT_CHANNELS_LAST,
                                     {g.k, g.oh, g.ow, pph, ppw, g.stride_h, g.stride_w, g.h + g.r - 1, g.w + g.s - 1},
-                                    (size_t)g.n * (g.h + g.r - 1) * (g.w + g.s - 1) * g.k * 2);
-            plan->fp = get_relayout(ctx, F, RELAYOUT_FILTER_ROTATED, {g.c, g.r, g.s, g.k}, (size_t)g.k * crs * 2);
+                                    (size_t)lay.x_bytes);
+            plan->fp = get_relayout(ctx, F, RELAYOUT_FILTER_ROTATED, {g.c, g.r, g.s, g.k}, (size_t)lay.f_bytes);
         } else {
-            plan->xp = get_relayout(ctx, X, RELAYOUT_CHANNELS_LAST, {g.c, g.h, g.w, g.pad_h, g.pad_w},
-                                    (size_t)g.n * (g.h + 2 * g.pad_h) * (g.w + 2 * g.pad_w) * g.c * 2);
+            plan->xp = get_relayout(ctx, X, RELAYOUT_CHANNELS_LAST,
+                                    {g.c, g.h, g.w, g.pad_h, g.pad_w, (int32_t)lay.x_images}, (size_t)lay.x_bytes);
             if (mode == CONV_FWD)
-                plan->fp = get_relayout(ctx, F, RELAYOUT_FILTER_RSC, {g.c, g.r, g.s, g.k}, (size_t)g.k * crs * 2);
+                plan->fp = get_relayout(ctx, F, RELAYOUT_FILTER_RSC, {g.c, g.r, g.s, g.k}, (size_t)lay.f_bytes);
             else
-                plan->yt = get_relayout(ctx, Y, RELAYOUT_CHANNELS_LAST, {g.k, g.oh, g.ow, 0, 0},
-                                        (size_t)g.n * sp_out * g.k * 2);
+                plan->yt = get_relayout(ctx, Y, RELAYOUT_CHANNELS_LAST, {g.k, g.oh, g.ow, 0, 0}, (size_t)lay.y_bytes);
         }
         const bool ok = plan->xp && (mode == CONV_BWD_FILTER ? plan->yt != nullptr : plan->fp != nullptr);
         if (!ok) {

@@ -135,8 +135,7 @@ def _config5(ctx, oracle, w, images, filters):
 
 
 FAST_GEOMS = [
-    # geometries that satisfy the preconditions of the specialised fp16 kernels (channels and
-    # filters multiples of 64, n*oh*ow a multiple of 64, planes a multiple of 4 pixels)
+    # geometries that run on the specialised fp16 kernels
     dict(n=4, c=128, h=16, w=16, k=256, r=3, s=3, pad_h=1, pad_w=1),
     dict(n=8, c=128, h=16, w=8, k=256, r=1, s=1),
     dict(n=2, c=256, h=16, w=16, k=256, r=5, s=3, pad_h=2, pad_w=1),
@@ -153,6 +152,13 @@ FAST_GEOMS = [
     dict(n=4, c=128, h=16, w=16, k=256, r=1, s=1, stride_h=2, stride_w=2),
     dict(n=4, c=64, h=16, w=32, k=128, r=3, s=5, pad_h=1, pad_w=2, stride_h=1, stride_w=2),
     dict(n=4, c=64, h=24, w=24, k=64, r=5, s=5, pad_h=2, pad_w=2, stride_h=3, stride_w=3),
+    # channel and filter counts rounded up to 64 inside the copies, planes of an odd number of
+    # pixels, n*oh*ow not a multiple of 64 (the weight gradient's last pixel tile reads zeros)
+    dict(n=4, c=96, h=13, w=13, k=96, r=3, s=3, pad_h=1, pad_w=1),
+    dict(n=3, c=128, h=7, w=7, k=384, r=3, s=3, pad_h=1, pad_w=1),        # planes of fewer than 64 pixels
+    dict(n=2, c=64, h=27, w=27, k=128, r=5, s=5, pad_h=2, pad_w=2),
+    dict(n=5, c=120, h=9, w=11, k=120, r=3, s=2, pad_h=1, pad_w=0, stride_h=2, stride_w=1),
+    dict(n=16, c=64, h=13, w=13, k=64, r=3, s=3, pad_h=1, pad_w=1),       # 43 pixel tiles in 5 uneven parts
 ]
 
 
@@ -219,13 +225,23 @@ def test_repeated_calls_rewrite_the_channels_last_copy(ctx, oracle):
 @pytest.mark.parametrize("seed", range(8))
 def test_random_geometries_against_oracle(ctx, oracle, seed):
     """Seeded sweep over geometries (filter sizes 1..5, strides 1..3, pads up to the filter size
-    minus one, odd channel counts; every third case a stride-1 geometry with channel counts that
-    the specialised fp16 kernels accept), row-blocked tensors, all three modes, small-integer data
-    compared bit for bit."""
+    minus one, odd channel counts; two cases in four are fp16 geometries that the specialised
+    kernels accept), row-blocked tensors, all three modes, small-integer data compared bit for
+    bit."""
     r = np.random.default_rng(8000 + seed)
     ctx.set_kernel_policy(0)
-    for case in range(3):
-        if case == 2:
+    for case in range(4):
+        if case == 3:
+            # fp16 with channel and filter counts just below multiples of 64, any plane size,
+            # strides and pads: the specialised kernels with padded copies and ragged tiles
+            rr, ss = int(r.integers(1, 5)), int(r.integers(1, 5))
+            g = dict(n=int(r.integers(1, 6)), c=int(r.integers(54, 65)) * int(r.integers(1, 3)),
+                     h=int(r.integers(rr, rr + 12)), w=int(r.integers(ss, ss + 12)),
+                     k=int(r.integers(54, 65)) * int(r.integers(1, 3)), r=rr, s=ss,
+                     pad_h=int(r.integers(0, rr)), pad_w=int(r.integers(0, ss)),
+                     stride_h=int(r.integers(1, 3)), stride_w=int(r.integers(1, 3)))
+            dt, out = dm.F16, [dm.F32, dm.F16][int(r.integers(0, 2))]
+        elif case == 2:
             rr, ss = int(r.integers(1, 4)), int(r.integers(1, 4))
             hw = [(8, 8), (16, 8), (16, 16), (12, 12), (14, 14), (10, 10)][int(r.integers(0, 6))]
             g = dict(n=int(r.integers(1, 4)) * 4, c=int(r.integers(1, 3)) * 128, h=hw[0], w=hw[1], k=256, r=rr, s=ss,
@@ -253,13 +269,14 @@ def test_random_geometries_against_oracle(ctx, oracle, seed):
                                dict(n=5, c=256, h=12, w=6, k=128, r=1, s=1)])
 @pytest.mark.parametrize("out", [dm.F32, dm.F16])
 def test_specialised_fp16_conv_ragged_last_row_tile(ctx, oracle, g, out):
-    """n*oh*ow is not a multiple of the 256-row tile: the last tile of the forward and of the data
-    gradient is ragged (clamped gathers, masked stores); the weight gradient of such a geometry
-    runs on the generic kernel.  Small-integer data, bit for bit, NaN-free neighbours."""
+    """n*oh*ow is not a multiple of the 256-row tile, nor of the weight gradient's 64-pixel tile:
+    the last tile of the forward and of the data gradient is ragged (clamped gathers, masked
+    stores), the weight gradient's last pixel tile reads zeros past the end.  Small-integer data,
+    bit for bit."""
     grids = {"X": (g["n"], 1), "F": (2, 1), "Y": (1, 1)}
     before = ctx.relayout_stats()["written"]
     res = three_modes(ctx, oracle, g, dm.F16, out, 1.0, 1.0, grids, ints=True, policy=0)
-    assert ctx.relayout_stats()["written"] - before == 4       # forward and data gradient: two copies each
+    assert ctx.relayout_stats()["written"] - before == 6       # every mode on the specialised kernels
     for mode, (got, ref) in res.items():
         if out == dm.F16 and np.abs(ref).max() > 2048:
             assert rel_fro(got, ref) <= TOL[dm.F16], mode
