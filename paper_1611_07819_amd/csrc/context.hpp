@@ -173,18 +173,18 @@ hipError_t launch_conv(const ConvPlan& p, int mode, double alpha, double beta, u
 hipError_t launch_reblock(dmath_dtype_t sd, dmath_dtype_t dd, const CopyCell* cells, int n_cells,
                           int max_rows, bool vectors, hipStream_t st);
 int reblock_vector_width(dmath_dtype_t sd, dmath_dtype_t dd);
-// Extents and sizes of the copies the specialised fp16 convolution kernels read: channel and
+// Extents and sizes of the copies the specialised convolution kernels read: channel and
 // filter counts rounded up to multiples of 64, images in the channels-last copy of X (one more,
-// all zeros, where n*oh*ow is not a multiple of 64), bytes of the activation copy (x), the
+// all zeros, where n*oh*ow is not a multiple of the pixel tile), bytes of the activation copy (x), the
 // permuted filter (f; 0 for the weight gradient) and the channels-last dY (y; weight gradient only).
-struct ConvF16Layout {
+struct ConvFastLayout {
     int32_t cp, kp;
     int64_t x_images, x_bytes, f_bytes, y_bytes;
 };
-ConvF16Layout conv_f16_layout(int mode, const ConvGeom& g);
-bool conv_f16_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype);
-int conv_f16_wgrad_split(const ConvGeom& g);
-hipError_t launch_conv_f16(const ConvPlan& p, int mode, double alpha, double beta, unsigned rewrite,
+ConvFastLayout conv_fast_layout(int mode, const ConvGeom& g, dmath_dtype_t in_dtype);
+bool conv_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype);
+int conv_fast_wgrad_split(const ConvGeom& g, dmath_dtype_t in_dtype);
+hipError_t launch_conv_fast(const ConvPlan& p, int mode, double alpha, double beta, unsigned rewrite,
                            hipStream_t st);
 bool read_cycle_probe(uint64_t* out6);  // gemm_f16.hip; false unless built with the cycle probe
 hipError_t launch_mfma_peak(dmath_dtype_t dt, int iters, void* scratch, hipStream_t st, double* flops);
@@ -202,7 +202,7 @@ struct SegView {
 };
 GemmChoice choose_gemm(const SegView& v);
 std::vector<GemmChoice> gemm_candidates(const SegView& v);
-// conv_f16.hip / launch.hip: the cost model's choice and everything worth a timing sample
+// conv_mfma.hip / launch.hip: the cost model's choice and everything worth a timing sample
 ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int32_t policy);
 std::vector<ConvChoice> conv_candidates(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int32_t policy);
 // plan.cpp: plans outside the cache, built for one given choice (timing samples)

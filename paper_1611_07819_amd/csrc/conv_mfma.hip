@@ -1,0 +1,843 @@
+// Specialised convolution kernels for gfx950, fp16 (fp32 accumulate) and fp32: forward, weight
+// gradient and data gradient as implicit GEMMs on the MFMA pipelines of f16_pipeline.hpp and
+// f32_pipeline.hpp (paper abstract: convolutions; section 1: data reorganisation to support a
+// series of operations).
+//
+// NCHW keeps pixels, not channels, contiguous, and the 3x3 taps shift the pixel index by +-1,
+// which no 16-byte load can follow.  So the activations are first rewritten into a
+// zero-bordered channels-last copy in the pool,
+//     Xp[n][h + 2*pad_h][w + 2*pad_w][c]          (borders zeroed once, when the copy is allocated)
+// after which row (n, oh, ow) of the lowered matrix for tap (r, s) is the contiguous c-vector
+// at Xp[n][oh*stride + r][ow*stride + s][:]: a k unit-stride operand whose rows are gathered,
+// with K ordered (r, s, c) and no masks.  The filter is permuted to the same K order, Fp[k][(r,s,c)].
+//   forward        : Y[m, k]   = sum_K  Xp-rows[m, K] * Fp[k, K]          (N,T)-like, M = n*oh*ow
+//   weight gradient: dF[k, K]  = sum_m  Yt[m, k] * Xp-rows[m, K]          (T,N)-like, deep sum over
+//                    m, split over workgroups, fixed-order reduction; Yt = dY rewritten
+//                    channels-last, [m][k].
+//   data gradient  : the forward kernel again (stride 1), over the zero-bordered channels-last
+//                    copy of dY (padding r-1-pad, pixels spread out by the stride) with the filter
+//                    rotated by 180 degrees and its channel roles swapped, Gp[c][(r',s',k)].
+// Channel and filter counts that are not multiples of 64 are rounded up in the copies (the pad
+// channels stay zero, as the allocation left them; stores skip the pad filters), and a pixel count
+// n*oh*ow that is not a multiple of the pipeline's k-tile (64 pixels fp16, 32 fp32) reads zeros
+// past its end (an extra, never-written image in Xp, extra rows in Yt).
+// A rewrite is skipped when the caller says the copy is still current (the context keeps the
+// copies and the version of the matrix each was made from); otherwise it is part of the call.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "context.hpp"
+#include "f16_pipeline.hpp"
+#include "f32_pipeline.hpp"
+
+namespace dm {
+
+namespace {
+
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+constexpr int NT = 256;
+
+// What the kernels below need to know about a pipeline.
+struct PipeF16 {
+    using Elem = _Float16;
+    static constexpr int BK = f16p::BK;
+    template <int BMN, bool KC> using Tile = f16p::OperandTile<BMN, KC>;
+    template <int BM, int BN> using Shape = f16p::TileShape<BM, BN>;
+    template <int BM, int BN, int STAGES, bool AKC, bool BKC, class Walk, class Acc>
+    __device__ __forceinline__ static void run(Walk& walk, int n_ktiles, char* smem, Acc& acc)
+    {
+        f16p::run<BM, BN, STAGES, AKC, BKC>(walk, n_ktiles, smem, acc);
+    }
+    static constexpr int lds_bytes(int bm, int bn, int stages) { return stages * (bm + bn) * BK * 2; }
+};
+struct PipeF32 {
+    using Elem = float;
+    static constexpr int BK = f32p::BK;
+    template <int BMN, bool KC> using Tile = f32p::OperandTile<BMN, KC>;
+    template <int BM, int BN> struct Shape {  // wavefronts 2 x 2
+        static constexpr int WM = BM / 2, WN = BN / 2, MT = WM / 32, NTL = WN / 32;
+        __device__ __forceinline__ static int wm(int wave) { return wave / 2; }
+        __device__ __forceinline__ static int wn(int wave) { return wave % 2; }
+    };
+    template <int BM, int BN, int STAGES, bool AKC, bool BKC, class Walk, class Acc>
+    __device__ __forceinline__ static void run(Walk& walk, int n_ktiles, char* smem, Acc& acc)
+    {
+        static_assert(STAGES == f32p::STAGES, "the fp32 ring has three stages");
+        f32p::run<BM, BN, 2, AKC, BKC>(walk, n_ktiles, smem, acc);
+    }
+    static constexpr int lds_bytes(int bm, int bn, int stages) { return stages * (bm + bn) * BK * 4; }
+};
+
+template <class TC> __device__ __forceinline__ TC to_out(float v) { return (TC)v; }
+
+// ------------------------------------------------------------------------------------------
+// layout rewrites
+// ------------------------------------------------------------------------------------------
+
+// src rows: image n -> [ch][hw] elements (NCHW inside a row).  dst: [n][HP][WP][chd] with pixel
+// (y, x) of the image placed at (ph + y*sy, pw + x*sx); sy = sx = 1 except for the data gradient
+// of a strided convolution, which reads dY spread out with zeros between its pixels.  One
+// workgroup of 1024 threads moves 64 channels of one image (of up to tcl_pixels<T>() pixels of
+// it: blockIdx.y) through LDS: fully coalesced 16-byte reads of the 64 planes, 16-byte writes
+// of consecutive channels per lane.  The plane stride (pixels + pad) keeps the transposed reads
+// spread over the banks.  dst has chd >= ch channels per pixel (a multiple of 64); channels
+// ch .. chd-1 are written as zeros.
+constexpr int kTclThreads = 1024;
+template <class T> constexpr int tcl_pixels() { return 2048 / sizeof(T); }  // 64 planes: 128 KiB of LDS
+template <class T> __host__ __device__ inline int tcl_stride(int px)
+{
+    // 16-bit: stride = 4 mod 16 elements; 32-bit: stride = 2 mod 8
+    return sizeof(T) == 2 ? px + ((20 - px % 16) % 16) : px + ((10 - px % 8) % 8);
+}
+
+// VB: bytes per global read: 16 where a plane is a multiple of 16 bytes, 8 where of 8, else one element.
+template <class T, int VB>
+__global__ __launch_bounds__(kTclThreads) void to_channels_last_kernel(const void* const* src_rows, int ch,
+                                                                       int chd, int h, int w, int ph, int pw,
+                                                                       int sy, int sx, int hp, int wp, T* dst)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    T* planes = reinterpret_cast<T*>(smem);  // [64][stride]
+    constexpr int VEC = VB / (int)sizeof(T), kPixels = tcl_pixels<T>();
+    constexpr int kPerLane = 16 / (int)sizeof(T), kLanesPerPixel = 64 / kPerLane;  // 16-byte writes
+    const int hw = h * w;
+    const int p0 = blockIdx.y * kPixels, pixels = min(kPixels, hw - p0);  // this workgroup's pixels
+    const int stride = tcl_stride<T>(min(kPixels, hw));
+    const int chunks_c = chd / 64;
+    const int n = blockIdx.x / chunks_c, c0 = (blockIdx.x % chunks_c) * 64;
+    const int planes_here = min(64, ch - c0);  // the last group of a padded channel count is short
+    const T* src = static_cast<const T*>(src_rows[n]) + (int64_t)c0 * hw + p0;
+    const int vec_per_plane = pixels / VEC;
+    for (int e = threadIdx.x; e < 64 * vec_per_plane; e += kTclThreads) {
+        const int c = e / vec_per_plane, v = e - c * vec_per_plane;
+        const bool real = c < planes_here;
+        if (VEC == 1) {
+            planes[c * stride + v] = real ? src[(int64_t)c * hw + v] : (T)0.f;
+            continue;
+        }
+        v2u* q = reinterpret_cast<v2u*>(planes + c * stride + v * VEC);  // rows are 8-byte aligned
+        if (VB == 16) {
+            v4u d = {0u, 0u, 0u, 0u};
+            if (real) d = *reinterpret_cast<const v4u*>(src + (int64_t)c * hw + v * VEC);
+            q[0] = v2u{d[0], d[1]};
+            q[1] = v2u{d[2], d[3]};
+        } else {
+            v2u d = {0u, 0u};
+            if (real) d = *reinterpret_cast<const v2u*>(src + (int64_t)c * hw + v * VEC);
+            q[0] = d;
+        }
+    }
+    __syncthreads();
+    T* out = dst + ((int64_t)n * hp * wp) * chd + c0;
+    typedef T vout __attribute__((ext_vector_type(kPerLane)));
+    for (int e = threadIdx.x; e < pixels * kLanesPerPixel; e += kTclThreads) {
+        const int pix = e / kLanesPerPixel, cg = e % kLanesPerPixel;
+        const int y = (p0 + pix) / w, x = (p0 + pix) - y * w;
+        vout v;
+#pragma unroll
+        for (int i = 0; i < kPerLane; ++i) v[i] = planes[(cg * kPerLane + i) * stride + pix];
+        *reinterpret_cast<vout*>(out + ((int64_t)(y * sy + ph) * wp + (x * sx + pw)) * chd + cg * kPerLane) = v;
+    }
+}
+
+// NCHW rows -> zero-bordered channels-last copy, on stream st.
+template <class T>
+static void to_channels_last(const void* const* src_rows, int n, int ch, int chd, int h, int w, int ph, int pw,
+                             int sy, int sx, int hp, int wp, T* dst, hipStream_t st)
+{
+    const int hw = h * w, lds = 64 * tcl_stride<T>(std::min(tcl_pixels<T>(), hw)) * (int)sizeof(T);
+    const dim3 grid(n * (chd / 64), (hw + tcl_pixels<T>() - 1) / tcl_pixels<T>());
+    const int plane_bytes = hw * (int)sizeof(T);
+    if (plane_bytes % 16 == 0)
+        to_channels_last_kernel<T, 16><<<grid, kTclThreads, lds, st>>>(src_rows, ch, chd, h, w, ph, pw, sy, sx, hp, wp, dst);
+    else if (plane_bytes % 8 == 0)
+        to_channels_last_kernel<T, 8><<<grid, kTclThreads, lds, st>>>(src_rows, ch, chd, h, w, ph, pw, sy, sx, hp, wp, dst);
+    else
+        to_channels_last_kernel<T, sizeof(T)><<<grid, kTclThreads, lds, st>>>(src_rows, ch, chd, h, w, ph, pw, sy, sx, hp, wp, dst);
+}
+
+// F[k][c][r][s] -> Fp[k][(r,s,cp)], cp >= c channels per tap (the pad channels written as zeros)
+template <class T>
+__global__ __launch_bounds__(256) void filter_to_rsc_kernel(const void* const* f_rows, int c, int cp, int rs,
+                                                            int k, T* fp)
+{
+    const int64_t total = (int64_t)k * cp * rs;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        const int kk = (int)(e / (cp * rs)), rem = (int)(e % (cp * rs));
+        const int q = rem / cp, cc = rem % cp;  // destination order (rs, cp)
+        fp[e] = cc < c ? static_cast<const T*>(f_rows[kk])[cc * rs + q] : (T)0.f;
+    }
+}
+
+// F[k][c][r][s] -> Gp[c][(r',s',kp)] with r' = R-1-r, s' = S-1-s: the filter of the forward
+// convolution (over dY, channels k) that computes the data gradient; kp >= k filters per tap
+// (the pad filters written as zeros).
+template <class T>
+__global__ __launch_bounds__(256) void filter_to_rsk_rotated_kernel(const void* const* f_rows, int c, int r,
+                                                                    int s, int k, int kp, T* gp)
+{
+    const int rs = r * s;
+    const int64_t total = (int64_t)c * rs * kp;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        const int cc = (int)(e / (rs * kp)), rem = (int)(e % (rs * kp));
+        const int q = rem / kp, kk = rem % kp;  // destination order (r', s', kp)
+        const int rr = r - 1 - q / s, ss = s - 1 - q % s;
+        gp[e] = kk < k ? static_cast<const T*>(f_rows[kk])[cc * rs + rr * s + ss] : (T)0.f;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// forward
+// ------------------------------------------------------------------------------------------
+struct FastConv {
+    ConvGeom g;  // c and k rounded up to multiples of 64: the extents of the copies
+    int c_real, k_real;  // what the tensors hold (forward, data gradient: k_real = output channels stored)
+    int hp, wp;
+    const void* const* y_rows;  // forward: output rows (images)
+    const void* const* f_rows;  // weight gradient: output rows (filters)
+    const void* xp;  // the copies, elements of the pipeline's input type
+    const void* fp;
+    const void* yt;
+    float* ws;
+    int split, ktiles, ktiles_per_split;  // weight gradient: parts, pixel k-tiles in all and per part
+};
+
+// byte offset of pixel m = (n, oh, ow) in Xp (tap (0,0), channel 0)
+template <class T> __device__ __forceinline__ uint32_t pixel_offset(const FastConv& p, int m)
+{
+    const int sp_out = p.g.oh * p.g.ow;
+    const int n = m / sp_out, sp = m % sp_out, oy = sp / p.g.ow, ox = sp % p.g.ow;
+    return (uint32_t)((((int64_t)n * p.hp + oy * p.g.stride_h) * p.wp + ox * p.g.stride_w) * p.g.c * sizeof(T));
+}
+
+template <class P, int BM, int BN> struct FwdWalk {
+    using T = typename P::Elem;
+    using TA = typename P::template Tile<BM, true>;
+    using TB = typename P::template Tile<BN, true>;
+    static constexpr int BK = P::BK;
+    const char *abase, *bbase, *xp;
+    uint32_t aoff[TA::kInstr], boff[TB::kInstr];
+    int c, wp, s_taps, cchunks, r, s, cc;
+
+    __device__ __forceinline__ FwdWalk(const FastConv& p, int m0, int n0, int wave, int lane)
+    {
+        xp = reinterpret_cast<const char*>(p.xp);
+        c = p.g.c; wp = p.wp; s_taps = p.g.s; cchunks = p.g.c / BK;
+        r = s = cc = 0;
+        abase = xp;
+        bbase = reinterpret_cast<const char*>(p.fp);
+        // rows past the last pixel (ragged last tile) fetch the last pixel again: in bounds, and
+        // what they bring in only reaches accumulators that the epilogue does not store
+        const int m_last = p.g.n * p.g.oh * p.g.ow - 1;
+#pragma unroll
+        for (int q = 0; q < TA::kInstr; ++q) {
+            int row, chunk;
+            TA::lane_slot(q, wave, lane, row, chunk);
+            aoff[q] = pixel_offset<T>(p, min(m0 + row, m_last)) + chunk * 16;
+        }
+        TB::offsets((int64_t)p.g.c * p.g.r * p.g.s, n0, BN, wave, lane, boff);
+    }
+    __device__ __forceinline__ void advance()
+    {
+        bbase += BK * sizeof(T);
+        if (++cc == cchunks) {
+            cc = 0;
+            if (++s == s_taps) {
+                s = 0;
+                ++r;
+            }
+        }
+        abase = xp + ((int64_t)(r * wp + s) * c + cc * BK) * sizeof(T);
+    }
+};
+
+// workgroup w of n: XCD w % 8 gets a contiguous run of the logical order
+__device__ __forceinline__ int xcd_logical(int w, int n)
+{
+    const int base = n / 8, rem = n % 8, x = w % 8, j = w / 8;
+    if (n < 16) return w;
+    return x * base + min(x, rem) + j;
+}
+
+template <class P, int BM, int BN, int STAGES, class TC>
+__global__ __launch_bounds__(NT) void conv_fwd_kernel(FastConv p, float alpha, float beta)
+{
+    using TS = typename P::template Shape<BM, BN>;
+    constexpr int WM = TS::WM, WN = TS::WN, MT = TS::MT, NTL = TS::NTL;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const int tiles_n = p.g.k / BN;
+    const int idx = xcd_logical(blockIdx.x, gridDim.x);
+    const int m0 = (idx / tiles_n) * BM, n0 = (idx % tiles_n) * BN;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = TS::wm(wave), wn = TS::wn(wave), h = lane >> 5, l32 = lane & 31;
+
+    v16f acc[MT][NTL];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NTL; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    FwdWalk<P, BM, BN> walk(p, m0, n0, wave, lane);
+    const int n_ktiles = p.g.r * p.g.s * (p.g.c / P::BK);
+    P::template run<BM, BN, STAGES, true, true>(walk, n_ktiles, smem, acc);
+
+    // epilogue: four consecutive registers are four consecutive pixels of one output plane
+    const int sp_out = p.g.oh * p.g.ow, m_end = p.g.n * sp_out;
+    if (sp_out % 4 != 0) {
+        // planes that 4-pixel groups straddle: one element at a time
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                if (m >= m_end) continue;
+                const int n_img = m / sp_out, sp = m % sp_out;
+                TC* yrow = static_cast<TC*>(const_cast<void*>(p.y_rows[n_img]));
+#pragma unroll
+                for (int j = 0; j < NTL; ++j) {
+                    const int ko = n0 + wn * WN + j * 32 + l32;
+                    if (ko >= p.k_real) continue;
+                    TC* dst = yrow + (int64_t)ko * sp_out + sp;
+                    float v = alpha * acc[i][j][r];
+                    if (beta != 0.f) v += beta * (float)*dst;
+                    *dst = to_out<TC>(v);
+                }
+            }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const int m = m0 + wm * WM + i * 32 + 8 * q4 + 4 * h;
+            if (m >= m_end) continue;  // ragged last tile (m_end is a multiple of 4, as sp_out is)
+            const int n_img = m / sp_out, sp = m % sp_out;
+            TC* yrow = static_cast<TC*>(const_cast<void*>(p.y_rows[n_img]));
+#pragma unroll
+            for (int j = 0; j < NTL; ++j) {
+                const int ko = n0 + wn * WN + j * 32 + l32;
+                if (ko >= p.k_real) continue;  // pad filters
+                TC* dst = yrow + (int64_t)ko * sp_out + sp;
+                typedef TC out4 __attribute__((ext_vector_type(4)));
+                out4 o;
+                if (beta != 0.f) o = *reinterpret_cast<out4*>(dst);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float v = alpha * acc[i][j][q4 * 4 + e];
+                    if (beta != 0.f) v += beta * (float)o[e];
+                    o[e] = to_out<TC>(v);
+                }
+                *reinterpret_cast<out4*>(dst) = o;
+            }
+        }
+}
+
+// ------------------------------------------------------------------------------------------
+// weight gradient
+// ------------------------------------------------------------------------------------------
+template <class P, int BM, int BN> struct WgradWalk {
+    using T = typename P::Elem;
+    using TA = typename P::template Tile<BM, false>;
+    using TB = typename P::template Tile<BN, false>;
+    static constexpr int BK = P::BK;
+    const char *abase, *bbase;
+    uint32_t aoff[TA::kInstr], boff[TB::kInstr];
+    // pixel (n, oy, ox) fetched by this lane for each B segment, and the geometry to step it
+    int pn[TB::kInstr], py[TB::kInstr], px[TB::kInstr], chunk16[TB::kInstr];
+    int oh, ow, hp, wp, c, d_oy, d_ox, sh, sw;
+    int64_t astep;
+
+    __device__ __forceinline__ WgradWalk(const FastConv& p, int k0_pixels, int m0_filters, int n0_cols, int wave,
+                                         int lane)
+    {
+        oh = p.g.oh; ow = p.g.ow; hp = p.hp; wp = p.wp; c = p.g.c; sh = p.g.stride_h; sw = p.g.stride_w;
+        d_oy = BK / ow; d_ox = BK % ow;
+        // A' = Yt[m][k]: dense, m/n (= k_out) unit-stride, filters m0 .. m0+BM of the tile
+        TA::offsets(p.g.k, m0_filters, BM, wave, lane, aoff);
+        astep = TA::step(p.g.k);
+        abase = reinterpret_cast<const char*>(p.yt) + (int64_t)k0_pixels * p.g.k * sizeof(T);
+        // B' columns n0 .. n0+BN of (r, s, c): one tap, BN consecutive channels
+        const int tap = n0_cols / c, c0 = n0_cols % c, r = tap / p.g.s, s = tap % p.g.s;
+        bbase = reinterpret_cast<const char*>(p.xp) + ((int64_t)(r * wp + s) * c + c0) * sizeof(T);
+        const int sp_out = oh * ow;
+#pragma unroll
+        for (int q = 0; q < TB::kInstr; ++q) {
+            int row, chunk;
+            TB::lane_slot(q, wave, lane, row, chunk);
+            const int m = k0_pixels + row;
+            pn[q] = m / sp_out;
+            const int sp = m % sp_out;
+            py[q] = sp / ow;
+            px[q] = sp % ow;
+            chunk16[q] = chunk * 16;
+        }
+        set_boff();
+    }
+    __device__ __forceinline__ void set_boff()
+    {
+#pragma unroll
+        for (int q = 0; q < TB::kInstr; ++q)
+            boff[q] = (uint32_t)((((int64_t)pn[q] * hp + py[q] * sh) * wp + px[q] * sw) * c * sizeof(T)) + chunk16[q];
+    }
+    __device__ __forceinline__ void advance()
+    {
+        abase += astep;
+#pragma unroll
+        for (int q = 0; q < TB::kInstr; ++q) {  // pixel index += BK
+            px[q] += d_ox;
+            py[q] += d_oy;
+            if (px[q] >= ow) { px[q] -= ow; ++py[q]; }
+            while (py[q] >= oh) { py[q] -= oh; ++pn[q]; }  // planes of fewer than BK pixels: several images
+        }
+        set_boff();
+    }
+};
+
+template <class P, int BM, int BN>
+__global__ __launch_bounds__(NT) void conv_wgrad_kernel(FastConv p)
+{
+    using TS = typename P::template Shape<BM, BN>;
+    constexpr int BK = P::BK;
+    constexpr int WM = TS::WM, WN = TS::WN, MT = TS::MT, NTL = TS::NTL;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const int ncols = p.g.c * p.g.r * p.g.s, tiles_n = ncols / BN, tiles_mn = (p.g.k / BM) * tiles_n;
+    const int idx = xcd_logical(blockIdx.x, gridDim.x);
+    const int split = idx / tiles_mn, mn = idx % tiles_mn;  // split-major: same pixels, same XCD
+    const int m0 = (mn / tiles_n) * BM, n0 = (mn % tiles_n) * BN;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = TS::wm(wave), wn = TS::wn(wave), l32 = lane & 31;
+
+    v16f acc[MT][NTL];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NTL; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // the last part may be shorter; pixels past n*oh*ow (last k-tile) read zeros on both sides
+    const int kt0 = split * p.ktiles_per_split;
+    WgradWalk<P, BM, BN> walk(p, kt0 * BK, m0, n0, wave, lane);
+    P::template run<BM, BN, 3, false, false>(walk, min(p.ktiles_per_split, p.ktiles - kt0), smem, acc);
+
+    float* ws = p.ws + (int64_t)split * p.g.k * ncols;
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NTL; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + wm * WM + i * 32 + acc32_row(lane, r);
+                const int col = n0 + wn * WN + j * 32 + l32;
+                ws[(int64_t)row * ncols + col] = acc[i][j][r];
+            }
+}
+
+// dF[k][c][r][s] <- alpha * sum over splits (ascending) + beta * dF; the partials are
+// [k][(r,s,c)], read four channels at a time.
+template <class TC>
+__global__ __launch_bounds__(256) void conv_wgrad_reduce_kernel(FastConv p, float alpha, float beta)
+{
+    const int rs = p.g.r * p.g.s, c = p.g.c, ncols = rs * c;
+    const int64_t total = (int64_t)p.g.k * ncols, quads = total / 4;
+    for (int64_t e4 = (int64_t)blockIdx.x * 256 + threadIdx.x; e4 < quads; e4 += (int64_t)gridDim.x * 256) {
+        const int64_t e = e4 * 4;
+        const int kk = (int)(e / ncols), col = (int)(e % ncols), q = col / c, cc = col % c;
+        if (kk >= p.k_real || cc >= p.c_real) continue;  // pad filters, pad channels
+        v4f sum = {0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < p.split; ++s) sum += *reinterpret_cast<const v4f*>(p.ws + (int64_t)s * total + e);
+        TC* dst = static_cast<TC*>(const_cast<void*>(p.f_rows[kk])) + cc * rs + q;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (cc + i >= p.c_real) break;
+            float v = alpha * sum[i];
+            if (beta != 0.f) v += beta * (float)dst[i * rs];
+            dst[i * rs] = to_out<TC>(v);
+        }
+    }
+}
+
+template <class K> hipError_t set_lds(K kern, int bytes)
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+}  // namespace
+
+static int round64(int v) { return (v + 63) / 64 * 64; }
+static int elem_bytes(dmath_dtype_t dt) { return dt == DMATH_F16 ? 2 : 4; }
+// pixels per k-tile of the weight gradient (= the pipeline's k-tile)
+static int pixel_tile(dmath_dtype_t dt) { return dt == DMATH_F16 ? PipeF16::BK : PipeF32::BK; }
+
+// Sizes of the copies that the specialised kernels read.
+ConvFastLayout conv_fast_layout(int mode, const ConvGeom& g, dmath_dtype_t dt)
+{
+    ConvFastLayout l{};
+    l.cp = round64(g.c);
+    l.kp = round64(g.k);
+    const int64_t m = (int64_t)g.n * g.oh * g.ow, crs_p = (int64_t)g.r * g.s * l.cp;
+    const int64_t eb = elem_bytes(dt), pt = pixel_tile(dt);
+    // one more (all-zero) image where the weight gradient's last pixel tile is not full
+    l.x_images = g.n + (m % pt ? 1 : 0);
+    if (mode == CONV_BWD_DATA) {
+        l.x_bytes = (int64_t)g.n * (g.h + g.r - 1) * (g.w + g.s - 1) * l.kp * eb;
+        l.f_bytes = (int64_t)l.cp * g.r * g.s * l.kp * eb;
+    } else {
+        l.x_bytes = (int64_t)l.x_images * (g.h + 2 * g.pad_h) * (g.w + 2 * g.pad_w) * l.cp * eb;
+        l.f_bytes = mode == CONV_FWD ? (int64_t)l.kp * crs_p * eb : 0;
+        l.y_bytes = mode == CONV_BWD_FILTER ? (m + pt - 1) / pt * pt * l.kp * eb : 0;
+    }
+    return l;
+}
+
+// Geometry the specialised kernels accept (everything else runs on the generic kernels): fp16 or
+// fp32, every copy below 4 GiB (32-bit lane offsets), at most four times the work from rounding
+// the channel and filter counts up to multiples of 64 (the matrix pipeline is more than ten
+// times faster than the generic kernel in fp16, three to four times in fp32: there the limit is
+// twice the work), and for the data gradient (a forward convolution of dY with padding r-1-pad)
+// a padding that does not exceed the filter.
+bool conv_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype)
+{
+    if (in_dtype != DMATH_F16 && in_dtype != DMATH_F32) return false;
+    const ConvFastLayout l = conv_fast_layout(mode, g, in_dtype);
+    const int64_t limit = 1ll << 32;
+    if (l.x_bytes >= limit || l.f_bytes >= limit || l.y_bytes >= limit) return false;
+    if ((int64_t)g.n * g.oh * g.ow >= (1ll << 31) - 256 || (int64_t)g.n * g.h * g.w >= (1ll << 31) - 256) return false;
+    if ((int64_t)l.cp * l.kp > (int64_t)g.c * g.k * (in_dtype == DMATH_F16 ? 4 : 2)) return false;
+    if (mode == CONV_BWD_DATA) return g.pad_h <= g.r - 1 && g.pad_w <= g.s - 1;
+    return true;
+}
+
+// C tiles of the weight gradient: 256 (fp16 only), 128 or 64 filters x 128 columns of (r,s,c)
+// (64 where the channel count is not a multiple of 128: a tile's columns are consecutive
+// channels of one tap).
+static int wgrad_tile_m(const ConvGeom& g, dmath_dtype_t dt)
+{
+    const int kp = round64(g.k);
+    return (kp % 256 == 0 && dt == DMATH_F16) ? 256 : kp % 128 == 0 ? 128 : 64;
+}
+static int wgrad_tile_n(const ConvGeom& g) { return round64(g.c) % 128 == 0 ? 128 : 64; }
+static int64_t wgrad_tiles(const ConvGeom& g, dmath_dtype_t dt)
+{
+    return (int64_t)(round64(g.k) / wgrad_tile_m(g, dt)) * ((int64_t)round64(g.c) * g.r * g.s / wgrad_tile_n(g));
+}
+static int64_t wgrad_ktiles(const ConvGeom& g, dmath_dtype_t dt)
+{
+    const int pt = pixel_tile(dt);
+    return ((int64_t)g.n * g.oh * g.ow + pt - 1) / pt;
+}
+
+// A split count is usable when no part is empty.
+static bool wgrad_split_ok(int64_t ktiles, int s)
+{
+    const int64_t per = (ktiles + s - 1) / s;
+    return (s - 1) * per < ktiles;
+}
+
+// Workgroups per CU by the LDS their tile needs (160 KiB per CU).
+static int per_cu(int bm, int bn, dmath_dtype_t dt)
+{
+    if (dt == DMATH_F16) return 1;
+    return 160 * 1024 / PipeF32::lds_bytes(bm, bn, 3);
+}
+
+// Split count for the weight gradient: the number of parts s (each of ceil(k-tiles / s) pixel
+// tiles, the last one possibly shorter) with at most one round of workgroups that minimises
+// (k-tiles per part + s), both counted in 64-pixel units: the parts shorten with s, the partial
+// sums written and read back grow with it (the balance point sqrt(k-tiles) matches the timing
+// samples on 1x1 and 3x3 layers of 14x14 and 28x28 pixels).
+int conv_fast_wgrad_split(const ConvGeom& g, dmath_dtype_t dt)
+{
+    const int64_t ktiles = wgrad_ktiles(g, dt);
+    const int64_t tiles = wgrad_tiles(g, dt);
+    const int unit = 64 / pixel_tile(dt);  // k-tiles per 64 pixels
+    const int slots = 256 * per_cu(wgrad_tile_m(g, dt), wgrad_tile_n(g), dt);
+    int best = 1;
+    int64_t best_cost = ktiles / unit + 1;
+    for (int s = 2; s <= 64; ++s) {
+        const int64_t per = (ktiles + s - 1) / s;
+        if (wgrad_split_ok(ktiles, s) && tiles * s <= slots && per >= 8 * unit && per / unit + s < best_cost) {
+            best_cost = per / unit + s;
+            best = s;
+        }
+    }
+    return best;
+}
+
+// Generic weight gradient: few C tiles and a very deep K.
+static int32_t generic_wgrad_split(const ConvGeom& g)
+{
+    const int64_t M = g.k, N = (int64_t)g.c * g.r * g.s, K = (int64_t)g.n * g.oh * g.ow;
+    const int64_t tiles = ((M + 63) / 64) * ((N + 63) / 64);
+    const int64_t want = std::max<int64_t>(1, 1024 / std::max<int64_t>(1, tiles));
+    const int64_t max_by_k = std::max<int64_t>(1, K / 512);
+    return (int32_t)std::min<int64_t>({want, max_by_k, 64});
+}
+
+// Tile shapes of the forward kernel (also the data gradient's), widest first.
+struct FwdShape { int bm, bn; };
+static std::vector<FwdShape> fwd_shapes(dmath_dtype_t dt, int n_out)
+{
+    std::vector<FwdShape> all;
+    if (dt == DMATH_F16)
+        all = {{256, 256}, {224, 256}, {256, 128}, {256, 64}};
+    else
+        all = {{128, 128}, {128, 64}};
+    std::vector<FwdShape> out;
+    for (const FwdShape& sh : all)
+        if (n_out % sh.bn == 0) out.push_back(sh);
+    return out;
+}
+
+// The cost model: the specialised kernels wherever their preconditions hold; the tile shape of
+// the forward pass and the data gradient from a cycle count per round of workgroups, the split
+// of the weight gradient from conv_fast_wgrad_split.
+ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int32_t policy)
+{
+    ConvChoice ch;
+    if (policy != 0 || !conv_fast_ok(mode, g, in_dtype)) {
+        if (mode == CONV_BWD_FILTER) ch.split_k = generic_wgrad_split(g);
+        return ch;
+    }
+    ch.kernel = 1;
+    if (mode == CONV_BWD_FILTER) {
+        ch.tile_m = wgrad_tile_m(g, in_dtype);
+        ch.tile_n = wgrad_tile_n(g);
+        ch.split_k = conv_fast_wgrad_split(g, in_dtype);
+        return ch;
+    }
+    const int64_t m = mode == CONV_FWD ? (int64_t)g.n * g.oh * g.ow : (int64_t)g.n * g.h * g.w;
+    const int n_out = round64(mode == CONV_FWD ? g.k : g.c);
+    // the tile shape whose longest chain of tiles on one CU takes the fewest cycles: rounds of
+    // workgroups over all slots x (k x the slower of the tile's matrix instructions -- fp16: 32.5
+    // cycles per 32x32x16 over four SIMDs, fp32: 64 per 32x32x2 -- and its operand loads at 60
+    // bytes per cycle and CU, + the tile's stores at 10 bytes per cycle and CU).  fp16, 50176
+    // pixels x 256 channels: 224 tiles of 224x256 are one round, against 196 of 256x256 or two
+    // rounds of 256x128; 64-wide tiles are load-bound and win only where they save whole
+    // rounds.  A narrower tile has to win by 3 %.
+    const int64_t k_depth = (int64_t)g.r * g.s * round64(mode == CONV_FWD ? g.c : g.k);
+    const int eb = elem_bytes(in_dtype);
+    const double mfma_per_k = in_dtype == DMATH_F16 ? 32.5 / 16 : 64.0 / 2;  // cycles per unit of k and 32x32 block
+    double best = -1;
+    for (const FwdShape& sh : fwd_shapes(in_dtype, n_out)) {
+        const int64_t tiles = (m + sh.bm - 1) / sh.bm * (n_out / sh.bn);
+        const int slots = per_cu(sh.bm, sh.bn, in_dtype);
+        const int64_t chain = (tiles + 256 * slots - 1) / (256 * slots) * slots;  // tiles the busiest CU runs
+        const double area = (double)sh.bm * sh.bn;
+        const double per_k = std::max(area / 1024 * mfma_per_k / 4, (sh.bm + sh.bn) * eb / 60.0);
+        const double cost = (double)chain * (k_depth * per_k + 0.4 * area);
+        if (best < 0 || cost < 0.97 * best) {
+            best = cost;
+            ch.tile_m = sh.bm;
+            ch.tile_n = sh.bn;
+        }
+    }
+    return ch;
+}
+
+// Everything worth a timing sample: the generic kernel (weight gradient: unsplit and with its
+// own split), and where the specialised kernels apply, every tile shape (forward, data
+// gradient) or the cost model's split and every split count that divides the k-tiles evenly,
+// keeps at least 8 of them per part and at most two rounds of workgroups (weight gradient).
+std::vector<ConvChoice> conv_candidates(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int32_t policy)
+{
+    std::vector<ConvChoice> out;
+    ConvChoice c;
+    out.push_back(c);
+    if (mode == CONV_BWD_FILTER && generic_wgrad_split(g) > 1) {
+        c.split_k = generic_wgrad_split(g);
+        out.push_back(c);
+    }
+    if (policy != 0 || !conv_fast_ok(mode, g, in_dtype)) return out;
+    c = ConvChoice{};
+    c.kernel = 1;
+    if (mode == CONV_BWD_FILTER) {
+        const int64_t ktiles = wgrad_ktiles(g, in_dtype), tiles = wgrad_tiles(g, in_dtype);
+        const int model = conv_fast_wgrad_split(g, in_dtype);
+        c.tile_m = wgrad_tile_m(g, in_dtype);
+        c.tile_n = wgrad_tile_n(g);
+        for (int s = 1; s <= 64; ++s)
+            if (s == model || (ktiles % s == 0 && tiles * s <= 512 && ktiles / s >= 8)) {
+                c.split_k = s;
+                out.push_back(c);
+            }
+        return out;
+    }
+    for (const FwdShape& sh : fwd_shapes(in_dtype, round64(mode == CONV_FWD ? g.k : g.c))) {
+        c.tile_m = sh.bm;
+        c.tile_n = sh.bn;
+        out.push_back(c);
+    }
+    return out;
+}
+
+namespace {
+
+// Launches the forward kernel (also the data gradient's) on tiles of BM x BN.
+template <class P, int BM, int BN, int STAGES>
+hipError_t launch_fwd_shape(const FastConv& p, dmath_dtype_t out, float alpha, float beta, hipStream_t st)
+{
+    const int64_t m = (int64_t)p.g.n * p.g.oh * p.g.ow;
+    const int tiles = (int)((m + BM - 1) / BM) * (p.g.k / BN);
+    constexpr int lds = P::lds_bytes(BM, BN, STAGES);
+    static bool configured = false;  // more than 64 KiB of LDS has to be asked for once per kernel
+    if (!configured) {
+        hipError_t e = set_lds(conv_fwd_kernel<P, BM, BN, STAGES, float>, lds);
+        if (e == hipSuccess && std::is_same<P, PipeF16>::value)
+            e = set_lds(conv_fwd_kernel<P, BM, BN, STAGES, typename P::Elem>, lds);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    if (out == DMATH_F16)
+        conv_fwd_kernel<P, BM, BN, STAGES, typename P::Elem><<<tiles, NT, lds, st>>>(p, alpha, beta);
+    else
+        conv_fwd_kernel<P, BM, BN, STAGES, float><<<tiles, NT, lds, st>>>(p, alpha, beta);
+    return hipGetLastError();
+}
+
+hipError_t launch_fwd(const FastConv& p, dmath_dtype_t in, int tile_m, int tile_n, dmath_dtype_t out, float alpha,
+                      float beta, hipStream_t st)
+{
+    if (in == DMATH_F32) {
+        if (tile_m == 128 && tile_n == 128) return launch_fwd_shape<PipeF32, 128, 128, 3>(p, out, alpha, beta, st);
+        if (tile_m == 128 && tile_n == 64) return launch_fwd_shape<PipeF32, 128, 64, 3>(p, out, alpha, beta, st);
+        return hipErrorInvalidValue;
+    }
+    if (tile_m == 224 && tile_n == 256) return launch_fwd_shape<PipeF16, 224, 256, 2>(p, out, alpha, beta, st);
+    if (tile_m == 256 && tile_n == 256) return launch_fwd_shape<PipeF16, 256, 256, 2>(p, out, alpha, beta, st);
+    if (tile_m == 256 && tile_n == 128) return launch_fwd_shape<PipeF16, 256, 128, 3>(p, out, alpha, beta, st);
+    if (tile_m == 256 && tile_n == 64) return launch_fwd_shape<PipeF16, 256, 64, 3>(p, out, alpha, beta, st);
+    return hipErrorInvalidValue;
+}
+
+template <class P, int BM, int BN> hipError_t launch_wgrad_shape(const FastConv& p, int tiles, hipStream_t st)
+{
+    constexpr int lds = P::lds_bytes(BM, BN, 3);
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = set_lds(conv_wgrad_kernel<P, BM, BN>, lds);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    conv_wgrad_kernel<P, BM, BN><<<tiles, NT, lds, st>>>(p);
+    return hipGetLastError();
+}
+
+hipError_t launch_wgrad(const FastConv& p, dmath_dtype_t in, int bm, int bn, int tiles, hipStream_t st)
+{
+    if (in == DMATH_F32) {
+        if (bm == 128 && bn == 128) return launch_wgrad_shape<PipeF32, 128, 128>(p, tiles, st);
+        if (bm == 128 && bn == 64) return launch_wgrad_shape<PipeF32, 128, 64>(p, tiles, st);
+        if (bm == 64 && bn == 128) return launch_wgrad_shape<PipeF32, 64, 128>(p, tiles, st);
+        if (bm == 64 && bn == 64) return launch_wgrad_shape<PipeF32, 64, 64>(p, tiles, st);
+        return hipErrorInvalidValue;
+    }
+    if (bm == 256 && bn == 128) return launch_wgrad_shape<PipeF16, 256, 128>(p, tiles, st);
+    if (bm == 128 && bn == 128) return launch_wgrad_shape<PipeF16, 128, 128>(p, tiles, st);
+    if (bm == 64 && bn == 128) return launch_wgrad_shape<PipeF16, 64, 128>(p, tiles, st);
+    if (bm == 256 && bn == 64) return launch_wgrad_shape<PipeF16, 256, 64>(p, tiles, st);
+    if (bm == 128 && bn == 64) return launch_wgrad_shape<PipeF16, 128, 64>(p, tiles, st);
+    if (bm == 64 && bn == 64) return launch_wgrad_shape<PipeF16, 64, 64>(p, tiles, st);
+    return hipErrorInvalidValue;
+}
+
+// The whole call for input element type T.
+template <class T>
+hipError_t launch_typed(const ConvPlan& plan, int mode, float alpha, float beta, unsigned rewrite, hipStream_t st)
+{
+    const ConvTables& t = plan.t;
+    const ConvGeom& g = t.g;
+    const dmath_dtype_t in = plan.in_dtype;
+    const int cp = round64(g.c), kp = round64(g.k);
+    FastConv p{};
+    p.g = g;
+    p.g.c = cp;
+    p.g.k = kp;
+    p.c_real = g.c;
+    p.k_real = g.k;
+    p.hp = g.h + 2 * g.pad_h;
+    p.wp = g.w + 2 * g.pad_w;
+    p.y_rows = t.y_rows;
+    p.f_rows = t.f_rows;
+    T* const xp = plan.xp ? static_cast<T*>(plan.xp->buf) : nullptr;
+    T* const fp = plan.fp ? static_cast<T*>(plan.fp->buf) : nullptr;
+    T* const yt = plan.yt ? static_cast<T*>(plan.yt->buf) : nullptr;
+    p.xp = xp;
+    p.fp = fp;
+    p.yt = yt;
+    p.ws = static_cast<float*>(t.workspace);
+    p.split = t.split_k;
+    if (!xp || (mode != CONV_BWD_FILTER && !fp) || (mode == CONV_BWD_FILTER && (!yt || !p.ws)))
+        return hipErrorInvalidValue;  // the plan was not made for this path
+
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = set_lds(to_channels_last_kernel<T, 16>, 150 * 1024);
+        if (e == hipSuccess) e = set_lds(to_channels_last_kernel<T, 8>, 150 * 1024);
+        if (e == hipSuccess) e = set_lds(to_channels_last_kernel<T, sizeof(T)>, 150 * 1024);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    if (mode == CONV_BWD_DATA) {
+        // forward convolution (stride 1) over dY with its pixels spread out by the stride: input
+        // channels k, padding r-1-pad in front, rotated filter, output channels c, output
+        // spatial h x w (so the copy has h+r-1 x w+s-1 pixels), output rows = images of dX
+        FastConv q = p;
+        const int pph = g.r - 1 - g.pad_h, ppw = g.s - 1 - g.pad_w;
+        q.g.c = kp; q.g.k = cp;
+        q.k_real = g.c;
+        q.g.h = g.oh; q.g.w = g.ow; q.g.oh = g.h; q.g.ow = g.w;
+        q.g.pad_h = pph; q.g.pad_w = ppw;
+        q.g.stride_h = q.g.stride_w = 1;
+        q.hp = g.h + g.r - 1;
+        q.wp = g.w + g.s - 1;
+        q.y_rows = t.x_rows;
+        if (rewrite & REWRITE_X)
+            to_channels_last<T>(t.y_rows, g.n, g.k, kp, g.oh, g.ow, pph, ppw, g.stride_h, g.stride_w, q.hp, q.wp, xp, st);
+        if (rewrite & REWRITE_F)
+            filter_to_rsk_rotated_kernel<T><<<512, 256, 0, st>>>(t.f_rows, g.c, g.r, g.s, g.k, kp, fp);
+        return launch_fwd(q, in, plan.tile_m, plan.tile_n, plan.out_dtype, alpha, beta, st);
+    }
+    // activations -> zero-bordered channels-last copy (borders were zeroed when the copy was allocated)
+    if (rewrite & REWRITE_X)
+        to_channels_last<T>(t.x_rows, g.n, g.c, cp, g.h, g.w, g.pad_h, g.pad_w, 1, 1, p.hp, p.wp, xp, st);
+    if (mode == CONV_FWD) {
+        if (rewrite & REWRITE_F) filter_to_rsc_kernel<T><<<512, 256, 0, st>>>(t.f_rows, g.c, cp, g.r * g.s, g.k, fp);
+        return launch_fwd(p, in, plan.tile_m, plan.tile_n, plan.out_dtype, alpha, beta, st);
+    }
+    // weight gradient: dY -> channels-last [m][k], split GEMM, fixed-order reduction
+    if (rewrite & REWRITE_Y) to_channels_last<T>(t.y_rows, g.n, g.k, kp, g.oh, g.ow, 0, 0, 1, 1, g.oh, g.ow, yt, st);
+    p.ktiles = (int)wgrad_ktiles(g, in);
+    p.ktiles_per_split = (p.ktiles + t.split_k - 1) / t.split_k;
+    if (!wgrad_split_ok(p.ktiles, t.split_k)) return hipErrorInvalidValue;  // a part without pixels
+    const int tiles = (int)wgrad_tiles(g, in) * t.split_k;
+    hipError_t e = launch_wgrad(p, in, wgrad_tile_m(g, in), wgrad_tile_n(g), tiles, st);
+    if (e != hipSuccess) return e;
+    if (plan.out_dtype == DMATH_F16)
+        conv_wgrad_reduce_kernel<_Float16><<<1024, 256, 0, st>>>(p, alpha, beta);
+    else
+        conv_wgrad_reduce_kernel<float><<<1024, 256, 0, st>>>(p, alpha, beta);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_conv_fast(const ConvPlan& plan, int mode, double alpha, double beta, unsigned rewrite,
+                            hipStream_t st)
+{
+    if (plan.in_dtype == DMATH_F16) return launch_typed<_Float16>(plan, mode, (float)alpha, (float)beta, rewrite, st);
+    if (plan.in_dtype == DMATH_F32) return launch_typed<float>(plan, mode, (float)alpha, (float)beta, rewrite, st);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace dm

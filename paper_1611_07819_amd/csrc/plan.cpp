@@ -499,13 +499,13 @@ size_t conv_choice_bytes(int mode, const ConvGeom& g, const ConvChoice& c, dmath
     const size_t sp_out = (size_t)g.oh * g.ow, crs = (size_t)g.c * g.r * g.s;
     size_t bytes = 0;
     if (c.kernel == 1 && mode == CONV_BWD_FILTER) {
-        const ConvF16Layout l = conv_f16_layout(mode, g);
+        const ConvFastLayout l = conv_fast_layout(mode, g, in_dtype);
         bytes += (size_t)c.split_k * l.kp * l.cp * g.r * g.s * 4;
     } else if (mode == CONV_BWD_FILTER && c.split_k > 1) {
         bytes += (size_t)c.split_k * g.k * crs * (in_dtype == DMATH_F64 ? 8 : 4);
     }
     if (c.kernel == 1) {
-        const ConvF16Layout l = conv_f16_layout(mode, g);
+        const ConvFastLayout l = conv_fast_layout(mode, g, in_dtype);
         bytes += (size_t)(l.x_bytes + l.f_bytes + l.y_bytes);
     }
     return bytes;
@@ -560,7 +560,7 @@ dmath_status_t make_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_
     void* ws = nullptr;
     // the specialised weight-gradient kernel always goes through the partial-sum workspace,
     // also with a single split
-    const ConvF16Layout lay = fast ? conv_f16_layout(mode, g) : ConvF16Layout{};
+    const ConvFastLayout lay = fast ? conv_fast_layout(mode, g, plan->in_dtype) : ConvFastLayout{};
     if (t.split_k > 1 || (fast && mode == CONV_BWD_FILTER)) {
         size_t acc = plan->in_dtype == DMATH_F64 ? 8 : 4;
         // the specialised kernel's partial sums have the padded extents of its copies

@@ -163,21 +163,21 @@ FAST_GEOMS = [
 
 
 @pytest.mark.parametrize("g", FAST_GEOMS)
-@pytest.mark.parametrize("out", [dm.F32, dm.F16])
-def test_specialised_fp16_conv_whole_result(ctx, oracle, g, out):
-    """Forward and weight gradient on the specialised path against the oracle: within the fp16
-    bar on random data (alpha/beta exercised) and bit for bit on small-integer data with a
-    row-blocked layout of every tensor."""
+@pytest.mark.parametrize("dt,out", [(dm.F16, dm.F32), (dm.F16, dm.F16), (dm.F32, dm.F32)])
+def test_specialised_conv_whole_result(ctx, oracle, g, dt, out):
+    """All three modes on the specialised path (fp16 and fp32 pipelines) against the oracle:
+    within the precision's bar on random data (alpha/beta exercised) and bit for bit on
+    small-integer data with a row-blocked layout of every tensor."""
     grids = {"X": (1, 1), "F": (1, 1), "Y": (1, 1)}
     before = ctx.relayout_stats()["written"]
-    res = three_modes(ctx, oracle, g, dm.F16, out, 1.5, -0.5, grids, policy=0)
+    res = three_modes(ctx, oracle, g, dt, out, 1.5, -0.5, grids, policy=0)
     # every mode went through the specialised kernels: each re-laid-out its two operands
     assert ctx.relayout_stats()["written"] - before == 6
     for mode in ("fwd", "bwd_filter", "bwd_data"):
         got, ref = res[mode]
-        assert rel_fro(got, ref) <= TOL[dm.F16], mode
-    d, t = tensors(g, dm.F16, 300, ints=True)
-    t = {k: np.sign(v).astype(np.float16) if k != "F" else v for k, v in t.items()}   # keep sums small
+        assert rel_fro(got, ref) <= TOL[dt], mode
+    d, t = tensors(g, dt, 300, ints=True)
+    t = {k: np.sign(v).astype(NP[dt]) if k != "F" else v for k, v in t.items()}   # keep sums small
     od = oracle.ConvDesc(**g)
     grids = {"X": (g["n"], 1), "F": (2, 1), "Y": (2, 1)}
     ctx.set_kernel_policy(0)
@@ -225,22 +225,22 @@ def test_repeated_calls_rewrite_the_channels_last_copy(ctx, oracle):
 @pytest.mark.parametrize("seed", range(8))
 def test_random_geometries_against_oracle(ctx, oracle, seed):
     """Seeded sweep over geometries (filter sizes 1..5, strides 1..3, pads up to the filter size
-    minus one, odd channel counts; two cases in four are fp16 geometries that the specialised
+    minus one, odd channel counts; two cases in four are geometries that the specialised
     kernels accept), row-blocked tensors, all three modes, small-integer data compared bit for
     bit."""
     r = np.random.default_rng(8000 + seed)
     ctx.set_kernel_policy(0)
     for case in range(4):
         if case == 3:
-            # fp16 with channel and filter counts just below multiples of 64, any plane size,
-            # strides and pads: the specialised kernels with padded copies and ragged tiles
+            # fp16 or fp32 with channel and filter counts just below multiples of 64, any plane
+            # size, strides and pads: the specialised kernels with padded copies and ragged tiles
             rr, ss = int(r.integers(1, 5)), int(r.integers(1, 5))
             g = dict(n=int(r.integers(1, 6)), c=int(r.integers(54, 65)) * int(r.integers(1, 3)),
                      h=int(r.integers(rr, rr + 12)), w=int(r.integers(ss, ss + 12)),
                      k=int(r.integers(54, 65)) * int(r.integers(1, 3)), r=rr, s=ss,
                      pad_h=int(r.integers(0, rr)), pad_w=int(r.integers(0, ss)),
                      stride_h=int(r.integers(1, 3)), stride_w=int(r.integers(1, 3)))
-            dt, out = dm.F16, [dm.F32, dm.F16][int(r.integers(0, 2))]
+            dt, out = [(dm.F16, dm.F32), (dm.F16, dm.F16), (dm.F32, dm.F32)][int(r.integers(0, 3))]
         elif case == 2:
             rr, ss = int(r.integers(1, 4)), int(r.integers(1, 4))
             hw = [(8, 8), (16, 8), (16, 16), (12, 12), (14, 14), (10, 10)][int(r.integers(0, 6))]
@@ -267,15 +267,15 @@ def test_random_geometries_against_oracle(ctx, oracle, seed):
 
 @pytest.mark.parametrize("g", [dict(n=3, c=128, h=14, w=14, k=256, r=3, s=3, pad_h=1, pad_w=1),
                                dict(n=5, c=256, h=12, w=6, k=128, r=1, s=1)])
-@pytest.mark.parametrize("out", [dm.F32, dm.F16])
-def test_specialised_fp16_conv_ragged_last_row_tile(ctx, oracle, g, out):
-    """n*oh*ow is not a multiple of the 256-row tile, nor of the weight gradient's 64-pixel tile:
+@pytest.mark.parametrize("dt,out", [(dm.F16, dm.F32), (dm.F16, dm.F16), (dm.F32, dm.F32)])
+def test_specialised_conv_ragged_last_row_tile(ctx, oracle, g, dt, out):
+    """n*oh*ow is not a multiple of the row tile, nor of the weight gradient's pixel tile:
     the last tile of the forward and of the data gradient is ragged (clamped gathers, masked
     stores), the weight gradient's last pixel tile reads zeros past the end.  Small-integer data,
     bit for bit."""
     grids = {"X": (g["n"], 1), "F": (2, 1), "Y": (1, 1)}
     before = ctx.relayout_stats()["written"]
-    res = three_modes(ctx, oracle, g, dm.F16, out, 1.0, 1.0, grids, ints=True, policy=0)
+    res = three_modes(ctx, oracle, g, dt, out, 1.0, 1.0, grids, ints=True, policy=0)
     assert ctx.relayout_stats()["written"] - before == 6       # every mode on the specialised kernels
     for mode, (got, ref) in res.items():
         if out == dm.F16 and np.abs(ref).max() > 2048:
