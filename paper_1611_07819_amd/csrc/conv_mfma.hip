@@ -115,21 +115,23 @@ __global__ __launch_bounds__(kTclThreads) void to_channels_last_kernel(const voi
     const int vec_per_plane = pixels / VEC;
     for (int e = threadIdx.x; e < 64 * vec_per_plane; e += kTclThreads) {
         const int c = e / vec_per_plane, v = e - c * vec_per_plane;
+        // planes past the last channel read plane 0 instead (unconditional loads) and store zeros
         const bool real = c < planes_here;
+        const T* from = src + (int64_t)(real ? c : 0) * hw + v * VEC;
         if (VEC == 1) {
-            planes[c * stride + v] = real ? src[(int64_t)c * hw + v] : (T)0.f;
+            const T d = *from;
+            planes[c * stride + v] = real ? d : (T)0.f;
             continue;
         }
         v2u* q = reinterpret_cast<v2u*>(planes + c * stride + v * VEC);  // rows are 8-byte aligned
+        const uint32_t keep = real ? ~0u : 0u;
         if (VB == 16) {
-            v4u d = {0u, 0u, 0u, 0u};
-            if (real) d = *reinterpret_cast<const v4u*>(src + (int64_t)c * hw + v * VEC);
-            q[0] = v2u{d[0], d[1]};
-            q[1] = v2u{d[2], d[3]};
+            const v4u d = *reinterpret_cast<const v4u*>(from);
+            q[0] = v2u{d[0] & keep, d[1] & keep};
+            q[1] = v2u{d[2] & keep, d[3] & keep};
         } else {
-            v2u d = {0u, 0u};
-            if (real) d = *reinterpret_cast<const v2u*>(src + (int64_t)c * hw + v * VEC);
-            q[0] = d;
+            const v2u d = *reinterpret_cast<const v2u*>(from);
+            q[0] = v2u{d[0] & keep, d[1] & keep};
         }
     }
     __syncthreads();
@@ -350,16 +352,26 @@ template <class P, int BM, int BN> struct WgradWalk {
     static constexpr int BK = P::BK;
     const char *abase, *bbase;
     uint32_t aoff[TA::kInstr], boff[TB::kInstr];
-    // pixel (n, oy, ox) fetched by this lane for each B segment, and the geometry to step it
-    int pn[TB::kInstr], py[TB::kInstr], px[TB::kInstr], chunk16[TB::kInstr];
-    int oh, ow, hp, wp, c, d_oy, d_ox, sh, sw;
+    // pixel (oy, ox) of its image fetched by this lane for each B segment; stepping it by one
+    // k-tile moves the byte offset by sums of four constants (all arithmetic modulo 2^32: the
+    // copy is smaller than 4 GiB, so the true offset is what remains)
+    int py[TB::kInstr], px[TB::kInstr];
+    int oh, ow, d_oy, d_ox;
+    uint32_t step_bytes, wrap_x_bytes, wrap_y_bytes;
     int64_t astep;
 
     __device__ __forceinline__ WgradWalk(const FastConv& p, int k0_pixels, int m0_filters, int n0_cols, int wave,
                                          int lane)
     {
-        oh = p.g.oh; ow = p.g.ow; hp = p.hp; wp = p.wp; c = p.g.c; sh = p.g.stride_h; sw = p.g.stride_w;
+        const int hp = p.hp, wp = p.wp, c = p.g.c;
+        oh = p.g.oh; ow = p.g.ow;
         d_oy = BK / ow; d_ox = BK % ow;
+        const uint32_t col_bytes = (uint32_t)(p.g.stride_w * c * (int)sizeof(T));   // ox + 1
+        const uint32_t row_bytes = (uint32_t)p.g.stride_h * wp * c * sizeof(T);     // oy + 1
+        const uint32_t img_bytes = (uint32_t)hp * wp * c * sizeof(T);               // n + 1
+        step_bytes = d_oy * row_bytes + d_ox * col_bytes;
+        wrap_x_bytes = row_bytes - ow * col_bytes;
+        wrap_y_bytes = img_bytes - oh * row_bytes;
         // A' = Yt[m][k]: dense, m/n (= k_out) unit-stride, filters m0 .. m0+BM of the tile
         TA::offsets(p.g.k, m0_filters, BM, wave, lane, aoff);
         astep = TA::step(p.g.k);
@@ -373,19 +385,11 @@ template <class P, int BM, int BN> struct WgradWalk {
             int row, chunk;
             TB::lane_slot(q, wave, lane, row, chunk);
             const int m = k0_pixels + row;
-            pn[q] = m / sp_out;
-            const int sp = m % sp_out;
+            const int pn = m / sp_out, sp = m % sp_out;
             py[q] = sp / ow;
             px[q] = sp % ow;
-            chunk16[q] = chunk * 16;
+            boff[q] = pn * img_bytes + py[q] * row_bytes + px[q] * col_bytes + chunk * 16;
         }
-        set_boff();
-    }
-    __device__ __forceinline__ void set_boff()
-    {
-#pragma unroll
-        for (int q = 0; q < TB::kInstr; ++q)
-            boff[q] = (uint32_t)((((int64_t)pn[q] * hp + py[q] * sh) * wp + px[q] * sw) * c * sizeof(T)) + chunk16[q];
     }
     __device__ __forceinline__ void advance()
     {
@@ -394,10 +398,13 @@ template <class P, int BM, int BN> struct WgradWalk {
         for (int q = 0; q < TB::kInstr; ++q) {  // pixel index += BK
             px[q] += d_ox;
             py[q] += d_oy;
-            if (px[q] >= ow) { px[q] -= ow; ++py[q]; }
-            while (py[q] >= oh) { py[q] -= oh; ++pn[q]; }  // planes of fewer than BK pixels: several images
+            boff[q] += step_bytes;
+            if (px[q] >= ow) { px[q] -= ow; ++py[q]; boff[q] += wrap_x_bytes; }
+            // a k-tile spans at most three image boundaries (conv_fast_ok: BK / ow < 3 * oh)
+            if (py[q] >= oh) { py[q] -= oh; boff[q] += wrap_y_bytes; }
+            if (py[q] >= oh) { py[q] -= oh; boff[q] += wrap_y_bytes; }
+            if (py[q] >= oh) { py[q] -= oh; boff[q] += wrap_y_bytes; }
         }
-        set_boff();
     }
 };
 
@@ -504,8 +511,9 @@ ConvFastLayout conv_fast_layout(int mode, const ConvGeom& g, dmath_dtype_t dt)
 // fp32, every copy below 4 GiB (32-bit lane offsets), at most four times the work from rounding
 // the channel and filter counts up to multiples of 64 (the matrix pipeline is more than ten
 // times faster than the generic kernel in fp16, three to four times in fp32: there the limit is
-// twice the work), and for the data gradient (a forward convolution of dY with padding r-1-pad)
-// a padding that does not exceed the filter.
+// twice the work), for the data gradient (a forward convolution of dY with padding r-1-pad)
+// a padding that does not exceed the filter, and for the weight gradient output planes that are
+// not tiny (4x4 and less in fp16).
 bool conv_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype)
 {
     if (in_dtype != DMATH_F16 && in_dtype != DMATH_F32) return false;
@@ -515,6 +523,8 @@ bool conv_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype)
     if ((int64_t)g.n * g.oh * g.ow >= (1ll << 31) - 256 || (int64_t)g.n * g.h * g.w >= (1ll << 31) - 256) return false;
     if ((int64_t)l.cp * l.kp > (int64_t)g.c * g.k * (in_dtype == DMATH_F16 ? 4 : 2)) return false;
     if (mode == CONV_BWD_DATA) return g.pad_h <= g.r - 1 && g.pad_w <= g.s - 1;
+    // the weight gradient steps its pixel index by one k-tile with three conditional wraps
+    if (mode == CONV_BWD_FILTER) return pixel_tile(in_dtype) / g.ow < 3 * g.oh;
     return true;
 }
 
@@ -553,23 +563,26 @@ static int per_cu(int bm, int bn, dmath_dtype_t dt)
 
 // Split count for the weight gradient: the number of parts s (each of ceil(k-tiles / s) pixel
 // tiles, the last one possibly shorter) with at most one round of workgroups that minimises
-// (k-tiles per part + s), both counted in 64-pixel units: the parts shorten with s, the partial
-// sums written and read back grow with it (the balance point sqrt(k-tiles) matches the timing
-// samples on 1x1 and 3x3 layers of 14x14 and 28x28 pixels).
+// (w x 64-pixel steps of the busiest CU + s): the parts shorten with s, the partial sums written
+// and read back grow with it.  w = 1 in fp16 (the balance point sqrt(k-tiles) matches the timing
+// samples on 1x1 and 3x3 layers of 14x14 and 28x28 pixels), 4 in fp32, whose steps take four
+// times as long; an fp32 CU with a single workgroup runs at 0.87 of the rate (as in choose_conv).
 int conv_fast_wgrad_split(const ConvGeom& g, dmath_dtype_t dt)
 {
     const int64_t ktiles = wgrad_ktiles(g, dt);
     const int64_t tiles = wgrad_tiles(g, dt);
     const int unit = 64 / pixel_tile(dt);  // k-tiles per 64 pixels
     const int slots = 256 * per_cu(wgrad_tile_m(g, dt), wgrad_tile_n(g), dt);
+    const double w = dt == DMATH_F16 ? 1 : 4;
+    auto cost = [&](int s) {
+        const int64_t per = (ktiles + s - 1) / s, on_cu = (tiles * s + 255) / 256;
+        const double rate = (dt == DMATH_F32 && on_cu == 1) ? 0.87 : 1.0;
+        return on_cu * (double)(per / unit) * w / rate + s;
+    };
     int best = 1;
-    int64_t best_cost = ktiles / unit + 1;
     for (int s = 2; s <= 64; ++s) {
         const int64_t per = (ktiles + s - 1) / s;
-        if (wgrad_split_ok(ktiles, s) && tiles * s <= slots && per >= 8 * unit && per / unit + s < best_cost) {
-            best_cost = per / unit + s;
-            best = s;
-        }
+        if (wgrad_split_ok(ktiles, s) && tiles * s <= slots && per >= 8 * unit && cost(s) < cost(best)) best = s;
     }
     return best;
 }
@@ -624,7 +637,8 @@ ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int3
     // bytes per cycle and CU, + the tile's stores at 10 bytes per cycle and CU).  fp16, 50176
     // pixels x 256 channels: 224 tiles of 224x256 are one round, against 196 of 256x256 or two
     // rounds of 256x128; 64-wide tiles are load-bound and win only where they save whole
-    // rounds.  A narrower tile has to win by 3 %.
+    // rounds.  A narrower tile has to win by 3 %.  fp32: with one workgroup per CU (128x128) the
+    // gathers are hidden less well than with two (128x64): 0.87 of the rate in the samples.
     const int64_t k_depth = (int64_t)g.r * g.s * round64(mode == CONV_FWD ? g.c : g.k);
     const int eb = elem_bytes(in_dtype);
     const double mfma_per_k = in_dtype == DMATH_F16 ? 32.5 / 16 : 64.0 / 2;  // cycles per unit of k and 32x32 block
@@ -635,7 +649,8 @@ ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int3
         const int64_t chain = (tiles + 256 * slots - 1) / (256 * slots) * slots;  // tiles the busiest CU runs
         const double area = (double)sh.bm * sh.bn;
         const double per_k = std::max(area / 1024 * mfma_per_k / 4, (sh.bm + sh.bn) * eb / 60.0);
-        const double cost = (double)chain * (k_depth * per_k + 0.4 * area);
+        const double rate = (in_dtype == DMATH_F32 && slots == 1) ? 0.87 : 1.0;
+        const double cost = (double)chain * (k_depth * per_k / rate + 0.4 * area);
         if (best < 0 || cost < 0.97 * best) {
             best = cost;
             ch.tile_m = sh.bm;
