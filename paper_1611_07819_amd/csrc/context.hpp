@@ -90,11 +90,11 @@ struct ConvPlan {
     ConvTables t{};
     void* dev_tables = nullptr;
     void* workspace = nullptr;
-    // specialised fp16 path: the copies it reads (owned by the context's table of re-layouts)
+    // specialised (MFMA pipeline) path: the copies it reads (owned by the context's table of re-layouts)
     Relayout* xp = nullptr;  // gathered activations, channels-last with zero border
     Relayout* fp = nullptr;  // permuted filter
     Relayout* yt = nullptr;  // weight gradient: dY channels-last, [n*oh*ow][k]
-    int32_t kernel = 0;  // 0 generic, 1 specialised fp16
+    int32_t kernel = 0;  // 0 generic, 1 specialised (fp16 or fp32 MFMA pipeline)
     int32_t tile_n = 0;  // specialised forward / data gradient: 128 or 256 output channels per tile
     int32_t tile_m = 0;  //   and 256 or 224 pixels
     dmath_dtype_t in_dtype = DMATH_F16, out_dtype = DMATH_F32;

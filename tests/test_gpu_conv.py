@@ -135,7 +135,7 @@ def _config5(ctx, oracle, w, images, filters):
 
 
 FAST_GEOMS = [
-    # geometries that run on the specialised fp16 kernels
+    # geometries that run on the specialised kernels
     dict(n=4, c=128, h=16, w=16, k=256, r=3, s=3, pad_h=1, pad_w=1),
     dict(n=8, c=128, h=16, w=8, k=256, r=1, s=1),
     dict(n=2, c=256, h=16, w=16, k=256, r=5, s=3, pad_h=2, pad_w=1),

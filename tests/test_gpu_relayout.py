@@ -11,7 +11,7 @@ from gpu_util import TOL, rel_fro
 
 pytestmark = pytest.mark.gpu
 
-GEO = dict(n=4, c=128, h=16, w=16, k=256, r=3, s=3, pad_h=1, pad_w=1)   # specialised fp16 path
+GEO = dict(n=4, c=128, h=16, w=16, k=256, r=3, s=3, pad_h=1, pad_w=1)   # specialised path
 
 
 @pytest.fixture()
