@@ -65,6 +65,11 @@ struct GemmPlan {
     // the reduction / beta-only kernel may move 16 bytes per lane: every n-segment a multiple of
     // 4, every C panel and the workspace rows 16-byte aligned
     bool reduce_vectors = false;
+    // k-segments that are not multiples of the kernel's k-tile: their last elements are copied
+    // into zero-padded scratch panels (which the panel tables point to) before every launch
+    const CopyCell* tail_cells = nullptr;
+    int32_t n_tail_cells = 0, tail_rows = 0;
+    void* tail_scratch = nullptr;
 };
 
 enum ConvMode : int32_t { CONV_FWD = 0, CONV_BWD_FILTER = 1, CONV_BWD_DATA = 2 };

@@ -201,6 +201,10 @@ hipError_t launch_gemm(const GemmPlan& p, double alpha, double beta, hipStream_t
 {
     if (alpha == 0.0) return launch_gemm_reduce(p, 0, 0.0, beta, st);
     hipError_t e;
+    if (p.n_tail_cells) {  // refresh the zero-padded copies of the k-tails
+        e = launch_reblock(p.in_dtype, p.in_dtype, p.tail_cells, p.n_tail_cells, p.tail_rows, false, st);
+        if (e != hipSuccess) return e;
+    }
     switch (p.info.kernel) {
     case KERNEL_F32_128: e = launch_gemm_f32(p, alpha, beta, st); break;
     case KERNEL_F64_128: e = launch_gemm_f64(p, alpha, beta, st); break;

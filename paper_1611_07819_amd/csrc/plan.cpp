@@ -212,7 +212,9 @@ void free_gemm_plan(dmath_ctx_s* ctx, GemmPlan& p)
 {
     if (p.dev_tables) ctx->pool.free(p.dev_tables);
     if (p.workspace) ctx->pool.free(p.workspace);
-    p.dev_tables = p.workspace = nullptr;
+    if (p.tail_scratch) ctx->pool.free(p.tail_scratch);
+    p.dev_tables = p.workspace = p.tail_scratch = nullptr;
+    p.n_tail_cells = 0;
 }
 
 dmath_status_t get_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_matrix_s* A,
@@ -238,6 +240,10 @@ dmath_status_t get_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_mat
     // memory decides, as in the paper's choice of algorithm under memory constraints, section 4.1)
     if (st == DMATH_ERR_OOM)
         st = make_gemm_plan(ctx, transA, transB, A, B, C, do_upload, forced, &plan, nullptr, true);
+    if (st == DMATH_ERR_OOM) {  // nor the scratch panels of the k-tails: the generic kernel needs none
+        const GemmChoice frugal;  // generic kernel, unsplit
+        st = make_gemm_plan(ctx, transA, transB, A, B, C, do_upload, &frugal, &plan, nullptr, true);
+    }
     if (st != DMATH_OK) return st;
     *out = plan.get();
     ctx->gemm_plans[key] = std::move(plan);
@@ -277,10 +283,18 @@ dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_ma
     for (auto& m : ms)
         for (auto& n : ns) al = al && aligned(locate(C, m.start, n.start), elem_size(C->dtype));
 
+    // k-segments that are not multiples of the specialised kernels' k-tile: those kernels can
+    // still run when the last (len % bk) of such a segment is copied, before every launch, into
+    // a zero-padded scratch panel of bk.  The chooser sees the lengths rounded up.
+    const int64_t bk = A->dtype == DMATH_F16 ? 64 : A->dtype == DMATH_F32 ? 32 : 16;
+    bool k_tails = false;
+    for (auto& s : ks) k_tails = k_tails || s.len % bk != 0;
+    const bool pad_tails = k_tails && K >= 4 * bk;
+
     std::vector<int64_t> mlen, nlen, klen;
     for (auto& s : ms) mlen.push_back(s.len);
     for (auto& s : ns) nlen.push_back(s.len);
-    for (auto& s : ks) klen.push_back(s.len);
+    for (auto& s : ks) klen.push_back(pad_tails ? (s.len + bk - 1) / bk * bk : s.len);
     bool small = true;  // the specialised kernels address a block through 32-bit byte offsets
     for (const dmath_matrix_s* m : {A, B})
         small = small && (uint64_t)m->rsplit.step * (uint64_t)m->csplit.step * elem_size(m->dtype) < (1ull << 32);
@@ -300,21 +314,87 @@ dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_ma
         ch.split_k = (int32_t)split_cuts.size() + 1;
         ks = refine(K, {&a_k, &b_k}, split_cuts);
     }
+    // cut the tails off: afterwards a segment is a multiple of bk or shorter than bk (a tail)
+    const bool tails = pad_tails && ch.kernel != KERNEL_GENERIC;
+    if (tails) {
+        std::vector<int64_t> cuts = split_cuts;
+        for (auto& k : ks)
+            if (k.len % bk != 0 && k.len > bk) cuts.push_back(k.start + k.len - k.len % bk);
+        ks = refine(K, {&a_k, &b_k}, cuts);
+    }
     std::vector<int32_t> ksplit{0};
     for (int64_t c : split_cuts)
         for (size_t i = 0; i < ks.size(); ++i)
             if (ks[i].start == c) ksplit.push_back((int32_t)i);
     ksplit.push_back((int32_t)ks.size());
 
+    // scratch panels of the tails, in the operand's own orientation: [M][bk] (k unit-stride) or
+    // [bk][M rounded up to 64]; zeroed once here, their first (len) k written before every launch
+    const int64_t Mp = (M + 63) / 64 * 64, Np = (N + 63) / 64 * 64;
+    const int64_t a_tail = (transA ? Mp : M) * bk, b_tail = (transB ? N : Np) * bk;  // elements per tail
+    size_t n_tails = 0;
+    for (auto& k : ks) n_tails += tails && k.len % bk != 0;
+    char* scratch = nullptr;
+    if (n_tails && do_upload) {
+        const size_t bytes = n_tails * (size_t)(a_tail + b_tail) * es;
+        scratch = static_cast<char*>(ctx->pool.alloc(bytes));
+        if (!scratch) return DMATH_ERR_OOM;
+        if (hipMemsetAsync(scratch, 0, bytes, ctx->stream) != hipSuccess) {
+            ctx->pool.free(scratch);
+            return DMATH_ERR_DEVICE;
+        }
+    }
     std::vector<Panel> pa, pb, pc;
-    for (auto& m : ms)
-        for (auto& k : ks) pa.push_back(panel_a(m, k));
-    for (auto& k : ks)
-        for (auto& n : ns) pb.push_back(panel_b(k, n));
+    std::vector<CopyCell> tail_cells;
+    int32_t tail_rows = 0;
+    {
+        std::vector<const char*> as(ks.size(), nullptr), bs(ks.size(), nullptr);
+        size_t t = 0;
+        for (size_t i = 0; i < ks.size(); ++i)
+            if (tails && ks[i].len % bk != 0 && scratch) {
+                as[i] = scratch + t * (size_t)(a_tail + b_tail) * es;
+                bs[i] = as[i] + a_tail * es;
+                ++t;
+            }
+        // one workgroup copies 16 rows of a cell: wide cells (few k rows x many columns) are cut
+        // into runs of 256 columns so that the copy spreads over the chip
+        auto cell = [&](const Panel& src, const char* dst, int64_t dst_ld, int64_t rows, int64_t cols) {
+            for (int64_t c0 = 0; c0 < cols; c0 += 256)
+                tail_cells.push_back({static_cast<const char*>(src.ptr) + c0 * es, const_cast<char*>(dst) + c0 * es,
+                                      src.ld, dst_ld, (int32_t)rows, (int32_t)std::min<int64_t>(256, cols - c0)});
+            tail_rows = std::max(tail_rows, (int32_t)rows);
+        };
+        for (auto& m : ms)
+            for (size_t i = 0; i < ks.size(); ++i) {
+                const Seg& k = ks[i];
+                if (!as[i]) {
+                    pa.push_back(panel_a(m, k));
+                } else if (transA) {  // stored [k][m]
+                    pa.push_back({as[i] + m.start * es, Mp});
+                    cell(panel_a(m, k), as[i] + m.start * es, Mp, k.len, m.len);
+                } else {
+                    pa.push_back({as[i] + m.start * bk * es, bk});
+                    cell(panel_a(m, k), as[i] + m.start * bk * es, bk, m.len, k.len);
+                }
+            }
+        for (size_t i = 0; i < ks.size(); ++i)
+            for (auto& n : ns) {
+                const Seg& k = ks[i];
+                if (!bs[i]) {
+                    pb.push_back(panel_b(k, n));
+                } else if (transB) {  // stored [n][k]
+                    pb.push_back({bs[i] + n.start * bk * es, bk});
+                    cell(panel_b(k, n), bs[i] + n.start * bk * es, bk, n.len, k.len);
+                } else {
+                    pb.push_back({bs[i] + n.start * es, Np});
+                    cell(panel_b(k, n), bs[i] + n.start * es, Np, k.len, n.len);
+                }
+            }
+    }
     for (auto& m : ms)
         for (auto& n : ns) pc.push_back(locate(C, m.start, n.start));
     std::vector<int32_t> kl;
-    for (auto& k : ks) kl.push_back((int32_t)k.len);
+    for (auto& k : ks) kl.push_back((int32_t)(tails ? (k.len + bk - 1) / bk * bk : k.len));
 
     // Tiles of all cells form one global grid (every cell of a segment row has the same m
     // cuts, every cell of a segment column the same n cuts).  Logical order: super-blocks of
@@ -411,21 +491,31 @@ dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_ma
         std::vector<char> buf;
         size_t oa = append(buf, pa), ob = append(buf, pb), oc = append(buf, pc);
         size_t ok = append(buf, kl), os = append(buf, ksplit), ot = append(buf, tiles);
+        size_t otc = append(buf, tail_cells);
+        plan->tail_scratch = scratch;  // from here on the plan owns it
         void* dev = ctx->pool.alloc(buf.size());
-        if (!dev) return DMATH_ERR_OOM;
+        if (!dev) {
+            free_gemm_plan(ctx, *plan);
+            return DMATH_ERR_OOM;
+        }
         void* ws = nullptr;
         if (info.workspace_bytes) {
             ws = ctx->pool.alloc(info.workspace_bytes);
             if (!ws) {
                 ctx->pool.free(dev);
+                free_gemm_plan(ctx, *plan);
                 return DMATH_ERR_OOM;
             }
         }
         if (upload(ctx, dev, buf) != hipSuccess) {
             ctx->pool.free(dev);
             if (ws) ctx->pool.free(ws);
+            free_gemm_plan(ctx, *plan);
             return DMATH_ERR_DEVICE;
         }
+        plan->tail_cells = reinterpret_cast<const CopyCell*>(static_cast<char*>(dev) + otc);
+        plan->n_tail_cells = (int32_t)tail_cells.size();
+        plan->tail_rows = tail_rows;
         char* d = static_cast<char*>(dev);
         t.a = reinterpret_cast<const Panel*>(d + oa);
         t.b = reinterpret_cast<const Panel*>(d + ob);

@@ -251,6 +251,16 @@ FAST_CASES = [
     (dm.F16, (512, 256, 128), ((1, 2), (2, 1), (1, 1))),
     (dm.F64, (128, 128, 16), ((1, 1), (1, 1), (1, 1))),
     (dm.F64, (256, 128, 32), ((1, 2), (2, 1), (1, 1))),
+    # K (or the K of a block) not a multiple of the kernel's k-step: the last elements of such a
+    # segment go through zero-padded scratch panels (1000 output classes, 784 input pixels)
+    (dm.F32, (256, 384, 1000), ((1, 1), (1, 1), (1, 1))),
+    (dm.F32, (384, 256, 784), ((2, 2), (2, 2), (2, 2))),
+    (dm.F32, (200, 300, 1000), ((1, 1), (1, 1), (1, 1))),
+    (dm.F16, (256, 256, 1000), ((1, 1), (1, 1), (1, 1))),
+    (dm.F16, (512, 256, 784), ((2, 1), (1, 2), (2, 2))),
+    (dm.F16, (200, 296, 1000), ((1, 1), (1, 1), (1, 1))),
+    (dm.F64, (256, 128, 200), ((1, 1), (1, 1), (1, 1))),
+    (dm.F64, (128, 256, 1000), ((2, 1), (1, 2), (1, 1))),
 ]
 
 
