@@ -131,3 +131,42 @@ def test_replay_with_workspaces_split_k_and_weight_gradient(ctx, oracle):
         step()
         assert np.array_equal(dC.get(), got_c) and np.array_equal(dF.get(), got_f)
     ctx.pipeline_destroy(pid)
+
+
+def test_replay_refreshes_the_padded_k_tails(ctx, oracle):
+    """A GEMM whose K is not a multiple of the kernel's k-step reads the end of K from scratch
+    panels that a copy kernel refreshes before the GEMM kernel; that copy is part of the
+    recorded sequence, so a replay on new operands must see their last columns (integer data,
+    bit for bit; fp32 forward and the fp32 convolution path beside it)."""
+    r = np.random.default_rng(802)
+    M, N, K = 256, 384, 1000
+    A = r.integers(-2, 3, (M, K)).astype(np.float32)
+    B = r.integers(-2, 3, (K, N)).astype(np.float32)
+    dA, dB, dC = ctx.from_host(A), ctx.from_host(B), ctx.matrix(M, N, (1, 1), dm.F32)
+    assert dm.gemm_plan_info(ctx, 0, 0, dA, dB, dC)["kernel"] != 0
+    geo = dict(n=4, c=64, h=12, w=12, k=64, r=3, s=3, pad_h=1, pad_w=1)
+    cd, od = dm.ConvDesc(**geo), oracle.ConvDesc(**geo)
+    hx = r.integers(-1, 2, (4, 64 * 144)).astype(np.float32)
+    hf = r.integers(-1, 2, (64, 64 * 9)).astype(np.float32)
+    dX, dF, dY = ctx.from_host(hx), ctx.from_host(hf), ctx.matrix(4, 64 * 144, (1, 1), dm.F32)
+
+    def step():
+        dm.gemm(ctx, 0, 0, 1.0, dA, dB, 0.0, dC)
+        dm.conv_fwd(ctx, cd, 1.0, dX, dF, 0.0, dY)
+
+    step()
+    ctx.pipeline_begin()
+    step()
+    pid = ctx.pipeline_end()
+    for rep in range(3):
+        A2 = A.copy()
+        A2[:, K - 8:] = r.integers(-2, 3, (M, 8))          # only the tail of K changes
+        B2 = B.copy()
+        B2[K - 8:, :] = r.integers(-2, 3, (8, N))
+        x2 = r.integers(-1, 2, hx.shape).astype(np.float32)
+        dA.set(A2); dB.set(B2); dX.set(x2)
+        dC.set(np.full((M, N), np.nan, np.float32))
+        ctx.pipeline_replay(pid)
+        assert np.array_equal(dC.get().astype(np.float64), oracle.gemm(False, False, 1.0, A2, B2, 0.0))
+        assert np.array_equal(dY.get().astype(np.float64), oracle.conv_fwd(od, 1.0, x2, hf))
+    ctx.pipeline_destroy(pid)
