@@ -105,7 +105,7 @@ int32_t generic_split(const SegView& v)
 // The cost model.  Time of a (shape, split) pair =
 //     workgroups on the busiest CU x work of one workgroup / (CU rate x shape efficiency x occupancy)
 //   + the reduction kernel (launch + reading the partial sums and writing C) when split > 1,
-// with the practical per-CU rates measured on configurations 2-4, occupancy 0.8 when an fp32 /
+// with the practical per-CU rates measured on configurations 2-4, occupancy 0.9 (fp32) or 0.8 (fp64) when an fp32 /
 // fp64 shape that wants two workgroups per CU gets only one, ragged tiles counted as whole ones.
 // Checked against timing samples on 30 shapes per precision: within 10 % of the best sample.
 double modelled_seconds(const SegView& v, const Shape& s, int32_t split)
@@ -115,9 +115,13 @@ double modelled_seconds(const SegView& v, const Shape& s, int32_t split)
     // workgroups are dispatched in rounds that fill every slot of the chip (per_cu per CU)
     const int64_t slots = (int64_t)kCUs * s.per_cu;
     const int64_t busiest = wgs <= kCUs ? 1 : (wgs + slots - 1) / slots * s.per_cu;
-    const double occupancy = s.kernel != KERNEL_F16_256 && s.per_cu > 1 && busiest < s.per_cu ? 0.8 : 1.0;
+    const double alone = s.kernel == KERNEL_F32_128 ? 0.9 : 0.8;  // a CU with one workgroup of a shape that fits two
+    const double occupancy = s.kernel != KERNEL_F16_256 && s.per_cu > 1 && busiest < s.per_cu ? alone : 1.0;
     const double wg_flops = 2.0 * s.bm * s.bn * ((double)v.K / split);
-    double t = busiest * wg_flops / (cu_flops * s.efficiency * occupancy);
+    // + what a workgroup spends outside its k-loop (filling the load ring, storing its tile),
+    // which the workgroups that share a CU overlap
+    const int64_t rounds = (busiest + s.per_cu - 1) / s.per_cu;
+    double t = busiest * wg_flops / (cu_flops * s.efficiency * occupancy) + rounds * 1.5e-6;
     if (split > 1) {
         const double acc_bytes = v.in_dtype == DMATH_F64 ? 8 : 4;
         t += 3e-6 + (split + 1.0) * v.M * v.N * acc_bytes / 3e12;
@@ -125,14 +129,14 @@ double modelled_seconds(const SegView& v, const Shape& s, int32_t split)
     return t;
 }
 
-// Splits are powers of two that leave at least 512 of K per part; a split has to be 3 % better
+// Splits are powers of two that leave at least 128 of K per part; a split has to be 3 % better
 // than the one before to pay for its workspace.
 int32_t best_split(const SegView& v, const Shape& s, double* seconds)
 {
     int32_t best = 1;
     double best_t = modelled_seconds(v, s, 1);
     for (int32_t sp = 2; sp <= 32; sp *= 2) {
-        if (v.K / sp < 512) break;
+        if (v.K / sp < 128) break;
         const double t = modelled_seconds(v, s, sp);
         if (t < best_t * 0.97) {
             best_t = t;
@@ -169,7 +173,7 @@ GemmChoice choose_gemm(const SegView& v)
 }
 
 // Every configuration worth a timing sample: each shape unsplit, with the cost model's split,
-// and with the power-of-two splits that keep at least 512 of K per part and at most two rounds
+// and with the power-of-two splits that keep at least 128 of K per part and at most two rounds
 // of workgroups; the generic kernel unsplit and with its own split.
 std::vector<GemmChoice> gemm_candidates(const SegView& v)
 {
@@ -190,7 +194,7 @@ std::vector<GemmChoice> gemm_candidates(const SegView& v)
         add(s.kernel, s.bm, s.bn, s.bk, 1);
         add(s.kernel, s.bm, s.bn, s.bk, best_split(v, s, nullptr));
         for (int32_t sp = 2; sp <= 32; sp *= 2)
-            if (v.K / sp >= 512 && tiles * sp <= 2 * kCUs) add(s.kernel, s.bm, s.bn, s.bk, sp);
+            if (v.K / sp >= 128 && tiles * sp <= 2 * kCUs) add(s.kernel, s.bm, s.bn, s.bk, sp);
     }
     add(KERNEL_GENERIC, 64, 64, 16, 1);
     add(KERNEL_GENERIC, 64, 64, 16, generic_split(v));
