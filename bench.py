@@ -190,9 +190,36 @@ def main():
             ms, _ = time_calls([step5], 10, 3)
             calls[f"cfg5.{name}"] = {"ms": round(ms, 4), "tflops": round(3 * fl5 / ms / 1e9, 2),
                                      "frac_peak": round(3 * fl5 / ms / 1e9 / PEAK_TFLOPS["f16"], 4)}
+        ctx.set_relayout_reuse(False)
+        for m in d5.values():
+            m.destroy()
+        # the same layer in fp32 (fp32 MFMA pipeline), per call, copies rewritten every call
+        d5 = {k: ctx.from_host(v.astype(np.float32)) for k, v in w5.mats.items()}
+        d5["dX"] = ctx.matrix(d5["X"].rows, d5["X"].cols, (1, 1), dm.F32)
+        for name, f in [("fwd", lambda: dm.conv_fwd(ctx, desc, 1.0, d5["X"], d5["F"], 0.0, d5["Y"])),
+                        ("bwd_filter", lambda: dm.conv_bwd_filter(ctx, desc, 1.0, d5["X"], d5["dY"], 0.0, d5["dF"])),
+                        ("bwd_data", lambda: dm.conv_bwd_data(ctx, desc, 1.0, d5["dY"], d5["F"], 0.0, d5["dX"]))]:
+            ms, _ = time_calls([f], 10, 3)
+            calls[f"cfg5_as_f32.{name}"] = {"ms": round(ms, 4), "tflops": round(fl5 / ms / 1e9, 2),
+                                            "frac_peak": round(fl5 / ms / 1e9 / PEAK_TFLOPS["f32"], 4)}
         ctx.set_relayout_reuse(True)
         for m in d5.values():
             m.destroy()
+        # K that is not a multiple of the kernels' k-step: data gradient of a 4096 -> 1000 layer at
+        # batch 1024 (K = 1000 goes through zero-padded scratch panels)
+        for tag, code, npdt in (("f32", dm.F32, np.float32), ("f16", dm.F16, np.float16)):
+            M, N, K = 1024, 4096, 1000
+            sa = ctx.from_host(rs.normal(0, 0.1, (M, K)).astype(npdt))
+            sb = ctx.from_host(rs.normal(0, 0.02, (N, K)).astype(npdt))
+            sc = ctx.matrix(M, N, (1, 1), dm.F32)
+            ms, _ = time_calls([lambda: dm.gemm(ctx, 0, 1, 1.0, sa, sb, 0.0, sc)], 20, 5)
+            pinfo = dm.gemm_plan_info(ctx, 0, 1, sa, sb, sc)
+            calls[f"ktail_{tag}.dX_nt_M{M}_N{N}_K{K}"] = {
+                "ms": round(ms, 4), "tflops": round(2.0 * M * N * K / ms / 1e9, 2),
+                "frac_peak": round(2.0 * M * N * K / ms / 1e9 / PEAK_TFLOPS[tag], 4),
+                "kernel": pinfo["kernel"], "tile": [pinfo["tile_m"], pinfo["tile_n"], pinfo["split_k"]]}
+            for m in (sa, sb, sc):
+                m.destroy()
 
     # ---------------- MFMA-only probe: what the matrix cores sustain at their clocks under load
     sustained = {}
