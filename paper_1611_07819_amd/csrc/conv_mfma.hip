@@ -594,7 +594,7 @@ static int32_t generic_wgrad_split(const ConvGeom& g)
     const int64_t tiles = ((M + 63) / 64) * ((N + 63) / 64);
     const int64_t want = std::max<int64_t>(1, 1024 / std::max<int64_t>(1, tiles));
     const int64_t max_by_k = std::max<int64_t>(1, K / 512);
-    return (int32_t)std::min<int64_t>({want, max_by_k, 64});
+    return (int32_t)std::min<int64_t>({want, max_by_k, 512});  // first layers: 3 tiles, K of 800 thousand
 }
 
 // Tile shapes of the forward kernel (also the data gradient's), widest first.

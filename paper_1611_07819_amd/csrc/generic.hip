@@ -129,37 +129,104 @@ __global__ __launch_bounds__(GTHREADS) void gemm_generic_kernel(GemmTables t, do
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc.v[r] = AccT(0);
 
-    const int ks0 = t.ksplit[split], ks1 = t.ksplit[split + 1];
-    for (int ks = ks0; ks < ks1; ++ks) {
-        const Panel pa = t.a[tile.mseg * t.n_kseg + ks];
-        const Panel pb = t.b[ks * t.n_nseg + tile.nseg];
-        const T* a = static_cast<const T*>(pa.ptr);
-        const T* b = static_cast<const T*>(pb.ptr);
-        const int64_t a_smn = t.a_kcontig ? pa.ld : 1, a_sk = t.a_kcontig ? 1 : pa.ld;
-        const int64_t b_smn = t.b_kcontig ? pb.ld : 1, b_sk = t.b_kcontig ? 1 : pb.ld;
-        const int kl = t.klen[ks];
-        for (int k0 = 0; k0 < kl; k0 += GK) {
+    if constexpr (sizeof(T) == 2) {
+        // 16-bit elements: fetched where they are stored (fetching ahead was measured slower)
+        const int ks0 = t.ksplit[split], ks1 = t.ksplit[split + 1];
+        for (int ks = ks0; ks < ks1; ++ks) {
+            const Panel pa = t.a[tile.mseg * t.n_kseg + ks];
+            const Panel pb = t.b[ks * t.n_nseg + tile.nseg];
+            const T* a = static_cast<const T*>(pa.ptr);
+            const T* b = static_cast<const T*>(pb.ptr);
+            const int64_t a_smn = t.a_kcontig ? pa.ld : 1, a_sk = t.a_kcontig ? 1 : pa.ld;
+            const int64_t b_smn = t.b_kcontig ? pb.ld : 1, b_sk = t.b_kcontig ? 1 : pb.ld;
+            const int kl = t.klen[ks];
+            for (int k0 = 0; k0 < kl; k0 += GK) {
 #pragma unroll
-            for (int q = 0; q < GT * GK / GTHREADS; ++q) {
-                int e = q * GTHREADS + tid;
+                for (int q = 0; q < GT * GK / GTHREADS; ++q) {
+                    int e = q * GTHREADS + tid;
+                    int row, kk;
+                    if (t.a_kcontig) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
+                    T v = T(0);
+                    if (row < tile.m_len && k0 + kk < kl)
+                        v = a[(int64_t)(tile.m_off + row) * a_smn + (int64_t)(k0 + kk) * a_sk];
+                    As[row * S + kk] = v;
+                    if (t.b_kcontig) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
+                    v = T(0);
+                    if (row < tile.n_len && k0 + kk < kl)
+                        v = b[(int64_t)(tile.n_off + row) * b_smn + (int64_t)(k0 + kk) * b_sk];
+                    Bs[row * S + kk] = v;
+                }
+                __syncthreads();
+                mma_step(As, Bs, wm, wn, lane, acc);
+                __syncthreads();
+            }
+        }
+
+    } else {
+        // The k-steps of all k-segments of this split form one sequence; the elements of step i+1
+        // are fetched into registers while step i is multiplied out of LDS (fp32, fp64).
+        constexpr int Q = GT * GK / GTHREADS;
+        const int ks1 = t.ksplit[split + 1];
+        int ks = t.ksplit[split], k0 = 0;  // the step that is fetched next
+        const T *a = nullptr, *b = nullptr;  // its k-segment's panels
+        int64_t a_smn = 0, a_sk = 0, b_smn = 0, b_sk = 0;
+        int kl = 0;
+        auto enter = [&]() {
+            if (ks >= ks1) return;
+            const Panel pa = t.a[tile.mseg * t.n_kseg + ks];
+            const Panel pb = t.b[ks * t.n_nseg + tile.nseg];
+            a = static_cast<const T*>(pa.ptr);
+            b = static_cast<const T*>(pb.ptr);
+            a_smn = t.a_kcontig ? pa.ld : 1; a_sk = t.a_kcontig ? 1 : pa.ld;
+            b_smn = t.b_kcontig ? pb.ld : 1; b_sk = t.b_kcontig ? 1 : pb.ld;
+            kl = t.klen[ks];
+        };
+        enter();
+        auto fetch = [&](T (&ra)[Q], T (&rb)[Q]) {
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const int e = q * GTHREADS + tid;
                 int row, kk;
                 if (t.a_kcontig) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
-                T v = T(0);
+                ra[q] = T(0);
                 if (row < tile.m_len && k0 + kk < kl)
-                    v = a[(int64_t)(tile.m_off + row) * a_smn + (int64_t)(k0 + kk) * a_sk];
-                As[row * S + kk] = v;
+                    ra[q] = a[(int64_t)(tile.m_off + row) * a_smn + (int64_t)(k0 + kk) * a_sk];
                 if (t.b_kcontig) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
-                v = T(0);
+                rb[q] = T(0);
                 if (row < tile.n_len && k0 + kk < kl)
-                    v = b[(int64_t)(tile.n_off + row) * b_smn + (int64_t)(k0 + kk) * b_sk];
-                Bs[row * S + kk] = v;
+                    rb[q] = b[(int64_t)(tile.n_off + row) * b_smn + (int64_t)(k0 + kk) * b_sk];
             }
+            k0 += GK;
+            if (k0 >= kl) {
+                k0 = 0;
+                ++ks;
+                enter();
+            }
+        };
+        auto stash = [&](const T (&ra)[Q], const T (&rb)[Q]) {
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const int e = q * GTHREADS + tid;
+                int row, kk;
+                if (t.a_kcontig) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
+                As[row * S + kk] = ra[q];
+                if (t.b_kcontig) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
+                Bs[row * S + kk] = rb[q];
+            }
+        };
+        T ra[Q], rb[Q];
+        bool more = ks < ks1;  // a fetched step is waiting in ra, rb
+        if (more) fetch(ra, rb);
+        while (more) {
+            stash(ra, rb);
             __syncthreads();
+            more = ks < ks1;
+            if (more) fetch(ra, rb);
             mma_step(As, Bs, wm, wn, lane, acc);
             __syncthreads();
         }
-    }
 
+    }
     if (t.split_k > 1) {
         AccT* ws = static_cast<AccT*>(t.workspace) + (int64_t)split * t.M * t.N;
 #pragma unroll
@@ -326,23 +393,60 @@ __global__ __launch_bounds__(GTHREADS) void conv_generic_kernel(ConvTables t, in
     // thread -> element maps: unit-stride axis of the gathered tensor goes across lanes
     constexpr bool a_kfast = (MODE == CONV_BWD_FILTER);
     constexpr bool b_kfast = (MODE != CONV_BWD_DATA);
-    for (int k0 = kbeg; k0 < kend; k0 += GK) {
+    if constexpr (sizeof(T) == 2) {
+        // 16-bit elements: gathered where they are stored (gathering ahead was measured slower)
+        for (int k0 = kbeg; k0 < kend; k0 += GK) {
 #pragma unroll
-        for (int q = 0; q < GT * GK / GTHREADS; ++q) {
-            int e = q * GTHREADS + tid;
-            int row, kk;
-            if (a_kfast) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
-            T v = T(0);
-            if (m0 + row < M && k0 + kk < kend) v = conv_a<T, MODE>(t, m0 + row, k0 + kk);
-            As[row * S + kk] = v;
-            if (b_kfast) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
-            v = T(0);
-            if (n0 + row < N && k0 + kk < kend) v = conv_b<T, MODE>(t, k0 + kk, n0 + row);
-            Bs[row * S + kk] = v;
+            for (int q = 0; q < GT * GK / GTHREADS; ++q) {
+                int e = q * GTHREADS + tid;
+                int row, kk;
+                if (a_kfast) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
+                T v = T(0);
+                if (m0 + row < M && k0 + kk < kend) v = conv_a<T, MODE>(t, m0 + row, k0 + kk);
+                As[row * S + kk] = v;
+                if (b_kfast) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
+                v = T(0);
+                if (n0 + row < N && k0 + kk < kend) v = conv_b<T, MODE>(t, k0 + kk, n0 + row);
+                Bs[row * S + kk] = v;
+            }
+            __syncthreads();
+            mma_step(As, Bs, wm, wn, lane, acc);
+            __syncthreads();
         }
-        __syncthreads();
-        mma_step(As, Bs, wm, wn, lane, acc);
-        __syncthreads();
+    } else {
+        // the elements of k-step i+1 are gathered into registers while step i is multiplied out of
+        // LDS (fp32, fp64)
+        constexpr int Q = GT * GK / GTHREADS;
+        auto fetch = [&](int k0, T (&ra)[Q], T (&rb)[Q]) {
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const int e = q * GTHREADS + tid;
+                int row, kk;
+                if (a_kfast) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
+                ra[q] = T(0);
+                if (m0 + row < M && k0 + kk < kend) ra[q] = conv_a<T, MODE>(t, m0 + row, k0 + kk);
+                if (b_kfast) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
+                rb[q] = T(0);
+                if (n0 + row < N && k0 + kk < kend) rb[q] = conv_b<T, MODE>(t, k0 + kk, n0 + row);
+            }
+        };
+        T ra[Q], rb[Q];
+        if (kbeg < kend) fetch(kbeg, ra, rb);
+        for (int k0 = kbeg; k0 < kend; k0 += GK) {
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                const int e = q * GTHREADS + tid;
+                int row, kk;
+                if (a_kfast) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
+                As[row * S + kk] = ra[q];
+                if (b_kfast) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
+                Bs[row * S + kk] = rb[q];
+            }
+            __syncthreads();
+            if (k0 + GK < kend) fetch(k0 + GK, ra, rb);
+            mma_step(As, Bs, wm, wn, lane, acc);
+            __syncthreads();
+        }
     }
     const AccT alpha = static_cast<AccT>(alpha_d), beta = static_cast<AccT>(beta_d);
 #pragma unroll
