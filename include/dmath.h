@@ -137,7 +137,9 @@ typedef struct {
     int32_t split_k;  /* partial sums per C tile (1 = none)                            */
     int32_t kernel;   /* 0 = guarded generic kernel, >0 = a specialised kernel id      */
     int32_t cached;   /* 1 if the plan was already in the cache                        */
-    uint64_t workspace_bytes;
+    uint64_t workspace_bytes; /* pool memory beyond the operands: split-K partial sums and the
+                                 zero-padded scratch panels of k-segments that are not
+                                 multiples of tile_k */
 } dmath_plan_info_t;
 
 /* Builds (or finds in the cache) the plan dmath_gemm would use and describes it.  Same

@@ -467,11 +467,14 @@ dmath_status_t dmath_gemm_tune(dmath_ctx_t ctx, dmath_op_t transA, dmath_op_t tr
     Events ev;
     if (!ev.ok()) return DMATH_ERR_DEVICE;
     *result = dmath_tune_result_t{};
-    const size_t acc = A->dtype == DMATH_F64 ? 8 : 4;
     double best = -1;
     GemmChoice best_choice;
     for (const GemmChoice& c : cands) {
-        const size_t need = c.split_k > 1 ? (size_t)c.split_k * C->rows * C->cols * acc : 0;
+        // what this candidate takes from the pool (partial sums, scratch panels of k-tails)
+        std::unique_ptr<GemmPlan> sized;
+        st = make_gemm_plan(ctx, transA, transB, A, B, C, false, &c, &sized, nullptr);
+        if (st != DMATH_OK) return st;
+        const size_t need = sized->info.workspace_bytes;
         if (need > workspace_limit) {
             ++result->skipped;
             continue;

@@ -335,8 +335,9 @@ dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_ma
     size_t n_tails = 0;
     for (auto& k : ks) n_tails += tails && k.len % bk != 0;
     char* scratch = nullptr;
+    const size_t scratch_bytes = n_tails * (size_t)(a_tail + b_tail) * es;
     if (n_tails && do_upload) {
-        const size_t bytes = n_tails * (size_t)(a_tail + b_tail) * es;
+        const size_t bytes = scratch_bytes;
         scratch = static_cast<char*>(ctx->pool.alloc(bytes));
         if (!scratch) return DMATH_ERR_OOM;
         if (hipMemsetAsync(scratch, 0, bytes, ctx->stream) != hipSuccess) {
@@ -474,7 +475,9 @@ dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_ma
     info.split_k = ch.split_k;
     info.kernel = ch.kernel;
     const size_t acc_size = A->dtype == DMATH_F64 ? 8 : 4;
-    info.workspace_bytes = ch.split_k > 1 ? (uint64_t)ch.split_k * M * N * acc_size : 0;
+    // pool memory beyond the operands: split-K partial sums and the scratch panels of k-tails
+    const uint64_t partial_bytes = ch.split_k > 1 ? (uint64_t)ch.split_k * M * N * acc_size : 0;
+    info.workspace_bytes = partial_bytes + scratch_bytes;
 
     GemmTables& t = plan->t;
     t.n_mseg = (int32_t)ms.size();
@@ -499,8 +502,8 @@ dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_ma
             return DMATH_ERR_OOM;
         }
         void* ws = nullptr;
-        if (info.workspace_bytes) {
-            ws = ctx->pool.alloc(info.workspace_bytes);
+        if (partial_bytes) {
+            ws = ctx->pool.alloc(partial_bytes);
             if (!ws) {
                 ctx->pool.free(dev);
                 free_gemm_plan(ctx, *plan);

@@ -69,6 +69,28 @@ def test_gemm_tune_honours_the_limit_and_keeps_parity(ctx, oracle, dt, out, shap
     check(model)
 
 
+def test_gemm_tune_counts_the_scratch_panels_of_k_tails(ctx, oracle):
+    """K = 1000 is not a multiple of the fp32 kernels' k-step: the specialised kernels read the
+    end of K from scratch panels in the pool, which count against the memory limit."""
+    M, N, K = 256, 384, 1000
+    r = np.random.default_rng(1103)
+    A = r.uniform(-1, 1, (M, K)).astype(np.float32)
+    B = r.uniform(-1, 1, (K, N)).astype(np.float32)
+    ref = oracle.gemm(False, False, 1.0, A, B, 0.0)
+    dA, dB, dC = ctx.from_host(A), ctx.from_host(B), ctx.matrix(M, N, (1, 1), dm.F32)
+    t0 = dm.gemm_tune(ctx, 0, 0, dA, dB, dC, 0, trials=2)
+    assert t0["kernel"] == 0 and t0["workspace_bytes"] == 0 and t0["skipped"] >= 2
+    dm.gemm(ctx, 0, 0, 1.0, dA, dB, 0.0, dC)
+    assert rel_fro(dC.get(), ref) <= TOL[dm.F32]
+    t1 = dm.gemm_tune(ctx, 0, 0, dA, dB, dC, 1 << 26, trials=2)
+    assert t1["kernel"] != 0 and t1["workspace_bytes"] >= (M + N) * 32 * 4
+    info = dm.gemm_plan_info(ctx, 0, 0, dA, dB, dC)
+    assert info["kernel"] == t1["kernel"] and info["workspace_bytes"] == t1["workspace_bytes"]
+    dm.gemm(ctx, 0, 0, 1.0, dA, dB, 0.0, dC)
+    assert rel_fro(dC.get(), ref) <= TOL[dm.F32]
+    ctx.tune_reset()
+
+
 GEO = dict(n=4, c=128, h=16, w=16, k=256, r=3, s=3, pad_h=1, pad_w=1)
 
 
