@@ -1,7 +1,7 @@
-// Specialised convolution kernels for gfx950, fp16 (fp32 accumulate) and fp32: forward, weight
-// gradient and data gradient as implicit GEMMs on the MFMA pipelines of f16_pipeline.hpp and
-// f32_pipeline.hpp (paper abstract: convolutions; section 1: data reorganisation to support a
-// series of operations).
+// Specialised convolution kernels for gfx950, fp16 (fp32 accumulate), fp32 and fp64: forward,
+// weight gradient and data gradient as implicit GEMMs on the MFMA pipelines of f16_pipeline.hpp,
+// f32_pipeline.hpp and f64_pipeline.hpp (paper abstract: convolutions; section 1: data
+// reorganisation to support a series of operations, double / float / half precision).
 //
 // NCHW keeps pixels, not channels, contiguous, and the 3x3 taps shift the pixel index by +-1,
 // which no 16-byte load can follow.  So the activations are first rewritten into a
@@ -19,7 +19,7 @@
 //                    rotated by 180 degrees and its channel roles swapped, Gp[c][(r',s',k)].
 // Channel and filter counts that are not multiples of 64 are rounded up in the copies (the pad
 // channels stay zero, as the allocation left them; stores skip the pad filters), and a pixel count
-// n*oh*ow that is not a multiple of the pipeline's k-tile (64 pixels fp16, 32 fp32) reads zeros
+// n*oh*ow that is not a multiple of the pipeline's k-tile (64 pixels fp16, 32 fp32, 16 fp64) reads zeros
 // past its end (an extra, never-written image in Xp, extra rows in Yt).
 // A rewrite is skipped when the caller says the copy is still current (the context keeps the
 // copies and the version of the matrix each was made from); otherwise it is part of the call.
@@ -33,6 +33,7 @@
 #include "context.hpp"
 #include "f16_pipeline.hpp"
 #include "f32_pipeline.hpp"
+#include "f64_pipeline.hpp"
 
 namespace dm {
 
@@ -43,7 +44,27 @@ typedef uint32_t v2u __attribute__((ext_vector_type(2)));
 constexpr int NT = 256;
 
 // What the kernels below need to know about a pipeline.
-struct PipeF16 {
+// Accumulators of the 32x32 MFMAs (fp16, fp32): 16 registers, register r of lane l holds row
+// 8*(r/4) + 4*(l/32) + r%4 and column l%32, so four consecutive registers are four consecutive rows.
+struct Acc32 {
+    using AccT = float;
+    using Acc = v16f;
+    static constexpr int kRegs = 16, kEdge = 32;
+    static constexpr bool kRowQuads = true;
+    __device__ __forceinline__ static int row(int lane, int r) { return acc32_row(lane, r); }
+    __device__ __forceinline__ static int col(int lane) { return acc32_col(lane); }
+};
+// Accumulators of the 16x16 fp64 MFMA: 4 registers, register r of lane l holds row 4*r + l/16.
+struct Acc16d {
+    using AccT = double;
+    using Acc = v4d;
+    static constexpr int kRegs = 4, kEdge = 16;
+    static constexpr bool kRowQuads = false;
+    __device__ __forceinline__ static int row(int lane, int r) { return acc16d_row(lane, r); }
+    __device__ __forceinline__ static int col(int lane) { return acc16d_col(lane); }
+};
+
+struct PipeF16 : Acc32 {
     using Elem = _Float16;
     static constexpr int BK = f16p::BK;
     template <int BMN, bool KC> using Tile = f16p::OperandTile<BMN, KC>;
@@ -55,7 +76,7 @@ struct PipeF16 {
     }
     static constexpr int lds_bytes(int bm, int bn, int stages) { return stages * (bm + bn) * BK * 2; }
 };
-struct PipeF32 {
+struct PipeF32 : Acc32 {
     using Elem = float;
     static constexpr int BK = f32p::BK;
     template <int BMN, bool KC> using Tile = f32p::OperandTile<BMN, KC>;
@@ -73,7 +94,25 @@ struct PipeF32 {
     static constexpr int lds_bytes(int bm, int bn, int stages) { return stages * (bm + bn) * BK * 4; }
 };
 
-template <class TC> __device__ __forceinline__ TC to_out(float v) { return (TC)v; }
+struct PipeF64 : Acc16d {
+    using Elem = double;
+    static constexpr int BK = f64p::BK;
+    template <int BMN, bool KC> using Tile = f64p::OperandTile<BMN, KC>;
+    template <int BM, int BN> struct Shape {  // wavefronts 2 x 2, 16 x 16 result tiles
+        static constexpr int WM = BM / 2, WN = BN / 2, MT = WM / 16, NTL = WN / 16;
+        __device__ __forceinline__ static int wm(int wave) { return wave / 2; }
+        __device__ __forceinline__ static int wn(int wave) { return wave % 2; }
+    };
+    template <int BM, int BN, int STAGES, bool AKC, bool BKC, class Walk, class Acc>
+    __device__ __forceinline__ static void run(Walk& walk, int n_ktiles, char* smem, Acc& acc)
+    {
+        static_assert(STAGES == f64p::STAGES, "the fp64 ring has three stages");
+        f64p::run<BM, BN, 2, AKC, BKC>(walk, n_ktiles, smem, acc);
+    }
+    static constexpr int lds_bytes(int bm, int bn, int stages) { return stages * (bm + bn) * BK * 8; }
+};
+
+template <class TC, class A> __device__ __forceinline__ TC to_out(A v) { return (TC)v; }
 
 // ------------------------------------------------------------------------------------------
 // layout rewrites
@@ -205,7 +244,7 @@ struct FastConv {
     const void* xp;  // the copies, elements of the pipeline's input type
     const void* fp;
     const void* yt;
-    float* ws;
+    void* ws;  // weight gradient: partial sums in the accumulation type
     int split, ktiles, ktiles_per_split;  // weight gradient: parts, pixel k-tiles in all and per part
 };
 
@@ -267,9 +306,11 @@ __device__ __forceinline__ int xcd_logical(int w, int n)
 }
 
 template <class P, int BM, int BN, int STAGES, class TC>
-__global__ __launch_bounds__(NT) void conv_fwd_kernel(FastConv p, float alpha, float beta)
+__global__ __launch_bounds__(NT) void conv_fwd_kernel(FastConv p, typename P::AccT alpha, typename P::AccT beta)
 {
     using TS = typename P::template Shape<BM, BN>;
+    using AccT = typename P::AccT;
+    constexpr int E = P::kEdge;
     constexpr int WM = TS::WM, WN = TS::WN, MT = TS::MT, NTL = TS::NTL;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const int tiles_n = p.g.k / BN;
@@ -277,44 +318,46 @@ __global__ __launch_bounds__(NT) void conv_fwd_kernel(FastConv p, float alpha, f
     const int m0 = (idx / tiles_n) * BM, n0 = (idx % tiles_n) * BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = TS::wm(wave), wn = TS::wn(wave), h = lane >> 5, l32 = lane & 31;
+    const int wm = TS::wm(wave), wn = TS::wn(wave), h = lane >> 5, lcol = P::col(lane);
 
-    v16f acc[MT][NTL];
+    typename P::Acc acc[MT][NTL];
 #pragma unroll
     for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int j = 0; j < NTL; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+            for (int r = 0; r < P::kRegs; ++r) acc[i][j][r] = AccT(0);
 
     FwdWalk<P, BM, BN> walk(p, m0, n0, wave, lane);
     const int n_ktiles = p.g.r * p.g.s * (p.g.c / P::BK);
     P::template run<BM, BN, STAGES, true, true>(walk, n_ktiles, smem, acc);
 
-    // epilogue: four consecutive registers are four consecutive pixels of one output plane
+    // epilogue: with the 32x32 MFMAs four consecutive registers are four consecutive pixels of one
+    // output plane (stored together where a plane is a multiple of 4 pixels)
     const int sp_out = p.g.oh * p.g.ow, m_end = p.g.n * sp_out;
-    if (sp_out % 4 != 0) {
-        // planes that 4-pixel groups straddle: one element at a time
+    if (!P::kRowQuads || sp_out % 4 != 0) {
+        // one element at a time
 #pragma unroll
         for (int i = 0; i < MT; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = m0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+            for (int r = 0; r < P::kRegs; ++r) {
+                const int m = m0 + wm * WM + i * E + P::row(lane, r);
                 if (m >= m_end) continue;
                 const int n_img = m / sp_out, sp = m % sp_out;
                 TC* yrow = static_cast<TC*>(const_cast<void*>(p.y_rows[n_img]));
 #pragma unroll
                 for (int j = 0; j < NTL; ++j) {
-                    const int ko = n0 + wn * WN + j * 32 + l32;
+                    const int ko = n0 + wn * WN + j * E + lcol;
                     if (ko >= p.k_real) continue;
                     TC* dst = yrow + (int64_t)ko * sp_out + sp;
-                    float v = alpha * acc[i][j][r];
-                    if (beta != 0.f) v += beta * (float)*dst;
+                    AccT v = alpha * acc[i][j][r];
+                    if (beta != AccT(0)) v += beta * (AccT)*dst;
                     *dst = to_out<TC>(v);
                 }
             }
         return;
     }
+    if constexpr (P::kRowQuads) {
 #pragma unroll
     for (int i = 0; i < MT; ++i)
 #pragma unroll
@@ -325,7 +368,7 @@ __global__ __launch_bounds__(NT) void conv_fwd_kernel(FastConv p, float alpha, f
             TC* yrow = static_cast<TC*>(const_cast<void*>(p.y_rows[n_img]));
 #pragma unroll
             for (int j = 0; j < NTL; ++j) {
-                const int ko = n0 + wn * WN + j * 32 + l32;
+                const int ko = n0 + wn * WN + j * 32 + lcol;
                 if (ko >= p.k_real) continue;  // pad filters
                 TC* dst = yrow + (int64_t)ko * sp_out + sp;
                 typedef TC out4 __attribute__((ext_vector_type(4)));
@@ -340,6 +383,7 @@ __global__ __launch_bounds__(NT) void conv_fwd_kernel(FastConv p, float alpha, f
                 *reinterpret_cast<out4*>(dst) = o;
             }
         }
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -421,53 +465,56 @@ __global__ __launch_bounds__(NT) void conv_wgrad_kernel(FastConv p)
     const int m0 = (mn / tiles_n) * BM, n0 = (mn % tiles_n) * BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = TS::wm(wave), wn = TS::wn(wave), l32 = lane & 31;
+    const int wm = TS::wm(wave), wn = TS::wn(wave);
+    using AccT = typename P::AccT;
 
-    v16f acc[MT][NTL];
+    typename P::Acc acc[MT][NTL];
 #pragma unroll
     for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int j = 0; j < NTL; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+            for (int r = 0; r < P::kRegs; ++r) acc[i][j][r] = AccT(0);
 
     // the last part may be shorter; pixels past n*oh*ow (last k-tile) read zeros on both sides
     const int kt0 = split * p.ktiles_per_split;
     WgradWalk<P, BM, BN> walk(p, kt0 * BK, m0, n0, wave, lane);
     P::template run<BM, BN, 3, false, false>(walk, min(p.ktiles_per_split, p.ktiles - kt0), smem, acc);
 
-    float* ws = p.ws + (int64_t)split * p.g.k * ncols;
+    AccT* ws = static_cast<AccT*>(p.ws) + (int64_t)split * p.g.k * ncols;
 #pragma unroll
     for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int j = 0; j < NTL; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm * WM + i * 32 + acc32_row(lane, r);
-                const int col = n0 + wn * WN + j * 32 + l32;
+            for (int r = 0; r < P::kRegs; ++r) {
+                const int row = m0 + wm * WM + i * P::kEdge + P::row(lane, r);
+                const int col = n0 + wn * WN + j * P::kEdge + P::col(lane);
                 ws[(int64_t)row * ncols + col] = acc[i][j][r];
             }
 }
 
 // dF[k][c][r][s] <- alpha * sum over splits (ascending) + beta * dF; the partials are
 // [k][(r,s,c)], read four channels at a time.
-template <class TC>
-__global__ __launch_bounds__(256) void conv_wgrad_reduce_kernel(FastConv p, float alpha, float beta)
+template <class AccT, class TC>
+__global__ __launch_bounds__(256) void conv_wgrad_reduce_kernel(FastConv p, AccT alpha, AccT beta)
 {
+    typedef AccT acc4 __attribute__((ext_vector_type(4)));
+    const AccT* ws = static_cast<const AccT*>(p.ws);
     const int rs = p.g.r * p.g.s, c = p.g.c, ncols = rs * c;
     const int64_t total = (int64_t)p.g.k * ncols, quads = total / 4;
     for (int64_t e4 = (int64_t)blockIdx.x * 256 + threadIdx.x; e4 < quads; e4 += (int64_t)gridDim.x * 256) {
         const int64_t e = e4 * 4;
         const int kk = (int)(e / ncols), col = (int)(e % ncols), q = col / c, cc = col % c;
         if (kk >= p.k_real || cc >= p.c_real) continue;  // pad filters, pad channels
-        v4f sum = {0.f, 0.f, 0.f, 0.f};
-        for (int s = 0; s < p.split; ++s) sum += *reinterpret_cast<const v4f*>(p.ws + (int64_t)s * total + e);
+        acc4 sum = {AccT(0), AccT(0), AccT(0), AccT(0)};
+        for (int s = 0; s < p.split; ++s) sum += *reinterpret_cast<const acc4*>(ws + (int64_t)s * total + e);
         TC* dst = static_cast<TC*>(const_cast<void*>(p.f_rows[kk])) + cc * rs + q;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             if (cc + i >= p.c_real) break;
-            float v = alpha * sum[i];
-            if (beta != 0.f) v += beta * (float)dst[i * rs];
+            AccT v = alpha * sum[i];
+            if (beta != AccT(0)) v += beta * (AccT)dst[i * rs];
             dst[i * rs] = to_out<TC>(v);
         }
     }
@@ -482,9 +529,12 @@ template <class K> hipError_t set_lds(K kern, int bytes)
 }  // namespace
 
 static int round64(int v) { return (v + 63) / 64 * 64; }
-static int elem_bytes(dmath_dtype_t dt) { return dt == DMATH_F16 ? 2 : 4; }
+static int elem_bytes(dmath_dtype_t dt) { return dt == DMATH_F16 ? 2 : dt == DMATH_F32 ? 4 : 8; }
 // pixels per k-tile of the weight gradient (= the pipeline's k-tile)
-static int pixel_tile(dmath_dtype_t dt) { return dt == DMATH_F16 ? PipeF16::BK : PipeF32::BK; }
+static int pixel_tile(dmath_dtype_t dt)
+{
+    return dt == DMATH_F16 ? PipeF16::BK : dt == DMATH_F32 ? PipeF32::BK : PipeF64::BK;
+}
 
 // Sizes of the copies that the specialised kernels read.
 ConvFastLayout conv_fast_layout(int mode, const ConvGeom& g, dmath_dtype_t dt)
@@ -507,16 +557,15 @@ ConvFastLayout conv_fast_layout(int mode, const ConvGeom& g, dmath_dtype_t dt)
     return l;
 }
 
-// Geometry the specialised kernels accept (everything else runs on the generic kernels): fp16 or
-// fp32, every copy below 4 GiB (32-bit lane offsets), at most four times the work from rounding
+// Geometry the specialised kernels accept (everything else runs on the generic kernels): every
+// copy below 4 GiB (32-bit lane offsets), at most four times the work from rounding
 // the channel and filter counts up to multiples of 64 (the matrix pipeline is more than ten
-// times faster than the generic kernel in fp16, three to four times in fp32: there the limit is
-// twice the work), for the data gradient (a forward convolution of dY with padding r-1-pad)
+// times faster than the generic kernel in fp16, two to four times in fp32 and fp64: there the
+// limit is twice the work), for the data gradient (a forward convolution of dY with padding r-1-pad)
 // a padding that does not exceed the filter, and for the weight gradient output planes that are
 // not tiny (4x4 and less in fp16).
 bool conv_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype)
 {
-    if (in_dtype != DMATH_F16 && in_dtype != DMATH_F32) return false;
     const ConvFastLayout l = conv_fast_layout(mode, g, in_dtype);
     const int64_t limit = 1ll << 32;
     if (l.x_bytes >= limit || l.f_bytes >= limit || l.y_bytes >= limit) return false;
@@ -558,25 +607,26 @@ static bool wgrad_split_ok(int64_t ktiles, int s)
 static int per_cu(int bm, int bn, dmath_dtype_t dt)
 {
     if (dt == DMATH_F16) return 1;
-    return 160 * 1024 / PipeF32::lds_bytes(bm, bn, 3);
+    return 160 * 1024 / (dt == DMATH_F32 ? PipeF32::lds_bytes(bm, bn, 3) : PipeF64::lds_bytes(bm, bn, 3));
 }
 
 // Split count for the weight gradient: the number of parts s (each of ceil(k-tiles / s) pixel
 // tiles, the last one possibly shorter) with at most one round of workgroups that minimises
 // (w x 64-pixel steps of the busiest CU + s): the parts shorten with s, the partial sums written
 // and read back grow with it.  w = 1 in fp16 (the balance point sqrt(k-tiles) matches the timing
-// samples on 1x1 and 3x3 layers of 14x14 and 28x28 pixels), 4 in fp32, whose steps take four
-// times as long; an fp32 CU with a single workgroup runs at 0.87 of the rate (as in choose_conv).
+// samples on 1x1 and 3x3 layers of 14x14 and 28x28 pixels), 4 in fp32 and 8 in fp64, whose steps
+// take that many times as long; an fp32 / fp64 CU with a single workgroup runs at 0.87 of the
+// rate (as in choose_conv).
 int conv_fast_wgrad_split(const ConvGeom& g, dmath_dtype_t dt)
 {
     const int64_t ktiles = wgrad_ktiles(g, dt);
     const int64_t tiles = wgrad_tiles(g, dt);
     const int unit = 64 / pixel_tile(dt);  // k-tiles per 64 pixels
     const int slots = 256 * per_cu(wgrad_tile_m(g, dt), wgrad_tile_n(g), dt);
-    const double w = dt == DMATH_F16 ? 1 : 4;
+    const double w = dt == DMATH_F16 ? 1 : dt == DMATH_F32 ? 4 : 8;
     auto cost = [&](int s) {
         const int64_t per = (ktiles + s - 1) / s, on_cu = (tiles * s + 255) / 256;
-        const double rate = (dt == DMATH_F32 && on_cu == 1) ? 0.87 : 1.0;
+        const double rate = (dt != DMATH_F16 && on_cu == 1) ? 0.87 : 1.0;
         return on_cu * (double)(per / unit) * w / rate + s;
     };
     int best = 1;
@@ -633,7 +683,7 @@ ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int3
     const int n_out = round64(mode == CONV_FWD ? g.k : g.c);
     // the tile shape whose longest chain of tiles on one CU takes the fewest cycles: rounds of
     // workgroups over all slots x (k x the slower of the tile's matrix instructions -- fp16: 32.5
-    // cycles per 32x32x16 over four SIMDs, fp32: 64 per 32x32x2 -- and its operand loads at 60
+    // cycles per 32x32x16 over four SIMDs, fp32: 64 per 32x32x2, fp64: 64 per 16x16x4 -- and its operand loads at 60
     // bytes per cycle and CU, + the tile's stores at 10 bytes per cycle and CU).  fp16, 50176
     // pixels x 256 channels: 224 tiles of 224x256 are one round, against 196 of 256x256 or two
     // rounds of 256x128; 64-wide tiles are load-bound and win only where they save whole
@@ -641,7 +691,8 @@ ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int3
     // gathers are hidden less well than with two (128x64): 0.87 of the rate in the samples.
     const int64_t k_depth = (int64_t)g.r * g.s * round64(mode == CONV_FWD ? g.c : g.k);
     const int eb = elem_bytes(in_dtype);
-    const double mfma_per_k = in_dtype == DMATH_F16 ? 32.5 / 16 : 64.0 / 2;  // cycles per unit of k and 32x32 block
+    // cycles per unit of k and 32x32 block (fp64: four 16x16x4 instructions of 64 cycles per 4 of k)
+    const double mfma_per_k = in_dtype == DMATH_F16 ? 32.5 / 16 : in_dtype == DMATH_F32 ? 64.0 / 2 : 64.0;
     double best = -1;
     for (const FwdShape& sh : fwd_shapes(in_dtype, n_out)) {
         const int64_t tiles = (m + sh.bm - 1) / sh.bm * (n_out / sh.bn);
@@ -649,7 +700,7 @@ ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int3
         const int64_t chain = (tiles + 256 * slots - 1) / (256 * slots) * slots;  // tiles the busiest CU runs
         const double area = (double)sh.bm * sh.bn;
         const double per_k = std::max(area / 1024 * mfma_per_k / 4, (sh.bm + sh.bn) * eb / 60.0);
-        const double rate = (in_dtype == DMATH_F32 && slots == 1) ? 0.87 : 1.0;
+        const double rate = (in_dtype != DMATH_F16 && slots == 1) ? 0.87 : 1.0;
         const double cost = (double)chain * (k_depth * per_k / rate + 0.4 * area);
         if (best < 0 || cost < 0.97 * best) {
             best = cost;
@@ -700,29 +751,36 @@ namespace {
 
 // Launches the forward kernel (also the data gradient's) on tiles of BM x BN.
 template <class P, int BM, int BN, int STAGES>
-hipError_t launch_fwd_shape(const FastConv& p, dmath_dtype_t out, float alpha, float beta, hipStream_t st)
+hipError_t launch_fwd_shape(const FastConv& p, dmath_dtype_t out, double alpha, double beta, hipStream_t st)
 {
+    using AccT = typename P::AccT;
+    using Wide = typename std::conditional<std::is_same<P, PipeF64>::value, double, float>::type;  // the wider output type
     const int64_t m = (int64_t)p.g.n * p.g.oh * p.g.ow;
     const int tiles = (int)((m + BM - 1) / BM) * (p.g.k / BN);
     constexpr int lds = P::lds_bytes(BM, BN, STAGES);
     static bool configured = false;  // more than 64 KiB of LDS has to be asked for once per kernel
     if (!configured) {
-        hipError_t e = set_lds(conv_fwd_kernel<P, BM, BN, STAGES, float>, lds);
+        hipError_t e = set_lds(conv_fwd_kernel<P, BM, BN, STAGES, Wide>, lds);
         if (e == hipSuccess && std::is_same<P, PipeF16>::value)
             e = set_lds(conv_fwd_kernel<P, BM, BN, STAGES, typename P::Elem>, lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
     if (out == DMATH_F16)
-        conv_fwd_kernel<P, BM, BN, STAGES, typename P::Elem><<<tiles, NT, lds, st>>>(p, alpha, beta);
+        conv_fwd_kernel<P, BM, BN, STAGES, typename P::Elem><<<tiles, NT, lds, st>>>(p, (AccT)alpha, (AccT)beta);
     else
-        conv_fwd_kernel<P, BM, BN, STAGES, float><<<tiles, NT, lds, st>>>(p, alpha, beta);
+        conv_fwd_kernel<P, BM, BN, STAGES, Wide><<<tiles, NT, lds, st>>>(p, (AccT)alpha, (AccT)beta);
     return hipGetLastError();
 }
 
-hipError_t launch_fwd(const FastConv& p, dmath_dtype_t in, int tile_m, int tile_n, dmath_dtype_t out, float alpha,
-                      float beta, hipStream_t st)
+hipError_t launch_fwd(const FastConv& p, dmath_dtype_t in, int tile_m, int tile_n, dmath_dtype_t out, double alpha,
+                      double beta, hipStream_t st)
 {
+    if (in == DMATH_F64) {
+        if (tile_m == 128 && tile_n == 128) return launch_fwd_shape<PipeF64, 128, 128, 3>(p, out, alpha, beta, st);
+        if (tile_m == 128 && tile_n == 64) return launch_fwd_shape<PipeF64, 128, 64, 3>(p, out, alpha, beta, st);
+        return hipErrorInvalidValue;
+    }
     if (in == DMATH_F32) {
         if (tile_m == 128 && tile_n == 128) return launch_fwd_shape<PipeF32, 128, 128, 3>(p, out, alpha, beta, st);
         if (tile_m == 128 && tile_n == 64) return launch_fwd_shape<PipeF32, 128, 64, 3>(p, out, alpha, beta, st);
@@ -750,6 +808,13 @@ template <class P, int BM, int BN> hipError_t launch_wgrad_shape(const FastConv&
 
 hipError_t launch_wgrad(const FastConv& p, dmath_dtype_t in, int bm, int bn, int tiles, hipStream_t st)
 {
+    if (in == DMATH_F64) {
+        if (bm == 128 && bn == 128) return launch_wgrad_shape<PipeF64, 128, 128>(p, tiles, st);
+        if (bm == 128 && bn == 64) return launch_wgrad_shape<PipeF64, 128, 64>(p, tiles, st);
+        if (bm == 64 && bn == 128) return launch_wgrad_shape<PipeF64, 64, 128>(p, tiles, st);
+        if (bm == 64 && bn == 64) return launch_wgrad_shape<PipeF64, 64, 64>(p, tiles, st);
+        return hipErrorInvalidValue;
+    }
     if (in == DMATH_F32) {
         if (bm == 128 && bn == 128) return launch_wgrad_shape<PipeF32, 128, 128>(p, tiles, st);
         if (bm == 128 && bn == 64) return launch_wgrad_shape<PipeF32, 128, 64>(p, tiles, st);
@@ -768,7 +833,7 @@ hipError_t launch_wgrad(const FastConv& p, dmath_dtype_t in, int bm, int bn, int
 
 // The whole call for input element type T.
 template <class T>
-hipError_t launch_typed(const ConvPlan& plan, int mode, float alpha, float beta, unsigned rewrite, hipStream_t st)
+hipError_t launch_typed(const ConvPlan& plan, int mode, double alpha, double beta, unsigned rewrite, hipStream_t st)
 {
     const ConvTables& t = plan.t;
     const ConvGeom& g = t.g;
@@ -790,7 +855,7 @@ hipError_t launch_typed(const ConvPlan& plan, int mode, float alpha, float beta,
     p.xp = xp;
     p.fp = fp;
     p.yt = yt;
-    p.ws = static_cast<float*>(t.workspace);
+    p.ws = t.workspace;
     p.split = t.split_k;
     if (!xp || (mode != CONV_BWD_FILTER && !fp) || (mode == CONV_BWD_FILTER && (!yt || !p.ws)))
         return hipErrorInvalidValue;  // the plan was not made for this path
@@ -838,10 +903,12 @@ hipError_t launch_typed(const ConvPlan& plan, int mode, float alpha, float beta,
     const int tiles = (int)wgrad_tiles(g, in) * t.split_k;
     hipError_t e = launch_wgrad(p, in, wgrad_tile_m(g, in), wgrad_tile_n(g), tiles, st);
     if (e != hipSuccess) return e;
-    if (plan.out_dtype == DMATH_F16)
-        conv_wgrad_reduce_kernel<_Float16><<<1024, 256, 0, st>>>(p, alpha, beta);
+    if (plan.out_dtype == DMATH_F64)
+        conv_wgrad_reduce_kernel<double, double><<<1024, 256, 0, st>>>(p, alpha, beta);
+    else if (plan.out_dtype == DMATH_F16)
+        conv_wgrad_reduce_kernel<float, _Float16><<<1024, 256, 0, st>>>(p, (float)alpha, (float)beta);
     else
-        conv_wgrad_reduce_kernel<float><<<1024, 256, 0, st>>>(p, alpha, beta);
+        conv_wgrad_reduce_kernel<float, float><<<1024, 256, 0, st>>>(p, (float)alpha, (float)beta);
     return hipGetLastError();
 }
 
@@ -850,9 +917,9 @@ hipError_t launch_typed(const ConvPlan& plan, int mode, float alpha, float beta,
 hipError_t launch_conv_fast(const ConvPlan& plan, int mode, double alpha, double beta, unsigned rewrite,
                             hipStream_t st)
 {
-    if (plan.in_dtype == DMATH_F16) return launch_typed<_Float16>(plan, mode, (float)alpha, (float)beta, rewrite, st);
-    if (plan.in_dtype == DMATH_F32) return launch_typed<float>(plan, mode, (float)alpha, (float)beta, rewrite, st);
-    return hipErrorInvalidValue;
+    if (plan.in_dtype == DMATH_F16) return launch_typed<_Float16>(plan, mode, alpha, beta, rewrite, st);
+    if (plan.in_dtype == DMATH_F32) return launch_typed<float>(plan, mode, alpha, beta, rewrite, st);
+    return launch_typed<double>(plan, mode, alpha, beta, rewrite, st);
 }
 
 }  // namespace dm

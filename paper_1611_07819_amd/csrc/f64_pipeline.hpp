@@ -1,0 +1,239 @@
+// The fp64 MFMA pipeline for gfx950 on v_mfma_f64_16x16x4_f64, shared by the fp64 GEMM and the
+// fp64 convolution kernels (paper section 1, feature d: double precision).
+//
+// Same structure as the fp32 pipeline: one workgroup of 4 wavefronts per BM x BN tile of C; k is
+// walked 16 at a time (128-byte rows) through a three-stage LDS ring filled by
+// global_load_lds_dwordx4 (16 bytes per lane straight into LDS), two tiles in flight while a
+// third is multiplied, explicit s_waitcnt vmcnt(), pinned instruction order.  A wavefront owns
+// its part of the tile as a grid of 16 x 16 result tiles.
+//
+// LDS layouts, both as the operand lies in memory:
+//   k unit-stride operand  : [mn][16 k], 128-byte rows, 16-byte chunk (2 doubles) index XOR
+//                            ((mn ^ (mn>>3)) & 7); one ds_read_b128 gives a lane its values for
+//                            two MFMA steps
+//   m/n unit-stride operand: [k][mn]; one ds_read_b64 per MFMA step, lanes on consecutive
+//                            addresses
+// Inside a group of 8 k the order is permuted identically for A and B: lane group g = lane/16
+// supplies k = 8u + 2g + j at step j of group u.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "mfma.hpp"
+
+namespace dm {
+namespace f64p {
+
+constexpr int BK = 16;
+typedef double v2d __attribute__((ext_vector_type(2)));
+constexpr int NT = 256;
+constexpr int STAGES = 3;
+typedef __attribute__((address_space(3))) char lds_char;
+
+__device__ __forceinline__ int swz(int mn) { return (mn ^ (mn >> 3)) & 7; }
+
+__device__ __forceinline__ const char* uniform_ptr(const char* p)
+{
+    uint64_t v = reinterpret_cast<uint64_t>(p);
+    uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const char*>(((uint64_t)hi << 32) | lo);
+}
+
+// One direct global->LDS load: lane fetches 16 bytes at (sbase + voff), lands at m0 + 16*lane.
+__device__ __forceinline__ void dma16(uint32_t lds_addr, const void* sbase, uint32_t voff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(sbase)
+                 : "memory");
+}
+
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int BMN, bool KC> struct OperandTile {
+    static constexpr int kInstr = BMN / 32;      // 1 KiB segments per wavefront and k-tile
+    static constexpr int kBytes = BMN * BK * 8;  // one stage of this operand
+    static constexpr int kChunksPerRow = KC ? 8 : BMN / 2;
+    static constexpr int kRowsPerSeg = 64 / kChunksPerRow;
+    static constexpr int kReadsPerFrag = KC ? 1 : 2;
+
+    // Row (k unit-stride: m/n index; otherwise: k index) inside the tile, and 16-byte chunk of
+    // that row in memory, which this lane fetches with segment q (operands whose rows are gathered).
+    __device__ __forceinline__ static void lane_slot(int q, int wave, int lane, int& row, int& chunk)
+    {
+        const int seg = q * 4 + wave;
+        row = seg * kRowsPerSeg + lane / kChunksPerRow;
+        const int cpos = lane % kChunksPerRow;
+        chunk = KC ? (cpos ^ swz(row)) : cpos;
+    }
+
+    // byte offsets (relative to the panel origin) of the chunks this lane fetches at k-tile 0
+    // Only `len` (<= BMN) rows/columns of the tile exist (ragged last tile): loads for the rest are
+    // redirected to the last existing row / 16-byte chunk, so every address stays inside the
+    // operand; what they bring in only reaches accumulators that the epilogue does not store.
+    __device__ __forceinline__ static void offsets(int64_t ld, int mn0, int len, int wave, int lane,
+                                                   uint32_t (&off)[kInstr])
+    {
+#pragma unroll
+        for (int q = 0; q < kInstr; ++q) {
+            const int seg = q * 4 + wave;
+            const int row = seg * kRowsPerSeg + lane / kChunksPerRow;
+            const int cpos = lane % kChunksPerRow;
+            if (KC)
+                off[q] = (uint32_t)((((int64_t)(mn0 + min(row, len - 1))) * ld + (cpos ^ swz(row)) * 2) * 8);
+            else
+                off[q] = (uint32_t)(((int64_t)row * ld + mn0 + min(cpos, (len - 1) >> 1) * 2) * 8);
+        }
+    }
+    __device__ __forceinline__ static int64_t step(int64_t ld) { return KC ? BK * 8 : BK * 8 * ld; }
+
+    // Part `part` of the fragment of group u (2 MFMA steps) for the lane whose row/column is mn
+    // and whose k-group is g = lane/16.
+    __device__ __forceinline__ static void read(const lds_char* tile, int mn, int g, int u, int part,
+                                                v2d& frag)
+    {
+        if (KC) {
+            frag = *reinterpret_cast<const __attribute__((address_space(3))) v2d*>(
+                tile + mn * 128 + ((((u << 2) + g) ^ swz(mn)) << 4));
+        } else {
+            frag[part] = *reinterpret_cast<const __attribute__((address_space(3))) double*>(
+                tile + ((8 * u + 2 * g + part) * BMN + mn) * 8);
+        }
+    }
+};
+
+template <int BMN, bool KC> struct KCheck {
+    static constexpr bool ok = KC || (64 % (BMN / 2) == 0);
+};
+
+// Runs the whole k-loop of one workgroup tile (wavefronts arranged WVM x 4/WVM).  `walk` must
+// provide
+//   const char *abase, *bbase;  uint32_t aoff[BM/32], boff[BN/32];  void advance();
+// describing the k-tile that is fetched next.  acc must be zeroed by the caller.
+template <int BM, int BN, int WVM, bool AKC, bool BKC, class Walk>
+__device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
+                                    v4d (&acc)[BM / WVM / 16][BN / (4 / WVM) / 16])
+{
+    using TA = OperandTile<BM, AKC>;
+    using TB = OperandTile<BN, BKC>;
+    constexpr int WVN = 4 / WVM;
+    constexpr int WM = BM / WVM, WN = BN / WVN;  // wavefront tile
+    static_assert(KCheck<BM, AKC>::ok && KCheck<BN, BKC>::ok, "m/n-major tiles must fill whole LDS segments");
+    constexpr int MT = WM / 16, NTL = WN / 16;
+    constexpr int kStage = TA::kBytes + TB::kBytes;
+    constexpr int kPerTile = TA::kInstr + TB::kInstr;
+    const lds_char* lds = (const lds_char*)smem;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WVN, wn = wave % WVN, h = lane >> 4, l32 = lane & 15;
+
+    auto issue_one = [&](uint32_t sbase, const char* ab, const char* bb, int idx) {
+        if (idx < TA::kInstr)
+            dma16(sbase + (idx * 4 + wave) * 1024, ab, walk.aoff[idx]);
+        else
+            dma16(sbase + TA::kBytes + ((idx - TA::kInstr) * 4 + wave) * 1024, bb, walk.boff[idx - TA::kInstr]);
+    };
+    auto issue_all = [&](int stage) {
+        const uint32_t sbase = lds0 + stage * kStage;
+        const char* ab = uniform_ptr(walk.abase);
+        const char* bb = uniform_ptr(walk.bbase);
+#pragma unroll
+        for (int idx = 0; idx < kPerTile; ++idx) issue_one(sbase, ab, bb, idx);
+        walk.advance();
+    };
+
+    // Multiplies the tile in `stage`: 4 groups of 8 k, each group 4 MFMA steps on every pair of
+    // fragments.  While group u is multiplied the fragments of group u+1 are read (register
+    // double buffer), one read unit after each MFMA, and -- when PREFETCH -- the loads of the
+    // tile two ahead are spread over the MFMA slots.
+    auto multiply = [&](int stage, int next_stage, auto prefetch) {
+        constexpr bool PREFETCH = decltype(prefetch)::value;
+        constexpr int kGroups = BK / 8, kMfma = 2 * MT * NTL;
+        constexpr int kUnitsA = MT * TA::kReadsPerFrag, kUnits = kUnitsA + NTL * TB::kReadsPerFrag;
+        constexpr int kPerSlot = (kUnits + kMfma - 1) / kMfma;
+        static_assert(kGroups * kMfma >= kPerTile, "not enough slots to spread the loads");
+        const lds_char* sa = lds + stage * kStage;
+        const lds_char* sb = sa + TA::kBytes;
+        const uint32_t nbase = lds0 + next_stage * kStage;
+        const char* ab = uniform_ptr(walk.abase);
+        const char* bb = uniform_ptr(walk.bbase);
+        v2d fa[2][MT], fb[2][NTL];
+        auto read_unit = [&](int buf, int r, int u) {
+            if (r < kUnitsA)
+                TA::read(sa, wm * WM + (r / TA::kReadsPerFrag) * 16 + l32, h, u, r % TA::kReadsPerFrag,
+                         fa[buf][r / TA::kReadsPerFrag]);
+            else
+                TB::read(sb, wn * WN + ((r - kUnitsA) / TB::kReadsPerFrag) * 16 + l32, h, u,
+                         (r - kUnitsA) % TB::kReadsPerFrag, fb[buf][(r - kUnitsA) / TB::kReadsPerFrag]);
+        };
+#pragma unroll
+        for (int r = 0; r < kUnits; ++r) read_unit(0, r, 0);
+        int issued = 0;
+#pragma unroll
+        for (int u = 0; u < kGroups; ++u) {
+            const int cur = u & 1;
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int i = 0; i < MT; ++i)
+#pragma unroll
+                    for (int j = 0; j < NTL; ++j) {
+                        const int m = (s * MT + i) * NTL + j;
+                        acc[i][j] = mfma_f64_16x16x4(fa[cur][i][s], fb[cur][j][s], acc[i][j]);
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (u + 1 < kGroups) {
+#pragma unroll
+                            for (int q = 0; q < kPerSlot; ++q)
+                                if (m * kPerSlot + q < kUnits) read_unit(cur ^ 1, m * kPerSlot + q, u + 1);
+                        }
+                        const int slot = u * kMfma + m;
+                        if (PREFETCH && issued < kPerTile && slot * kPerTile >= issued * (kGroups * kMfma)) {
+                            issue_one(nbase, ab, bb, issued);
+                            ++issued;
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+        }
+        if (PREFETCH) walk.advance();
+    };
+
+    // Prologue: STAGES-1 tiles in flight.
+#pragma unroll
+    for (int p = 0; p < STAGES - 1; ++p)
+        if (p < n_ktiles) issue_all(p);
+
+    // k-tile kt is multiplied from stage kt % STAGES.  Before that, its loads must have landed
+    // (only the loads of the younger tile may still be outstanding) and every wavefront must be
+    // past tile kt-1, whose stage then receives tile kt+2.
+    int stage = 0;
+    int kt = 0;
+    for (; kt + STAGES - 1 < n_ktiles; ++kt) {
+        wait_vmcnt<kPerTile>();
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        multiply(stage, stage == 0 ? STAGES - 1 : stage - 1, std::true_type{});
+        asm volatile("" ::: "memory");
+        stage = stage == STAGES - 1 ? 0 : stage + 1;
+    }
+    if (kt + 1 < n_ktiles) {
+        wait_vmcnt<kPerTile>();
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        multiply(stage, 0, std::false_type{});
+        asm volatile("" ::: "memory");
+        stage = stage == STAGES - 1 ? 0 : stage + 1;
+    }
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    multiply(stage, 0, std::false_type{});
+}
+
+}  // namespace f64p
+}  // namespace dm

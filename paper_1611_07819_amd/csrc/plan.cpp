@@ -593,7 +593,7 @@ size_t conv_choice_bytes(int mode, const ConvGeom& g, const ConvChoice& c, dmath
     size_t bytes = 0;
     if (c.kernel == 1 && mode == CONV_BWD_FILTER) {
         const ConvFastLayout l = conv_fast_layout(mode, g, in_dtype);
-        bytes += (size_t)c.split_k * l.kp * l.cp * g.r * g.s * 4;
+        bytes += (size_t)c.split_k * l.kp * l.cp * g.r * g.s * (in_dtype == DMATH_F64 ? 8 : 4);
     } else if (mode == CONV_BWD_FILTER && c.split_k > 1) {
         bytes += (size_t)c.split_k * g.k * crs * (in_dtype == DMATH_F64 ? 8 : 4);
     }

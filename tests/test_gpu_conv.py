@@ -163,9 +163,9 @@ FAST_GEOMS = [
 
 
 @pytest.mark.parametrize("g", FAST_GEOMS)
-@pytest.mark.parametrize("dt,out", [(dm.F16, dm.F32), (dm.F16, dm.F16), (dm.F32, dm.F32)])
+@pytest.mark.parametrize("dt,out", [(dm.F16, dm.F32), (dm.F16, dm.F16), (dm.F32, dm.F32), (dm.F64, dm.F64)])
 def test_specialised_conv_whole_result(ctx, oracle, g, dt, out):
-    """All three modes on the specialised path (fp16 and fp32 pipelines) against the oracle:
+    """All three modes on the specialised path (fp16, fp32 and fp64 pipelines) against the oracle:
     within the precision's bar on random data (alpha/beta exercised) and bit for bit on
     small-integer data with a row-blocked layout of every tensor."""
     grids = {"X": (1, 1), "F": (1, 1), "Y": (1, 1)}
@@ -232,7 +232,7 @@ def test_random_geometries_against_oracle(ctx, oracle, seed):
     ctx.set_kernel_policy(0)
     for case in range(4):
         if case == 3:
-            # fp16 or fp32 with channel and filter counts just below multiples of 64, any plane
+            # any precision with channel and filter counts just below multiples of 64, any plane
             # size, strides and pads: the specialised kernels with padded copies and ragged tiles
             rr, ss = int(r.integers(1, 5)), int(r.integers(1, 5))
             g = dict(n=int(r.integers(1, 6)), c=int(r.integers(54, 65)) * int(r.integers(1, 3)),
@@ -240,7 +240,7 @@ def test_random_geometries_against_oracle(ctx, oracle, seed):
                      k=int(r.integers(54, 65)) * int(r.integers(1, 3)), r=rr, s=ss,
                      pad_h=int(r.integers(0, rr)), pad_w=int(r.integers(0, ss)),
                      stride_h=int(r.integers(1, 3)), stride_w=int(r.integers(1, 3)))
-            dt, out = [(dm.F16, dm.F32), (dm.F16, dm.F16), (dm.F32, dm.F32)][int(r.integers(0, 3))]
+            dt, out = [(dm.F16, dm.F32), (dm.F16, dm.F16), (dm.F32, dm.F32), (dm.F64, dm.F64)][int(r.integers(0, 4))]
         elif case == 2:
             rr, ss = int(r.integers(1, 4)), int(r.integers(1, 4))
             hw = [(8, 8), (16, 8), (16, 16), (12, 12), (14, 14), (10, 10)][int(r.integers(0, 6))]
@@ -267,7 +267,7 @@ def test_random_geometries_against_oracle(ctx, oracle, seed):
 
 @pytest.mark.parametrize("g", [dict(n=3, c=128, h=14, w=14, k=256, r=3, s=3, pad_h=1, pad_w=1),
                                dict(n=5, c=256, h=12, w=6, k=128, r=1, s=1)])
-@pytest.mark.parametrize("dt,out", [(dm.F16, dm.F32), (dm.F16, dm.F16), (dm.F32, dm.F32)])
+@pytest.mark.parametrize("dt,out", [(dm.F16, dm.F32), (dm.F16, dm.F16), (dm.F32, dm.F32), (dm.F64, dm.F64)])
 def test_specialised_conv_ragged_last_row_tile(ctx, oracle, g, dt, out):
     """n*oh*ow is not a multiple of the row tile, nor of the weight gradient's pixel tile:
     the last tile of the forward and of the data gradient is ragged (clamped gathers, masked

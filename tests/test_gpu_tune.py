@@ -94,7 +94,7 @@ def test_gemm_tune_counts_the_scratch_panels_of_k_tails(ctx, oracle):
 GEO = dict(n=4, c=128, h=16, w=16, k=256, r=3, s=3, pad_h=1, pad_w=1)
 
 
-@pytest.mark.parametrize("dt", [dm.F16, dm.F32])
+@pytest.mark.parametrize("dt", [dm.F16, dm.F32, dm.F64])
 def test_conv_tune_all_modes(ctx, oracle, dt):
     d, od = dm.ConvDesc(**GEO), oracle.ConvDesc(**GEO)
     r = np.random.default_rng(1101)
@@ -102,9 +102,10 @@ def test_conv_tune_all_modes(ctx, oracle, dt):
     hf = r.normal(0, 0.05, (256, 128 * 9)).astype(NP[dt])
     hy = r.normal(0, 0.1, (4, 256 * 256)).astype(NP[dt])
     X, F, dY = ctx.from_host(hx), ctx.from_host(hf), ctx.from_host(hy)
-    Y = ctx.matrix(4, 256 * 256, (1, 1), dm.F32)
-    dF = ctx.matrix(256, 128 * 9, (1, 1), dm.F32)
-    dX = ctx.matrix(4, 128 * 256, (1, 1), dm.F32)
+    out = dm.F64 if dt == dm.F64 else dm.F32
+    Y = ctx.matrix(4, 256 * 256, (1, 1), out)
+    dF = ctx.matrix(256, 128 * 9, (1, 1), out)
+    dX = ctx.matrix(4, 128 * 256, (1, 1), out)
     refs = {0: oracle.conv_fwd(od, 1.0, hx, hf), 1: oracle.conv_bwd_filter(od, 1.0, hx, hy),
             2: oracle.conv_bwd_data(od, 1.0, hy, hf)}
 
