@@ -372,14 +372,174 @@ template <class TC, int MODE> __device__ __forceinline__ TC* conv_c(const ConvTa
     return static_cast<TC*>(const_cast<void*>(t.x_rows[n])) + j * sp_in + sp;
 }
 
+// The gathers of one thread.  Every k-step the workgroup shares a table with the decomposition of
+// its 16 k indices (computed by 16 threads instead of by every thread for every element), and a
+// thread's own row or column of the lowered matrices is decomposed once.
+//   forward        : k = (c, r, s) -> table (c, r, s); A row = pixel (n, oh, ow) of this thread
+//   weight gradient: k = pixel     -> table (n, oh, ow); B columns (c, r, s) of this thread's slots
+//   data gradient  : k = (ko, r, s) -> table (ko, r, s); A row = input pixel (n, ih, iw)
+// Thread -> element maps: the unit-stride axis of the gathered tensor goes across lanes.
+// Decomposition of one k index, with the row pointers that go with it (weight gradient: the
+// image's rows of dY and X; data gradient: the filter's row).
+struct KEntry {
+    const void *p0, *p1;
+    int d0, d1, d2, pad;
+};
+
+template <class T, int MODE> struct ConvGather {
+    static constexpr int Q = GT * GK / GTHREADS;
+    static constexpr bool a_kfast = (MODE == CONV_BWD_FILTER);
+    static constexpr bool b_kfast = (MODE != CONV_BWD_DATA);
+    const ConvTables& t;
+    const KEntry (*kd)[GK];  // [2][GK] in LDS
+    int tid, kend;
+    // forward / data gradient: this thread's A row
+    const T* a_ptr;
+    int a0, a1;  // forward: ih0, iw0; data gradient: ih + pad_h, iw + pad_w
+    bool a_ok;
+    // per slot: forward B = filter row; weight gradient A = filter index, B = column (c, r, s);
+    // data gradient B = channel
+    const T* b_ptr[Q];
+    int row_q[Q], bc[Q], br[Q], bs[Q];
+    bool b_ok[Q], a_okq[Q];
+
+    __device__ __forceinline__ ConvGather(const ConvTables& t_, const KEntry (*kd_)[GK], int m0, int n0, int tid_,
+                                          int kend_)
+        : t(t_), kd(kd_), tid(tid_), kend(kend_)
+    {
+        const ConvGeom& g = t.g;
+        const int M = (int)t.M, N = (int)t.N;
+        a_ptr = nullptr;
+        a0 = a1 = 0;
+        a_ok = false;
+        if (MODE == CONV_FWD) {
+            const int m = m0 + tid % GT, sp_out = g.oh * g.ow;
+            a_ok = m < M;
+            if (a_ok) {
+                const int n = m / sp_out, sp = m % sp_out;
+                a_ptr = static_cast<const T*>(t.x_rows[n]);
+                a0 = (sp / g.ow) * g.stride_h - g.pad_h;
+                a1 = (sp % g.ow) * g.stride_w - g.pad_w;
+            }
+        } else if (MODE == CONV_BWD_DATA) {
+            const int m = m0 + tid % GT, sp_in = g.h * g.w;
+            a_ok = m < M;
+            if (a_ok) {
+                const int n = m / sp_in, sp = m % sp_in;
+                a_ptr = static_cast<const T*>(t.y_rows[n]);
+                a0 = sp / g.w + g.pad_h;
+                a1 = sp % g.w + g.pad_w;
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const int e = q * GTHREADS + tid;
+            b_ptr[q] = nullptr;
+            row_q[q] = bc[q] = br[q] = bs[q] = 0;
+            a_okq[q] = false;
+            if (MODE == CONV_FWD) {
+                const int j = n0 + e / GK;
+                b_ok[q] = j < N;
+                if (b_ok[q]) b_ptr[q] = static_cast<const T*>(t.f_rows[j]);
+            } else if (MODE == CONV_BWD_FILTER) {
+                row_q[q] = m0 + e / GK;  // filter index of the A element
+                a_okq[q] = row_q[q] < M;
+                const int j = n0 + e / GK, rs = g.r * g.s;
+                b_ok[q] = j < N;
+                if (b_ok[q]) {
+                    bc[q] = j / rs;
+                    br[q] = (j % rs) / g.s - g.pad_h;
+                    bs[q] = (j % rs) % g.s - g.pad_w;
+                }
+            } else {
+                row_q[q] = n0 + tid % GT;  // channel of the B element
+                b_ok[q] = row_q[q] < N;
+            }
+        }
+    }
+
+    // the shared decomposition of k-step k0, written into table `buf` by the first GK threads
+    __device__ __forceinline__ static void fill_table(const ConvTables& t, KEntry (*kd)[GK], int buf, int k0, int tid,
+                                                      int kend)
+    {
+        if (tid >= GK) return;
+        const ConvGeom& g = t.g;
+        const int kk = k0 + tid;
+        if (kk >= kend) return;  // never read
+        KEntry e{};
+        if (MODE == CONV_BWD_FILTER) {
+            const int sp_out = g.oh * g.ow, sp = kk % sp_out;
+            e.d0 = kk / sp_out;
+            e.d1 = sp / g.ow;
+            e.d2 = sp % g.ow;
+            e.p0 = t.y_rows[e.d0];
+            e.p1 = t.x_rows[e.d0];
+        } else {
+            const int rs = g.r * g.s, q = kk % rs;
+            e.d0 = kk / rs;
+            e.d1 = q / g.s;
+            e.d2 = q % g.s;
+            if (MODE == CONV_BWD_DATA) e.p0 = t.f_rows[e.d0];
+        }
+        kd[buf][tid] = e;
+    }
+
+    __device__ __forceinline__ T a(int q, int k0, int buf) const
+    {
+        const ConvGeom& g = t.g;
+        const int e = q * GTHREADS + tid;
+        const int kl = a_kfast ? e % GK : e / GT;
+        if (k0 + kl >= kend) return T(0);
+        const KEntry& k = kd[buf][kl];
+        const int d0 = k.d0, d1 = k.d1, d2 = k.d2;
+        if (MODE == CONV_FWD) {
+            if (!a_ok) return T(0);
+            const int ih = a0 + d1, iw = a1 + d2;
+            if (ih < 0 || ih >= g.h || iw < 0 || iw >= g.w) return T(0);
+            return a_ptr[(d0 * g.h + ih) * g.w + iw];
+        }
+        if (MODE == CONV_BWD_FILTER) {
+            // dY viewed as [k x (n, oh, ow)]
+            if (!a_okq[q]) return T(0);
+            return static_cast<const T*>(k.p0)[row_q[q] * (g.oh * g.ow) + d1 * g.ow + d2];
+        }
+        if (!a_ok) return T(0);
+        const int th = a0 - d1, tw = a1 - d2;
+        if (th < 0 || tw < 0 || th % g.stride_h || tw % g.stride_w) return T(0);
+        const int oy = th / g.stride_h, ox = tw / g.stride_w;
+        if (oy >= g.oh || ox >= g.ow) return T(0);
+        return a_ptr[(d0 * g.oh + oy) * g.ow + ox];
+    }
+
+    __device__ __forceinline__ T b(int q, int k0, int buf) const
+    {
+        const ConvGeom& g = t.g;
+        const int e = q * GTHREADS + tid;
+        const int kl = b_kfast ? e % GK : e / GT;
+        if (k0 + kl >= kend || !b_ok[q]) return T(0);
+        if (MODE == CONV_FWD) return b_ptr[q][k0 + kl];
+        const KEntry& k = kd[buf][kl];
+        const int d1 = k.d1, d2 = k.d2;
+        if (MODE == CONV_BWD_FILTER) {
+            const int ih = d1 * g.stride_h + br[q], iw = d2 * g.stride_w + bs[q];
+            if (ih < 0 || ih >= g.h || iw < 0 || iw >= g.w) return T(0);
+            return static_cast<const T*>(k.p1)[(bc[q] * g.h + ih) * g.w + iw];
+        }
+        return static_cast<const T*>(k.p0)[row_q[q] * (g.r * g.s) + d1 * g.s + d2];
+    }
+};
+
 template <class T, class TC, int MODE>
 __global__ __launch_bounds__(GTHREADS) void conv_generic_kernel(ConvTables t, int k_per_split,
                                                                 double alpha_d, double beta_d)
 {
     using AccT = typename Traits<T>::acc_t;
+    using Gather = ConvGather<T, MODE>;
     constexpr int S = Traits<T>::kStride;
+    constexpr int Q = Gather::Q;
     __shared__ __attribute__((aligned(16))) T As[GT * S];
     __shared__ __attribute__((aligned(16))) T Bs[GT * S];
+    __shared__ KEntry kd[2][GK];
     const int tiles_n = (int)((t.N + GT - 1) / GT);
     const int m0 = (blockIdx.x / tiles_n) * GT, n0 = (blockIdx.x % tiles_n) * GT;
     const int split = blockIdx.y;
@@ -390,60 +550,49 @@ __global__ __launch_bounds__(GTHREADS) void conv_generic_kernel(ConvTables t, in
     for (int r = 0; r < 16; ++r) acc.v[r] = AccT(0);
     const int kbeg = split * k_per_split;
     const int kend = min(K, kbeg + k_per_split);
-    // thread -> element maps: unit-stride axis of the gathered tensor goes across lanes
-    constexpr bool a_kfast = (MODE == CONV_BWD_FILTER);
-    constexpr bool b_kfast = (MODE != CONV_BWD_DATA);
+    const Gather gather(t, kd, m0, n0, tid, kend);
+    auto stash = [&](const T (&ra)[Q], const T (&rb)[Q]) {
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const int e = q * GTHREADS + tid;
+            if (Gather::a_kfast) As[(e / GK) * S + e % GK] = ra[q]; else As[(e % GT) * S + e / GT] = ra[q];
+            if (Gather::b_kfast) Bs[(e / GK) * S + e % GK] = rb[q]; else Bs[(e % GT) * S + e / GT] = rb[q];
+        }
+    };
+    auto fetch = [&](int k0, int buf, T (&ra)[Q], T (&rb)[Q]) {
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            ra[q] = gather.a(q, k0, buf);
+            rb[q] = gather.b(q, k0, buf);
+        }
+    };
+    T ra[Q], rb[Q];
+    Gather::fill_table(t, kd, 0, kbeg, tid, kend);
     if constexpr (sizeof(T) == 2) {
         // 16-bit elements: gathered where they are stored (gathering ahead was measured slower)
-        for (int k0 = kbeg; k0 < kend; k0 += GK) {
-#pragma unroll
-            for (int q = 0; q < GT * GK / GTHREADS; ++q) {
-                int e = q * GTHREADS + tid;
-                int row, kk;
-                if (a_kfast) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
-                T v = T(0);
-                if (m0 + row < M && k0 + kk < kend) v = conv_a<T, MODE>(t, m0 + row, k0 + kk);
-                As[row * S + kk] = v;
-                if (b_kfast) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
-                v = T(0);
-                if (n0 + row < N && k0 + kk < kend) v = conv_b<T, MODE>(t, k0 + kk, n0 + row);
-                Bs[row * S + kk] = v;
-            }
+        __syncthreads();
+        int buf = 0;
+        for (int k0 = kbeg; k0 < kend; k0 += GK, buf ^= 1) {
+            fetch(k0, buf, ra, rb);
+            stash(ra, rb);
+            Gather::fill_table(t, kd, buf ^ 1, k0 + GK, tid, kend);  // last read before the barrier below, one step ago
             __syncthreads();
             mma_step(As, Bs, wm, wn, lane, acc);
             __syncthreads();
         }
     } else {
         // the elements of k-step i+1 are gathered into registers while step i is multiplied out of
-        // LDS (fp32, fp64)
-        constexpr int Q = GT * GK / GTHREADS;
-        auto fetch = [&](int k0, T (&ra)[Q], T (&rb)[Q]) {
-#pragma unroll
-            for (int q = 0; q < Q; ++q) {
-                const int e = q * GTHREADS + tid;
-                int row, kk;
-                if (a_kfast) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
-                ra[q] = T(0);
-                if (m0 + row < M && k0 + kk < kend) ra[q] = conv_a<T, MODE>(t, m0 + row, k0 + kk);
-                if (b_kfast) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
-                rb[q] = T(0);
-                if (n0 + row < N && k0 + kk < kend) rb[q] = conv_b<T, MODE>(t, k0 + kk, n0 + row);
-            }
-        };
-        T ra[Q], rb[Q];
-        if (kbeg < kend) fetch(kbeg, ra, rb);
-        for (int k0 = kbeg; k0 < kend; k0 += GK) {
-#pragma unroll
-            for (int q = 0; q < Q; ++q) {
-                const int e = q * GTHREADS + tid;
-                int row, kk;
-                if (a_kfast) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
-                As[row * S + kk] = ra[q];
-                if (b_kfast) { kk = e % GK; row = e / GK; } else { row = e % GT; kk = e / GT; }
-                Bs[row * S + kk] = rb[q];
-            }
+        // LDS (fp32, fp64); the table of step i+2 is written meanwhile
+        Gather::fill_table(t, kd, 1, kbeg + GK, tid, kend);
+        __syncthreads();
+        if (kbeg < kend) fetch(kbeg, 0, ra, rb);
+        __syncthreads();  // table 0 is rewritten in the first iteration
+        int buf = 0;      // table of the step held in ra, rb
+        for (int k0 = kbeg; k0 < kend; k0 += GK, buf ^= 1) {
+            stash(ra, rb);
+            Gather::fill_table(t, kd, buf, k0 + 2 * GK, tid, kend);
             __syncthreads();
-            if (k0 + GK < kend) fetch(k0 + GK, ra, rb);
+            if (k0 + GK < kend) fetch(k0 + GK, buf ^ 1, ra, rb);
             mma_step(As, Bs, wm, wn, lane, acc);
             __syncthreads();
         }
