@@ -209,7 +209,8 @@ hipError_t launch_shape(const GemmPlan& p, float alpha, float beta, hipStream_t 
 }
 
 // Tile shapes: 256x256 (two 64 KiB stages), 256x128 (three 48 KiB stages), 128x128 (two 32 KiB
-// stages, so that two workgroups share a CU).
+// stages, so that two workgroups share a CU); 64x128 and 64x64 (three stages) for batches of at
+// most 64 rows, which are bound by streaming the other operand from HBM.
 template <class TC>
 hipError_t launch_out(const GemmPlan& p, float alpha, float beta, hipStream_t st)
 {
@@ -217,6 +218,8 @@ hipError_t launch_out(const GemmPlan& p, float alpha, float beta, hipStream_t st
     if (bm == 256 && bn == 256) return launch_shape<256, 256, 2, TC>(p, alpha, beta, st);
     if (bm == 256 && bn == 128) return launch_shape<256, 128, 3, TC>(p, alpha, beta, st);
     if (bm == 128 && bn == 128) return launch_shape<128, 128, 2, TC>(p, alpha, beta, st);
+    if (bm == 64 && bn == 128) return launch_shape<64, 128, 3, TC>(p, alpha, beta, st);
+    if (bm == 64 && bn == 64) return launch_shape<64, 64, 3, TC>(p, alpha, beta, st);
     return hipErrorInvalidValue;
 }
 

@@ -89,6 +89,10 @@ std::vector<Shape> specialised_shapes(const SegView& v)
         out.push_back({KERNEL_F16_256, 256, 256, 64, 1, 1.0});
         out.push_back({KERNEL_F16_256, 256, 128, 64, 1, 1.0});
         out.push_back({KERNEL_F16_256, 128, 128, 64, 2, 0.7});
+        if (few_rows(v)) {  // half the padding rows and half the partial sums of a 128-row tile
+            out.push_back({KERNEL_F16_256, 64, 128, 64, 2, 0.5});
+            out.push_back({KERNEL_F16_256, 64, 64, 64, 3, 0.4});
+        }
     }
     return out;
 }

@@ -299,7 +299,10 @@ def test_specialised_kernels_whole_result(ctx, oracle, dt, mnk, grids, ta, tb):
 
 @pytest.mark.parametrize("dt,shape", [(dm.F16, "256x256"), (dm.F16, "256x128"), (dm.F16, "128x128"),
                                       (dm.F32, "128x128"), (dm.F32, "128x64"), (dm.F32, "128x96"),
-                                      (dm.F64, "128x128"), (dm.F64, "128x64")])
+                                      (dm.F64, "128x128"), (dm.F64, "128x64"),
+                                      # the shapes offered to batches of at most 64 rows
+                                      (dm.F16, "64x128"), (dm.F16, "64x64"), (dm.F32, "64x128"),
+                                      (dm.F32, "64x256"), (dm.F64, "64x128")])
 @pytest.mark.parametrize("ta,tb", OPS)
 def test_every_tile_shape_of_the_specialised_kernels(ctx, oracle, dt, shape, ta, tb, monkeypatch):
     """The scheduler normally picks the tile shape by cost; DMATH_TILE pins it, so that every
@@ -310,6 +313,8 @@ def test_every_tile_shape_of_the_specialised_kernels(ctx, oracle, dt, shape, ta,
     monkeypatch.setenv("DMATH_TILE", shape)
     r = np.random.default_rng(500)
     M, N, K = 512, (576 if shape == "128x96" else 768), 448 if dt != dm.F16 else 448 + 64 * 3
+    if shape.startswith("64x"):
+        M = 128 - 16                     # two row blocks of 56 rows: ragged 64-row tiles, 16-byte aligned when stored transposed
     opA = r.integers(-2, 3, (M, K)).astype(NP[dt])
     opB = r.integers(-2, 3, (K, N)).astype(NP[dt])
     C0 = r.integers(-3, 4, (M, N)).astype(NP[dt])
