@@ -193,3 +193,45 @@ def test_size_limits(ctx):
     with pytest.raises(dm.DmathError) as e:
         ctx.matrix(1 << 31, 1, (1, 1), dm.F16)
     assert e.value.code == 7
+
+
+def test_scheduler_pads_k_tails_and_counts_their_scratch(ctx):
+    """K = 1000 is not a multiple of the fp32 kernels' k-step of 32: the plan keeps a specialised
+    kernel, cuts the last 8 of K off as a segment of its own and reports the zero-padded scratch
+    panels it reads them from ([M][32] for the k-major A, [32][N rounded up to 64] for B)."""
+    A = ctx.matrix(256, 1000, (1, 1), dm.F32)
+    B = ctx.matrix(1000, 384, (1, 1), dm.F32)
+    C = ctx.matrix(256, 384, (1, 1), dm.F32)
+    p = dm.gemm_plan_info(ctx, 0, 0, A, B, C)
+    assert p["kernel"] != 0 and p["tile_k"] == 32
+    # the segments are [0, 992) and [992, 1000), the first possibly cut further by split-K
+    assert p["k_segments"] == p["split_k"] + 1
+    partials = p["split_k"] * 256 * 384 * 4 if p["split_k"] > 1 else 0
+    assert p["workspace_bytes"] == partials + (256 + 384) * 32 * 4
+    # rows of 1001 floats are not 16-byte aligned: the guarded generic kernel, no scratch
+    A1 = ctx.matrix(256, 1001, (1, 1), dm.F32)
+    B1 = ctx.matrix(1001, 384, (1, 1), dm.F32)
+    p = dm.gemm_plan_info(ctx, 0, 0, A1, B1, C)
+    assert p["kernel"] == 0 and p["k_segments"] == 1
+    # a K of fewer than four k-steps is left to the generic kernel as well
+    A2 = ctx.matrix(256, 100, (1, 1), dm.F32)
+    B2 = ctx.matrix(100, 384, (1, 1), dm.F32)
+    assert dm.gemm_plan_info(ctx, 0, 0, A2, B2, C)["kernel"] == 0
+
+
+def test_scheduler_choices_for_small_problems(ctx):
+    """Where one round of tiles does not fill the 256 CUs the time model splits K (down to 128 of
+    K per part), and a batch of at most 64 rows gets 64-row tiles."""
+    A = ctx.matrix(512, 512, (1, 1), dm.F32)
+    B = ctx.matrix(512, 512, (1, 1), dm.F32)
+    C = ctx.matrix(512, 512, (1, 1), dm.F32)
+    p = dm.gemm_plan_info(ctx, 0, 0, A, B, C)
+    assert p["kernel"] != 0 and 2 <= p["split_k"] <= 4 and p["tiles"] * p["split_k"] <= 512
+    big = dm.Context(FAKE_SLAB, 8 << 30)
+    for dt in (dm.F16, dm.F32, dm.F64):
+        X = big.matrix(64, 4096, (1, 1), dt)
+        W = big.matrix(4096, 4096, (1, 1), dt)
+        Y = big.matrix(64, 4096, (1, 1), dm.F32 if dt == dm.F16 else dt)
+        p = dm.gemm_plan_info(big, 0, 0, X, W, Y)
+        assert p["kernel"] != 0 and p["tile_m"] == 64 and p["split_k"] > 1
+    big.close()
