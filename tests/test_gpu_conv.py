@@ -118,18 +118,36 @@ def test_config5_full_size_sampled(ctx, oracle, out):
     _config5(ctx, oracle, w, [0, 37, 63], [1, 200])
 
 
-def _config5(ctx, oracle, w, images, filters):
+@pytest.mark.parametrize("dt", [dm.F32, dm.F64])
+def test_config5_geometry_full_size_sampled_in_the_wider_precisions(ctx, oracle, dt):
+    """The configuration-5 layer with its tensors widened to fp32 / fp64 (the launch
+    configuration that the benchmark's cfg5_as_f32 lines time), sampled images and filters."""
+    w = synth.config5("f32")
+    mats = {k: v.astype(NP[dt]) for k, v in w.mats.items()}
+    _config5(ctx, oracle, w, [0, 37, 63], [1, 200], mats=mats, dt=dt)
+
+
+def _config5(ctx, oracle, w, images, filters, mats=None, dt=dm.F16):
+    """Forward, weight gradient and data gradient of the layer against the oracle (all outputs,
+    or the sampled images / filters)."""
+    mats = w.mats if mats is None else mats
     d = dm.ConvDesc(**w.conv)
     od = oracle.ConvDesc(**w.conv)
-    dev = {k: ctx.from_host(v) for k, v in w.mats.items()}
+    dev = {k: ctx.from_host(v) for k, v in mats.items()}
     dm.conv_fwd(ctx, d, 1.0, dev["X"], dev["F"], 0.0, dev["Y"])
     got = dev["Y"].get()
-    ref = oracle.conv_fwd(od, 1.0, w.mats["X"], w.mats["F"], images=images)
-    assert rel_fro(got if images is None else got[images], ref) <= TOL[dm.F16]
+    ref = oracle.conv_fwd(od, 1.0, mats["X"], mats["F"], images=images)
+    assert rel_fro(got if images is None else got[images], ref) <= TOL[dt]
     dm.conv_bwd_filter(ctx, d, 1.0, dev["X"], dev["dY"], 0.0, dev["dF"])
     got = dev["dF"].get()
-    ref = oracle.conv_bwd_filter(od, 1.0, w.mats["X"], w.mats["dY"], filters=filters)
-    assert rel_fro(got if filters is None else got[filters], ref) <= TOL[dm.F16]
+    ref = oracle.conv_bwd_filter(od, 1.0, mats["X"], mats["dY"], filters=filters)
+    assert rel_fro(got if filters is None else got[filters], ref) <= TOL[dt]
+    dX = ctx.matrix(dev["X"].rows, dev["X"].cols, (1, 1), dev["Y"].dtype)
+    dm.conv_bwd_data(ctx, d, 1.0, dev["dY"], dev["F"], 0.0, dX)
+    got = dX.get()
+    ref = oracle.conv_bwd_data(od, 1.0, mats["dY"], mats["F"], images=images)
+    assert rel_fro(got if images is None else got[images], ref) <= TOL[dt]
+    dX.destroy()
     for m in dev.values():
         m.destroy()
 
