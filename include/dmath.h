@@ -257,7 +257,8 @@ dmath_status_t dmath_matrix_touch(dmath_matrix_t m);
 typedef struct dmath_tune_result {
     int32_t candidates;       /* configurations timed */
     int32_t skipped;          /* configurations left out for memory */
-    int32_t kernel;           /* chosen: kernel family (0 generic), */
+    int32_t kernel;           /* chosen: kernel family (0 generic; convolutions: 1 gathering
+                                 MFMA kernels, 2 a 1x1 convolution run as a block GEMM), */
     int32_t tile_m, tile_n;   /*   tile shape, */
     int32_t split_k;          /*   split-K parts, */
     uint64_t workspace_bytes; /*   pool memory beyond the operands */

@@ -596,6 +596,9 @@ dmath_status_t dmath_conv_tune(dmath_ctx_t ctx, int32_t mode, const dmath_conv_d
         });
         for (Relayout* r : {plan->xp, plan->fp, plan->yt})
             if (r) r->version = 0;  // written outside the version bookkeeping: never trusted
+        const int32_t gemm_tile_m = plan->gemm ? plan->gemm->info.tile_m : 0;
+        const int32_t gemm_tile_n = plan->gemm ? plan->gemm->info.tile_n : 0;
+        const int32_t gemm_split = plan->gemm ? plan->gemm->info.split_k : 1;
         free_conv_plan(ctx, *plan);
         if (us < 0) return DMATH_ERR_DEVICE;
         ++result->candidates;
@@ -607,9 +610,9 @@ dmath_status_t dmath_conv_tune(dmath_ctx_t ctx, int32_t mode, const dmath_conv_d
             best = us * handicap;
             best_choice = c;
             result->kernel = c.kernel;
-            result->tile_m = c.kernel == 1 ? c.tile_m : 64;
-            result->tile_n = c.kernel == 1 ? c.tile_n : 64;
-            result->split_k = c.split_k;
+            result->tile_m = c.kernel == 1 ? c.tile_m : c.kernel == 2 ? gemm_tile_m : 64;
+            result->tile_n = c.kernel == 1 ? c.tile_n : c.kernel == 2 ? gemm_tile_n : 64;
+            result->split_k = c.kernel == 2 ? gemm_split : c.split_k;
             result->workspace_bytes = need;
             result->chosen_us = us;
         }

@@ -99,7 +99,10 @@ struct ConvPlan {
     Relayout* xp = nullptr;  // gathered activations, channels-last with zero border
     Relayout* fp = nullptr;  // permuted filter
     Relayout* yt = nullptr;  // weight gradient: dY channels-last, [n*oh*ow][k]
-    int32_t kernel = 0;  // 0 generic, 1 specialised (fp16 or fp32 MFMA pipeline)
+    // 0 generic, 1 specialised (gathering MFMA kernels over re-layout copies), 2 as a block GEMM
+    // (1x1, stride 1, no padding: the images are the column blocks of a k x c by c x n*h*w product)
+    int32_t kernel = 0;
+    std::unique_ptr<GemmPlan> gemm;  // kernel 2
     int32_t tile_n = 0;  // specialised forward / data gradient: 128 or 256 output channels per tile
     int32_t tile_m = 0;  //   and 256 or 224 pixels
     dmath_dtype_t in_dtype = DMATH_F16, out_dtype = DMATH_F32;
@@ -188,6 +191,8 @@ struct ConvFastLayout {
 };
 ConvFastLayout conv_fast_layout(int mode, const ConvGeom& g, dmath_dtype_t in_dtype);
 bool conv_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype);
+// A 1x1 convolution with stride 1 and no padding that is better run as a block GEMM.
+bool conv_as_gemm_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype);
 int conv_fast_wgrad_split(const ConvGeom& g, dmath_dtype_t in_dtype);
 hipError_t launch_conv_fast(const ConvPlan& p, int mode, double alpha, double beta, unsigned rewrite,
                            hipStream_t st);

@@ -577,6 +577,20 @@ bool conv_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype)
     return true;
 }
 
+// A 1x1 convolution with stride 1 and no padding is, image by image, Y_n[k x hw] = F[k x c] *
+// X_n[c x hw] on the tensors as they lie in memory (dX_n = F^T * dY_n; dF = sum over the images
+// of dY_n * X_n^T, the images being the k-segments): a block GEMM with one column block per
+// image.  No copy is made.  Taken where the rows of a plane and of the filter are 16-byte aligned
+// and a plane is either a whole number of 64-element tiles or large enough for its ragged last
+// tile (weight gradient: its padded k-tail) not to matter.
+bool conv_as_gemm_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype)
+{
+    if (g.r != 1 || g.s != 1 || g.stride_h != 1 || g.stride_w != 1 || g.pad_h != 0 || g.pad_w != 0) return false;
+    const int64_t sp = (int64_t)g.h * g.w, eb = elem_bytes(in_dtype);
+    if ((sp * eb) % 16 != 0 || ((int64_t)g.c * eb) % 16 != 0) return false;
+    return sp % 64 == 0 || sp >= 512;
+}
+
 // C tiles of the weight gradient: 256 (fp16 only), 128 or 64 filters x 128 columns of (r,s,c)
 // (64 where the channel count is not a multiple of 128: a tile's columns are consecutive
 // channels of one tap).
@@ -668,6 +682,10 @@ static std::vector<FwdShape> fwd_shapes(dmath_dtype_t dt, int n_out)
 ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int32_t policy)
 {
     ConvChoice ch;
+    if (policy == 0 && conv_as_gemm_ok(mode, g, in_dtype)) {
+        ch.kernel = 2;  // tile shape and split are the GEMM chooser's
+        return ch;
+    }
     if (policy != 0 || !conv_fast_ok(mode, g, in_dtype)) {
         if (mode == CONV_BWD_FILTER) ch.split_k = generic_wgrad_split(g);
         return ch;
@@ -722,6 +740,11 @@ std::vector<ConvChoice> conv_candidates(int mode, const ConvGeom& g, dmath_dtype
     out.push_back(c);
     if (mode == CONV_BWD_FILTER && generic_wgrad_split(g) > 1) {
         c.split_k = generic_wgrad_split(g);
+        out.push_back(c);
+    }
+    if (policy == 0 && conv_as_gemm_ok(mode, g, in_dtype)) {
+        c = ConvChoice{};
+        c.kernel = 2;
         out.push_back(c);
     }
     if (policy != 0 || !conv_fast_ok(mode, g, in_dtype)) return out;

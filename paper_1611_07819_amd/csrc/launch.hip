@@ -225,6 +225,7 @@ hipError_t launch_gemm(const GemmPlan& p, double alpha, double beta, hipStream_t
 
 hipError_t launch_conv(const ConvPlan& p, int mode, double alpha, double beta, unsigned rewrite, hipStream_t st)
 {
+    if (p.kernel == 2 && alpha != 0.0 && p.gemm) return launch_gemm(*p.gemm, alpha, beta, st);
     if (p.kernel == 1 && alpha != 0.0) return launch_conv_fast(p, mode, alpha, beta, rewrite, st);
     return launch_conv_generic(p, mode, alpha, beta, st);
 }

@@ -86,6 +86,10 @@ void free_conv_plan(dmath_ctx_s* ctx, ConvPlan& p)
             *q = nullptr;
         }
     p.xp = p.fp = p.yt = nullptr;  // the copies belong to the context's table
+    if (p.gemm) {
+        free_gemm_plan(ctx, *p.gemm);
+        p.gemm.reset();
+    }
 }
 
 // The copy of matrix `src` in the given layout: found, or allocated (zeroed once: the border of a
@@ -591,6 +595,7 @@ size_t conv_choice_bytes(int mode, const ConvGeom& g, const ConvChoice& c, dmath
 {
     const size_t sp_out = (size_t)g.oh * g.ow, crs = (size_t)g.c * g.r * g.s;
     size_t bytes = 0;
+    if (c.kernel == 2) return 0;  // no copies; its GEMM plan takes partial sums only for tiny outputs
     if (c.kernel == 1 && mode == CONV_BWD_FILTER) {
         const ConvFastLayout l = conv_fast_layout(mode, g, in_dtype);
         bytes += (size_t)c.split_k * l.kp * l.cp * g.r * g.s * (in_dtype == DMATH_F64 ? 8 : 4);
@@ -704,6 +709,40 @@ dmath_status_t make_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_
     t.workspace = ws;
     plan->dev_tables = dev;
     plan->workspace = ws;
+    if (ch.kernel == 2) {
+        // 1x1, stride 1, no padding: image i of a tensor with `channels` channels is a dense
+        // [channels x h*w] matrix where it lies, so the tensor is a [channels x n*h*w] block matrix
+        // with one column block per image, and F is [k x c] as stored:
+        //   forward:         Y (k x n*hw) = F * X (c x n*hw)
+        //   data gradient:  dX (c x n*hw) = F^T * dY (k x n*hw)
+        //   weight gradient: dF (k x c)   = dY (k x n*hw) * X^T (n*hw x c), one k-segment per image
+        auto images_as_blocks = [&](const dmath_matrix_s* m, int64_t channels) {
+            dmath_matrix_s v;
+            v.ctx = ctx;
+            v.id = m->id;
+            v.rows = channels;
+            v.cols = g.n * sp_in;
+            v.rsplit = Split(channels, 1);
+            v.csplit = Split(g.n * sp_in, g.n);
+            v.dtype = m->dtype;
+            for (const void* row : row_ptrs(m)) v.blocks.push_back(const_cast<void*>(row));
+            return v;
+        };
+        dmath_matrix_s xs = images_as_blocks(X, g.c), ys = images_as_blocks(Y, g.k);
+        std::unique_ptr<GemmPlan> gp;
+        auto make = [&](bool unsplit) {
+            if (mode == CONV_FWD) return make_gemm_plan(ctx, 0, 0, F, &xs, &ys, true, nullptr, &gp, nullptr, unsplit);
+            if (mode == CONV_BWD_DATA) return make_gemm_plan(ctx, 1, 0, F, &ys, &xs, true, nullptr, &gp, nullptr, unsplit);
+            return make_gemm_plan(ctx, 0, 1, &ys, &xs, F, true, nullptr, &gp, nullptr, unsplit);
+        };
+        dmath_status_t st = make(false);
+        if (st == DMATH_ERR_OOM) st = make(true);
+        if (st != DMATH_OK) {
+            free_conv_plan(ctx, *plan);
+            return st;
+        }
+        plan->gemm = std::move(gp);
+    }
     *out = std::move(plan);
     return DMATH_OK;
 }

@@ -152,6 +152,17 @@ def _config5(ctx, oracle, w, images, filters, mats=None, dt=dm.F16):
         m.destroy()
 
 
+def runs_as_block_gemm(g, dt):
+    """1x1, stride 1, no padding, 16-byte aligned planes and filter rows, planes that are whole
+    64-element tiles or large: all three modes are block GEMMs on the tensors as they lie, with
+    one column block (weight gradient: one k-segment) per image and no re-layout copies."""
+    es = {dm.F16: 2, dm.F32: 4, dm.F64: 8}[dt]
+    sp = g["h"] * g["w"]
+    return (g["r"] == 1 and g["s"] == 1 and g.get("stride_h", 1) == 1 and g.get("stride_w", 1) == 1 and
+            g.get("pad_h", 0) == 0 and g.get("pad_w", 0) == 0 and (sp * es) % 16 == 0 and
+            (g["c"] * es) % 16 == 0 and (sp % 64 == 0 or sp >= 512))
+
+
 FAST_GEOMS = [
     # geometries that run on the specialised kernels
     dict(n=4, c=128, h=16, w=16, k=256, r=3, s=3, pad_h=1, pad_w=1),
@@ -177,6 +188,11 @@ FAST_GEOMS = [
     dict(n=2, c=64, h=27, w=27, k=128, r=5, s=5, pad_h=2, pad_w=2),
     dict(n=5, c=120, h=9, w=11, k=120, r=3, s=2, pad_h=1, pad_w=0, stride_h=2, stride_w=1),
     dict(n=16, c=64, h=13, w=13, k=64, r=3, s=3, pad_h=1, pad_w=1),       # 43 pixel tiles in 5 uneven parts
+    # 1x1, stride 1, no padding: block GEMMs with one column block per image (planes of 576 pixels:
+    # ragged last column tile, and a k-tail per image in the weight gradient; 56 channels: a k-tail
+    # in the forward pass)
+    dict(n=3, c=128, h=24, w=24, k=192, r=1, s=1),
+    dict(n=2, c=56, h=32, w=16, k=120, r=1, s=1),
 ]
 
 
@@ -190,7 +206,7 @@ def test_specialised_conv_whole_result(ctx, oracle, g, dt, out):
     before = ctx.relayout_stats()["written"]
     res = three_modes(ctx, oracle, g, dt, out, 1.5, -0.5, grids, policy=0)
     # every mode went through the specialised kernels: each re-laid-out its two operands
-    assert ctx.relayout_stats()["written"] - before == 6
+    assert ctx.relayout_stats()["written"] - before == (0 if runs_as_block_gemm(g, dt) else 6)
     for mode in ("fwd", "bwd_filter", "bwd_data"):
         got, ref = res[mode]
         assert rel_fro(got, ref) <= TOL[dt], mode
