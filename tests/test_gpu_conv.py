@@ -154,13 +154,13 @@ def _config5(ctx, oracle, w, images, filters, mats=None, dt=dm.F16):
 
 def runs_as_block_gemm(g, dt):
     """1x1, stride 1, no padding, 16-byte aligned planes and filter rows, planes that are whole
-    64-element tiles or large: all three modes are block GEMMs on the tensors as they lie, with
+    64-element tiles or nearly: all three modes are block GEMMs on the tensors as they lie, with
     one column block (weight gradient: one k-segment) per image and no re-layout copies."""
     es = {dm.F16: 2, dm.F32: 4, dm.F64: 8}[dt]
     sp = g["h"] * g["w"]
     return (g["r"] == 1 and g["s"] == 1 and g.get("stride_h", 1) == 1 and g.get("stride_w", 1) == 1 and
             g.get("pad_h", 0) == 0 and g.get("pad_w", 0) == 0 and (sp * es) % 16 == 0 and
-            (g["c"] * es) % 16 == 0 and (sp % 64 == 0 or sp >= 512))
+            (g["c"] * es) % 16 == 0 and (sp + 63) // 64 * 64 * 100 <= sp * 135)
 
 
 FAST_GEOMS = [
