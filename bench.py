@@ -205,6 +205,24 @@ def main():
         ctx.set_relayout_reuse(True)
         for m in d5.values():
             m.destroy()
+        # a 1x1 stride-1 layer (n=64, 256 -> 512 channels, 28x28, fp16): run as a block GEMM on the
+        # tensors as they lie, one column block per image, no re-layout copies
+        g1 = dict(n=64, c=256, h=28, w=28, k=512, r=1, s=1)
+        d1 = dm.ConvDesc(**g1)
+        x1 = ctx.from_host(rs.uniform(0, 1, (64, 256 * 784)).astype(np.float16))
+        f1 = ctx.from_host(rs.normal(0, 0.06, (512, 256)).astype(np.float16))
+        y1 = ctx.from_host(rs.normal(0, 0.1, (64, 512 * 784)).astype(np.float16))
+        o1 = {"Y": ctx.matrix(64, 512 * 784, (1, 1), dm.F32), "dF": ctx.matrix(512, 256, (1, 1), dm.F32),
+              "dX": ctx.matrix(64, 256 * 784, (1, 1), dm.F32)}
+        fl1 = 2.0 * 64 * 784 * 512 * 256
+        for name, f in [("fwd", lambda: dm.conv_fwd(ctx, d1, 1.0, x1, f1, 0.0, o1["Y"])),
+                        ("bwd_filter", lambda: dm.conv_bwd_filter(ctx, d1, 1.0, x1, y1, 0.0, o1["dF"])),
+                        ("bwd_data", lambda: dm.conv_bwd_data(ctx, d1, 1.0, y1, f1, 0.0, o1["dX"]))]:
+            ms, _ = time_calls([f], 10, 3)
+            calls[f"conv1x1_f16.{name}"] = {"ms": round(ms, 4), "tflops": round(fl1 / ms / 1e9, 2),
+                                            "frac_peak": round(fl1 / ms / 1e9 / PEAK_TFLOPS["f16"], 4)}
+        for m in [x1, f1, y1] + list(o1.values()):
+            m.destroy()
         # K that is not a multiple of the kernels' k-step: data gradient of a 4096 -> 1000 layer at
         # batch 1024 (K = 1000 goes through zero-padded scratch panels)
         for tag, code, npdt in (("f32", dm.F32, np.float32), ("f16", dm.F16, np.float16)):
