@@ -591,6 +591,13 @@ dmath_status_t dmath_conv_tune(dmath_ctx_t ctx, int32_t mode, const dmath_conv_d
             continue;
         }
         if (st != DMATH_OK) return st;
+        // a convolution run as a block GEMM takes what its GEMM plan takes (partial sums, k-tails)
+        const size_t taken = plan->gemm ? (size_t)plan->gemm->info.workspace_bytes : need;
+        if (taken > workspace_limit) {
+            free_conv_plan(ctx, *plan);
+            ++result->skipped;
+            continue;
+        }
         const double us = sample_us(ctx, ev.e0, ev.e1, trials, result->candidates ? 3e3 : 2e4, [&] {
             return launch_conv(*plan, mode, 1.0, 0.0, REWRITE_X | REWRITE_F | REWRITE_Y, ctx->stream);
         });
@@ -613,7 +620,7 @@ dmath_status_t dmath_conv_tune(dmath_ctx_t ctx, int32_t mode, const dmath_conv_d
             result->tile_m = c.kernel == 1 ? c.tile_m : c.kernel == 2 ? gemm_tile_m : 64;
             result->tile_n = c.kernel == 1 ? c.tile_n : c.kernel == 2 ? gemm_tile_n : 64;
             result->split_k = c.kernel == 2 ? gemm_split : c.split_k;
-            result->workspace_bytes = need;
+            result->workspace_bytes = taken;
             result->chosen_us = us;
         }
     }

@@ -142,6 +142,36 @@ def test_conv_tune_all_modes(ctx, oracle, dt):
         assert rel_fro(run(mode), refs[mode]) <= TOL[dt], mode
 
 
+def test_conv_tune_of_a_1x1_layer_counts_what_its_block_gemm_takes(ctx, oracle):
+    """A 1x1 stride-1 layer can run as a block GEMM without re-layout copies; its weight gradient
+    is a deep split-K GEMM whose partial sums (and padded k-tails) come from the pool and count
+    against the limit."""
+    geo = dict(n=8, c=128, h=24, w=24, k=128, r=1, s=1)
+    d, od = dm.ConvDesc(**geo), oracle.ConvDesc(**geo)
+    r = np.random.default_rng(1104)
+    hx = r.uniform(0, 1, (8, 128 * 576)).astype(np.float16)
+    hf = r.normal(0, 0.05, (128, 128)).astype(np.float16)
+    hy = r.normal(0, 0.1, (8, 128 * 576)).astype(np.float16)
+    X, F, dY = ctx.from_host(hx), ctx.from_host(hf), ctx.from_host(hy)
+    Y = ctx.matrix(8, 128 * 576, (1, 1), dm.F32)
+    dF = ctx.matrix(128, 128, (1, 1), dm.F32)
+    # forward: the block GEMM needs nothing from the pool and is a candidate even with no memory
+    t = dm.conv_tune(ctx, 0, d, X, F, Y, 0, trials=2)
+    assert t["candidates"] >= 2 and t["workspace_bytes"] == 0
+    dm.conv_fwd(ctx, d, 1.0, X, F, 0.0, Y)
+    assert rel_fro(Y.get(), oracle.conv_fwd(od, 1.0, hx, hf)) <= TOL[dm.F16]
+    # weight gradient: with no memory only configurations without partial sums remain
+    t0 = dm.conv_tune(ctx, 1, d, X, dF, dY, 0, trials=2)
+    assert t0["workspace_bytes"] == 0 and t0["skipped"] >= 1
+    dm.conv_bwd_filter(ctx, d, 1.0, X, dY, 0.0, dF)
+    assert rel_fro(dF.get(), oracle.conv_bwd_filter(od, 1.0, hx, hy)) <= TOL[dm.F16]
+    t1 = dm.conv_tune(ctx, 1, d, X, dF, dY, 1 << 28, trials=2)
+    assert t1["candidates"] > t0["candidates"] and t1["chosen_us"] <= t0["chosen_us"] * 1.05
+    dm.conv_bwd_filter(ctx, d, 1.0, X, dY, 0.0, dF)
+    assert rel_fro(dF.get(), oracle.conv_bwd_filter(od, 1.0, hx, hy)) <= TOL[dm.F16]
+    ctx.tune_reset()
+
+
 def test_tune_argument_errors(ctx):
     A, B = ctx.matrix(128, 128, (1, 1), dm.F32), ctx.matrix(128, 128, (1, 1), dm.F32)
     C = ctx.matrix(128, 128, (1, 1), dm.F32)
