@@ -148,36 +148,60 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
         walk.advance();
     };
 
-    // Multiplies the tile in `stage`: 4 groups of 8 k, each group 4 MFMA steps on every pair of
-    // fragments.  While group u is multiplied the fragments of group u+1 are read (register
-    // double buffer), one read unit after each MFMA, and -- when PREFETCH -- the loads of the
-    // tile two ahead are spread over the MFMA slots.
-    auto multiply = [&](int stage, int next_stage, auto prefetch) {
-        constexpr bool PREFETCH = decltype(prefetch)::value;
-        constexpr int kGroups = BK / 8, kMfma = 2 * MT * NTL;
-        constexpr int kUnitsA = MT * TA::kReadsPerFrag, kUnits = kUnitsA + NTL * TB::kReadsPerFrag;
-        constexpr int kPerSlot = (kUnits + kMfma - 1) / kMfma;
-        static_assert(kGroups * kMfma >= kPerTile, "not enough slots to spread the loads");
-        const lds_char* sa = lds + stage * kStage;
+    // Ring protocol.  k-tile kt lives in stage kt % STAGES and is multiplied in groups of 8 k, each
+    // group 2 MFMA steps on every pair of fragments; the fragments of group u+1 are read from LDS
+    // while group u is multiplied (register double buffer), one read unit after each MFMA.
+    // Before the LAST group of tile kt every wavefront
+    //   - waits until its own loads of tile kt+1 have landed (s_waitcnt vmcnt),
+    //   - waits for its last fragment reads of tile kt (s_waitcnt lgkmcnt(0)),
+    //   - meets the others at the workgroup barrier.
+    // After that barrier tile kt+1 is visible to everybody and nobody reads tile kt's stage any
+    // more, so the last group of tile kt already reads the first fragments of tile kt+1 (no LDS
+    // latency is exposed at tile boundaries).  Tile kt+2 is fetched during the groups before
+    // that barrier into the stage of tile kt-1 (freed by the barrier of iteration kt-1); at the
+    // barrier only those loads may still be outstanding.
+    constexpr int kGroups = BK / 8, kMfma = 2 * MT * NTL;
+    constexpr int kUnitsA = MT * TA::kReadsPerFrag, kUnits = kUnitsA + NTL * TB::kReadsPerFrag;
+    constexpr int kPerSlot = (kUnits + kMfma - 1) / kMfma;
+    constexpr int kDmaSlots = (kGroups - 1) * kMfma;
+    static_assert(kGroups % 2 == 0, "the fragment double buffer returns to buffer 0 every tile");
+    static_assert(kDmaSlots >= kPerTile, "not enough slots to spread the loads");
+
+    v2d fa[2][MT], fb[2][NTL];
+    auto read_unit = [&](const lds_char* sa, int buf, int r, int u) {
         const lds_char* sb = sa + TA::kBytes;
-        const uint32_t nbase = lds0 + next_stage * kStage;
+        if (r < kUnitsA)
+            TA::read(sa, wm * WM + (r / TA::kReadsPerFrag) * 16 + l32, h, u, r % TA::kReadsPerFrag,
+                     fa[buf][r / TA::kReadsPerFrag]);
+        else
+            TB::read(sb, wn * WN + ((r - kUnitsA) / TB::kReadsPerFrag) * 16 + l32, h, u,
+                     (r - kUnitsA) % TB::kReadsPerFrag, fb[buf][(r - kUnitsA) / TB::kReadsPerFrag]);
+    };
+
+    // One iteration.  HAS_NEXT: tile kt+1 exists; HAS_DMA: tile kt+2 exists and is fetched.
+    auto iteration = [&](int stage, auto has_next, auto has_dma) {
+        constexpr bool HAS_NEXT = decltype(has_next)::value, HAS_DMA = decltype(has_dma)::value;
+        const int stage1 = stage + 1 == STAGES ? 0 : stage + 1;   // tile kt+1
+        const int stage2 = stage == 0 ? STAGES - 1 : stage - 1;   // tile kt+2 (= stage of tile kt-1)
+        const lds_char* sa = lds + stage * kStage;
+        const lds_char* sa1 = lds + stage1 * kStage;
+        const uint32_t dbase = lds0 + stage2 * kStage;
         const char* ab = uniform_ptr(walk.abase);
         const char* bb = uniform_ptr(walk.bbase);
-        v2d fa[2][MT], fb[2][NTL];
-        auto read_unit = [&](int buf, int r, int u) {
-            if (r < kUnitsA)
-                TA::read(sa, wm * WM + (r / TA::kReadsPerFrag) * 16 + l32, h, u, r % TA::kReadsPerFrag,
-                         fa[buf][r / TA::kReadsPerFrag]);
-            else
-                TB::read(sb, wn * WN + ((r - kUnitsA) / TB::kReadsPerFrag) * 16 + l32, h, u,
-                         (r - kUnitsA) % TB::kReadsPerFrag, fb[buf][(r - kUnitsA) / TB::kReadsPerFrag]);
-        };
-#pragma unroll
-        for (int r = 0; r < kUnits; ++r) read_unit(0, r, 0);
         int issued = 0;
 #pragma unroll
         for (int u = 0; u < kGroups; ++u) {
             const int cur = u & 1;
+            if (u == kGroups - 1 && HAS_NEXT) {
+                if (HAS_DMA)
+                    wait_vmcnt<kPerTile>();
+                else
+                    wait_vmcnt<0>();
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
+            }
 #pragma unroll
             for (int s = 0; s < 2; ++s)
 #pragma unroll
@@ -187,52 +211,51 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
                         const int m = (s * MT + i) * NTL + j;
                         acc[i][j] = mfma_f64_16x16x4(fa[cur][i][s], fb[cur][j][s], acc[i][j]);
                         __builtin_amdgcn_sched_barrier(0);
-                        if (u + 1 < kGroups) {
 #pragma unroll
-                            for (int q = 0; q < kPerSlot; ++q)
-                                if (m * kPerSlot + q < kUnits) read_unit(cur ^ 1, m * kPerSlot + q, u + 1);
+                        for (int q = 0; q < kPerSlot; ++q) {
+                            const int r = m * kPerSlot + q;
+                            if (r < kUnits) {
+                                if (u + 1 < kGroups)
+                                    read_unit(sa, cur ^ 1, r, u + 1);
+                                else if (HAS_NEXT)
+                                    read_unit(sa1, cur ^ 1, r, 0);
+                            }
                         }
                         const int slot = u * kMfma + m;
-                        if (PREFETCH && issued < kPerTile && slot * kPerTile >= issued * (kGroups * kMfma)) {
-                            issue_one(nbase, ab, bb, issued);
+                        if (HAS_DMA && u < kGroups - 1 && issued < kPerTile && slot * kPerTile >= issued * kDmaSlots) {
+                            issue_one(dbase, ab, bb, issued);
                             ++issued;
                         }
                         __builtin_amdgcn_sched_barrier(0);
                     }
         }
-        if (PREFETCH) walk.advance();
+        if (HAS_DMA) walk.advance();
     };
 
-    // Prologue: STAGES-1 tiles in flight.
-#pragma unroll
-    for (int p = 0; p < STAGES - 1; ++p)
-        if (p < n_ktiles) issue_all(p);
-
-    // k-tile kt is multiplied from stage kt % STAGES.  Before that, its loads must have landed
-    // (only the loads of the younger tile may still be outstanding) and every wavefront must be
-    // past tile kt-1, whose stage then receives tile kt+2.
-    int stage = 0;
-    int kt = 0;
-    for (; kt + STAGES - 1 < n_ktiles; ++kt) {
+    // Prologue: tiles 0 and 1 in flight, tile 0 landed and visible, its first fragments read.
+    issue_all(0);
+    if (n_ktiles > 1) {
+        issue_all(1);
         wait_vmcnt<kPerTile>();
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        multiply(stage, stage == 0 ? STAGES - 1 : stage - 1, std::true_type{});
-        asm volatile("" ::: "memory");
-        stage = stage == STAGES - 1 ? 0 : stage + 1;
+    } else {
+        wait_vmcnt<0>();
     }
-    if (kt + 1 < n_ktiles) {
-        wait_vmcnt<kPerTile>();
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        multiply(stage, 0, std::false_type{});
-        asm volatile("" ::: "memory");
-        stage = stage == STAGES - 1 ? 0 : stage + 1;
-    }
-    wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    multiply(stage, 0, std::false_type{});
+#pragma unroll
+    for (int r = 0; r < kUnits; ++r) read_unit(lds, 0, r, 0);
+
+    int stage = 0;
+    int kt = 0;
+    for (; kt + 2 < n_ktiles; ++kt) {
+        iteration(stage, std::true_type{}, std::true_type{});
+        stage = stage + 1 == STAGES ? 0 : stage + 1;
+    }
+    if (kt + 1 < n_ktiles) {
+        iteration(stage, std::true_type{}, std::false_type{});
+        stage = stage + 1 == STAGES ? 0 : stage + 1;
+    }
+    iteration(stage, std::false_type{}, std::false_type{});
 }
 
 }  // namespace f64p
