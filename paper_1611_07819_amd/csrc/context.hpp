@@ -194,6 +194,7 @@ bool conv_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype);
 // A 1x1 convolution with stride 1 and no padding that is better run as a block GEMM.
 bool conv_as_gemm_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype);
 int conv_fast_wgrad_split(const ConvGeom& g, dmath_dtype_t in_dtype);
+int64_t conv_fast_partial_elems(int mode, const ConvGeom& g, int tile_m);
 hipError_t launch_conv_fast(const ConvPlan& p, int mode, double alpha, double beta, unsigned rewrite,
                            hipStream_t st);
 bool read_cycle_probe(uint64_t* out6);  // gemm_f16.hip; false unless built with the cycle probe

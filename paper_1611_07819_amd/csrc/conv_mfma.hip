@@ -244,8 +244,8 @@ struct FastConv {
     const void* xp;  // the copies, elements of the pipeline's input type
     const void* fp;
     const void* yt;
-    void* ws;  // weight gradient: partial sums in the accumulation type
-    int split, ktiles, ktiles_per_split;  // weight gradient: parts, pixel k-tiles in all and per part
+    void* ws;  // partial sums in the accumulation type (weight gradient: always; others: when split)
+    int split, ktiles, ktiles_per_split;  // parts of the k-loop, its k-tiles in all and per part
 };
 
 // byte offset of pixel m = (n, oh, ow) in Xp (tap (0,0), channel 0)
@@ -265,13 +265,16 @@ template <class P, int BM, int BN> struct FwdWalk {
     uint32_t aoff[TA::kInstr], boff[TB::kInstr];
     int c, wp, s_taps, cchunks, r, s, cc;
 
-    __device__ __forceinline__ FwdWalk(const FastConv& p, int m0, int n0, int wave, int lane)
+    // starts at k-tile kt0 of the (r, s, c) order
+    __device__ __forceinline__ FwdWalk(const FastConv& p, int m0, int n0, int wave, int lane, int kt0)
     {
         xp = reinterpret_cast<const char*>(p.xp);
         c = p.g.c; wp = p.wp; s_taps = p.g.s; cchunks = p.g.c / BK;
-        r = s = cc = 0;
-        abase = xp;
-        bbase = reinterpret_cast<const char*>(p.fp);
+        cc = kt0 % cchunks;
+        r = (kt0 / cchunks) / s_taps;
+        s = (kt0 / cchunks) % s_taps;
+        abase = xp + ((int64_t)(r * wp + s) * c + cc * BK) * sizeof(T);
+        bbase = reinterpret_cast<const char*>(p.fp) + (int64_t)kt0 * BK * sizeof(T);
         // rows past the last pixel (ragged last tile) fetch the last pixel again: in bounds, and
         // what they bring in only reaches accumulators that the epilogue does not store
         const int m_last = p.g.n * p.g.oh * p.g.ow - 1;
@@ -313,9 +316,10 @@ __global__ __launch_bounds__(NT) void conv_fwd_kernel(FastConv p, typename P::Ac
     constexpr int E = P::kEdge;
     constexpr int WM = TS::WM, WN = TS::WN, MT = TS::MT, NTL = TS::NTL;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
-    const int tiles_n = p.g.k / BN;
+    const int tiles_n = p.g.k / BN, tiles_mn = gridDim.x / p.split;
     const int idx = xcd_logical(blockIdx.x, gridDim.x);
-    const int m0 = (idx / tiles_n) * BM, n0 = (idx % tiles_n) * BN;
+    const int part = idx / tiles_mn, mn = idx % tiles_mn;  // part-major: same k-range, same XCD
+    const int m0 = (mn / tiles_n) * BM, n0 = (mn % tiles_n) * BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = TS::wm(wave), wn = TS::wn(wave), h = lane >> 5, lcol = P::col(lane);
@@ -328,9 +332,35 @@ __global__ __launch_bounds__(NT) void conv_fwd_kernel(FastConv p, typename P::Ac
 #pragma unroll
             for (int r = 0; r < P::kRegs; ++r) acc[i][j][r] = AccT(0);
 
-    FwdWalk<P, BM, BN> walk(p, m0, n0, wave, lane);
-    const int n_ktiles = p.g.r * p.g.s * (p.g.c / P::BK);
-    P::template run<BM, BN, STAGES, true, true>(walk, n_ktiles, smem, acc);
+    const int kt0 = part * p.ktiles_per_split;
+    FwdWalk<P, BM, BN> walk(p, m0, n0, wave, lane, kt0);
+    P::template run<BM, BN, STAGES, true, true>(walk, min(p.ktiles_per_split, p.ktiles - kt0), smem, acc);
+
+    if (p.split > 1) {
+        // partial sums [part][output channel][pixel], the pixels those of whole tiles
+        const int64_t mp = (int64_t)(tiles_mn / tiles_n) * BM;
+        AccT* ws = static_cast<AccT*>(p.ws) + (int64_t)part * p.g.k * mp;
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NTL; ++j) {
+                AccT* col = ws + (int64_t)(n0 + wn * WN + j * E + lcol) * mp + m0 + wm * WM + i * E;
+                if constexpr (P::kRowQuads) {
+                    typedef AccT acc4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        acc4 o;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = acc[i][j][q4 * 4 + e];
+                        *reinterpret_cast<acc4*>(col + 8 * q4 + 4 * h) = o;
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < P::kRegs; ++r) col[P::row(lane, r)] = acc[i][j][r];
+                }
+            }
+        return;
+    }
 
     // epilogue: with the 32x32 MFMAs four consecutive registers are four consecutive pixels of one
     // output plane (stored together where a plane is a multiple of 4 pixels)
@@ -383,6 +413,28 @@ __global__ __launch_bounds__(NT) void conv_fwd_kernel(FastConv p, typename P::Ac
                 *reinterpret_cast<out4*>(dst) = o;
             }
         }
+    }
+}
+
+// Y[n][ko][pixel] <- alpha * sum over parts (ascending) + beta * Y from the partial sums
+// [part][ko][pixel of whole tiles, mp of them].
+template <class AccT, class TC>
+__global__ __launch_bounds__(256) void conv_fwd_reduce_kernel(FastConv p, int64_t mp, AccT alpha, AccT beta)
+{
+    const AccT* ws = static_cast<const AccT*>(p.ws);
+    const int sp_out = p.g.oh * p.g.ow;
+    const int64_t m_end = (int64_t)p.g.n * sp_out, total = (int64_t)p.k_real * m_end, part_elems = (int64_t)p.g.k * mp;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        const int ko = (int)(e / m_end);
+        const int64_t m = e % m_end;
+        const AccT* src = ws + (int64_t)ko * mp + m;
+        AccT sum = AccT(0);
+        for (int s = 0; s < p.split; ++s) sum += src[(int64_t)s * part_elems];
+        const int n_img = (int)(m / sp_out), sp = (int)(m % sp_out);
+        TC* dst = static_cast<TC*>(const_cast<void*>(p.y_rows[n_img])) + (int64_t)ko * sp_out + sp;
+        AccT v = alpha * sum;
+        if (beta != AccT(0)) v += beta * (AccT)*dst;
+        *dst = to_out<TC>(v);
     }
 }
 
@@ -662,6 +714,20 @@ static int32_t generic_wgrad_split(const ConvGeom& g)
     return (int32_t)std::min<int64_t>({want, max_by_k, 512});  // first layers: 3 tiles, K of 800 thousand
 }
 
+// Elements of the partial sums of a forward pass / data gradient whose k-loop is split:
+// [part][output channel, padded][pixel of whole tiles].
+int64_t conv_fast_partial_elems(int mode, const ConvGeom& g, int tile_m)
+{
+    const int64_t m = mode == CONV_FWD ? (int64_t)g.n * g.oh * g.ow : (int64_t)g.n * g.h * g.w;
+    return (m + tile_m - 1) / tile_m * tile_m * round64(mode == CONV_FWD ? g.k : g.c);
+}
+
+// k-tiles of the forward pass (data gradient: filters take the channels' place)
+static int64_t fwd_ktiles(int mode, const ConvGeom& g, dmath_dtype_t dt)
+{
+    return (int64_t)g.r * g.s * round64(mode == CONV_FWD ? g.c : g.k) / pixel_tile(dt);
+}
+
 // Tile shapes of the forward kernel (also the data gradient's), widest first.
 struct FwdShape { int bm, bn; };
 static std::vector<FwdShape> fwd_shapes(dmath_dtype_t dt, int n_out)
@@ -709,23 +775,44 @@ ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int3
     // rounds.  A narrower tile has to win by 3 %.  fp32: with one workgroup per CU (128x128) the
     // gathers are hidden less well than with two (128x64): 0.87 of the rate in the samples.
     const int64_t k_depth = (int64_t)g.r * g.s * round64(mode == CONV_FWD ? g.c : g.k);
+    const int64_t ktiles = fwd_ktiles(mode, g, in_dtype);
     const int eb = elem_bytes(in_dtype);
     // cycles per unit of k and 32x32 block (fp64: four 16x16x4 instructions of 64 cycles per 4 of k)
     const double mfma_per_k = in_dtype == DMATH_F16 ? 32.5 / 16 : in_dtype == DMATH_F32 ? 64.0 / 2 : 64.0;
+    // Few tiles and a deep k-loop (small batches, late layers): the loop is cut into parts
+    // (powers of two, no part empty, at least four k-tiles each) that different workgroups run,
+    // and a second kernel adds the partial sums in a fixed order: + its launch (3 us at 2.4 GHz)
+    // and the partial sums written and read back at 3 TB/s.  A split has to win by 3 % as well.
+    // Against that absolute cost the cycle count of the tiles is scaled to what small batches
+    // take in the timing samples (2.0, 1.15 and 1.4 measured cycles per modelled one).
+    const double measured = in_dtype == DMATH_F16 ? 2.0 : in_dtype == DMATH_F32 ? 1.15 : 1.4;
     double best = -1;
     for (const FwdShape& sh : fwd_shapes(in_dtype, n_out)) {
         const int64_t tiles = (m + sh.bm - 1) / sh.bm * (n_out / sh.bn);
         const int slots = per_cu(sh.bm, sh.bn, in_dtype);
-        const int64_t chain = (tiles + 256 * slots - 1) / (256 * slots) * slots;  // tiles the busiest CU runs
         const double area = (double)sh.bm * sh.bn;
         const double per_k = std::max(area / 1024 * mfma_per_k / 4, (sh.bm + sh.bn) * eb / 60.0);
-        const double rate = (in_dtype != DMATH_F16 && slots == 1) ? 0.87 : 1.0;
-        const double cost = (double)chain * (k_depth * per_k / rate + 0.4 * area);
-        if (best < 0 || cost < 0.97 * best) {
-            best = cost;
-            ch.tile_m = sh.bm;
-            ch.tile_n = sh.bn;
+        for (int split = 1; split <= 32; split *= 2) {
+            if (split > 1 && (!wgrad_split_ok(ktiles, split) || (ktiles + split - 1) / split < 4)) break;
+            const int64_t wgs = tiles * split;
+            // tiles the busiest CU runs
+            const int64_t chain = wgs <= 256 ? 1 : (wgs + 256 * slots - 1) / (256 * slots) * slots;
+            const double rate = (in_dtype != DMATH_F16 && (slots == 1 || chain == 1)) ? 0.87 : 1.0;  // a workgroup alone on its CU
+            double cost = measured * (double)chain * ((double)k_depth / split * per_k / rate + 0.4 * area);
+            if (split > 1)
+                cost += 2.4e9 * (3e-6 + (split + 1.0) * (double)m * n_out * (in_dtype == DMATH_F64 ? 8 : 4) / 3e12);
+            if (best < 0 || cost < 0.97 * best) {
+                best = cost;
+                ch.tile_m = sh.bm;
+                ch.tile_n = sh.bn;
+                ch.split_k = split;
+            }
         }
+    }
+    // optional override for experiments and tests, e.g. DMATH_CONV_SPLIT=3 (parts may be uneven)
+    if (const char* e = std::getenv("DMATH_CONV_SPLIT")) {
+        const int forced = std::atoi(e);
+        if (forced >= 1 && forced <= 64 && wgrad_split_ok(ktiles, forced)) ch.split_k = forced;
     }
     return ch;
 }
@@ -763,11 +850,26 @@ std::vector<ConvChoice> conv_candidates(int mode, const ConvGeom& g, dmath_dtype
             }
         return out;
     }
-    for (const FwdShape& sh : fwd_shapes(in_dtype, round64(mode == CONV_FWD ? g.k : g.c))) {
+    const int64_t m = mode == CONV_FWD ? (int64_t)g.n * g.oh * g.ow : (int64_t)g.n * g.h * g.w;
+    const int n_out = round64(mode == CONV_FWD ? g.k : g.c);
+    const int64_t ktiles = fwd_ktiles(mode, g, in_dtype);
+    for (const FwdShape& sh : fwd_shapes(in_dtype, n_out)) {
+        const int64_t tiles = (m + sh.bm - 1) / sh.bm * (n_out / sh.bn);
         c.tile_m = sh.bm;
         c.tile_n = sh.bn;
-        out.push_back(c);
+        for (int split = 1; split <= 32; split *= 2) {
+            if (split > 1 && (!wgrad_split_ok(ktiles, split) || (ktiles + split - 1) / split < 4 || tiles * split > 512))
+                break;
+            c.split_k = split;
+            out.push_back(c);
+        }
     }
+    const ConvChoice model = choose_conv(mode, g, in_dtype, policy);
+    bool listed = false;
+    for (const ConvChoice& o : out)
+        listed = listed || (o.kernel == model.kernel && o.tile_m == model.tile_m && o.tile_n == model.tile_n &&
+                            o.split_k == model.split_k);
+    if (!listed) out.push_back(model);
     return out;
 }
 
@@ -775,12 +877,18 @@ namespace {
 
 // Launches the forward kernel (also the data gradient's) on tiles of BM x BN.
 template <class P, int BM, int BN, int STAGES>
-hipError_t launch_fwd_shape(const FastConv& p, dmath_dtype_t out, double alpha, double beta, hipStream_t st)
+hipError_t launch_fwd_shape(const FastConv& geom, dmath_dtype_t out, double alpha, double beta, hipStream_t st)
 {
     using AccT = typename P::AccT;
     using Wide = typename std::conditional<std::is_same<P, PipeF64>::value, double, float>::type;  // the wider output type
+    FastConv p = geom;
     const int64_t m = (int64_t)p.g.n * p.g.oh * p.g.ow;
-    const int tiles = (int)((m + BM - 1) / BM) * (p.g.k / BN);
+    const int tiles_m = (int)((m + BM - 1) / BM);
+    if (p.split < 1) p.split = 1;
+    p.ktiles = p.g.r * p.g.s * (p.g.c / P::BK);
+    p.ktiles_per_split = (p.ktiles + p.split - 1) / p.split;
+    if (!wgrad_split_ok(p.ktiles, p.split) || (p.split > 1 && !p.ws)) return hipErrorInvalidValue;
+    const int tiles = tiles_m * (p.g.k / BN) * p.split;
     constexpr int lds = P::lds_bytes(BM, BN, STAGES);
     static bool configured = false;  // more than 64 KiB of LDS has to be asked for once per kernel
     if (!configured) {
@@ -794,6 +902,14 @@ hipError_t launch_fwd_shape(const FastConv& p, dmath_dtype_t out, double alpha, 
         conv_fwd_kernel<P, BM, BN, STAGES, typename P::Elem><<<tiles, NT, lds, st>>>(p, (AccT)alpha, (AccT)beta);
     else
         conv_fwd_kernel<P, BM, BN, STAGES, Wide><<<tiles, NT, lds, st>>>(p, (AccT)alpha, (AccT)beta);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || p.split == 1) return e;
+    const int64_t mp = (int64_t)tiles_m * BM;
+    const int blocks = (int)std::min<int64_t>(2048, ((int64_t)p.k_real * m + 255) / 256);
+    if (out == DMATH_F16)
+        conv_fwd_reduce_kernel<AccT, typename P::Elem><<<blocks, 256, 0, st>>>(p, mp, (AccT)alpha, (AccT)beta);
+    else
+        conv_fwd_reduce_kernel<AccT, Wide><<<blocks, 256, 0, st>>>(p, mp, (AccT)alpha, (AccT)beta);
     return hipGetLastError();
 }
 

@@ -599,6 +599,8 @@ size_t conv_choice_bytes(int mode, const ConvGeom& g, const ConvChoice& c, dmath
     if (c.kernel == 1 && mode == CONV_BWD_FILTER) {
         const ConvFastLayout l = conv_fast_layout(mode, g, in_dtype);
         bytes += (size_t)c.split_k * l.kp * l.cp * g.r * g.s * (in_dtype == DMATH_F64 ? 8 : 4);
+    } else if (c.kernel == 1 && c.split_k > 1) {
+        bytes += (size_t)c.split_k * conv_fast_partial_elems(mode, g, c.tile_m) * (in_dtype == DMATH_F64 ? 8 : 4);
     } else if (mode == CONV_BWD_FILTER && c.split_k > 1) {
         bytes += (size_t)c.split_k * g.k * crs * (in_dtype == DMATH_F64 ? 8 : 4);
     }
@@ -640,7 +642,7 @@ dmath_status_t make_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_
     plan->kernel = ch.kernel;
     plan->tile_n = ch.tile_n;
     plan->tile_m = ch.tile_m;
-    t.split_k = ch.split_k;  // weight gradient only: few C tiles, very deep K
+    t.split_k = ch.split_k;  // few C tiles, deep K (generic kernel: weight gradient only)
 
     auto row_ptrs = [](const dmath_matrix_s* m) {
         std::vector<const void*> v((size_t)m->rows);
@@ -662,7 +664,9 @@ dmath_status_t make_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_
     if (t.split_k > 1 || (fast && mode == CONV_BWD_FILTER)) {
         size_t acc = plan->in_dtype == DMATH_F64 ? 8 : 4;
         // the specialised kernel's partial sums have the padded extents of its copies
-        const size_t elems = fast ? (size_t)lay.kp * lay.cp * g.r * g.s : (size_t)(t.M * t.N);
+        const size_t elems = !fast                     ? (size_t)(t.M * t.N)
+                             : mode == CONV_BWD_FILTER ? (size_t)lay.kp * lay.cp * g.r * g.s
+                                                       : (size_t)conv_fast_partial_elems(mode, g, ch.tile_m);
         ws = ctx->pool.alloc((size_t)t.split_k * elems * acc);
         if (!ws) {
             ctx->pool.free(dev);

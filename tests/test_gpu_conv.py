@@ -237,6 +237,41 @@ def test_specialised_conv_whole_result(ctx, oracle, g, dt, out):
             m.destroy()
 
 
+SPLIT_GEOMS = [
+    dict(n=3, c=128, h=14, w=14, k=256, r=3, s=3, pad_h=1, pad_w=1),                  # ragged last row tile
+    dict(n=5, c=120, h=9, w=11, k=120, r=3, s=2, pad_h=1, pad_w=0, stride_h=2, stride_w=1),  # padded channels, odd planes
+    dict(n=2, c=192, h=16, w=16, k=64, r=5, s=5, pad_h=2, pad_w=2),
+]
+
+
+@pytest.mark.parametrize("split", ["1", "3", "8"])
+@pytest.mark.parametrize("g", SPLIT_GEOMS)
+@pytest.mark.parametrize("dt,out", [(dm.F16, dm.F32), (dm.F16, dm.F16), (dm.F32, dm.F32), (dm.F64, dm.F64)])
+def test_forward_and_data_gradient_with_a_split_k_loop(oracle, monkeypatch, g, dt, out, split):
+    """The forward pass and the data gradient with the (r, s, c) loop whole and cut into 3 (uneven)
+    and 8 parts whose partial sums a second kernel adds: bit for bit on small-integer data, within
+    the precision's bar on random data with alpha and beta."""
+    monkeypatch.setenv("DMATH_CONV_SPLIT", split)
+    c = make_context(1.0)
+    try:
+        grids = {"X": (g["n"], 1), "F": (2, 1), "Y": (1, 1)}
+        before = c.relayout_stats()["written"]
+        res = three_modes(c, oracle, g, dt, out, 1.0, 1.0, grids, ints=True, policy=0)
+        assert c.relayout_stats()["written"] - before == 6       # every mode on the specialised kernels
+        for mode in ("fwd", "bwd_data"):
+            got, ref = res[mode]
+            if out == dm.F16 and np.abs(ref).max() > 2048:
+                assert rel_fro(got, ref) <= TOL[dm.F16], mode
+            else:
+                assert np.array_equal(got.astype(np.float64), ref), mode
+        res = three_modes(c, oracle, g, dt, out, 1.5, -0.5, {"X": (1, 1), "F": (1, 1), "Y": (1, 1)}, policy=0)
+        for mode in ("fwd", "bwd_data"):
+            got, ref = res[mode]
+            assert rel_fro(got, ref) <= TOL[dt], mode
+    finally:
+        c.close()
+
+
 def test_repeated_calls_rewrite_the_channels_last_copy(ctx, oracle):
     # the specialised path keeps a channels-last copy of X in the pool; a second call with new
     # contents of X must not see the old copy

@@ -172,6 +172,35 @@ def test_conv_tune_of_a_1x1_layer_counts_what_its_block_gemm_takes(ctx, oracle):
     ctx.tune_reset()
 
 
+@pytest.mark.parametrize("dt", [dm.F16, dm.F32])
+def test_conv_tune_of_a_small_batch_splits_the_k_loop(ctx, oracle, dt):
+    """One image of a deep layer: eight output tiles against a k-loop of 2304.  The cost model and
+    the tuner cut the loop of the forward pass and the data gradient into parts (the unsplit
+    configuration is several times slower), and the partial sums count as workspace."""
+    geo = dict(n=1, c=256, h=14, w=14, k=256, r=3, s=3, pad_h=1, pad_w=1)
+    d, od = dm.ConvDesc(**geo), oracle.ConvDesc(**geo)
+    r = np.random.default_rng(1105)
+    hx = r.uniform(0, 1, (1, 256 * 196)).astype(NP[dt])
+    hf = r.normal(0, 0.05, (256, 256 * 9)).astype(NP[dt])
+    hy = r.normal(0, 0.1, (1, 256 * 196)).astype(NP[dt])
+    X, F, dY = ctx.from_host(hx), ctx.from_host(hf), ctx.from_host(hy)
+    Y = ctx.matrix(1, 256 * 196, (1, 1), dm.F32)
+    dX = ctx.matrix(1, 256 * 196, (1, 1), dm.F32)
+    for mode, operands in ((0, (X, F, Y)), (2, (dX, F, dY))):
+        t = dm.conv_tune(ctx, mode, d, *operands, 1 << 28, trials=5)
+        assert t["kernel"] == 1 and t["split_k"] > 1, t
+        assert t["default_us"] > 0 and t["chosen_us"] >= 0.6 * t["default_us"], t    # the model's own choice is split too
+        tile_rows = 256 if dt == dm.F16 else 128
+        assert t["workspace_bytes"] >= t["split_k"] * tile_rows * 256 * 4
+    dm.conv_fwd(ctx, d, 1.0, X, F, 0.0, Y)
+    assert rel_fro(Y.get(), oracle.conv_fwd(od, 1.0, hx, hf)) <= TOL[dt]
+    dm.conv_bwd_data(ctx, d, 1.0, dY, F, 0.0, dX)
+    assert rel_fro(dX.get(), oracle.conv_bwd_data(od, 1.0, hy, hf)) <= TOL[dt]
+    ctx.tune_reset()
+    for m in (X, F, dY, Y, dX):
+        m.destroy()
+
+
 def test_tune_argument_errors(ctx):
     A, B = ctx.matrix(128, 128, (1, 1), dm.F32), ctx.matrix(128, 128, (1, 1), dm.F32)
     C = ctx.matrix(128, 128, (1, 1), dm.F32)
