@@ -215,20 +215,71 @@ __global__ __launch_bounds__(256) void filter_to_rsc_kernel(const void* const* f
     }
 }
 
+// The same through LDS: workgroup (channel chunk, filter) reads 64 channels x rs taps, which lie
+// contiguously in F, and writes rs runs of 64 consecutive channels (both sides coalesced; the
+// tile's rows are an odd number of elements apart).
+template <class T>
+__global__ __launch_bounds__(256) void filter_to_rsc_tiled_kernel(const void* const* f_rows, int c, int cp, int rs,
+                                                                  T* fp)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+    T* tile = reinterpret_cast<T*>(smem_raw);
+    const int rsp = rs | 1, kk = blockIdx.y, c0 = blockIdx.x * 64, nch = min(64, c - c0);
+    const int tid = threadIdx.x;
+    if (nch > 0) {
+        const T* src = static_cast<const T*>(f_rows[kk]) + (int64_t)c0 * rs;
+        for (int i = tid; i < nch * rs; i += 256) {
+            const int ch = i / rs;
+            tile[ch * rsp + (i - ch * rs)] = src[i];
+        }
+    }
+    __syncthreads();
+    T* dst = fp + (int64_t)kk * rs * cp + c0;
+    for (int i = tid; i < 64 * rs; i += 256) {
+        const int q = i >> 6, ch = i & 63;
+        dst[(int64_t)q * cp + ch] = ch < nch ? tile[ch * rsp + q] : (T)0.f;
+    }
+}
+
+template <class T>
+void filter_to_rsc(const void* const* f_rows, int c, int cp, int rs, int k, T* fp, hipStream_t st)
+{
+    const size_t lds = (size_t)64 * (rs | 1) * sizeof(T);
+    if (lds <= 64 * 1024)
+        filter_to_rsc_tiled_kernel<T><<<dim3(cp / 64, k), 256, lds, st>>>(f_rows, c, cp, rs, fp);
+    else
+        filter_to_rsc_kernel<T><<<512, 256, 0, st>>>(f_rows, c, cp, rs, k, fp);
+}
+
 // F[k][c][r][s] -> Gp[c][(r',s',kp)] with r' = R-1-r, s' = S-1-s: the filter of the forward
 // convolution (over dY, channels k) that computes the data gradient; kp >= k filters per tap
-// (the pad filters written as zeros).
+// (the pad filters written as zeros).  A tiled transpose of F seen as [k][c*rs]: 64 filters x 64
+// columns per workgroup through LDS, the taps of a channel written in reverse order.
 template <class T>
-__global__ __launch_bounds__(256) void filter_to_rsk_rotated_kernel(const void* const* f_rows, int c, int r,
-                                                                    int s, int k, int kp, T* gp)
+__global__ __launch_bounds__(256) void filter_to_rsk_rotated_tiled_kernel(const void* const* f_rows, int c, int rs,
+                                                                          int k, int kp, T* gp)
 {
-    const int rs = r * s;
-    const int64_t total = (int64_t)c * rs * kp;
-    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-        const int cc = (int)(e / (rs * kp)), rem = (int)(e % (rs * kp));
-        const int q = rem / kp, kk = rem % kp;  // destination order (r', s', kp)
-        const int rr = r - 1 - q / s, ss = s - 1 - q % s;
-        gp[e] = kk < k ? static_cast<const T*>(f_rows[kk])[cc * rs + rr * s + ss] : (T)0.f;
+    __shared__ T tile[64][65];
+    const int crs = c * rs, col0 = blockIdx.x * 64, k0 = blockIdx.y * 64, tid = threadIdx.x;
+    {
+        // 16 rows per thread: all row pointers first, then all elements, so that the loads overlap
+        const int col = tid & 63, row0 = tid >> 6;
+        const bool col_ok = col0 + col < crs;
+        const T* src[16];
+        T v[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) src[j] = static_cast<const T*>(f_rows[min(k0 + row0 + 4 * j, k - 1)]);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) v[j] = col_ok ? src[j][col0 + col] : (T)0.f;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) tile[row0 + 4 * j][col] = k0 + row0 + 4 * j < k ? v[j] : (T)0.f;
+    }
+    __syncthreads();
+    for (int i = tid; i < 64 * 64; i += 256) {
+        const int col = i >> 6, row = i & 63, cidx = col0 + col;
+        if (cidx >= crs) continue;
+        const int cc = cidx / rs, q = cidx - cc * rs;
+        gp[((int64_t)cc * rs + (rs - 1 - q)) * kp + k0 + row] = tile[row][col];
     }
 }
 
@@ -429,6 +480,7 @@ __global__ __launch_bounds__(256) void conv_fwd_reduce_kernel(FastConv p, int64_
         const int64_t m = e % m_end;
         const AccT* src = ws + (int64_t)ko * mp + m;
         AccT sum = AccT(0);
+#pragma unroll 8
         for (int s = 0; s < p.split; ++s) sum += src[(int64_t)s * part_elems];
         const int n_img = (int)(m / sp_out), sp = (int)(m % sp_out);
         TC* dst = static_cast<TC*>(const_cast<void*>(p.y_rows[n_img])) + (int64_t)ko * sp_out + sp;
@@ -570,6 +622,56 @@ __global__ __launch_bounds__(256) void conv_wgrad_reduce_kernel(FastConv p, AccT
             dst[i * rs] = to_out<TC>(v);
         }
     }
+}
+
+// The same through LDS: workgroup (channel chunk, filter) sums 64 channels x rs taps (runs of 64
+// consecutive channels in the partials), and writes them where they lie contiguously in dF.
+// With many parts and few workgroups (64-channel layers) the parts are dealt to `groups` sets of
+// threads (part s to set s % groups, each set adding its parts in ascending order) and the sets'
+// sums are added in ascending order: still one fixed order.
+template <class AccT, class TC>
+__global__ __launch_bounds__(256) void conv_wgrad_reduce_tiled_kernel(FastConv p, int groups, AccT alpha, AccT beta)
+{
+    typedef AccT acc4 __attribute__((ext_vector_type(4)));
+    extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+    AccT* tile = reinterpret_cast<AccT*>(smem_raw);  // [groups][64][rsp]
+    const int rs = p.g.r * p.g.s, rsp = rs | 1, c = p.g.c, ncols = rs * c;
+    const int kk = blockIdx.y, c0 = blockIdx.x * 64, nch = min(64, p.c_real - c0), tid = threadIdx.x;
+    if (nch <= 0) return;  // a chunk of pad channels only (the whole workgroup leaves)
+    const int64_t total = (int64_t)p.g.k * ncols;
+    const AccT* ws = static_cast<const AccT*>(p.ws) + (int64_t)kk * ncols + c0;
+    for (int i = tid; i < groups * rs * 16; i += 256) {
+        const int grp = i / (rs * 16), rem = i - grp * (rs * 16), q = rem >> 4, c4 = (rem & 15) * 4;
+        const AccT* src = ws + (int64_t)q * c + c4;
+        acc4 sum = {AccT(0), AccT(0), AccT(0), AccT(0)};
+#pragma unroll 8
+        for (int s = grp; s < p.split; s += groups) sum += *reinterpret_cast<const acc4*>(src + (int64_t)s * total);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) tile[(grp * 64 + c4 + e) * rsp + q] = sum[e];
+    }
+    __syncthreads();
+    TC* dst = static_cast<TC*>(const_cast<void*>(p.f_rows[kk])) + (int64_t)c0 * rs;
+    for (int i = tid; i < nch * rs; i += 256) {
+        const int ch = i / rs, at = ch * rsp + (i - ch * rs);
+        AccT sum = tile[at];
+        for (int grp = 1; grp < groups; ++grp) sum += tile[grp * 64 * rsp + at];
+        AccT v = alpha * sum;
+        if (beta != AccT(0)) v += beta * (AccT)dst[i];
+        dst[i] = to_out<TC>(v);
+    }
+}
+
+template <class AccT, class TC>
+void wgrad_reduce(const FastConv& p, double alpha, double beta, hipStream_t st)
+{
+    const size_t lds = (size_t)64 * ((p.g.r * p.g.s) | 1) * sizeof(AccT);
+    const int wgs = p.g.c / 64 * p.k_real;
+    const int groups = (p.split >= 8 && wgs < 1024 && 4 * lds <= 64 * 1024) ? 4 : 1;
+    if (lds <= 64 * 1024)
+        conv_wgrad_reduce_tiled_kernel<AccT, TC>
+            <<<dim3(p.g.c / 64, p.k_real), 256, groups * lds, st>>>(p, groups, (AccT)alpha, (AccT)beta);
+    else
+        conv_wgrad_reduce_kernel<AccT, TC><<<1024, 256, 0, st>>>(p, (AccT)alpha, (AccT)beta);
 }
 
 template <class K> hipError_t set_lds(K kern, int bytes)
@@ -1025,14 +1127,15 @@ hipError_t launch_typed(const ConvPlan& plan, int mode, double alpha, double bet
         if (rewrite & REWRITE_X)
             to_channels_last<T>(t.y_rows, g.n, g.k, kp, g.oh, g.ow, pph, ppw, g.stride_h, g.stride_w, q.hp, q.wp, xp, st);
         if (rewrite & REWRITE_F)
-            filter_to_rsk_rotated_kernel<T><<<512, 256, 0, st>>>(t.f_rows, g.c, g.r, g.s, g.k, kp, fp);
+            filter_to_rsk_rotated_tiled_kernel<T>
+                <<<dim3((g.c * g.r * g.s + 63) / 64, kp / 64), 256, 0, st>>>(t.f_rows, g.c, g.r * g.s, g.k, kp, fp);
         return launch_fwd(q, in, plan.tile_m, plan.tile_n, plan.out_dtype, alpha, beta, st);
     }
     // activations -> zero-bordered channels-last copy (borders were zeroed when the copy was allocated)
     if (rewrite & REWRITE_X)
         to_channels_last<T>(t.x_rows, g.n, g.c, cp, g.h, g.w, g.pad_h, g.pad_w, 1, 1, p.hp, p.wp, xp, st);
     if (mode == CONV_FWD) {
-        if (rewrite & REWRITE_F) filter_to_rsc_kernel<T><<<512, 256, 0, st>>>(t.f_rows, g.c, cp, g.r * g.s, g.k, fp);
+        if (rewrite & REWRITE_F) filter_to_rsc<T>(t.f_rows, g.c, cp, g.r * g.s, g.k, fp, st);
         return launch_fwd(p, in, plan.tile_m, plan.tile_n, plan.out_dtype, alpha, beta, st);
     }
     // weight gradient: dY -> channels-last [m][k], split GEMM, fixed-order reduction
@@ -1044,11 +1147,11 @@ hipError_t launch_typed(const ConvPlan& plan, int mode, double alpha, double bet
     hipError_t e = launch_wgrad(p, in, wgrad_tile_m(g, in), wgrad_tile_n(g), tiles, st);
     if (e != hipSuccess) return e;
     if (plan.out_dtype == DMATH_F64)
-        conv_wgrad_reduce_kernel<double, double><<<1024, 256, 0, st>>>(p, alpha, beta);
+        wgrad_reduce<double, double>(p, alpha, beta, st);
     else if (plan.out_dtype == DMATH_F16)
-        conv_wgrad_reduce_kernel<float, _Float16><<<1024, 256, 0, st>>>(p, (float)alpha, (float)beta);
+        wgrad_reduce<float, _Float16>(p, alpha, beta, st);
     else
-        conv_wgrad_reduce_kernel<float, float><<<1024, 256, 0, st>>>(p, (float)alpha, (float)beta);
+        wgrad_reduce<float, float>(p, alpha, beta, st);
     return hipGetLastError();
 }
 

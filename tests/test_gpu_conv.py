@@ -188,6 +188,7 @@ FAST_GEOMS = [
     dict(n=2, c=64, h=27, w=27, k=128, r=5, s=5, pad_h=2, pad_w=2),
     dict(n=5, c=120, h=9, w=11, k=120, r=3, s=2, pad_h=1, pad_w=0, stride_h=2, stride_w=1),
     dict(n=16, c=64, h=13, w=13, k=64, r=3, s=3, pad_h=1, pad_w=1),       # 43 pixel tiles in 5 uneven parts
+    dict(n=2, c=64, h=16, w=16, k=64, r=12, s=12),                        # 144 taps: fp64 filter permute / reduction without LDS staging
     # 1x1, stride 1, no padding: block GEMMs with one column block per image (planes of 576 pixels:
     # ragged last column tile, and a k-tail per image in the weight gradient; 56 channels: a k-tail
     # in the forward pass)
