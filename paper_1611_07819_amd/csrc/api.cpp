@@ -609,8 +609,7 @@ dmath_status_t dmath_conv_tune(dmath_ctx_t ctx, int32_t mode, const dmath_conv_d
         free_conv_plan(ctx, *plan);
         if (us < 0) return DMATH_ERR_DEVICE;
         ++result->candidates;
-        const bool is_model = c.kernel == model.kernel && c.tile_m == model.tile_m && c.tile_n == model.tile_n &&
-                              c.split_k == model.split_k;
+        const bool is_model = c == model;
         if (is_model) result->default_us = us;
         const double handicap = is_model ? 0.98 : 1.0;
         if (best < 0 || us * handicap < best) {

@@ -105,12 +105,21 @@ struct ConvPlan {
     std::unique_ptr<GemmPlan> gemm;  // kernel 2
     int32_t tile_n = 0;  // specialised forward / data gradient: 128 or 256 output channels per tile
     int32_t tile_m = 0;  //   and 256 or 224 pixels
+    int32_t tail_only = 0;  //   split_k parts only for the tiles after the last full round
     dmath_dtype_t in_dtype = DMATH_F16, out_dtype = DMATH_F32;
 };
 
 // Kernel / tile / split-K decision for a convolution.
 struct ConvChoice {
     int32_t kernel = 0, tile_m = 0, tile_n = 0, split_k = 1;
+    // specialised forward / data gradient: the split applies only to the tiles left over after
+    // the last full round of workgroups
+    int32_t tail_only = 0;
+    bool operator==(const ConvChoice& o) const
+    {
+        return kernel == o.kernel && tile_m == o.tile_m && tile_n == o.tile_n && split_k == o.split_k &&
+               tail_only == o.tail_only;
+    }
 };
 
 using GemmKey = std::tuple<uint64_t, uint64_t, uint64_t, int, int>;
@@ -194,7 +203,7 @@ bool conv_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype);
 // A 1x1 convolution with stride 1 and no padding that is better run as a block GEMM.
 bool conv_as_gemm_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype);
 int conv_fast_wgrad_split(const ConvGeom& g, dmath_dtype_t in_dtype);
-int64_t conv_fast_partial_elems(int mode, const ConvGeom& g, int tile_m);
+int64_t conv_fast_partial_elems(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, const ConvChoice& c);
 hipError_t launch_conv_fast(const ConvPlan& p, int mode, double alpha, double beta, unsigned rewrite,
                            hipStream_t st);
 bool read_cycle_probe(uint64_t* out6);  // gemm_f16.hip; false unless built with the cycle probe

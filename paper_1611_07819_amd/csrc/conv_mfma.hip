@@ -297,6 +297,10 @@ struct FastConv {
     const void* yt;
     void* ws;  // partial sums in the accumulation type (weight gradient: always; others: when split)
     int split, ktiles, ktiles_per_split;  // parts of the k-loop, its k-tiles in all and per part
+    // forward, data gradient: tiles (in launch order) that run the whole k-loop; the tiles after
+    // them run it in `split` parts.  tail_only (host side): only the tiles after the last full
+    // round of workgroups are split.
+    int full_tiles, tail_only;
 };
 
 // byte offset of pixel m = (n, oh, ow) in Xp (tap (0,0), channel 0)
@@ -367,9 +371,18 @@ __global__ __launch_bounds__(NT) void conv_fwd_kernel(FastConv p, typename P::Ac
     constexpr int E = P::kEdge;
     constexpr int WM = TS::WM, WN = TS::WN, MT = TS::MT, NTL = TS::NTL;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
-    const int tiles_n = p.g.k / BN, tiles_mn = gridDim.x / p.split;
-    const int idx = xcd_logical(blockIdx.x, gridDim.x);
-    const int part = idx / tiles_mn, mn = idx % tiles_mn;  // part-major: same k-range, same XCD
+    const int tiles_n = p.g.k / BN;
+    // whole tiles first; then the split ones, part-major (same k-range, same XCD)
+    const bool partial = (int)blockIdx.x >= p.full_tiles;
+    const int split_wgs = gridDim.x - p.full_tiles, split_tiles = split_wgs / p.split;
+    int part = 0, mn;
+    if (!partial) {
+        mn = xcd_logical(blockIdx.x, p.full_tiles);
+    } else {
+        const int lt = xcd_logical(blockIdx.x - p.full_tiles, split_wgs);
+        part = lt / split_tiles;
+        mn = p.full_tiles + lt % split_tiles;
+    }
     const int m0 = (mn / tiles_n) * BM, n0 = (mn % tiles_n) * BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -385,17 +398,20 @@ __global__ __launch_bounds__(NT) void conv_fwd_kernel(FastConv p, typename P::Ac
 
     const int kt0 = part * p.ktiles_per_split;
     FwdWalk<P, BM, BN> walk(p, m0, n0, wave, lane, kt0);
-    P::template run<BM, BN, STAGES, true, true>(walk, min(p.ktiles_per_split, p.ktiles - kt0), smem, acc);
+    P::template run<BM, BN, STAGES, true, true>(walk, partial ? min(p.ktiles_per_split, p.ktiles - kt0) : p.ktiles,
+                                                smem, acc);
 
-    if (p.split > 1) {
-        // partial sums [part][output channel][pixel], the pixels those of whole tiles
-        const int64_t mp = (int64_t)(tiles_mn / tiles_n) * BM;
+    if (partial) {
+        // partial sums [part][output channel][pixel], the pixels those of the split tiles (whole
+        // rows of tiles: full_tiles is a multiple of tiles_n)
+        const int64_t mp = (int64_t)(split_tiles / tiles_n) * BM;
+        const int m_first = (p.full_tiles / tiles_n) * BM;
         AccT* ws = static_cast<AccT*>(p.ws) + (int64_t)part * p.g.k * mp;
 #pragma unroll
         for (int i = 0; i < MT; ++i)
 #pragma unroll
             for (int j = 0; j < NTL; ++j) {
-                AccT* col = ws + (int64_t)(n0 + wn * WN + j * E + lcol) * mp + m0 + wm * WM + i * E;
+                AccT* col = ws + (int64_t)(n0 + wn * WN + j * E + lcol) * mp + (m0 - m_first) + wm * WM + i * E;
                 if constexpr (P::kRowQuads) {
                     typedef AccT acc4 __attribute__((ext_vector_type(4)));
 #pragma unroll
@@ -468,17 +484,19 @@ __global__ __launch_bounds__(NT) void conv_fwd_kernel(FastConv p, typename P::Ac
 }
 
 // Y[n][ko][pixel] <- alpha * sum over parts (ascending) + beta * Y from the partial sums
-// [part][ko][pixel of whole tiles, mp of them].
+// [part][ko][pixel of the split tiles: mp of them, the first one pixel m_first].
 template <class AccT, class TC>
-__global__ __launch_bounds__(256) void conv_fwd_reduce_kernel(FastConv p, int64_t mp, AccT alpha, AccT beta)
+__global__ __launch_bounds__(256) void conv_fwd_reduce_kernel(FastConv p, int64_t mp, int m_first, AccT alpha,
+                                                              AccT beta)
 {
     const AccT* ws = static_cast<const AccT*>(p.ws);
     const int sp_out = p.g.oh * p.g.ow;
-    const int64_t m_end = (int64_t)p.g.n * sp_out, total = (int64_t)p.k_real * m_end, part_elems = (int64_t)p.g.k * mp;
+    const int64_t m_end = (int64_t)p.g.n * sp_out, span = m_end - m_first;
+    const int64_t total = (int64_t)p.k_real * span, part_elems = (int64_t)p.g.k * mp;
     for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-        const int ko = (int)(e / m_end);
-        const int64_t m = e % m_end;
-        const AccT* src = ws + (int64_t)ko * mp + m;
+        const int ko = (int)(e / span);
+        const int64_t m = m_first + e % span;
+        const AccT* src = ws + (int64_t)ko * mp + (m - m_first);
         AccT sum = AccT(0);
 #pragma unroll 8
         for (int s = 0; s < p.split; ++s) sum += src[(int64_t)s * part_elems];
@@ -818,10 +836,21 @@ static int32_t generic_wgrad_split(const ConvGeom& g)
 
 // Elements of the partial sums of a forward pass / data gradient whose k-loop is split:
 // [part][output channel, padded][pixel of whole tiles].
-int64_t conv_fast_partial_elems(int mode, const ConvGeom& g, int tile_m)
+// Tiles of the forward pass / data gradient (in launch order: row of tiles by row of tiles) that
+// fill whole rounds of workgroups, as whole rows of tiles.
+static int64_t fwd_full_tiles(int64_t tiles_m, int tiles_n, int bm, int bn, dmath_dtype_t dt)
+{
+    const int64_t slots = 256 * per_cu(bm, bn, dt);
+    return tiles_m * tiles_n / slots * slots / tiles_n * tiles_n;
+}
+
+int64_t conv_fast_partial_elems(int mode, const ConvGeom& g, dmath_dtype_t dt, const ConvChoice& c)
 {
     const int64_t m = mode == CONV_FWD ? (int64_t)g.n * g.oh * g.ow : (int64_t)g.n * g.h * g.w;
-    return (m + tile_m - 1) / tile_m * tile_m * round64(mode == CONV_FWD ? g.k : g.c);
+    const int n_out = round64(mode == CONV_FWD ? g.k : g.c), tiles_n = n_out / c.tile_n;
+    const int64_t tiles_m = (m + c.tile_m - 1) / c.tile_m;
+    const int64_t full = c.tail_only ? fwd_full_tiles(tiles_m, tiles_n, c.tile_m, c.tile_n, dt) : 0;
+    return (tiles_m - full / tiles_n) * c.tile_m * n_out;
 }
 
 // k-tiles of the forward pass (data gradient: filters take the channels' place)
@@ -908,13 +937,54 @@ ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int3
                 ch.tile_m = sh.bm;
                 ch.tile_n = sh.bn;
                 ch.split_k = split;
+                ch.tail_only = 0;
+            }
+        }
+        // More than one round of workgroups and a last round that is less than half full: only
+        // the tiles of that round are split, into as many parts as still fit one round.
+        const int tiles_n = n_out / sh.bn;
+        const int64_t full = fwd_full_tiles(tiles / tiles_n, tiles_n, sh.bm, sh.bn, in_dtype), left = tiles - full;
+        if (full > 0 && left > 0 && left * 2 <= 256 * slots) {
+            int split = 1;
+            while (split < 16 && left * split * 2 <= 256 * slots && wgrad_split_ok(ktiles, split * 2) &&
+                   (ktiles + split * 2 - 1) / (split * 2) >= 4)
+                split *= 2;
+            if (split > 1) {
+                const int64_t chain_left = left * split <= 256 ? 1 : slots;
+                const double rate = (in_dtype != DMATH_F16 && (slots == 1 || chain_left == 1)) ? 0.87 : 1.0;
+                const double full_rate = (in_dtype != DMATH_F16 && slots == 1) ? 0.87 : 1.0;
+                double cost = measured * ((double)(full / 256) * ((double)k_depth * per_k / full_rate + 0.4 * area) +
+                                          (double)chain_left * ((double)k_depth / split * per_k / rate + 0.4 * area));
+                cost += 2.4e9 * (3e-6 + (split + 1.0) * (double)left / tiles_n * sh.bm * n_out *
+                                            (in_dtype == DMATH_F64 ? 8 : 4) / 3e12);
+                if (cost < 0.97 * best) {
+                    best = cost;
+                    ch.tile_m = sh.bm;
+                    ch.tile_n = sh.bn;
+                    ch.split_k = split;
+                    ch.tail_only = 1;
+                }
             }
         }
     }
-    // optional override for experiments and tests, e.g. DMATH_CONV_SPLIT=3 (parts may be uneven)
+    // optional overrides for experiments and tests: DMATH_CONV_TILE=128x64 (one of the shapes
+    // above), DMATH_CONV_SPLIT=3 (parts may be uneven) or =8t (only the tiles after the last full
+    // round of workgroups)
+    if (const char* e = std::getenv("DMATH_CONV_TILE")) {
+        int bm = 0, bn = 0;
+        if (std::sscanf(e, "%dx%d", &bm, &bn) == 2)
+            for (const FwdShape& sh : fwd_shapes(in_dtype, n_out))
+                if (sh.bm == bm && sh.bn == bn) {
+                    ch.tile_m = bm;
+                    ch.tile_n = bn;
+                }
+    }
     if (const char* e = std::getenv("DMATH_CONV_SPLIT")) {
         const int forced = std::atoi(e);
-        if (forced >= 1 && forced <= 64 && wgrad_split_ok(ktiles, forced)) ch.split_k = forced;
+        if (forced >= 1 && forced <= 64 && wgrad_split_ok(ktiles, forced)) {
+            ch.split_k = forced;
+            ch.tail_only = std::strchr(e, 't') != nullptr;
+        }
     }
     return ch;
 }
@@ -965,12 +1035,21 @@ std::vector<ConvChoice> conv_candidates(int mode, const ConvGeom& g, dmath_dtype
             c.split_k = split;
             out.push_back(c);
         }
+        const int tiles_n = n_out / sh.bn;
+        const int64_t slots = 256 * per_cu(sh.bm, sh.bn, in_dtype);
+        const int64_t left = tiles - fwd_full_tiles(tiles / tiles_n, tiles_n, sh.bm, sh.bn, in_dtype);
+        if (left < tiles && left > 0)
+            for (int split = 2; split <= 16; split *= 2)
+                if (left * split <= slots && wgrad_split_ok(ktiles, split) && (ktiles + split - 1) / split >= 4) {
+                    c.split_k = split;
+                    c.tail_only = 1;
+                    out.push_back(c);
+                }
+        c.tail_only = 0;
     }
     const ConvChoice model = choose_conv(mode, g, in_dtype, policy);
     bool listed = false;
-    for (const ConvChoice& o : out)
-        listed = listed || (o.kernel == model.kernel && o.tile_m == model.tile_m && o.tile_n == model.tile_n &&
-                            o.split_k == model.split_k);
+    for (const ConvChoice& o : out) listed = listed || o == model;
     if (!listed) out.push_back(model);
     return out;
 }
@@ -985,12 +1064,17 @@ hipError_t launch_fwd_shape(const FastConv& geom, dmath_dtype_t out, double alph
     using Wide = typename std::conditional<std::is_same<P, PipeF64>::value, double, float>::type;  // the wider output type
     FastConv p = geom;
     const int64_t m = (int64_t)p.g.n * p.g.oh * p.g.ow;
-    const int tiles_m = (int)((m + BM - 1) / BM);
+    const int tiles_m = (int)((m + BM - 1) / BM), tiles_n = p.g.k / BN;
     if (p.split < 1) p.split = 1;
     p.ktiles = p.g.r * p.g.s * (p.g.c / P::BK);
     p.ktiles_per_split = (p.ktiles + p.split - 1) / p.split;
     if (!wgrad_split_ok(p.ktiles, p.split) || (p.split > 1 && !p.ws)) return hipErrorInvalidValue;
-    const int tiles = tiles_m * (p.g.k / BN) * p.split;
+    const dmath_dtype_t in = std::is_same<P, PipeF16>::value ? DMATH_F16 : std::is_same<P, PipeF32>::value ? DMATH_F32 : DMATH_F64;
+    p.full_tiles = p.split == 1    ? tiles_m * tiles_n
+                   : p.tail_only   ? (int)fwd_full_tiles(tiles_m, tiles_n, BM, BN, in)
+                                   : 0;
+    const int split_tiles = tiles_m * tiles_n - p.full_tiles;
+    const int tiles = p.full_tiles + split_tiles * p.split;
     constexpr int lds = P::lds_bytes(BM, BN, STAGES);
     static bool configured = false;  // more than 64 KiB of LDS has to be asked for once per kernel
     if (!configured) {
@@ -1005,13 +1089,14 @@ hipError_t launch_fwd_shape(const FastConv& geom, dmath_dtype_t out, double alph
     else
         conv_fwd_kernel<P, BM, BN, STAGES, Wide><<<tiles, NT, lds, st>>>(p, (AccT)alpha, (AccT)beta);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || p.split == 1) return e;
-    const int64_t mp = (int64_t)tiles_m * BM;
-    const int blocks = (int)std::min<int64_t>(2048, ((int64_t)p.k_real * m + 255) / 256);
+    if (e != hipSuccess || split_tiles == 0) return e;
+    const int64_t mp = (int64_t)(split_tiles / tiles_n) * BM;
+    const int m_first = p.full_tiles / tiles_n * BM;
+    const int blocks = (int)std::min<int64_t>(2048, ((int64_t)p.k_real * (m - m_first) + 255) / 256);
     if (out == DMATH_F16)
-        conv_fwd_reduce_kernel<AccT, typename P::Elem><<<blocks, 256, 0, st>>>(p, mp, (AccT)alpha, (AccT)beta);
+        conv_fwd_reduce_kernel<AccT, typename P::Elem><<<blocks, 256, 0, st>>>(p, mp, m_first, (AccT)alpha, (AccT)beta);
     else
-        conv_fwd_reduce_kernel<AccT, Wide><<<blocks, 256, 0, st>>>(p, mp, (AccT)alpha, (AccT)beta);
+        conv_fwd_reduce_kernel<AccT, Wide><<<blocks, 256, 0, st>>>(p, mp, m_first, (AccT)alpha, (AccT)beta);
     return hipGetLastError();
 }
 
@@ -1099,6 +1184,7 @@ hipError_t launch_typed(const ConvPlan& plan, int mode, double alpha, double bet
     p.yt = yt;
     p.ws = t.workspace;
     p.split = t.split_k;
+    p.tail_only = plan.tail_only;
     if (!xp || (mode != CONV_BWD_FILTER && !fp) || (mode == CONV_BWD_FILTER && (!yt || !p.ws)))
         return hipErrorInvalidValue;  // the plan was not made for this path
 

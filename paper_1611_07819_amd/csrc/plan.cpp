@@ -600,7 +600,7 @@ size_t conv_choice_bytes(int mode, const ConvGeom& g, const ConvChoice& c, dmath
         const ConvFastLayout l = conv_fast_layout(mode, g, in_dtype);
         bytes += (size_t)c.split_k * l.kp * l.cp * g.r * g.s * (in_dtype == DMATH_F64 ? 8 : 4);
     } else if (c.kernel == 1 && c.split_k > 1) {
-        bytes += (size_t)c.split_k * conv_fast_partial_elems(mode, g, c.tile_m) * (in_dtype == DMATH_F64 ? 8 : 4);
+        bytes += (size_t)c.split_k * conv_fast_partial_elems(mode, g, in_dtype, c) * (in_dtype == DMATH_F64 ? 8 : 4);
     } else if (mode == CONV_BWD_FILTER && c.split_k > 1) {
         bytes += (size_t)c.split_k * g.k * crs * (in_dtype == DMATH_F64 ? 8 : 4);
     }
@@ -642,6 +642,7 @@ dmath_status_t make_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_
     plan->kernel = ch.kernel;
     plan->tile_n = ch.tile_n;
     plan->tile_m = ch.tile_m;
+    plan->tail_only = ch.tail_only;
     t.split_k = ch.split_k;  // few C tiles, deep K (generic kernel: weight gradient only)
 
     auto row_ptrs = [](const dmath_matrix_s* m) {
@@ -666,7 +667,7 @@ dmath_status_t make_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_
         // the specialised kernel's partial sums have the padded extents of its copies
         const size_t elems = !fast                     ? (size_t)(t.M * t.N)
                              : mode == CONV_BWD_FILTER ? (size_t)lay.kp * lay.cp * g.r * g.s
-                                                       : (size_t)conv_fast_partial_elems(mode, g, ch.tile_m);
+                                                       : (size_t)conv_fast_partial_elems(mode, g, plan->in_dtype, ch);
         ws = ctx->pool.alloc((size_t)t.split_k * elems * acc);
         if (!ws) {
             ctx->pool.free(dev);

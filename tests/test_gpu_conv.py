@@ -273,6 +273,34 @@ def test_forward_and_data_gradient_with_a_split_k_loop(oracle, monkeypatch, g, d
         c.close()
 
 
+@pytest.mark.parametrize("dt,out,tile", [(dm.F16, dm.F32, "256x64"), (dm.F32, dm.F32, "128x64"),
+                                         (dm.F64, dm.F64, "128x64")])
+def test_split_of_the_tiles_after_the_last_full_round(oracle, monkeypatch, dt, out, tile):
+    """18000 pixels x 256 channels are 284 tiles of 256x64 (fp16: 256 workgroup slots) or 564 of
+    128x64 (fp32, fp64: 512 slots): the tiles of the first full round run the whole (r, s, c)
+    loop, the 28 / 52 left over run it in four parts.  Forward and data gradient, small-integer
+    data, bit for bit on images of both kinds (the split tiles start at pixel 16384, in image 18)."""
+    monkeypatch.setenv("DMATH_CONV_TILE", tile)
+    monkeypatch.setenv("DMATH_CONV_SPLIT", "4t")
+    g = dict(n=20, c=256, h=30, w=30, k=256, r=3, s=3, pad_h=1, pad_w=1)
+    images = [0, 10, 18, 19]
+    c = make_context(1.5)
+    try:
+        d, t = tensors(g, dt, 302, ints=True)
+        od = oracle.ConvDesc(**g)
+        X, F, dY = c.from_host(t["X"]), c.from_host(t["F"]), c.from_host(t["Y"])
+        Y = c.from_host(np.ones(t["Y"].shape, NP[out]))
+        dX = c.from_host(np.ones(t["X"].shape, NP[out]))
+        dm.conv_fwd(c, d, 1.0, X, F, 1.0, Y)
+        ref = oracle.conv_fwd(od, 1.0, t["X"], t["F"], images=images) + 1.0
+        assert np.array_equal(Y.get()[images].astype(np.float64), ref)
+        dm.conv_bwd_data(c, d, 1.0, dY, F, 1.0, dX)
+        ref = oracle.conv_bwd_data(od, 1.0, t["Y"], t["F"], images=images) + 1.0
+        assert np.array_equal(dX.get()[images].astype(np.float64), ref)
+    finally:
+        c.close()
+
+
 def test_repeated_calls_rewrite_the_channels_last_copy(ctx, oracle):
     # the specialised path keeps a channels-last copy of X in the pool; a second call with new
     # contents of X must not see the old copy
