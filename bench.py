@@ -18,9 +18,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"f16": 2516.6, "f32": 157.3, "f64": 78.6}   # dense MFMA peaks of MI355X
-# HBM bytes per launch of the dominant kernel (mean over the three cfg2 GEMMs), from the two
+# HBM bytes per GEMM call of cfg2 (mean over the three calls of a step), from the two
 # rocprofv3 --pmc runs summarised in profiles/gemm_f32_cfg2_hbm_traffic.txt; None until measured.
-MEASURED_TRAFFIC_BYTES = 562149187
+MEASURED_TRAFFIC_BYTES = 595861216
 
 
 def main():
@@ -81,8 +81,9 @@ def main():
         flops.append(2.0 * M * N * K)
     ms_step, wall_ms = time_calls(fns, args.steps, args.warmup)
     value = sum(flops) / (ms_step * 1e-3) / 1e12
-    # dominant kernel = the GEMM main loop; one launch per call, three launches per step, each
-    # doing the same 2*M*N*K = 77.31 GFLOP.
+    # dominant kernel = the GEMM main loop; three calls per step, each doing the same
+    # 2*M*N*K = 77.31 GFLOP in one launch (dX: two, the second over the tiles left after the
+    # last full round of workgroups, in four k-parts, plus the kernel that adds them).
     avg_launch_ms = ms_step / len(fns)
     achieved = (sum(flops) / len(fns)) / (avg_launch_ms * 1e-3) / 1e12
     calls = {}

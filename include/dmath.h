@@ -137,6 +137,8 @@ typedef struct {
     int32_t split_k;  /* partial sums per C tile (1 = none)                            */
     int32_t kernel;   /* 0 = guarded generic kernel, >0 = a specialised kernel id      */
     int32_t cached;   /* 1 if the plan was already in the cache                        */
+    int32_t split_tiles; /* C tiles that take partial sums: 0, all of them, or only those
+                            left over after the last full round of workgroups            */
     uint64_t workspace_bytes; /* pool memory beyond the operands: split-K partial sums and the
                                  zero-padded scratch panels of k-segments that are not
                                  multiples of tile_k */

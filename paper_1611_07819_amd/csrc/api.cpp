@@ -464,6 +464,7 @@ dmath_status_t dmath_gemm_tune(dmath_ctx_t ctx, dmath_op_t transA, dmath_op_t tr
     st = make_gemm_plan(ctx, transA, transB, A, B, C, false, nullptr, &described, &cands);
     if (st != DMATH_OK) return st;
     const dmath_plan_info_t model = described->info;
+    const int32_t model_full_tiles = described->full_tiles;
     Events ev;
     if (!ev.ok()) return DMATH_ERR_DEVICE;
     *result = dmath_tune_result_t{};
@@ -489,11 +490,13 @@ dmath_status_t dmath_gemm_tune(dmath_ctx_t ctx, dmath_op_t transA, dmath_op_t tr
         const double us = sample_us(ctx, ev.e0, ev.e1, trials, result->candidates ? 3e3 : 2e4,
                                     [&] { return launch_gemm(*plan, 1.0, 0.0, ctx->stream); });
         const dmath_plan_info_t info = plan->info;
+        const int32_t full_tiles = plan->full_tiles;
         free_gemm_plan(ctx, *plan);  // stream order: the samples have completed (event wait)
         if (us < 0) return DMATH_ERR_DEVICE;
         ++result->candidates;
         const bool is_model = info.kernel == model.kernel && info.tile_m == model.tile_m &&
-                              info.tile_n == model.tile_n && info.split_k == model.split_k;
+                              info.tile_n == model.tile_n && info.split_k == model.split_k &&
+                              full_tiles == model_full_tiles;
         if (is_model) result->default_us = us;
         // a sample has to beat the cost model's choice by more than 2 % (noise) to replace it
         const double handicap = is_model ? 0.98 : 1.0;

@@ -70,6 +70,10 @@ struct GemmPlan {
     const CopyCell* tail_cells = nullptr;
     int32_t n_tail_cells = 0, tail_rows = 0;
     void* tail_scratch = nullptr;
+    // > 0: only the tiles from this index on (those after the last full round of workgroups) are
+    // split; their m_glob / n_glob address a compact workspace [split][tiles x tile_m][tile_n]
+    int32_t full_tiles = 0;
+    const int32_t* ksplit_whole = nullptr;  // {0, n_kseg}: the whole k-loop as one part
 };
 
 enum ConvMode : int32_t { CONV_FWD = 0, CONV_BWD_FILTER = 1, CONV_BWD_DATA = 2 };
@@ -137,6 +141,9 @@ struct GemmChoice {
     int32_t kernel = KERNEL_GENERIC;
     int32_t tile_m = 64, tile_n = 64, tile_k = 16;
     int32_t split_k = 1;
+    // > 0 (with split_k > 1): the first full_tiles tiles of the launch order, whole rounds of
+    // workgroups, run the whole k-loop; only the tiles after them are split
+    int32_t full_tiles = 0;
 };
 
 }  // namespace dm

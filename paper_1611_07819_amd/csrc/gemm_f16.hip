@@ -199,9 +199,8 @@ hipError_t launch_one(const GemmTables& t, float alpha, float beta, hipStream_t 
 }
 
 template <int BM, int BN, int STAGES, class TC>
-hipError_t launch_shape(const GemmPlan& p, float alpha, float beta, hipStream_t st)
+hipError_t launch_shape(const GemmTables& t, float alpha, float beta, hipStream_t st)
 {
-    const GemmTables& t = p.t;
     if (t.a_kcontig && t.b_kcontig) return launch_one<BM, BN, STAGES, true, true, TC>(t, alpha, beta, st);
     if (t.a_kcontig && !t.b_kcontig) return launch_one<BM, BN, STAGES, true, false, TC>(t, alpha, beta, st);
     if (!t.a_kcontig && t.b_kcontig) return launch_one<BM, BN, STAGES, false, true, TC>(t, alpha, beta, st);
@@ -212,23 +211,23 @@ hipError_t launch_shape(const GemmPlan& p, float alpha, float beta, hipStream_t 
 // stages, so that two workgroups share a CU); 64x128 and 64x64 (three stages) for batches of at
 // most 64 rows, which are bound by streaming the other operand from HBM.
 template <class TC>
-hipError_t launch_out(const GemmPlan& p, float alpha, float beta, hipStream_t st)
+hipError_t launch_out(const GemmPlan& p, const GemmTables& t, float alpha, float beta, hipStream_t st)
 {
     const int bm = p.info.tile_m, bn = p.info.tile_n;
-    if (bm == 256 && bn == 256) return launch_shape<256, 256, 2, TC>(p, alpha, beta, st);
-    if (bm == 256 && bn == 128) return launch_shape<256, 128, 3, TC>(p, alpha, beta, st);
-    if (bm == 128 && bn == 128) return launch_shape<128, 128, 2, TC>(p, alpha, beta, st);
-    if (bm == 64 && bn == 128) return launch_shape<64, 128, 3, TC>(p, alpha, beta, st);
-    if (bm == 64 && bn == 64) return launch_shape<64, 64, 3, TC>(p, alpha, beta, st);
+    if (bm == 256 && bn == 256) return launch_shape<256, 256, 2, TC>(t, alpha, beta, st);
+    if (bm == 256 && bn == 128) return launch_shape<256, 128, 3, TC>(t, alpha, beta, st);
+    if (bm == 128 && bn == 128) return launch_shape<128, 128, 2, TC>(t, alpha, beta, st);
+    if (bm == 64 && bn == 128) return launch_shape<64, 128, 3, TC>(t, alpha, beta, st);
+    if (bm == 64 && bn == 64) return launch_shape<64, 64, 3, TC>(t, alpha, beta, st);
     return hipErrorInvalidValue;
 }
 
 }  // namespace
 
-hipError_t launch_gemm_f16(const GemmPlan& p, double alpha, double beta, hipStream_t st)
+hipError_t launch_gemm_f16(const GemmPlan& p, const GemmTables& t, double alpha, double beta, hipStream_t st)
 {
-    if (p.out_dtype == DMATH_F16) return launch_out<_Float16>(p, (float)alpha, (float)beta, st);
-    return launch_out<float>(p, (float)alpha, (float)beta, st);
+    if (p.out_dtype == DMATH_F16) return launch_out<_Float16>(p, t, (float)alpha, (float)beta, st);
+    return launch_out<float>(p, t, (float)alpha, (float)beta, st);
 }
 
 }  // namespace dm

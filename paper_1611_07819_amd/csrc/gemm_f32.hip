@@ -145,9 +145,8 @@ hipError_t launch_one(const GemmTables& t, float alpha, float beta, hipStream_t 
 }
 
 template <int BM, int BN, int WVM>
-hipError_t launch_shape(const GemmPlan& p, float alpha, float beta, hipStream_t st)
+hipError_t launch_shape(const GemmTables& t, float alpha, float beta, hipStream_t st)
 {
-    const GemmTables& t = p.t;
     if (t.a_kcontig && t.b_kcontig) return launch_one<BM, BN, WVM, true, true>(t, alpha, beta, st);
     if (!t.a_kcontig && t.b_kcontig) return launch_one<BM, BN, WVM, false, true>(t, alpha, beta, st);
     if constexpr (64 % (BN / 4) == 0) {  // an m/n-major B tile must fill whole 1 KiB LDS segments
@@ -161,14 +160,14 @@ hipError_t launch_shape(const GemmPlan& p, float alpha, float beta, hipStream_t 
 
 // 128x96 (wavefronts 4 x 1) exists for outputs whose tile count would otherwise leave the last
 // round of workgroups mostly empty; it needs a k-major B.
-hipError_t launch_gemm_f32(const GemmPlan& p, double alpha, double beta, hipStream_t st)
+hipError_t launch_gemm_f32(const GemmPlan& p, const GemmTables& t, double alpha, double beta, hipStream_t st)
 {
     const int bm = p.info.tile_m, bn = p.info.tile_n;
-    if (bm == 128 && bn == 128) return launch_shape<128, 128, 2>(p, (float)alpha, (float)beta, st);
-    if (bm == 128 && bn == 64) return launch_shape<128, 64, 2>(p, (float)alpha, (float)beta, st);
-    if (bm == 128 && bn == 96) return launch_shape<128, 96, 4>(p, (float)alpha, (float)beta, st);
-    if (bm == 64 && bn == 256) return launch_shape<64, 256, 2>(p, (float)alpha, (float)beta, st);
-    if (bm == 64 && bn == 128) return launch_shape<64, 128, 2>(p, (float)alpha, (float)beta, st);
+    if (bm == 128 && bn == 128) return launch_shape<128, 128, 2>(t, (float)alpha, (float)beta, st);
+    if (bm == 128 && bn == 64) return launch_shape<128, 64, 2>(t, (float)alpha, (float)beta, st);
+    if (bm == 128 && bn == 96) return launch_shape<128, 96, 4>(t, (float)alpha, (float)beta, st);
+    if (bm == 64 && bn == 256) return launch_shape<64, 256, 2>(t, (float)alpha, (float)beta, st);
+    if (bm == 64 && bn == 128) return launch_shape<64, 128, 2>(t, (float)alpha, (float)beta, st);
     return hipErrorInvalidValue;
 }
 

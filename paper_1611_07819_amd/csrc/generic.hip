@@ -13,7 +13,8 @@
 
 namespace dm {
 
-hipError_t launch_gemm_reduce(const GemmPlan& p, int n_partials, double alpha, double beta, hipStream_t st);
+hipError_t launch_gemm_reduce(const GemmPlan& p, const GemmTables& t, int n_partials, double alpha, double beta,
+                              hipStream_t st);
 
 namespace {
 
@@ -628,9 +629,9 @@ __global__ __launch_bounds__(GTHREADS) void conv_reduce_kernel(ConvTables t, int
     }
 }
 
-dim3 reduce_grid(const GemmPlan& p)
+dim3 reduce_grid(const GemmPlan& p, const GemmTables& t)
 {
-    return dim3(p.t.n_tiles, (p.info.tile_m + kReduceRows - 1) / kReduceRows);
+    return dim3(t.n_tiles, (p.info.tile_m + kReduceRows - 1) / kReduceRows);
 }
 
 template <class T, class TC>
@@ -639,12 +640,12 @@ hipError_t run_gemm_generic(const GemmPlan& p, double alpha, double beta, hipStr
     using AccT = typename Traits<T>::acc_t;
     const GemmTables& t = p.t;
     if (alpha == 0.0) {
-        return launch_gemm_reduce(p, 0, 0.0, beta, st);
+        return launch_gemm_reduce(p, t, 0, 0.0, beta, st);
     }
     gemm_generic_kernel<T, TC><<<dim3(t.n_tiles, t.split_k), GTHREADS, 0, st>>>(t, alpha, beta);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || t.split_k == 1) return e;
-    return launch_gemm_reduce(p, t.split_k, alpha, beta, st);
+    return launch_gemm_reduce(p, t, t.split_k, alpha, beta, st);
 }
 
 template <class T, class TC, int MODE>
@@ -690,23 +691,26 @@ hipError_t launch_gemm_generic(const GemmPlan& p, double alpha, double beta, hip
 // C <- alpha * (sum of the first n_partials split-K partials, ascending) + beta * C, for any
 // tile shape.  n_partials == 0 is the alpha == 0 path: A and B are never read.
 template <class AccT, class TC>
-static void reduce_launch(const GemmPlan& p, int n_partials, double alpha, double beta, hipStream_t st)
+static void reduce_launch(const GemmPlan& p, const GemmTables& t, int n_partials, double alpha, double beta,
+                          hipStream_t st)
 {
     constexpr int kVec = 16 / sizeof(AccT);
     if (p.reduce_vectors)
-        gemm_reduce_kernel<AccT, TC, kVec><<<reduce_grid(p), GTHREADS, 0, st>>>(p.t, n_partials, alpha, beta);
+        gemm_reduce_kernel<AccT, TC, kVec><<<reduce_grid(p, t), GTHREADS, 0, st>>>(t, n_partials, alpha, beta);
     else
-        gemm_reduce_kernel<AccT, TC, 1><<<reduce_grid(p), GTHREADS, 0, st>>>(p.t, n_partials, alpha, beta);
+        gemm_reduce_kernel<AccT, TC, 1><<<reduce_grid(p, t), GTHREADS, 0, st>>>(t, n_partials, alpha, beta);
 }
 
-hipError_t launch_gemm_reduce(const GemmPlan& p, int n_partials, double alpha, double beta, hipStream_t st)
+// t: the plan's tables, or a view of them (some of the tiles, their own workspace extents)
+hipError_t launch_gemm_reduce(const GemmPlan& p, const GemmTables& t, int n_partials, double alpha, double beta,
+                              hipStream_t st)
 {
     if (p.in_dtype == DMATH_F64)
-        reduce_launch<double, double>(p, n_partials, alpha, beta, st);
+        reduce_launch<double, double>(p, t, n_partials, alpha, beta, st);
     else if (p.out_dtype == DMATH_F32)
-        reduce_launch<float, float>(p, n_partials, alpha, beta, st);
+        reduce_launch<float, float>(p, t, n_partials, alpha, beta, st);
     else
-        reduce_launch<float, _Float16>(p, n_partials, alpha, beta, st);
+        reduce_launch<float, _Float16>(p, t, n_partials, alpha, beta, st);
     return hipGetLastError();
 }
 

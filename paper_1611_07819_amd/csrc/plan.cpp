@@ -452,8 +452,19 @@ dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_ma
                     tiles.push_back(t);
                 }
     tiles = xcd_interleave(tiles);
+    // split only the tiles after the last full round: they get a compact workspace of their own,
+    // [split][those tiles x tile_m][tile_n]
+    int32_t full_tiles = 0;
+    if (ch.split_k > 1 && ch.full_tiles > 0 && ch.full_tiles < (int32_t)tiles.size() && ch.kernel != KERNEL_GENERIC) {
+        full_tiles = ch.full_tiles;
+        for (size_t j = (size_t)full_tiles; j < tiles.size(); ++j) {
+            tiles[j].m_glob = (int32_t)(j - (size_t)full_tiles) * ch.tile_m;
+            tiles[j].n_glob = 0;
+        }
+    }
 
     auto plan = std::make_unique<GemmPlan>();
+    plan->full_tiles = full_tiles;
     plan->uses = {A->id, B->id, C->id};
     plan->in_dtype = A->dtype;
     plan->out_dtype = C->dtype;
@@ -480,8 +491,11 @@ dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_ma
     info.kernel = ch.kernel;
     const size_t acc_size = A->dtype == DMATH_F64 ? 8 : 4;
     // pool memory beyond the operands: split-K partial sums and the scratch panels of k-tails
-    const uint64_t partial_bytes = ch.split_k > 1 ? (uint64_t)ch.split_k * M * N * acc_size : 0;
+    const uint64_t split_elems = full_tiles ? (uint64_t)(tiles.size() - (size_t)full_tiles) * ch.tile_m * ch.tile_n
+                                            : (uint64_t)M * N;
+    const uint64_t partial_bytes = ch.split_k > 1 ? (uint64_t)ch.split_k * split_elems * acc_size : 0;
     info.workspace_bytes = partial_bytes + scratch_bytes;
+    info.split_tiles = ch.split_k > 1 ? (int32_t)tiles.size() - full_tiles : 0;
 
     GemmTables& t = plan->t;
     t.n_mseg = (int32_t)ms.size();
@@ -498,6 +512,7 @@ dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_ma
         std::vector<char> buf;
         size_t oa = append(buf, pa), ob = append(buf, pb), oc = append(buf, pc);
         size_t ok = append(buf, kl), os = append(buf, ksplit), ot = append(buf, tiles);
+        size_t ow = append(buf, std::vector<int32_t>{0, (int32_t)ks.size()});
         size_t otc = append(buf, tail_cells);
         plan->tail_scratch = scratch;  // from here on the plan owns it
         void* dev = ctx->pool.alloc(buf.size());
@@ -529,6 +544,7 @@ dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_ma
         t.c = reinterpret_cast<const Panel*>(d + oc);
         t.klen = reinterpret_cast<const int32_t*>(d + ok);
         t.ksplit = reinterpret_cast<const int32_t*>(d + os);
+        plan->ksplit_whole = reinterpret_cast<const int32_t*>(d + ow);
         t.tiles = reinterpret_cast<const Tile*>(d + ot);
         t.workspace = ws;
         plan->dev_tables = dev;

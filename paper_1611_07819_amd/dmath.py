@@ -40,7 +40,7 @@ class _PlanInfo(ctypes.Structure):
                 ("k_segments", ctypes.c_int32), ("tile_m", ctypes.c_int32),
                 ("tile_n", ctypes.c_int32), ("tile_k", ctypes.c_int32), ("tiles", ctypes.c_int32),
                 ("split_k", ctypes.c_int32), ("kernel", ctypes.c_int32), ("cached", ctypes.c_int32),
-                ("workspace_bytes", ctypes.c_uint64)]
+                ("split_tiles", ctypes.c_int32), ("workspace_bytes", ctypes.c_uint64)]
 
 
 class _ConvDesc(ctypes.Structure):

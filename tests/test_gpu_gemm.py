@@ -478,3 +478,51 @@ def test_random_shapes_grids_ops_against_oracle(ctx, oracle, seed):
             assert np.array_equal(dC.get().astype(np.float64), ref), what
         for m in (dA, dB, dC):
             m.destroy()
+
+
+@pytest.mark.parametrize("dt,out,tile,shape", [
+    (dm.F32, dm.F32, "128x64", (1300, 4128, 256)),     # 11 x 65 = 715 tiles on 512 workgroup slots
+    (dm.F64, dm.F64, "128x64", (1300, 4128, 256)),
+    (dm.F16, dm.F32, "256x128", (2400, 4128, 512)),    # 10 x 33 = 330 tiles on 256 slots
+    (dm.F16, dm.F16, "256x128", (2400, 4128, 512)),
+])
+@pytest.mark.parametrize("ta,tb", [(0, 0), (1, 0), (0, 1)])
+def test_split_of_the_tiles_after_the_last_full_round(oracle, monkeypatch, dt, out, tile, shape, ta, tb):
+    """More tiles than one round of workgroups holds: the tiles of the full rounds run the whole
+    k-loop and store C, the rest are split into four parts with a compact workspace of their own
+    and reduced in a fixed order (forced here; the cost model takes the same path where it pays).
+    Ragged last tiles in both directions; small-integer data, bit for bit; sampled rows of a
+    random case within the precision's bar."""
+    monkeypatch.setenv("DMATH_TILE", tile)
+    monkeypatch.setenv("DMATH_GEMM_SPLIT", "4t")
+    M, N, K = shape
+    r = np.random.default_rng(260)
+    c = make_context(1.0)
+    try:
+        opA = r.integers(-2, 3, (M, K)).astype(NP[dt])
+        opB = r.integers(-2, 3, (K, N)).astype(NP[dt])
+        C0 = r.integers(-2, 3, (M, N)).astype(NP[out])
+        A, B = stored(opA, ta), stored(opB, tb)
+        dA, dB, dC = c.from_host(A), c.from_host(B), c.from_host(C0)
+        info = dm.gemm_plan_info(c, ta, tb, dA, dB, dC)
+        assert info["kernel"] > 0 and info["split_k"] == 4 and 0 < info["split_tiles"] < info["tiles"], info
+        slots = 512 if dt != dm.F16 else 256
+        assert info["tiles"] - info["split_tiles"] == info["tiles"] // slots * slots
+        dm.gemm(c, ta, tb, 1.0, dA, dB, 1.0, dC)
+        rows = list(range(0, M, 37)) + [M - 1]
+        ref = oracle.gemm(bool(ta), bool(tb), 1.0, A, B, 1.0, C0, rows=rows)
+        got = dC.get()[rows].astype(np.float64)
+        if out == dm.F16 and np.abs(ref).max() > 2048:
+            assert rel_fro(got, ref) <= TOL[dt]
+        else:
+            assert np.array_equal(got, ref)
+        # random data, alpha and beta, on the same plan
+        ra = r.uniform(-1, 1, A.shape).astype(NP[dt])
+        rb = r.uniform(-1, 1, B.shape).astype(NP[dt])
+        rc = r.uniform(-1, 1, (M, N)).astype(NP[out])
+        dA.set(ra), dB.set(rb), dC.set(rc)
+        dm.gemm(c, ta, tb, 1.5, dA, dB, -0.5, dC)
+        ref = oracle.gemm(bool(ta), bool(tb), 1.5, ra, rb, -0.5, rc, rows=rows)
+        assert rel_fro(dC.get()[rows], ref) <= TOL[dt]
+    finally:
+        c.close()
