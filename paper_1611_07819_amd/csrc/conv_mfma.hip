@@ -940,30 +940,27 @@ ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int3
                 ch.tail_only = 0;
             }
         }
-        // More than one round of workgroups and a last round that is less than half full: only
-        // the tiles of that round are split, into as many parts as still fit one round.
+        // More than one round of workgroups and a last round that is not full: only the tiles of
+        // that round are split, into 2, 4, 8 or 16 parts (which may take several short rounds of
+        // their own).
         const int tiles_n = n_out / sh.bn;
         const int64_t full = fwd_full_tiles(tiles / tiles_n, tiles_n, sh.bm, sh.bn, in_dtype), left = tiles - full;
-        if (full > 0 && left > 0 && left * 2 <= 256 * slots) {
-            int split = 1;
-            while (split < 16 && left * split * 2 <= 256 * slots && wgrad_split_ok(ktiles, split * 2) &&
-                   (ktiles + split * 2 - 1) / (split * 2) >= 4)
-                split *= 2;
-            if (split > 1) {
-                const int64_t chain_left = left * split <= 256 ? 1 : slots;
-                const double rate = (in_dtype != DMATH_F16 && (slots == 1 || chain_left == 1)) ? 0.87 : 1.0;
-                const double full_rate = (in_dtype != DMATH_F16 && slots == 1) ? 0.87 : 1.0;
-                double cost = measured * ((double)(full / 256) * ((double)k_depth * per_k / full_rate + 0.4 * area) +
-                                          (double)chain_left * ((double)k_depth / split * per_k / rate + 0.4 * area));
-                cost += 2.4e9 * (3e-6 + (split + 1.0) * (double)left / tiles_n * sh.bm * n_out *
-                                            (in_dtype == DMATH_F64 ? 8 : 4) / 3e12);
-                if (cost < 0.97 * best) {
-                    best = cost;
-                    ch.tile_m = sh.bm;
-                    ch.tile_n = sh.bn;
-                    ch.split_k = split;
-                    ch.tail_only = 1;
-                }
+        for (int split = 2; full > 0 && left > 0 && split <= 16; split *= 2) {
+            if (!wgrad_split_ok(ktiles, split) || (ktiles + split - 1) / split < 4) break;
+            const int64_t wgs = left * split;
+            const int64_t chain_left = wgs <= 256 ? 1 : (wgs + 256 * slots - 1) / (256 * slots) * slots;
+            const double rate = (in_dtype != DMATH_F16 && (slots == 1 || chain_left == 1)) ? 0.87 : 1.0;
+            const double full_rate = (in_dtype != DMATH_F16 && slots == 1) ? 0.87 : 1.0;
+            double cost = measured * ((double)(full / 256) * ((double)k_depth * per_k / full_rate + 0.4 * area) +
+                                      (double)chain_left * ((double)k_depth / split * per_k / rate + 0.4 * area));
+            cost += 2.4e9 * (3e-6 + (split + 1.0) * (double)left / tiles_n * sh.bm * n_out *
+                                        (in_dtype == DMATH_F64 ? 8 : 4) / 3e12);
+            if (cost < (ch.tail_only ? 1.0 : 0.97) * best) {
+                best = cost;
+                ch.tile_m = sh.bm;
+                ch.tile_n = sh.bn;
+                ch.split_k = split;
+                ch.tail_only = 1;
             }
         }
     }
@@ -1040,7 +1037,7 @@ std::vector<ConvChoice> conv_candidates(int mode, const ConvGeom& g, dmath_dtype
         const int64_t left = tiles - fwd_full_tiles(tiles / tiles_n, tiles_n, sh.bm, sh.bn, in_dtype);
         if (left < tiles && left > 0)
             for (int split = 2; split <= 16; split *= 2)
-                if (left * split <= slots && wgrad_split_ok(ktiles, split) && (ktiles + split - 1) / split >= 4) {
+                if (wgrad_split_ok(ktiles, split) && (ktiles + split - 1) / split >= 4) {
                     c.split_k = split;
                     c.tail_only = 1;
                     out.push_back(c);
