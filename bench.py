@@ -240,6 +240,24 @@ def main():
             for m in (sa, sb, sc):
                 m.destroy()
 
+        # tile counts that do not fill whole rounds of workgroups (1.25 and 2.125 rounds): the
+        # tiles of the last round are split in k
+        for tag, code, npdt, (M, N, K) in (("f32", dm.F32, np.float32, (1280, 4096, 4096)),
+                                           ("f64", dm.F64, np.float64, (1280, 4096, 4096)),
+                                           ("f16", dm.F16, np.float16, (4352, 4096, 4096))):
+            sa = ctx.from_host(rs.uniform(0, 1, (M, K)).astype(npdt))
+            sb = ctx.from_host(rs.normal(0, 0.02, (K, N)).astype(npdt))
+            sc = ctx.matrix(M, N, (1, 1), dm.F32 if code == dm.F16 else code)
+            ms, _ = time_calls([lambda: dm.gemm(ctx, 0, 0, 1.0, sa, sb, 0.0, sc)], 20, 5)
+            pinfo = dm.gemm_plan_info(ctx, 0, 0, sa, sb, sc)
+            calls[f"partial_round_{tag}.nn_M{M}_N{N}_K{K}"] = {
+                "ms": round(ms, 4), "tflops": round(2.0 * M * N * K / ms / 1e9, 2),
+                "frac_peak": round(2.0 * M * N * K / ms / 1e9 / PEAK_TFLOPS[tag], 4),
+                "tile": [pinfo["tile_m"], pinfo["tile_n"], pinfo["split_k"]],
+                "split_tiles": [pinfo["split_tiles"], pinfo["tiles"]]}
+            for m in (sa, sb, sc):
+                m.destroy()
+
     # ---------------- MFMA-only probe: what the matrix cores sustain at their clocks under load
     sustained = {}
     for key, code, iters in (("f32", dm.F32, 4000), ("f16", dm.F16, 8000), ("f64", dm.F64, 4000)):

@@ -12,6 +12,7 @@
 #include <type_traits>
 
 #include "context.hpp"
+#include "epilogue.hpp"
 #include "f32_pipeline.hpp"
 
 namespace dm {
@@ -70,7 +71,7 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmTables t, float alpha,
     const Tile tile = t.tiles[blockIdx.x];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WVN, wn = wave % WVN, l32 = lane & 31;
+    const int wm = wave / WVN, wn = wave % WVN;
 
     v16f acc[MT][NTL];
 #pragma unroll
@@ -88,44 +89,7 @@ __global__ __launch_bounds__(NT) void gemm_f32_kernel(GemmTables t, float alpha,
     PanelWalk<BM, BN, AKC, BKC> walk(t, tile, ks, ks_end, wave, lane);
     run<BM, BN, WVM, AKC, BKC>(walk, n_ktiles, smem, acc);
 
-    if (t.split_k > 1) {  // partial sums; the fixed-order reduction kernel finishes the job
-        float* ws = static_cast<float*>(t.workspace) + (int64_t)split * t.M * t.N;
-#pragma unroll
-        for (int i = 0; i < MT; ++i)
-#pragma unroll
-            for (int j = 0; j < NTL; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = wm * WM + i * 32 + acc32_row(lane, r);
-                    const int col = wn * WN + j * 32 + l32;
-                    if (row < tile.m_len && col < tile.n_len)
-                        ws[(int64_t)(tile.m_glob + row) * t.N + tile.n_glob + col] = acc[i][j][r];
-                }
-        return;
-    }
-    // epilogue: register r of a 32x32 result tile holds row 8*(r/4) + 4*h + r%4, column l32
-    const Panel pc = t.c[tile.mseg * t.n_nseg + tile.nseg];
-    float* c = static_cast<float*>(const_cast<void*>(pc.ptr));
-    // full tiles (the common case) store unmasked; a ragged last tile masks every element
-    auto store = [&](auto ragged) {
-#pragma unroll
-        for (int i = 0; i < MT; ++i)
-#pragma unroll
-            for (int j = 0; j < NTL; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = wm * WM + i * 32 + acc32_row(lane, r);
-                    const int col = wn * WN + j * 32 + l32;
-                    if constexpr (decltype(ragged)::value)
-                        if (row >= tile.m_len || col >= tile.n_len) continue;
-                    float* p = c + (int64_t)(tile.m_off + row) * pc.ld + tile.n_off + col;
-                    float v = alpha * acc[i][j][r];
-                    if (beta != 0.f) v += beta * *p;
-                    *p = v;
-                }
-    };
-    if (tile.m_len == BM && tile.n_len == BN) store(std::false_type{});
-    else store(std::true_type{});
+    store_tile<32, BM, BN, float>(t, tile, split, wm * WM, wn * WN, lane, acc, alpha, beta);
 }
 
 template <int BM, int BN, int WVM, bool AKC, bool BKC>

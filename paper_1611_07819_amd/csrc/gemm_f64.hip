@@ -12,6 +12,7 @@
 #include <type_traits>
 
 #include "context.hpp"
+#include "epilogue.hpp"
 #include "f64_pipeline.hpp"
 
 namespace dm {
@@ -70,7 +71,7 @@ __global__ __launch_bounds__(NT) void gemm_f64_kernel(GemmTables t, double alpha
     const Tile tile = t.tiles[blockIdx.x];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WVN, wn = wave % WVN, l32 = lane & 15;
+    const int wm = wave / WVN, wn = wave % WVN;
 
     v4d acc[MT][NTL];
 #pragma unroll
@@ -88,44 +89,7 @@ __global__ __launch_bounds__(NT) void gemm_f64_kernel(GemmTables t, double alpha
     PanelWalk<BM, BN, AKC, BKC> walk(t, tile, ks, ks_end, wave, lane);
     run<BM, BN, WVM, AKC, BKC>(walk, n_ktiles, smem, acc);
 
-    if (t.split_k > 1) {  // partial sums; the fixed-order reduction kernel finishes the job
-        double* ws = static_cast<double*>(t.workspace) + (int64_t)split * t.M * t.N;
-#pragma unroll
-        for (int i = 0; i < MT; ++i)
-#pragma unroll
-            for (int j = 0; j < NTL; ++j)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int row = wm * WM + i * 16 + acc16d_row(lane, r);
-                    const int col = wn * WN + j * 16 + l32;
-                    if (row < tile.m_len && col < tile.n_len)
-                        ws[(int64_t)(tile.m_glob + row) * t.N + tile.n_glob + col] = acc[i][j][r];
-                }
-        return;
-    }
-    // epilogue: register r of a 16x16 result tile holds row 4*r + lane/16, column lane%16
-    const Panel pc = t.c[tile.mseg * t.n_nseg + tile.nseg];
-    double* c = static_cast<double*>(const_cast<void*>(pc.ptr));
-    // full tiles (the common case) store unmasked; a ragged last tile masks every element
-    auto store = [&](auto ragged) {
-#pragma unroll
-        for (int i = 0; i < MT; ++i)
-#pragma unroll
-            for (int j = 0; j < NTL; ++j)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int row = wm * WM + i * 16 + acc16d_row(lane, r);
-                    const int col = wn * WN + j * 16 + l32;
-                    if constexpr (decltype(ragged)::value)
-                        if (row >= tile.m_len || col >= tile.n_len) continue;
-                    double* p = c + (int64_t)(tile.m_off + row) * pc.ld + tile.n_off + col;
-                    double v = alpha * acc[i][j][r];
-                    if (beta != 0.0) v += beta * *p;
-                    *p = v;
-                }
-    };
-    if (tile.m_len == BM && tile.n_len == BN) store(std::false_type{});
-    else store(std::true_type{});
+    store_tile<16, BM, BN, double>(t, tile, split, wm * WM, wn * WN, lane, acc, alpha, beta);
 }
 
 template <int BM, int BN, int WVM, bool AKC, bool BKC>

@@ -300,7 +300,7 @@ dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_ma
     for (auto& s : ns) nlen.push_back(s.len);
     for (auto& s : ks) klen.push_back(pad_tails ? (s.len + bk - 1) / bk * bk : s.len);
     bool small = true;  // the specialised kernels address a block through 32-bit byte offsets
-    for (const dmath_matrix_s* m : {A, B})
+    for (const dmath_matrix_s* m : {(const dmath_matrix_s*)A, (const dmath_matrix_s*)B, (const dmath_matrix_s*)C})  // C: the epilogue
         small = small && (uint64_t)m->rsplit.step * (uint64_t)m->csplit.step * elem_size(m->dtype) < (1ull << 32);
     SegView view{M, N, K, &mlen, &nlen, &klen, !transA, (bool)transB, al, small, A->dtype, C->dtype,
                  ctx->policy};
@@ -308,6 +308,11 @@ dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_ma
     if (unsplit) ch.split_k = 1;
     if (candidates) *candidates = gemm_candidates(view);
 
+    // the specialised kernels store a tile's partial sums through 32-bit byte offsets from the
+    // tile's first element: rows of the whole-C workspace must allow that
+    if (ch.split_k > 1 && ch.kernel != KERNEL_GENERIC && ch.full_tiles == 0 &&
+        (uint64_t)N * (uint64_t)ch.tile_m * 8 >= (1ull << 32))
+        ch.split_k = 1;
     // split-K: extra cuts of the k axis at multiples of 64 (every kernel's k-step divides 64)
     std::vector<int64_t> split_cuts;
     if (ch.split_k > 1) {
