@@ -301,6 +301,7 @@ struct FastConv {
     // them run it in `split` parts.  tail_only (host side): only the tiles after the last full
     // round of workgroups are split.
     int full_tiles, tail_only;
+    void* sink;  // 256 bytes that nobody reads: where lanes with nothing to store store
 };
 
 // byte offset of pixel m = (n, oh, ow) in Xp (tap (0,0), channel 0)
@@ -429,56 +430,114 @@ __global__ __launch_bounds__(NT) void conv_fwd_kernel(FastConv p, typename P::Ac
         return;
     }
 
-    // epilogue: with the 32x32 MFMAs four consecutive registers are four consecutive pixels of one
-    // output plane (stored together where a plane is a multiple of 4 pixels)
+    // Epilogue.  No store sits in a branch of its own and no load between two stores: the row
+    // pointers (one per image) of a block of rows are loaded together before its stores, and a
+    // lane with nothing to store (pixels past the end, pad filters) stores to `sink`, 256 bytes of
+    // the plan that nobody reads.  (Loads and stores complete in order, so a pointer loaded
+    // between two stores waited for every store before it, and a branch per element made the
+    // compiler wait for everything outstanding.)
+    typedef __attribute__((address_space(1))) TC GTC;
     const int sp_out = p.g.oh * p.g.ow, m_end = p.g.n * sp_out;
+    GTC* const sink = (GTC*)static_cast<TC*>(p.sink);
+    const bool read_c = beta != AccT(0);
     if (!P::kRowQuads || sp_out % 4 != 0) {
-        // one element at a time
+        // one element at a time, four rows (registers) of a block per round
 #pragma unroll
         for (int i = 0; i < MT; ++i)
 #pragma unroll
-            for (int r = 0; r < P::kRegs; ++r) {
-                const int m = m0 + wm * WM + i * E + P::row(lane, r);
-                if (m >= m_end) continue;
-                const int n_img = m / sp_out, sp = m % sp_out;
-                TC* yrow = static_cast<TC*>(const_cast<void*>(p.y_rows[n_img]));
+            for (int g4 = 0; g4 < P::kRegs / 4; ++g4) {
+                GTC* rowp[4];  // &Y[image][0][pixel] of each of these rows; null: no such pixel
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int m = m0 + wm * WM + i * E + P::row(lane, g4 * 4 + e);
+                    const bool ok = m < m_end;
+                    const int mm = ok ? m : 0, n_img = mm / sp_out, sp = mm - n_img * sp_out;
+                    GTC* y = (GTC*)static_cast<TC*>(const_cast<void*>(p.y_rows[n_img]));
+                    rowp[e] = ok ? y + sp : nullptr;
+                }
 #pragma unroll
                 for (int j = 0; j < NTL; ++j) {
                     const int ko = n0 + wn * WN + j * E + lcol;
-                    if (ko >= p.k_real) continue;
-                    TC* dst = yrow + (int64_t)ko * sp_out + sp;
-                    AccT v = alpha * acc[i][j][r];
-                    if (beta != AccT(0)) v += beta * (AccT)*dst;
-                    *dst = to_out<TC>(v);
+                    const bool k_ok = ko < p.k_real;
+                    const int64_t plane = (int64_t)ko * sp_out;
+                    GTC* dst[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) dst[e] = (k_ok && rowp[e]) ? rowp[e] + plane : sink;
+                    if (!read_c) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) *dst[e] = to_out<TC>(alpha * acc[i][j][g4 * 4 + e]);
+                    } else {
+                        AccT old[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) old[e] = (AccT)*dst[e];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            AccT v = alpha * acc[i][j][g4 * 4 + e];
+                            v += beta * old[e];
+                            *dst[e] = to_out<TC>(v);
+                        }
+                    }
                 }
             }
         return;
     }
     if constexpr (P::kRowQuads) {
+        // with the 32x32 MFMAs four consecutive registers are four consecutive pixels of one
+        // output plane: stored together where a plane is a multiple of 4 pixels
+        typedef TC out4 __attribute__((ext_vector_type(4)));
+        typedef __attribute__((address_space(1))) out4 GOut4;
+        // the row pointers of block row i + 1 are loaded before the stores of block row i
+        auto row_pointers = [&](int i, GTC* (&rowp)[4]) {
 #pragma unroll
-    for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            const int m = m0 + wm * WM + i * 32 + 8 * q4 + 4 * h;
-            if (m >= m_end) continue;  // ragged last tile (m_end is a multiple of 4, as sp_out is)
-            const int n_img = m / sp_out, sp = m % sp_out;
-            TC* yrow = static_cast<TC*>(const_cast<void*>(p.y_rows[n_img]));
-#pragma unroll
-            for (int j = 0; j < NTL; ++j) {
-                const int ko = n0 + wn * WN + j * 32 + lcol;
-                if (ko >= p.k_real) continue;  // pad filters
-                TC* dst = yrow + (int64_t)ko * sp_out + sp;
-                typedef TC out4 __attribute__((ext_vector_type(4)));
-                out4 o;
-                if (beta != 0.f) o = *reinterpret_cast<out4*>(dst);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    float v = alpha * acc[i][j][q4 * 4 + e];
-                    if (beta != 0.f) v += beta * (float)o[e];
-                    o[e] = to_out<TC>(v);
-                }
-                *reinterpret_cast<out4*>(dst) = o;
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int m = m0 + wm * WM + i * 32 + 8 * q4 + 4 * h;
+                const bool ok = m < m_end;  // ragged last tile (m_end is a multiple of 4, as sp_out is)
+                const int mm = ok ? m : 0, n_img = mm / sp_out, sp = mm - n_img * sp_out;
+                GTC* y = (GTC*)static_cast<TC*>(const_cast<void*>(p.y_rows[n_img]));
+                rowp[q4] = ok ? y + sp : nullptr;
             }
+        };
+        GTC* rowp[4];
+        row_pointers(0, rowp);
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+            GTC* next[4] = {nullptr, nullptr, nullptr, nullptr};
+            if (i + 1 < MT) row_pointers(i + 1, next);
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                GOut4* dst[NTL];
+#pragma unroll
+                for (int j = 0; j < NTL; ++j) {
+                    const int ko = n0 + wn * WN + j * 32 + lcol;
+                    GTC* d = (ko < p.k_real && rowp[q4]) ? rowp[q4] + (int64_t)ko * sp_out : sink;  // pad filters
+                    dst[j] = reinterpret_cast<GOut4*>(d);
+                }
+                if (!read_c) {
+#pragma unroll
+                    for (int j = 0; j < NTL; ++j) {
+                        out4 o;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = to_out<TC>(alpha * acc[i][j][q4 * 4 + e]);
+                        *dst[j] = o;
+                    }
+                } else {
+                    out4 o[NTL];
+#pragma unroll
+                    for (int j = 0; j < NTL; ++j) o[j] = *dst[j];
+#pragma unroll
+                    for (int j = 0; j < NTL; ++j) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            float v = alpha * acc[i][j][q4 * 4 + e];
+                            v += beta * (float)o[j][e];
+                            o[j][e] = to_out<TC>(v);
+                        }
+                        *dst[j] = o[j];
+                    }
+                }
+            }
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) rowp[q4] = next[q4];
         }
     }
 }
@@ -1182,7 +1241,8 @@ hipError_t launch_typed(const ConvPlan& plan, int mode, double alpha, double bet
     p.ws = t.workspace;
     p.split = t.split_k;
     p.tail_only = plan.tail_only;
-    if (!xp || (mode != CONV_BWD_FILTER && !fp) || (mode == CONV_BWD_FILTER && (!yt || !p.ws)))
+    p.sink = t.sink;
+    if (!xp || !p.sink || (mode != CONV_BWD_FILTER && !fp) || (mode == CONV_BWD_FILTER && (!yt || !p.ws)))
         return hipErrorInvalidValue;  // the plan was not made for this path
 
     static bool configured = false;

@@ -677,6 +677,8 @@ dmath_status_t make_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_
     };
     std::vector<char> buf;
     size_t ox = append(buf, row_ptrs(X)), of = append(buf, row_ptrs(F)), oy = append(buf, row_ptrs(Y));
+    const size_t osink = (buf.size() + 255) / 256 * 256;
+    buf.resize(osink + 256);
     void* dev = ctx->pool.alloc(buf.size());
     if (!dev) return DMATH_ERR_OOM;
     void* ws = nullptr;
@@ -732,6 +734,7 @@ dmath_status_t make_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_
     t.x_rows = reinterpret_cast<const void* const*>(dp + ox);
     t.f_rows = reinterpret_cast<const void* const*>(dp + of);
     t.y_rows = reinterpret_cast<const void* const*>(dp + oy);
+    t.sink = dp + osink;
     t.workspace = ws;
     plan->dev_tables = dev;
     plan->workspace = ws;

@@ -57,6 +57,7 @@ struct ConvTables {
     int32_t split_k;
     void* workspace;  // [split_k][M][N]
     int64_t M, N, K;  // implicit GEMM sizes of the chosen mode
+    void* sink;       // 256 bytes nobody reads (the specialised kernels' masked-out lanes store there)
 };
 
 }  // namespace dm
