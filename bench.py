@@ -20,7 +20,7 @@ if ROOT not in sys.path:
 PEAK_TFLOPS = {"f16": 2516.6, "f32": 157.3, "f64": 78.6}   # dense MFMA peaks of MI355X
 # HBM bytes per GEMM call of cfg2 (mean over the three calls of a step), from the two
 # rocprofv3 --pmc runs summarised in profiles/gemm_f32_cfg2_hbm_traffic.txt; None until measured.
-MEASURED_TRAFFIC_BYTES = 595861216
+MEASURED_TRAFFIC_BYTES = 583725184
 
 
 def main():
