@@ -823,18 +823,29 @@ bool conv_as_gemm_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype)
     return (sp + 63) / 64 * 64 * 100 <= sp * 135;  // planes padded to 64-element tiles: at most 35 % more
 }
 
-// C tiles of the weight gradient: 256 (fp16 only), 128 or 64 filters x 128 columns of (r,s,c)
-// (64 where the channel count is not a multiple of 128: a tile's columns are consecutive
+// C tiles of the weight gradient: 256 (fp16 only), 128 or 64 filters x 128 or 64 columns of
+// (r,s,c) (64 where the channel count is not a multiple of 128: a tile's columns are consecutive
 // channels of one tap).
 static int wgrad_tile_m(const ConvGeom& g, dmath_dtype_t dt)
 {
     const int kp = round64(g.k);
     return (kp % 256 == 0 && dt == DMATH_F16) ? 256 : kp % 128 == 0 ? 128 : 64;
 }
-static int wgrad_tile_n(const ConvGeom& g) { return round64(g.c) % 128 == 0 ? 128 : 64; }
+static int wgrad_tile_n(const ConvGeom& g, dmath_dtype_t dt)
+{
+    if (round64(g.c) % 128 != 0) return 64;
+    // fp64: two 64-wide workgroups per CU are 8-25 % faster than one 128-wide (seven layers);
+    // fp32: level, except where there are few tiles (1x1 layers: 50 -> 41 us with 8 -> 16 tiles)
+    if (dt == DMATH_F64) return 64;
+    if (dt == DMATH_F32) {
+        const int64_t tiles128 = (int64_t)(round64(g.k) / wgrad_tile_m(g, dt)) * ((int64_t)round64(g.c) * g.r * g.s / 128);
+        return tiles128 < 16 ? 64 : 128;
+    }
+    return 128;
+}
 static int64_t wgrad_tiles(const ConvGeom& g, dmath_dtype_t dt)
 {
-    return (int64_t)(round64(g.k) / wgrad_tile_m(g, dt)) * ((int64_t)round64(g.c) * g.r * g.s / wgrad_tile_n(g));
+    return (int64_t)(round64(g.k) / wgrad_tile_m(g, dt)) * ((int64_t)round64(g.c) * g.r * g.s / wgrad_tile_n(g, dt));
 }
 static int64_t wgrad_ktiles(const ConvGeom& g, dmath_dtype_t dt)
 {
@@ -868,7 +879,7 @@ int conv_fast_wgrad_split(const ConvGeom& g, dmath_dtype_t dt)
     const int64_t ktiles = wgrad_ktiles(g, dt);
     const int64_t tiles = wgrad_tiles(g, dt);
     const int unit = 64 / pixel_tile(dt);  // k-tiles per 64 pixels
-    const int slots = 256 * per_cu(wgrad_tile_m(g, dt), wgrad_tile_n(g), dt);
+    const int slots = 256 * per_cu(wgrad_tile_m(g, dt), wgrad_tile_n(g, dt), dt);
     const double w = dt == DMATH_F16 ? 1 : dt == DMATH_F32 ? 4 : 8;
     auto cost = [&](int s) {
         const int64_t per = (ktiles + s - 1) / s, on_cu = (tiles * s + 255) / 256;
@@ -950,7 +961,7 @@ ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int3
     ch.kernel = 1;
     if (mode == CONV_BWD_FILTER) {
         ch.tile_m = wgrad_tile_m(g, in_dtype);
-        ch.tile_n = wgrad_tile_n(g);
+        ch.tile_n = wgrad_tile_n(g, in_dtype);
         ch.split_k = conv_fast_wgrad_split(g, in_dtype);
         return ch;
     }
@@ -1070,7 +1081,7 @@ std::vector<ConvChoice> conv_candidates(int mode, const ConvGeom& g, dmath_dtype
         const int64_t ktiles = wgrad_ktiles(g, in_dtype), tiles = wgrad_tiles(g, in_dtype);
         const int model = conv_fast_wgrad_split(g, in_dtype);
         c.tile_m = wgrad_tile_m(g, in_dtype);
-        c.tile_n = wgrad_tile_n(g);
+        c.tile_n = wgrad_tile_n(g, in_dtype);
         for (int s = 1; s <= 64; ++s)
             if (s == model || (ktiles % s == 0 && tiles * s <= 512 && ktiles / s >= 8)) {
                 c.split_k = s;
@@ -1287,7 +1298,7 @@ hipError_t launch_typed(const ConvPlan& plan, int mode, double alpha, double bet
     p.ktiles_per_split = (p.ktiles + t.split_k - 1) / t.split_k;
     if (!wgrad_split_ok(p.ktiles, t.split_k)) return hipErrorInvalidValue;  // a part without pixels
     const int tiles = (int)wgrad_tiles(g, in) * t.split_k;
-    hipError_t e = launch_wgrad(p, in, wgrad_tile_m(g, in), wgrad_tile_n(g), tiles, st);
+    hipError_t e = launch_wgrad(p, in, wgrad_tile_m(g, in), wgrad_tile_n(g, in), tiles, st);
     if (e != hipSuccess) return e;
     if (plan.out_dtype == DMATH_F64)
         wgrad_reduce<double, double>(p, alpha, beta, st);
