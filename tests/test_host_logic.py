@@ -235,3 +235,29 @@ def test_scheduler_choices_for_small_problems(ctx):
         p = dm.gemm_plan_info(big, 0, 0, X, W, Y)
         assert p["kernel"] != 0 and p["tile_m"] == 64 and p["split_k"] > 1
     big.close()
+
+
+def test_scheduler_splits_only_the_tiles_after_the_last_full_round(ctx):
+    """Tile counts that do not fill whole rounds of workgroups (256 CUs x workgroups per CU): the
+    tiles of the full rounds run unsplit, the rest take partial sums in a compact workspace."""
+    big = dm.Context(FAKE_SLAB, 8 << 30)
+    # fp32, 128x64 tiles, two workgroups per CU: 640 tiles = one round of 512 + 128
+    A, B, C = big.matrix(1280, 4096, (1, 1), dm.F32), big.matrix(4096, 4096, (1, 1), dm.F32), big.matrix(1280, 4096, (1, 1), dm.F32)
+    p = dm.gemm_plan_info(big, 0, 0, A, B, C)
+    assert (p["tile_m"], p["tile_n"], p["tiles"]) == (128, 64, 640)
+    assert p["split_tiles"] == 128 and p["split_k"] >= 2
+    assert p["workspace_bytes"] == p["split_k"] * 128 * 128 * 64 * 4      # only those tiles, not the whole C
+    # exactly two rounds: nothing is split
+    A2, C2 = big.matrix(2048, 4096, (1, 1), dm.F32), big.matrix(2048, 4096, (1, 1), dm.F32)
+    p = dm.gemm_plan_info(big, 0, 0, A2, B, C2)
+    assert p["tiles"] == 1024 and p["split_k"] == 1 and p["split_tiles"] == 0 and p["workspace_bytes"] == 0
+    # fp16, 256x128 tiles, one workgroup per CU: 544 tiles = two rounds + 32
+    Ah, Bh = big.matrix(4352, 4096, (1, 1), dm.F16), big.matrix(4096, 4096, (1, 1), dm.F16)
+    Ch = big.matrix(4352, 4096, (1, 1), dm.F32)
+    p = dm.gemm_plan_info(big, 0, 0, Ah, Bh, Ch)
+    assert (p["tile_m"], p["tile_n"], p["tiles"], p["split_tiles"]) == (256, 128, 544, 32) and p["split_k"] >= 2
+    # the data gradient of the benchmark's fp32 layer: 1152 tiles = 2.25 rounds
+    Y, W, dX = big.matrix(1024, 4096, (4, 4), dm.F32), big.matrix(9216, 4096, (4, 4), dm.F32), big.matrix(1024, 9216, (4, 4), dm.F32)
+    p = dm.gemm_plan_info(big, 0, 1, Y, W, dX)
+    assert (p["tile_m"], p["tile_n"], p["tiles"], p["split_tiles"]) == (128, 64, 1152, 128)
+    big.close()
