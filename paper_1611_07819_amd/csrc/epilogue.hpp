@@ -2,14 +2,15 @@
 // into a split-K workspace) from the MFMA result registers of one wavefront.
 //
 // A full tile stores unmasked.  A ragged last tile goes block by block (one MFMA result tile,
-// 32x32 or 16x16): blocks outside the tile's extent are skipped (decided on scalars), the rest
-// are stored unmasked when they lie wholly inside it and otherwise mask every element without a
-// branch, through raw buffer accesses whose masked-out lanes get an offset past the descriptor's
-// extent (buffer stores with per-lane offsets issue 2.7 times slower than plain stores here).  (With one branch per masked element the compiler waited
-// for all outstanding memory operations, stores included, before every element: the epilogue
-// of a ragged 256x256 fp16 tile took 69000 cycles against 8000 for a full one.)  The beta == 0
-// and beta != 0 cases are separate code; with beta != 0 the old values of a block are loaded
-// together, before its stores.
+// 32x32 or 16x16): blocks outside the tile's extent are skipped (decided on scalars), blocks
+// wholly inside it are stored unmasked, and the blocks across its edge mask every element
+// without a branch, through raw buffer accesses whose masked-out lanes get an offset past the
+// descriptor's extent (buffer stores with per-lane offsets issue 2.7 times slower than plain
+// stores here, hence only for those blocks).  With one branch per masked element the compiler
+// waited for all outstanding memory operations, stores included, before every element: the
+// epilogue of a ragged 256x256 fp16 tile took 69000 cycles against 8000 for a full one.  The
+// beta == 0 and beta != 0 cases are separate code; with beta != 0 the old values of a block are
+// loaded together, before its stores.
 #pragma once
 #include <hip/hip_runtime.h>
 
