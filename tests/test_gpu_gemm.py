@@ -526,3 +526,39 @@ def test_split_of_the_tiles_after_the_last_full_round(oracle, monkeypatch, dt, o
         assert rel_fro(dC.get()[rows], ref) <= TOL[dt]
     finally:
         c.close()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_shapes_with_partial_last_rounds(ctx, oracle, seed):
+    """Seeded shapes whose tile count is a little more than whole rounds of workgroups, ragged in
+    both directions, random ops, grids and precisions, the cost model's own choices (which split
+    the tiles after the last full round where that pays): small-integer data, bit for bit."""
+    r = np.random.default_rng(9100 + seed)
+    dt, out = [(dm.F32, dm.F32), (dm.F64, dm.F64), (dm.F16, dm.F32), (dm.F16, dm.F16)][seed % 4]
+    rows, cols = (128, 64) if dt != dm.F16 else (256, 128)
+    slots = 512 if dt != dm.F16 else 256
+    tn = int(r.integers(24, 40))                             # column tiles
+    tm = (slots * int(r.integers(1, 3)) + int(r.integers(8, 120))) // tn + 1
+    M = tm * rows - int(r.integers(1, rows // 2)) // 8 * 8
+    N = tn * cols - int(r.integers(1, cols // 2)) // 8 * 8
+    K = 64 * int(r.integers(2, 9))
+    ta, tb = int(r.integers(0, 2)), int(r.integers(0, 2))
+    opA = r.integers(-2, 3, (M, K)).astype(NP[dt])
+    opB = r.integers(-2, 3, (K, N)).astype(NP[dt])
+    C0 = r.integers(-2, 3, (M, N)).astype(NP[out])
+    A, B = stored(opA, ta), stored(opB, tb)
+    ctx.set_kernel_policy(0)
+    dA, dB, dC = ctx.from_host(A), ctx.from_host(B), ctx.from_host(C0)
+    info = dm.gemm_plan_info(ctx, ta, tb, dA, dB, dC)
+    assert info["kernel"] > 0, info
+    dm.gemm(ctx, ta, tb, 1.0, dA, dB, 1.0, dC)
+    sel = sorted(set(int(x) for x in r.integers(0, M, 48)) | {0, M - 1})
+    ref = oracle.gemm(bool(ta), bool(tb), 1.0, A, B, 1.0, C0, rows=sel)
+    got = dC.get()[sel].astype(np.float64)
+    for m in (dA, dB, dC):
+        m.destroy()
+    what = (seed, dt, out, (M, N, K), (ta, tb), info)
+    if out == dm.F16 and np.abs(ref).max() > 2048:
+        assert rel_fro(got, ref) <= TOL[dt], what
+    else:
+        assert np.array_equal(got, ref), what
