@@ -863,7 +863,8 @@ static bool wgrad_split_ok(int64_t ktiles, int s)
 // Workgroups per CU by the LDS their tile needs (160 KiB per CU).
 static int per_cu(int bm, int bn, dmath_dtype_t dt)
 {
-    if (dt == DMATH_F16) return 1;
+    // (fp16: the 256x256 and 224x256 forward tiles run two stages, every other tile three)
+    if (dt == DMATH_F16) return 160 * 1024 / PipeF16::lds_bytes(bm, bn, bm * bn >= 224 * 256 ? 2 : 3);
     return 160 * 1024 / (dt == DMATH_F32 ? PipeF32::lds_bytes(bm, bn, 3) : PipeF64::lds_bytes(bm, bn, 3));
 }
 
@@ -873,7 +874,10 @@ static int per_cu(int bm, int bn, dmath_dtype_t dt)
 // and read back grow with it.  w = 1 in fp16 (the balance point sqrt(k-tiles) matches the timing
 // samples on 1x1 and 3x3 layers of 14x14 and 28x28 pixels), 4 in fp32 and 8 in fp64, whose steps
 // take that many times as long; an fp32 / fp64 CU with a single workgroup runs at 0.87 of the
-// rate (as in choose_conv).
+// rate (as in choose_conv).  Small fp16 tiles leave a CU partly idle unless several workgroups
+// share it (64x64: three fit, one alone reaches 0.45 of the rate of three, two 0.8; 128x64 and
+// 64x128: two fit, one alone 0.73): measured on 64-channel layers of 56x56 pixels, where 56 parts
+// on two workgroups per CU take 37.7 us against 47.0 us for 28 parts on one.
 int conv_fast_wgrad_split(const ConvGeom& g, dmath_dtype_t dt)
 {
     const int64_t ktiles = wgrad_ktiles(g, dt);
@@ -881,13 +885,20 @@ int conv_fast_wgrad_split(const ConvGeom& g, dmath_dtype_t dt)
     const int unit = 64 / pixel_tile(dt);  // k-tiles per 64 pixels
     const int slots = 256 * per_cu(wgrad_tile_m(g, dt), wgrad_tile_n(g, dt), dt);
     const double w = dt == DMATH_F16 ? 1 : dt == DMATH_F32 ? 4 : 8;
+    const int fit = slots / 256;
     auto cost = [&](int s) {
         const int64_t per = (ktiles + s - 1) / s, on_cu = (tiles * s + 255) / 256;
-        const double rate = (dt != DMATH_F16 && on_cu == 1) ? 0.87 : 1.0;
+        double rate = 1.0;
+        if (dt != DMATH_F16)
+            rate = on_cu == 1 ? 0.87 : 1.0;
+        else if (fit == 3)
+            rate = on_cu == 1 ? 0.45 : on_cu == 2 ? 0.8 : 1.0;
+        else if (fit == 2)
+            rate = on_cu == 1 ? 0.73 : 1.0;
         return on_cu * (double)(per / unit) * w / rate + s;
     };
     int best = 1;
-    for (int s = 2; s <= 64; ++s) {
+    for (int s = 2; s <= 96; ++s) {
         const int64_t per = (ktiles + s - 1) / s;
         if (wgrad_split_ok(ktiles, s) && tiles * s <= slots && per >= 8 * unit && cost(s) < cost(best)) best = s;
     }
@@ -963,6 +974,10 @@ ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int3
         ch.tile_m = wgrad_tile_m(g, in_dtype);
         ch.tile_n = wgrad_tile_n(g, in_dtype);
         ch.split_k = conv_fast_wgrad_split(g, in_dtype);
+        if (const char* e = std::getenv("DMATH_CONV_SPLIT")) {  // experiments and tests
+            const int forced = std::atoi(e);
+            if (forced >= 1 && forced <= 128 && wgrad_split_ok(wgrad_ktiles(g, in_dtype), forced)) ch.split_k = forced;
+        }
         return ch;
     }
     const int64_t m = mode == CONV_FWD ? (int64_t)g.n * g.oh * g.ow : (int64_t)g.n * g.h * g.w;
@@ -1082,8 +1097,8 @@ std::vector<ConvChoice> conv_candidates(int mode, const ConvGeom& g, dmath_dtype
         const int model = conv_fast_wgrad_split(g, in_dtype);
         c.tile_m = wgrad_tile_m(g, in_dtype);
         c.tile_n = wgrad_tile_n(g, in_dtype);
-        for (int s = 1; s <= 64; ++s)
-            if (s == model || (ktiles % s == 0 && tiles * s <= 512 && ktiles / s >= 8)) {
+        for (int s = 1; s <= 96; ++s)
+            if (s == model || (ktiles % s == 0 && tiles * s <= 768 && ktiles / s >= 8)) {
                 c.split_k = s;
                 out.push_back(c);
             }
