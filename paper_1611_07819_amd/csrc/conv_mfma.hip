@@ -869,7 +869,9 @@ static int per_cu(int bm, int bn, dmath_dtype_t dt)
 }
 
 // Split count for the weight gradient: the number of parts s (each of ceil(k-tiles / s) pixel
-// tiles, the last one possibly shorter) with at most one round of workgroups that minimises
+// tiles, at least 256 pixels, the last one possibly shorter) with at most four rounds of
+// workgroups (144 tiles of an fp32 layer leave 112 CUs idle unsplit: 424 us, 332 us in four
+// parts) that minimises
 // (w x 64-pixel steps of the busiest CU + s): the parts shorten with s, the partial sums written
 // and read back grow with it.  w = 1 in fp16 (the balance point sqrt(k-tiles) matches the timing
 // samples on 1x1 and 3x3 layers of 14x14 and 28x28 pixels), 4 in fp32 and 8 in fp64, whose steps
@@ -900,7 +902,7 @@ int conv_fast_wgrad_split(const ConvGeom& g, dmath_dtype_t dt)
     int best = 1;
     for (int s = 2; s <= 96; ++s) {
         const int64_t per = (ktiles + s - 1) / s;
-        if (wgrad_split_ok(ktiles, s) && tiles * s <= slots && per >= 8 * unit && cost(s) < cost(best)) best = s;
+        if (wgrad_split_ok(ktiles, s) && tiles * s <= 4 * slots && per >= 4 * unit && cost(s) < cost(best)) best = s;
     }
     return best;
 }
@@ -1074,7 +1076,7 @@ ConvChoice choose_conv(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int3
 // Everything worth a timing sample: the generic kernel (weight gradient: unsplit and with its
 // own split), and where the specialised kernels apply, every tile shape (forward, data
 // gradient) or the cost model's split and every split count that divides the k-tiles evenly,
-// keeps at least 8 of them per part and at most two rounds of workgroups (weight gradient).
+// keeps at least 4 of them per part and at most 1024 workgroups (weight gradient).
 std::vector<ConvChoice> conv_candidates(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, int32_t policy)
 {
     std::vector<ConvChoice> out;
@@ -1098,7 +1100,7 @@ std::vector<ConvChoice> conv_candidates(int mode, const ConvGeom& g, dmath_dtype
         c.tile_m = wgrad_tile_m(g, in_dtype);
         c.tile_n = wgrad_tile_n(g, in_dtype);
         for (int s = 1; s <= 96; ++s)
-            if (s == model || (ktiles % s == 0 && tiles * s <= 768 && ktiles / s >= 8)) {
+            if (s == model || (ktiles % s == 0 && tiles * s <= 1024 && ktiles / s >= 4)) {
                 c.split_k = s;
                 out.push_back(c);
             }
