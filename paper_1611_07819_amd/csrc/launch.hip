@@ -245,7 +245,7 @@ GemmChoice choose_gemm(const SegView& v)
 }
 
 // Every configuration worth a timing sample: each shape unsplit, with the cost model's split,
-// with the power-of-two splits that keep at least 128 of K per part and at most two rounds
+// with the power-of-two splits that keep at least 128 of K per part and at most four rounds
 // of workgroups, and with only the tiles after the last full round split; the generic kernel unsplit and with its own split.
 std::vector<GemmChoice> gemm_candidates(const SegView& v)
 {
@@ -269,7 +269,7 @@ std::vector<GemmChoice> gemm_candidates(const SegView& v)
         add(s.kernel, s.bm, s.bn, s.bk, 1);
         add(s.kernel, s.bm, s.bn, s.bk, best_split(v, s, nullptr));
         for (int32_t sp = 2; sp <= 32; sp *= 2)
-            if (v.K / sp >= 128 && tiles * sp <= 2 * kCUs) add(s.kernel, s.bm, s.bn, s.bk, sp);
+            if (v.K / sp >= 128 && tiles * sp <= 4 * kCUs * s.per_cu) add(s.kernel, s.bm, s.bn, s.bk, sp);
         int32_t tsplit = 1;
         double tt = 0;
         const int32_t full = tail_split(v, s, &tsplit, &tt);  // only the last round split
