@@ -170,3 +170,53 @@ def test_replay_refreshes_the_padded_k_tails(ctx, oracle):
         assert np.array_equal(dC.get().astype(np.float64), oracle.gemm(False, False, 1.0, A2, B2, 0.0))
         assert np.array_equal(dY.get().astype(np.float64), oracle.conv_fwd(od, 1.0, x2, hf))
     ctx.pipeline_destroy(pid)
+
+
+def test_replay_with_split_last_rounds(ctx, oracle, monkeypatch):
+    """A GEMM whose tiles after the last full round of workgroups are split (two launches over
+    views of one tile table and a reduction over those tiles) and a convolution forward pass
+    whose (r, s, c) loop is split, recorded and replayed three times on changing inputs: every
+    replay equals the eager run bit for bit and the oracle on sampled rows."""
+    monkeypatch.setenv("DMATH_TILE", "128x64")
+    monkeypatch.setenv("DMATH_GEMM_SPLIT", "4t")
+    monkeypatch.setenv("DMATH_CONV_SPLIT", "3")
+    r = np.random.default_rng(803)
+    M, N, K = 1300, 4128, 256                     # 715 tiles of 128x64 on 512 workgroup slots
+    A = r.integers(-2, 3, (M, K)).astype(np.float32)
+    B = r.integers(-2, 3, (K, N)).astype(np.float32)
+    dA, dB, dC = ctx.from_host(A), ctx.from_host(B), ctx.matrix(M, N, (1, 1), dm.F32)
+    info = dm.gemm_plan_info(ctx, 0, 0, dA, dB, dC)
+    assert info["split_k"] == 4 and 0 < info["split_tiles"] < info["tiles"], info
+    geo = dict(n=3, c=128, h=14, w=14, k=256, r=3, s=3, pad_h=1, pad_w=1)
+    cd, od = dm.ConvDesc(**geo), oracle.ConvDesc(**geo)
+    hx = r.integers(-1, 2, (3, 128 * 196)).astype(np.float16)
+    hf = r.integers(-1, 2, (256, 128 * 9)).astype(np.float16)
+    dX, dF = ctx.from_host(hx), ctx.from_host(hf)
+    dY = ctx.matrix(3, 256 * 196, (1, 1), dm.F32)
+    rows = list(range(0, M, 97)) + [M - 1]
+
+    def step():
+        dm.gemm(ctx, 0, 0, 1.0, dA, dB, 1.0, dC)                 # accumulates into C
+        dm.conv_fwd(ctx, cd, 1.0, dX, dF, 0.0, dY)
+
+    dC.set(np.zeros((M, N), np.float32))
+    step()
+    ctx.pipeline_begin()
+    step()
+    pid = ctx.pipeline_end()
+    for rep in range(3):
+        A2 = r.integers(-2, 3, (M, K)).astype(np.float32)
+        x2 = r.integers(-1, 2, hx.shape).astype(np.float16)
+        c0 = r.integers(-3, 4, (M, N)).astype(np.float32)
+        dA.set(A2); dX.set(x2); dC.set(c0)
+        ctx.pipeline_replay(pid)
+        got_c, got_y = dC.get(), dY.get()
+        assert np.array_equal(got_c[rows].astype(np.float64), oracle.gemm(False, False, 1.0, A2, B, 1.0, c0, rows=rows))
+        assert np.array_equal(got_y.astype(np.float64), oracle.conv_fwd(od, 1.0, x2, hf))
+        dC.set(c0)
+        step()
+        assert np.array_equal(dC.get(), got_c) and np.array_equal(dY.get(), got_y)
+    ctx.pipeline_destroy(pid)
+    ctx.tune_reset()                              # drop the plans made under the overrides
+    for m in (dA, dB, dC, dX, dF, dY):
+        m.destroy()
