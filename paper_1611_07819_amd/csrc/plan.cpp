@@ -559,6 +559,8 @@ dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_ma
     return DMATH_OK;
 }
 
+static ConvGeom geometry_of(const dmath_conv_desc_t* d);
+
 dmath_status_t get_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t* d,
                              dmath_matrix_s* X, dmath_matrix_s* F, dmath_matrix_s* Y,
                              ConvPlan** out)
@@ -577,6 +579,18 @@ dmath_status_t get_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t
     if (tuned != ctx->tuned_conv.end() && ctx->policy == 0) forced = &tuned->second;
     std::unique_ptr<ConvPlan> plan;
     dmath_status_t st = make_conv_plan(ctx, mode, d, X, F, Y, forced, &plan);
+    if (st == DMATH_ERR_OOM) {
+        // no room for the partial sums of a split forward pass / data gradient: the same kernel
+        // and tile without the split
+        ConvChoice ch = forced ? *forced
+                               : choose_conv(mode, geometry_of(d), mode == CONV_FWD ? X->dtype : Y->dtype, ctx->policy);
+        if (ch.kernel == 1 && mode != CONV_BWD_FILTER && ch.split_k > 1) {
+            ch.split_k = 1;
+            ch.tail_only = 0;
+            drop_unused_relayouts(ctx);
+            st = make_conv_plan(ctx, mode, d, X, F, Y, &ch, &plan);
+        }
+    }
     if (st == DMATH_ERR_OOM) {
         // no room for the re-layout copies or the partial sums: the generic kernel, unsplit,
         // needs neither (section 4.1: a slower algorithm where memory is the constraint)

@@ -273,4 +273,14 @@ def test_full_pool_falls_back_to_configurations_without_workspace(oracle):
     dm.conv_fwd(ctx, d, 1.0, X, F, 0.0, Y)
     assert ctx.relayout_stats()["bytes_held"] > 0
     assert rel_fro(Y.get(), oracle.conv_fwd(od, 1.0, hx, hf)) <= TOL[dm.F16]
+    # room for the copies (0.9 MB) but not for the partial sums of a forward pass whose k-loop is
+    # split (4 tiles: the cost model wants at least 2 parts of 1 MB each): same kernel, unsplit
+    ctx.tune_reset()
+    assert ctx.relayout_stats()["bytes_held"] == 0
+    filler = fill_pool((1 << 20) + (600 << 10))
+    dm.conv_fwd(ctx, d, 1.0, X, F, 0.0, Y)
+    assert ctx.relayout_stats()["bytes_held"] > 0            # the specialised kernel's copies
+    assert ctx.pool_stats()["capacity"] - ctx.pool_stats()["in_use"] < 1 << 20
+    assert rel_fro(Y.get(), oracle.conv_fwd(od, 1.0, hx, hf)) <= TOL[dm.F16]
+    filler.destroy()
     ctx.close()
