@@ -276,29 +276,9 @@ dmath_status_t dmath_conv_tune(dmath_ctx_t ctx, int32_t mode, const dmath_conv_d
                                size_t workspace_limit, int32_t trials, dmath_tune_result_t *result);
 dmath_status_t dmath_tune_reset(dmath_ctx_t ctx);
 
-/*
- * Measurement aid, for builds of the library made with -DDMATH_CYCLE_PROBE only (the product
- * library returns DMATH_ERR_UNSUPPORTED): after a specialised fp16 dmath_gemm, waits for
- * the stream and returns what wavefront 0 of the workgroup owning C tile (0,0) (first k-split) counted:
- * out6[0..2] shader-clock cycles of prologue, k-loop, epilogue; out6[3] cycles waiting at the
- * per-k-tile barrier; out6[4] elapsed ticks of the 100 MHz reference clock; out6[5] k-tiles.
- * (cycles / ticks * 100 MHz = the clock the kernel ran at.)
- */
-dmath_status_t dmath_cycle_probe_read(dmath_ctx_t ctx, uint64_t *out6);
-
 /* Kernel selection: 0 = automatic (specialised kernels where their preconditions hold),
  * 1 = always the guarded generic kernel (for testing and debugging).  Drops cached plans. */
 dmath_status_t dmath_set_kernel_policy(dmath_ctx_t ctx, int32_t policy);
-
-/*
- * Measurement aid (not part of the paper's method): enqueues a register-only kernel in which
- * every wavefront issues independent chains of the MFMA instruction the GEMM kernels of
- * `dtype` use, `iters` times 16 instructions per wavefront, and returns in *flops the number
- * of floating-point operations it performs.  Timing it gives the matrix-core rate the chip
- * sustains at its clocks under load, to be read beside the nominal peak.
- */
-dmath_status_t dmath_mfma_peak_probe(dmath_ctx_t ctx, dmath_dtype_t dtype, int32_t iters,
-                                     double *flops);
 
 /* Waits for all work enqueued on the context's stream. */
 dmath_status_t dmath_synchronize(dmath_ctx_t ctx);

@@ -1,0 +1,40 @@
+/*
+ * dmath_measure.h -- measurement aids of the dMath GEMM / convolution library.  Nothing here is
+ * part of the paper's method or of the product interface (dmath.h); bench and profiling programs
+ * use these calls to put the kernels' timings beside what the matrix cores sustain and to read a
+ * kernel's own cycle counts.  Same conventions as dmath.h: a status is returned, nothing throws,
+ * out-parameters are untouched on error.
+ */
+#ifndef DMATH_MEASURE_H
+#define DMATH_MEASURE_H
+
+#include "dmath.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Measurement aid, for builds of the library made with -DDMATH_CYCLE_PROBE only (the product
+ * library returns DMATH_ERR_UNSUPPORTED): after a specialised fp16 dmath_gemm, waits for
+ * the stream and returns what wavefront 0 of the workgroup owning C tile (0,0) (first k-split) counted:
+ * out6[0..2] shader-clock cycles of prologue, k-loop, epilogue; out6[3] cycles waiting at the
+ * per-k-tile barrier; out6[4] elapsed ticks of the 100 MHz reference clock; out6[5] k-tiles.
+ * (cycles / ticks * 100 MHz = the clock the kernel ran at.)
+ */
+dmath_status_t dmath_cycle_probe_read(dmath_ctx_t ctx, uint64_t *out6);
+
+/*
+ * Measurement aid (not part of the paper's method): enqueues a register-only kernel in which
+ * every wavefront issues independent chains of the MFMA instruction the GEMM kernels of
+ * `dtype` use, `iters` times 16 instructions per wavefront, and returns in *flops the number
+ * of floating-point operations it performs.  Timing it gives the matrix-core rate the chip
+ * sustains at its clocks under load, to be read beside the nominal peak.
+ */
+dmath_status_t dmath_mfma_peak_probe(dmath_ctx_t ctx, dmath_dtype_t dtype, int32_t iters,
+                                     double *flops);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DMATH_MEASURE_H */

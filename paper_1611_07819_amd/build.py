@@ -26,7 +26,7 @@ def sources():
 
 def _newest_header():
     hs = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hpp")]
-    hs.append(os.path.join(INCLUDE, "dmath.h"))
+    hs += [os.path.join(INCLUDE, h) for h in os.listdir(INCLUDE) if h.endswith(".h")]
     return max(os.path.getmtime(h) for h in hs)
 
 

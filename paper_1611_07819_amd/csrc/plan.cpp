@@ -161,8 +161,7 @@ void drop_plans_using(dmath_ctx_s* ctx, uint64_t id)
     for (auto it = ctx->gemm_plans.begin(); it != ctx->gemm_plans.end();) {
         auto& u = it->second->uses;
         if (std::find(u.begin(), u.end(), id) != u.end()) {
-            if (it->second->dev_tables) ctx->pool.free(it->second->dev_tables);
-            if (it->second->workspace) ctx->pool.free(it->second->workspace);
+            free_gemm_plan(ctx, *it->second);
             it = ctx->gemm_plans.erase(it);
         } else
             ++it;
@@ -181,10 +180,7 @@ void drop_plans_using(dmath_ctx_s* ctx, uint64_t id)
 void drop_all_plans(dmath_ctx_s* ctx)
 {
     drop_all_pipelines(ctx);
-    for (auto& kv : ctx->gemm_plans) {
-        if (kv.second->dev_tables) ctx->pool.free(kv.second->dev_tables);
-        if (kv.second->workspace) ctx->pool.free(kv.second->workspace);
-    }
+    for (auto& kv : ctx->gemm_plans) free_gemm_plan(ctx, *kv.second);
     ctx->gemm_plans.clear();
     for (auto& kv : ctx->conv_plans) free_conv_plan(ctx, *kv.second);
     ctx->conv_plans.clear();

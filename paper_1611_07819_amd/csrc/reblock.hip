@@ -5,6 +5,8 @@
 // threads, 16 rows per workgroup, 16 bytes of the wider type per lane where alignment allows.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "context.hpp"
 
 namespace dm {
@@ -36,27 +38,28 @@ template <class TD, class TS, int VEC>
 __global__ __launch_bounds__(256) void reblock_kernel(const CopyCell* cells)
 {
     const CopyCell c = cells[blockIdx.x];
-    const int r0 = blockIdx.y * kRows;
-    if (r0 >= c.rows) return;
-    const int rows = min(kRows, c.rows - r0);
-    const TS* src = static_cast<const TS*>(c.src);
-    TD* dst = static_cast<TD*>(c.dst);
-    const int vcols = c.cols / VEC;
-    const int count = rows * vcols;
-    for (int e = threadIdx.x; e < count; e += 256) {
-        const int i = r0 + e / vcols, j = (e % vcols) * VEC;
-        const TS* sp = src + (int64_t)i * c.src_ld + j;
-        TD* dp = dst + (int64_t)i * c.dst_ld + j;
-        if constexpr (VEC == 1) {
-            *dp = convert<TD, TS>(*sp);
-        } else {
-            typedef TS vsrc __attribute__((ext_vector_type(VEC)));
-            typedef TD vdst __attribute__((ext_vector_type(VEC)));
-            const vsrc v = *reinterpret_cast<const vsrc*>(sp);
-            vdst o;
+    // grid.y is capped by the launcher: taller cells are walked in strides of the grid
+    for (int r0 = blockIdx.y * kRows; r0 < c.rows; r0 += gridDim.y * kRows) {
+        const int rows = min(kRows, c.rows - r0);
+        const TS* src = static_cast<const TS*>(c.src);
+        TD* dst = static_cast<TD*>(c.dst);
+        const int vcols = c.cols / VEC;
+        const int count = rows * vcols;
+        for (int e = threadIdx.x; e < count; e += 256) {
+            const int i = r0 + e / vcols, j = (e % vcols) * VEC;
+            const TS* sp = src + (int64_t)i * c.src_ld + j;
+            TD* dp = dst + (int64_t)i * c.dst_ld + j;
+            if constexpr (VEC == 1) {
+                *dp = convert<TD, TS>(*sp);
+            } else {
+                typedef TS vsrc __attribute__((ext_vector_type(VEC)));
+                typedef TD vdst __attribute__((ext_vector_type(VEC)));
+                const vsrc v = *reinterpret_cast<const vsrc*>(sp);
+                vdst o;
 #pragma unroll
-            for (int q = 0; q < VEC; ++q) o[q] = convert<TD, TS>(v[q]);
-            *reinterpret_cast<vdst*>(dp) = o;
+                for (int q = 0; q < VEC; ++q) o[q] = convert<TD, TS>(v[q]);
+                *reinterpret_cast<vdst*>(dp) = o;
+            }
         }
     }
 }
@@ -92,7 +95,7 @@ int reblock_vector_width(dmath_dtype_t sd, dmath_dtype_t dd)
 hipError_t launch_reblock(dmath_dtype_t sd, dmath_dtype_t dd, const CopyCell* cells, int n_cells,
                           int max_rows, bool vectors, hipStream_t st)
 {
-    dim3 grid(n_cells, (max_rows + kRows - 1) / kRows);
+    dim3 grid(n_cells, std::min((max_rows + kRows - 1) / kRows, 65535));  // grid.y limit of the device
     if (sd == DMATH_F64) return launch_src<double>(dd, cells, grid, vectors, st);
     if (sd == DMATH_F32) return launch_src<float>(dd, cells, grid, vectors, st);
     return launch_src<_Float16>(dd, cells, grid, vectors, st);

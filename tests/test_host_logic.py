@@ -22,8 +22,12 @@ def ctx():
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "dmath.h")).read()
-    names = set(re.findall(r"\b(dmath_[a-z_0-9]+)\s*\(", header))
+    names = set()
+    for h in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if h.endswith(".h"):
+            names |= set(re.findall(r"\b(dmath_[a-z_0-9]+)\s*\(", open(os.path.join(ROOT, "include", h)).read()))
+    product = open(os.path.join(ROOT, "include", "dmath.h")).read()
+    assert "probe" not in product          # measurement aids live in dmath_measure.h
     assert {"dmath_init", "dmath_matrix_create", "dmath_gemm", "dmath_conv_fwd",
             "dmath_conv_bwd_filter", "dmath_conv_bwd_data"} <= names
     lib = ctypes.CDLL(os.path.join(ROOT, "paper_1611_07819_amd", "libdmath.so"))
@@ -261,3 +265,35 @@ def test_scheduler_splits_only_the_tiles_after_the_last_full_round(ctx):
     p = dm.gemm_plan_info(big, 0, 1, Y, W, dX)
     assert (p["tile_m"], p["tile_n"], p["tiles"], p["split_tiles"]) == (128, 64, 1152, 128)
     big.close()
+
+
+def test_exceptions_do_not_cross_the_c_boundary():
+    """A grid whose bookkeeping cannot be allocated must come back as DMATH_ERR_OOM, not as a C++
+    exception that ends the process.  Run in a child whose address space is limited, so that the
+    allocation fails quickly and this process is not disturbed."""
+    import subprocess
+    import sys
+    code = r"""
+import resource, sys
+sys.path.insert(0, %r)
+import paper_1611_07819_amd as dm
+from paper_1611_07819_amd import dmath as binding
+ctx = dm.Context(0x7F0000000100, 1 << 46)          # fake slab: host logic never dereferences it
+resource.setrlimit(resource.RLIMIT_AS, (3 << 30, 3 << 30))
+n = (1 << 31) - 1
+for shape, grid in (((n, n), (n, n)),              # 2^62 block pointers: no container can hold them
+                    ((n, 1), (n, 1))):             # 16 GiB of block pointers: bad_alloc under the limit
+    try:
+        ctx.matrix(shape[0], shape[1], grid, dm.F16)
+    except binding.DmathError as e:
+        assert e.code == 6, e.code                 # DMATH_ERR_OOM
+    else:
+        raise SystemExit("huge grid was accepted")
+assert ctx.pool_stats()["in_use"] == 0             # nothing of the failed handles is left behind
+m = ctx.matrix(64, 64, (2, 2), dm.F32)             # and the context still works
+assert ctx.pool_stats()["in_use"] == 4 * 32 * 32 * 4
+ctx.close()
+print("barrier ok")
+""" % ROOT
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and "barrier ok" in r.stdout, (r.returncode, r.stdout[-400:], r.stderr[-800:])
