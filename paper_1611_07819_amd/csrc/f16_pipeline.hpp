@@ -214,19 +214,31 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
     //   - meets the others at the workgroup barrier.
     // After that barrier tile kt+1 is visible to everybody and nobody reads tile kt's stage
     // any more.  So the last step of tile kt already prefetches the first fragments of tile
-    // kt+1 (no LDS latency is exposed at tile boundaries), and the stage of tile kt is free:
-    //   STAGES == 3: tile kt+2 is fetched during steps 0..2 of iteration kt into the stage of
-    //                tile kt-1 (freed by the barrier of iteration kt-1); at the barrier only
-    //                those loads may still be outstanding;
-    //   STAGES == 2: tile kt+2 is fetched during the last step of iteration kt into the stage
-    //                of tile kt itself; at the barrier nothing may be outstanding.
+    // kt+1 (no LDS latency is exposed at tile boundaries), and the stage of tile kt is free for
+    // tile kt+STAGES.  The loads of that tile are spread over a whole iteration, because the
+    // four wavefronts run in lockstep and share one address unit that takes 16 cycles per
+    // 1 KiB load: bunched into one k-step they queue behind each other and the matrix
+    // instructions behind them (a 256x256 tile lost a quarter of its cycles that way).  Its
+    // first kFirst loads are issued during the last step of iteration kt (right after the
+    // barrier that freed the stage), the others during the first kRestSteps steps of iteration
+    // kt+1:
+    //   STAGES == 3: all four steps are used; the tile has until the barrier of iteration kt+2
+    //                to land, and at a barrier only the loads of the tile after the next one may
+    //                still be outstanding;
+    //   STAGES == 2: the tile must have landed at the barrier of iteration kt+1, so its last
+    //                loads are issued no later than step kRestSteps-1 of that iteration and at
+    //                the barrier nothing may be outstanding.
     // The instruction order inside a step is pinned: after every MFMA one fragment read (two in
     // the narrow tiles, which have more fragments than MFMAs per step) and at most one load, so
     // neither LDS nor the memory pipeline holds up the matrix instructions.
     constexpr int kSteps = BK / 16, kMfma = MT * NTL, kReads = MT + NTL;
     constexpr int kReadsPerSlot = (kReads + kMfma - 1) / kMfma;  // 1 except for the narrow tiles
-    constexpr int kDmaSlots = (STAGES == 3 ? (kSteps - 1) : 1) * kMfma;
-    constexpr int kDmaPerSlot = (kPerTile + kDmaSlots - 1) / kDmaSlots;
+    constexpr int kRestSteps = STAGES == 3 ? kSteps - 1 : 2;
+    constexpr int kFirst = (kPerTile + kRestSteps) / (kRestSteps + 1);  // loads issued in the last step
+    constexpr int kRest = kPerTile - kFirst;                            // ... in steps 0 .. kRestSteps-1
+    constexpr int kRestSlots = kRestSteps * kMfma;
+    constexpr int kRestPerSlot = (kRest + kRestSlots - 1) / kRestSlots;
+    constexpr int kFirstPerSlot = (kFirst + kMfma - 1) / kMfma;
 
     v8h fa[2][MT], fb[2][NTL];
     // read order: what the first MFMAs need comes first (A0, all B, then the other A)
@@ -240,23 +252,37 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
             fa[buf][r - NTL] = TA::fragment(sa, fa_base[r - NTL], wm * WM + (r - NTL) * 32 + l32, h, s);
     };
 
-    // One iteration.  HAS_NEXT: tile kt+1 exists; HAS_DMA: tile kt+2 exists and is fetched.
-    auto iteration = [&](int stage, auto has_next, auto has_dma) {
-        constexpr bool HAS_NEXT = decltype(has_next)::value, HAS_DMA = decltype(has_dma)::value;
-        const int stage1 = stage + 1 == STAGES ? 0 : stage + 1;               // tile kt+1
-        const int stage2 = STAGES == 3 ? (stage == 0 ? 2 : stage - 1) : stage;  // tile kt+2
+    // One iteration (tile kt in `stage`).  HAS_NEXT: tile kt+1 exists; DMA_REST: tile
+    // kt+STAGES-1 exists (its first loads are in flight, `walk` describes it, the others are
+    // issued now); DMA_FIRST: tile kt+STAGES exists (its first loads are issued in the last step).
+    auto iteration = [&](int stage, auto has_next, auto dma_rest, auto dma_first) {
+        constexpr bool HAS_NEXT = decltype(has_next)::value, DMA_REST = decltype(dma_rest)::value,
+                       DMA_FIRST = decltype(dma_first)::value;
+        const int stage1 = stage + 1 == STAGES ? 0 : stage + 1;    // tile kt+1
+        const int stage_rest = stage == 0 ? STAGES - 1 : stage - 1;  // tile kt+STAGES-1
         const lds_char* sa = lds + stage * kStage;
         const lds_char* sa1 = lds + stage1 * kStage;
-        const uint32_t dbase = lds0 + stage2 * kStage;
-        const char* ab = uniform_ptr(walk.abase);
-        const char* bb = uniform_ptr(walk.bbase);
-        int issued = 0;
+        const uint32_t rest_base = lds0 + stage_rest * kStage, first_base = lds0 + stage * kStage;
+        const char *ab = nullptr, *bb = nullptr;
+        if (DMA_REST) {
+            ab = uniform_ptr(walk.abase);
+            bb = uniform_ptr(walk.bbase);
+        }
+        int issued = kFirst;
 #pragma unroll
         for (int s = 0; s < kSteps; ++s) {
             const int cur = s & 1;
+            if (s == kSteps - 1) {
+                if (DMA_REST) walk.advance();  // every load of tile kt+STAGES-1 has been issued
+                if (DMA_FIRST) {
+                    ab = uniform_ptr(walk.abase);
+                    bb = uniform_ptr(walk.bbase);
+                    issued = 0;
+                }
+            }
             if (s == kSteps - 1 && HAS_NEXT) {
                 probe.wait_begin();
-                if (HAS_DMA && STAGES == 3)
+                if (DMA_REST && STAGES == 3)
                     wait_vmcnt<kPerTile>();
                 else
                     wait_vmcnt<0>();
@@ -283,26 +309,40 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
                                 read_frag(sa1, cur ^ 1, r, 0);
                         }
                     }
-                    if (HAS_DMA) {
-                        const bool window = STAGES == 3 ? (s < kSteps - 1) : (s == kSteps - 1);
-                        const int slot = (STAGES == 3 ? s : 0) * kMfma + m;
+                    if (DMA_REST && s < kRestSteps) {
+                        const int slot = s * kMfma + m;
 #pragma unroll
-                        for (int q = 0; q < kDmaPerSlot; ++q)
-                            if (window && issued < kPerTile && (slot + 1) * kPerTile > issued * kDmaSlots) {
-                                issue_one(dbase, ab, bb, issued);
+                        for (int q = 0; q < kRestPerSlot; ++q)
+                            if (issued < kPerTile && (slot + 1) * kRest > (issued - kFirst) * kRestSlots) {
+                                issue_one(rest_base, ab, bb, issued);
+                                ++issued;
+                            }
+                    }
+                    if (DMA_FIRST && s == kSteps - 1) {
+#pragma unroll
+                        for (int q = 0; q < kFirstPerSlot; ++q)
+                            if (issued < kFirst && (m + 1) * kFirst > issued * kMfma) {
+                                issue_one(first_base, ab, bb, issued);
                                 ++issued;
                             }
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
         }
-        if (HAS_DMA) walk.advance();
     };
 
-    // Prologue: tiles 0 and 1 in flight, tile 0 landed and visible, its first fragments read.
+    // Prologue: tiles 0 .. STAGES-2 and the first loads of tile STAGES-1 in flight, tile 0 landed
+    // and visible, its first fragments read.
     issue_all(0);
-    if (n_ktiles > 1) {
-        issue_all(1);
+    if (STAGES == 3 && n_ktiles > 1) issue_all(1);
+    if (n_ktiles > STAGES - 1) {
+        const uint32_t sbase = lds0 + (STAGES - 1) * kStage;
+        const char* ab = uniform_ptr(walk.abase);
+        const char* bb = uniform_ptr(walk.bbase);
+#pragma unroll
+        for (int idx = 0; idx < kFirst; ++idx) issue_one(sbase, ab, bb, idx);
+        wait_vmcnt<(STAGES - 2) * kPerTile + kFirst>();
+    } else if (STAGES == 3 && n_ktiles > 1) {
         wait_vmcnt<kPerTile>();
     } else {
         wait_vmcnt<0>();
@@ -315,15 +355,19 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
     probe.prologue_done();
     int stage = 0;
     int kt = 0;
-    for (; kt + 2 < n_ktiles; ++kt) {
-        iteration(stage, std::true_type{}, std::true_type{});
-        stage = stage + 1 == STAGES ? 0 : stage + 1;
+    auto next_stage = [&] { stage = stage + 1 == STAGES ? 0 : stage + 1; };
+    for (; kt + STAGES < n_ktiles; ++kt) {
+        iteration(stage, std::true_type{}, std::true_type{}, std::true_type{});
+        next_stage();
     }
-    if (kt + 1 < n_ktiles) {
-        iteration(stage, std::true_type{}, std::false_type{});
-        stage = stage + 1 == STAGES ? 0 : stage + 1;
+    for (; kt + 1 < n_ktiles; ++kt) {
+        if (kt + STAGES - 1 < n_ktiles)
+            iteration(stage, std::true_type{}, std::true_type{}, std::false_type{});
+        else
+            iteration(stage, std::true_type{}, std::false_type{}, std::false_type{});
+        next_stage();
     }
-    iteration(stage, std::false_type{}, std::false_type{});
+    iteration(stage, std::false_type{}, std::false_type{}, std::false_type{});
 }
 
 template <int BM, int BN, int STAGES, bool AKC, bool BKC, class Walk>
