@@ -47,7 +47,8 @@ typedef enum {
     DMATH_ERR_ALIAS = 5,       /* output handle is also an input                              */
     DMATH_ERR_OOM = 6,         /* the pool cannot satisfy the request                         */
     DMATH_ERR_UNSUPPORTED = 7, /* valid in principle, not implemented (dilation, groups, ...) */
-    DMATH_ERR_DEVICE = 8       /* a HIP call failed                                           */
+    DMATH_ERR_DEVICE = 8,      /* a HIP call failed                                           */
+    DMATH_ERR_SCRATCH_LIMIT = 9 /* dmath_gemm_noalloc: the plan does not fit the fixed scratch array */
 } dmath_status_t;
 
 /*
@@ -143,6 +144,30 @@ typedef struct {
                                  zero-padded scratch panels of k-segments that are not
                                  multiples of tile_k */
 } dmath_plan_info_t;
+
+/*
+ * dmath_gemm for callers that cannot allocate: code whose stream is under HIP graph capture,
+ * tight serving loops, harnesses that forbid allocation.  Same arguments, result, status codes
+ * and asynchrony as dmath_gemm, but the call takes nothing from the context's pool and makes no
+ * driver allocation: what its kernels need beyond the operands (descriptor tables, partial sums
+ * of a split k-loop, zero-padded panels of k-tails) lies in a static device array of
+ * DMATH_NOALLOC_SCRATCH_BYTES that every GPU running the library holds from the first such call
+ * on it until the process ends.
+ *   - The array holds ONE plan, the last call's.  A call with the same handles and ops as the
+ *     one before it only launches kernels; any other call rewrites the array first, which copies
+ *     tables from host memory and waits for the context's stream -- so make the first call for
+ *     a set of operands outside stream capture, and do not replay a captured call after the
+ *     array has been rewritten.
+ *   - All contexts on one GPU share that GPU's array; calls that overlap on one GPU (different
+ *     streams) race.  The device that is current at the call is the one whose array is used.
+ *   - As with dmath_gemm and a full pool, memory decides: partial sums that do not fit make
+ *     the same kernel run unsplit, k-tail panels that do not fit the generic kernel.
+ * Errors: those of dmath_gemm; DMATH_ERR_SCRATCH_LIMIT if even the descriptor tables exceed the
+ * array (very fine block grids); DMATH_ERR_UNSUPPORTED between dmath_pipeline_begin and _end.
+ */
+#define DMATH_NOALLOC_SCRATCH_BYTES (32u << 20)
+dmath_status_t dmath_gemm_noalloc(dmath_ctx_t ctx, dmath_op_t transA, dmath_op_t transB, double alpha,
+                                  dmath_matrix_t A, dmath_matrix_t B, double beta, dmath_matrix_t C);
 
 /* Builds (or finds in the cache) the plan dmath_gemm would use and describes it.  Same
  * argument checks and errors as dmath_gemm.  Section 3.3: the metadata of an operation is

@@ -821,6 +821,7 @@ const char* dmath_status_string(dmath_status_t s)
     case DMATH_ERR_OOM: return "DMATH_ERR_OOM";
     case DMATH_ERR_UNSUPPORTED: return "DMATH_ERR_UNSUPPORTED";
     case DMATH_ERR_DEVICE: return "DMATH_ERR_DEVICE";
+    case DMATH_ERR_SCRATCH_LIMIT: return "DMATH_ERR_SCRATCH_LIMIT";
     }
     return "DMATH_ERR_UNKNOWN";
 }

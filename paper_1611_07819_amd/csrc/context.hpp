@@ -74,6 +74,22 @@ struct GemmPlan {
     // split; their m_glob / n_glob address a compact workspace [split][tiles x tile_m][tile_n]
     int32_t full_tiles = 0;
     const int32_t* ksplit_whole = nullptr;  // {0, n_kseg}: the whole k-loop as one part
+    bool in_arena = false;  // tables, partial sums and k-tail panels lie in a fixed arena, not in the pool
+};
+
+// A fixed range of device memory handed out front to back, 256 bytes at a time (the plan of the
+// entry point that allocates nothing lives in one).
+struct Arena {
+    char* base = nullptr;
+    size_t cap = 0, used = 0;
+    void* take(size_t bytes)
+    {
+        const size_t need = ((bytes ? bytes : 1) + 255) / 256 * 256;
+        if (need > cap - used) return nullptr;
+        void* p = base + used;
+        used += need;
+        return p;
+    }
 };
 
 enum ConvMode : int32_t { CONV_FWD = 0, CONV_BWD_FILTER = 1, CONV_BWD_DATA = 2 };
@@ -169,6 +185,11 @@ struct dmath_ctx_s {
     bool reuse_relayouts = true;
     uint64_t epoch = 1;
     uint64_t relayouts_reused = 0, relayouts_written = 0;
+    // dmath_gemm_noalloc: its one plan (in the device's static scratch array), what it was made
+    // for, and the token under which this context last wrote the array
+    std::unique_ptr<dm::GemmPlan> noalloc_plan;
+    dm::GemmKey noalloc_key{};
+    uint64_t noalloc_token = 0;
     dmath_ctx_s(void* slab, size_t bytes, hipStream_t s) : pool(slab, bytes), stream(s) {}
 };
 
@@ -236,7 +257,7 @@ std::vector<ConvChoice> conv_candidates(int mode, const ConvGeom& g, dmath_dtype
 dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_matrix_s* A, dmath_matrix_s* B,
                               dmath_matrix_s* C, bool upload, const GemmChoice* forced,
                               std::unique_ptr<GemmPlan>* out, std::vector<GemmChoice>* candidates,
-                              bool unsplit = false);
+                              bool unsplit = false, Arena* arena = nullptr);
 void free_gemm_plan(dmath_ctx_s* ctx, GemmPlan& p);
 dmath_status_t make_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_t* d, dmath_matrix_s* X,
                               dmath_matrix_s* F, dmath_matrix_s* Y, const ConvChoice* forced,

@@ -158,6 +158,10 @@ void drop_all_pipelines(dmath_ctx_s* ctx)
 void drop_plans_using(dmath_ctx_s* ctx, uint64_t id)
 {
     drop_pipelines_using(ctx, id);
+    if (ctx->noalloc_plan) {
+        const auto& u = ctx->noalloc_plan->uses;
+        if (std::find(u.begin(), u.end(), id) != u.end()) ctx->noalloc_plan.reset();
+    }
     for (auto it = ctx->gemm_plans.begin(); it != ctx->gemm_plans.end();) {
         auto& u = it->second->uses;
         if (std::find(u.begin(), u.end(), id) != u.end()) {
@@ -180,6 +184,7 @@ void drop_plans_using(dmath_ctx_s* ctx, uint64_t id)
 void drop_all_plans(dmath_ctx_s* ctx)
 {
     drop_all_pipelines(ctx);
+    ctx->noalloc_plan.reset();
     for (auto& kv : ctx->gemm_plans) free_gemm_plan(ctx, *kv.second);
     ctx->gemm_plans.clear();
     for (auto& kv : ctx->conv_plans) free_conv_plan(ctx, *kv.second);
@@ -210,9 +215,11 @@ std::vector<int64_t> gemm_signature(int transA, int transB, const dmath_matrix_s
 
 void free_gemm_plan(dmath_ctx_s* ctx, GemmPlan& p)
 {
-    if (p.dev_tables) ctx->pool.free(p.dev_tables);
-    if (p.workspace) ctx->pool.free(p.workspace);
-    if (p.tail_scratch) ctx->pool.free(p.tail_scratch);
+    if (!p.in_arena) {  // an arena is not given back piece by piece
+        if (p.dev_tables) ctx->pool.free(p.dev_tables);
+        if (p.workspace) ctx->pool.free(p.workspace);
+        if (p.tail_scratch) ctx->pool.free(p.tail_scratch);
+    }
     p.dev_tables = p.workspace = p.tail_scratch = nullptr;
     p.n_tail_cells = 0;
 }
@@ -252,8 +259,14 @@ dmath_status_t get_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_mat
 
 dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_matrix_s* A, dmath_matrix_s* B,
                               dmath_matrix_s* C, bool do_upload, const GemmChoice* forced,
-                              std::unique_ptr<GemmPlan>* out, std::vector<GemmChoice>* candidates, bool unsplit)
+                              std::unique_ptr<GemmPlan>* out, std::vector<GemmChoice>* candidates, bool unsplit,
+                              Arena* arena)
 {
+    // device memory beyond the operands comes from the pool, or from the caller's fixed arena
+    auto take = [&](size_t bytes) -> void* { return arena ? arena->take(bytes) : ctx->pool.alloc(bytes); };
+    auto give = [&](void* q) {
+        if (!arena) ctx->pool.free(q);
+    };
     const int64_t M = C->rows, N = C->cols, K = transA ? A->rows : A->cols;
     const Split& a_m = transA ? A->csplit : A->rsplit;
     const Split& a_k = transA ? A->rsplit : A->csplit;
@@ -343,10 +356,10 @@ dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_ma
     const size_t scratch_bytes = n_tails * (size_t)(a_tail + b_tail) * es;
     if (n_tails && do_upload) {
         const size_t bytes = scratch_bytes;
-        scratch = static_cast<char*>(ctx->pool.alloc(bytes));
+        scratch = static_cast<char*>(take(bytes));
         if (!scratch) return DMATH_ERR_OOM;
         if (hipMemsetAsync(scratch, 0, bytes, ctx->stream) != hipSuccess) {
-            ctx->pool.free(scratch);
+            give(scratch);
             return DMATH_ERR_DEVICE;
         }
     }
@@ -465,6 +478,7 @@ dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_ma
     }
 
     auto plan = std::make_unique<GemmPlan>();
+    plan->in_arena = arena != nullptr;
     plan->full_tiles = full_tiles;
     plan->uses = {A->id, B->id, C->id};
     plan->in_dtype = A->dtype;
@@ -516,23 +530,23 @@ dmath_status_t make_gemm_plan(dmath_ctx_s* ctx, int transA, int transB, dmath_ma
         size_t ow = append(buf, std::vector<int32_t>{0, (int32_t)ks.size()});
         size_t otc = append(buf, tail_cells);
         plan->tail_scratch = scratch;  // from here on the plan owns it
-        void* dev = ctx->pool.alloc(buf.size());
+        void* dev = take(buf.size());
         if (!dev) {
             free_gemm_plan(ctx, *plan);
             return DMATH_ERR_OOM;
         }
         void* ws = nullptr;
         if (partial_bytes) {
-            ws = ctx->pool.alloc(partial_bytes);
+            ws = take(partial_bytes);
             if (!ws) {
-                ctx->pool.free(dev);
+                give(dev);
                 free_gemm_plan(ctx, *plan);
                 return DMATH_ERR_OOM;
             }
         }
         if (upload(ctx, dev, buf) != hipSuccess) {
-            ctx->pool.free(dev);
-            if (ws) ctx->pool.free(ws);
+            give(dev);
+            if (ws) give(ws);
             free_gemm_plan(ctx, *plan);
             return DMATH_ERR_DEVICE;
         }

@@ -94,6 +94,7 @@ def load_library(build_if_missing: bool = True):
         "dmath_matrix_block": [vp, i32, i32, P(vp), P(i64), P(i64), P(i64)],
         "dmath_matrix_reblock": [vp, vp, vp],
         "dmath_gemm": [vp, ctypes.c_int, ctypes.c_int, dbl, vp, vp, dbl, vp],
+        "dmath_gemm_noalloc": [vp, ctypes.c_int, ctypes.c_int, dbl, vp, vp, dbl, vp],
         "dmath_gemm_plan_info": [vp, ctypes.c_int, ctypes.c_int, vp, vp, vp, P(_PlanInfo)],
         "dmath_conv_fwd": [vp, P(_ConvDesc), dbl, vp, vp, dbl, vp],
         "dmath_conv_bwd_filter": [vp, P(_ConvDesc), dbl, vp, vp, dbl, vp],
@@ -271,6 +272,12 @@ def reblock(ctx: Context, src: Matrix, dst: Matrix):
 def gemm(ctx: Context, transA, transB, alpha, A: Matrix, B: Matrix, beta, C: Matrix):
     _check(ctx._lib.dmath_gemm(ctx._h, int(transA), int(transB), float(alpha), A._h, B._h,
                                float(beta), C._h), "dmath_gemm")
+
+
+def gemm_noalloc(ctx: Context, transA, transB, alpha, A: Matrix, B: Matrix, beta, C: Matrix):
+    """dmath_gemm that takes nothing from the pool: its scratch is the library's static device array."""
+    _check(ctx._lib.dmath_gemm_noalloc(ctx._h, int(transA), int(transB), float(alpha), A._h, B._h,
+                                       float(beta), C._h), "dmath_gemm_noalloc")
 
 
 def gemm_plan_info(ctx: Context, transA, transB, A: Matrix, B: Matrix, C: Matrix) -> dict:
