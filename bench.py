@@ -18,9 +18,31 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"f16": 2516.6, "f32": 157.3, "f64": 78.6}   # dense MFMA peaks of MI355X
-# HBM bytes per GEMM call of cfg2 (mean over the three calls of a step), from the two
-# rocprofv3 --pmc runs summarised in profiles/gemm_f32_cfg2_hbm_traffic.txt; None until measured.
+# HBM bytes per GEMM call of cfg2 (mean over the three calls of a step): FETCH_SIZE + WRITE_SIZE of
+# two rocprofv3 --pmc runs of this program, scaled by a 1 GiB copy of known size; the runs, their
+# command lines and the commit they were made at are in profiles/gemm_f32_cfg2_hbm_traffic.txt.  A
+# counter cannot be read from inside this program, so the figure is carried here, not re-measured.
 MEASURED_TRAFFIC_BYTES = 583725184
+
+
+def cpu_model():
+    """Model string of the host CPU the oracle is timed on."""
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    import platform
+    return platform.processor() or platform.machine()
+
+
+def set_oracle_threads(n):
+    """Thread count of the OpenMP runtime the oracle library is linked with (the oracle itself
+    is not touched: it is timed as it stands)."""
+    import ctypes
+    ctypes.CDLL("libgomp.so.1").omp_set_num_threads(int(n))
 
 
 def main():
@@ -53,12 +75,14 @@ def main():
     torch.cuda.synchronize()
     ctx = dm.Context(slab, stream=stream.cuda_stream)
 
-    def time_calls(fns, steps, warmup, warm_ms=20.0):
-        """ms per pass over fns, HIP events on the stream the kernels are launched on.  The side
-        table's short calls are warmed up for warm_ms of wall time on top of `warmup` passes: after
-        an idle gap (uploading the next operands) the first 10 ms of kernels run at lower clocks
-        (fp32 1280x4096x4096: 382 us in the first 25 calls, 326 us from then on).  The main
-        workload passes warm_ms=0: exactly --warmup steps."""
+    def time_calls(fns, steps, warmup, warm_ms=20.0, stats=None):
+        """ms per pass over fns (mean), HIP events on the stream the kernels are launched on, one
+        event between every two passes so that the median and the minimum pass can be reported
+        beside the mean (`stats`, a dict, receives them; they come from a second run of the same
+        passes, so that the mean is taken without events between the passes).  After `warmup` passes the warm-up goes on
+        until warm_ms of wall time have passed: after an idle gap (uploading the next operands) the
+        first 10-20 ms of kernels run at lower clocks (fp32 1280x4096x4096: 382 us in the first 25
+        calls, 326 us from then on)."""
         t_warm = time.perf_counter()
         for _ in range(warmup):
             for f in fns:
@@ -77,7 +101,28 @@ def main():
         e1.record(stream)
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) * 1e3 / steps
+        if stats is not None:      # a second run of the same passes, one event after each
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+            ev[0].record(stream)
+            for i in range(steps):
+                for f in fns:
+                    f()
+                ev[i + 1].record(stream)
+            torch.cuda.synchronize()
+            per = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(steps))
+            mid = len(per) // 2
+            stats["median_ms"] = round(per[mid] if len(per) % 2 else 0.5 * (per[mid - 1] + per[mid]), 4)
+            stats["min_ms"] = round(per[0], 4)
+            stats["timed"] = steps
         return e0.elapsed_time(e1) / steps, wall
+
+    def entry(ms, flop, peak_key, stats=None, **more):
+        e = {"ms": round(ms, 4), "tflops": round(flop / ms / 1e9, 2),
+             "frac_peak": round(flop / ms / 1e9 / PEAK_TFLOPS[peak_key], 4)}
+        if stats:
+            e.update(stats)
+        e.update(more)
+        return e
 
     # ---------------- main workload: configuration 2 ----------------
     w = synth.config2()
@@ -88,7 +133,8 @@ def main():
                                        dev[c.b], c.beta, dev[c.c]))
         M, N, K = c.mnk(w.mats)
         flops.append(2.0 * M * N * K)
-    ms_step, wall_ms = time_calls(fns, args.steps, args.warmup, warm_ms=0)
+    main_stats = {}
+    ms_step, wall_ms = time_calls(fns, args.steps, args.warmup, stats=main_stats)
     value = sum(flops) / (ms_step * 1e-3) / 1e12
     # dominant kernel = the GEMM main loop; three calls per step, each doing the same
     # 2*M*N*K = 77.31 GFLOP in one launch (dX: two, the second over the tiles left after the
@@ -98,19 +144,19 @@ def main():
     calls = {}
     if not args.only_main:
         for c, f, fl in zip(w.calls, fns, flops):
-            ms, _ = time_calls([f], max(5, args.steps // 2), 3)
-            calls[f"cfg2.{c.name}"] = {"ms": round(ms, 4), "tflops": round(fl / ms / 1e9, 2),
-                                       "frac_peak": round(fl / ms / 1e9 / PEAK_TFLOPS["f32"], 4)}
+            st = {}
+            ms, _ = time_calls([f], 50, 3, stats=st)
+            calls[f"cfg2.{c.name}"] = entry(ms, fl, "f32", st)
     info = dm.gemm_plan_info(ctx, 0, 0, dev["X"], dev["W"], dev["Y"])
     if not args.only_main:
         # the same step after selection from timing samples (done once, outside the timed region,
         # as plans are); the headline value above stays on the cost model's choices
         tuned = [dm.gemm_tune(ctx, int(c.transA), int(c.transB), dev[c.a], dev[c.b], dev[c.c], 1 << 30, 10)
                  for c in w.calls]
-        ms, _ = time_calls(fns, args.steps, 3)
-        calls["cfg2.step_tuned"] = {"ms": round(ms, 4), "tflops": round(sum(flops) / ms / 1e9, 2),
-                                    "frac_peak": round(sum(flops) / ms / 1e9 / PEAK_TFLOPS["f32"], 4),
-                                    "tiles": [[t["tile_m"], t["tile_n"], t["split_k"]] for t in tuned]}
+        st = {}
+        ms, _ = time_calls(fns, args.steps, 3, stats=st)
+        calls["cfg2.step_tuned"] = entry(ms, sum(flops), "f32", st,
+                                         tiles=[[t["tile_m"], t["tile_n"], t["split_k"]] for t in tuned])
         ctx.tune_reset()
     for m in dev.values():
         m.destroy()
@@ -124,9 +170,9 @@ def main():
                 fl = 2.0 * M * N * K
                 f = lambda c=c: dm.gemm(ctx, int(c.transA), int(c.transB), c.alpha, d[c.a], d[c.b],
                                         c.beta, d[c.c])
-                ms, _ = time_calls([f], 10, 3)
-                calls[f"{tag}.{c.name}"] = {"ms": round(ms, 4), "tflops": round(fl / ms / 1e9, 2),
-                                            "frac_peak": round(fl / ms / 1e9 / PEAK_TFLOPS[dtype_key], 4)}
+                st = {}
+                ms, _ = time_calls([f], 50 if fl < 5e11 else 10, 3, stats=st)
+                calls[f"{tag}.{c.name}"] = entry(ms, fl, dtype_key, st)
             for m in d.values():
                 m.destroy()
         def bench_step(wl, tag, dtype_key):
@@ -143,9 +189,9 @@ def main():
             step()
             pid = ctx.pipeline_end()
             for name, f in (("step_eager", step), ("step_replay", lambda: ctx.pipeline_replay(pid))):
-                ms, _ = time_calls([f], 20, 5)
-                calls[f"{tag}.{name}"] = {"ms": round(ms, 4), "tflops": round(fl / ms / 1e9, 2),
-                                          "frac_peak": round(fl / ms / 1e9 / PEAK_TFLOPS[dtype_key], 4)}
+                st = {}
+                ms, _ = time_calls([f], 50, 5, stats=st)
+                calls[f"{tag}.{name}"] = entry(ms, fl, dtype_key, st)
             ctx.pipeline_destroy(pid)
             for m in d.values():
                 m.destroy()
@@ -163,13 +209,14 @@ def main():
             sa = ctx.from_host(rs.uniform(0, 1, (M, K)).astype(npdt))
             sb = ctx.from_host(rs.normal(0, 0.01, (K, N)).astype(npdt))
             sc = ctx.matrix(M, N, (1, 1), dm.F32)
-            ms, _ = time_calls([lambda: dm.gemm(ctx, 0, 0, 1.0, sa, sb, 0.0, sc)], 20, 5)
+            st = {}
+            ms, _ = time_calls([lambda: dm.gemm(ctx, 0, 0, 1.0, sa, sb, 0.0, sc)], 50, 5, stats=st)
             byt = (M * K + K * N) * npdt().itemsize + M * N * 4
             pinfo = dm.gemm_plan_info(ctx, 0, 0, sa, sb, sc)
             calls[f"skinny_{tag}.M{M}_N{N}_K{K}"] = {
                 "ms": round(ms, 4), "tflops": round(2.0 * M * N * K / ms / 1e9, 2),
                 "hbm_tb_s": round(byt / ms / 1e9, 3), "frac_hbm_peak": round(byt / ms / 1e9 / 8.0, 4),
-                "tile": [pinfo["tile_m"], pinfo["tile_n"], pinfo["split_k"]]}
+                "tile": [pinfo["tile_m"], pinfo["tile_n"], pinfo["split_k"]], **st}
             for m in (sa, sb, sc):
                 m.destroy()
         w5 = synth.config5("f32")
@@ -183,9 +230,9 @@ def main():
         for name, f in [("fwd", lambda: dm.conv_fwd(ctx, desc, 1.0, d5["X"], d5["F"], 0.0, d5["Y"])),
                         ("bwd_filter", lambda: dm.conv_bwd_filter(ctx, desc, 1.0, d5["X"], d5["dY"], 0.0, d5["dF"])),
                         ("bwd_data", lambda: dm.conv_bwd_data(ctx, desc, 1.0, d5["dY"], d5["F"], 0.0, d5["dX"]))]:
-            ms, _ = time_calls([f], 10, 3)
-            calls[f"cfg5.{name}"] = {"ms": round(ms, 4), "tflops": round(fl5 / ms / 1e9, 2),
-                                     "frac_peak": round(fl5 / ms / 1e9 / PEAK_TFLOPS["f16"], 4)}
+            st = {}
+            ms, _ = time_calls([f], 50, 3, stats=st)
+            calls[f"cfg5.{name}"] = entry(ms, fl5, "f16", st)
         # one training step of the layer: new activations, new gradient and an updated filter
         # arrive (declared with touch), then forward + weight gradient + data gradient; with
         # copies kept, X is re-laid-out once for the two calls that read it
@@ -197,9 +244,9 @@ def main():
             dm.conv_bwd_data(ctx, desc, 1.0, d5["dY"], d5["F"], 0.0, d5["dX"])
         for name, keep in (("step_rewrite_all", False), ("step_copies_kept", True)):
             ctx.set_relayout_reuse(keep)
-            ms, _ = time_calls([step5], 10, 3)
-            calls[f"cfg5.{name}"] = {"ms": round(ms, 4), "tflops": round(3 * fl5 / ms / 1e9, 2),
-                                     "frac_peak": round(3 * fl5 / ms / 1e9 / PEAK_TFLOPS["f16"], 4)}
+            st = {}
+            ms, _ = time_calls([step5], 50, 3, stats=st)
+            calls[f"cfg5.{name}"] = entry(ms, 3 * fl5, "f16", st)
         ctx.set_relayout_reuse(False)
         for m in d5.values():
             m.destroy()
@@ -209,9 +256,9 @@ def main():
         for name, f in [("fwd", lambda: dm.conv_fwd(ctx, desc, 1.0, d5["X"], d5["F"], 0.0, d5["Y"])),
                         ("bwd_filter", lambda: dm.conv_bwd_filter(ctx, desc, 1.0, d5["X"], d5["dY"], 0.0, d5["dF"])),
                         ("bwd_data", lambda: dm.conv_bwd_data(ctx, desc, 1.0, d5["dY"], d5["F"], 0.0, d5["dX"]))]:
-            ms, _ = time_calls([f], 10, 3)
-            calls[f"cfg5_as_f32.{name}"] = {"ms": round(ms, 4), "tflops": round(fl5 / ms / 1e9, 2),
-                                            "frac_peak": round(fl5 / ms / 1e9 / PEAK_TFLOPS["f32"], 4)}
+            st = {}
+            ms, _ = time_calls([f], 50, 3, stats=st)
+            calls[f"cfg5_as_f32.{name}"] = entry(ms, fl5, "f32", st)
         ctx.set_relayout_reuse(True)
         for m in d5.values():
             m.destroy()
@@ -228,9 +275,9 @@ def main():
         for name, f in [("fwd", lambda: dm.conv_fwd(ctx, d1, 1.0, x1, f1, 0.0, o1["Y"])),
                         ("bwd_filter", lambda: dm.conv_bwd_filter(ctx, d1, 1.0, x1, y1, 0.0, o1["dF"])),
                         ("bwd_data", lambda: dm.conv_bwd_data(ctx, d1, 1.0, y1, f1, 0.0, o1["dX"]))]:
-            ms, _ = time_calls([f], 10, 3)
-            calls[f"conv1x1_f16.{name}"] = {"ms": round(ms, 4), "tflops": round(fl1 / ms / 1e9, 2),
-                                            "frac_peak": round(fl1 / ms / 1e9 / PEAK_TFLOPS["f16"], 4)}
+            st = {}
+            ms, _ = time_calls([f], 50, 3, stats=st)
+            calls[f"conv1x1_f16.{name}"] = entry(ms, fl1, "f16", st)
         for m in [x1, f1, y1] + list(o1.values()):
             m.destroy()
         # K that is not a multiple of the kernels' k-step: data gradient of a 4096 -> 1000 layer at
@@ -240,12 +287,12 @@ def main():
             sa = ctx.from_host(rs.normal(0, 0.1, (M, K)).astype(npdt))
             sb = ctx.from_host(rs.normal(0, 0.02, (N, K)).astype(npdt))
             sc = ctx.matrix(M, N, (1, 1), dm.F32)
-            ms, _ = time_calls([lambda: dm.gemm(ctx, 0, 1, 1.0, sa, sb, 0.0, sc)], 20, 5)
+            st = {}
+            ms, _ = time_calls([lambda: dm.gemm(ctx, 0, 1, 1.0, sa, sb, 0.0, sc)], 50, 5, stats=st)
             pinfo = dm.gemm_plan_info(ctx, 0, 1, sa, sb, sc)
-            calls[f"ktail_{tag}.dX_nt_M{M}_N{N}_K{K}"] = {
-                "ms": round(ms, 4), "tflops": round(2.0 * M * N * K / ms / 1e9, 2),
-                "frac_peak": round(2.0 * M * N * K / ms / 1e9 / PEAK_TFLOPS[tag], 4),
-                "kernel": pinfo["kernel"], "tile": [pinfo["tile_m"], pinfo["tile_n"], pinfo["split_k"]]}
+            calls[f"ktail_{tag}.dX_nt_M{M}_N{N}_K{K}"] = entry(
+                ms, 2.0 * M * N * K, tag, st, kernel=pinfo["kernel"],
+                tile=[pinfo["tile_m"], pinfo["tile_n"], pinfo["split_k"]])
             for m in (sa, sb, sc):
                 m.destroy()
 
@@ -257,13 +304,12 @@ def main():
             sa = ctx.from_host(rs.uniform(0, 1, (M, K)).astype(npdt))
             sb = ctx.from_host(rs.normal(0, 0.02, (K, N)).astype(npdt))
             sc = ctx.matrix(M, N, (1, 1), dm.F32 if code == dm.F16 else code)
-            ms, _ = time_calls([lambda: dm.gemm(ctx, 0, 0, 1.0, sa, sb, 0.0, sc)], 20, 5)
+            st = {}
+            ms, _ = time_calls([lambda: dm.gemm(ctx, 0, 0, 1.0, sa, sb, 0.0, sc)], 50, 5, stats=st)
             pinfo = dm.gemm_plan_info(ctx, 0, 0, sa, sb, sc)
-            calls[f"partial_round_{tag}.nn_M{M}_N{N}_K{K}"] = {
-                "ms": round(ms, 4), "tflops": round(2.0 * M * N * K / ms / 1e9, 2),
-                "frac_peak": round(2.0 * M * N * K / ms / 1e9 / PEAK_TFLOPS[tag], 4),
-                "tile": [pinfo["tile_m"], pinfo["tile_n"], pinfo["split_k"]],
-                "split_tiles": [pinfo["split_tiles"], pinfo["tiles"]]}
+            calls[f"partial_round_{tag}.nn_M{M}_N{N}_K{K}"] = entry(
+                ms, 2.0 * M * N * K, tag, st, tile=[pinfo["tile_m"], pinfo["tile_n"], pinfo["split_k"]],
+                split_tiles=[pinfo["split_tiles"], pinfo["tiles"]])
             for m in (sa, sb, sc):
                 m.destroy()
 
@@ -289,9 +335,24 @@ def main():
             oracle.gemm(c.transA, c.transB, c.alpha, blk[c.a], blk[c.b], c.beta, blk[c.c])
         t = time.perf_counter() - t0
         cpu = {"value": round(sum(flops) / t / 1e12, 5), "unit": "TFLOP/s",
-               "cores": oracle.num_threads(), "kind": "oracle",
+               "cores": oracle.num_threads(), "kind": "oracle", "cpu_model": cpu_model(),
                "sample": f"one whole cfg2 step (all three GEMMs, all rows, 231.9 GFLOP) in {t:.1f} s "
                          f"including the exact widening of the operands to fp64"}
+        # configuration 1 (256^3, 33.6 MFLOP) on one thread: what a single host core does
+        w1 = synth.config1()
+        b1 = {k: oracle.BlockMatrix(v, w1.grid) for k, v in w1.mats.items()}
+        threads = oracle.num_threads()
+        set_oracle_threads(1)
+        try:
+            reps, t0 = 0, time.perf_counter()
+            while reps < 3 or time.perf_counter() - t0 < 0.5:
+                oracle.gemm(False, False, 1.0, b1["A"], b1["B"], 1.0, b1["C"])
+                reps += 1
+            t1 = (time.perf_counter() - t0) / reps
+        finally:
+            set_oracle_threads(threads)
+        cpu["cfg1_one_thread"] = {"ms": round(t1 * 1e3, 3), "gflops": round(2.0 * 256 ** 3 / t1 / 1e9, 3),
+                                  "threads": 1}
 
     if args.copy_probe:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
@@ -310,7 +371,8 @@ def main():
                                "X[1024x9216] W[9216x4096], 4x4 block grids, alpha=1 beta=0",
                    "gflop_per_step": round(sum(flops) / 1e9, 2), "kernel": info["kernel"],
                    "tile": [info["tile_m"], info["tile_n"], info["tile_k"]],
-                   "wall_ms_per_step": round(wall_ms, 4)},
+                   "wall_ms_per_step": round(wall_ms, 4), "median_ms_per_step": main_stats.get("median_ms"),
+                   "min_ms_per_step": main_stats.get("min_ms")},
         "frac_of_peak": round(value / PEAK_TFLOPS["f32"], 4),
         "roofline": {"bound": "mfma", "achieved": round(achieved, 3), "peak": PEAK_TFLOPS["f32"],
                      "unit": "TFLOP/s", "frac": round(achieved / PEAK_TFLOPS["f32"], 4),
