@@ -53,11 +53,12 @@ template <> __device__ __forceinline__ double buffer_load<double>(__amdgpu_buffe
 }
 
 // E: edge of an MFMA result tile (32: 16 registers, row 8*(r/4) + 4*(lane/32) + r%4, column
-// lane%32; 16: 4 registers, row 4*r + lane/16, column lane%16).  row0 / col0: origin of this
+// lane%32; 16: 4 registers, column lane%16, row 4*r + lane/16 (fp64) or, with QUAD, row
+// 4*(lane/16) + r (the 16x16 fp32 result of the fp16 instruction)).  row0 / col0: origin of this
 // wavefront's part of the tile.  MASKED: the tile is ragged.  BETA: C is read.
 // c (the tile's first element), ld and the extents are the same in every lane and the tile spans
 // less than 4 GiB (the plan sees to that): addresses are a scalar base plus 32-bit byte offsets.
-template <int E, bool MASKED, bool BETA, class TC, class AccT, class Acc, int MT, int NTL>
+template <int E, bool MASKED, bool BETA, bool QUAD = false, class TC, class AccT, class Acc, int MT, int NTL>
 __device__ __forceinline__ void store_wave_tile(TC* c, int64_t ld, int m_len, int n_len, int row0, int col0, int lane,
                                                 const Acc (&acc)[MT][NTL], AccT alpha, AccT beta)
 {
@@ -71,9 +72,9 @@ __device__ __forceinline__ void store_wave_tile(TC* c, int64_t ld, int m_len, in
     const uint32_t ldb = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint64_t)ld * ES));  // bytes per row
     m_len = __builtin_amdgcn_readfirstlane(m_len);
     n_len = __builtin_amdgcn_readfirstlane(n_len);
-    const int lane_row = E == 32 ? 4 * (lane >> 5) : (lane >> 4), lane_col = lane & (E - 1);
+    const int lane_row = E == 32 ? 4 * (lane >> 5) : QUAD ? 4 * (lane >> 4) : (lane >> 4), lane_col = lane & (E - 1);
     const uint32_t lane_off = (uint32_t)(row0 + lane_row) * ldb + (uint32_t)(col0 + lane_col) * ES;
-    auto reg_row = [](int r) { return E == 32 ? 8 * (r >> 2) + (r & 3) : 4 * r; };  // the register's part of the row
+    auto reg_row = [](int r) { return E == 32 ? 8 * (r >> 2) + (r & 3) : QUAD ? r : 4 * r; };  // the register's part of the row
     if constexpr (!MASKED) {
         GChar* base = reinterpret_cast<GChar*>(sbase);
         auto at = [&](uint32_t off) { return reinterpret_cast<GTC*>(base + off); };
@@ -151,25 +152,25 @@ __device__ __forceinline__ void store_wave_tile(TC* c, int64_t ld, int m_len, in
 }
 
 // The whole epilogue of a workgroup tile (wavefront part at row0 / col0 of it).
-template <int E, int BM, int BN, class TC, class AccT, class Acc, int MT, int NTL>
+template <int E, int BM, int BN, class TC, bool QUAD = false, class AccT, class Acc, int MT, int NTL>
 __device__ __forceinline__ void store_tile(const GemmTables& t, const Tile& tile, int split, int row0, int col0, int lane,
                                            const Acc (&acc)[MT][NTL], AccT alpha, AccT beta)
 {
     const bool full = tile.m_len == BM && tile.n_len == BN;
     if (t.split_k > 1) {  // partial sums; the fixed-order reduction kernel finishes the job
         AccT* ws = static_cast<AccT*>(t.workspace) + (int64_t)split * t.M * t.N + (int64_t)tile.m_glob * t.N + tile.n_glob;
-        if (full) store_wave_tile<E, false, false>(ws, t.N, tile.m_len, tile.n_len, row0, col0, lane, acc, AccT(1), AccT(0));
-        else store_wave_tile<E, true, false>(ws, t.N, tile.m_len, tile.n_len, row0, col0, lane, acc, AccT(1), AccT(0));
+        if (full) store_wave_tile<E, false, false, QUAD>(ws, t.N, tile.m_len, tile.n_len, row0, col0, lane, acc, AccT(1), AccT(0));
+        else store_wave_tile<E, true, false, QUAD>(ws, t.N, tile.m_len, tile.n_len, row0, col0, lane, acc, AccT(1), AccT(0));
         return;
     }
     const Panel pc = t.c[tile.mseg * t.n_nseg + tile.nseg];
     TC* c = static_cast<TC*>(const_cast<void*>(pc.ptr)) + (int64_t)tile.m_off * pc.ld + tile.n_off;
     if (beta == AccT(0)) {
-        if (full) store_wave_tile<E, false, false>(c, pc.ld, tile.m_len, tile.n_len, row0, col0, lane, acc, alpha, beta);
-        else store_wave_tile<E, true, false>(c, pc.ld, tile.m_len, tile.n_len, row0, col0, lane, acc, alpha, beta);
+        if (full) store_wave_tile<E, false, false, QUAD>(c, pc.ld, tile.m_len, tile.n_len, row0, col0, lane, acc, alpha, beta);
+        else store_wave_tile<E, true, false, QUAD>(c, pc.ld, tile.m_len, tile.n_len, row0, col0, lane, acc, alpha, beta);
     } else {
-        if (full) store_wave_tile<E, false, true>(c, pc.ld, tile.m_len, tile.n_len, row0, col0, lane, acc, alpha, beta);
-        else store_wave_tile<E, true, true>(c, pc.ld, tile.m_len, tile.n_len, row0, col0, lane, acc, alpha, beta);
+        if (full) store_wave_tile<E, false, true, QUAD>(c, pc.ld, tile.m_len, tile.n_len, row0, col0, lane, acc, alpha, beta);
+        else store_wave_tile<E, true, true, QUAD>(c, pc.ld, tile.m_len, tile.n_len, row0, col0, lane, acc, alpha, beta);
     }
 }
 

@@ -34,42 +34,27 @@
 
 #include <type_traits>
 
+#include "lds_dma.hpp"
 #include "mfma.hpp"
 
 namespace dm {
 namespace f16p {
 
+using ldsdma::cdiv;
+using ldsdma::dma16;
+using ldsdma::lds_char;
+using ldsdma::swz;
+using ldsdma::uniform_ptr;
+using ldsdma::wait_vmcnt;
+
 constexpr int BK = 64;
 constexpr int NT = 256;
 typedef short v4s __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) char lds_char;
 
-__device__ __forceinline__ int swz(int mn) { return (mn ^ (mn >> 3)) & 7; }
 
-// Forces a wavefront-uniform pointer into scalar registers.
-__device__ __forceinline__ const char* uniform_ptr(const char* p)
-{
-    uint64_t v = reinterpret_cast<uint64_t>(p);
-    uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-    uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return reinterpret_cast<const char*>(((uint64_t)hi << 32) | lo);
-}
-
-// One direct global->LDS load: lane fetches 16 bytes at (sbase + voff), lands at m0 + 16*lane.
-__device__ __forceinline__ void dma16(uint32_t lds_addr, const void* sbase, uint32_t voff)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :
-                 : "s"(lds_addr), "v"(voff), "s"(sbase)
-                 : "memory");
-}
-
-template <int N> __device__ __forceinline__ void wait_vmcnt()
-{
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
-template <int BMN, bool KC> struct OperandTile {
+// MF: edge of the matrix instruction the fragments are read for (32: 32x32x16, 16: 16x16x32).
+template <int BMN, bool KC, int MF = 32> struct OperandTile {
+    static_assert(MF == 32 || (MF == 16 && BMN >= 128), "16-row fragments: tiles of 128 or more only");
     static constexpr int kInstr = BMN / 32;      // 1 KiB segments per wavefront and k-tile
     static constexpr int kBytes = BMN * BK * 2;  // one stage of this operand
     static constexpr int kChunksPerRow = KC ? 8 : BMN / 8;
@@ -79,8 +64,11 @@ template <int BMN, bool KC> struct OperandTile {
     // on the same bank, so the four rows a transposing read touches are spread by two chunk bits;
     // 128-byte rows (64 columns) alternate between two bank halves already and need one bit,
     // taken from the row pair.  Both are the same for rows 4 and 16 apart.
+    // 16-row fragments: a transposing read of 32 lanes touches k rows r .. r+3 and r+8 .. r+11 of
+    // one 16-column group, so a third chunk bit, taken from row bit 3, separates the two row groups.
     __device__ __forceinline__ static int mswz(int row)
     {
+        if (MF == 16) return ((row & 3) << 2) | (((row >> 3) & 1) << 1);
         return BMN >= 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
     }
 
@@ -116,26 +104,62 @@ template <int BMN, bool KC> struct OperandTile {
     __device__ __forceinline__ static int64_t step(int64_t ld) { return KC ? BK * 2 : BK * 2 * ld; }
 
     // Per-lane LDS byte offset (inside the operand's stage) of the fragment for k-step 0 of the
-    // 32-row tile starting at mn_base.
+    // MF-row tile starting at mn_base.
     __device__ __forceinline__ static uint32_t frag_base(int mn_base, int lane)
     {
-        if (KC) return (uint32_t)((mn_base + (lane & 31)) * 128);
+        if (KC) return (uint32_t)((mn_base + (lane & (MF - 1))) * 128);
         const int g = lane >> 4, i = lane & 15;
-        const int row = 8 * (g >> 1) + (i >> 2);
-        const int col = mn_base + 16 * (g & 1) + 4 * (i & 3);
+        // the 16-lane group g reads a 4 (k) x 16 (mn) patch: 32-row fragments have two column
+        // groups and two k-groups of 8, 16-row fragments one column group and four k-groups
+        const int row = (MF == 32 ? 8 * (g >> 1) : 8 * g) + (i >> 2);
+        const int col = mn_base + (MF == 32 ? 16 * (g & 1) : 0) + 4 * (i & 3);
         return (uint32_t)(row * (BMN * 2) + (((col >> 3) ^ mswz(row)) << 4) + (col & 7) * 2);
     }
 
+    // The fragment of k-step s (16 deep for 32-row fragments, 32 deep for 16-row ones); h is the
+    // lane's k-group (lane / MF), mn_row its row of the tile.
     __device__ __forceinline__ static v8h fragment(const lds_char* tile, uint32_t fb, int mn_row,
                                                    int h, int s)
     {
         if (KC) {
-            const int chunk = ((s << 1) + h) ^ swz(mn_row);
+            const int chunk = (MF == 32 ? (s << 1) + h : (s << 2) + h) ^ swz(mn_row);
             return *reinterpret_cast<const __attribute__((address_space(3))) v8h*>(tile + fb + (chunk << 4));
         }
-        const lds_char* p = tile + fb + s * (16 * BMN * 2);
+        const lds_char* p = tile + fb + s * ((MF == 32 ? 16 : 32) * BMN * 2);
         v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4s __attribute__((address_space(3)))*)p);
         v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4s __attribute__((address_space(3)))*)(p + 4 * BMN * 2));
+        typedef short v8s __attribute__((ext_vector_type(8)));
+        v8s both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(v8h, both);
+    }
+
+    // 16-row fragments, addressed so that a read is ONE instruction: a loop-invariant lane address
+    // out of a small table plus an immediate.  f: which of the wavefront's 16-row blocks, s: which
+    // 32-deep k-step; the wavefront's first row mn0 is a multiple of 64.
+    //   k unit-stride: chunk = (4s + g) ^ swz(row) = [g ^ (l&7) ^ (l>>3)] ^ [(4s) ^ (2f & 7)] (g = lane/16,
+    //     l = lane%16): the bracket on the right is one of eight constants, so eight lane addresses
+    //     serve every fragment, the block's row offset 2048*f goes into the immediate;
+    //   m/n unit-stride: the chunk XOR depends on the lane only, one lane address per block, the
+    //     k-step goes into the immediate.
+    static constexpr int kAddr = KC ? 8 : BMN / 32;
+    __device__ __forceinline__ static void lane_addrs(int mn0, int lane, uint32_t (&x)[kAddr])
+    {
+        const int g = lane >> 4, l = lane & 15;
+#pragma unroll
+        for (int k = 0; k < kAddr; ++k) {
+            if (KC)
+                x[k] = (uint32_t)((mn0 + l) * 128 + (((g ^ (l & 7) ^ (l >> 3)) ^ k) << 4));
+            else
+                x[k] = frag_base(mn0 + 16 * k, lane);
+        }
+    }
+    __device__ __forceinline__ static constexpr int addr_index(int f, int s) { return KC ? (((4 * s) ^ (2 * f)) & 7) : f; }
+    __device__ __forceinline__ static constexpr int addr_imm(int f, int s) { return KC ? 2048 * f : s * (32 * BMN * 2); }
+    __device__ __forceinline__ static v8h fragment16(const lds_char* at)
+    {
+        if (KC) return *reinterpret_cast<const __attribute__((address_space(3))) v8h*>(at);
+        v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4s __attribute__((address_space(3)))*)at);
+        v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4s __attribute__((address_space(3)))*)(at + 4 * BMN * 2));
         typedef short v8s __attribute__((ext_vector_type(8)));
         v8s both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         return __builtin_bit_cast(v8h, both);
@@ -255,7 +279,7 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
     // One iteration (tile kt in `stage`).  HAS_NEXT: tile kt+1 exists; DMA_REST: tile
     // kt+STAGES-1 exists (its first loads are in flight, `walk` describes it, the others are
     // issued now); DMA_FIRST: tile kt+STAGES exists (its first loads are issued in the last step).
-    auto iteration = [&](int stage, auto has_next, auto dma_rest, auto dma_first) {
+    auto iteration = [&](int stage, auto has_next, auto dma_rest, auto dma_first) __attribute__((always_inline)) {
         constexpr bool HAS_NEXT = decltype(has_next)::value, DMA_REST = decltype(dma_rest)::value,
                        DMA_FIRST = decltype(dma_first)::value;
         const int stage1 = stage + 1 == STAGES ? 0 : stage + 1;    // tile kt+1
@@ -268,7 +292,6 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
             ab = uniform_ptr(walk.abase);
             bb = uniform_ptr(walk.bbase);
         }
-        int issued = kFirst;
 #pragma unroll
         for (int s = 0; s < kSteps; ++s) {
             const int cur = s & 1;
@@ -277,7 +300,6 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
                 if (DMA_FIRST) {
                     ab = uniform_ptr(walk.abase);
                     bb = uniform_ptr(walk.bbase);
-                    issued = 0;
                 }
             }
             if (s == kSteps - 1 && HAS_NEXT) {
@@ -309,22 +331,22 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
                                 read_frag(sa1, cur ^ 1, r, 0);
                         }
                     }
+                    // load d of a window of n slots goes into slot floor(d * n / count): a pure
+                    // function of the slot, so that every index is a constant after unrolling
                     if (DMA_REST && s < kRestSteps) {
                         const int slot = s * kMfma + m;
 #pragma unroll
-                        for (int q = 0; q < kRestPerSlot; ++q)
-                            if (issued < kPerTile && (slot + 1) * kRest > (issued - kFirst) * kRestSlots) {
-                                issue_one(rest_base, ab, bb, issued);
-                                ++issued;
-                            }
+                        for (int q = 0; q < kRestPerSlot; ++q) {
+                            const int d = cdiv(slot * kRest, kRestSlots) + q;
+                            if (d < cdiv((slot + 1) * kRest, kRestSlots)) issue_one(rest_base, ab, bb, kFirst + d);
+                        }
                     }
                     if (DMA_FIRST && s == kSteps - 1) {
 #pragma unroll
-                        for (int q = 0; q < kFirstPerSlot; ++q)
-                            if (issued < kFirst && (m + 1) * kFirst > issued * kMfma) {
-                                issue_one(first_base, ab, bb, issued);
-                                ++issued;
-                            }
+                        for (int q = 0; q < kFirstPerSlot; ++q) {
+                            const int d = cdiv(m * kFirst, kMfma) + q;
+                            if (d < cdiv((m + 1) * kFirst, kMfma)) issue_one(first_base, ab, bb, d);
+                        }
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -376,6 +398,248 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
 {
     NoProbe none;
     run<BM, BN, STAGES, AKC, BKC>(walk, n_ktiles, smem, acc, none);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same ring on v_mfma_f32_16x16x32_f16 fragments (2 x 2 wavefronts, tiles of 128 rows and
+// columns or more).  A k-tile is two 32-deep k-steps; each step's matrix instructions are cut
+// into two halves (the first and the second half of the wavefront's 16-row blocks), which gives
+// the four phases that the load schedule and the barrier are laid over: the fragments of k-step 1
+// are read during phases 0 and 1, the barrier sits before phase 3, and phase 3 reads the first
+// fragments of the next tile.
+template <int BM, int BN> struct TileShape16 {
+    static constexpr int WM = BM / 2, WN = BN / 2;  // wavefront tile
+    static constexpr int MT = WM / 16, NTL = WN / 16;
+    static_assert(MT % 2 == 0, "two halves of row blocks");
+    __device__ __forceinline__ static int wm(int wave) { return wave >> 1; }
+    __device__ __forceinline__ static int wn(int wave) { return wave & 1; }
+};
+
+template <int BM, int BN, int STAGES, bool AKC, bool BKC, class Walk, class Probe>
+__device__ __forceinline__ void run16(Walk& walk, int n_ktiles, char* smem,
+                                      v4f (&acc)[TileShape16<BM, BN>::MT][TileShape16<BM, BN>::NTL], Probe& probe)
+{
+    using TA = OperandTile<BM, AKC, 16>;
+    using TB = OperandTile<BN, BKC, 16>;
+    using TS = TileShape16<BM, BN>;
+    constexpr int WM = TS::WM, WN = TS::WN, MT = TS::MT, NTL = TS::NTL;
+    constexpr int kPerTile = TA::kInstr + TB::kInstr;
+    static_assert(STAGES == 2 || STAGES == 3, "ring of two or three stages");
+    // LDS: the STAGES stages of A, then those of B.  A 16x16x32 instruction takes 16 cycles, and a
+    // wavefront issues one instruction every four: between two of them there is room for three
+    // others.  So in the steady state the stage of every iteration is a compile-time constant
+    // (the loop is unrolled by STAGES): a fragment read is one instruction, a lane's loop-invariant
+    // address plus an immediate offset (which must stay below 64 KiB: hence the two regions, with
+    // B's origin inside the lane address), and the LDS address of a load is one scalar add.
+    constexpr int kAStage = TA::kBytes, kBStage = TB::kBytes, kBRegion = STAGES * kAStage;
+    const lds_char* lds = (const lds_char*)smem;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t wave_lds = lds0 + wave * 1024;  // where this wavefront's segments start (scalar)
+    const int wm = TS::wm(wave), wn = TS::wn(wave), g = lane >> 4, l16 = lane & 15;
+
+    // lane addresses of the fragment reads (see OperandTile::lane_addrs); B's carry the origin of
+    // its region, and a second copy 32 KiB up serves the stages a 16-bit immediate cannot reach
+    constexpr bool kFarA = (STAGES - 1) * kAStage + 16384 + 2048 >= 65536,
+                   kFarB = (STAGES - 1) * kBStage + 16384 + 2048 >= 65536;
+    uint32_t xa[TA::kAddr], xb[TB::kAddr], xa_far[kFarA ? TA::kAddr : 1], xb_far[kFarB ? TB::kAddr : 1];
+    TA::lane_addrs(wm * WM, lane, xa);
+    TB::lane_addrs(wn * WN, lane, xb);
+#pragma unroll
+    for (int k = 0; k < TB::kAddr; ++k) xb[k] += kBRegion;
+    if (kFarA)
+#pragma unroll
+        for (int k = 0; k < TA::kAddr; ++k) xa_far[k] = xa[k] + 32768;
+    if (kFarB)
+#pragma unroll
+        for (int k = 0; k < TB::kAddr; ++k) xb_far[k] = xb[k] + 32768;
+
+    // load idx of a k-tile (A segments first) into `stage`
+    auto issue_one = [&](int stage, const char* ab, const char* bb, int idx) {
+        if (idx < TA::kInstr)
+            dma16(wave_lds, stage * kAStage + idx * 4096, ab, walk.aoff[idx]);
+        else
+            dma16(wave_lds, kBRegion + stage * kBStage + (idx - TA::kInstr) * 4096, bb, walk.boff[idx - TA::kInstr]);
+    };
+    auto issue_all = [&](int stage) {
+        const char* ab = uniform_ptr(walk.abase);
+        const char* bb = uniform_ptr(walk.bbase);
+#pragma unroll
+        for (int idx = 0; idx < kPerTile; ++idx) issue_one(stage, ab, bb, idx);
+        walk.advance();
+    };
+
+    constexpr int kPhases = 4, kMfma = MT * NTL / 2, kReads = MT + NTL;  // per phase / per k-step
+    constexpr int kRestSteps = STAGES == 3 ? kPhases - 1 : 2;
+    constexpr int kFirst = (kPerTile + kRestSteps) / (kRestSteps + 1);
+    constexpr int kRest = kPerTile - kFirst;
+    constexpr int kRestSlots = kRestSteps * kMfma;
+    constexpr int kRestPerSlot = (kRest + kRestSlots - 1) / kRestSlots;
+    constexpr int kFirstPerSlot = (kFirst + kMfma - 1) / kMfma;
+
+    v8h fa[2][MT], fb[2][NTL];
+    // read order: what the first instructions need comes first (A0, all B, then the other A)
+    auto read_frag = [&](int stage, int buf, int r, int s) {
+        // with a constant stage the whole offset is an immediate of the read
+        auto frag_a = [&](int f) {
+            const int off = stage * kAStage + TA::addr_imm(f, s);
+            const int k = TA::addr_index(f, s);
+            if (kFarA && off >= 32768) return TA::fragment16(lds + xa_far[kFarA ? k : 0] + (off - 32768));
+            return TA::fragment16(lds + xa[k] + off);
+        };
+        auto frag_b = [&](int f) {
+            const int off = stage * kBStage + TB::addr_imm(f, s);
+            const int k = TB::addr_index(f, s);
+            if (kFarB && off >= 32768) return TB::fragment16(lds + xb_far[kFarB ? k : 0] + (off - 32768));
+            return TB::fragment16(lds + xb[k] + off);
+        };
+        if (r == 0)
+            fa[buf][0] = frag_a(0);
+        else if (r <= NTL)
+            fb[buf][r - 1] = frag_b(r - 1);
+        else
+            fa[buf][r - NTL] = frag_a(r - NTL);
+    };
+
+    // One iteration (tile kt in `stage`, an int or a compile-time constant).  HAS_NEXT: tile kt+1
+    // exists; DMA_REST: tile kt+STAGES-1 exists (its first loads are in flight, `walk` describes
+    // it, the others are issued now); DMA_FIRST: tile kt+STAGES exists (its first loads are issued
+    // in the last phase).
+    auto iteration = [&](auto stage_v, auto has_next, auto dma_rest, auto dma_first) __attribute__((always_inline)) {
+        constexpr bool HAS_NEXT = decltype(has_next)::value, DMA_REST = decltype(dma_rest)::value,
+                       DMA_FIRST = decltype(dma_first)::value;
+        const int stage = stage_v;
+        const int stage1 = stage + 1 == STAGES ? 0 : stage + 1;      // tile kt+1
+        const int stage_rest = stage == 0 ? STAGES - 1 : stage - 1;  // tile kt+STAGES-1
+        const char *ab = nullptr, *bb = nullptr;
+        if (DMA_REST) {
+            ab = uniform_ptr(walk.abase);
+            bb = uniform_ptr(walk.bbase);
+        }
+#pragma unroll
+        for (int p = 0; p < kPhases; ++p) {
+            const int cur = p >> 1, half = p & 1;
+            if (p == kPhases - 1) {
+                if (DMA_REST) walk.advance();  // every load of tile kt+STAGES-1 has been issued
+                if (DMA_FIRST) {
+                    ab = uniform_ptr(walk.abase);
+                    bb = uniform_ptr(walk.bbase);
+                }
+            }
+            if (p == kPhases - 1 && HAS_NEXT) {
+                probe.wait_begin();
+                if (DMA_REST && STAGES == 3)
+                    wait_vmcnt<kPerTile>();
+                else
+                    wait_vmcnt<0>();
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                probe.wait_end();
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // fragment reads of this phase: half of k-step 1's in phases 0 and 1, all of the next
+            // tile's k-step 0 in phase 3
+            const int r_begin = p == 1 ? kReads / 2 : 0;
+            const int r_end = p == 0 ? kReads / 2 : (p == 1 || (p == 3 && HAS_NEXT)) ? kReads : 0;
+            const int r_count = r_end - r_begin;
+#pragma unroll
+            for (int m = 0; m < kMfma; ++m) {
+                const int i = half * (MT / 2) + m / NTL, j = m % NTL;
+                mfma_f16_16x16x32(acc[i][j], fa[cur][i], fb[cur][j]);
+                __builtin_amdgcn_sched_barrier(0);
+                // reads m*r_count/kMfma .. (m+1)*r_count/kMfma of the phase's share go into this slot
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const int r = r_begin + m * r_count / kMfma + q;
+                    if (r < r_begin + (m + 1) * r_count / kMfma) {
+                        if (p < 2)
+                            read_frag(stage, 1, r, 1);
+                        else
+                            read_frag(stage1, 0, r, 0);
+                    }
+                }
+                // load d of a window of n slots goes into slot floor(d * n / count): a pure function
+                // of the slot, so that every index is a constant after unrolling
+                if (DMA_REST && p < kRestSteps) {
+                    const int slot = p * kMfma + m;
+#pragma unroll
+                    for (int q = 0; q < kRestPerSlot; ++q) {
+                        const int d = cdiv(slot * kRest, kRestSlots) + q;
+                        if (d < cdiv((slot + 1) * kRest, kRestSlots)) issue_one(stage_rest, ab, bb, kFirst + d);
+                    }
+                }
+                if (DMA_FIRST && p == kPhases - 1) {
+#pragma unroll
+                    for (int q = 0; q < kFirstPerSlot; ++q) {
+                        const int d = cdiv(m * kFirst, kMfma) + q;
+                        if (d < cdiv((m + 1) * kFirst, kMfma)) issue_one(stage, ab, bb, d);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+
+    // Prologue: tiles 0 .. STAGES-2 and the first loads of tile STAGES-1 in flight, tile 0 landed
+    // and visible, its first fragments read.
+    issue_all(0);
+    if (STAGES == 3 && n_ktiles > 1) issue_all(1);
+    if (n_ktiles > STAGES - 1) {
+        const char* ab = uniform_ptr(walk.abase);
+        const char* bb = uniform_ptr(walk.bbase);
+#pragma unroll
+        for (int idx = 0; idx < kFirst; ++idx) issue_one(STAGES - 1, ab, bb, idx);
+        wait_vmcnt<(STAGES - 2) * kPerTile + kFirst>();
+    } else if (STAGES == 3 && n_ktiles > 1) {
+        wait_vmcnt<kPerTile>();
+    } else {
+        wait_vmcnt<0>();
+    }
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int r = 0; r < kReads; ++r) read_frag(0, 0, r, 0);
+
+    probe.prologue_done();
+    // Wherever the accumulators may be touched by anything but a matrix instruction -- the
+    // epilogue, and the copies the compiler may place between the differently unrolled
+    // iterations below -- the matrix pipeline is drained first and every accumulator is tied to
+    // a point after the drain.
+    auto settle = [&]() __attribute__((always_inline)) {
+        mfma_drain();
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NTL; ++j) pin(acc[i][j]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    using T = std::true_type;
+    using F = std::false_type;
+    int kt = 0;
+    // steady state: rounds of STAGES iterations whose stages are constants
+    for (; kt + 2 * STAGES - 1 < n_ktiles; kt += STAGES) {
+        iteration(std::integral_constant<int, 0>{}, T{}, T{}, T{});
+        iteration(std::integral_constant<int, 1>{}, T{}, T{}, T{});
+        if (STAGES == 3) iteration(std::integral_constant<int, 2>{}, T{}, T{}, T{});
+    }
+    settle();
+    // what is left: up to STAGES-1 full iterations, then the ones that run out of tiles to fetch
+    int stage = 0;
+    auto next_stage = [&] { stage = stage + 1 == STAGES ? 0 : stage + 1; };
+    for (; kt + 1 < n_ktiles; ++kt) {
+        if (kt + STAGES < n_ktiles)
+            iteration(stage, T{}, T{}, T{});
+        else if (kt + STAGES - 1 < n_ktiles)
+            iteration(stage, T{}, T{}, F{});
+        else
+            iteration(stage, T{}, F{}, F{});
+        next_stage();
+        settle();
+    }
+    iteration(stage, F{}, F{}, F{});
+    settle();
 }
 
 }  // namespace f16p

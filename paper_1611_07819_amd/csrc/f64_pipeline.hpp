@@ -20,40 +20,24 @@
 
 #include <type_traits>
 
+#include "lds_dma.hpp"
 #include "mfma.hpp"
 
 namespace dm {
 namespace f64p {
 
+using ldsdma::cdiv;
+using ldsdma::dma16;
+using ldsdma::lds_char;
+using ldsdma::swz;
+using ldsdma::uniform_ptr;
+using ldsdma::wait_vmcnt;
+
 constexpr int BK = 16;
 typedef double v2d __attribute__((ext_vector_type(2)));
 constexpr int NT = 256;
 constexpr int STAGES = 3;
-typedef __attribute__((address_space(3))) char lds_char;
 
-__device__ __forceinline__ int swz(int mn) { return (mn ^ (mn >> 3)) & 7; }
-
-__device__ __forceinline__ const char* uniform_ptr(const char* p)
-{
-    uint64_t v = reinterpret_cast<uint64_t>(p);
-    uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-    uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return reinterpret_cast<const char*>(((uint64_t)hi << 32) | lo);
-}
-
-// One direct global->LDS load: lane fetches 16 bytes at (sbase + voff), lands at m0 + 16*lane.
-__device__ __forceinline__ void dma16(uint32_t lds_addr, const void* sbase, uint32_t voff)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :
-                 : "s"(lds_addr), "v"(voff), "s"(sbase)
-                 : "memory");
-}
-
-template <int N> __device__ __forceinline__ void wait_vmcnt()
-{
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
 
 template <int BMN, bool KC> struct OperandTile {
     static constexpr int kInstr = BMN / 32;      // 1 KiB segments per wavefront and k-tile

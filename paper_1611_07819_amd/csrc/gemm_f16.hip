@@ -10,6 +10,7 @@
 // aligned panel origins and leading dimensions, blocks smaller than 4 GiB.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
 #include <type_traits>
 
 #include "context.hpp"
@@ -51,9 +52,9 @@ struct CycleProbe {
 #endif
 
 // Walks the k-panels of one C tile: dense panels, pointer + leading dimension per k-segment.
-template <int BM, int BN, bool AKC, bool BKC> struct PanelWalk {
-    using TA = OperandTile<BM, AKC>;
-    using TB = OperandTile<BN, BKC>;
+template <int BM, int BN, bool AKC, bool BKC, int MF> struct PanelWalk {
+    using TA = OperandTile<BM, AKC, MF>;
+    using TB = OperandTile<BN, BKC, MF>;
     const GemmTables& t;
     const Tile& tile;
     int wave, lane, ks, ks_end, kleft;
@@ -89,10 +90,13 @@ template <int BM, int BN, bool AKC, bool BKC> struct PanelWalk {
     }
 };
 
-template <int BM, int BN, int STAGES, bool AKC, bool BKC, class TC>
+// MF: 32 = v_mfma_f32_32x32x16_f16 fragments (every tile shape), 16 = v_mfma_f32_16x16x32_f16
+// (2 x 2 wavefronts on tiles of 128 or more rows and columns).
+template <int BM, int BN, int STAGES, bool AKC, bool BKC, class TC, int MF>
 __global__ __launch_bounds__(NT) void gemm_f16_kernel(GemmTables t, float alpha, float beta)
 {
-    using TS = TileShape<BM, BN>;
+    using TS = std::conditional_t<MF == 16, TileShape16<BM, BN>, TileShape<BM, BN>>;
+    using Acc = std::conditional_t<MF == 16, v4f, v16f>;
     constexpr int WM = TS::WM, WN = TS::WN, MT = TS::MT, NTL = TS::NTL;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
@@ -101,28 +105,30 @@ __global__ __launch_bounds__(NT) void gemm_f16_kernel(GemmTables t, float alpha,
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = TS::wm(wave), wn = TS::wn(wave);
 
-    v16f acc[MT][NTL];
+    Acc acc[MT][NTL];
 #pragma unroll
     for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int j = 0; j < NTL; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+            for (int r = 0; r < (MF == 16 ? 4 : 16); ++r) acc[i][j][r] = 0.f;
 
     const int split = blockIdx.y, ks0 = t.ksplit[split], ks1 = t.ksplit[split + 1];
     int n_ktiles = 0;
     for (int s = ks0; s < ks1; ++s) n_ktiles += t.klen[s] / BK;
-    PanelWalk<BM, BN, AKC, BKC> walk(t, tile, wave, lane, ks0, ks1);
+    PanelWalk<BM, BN, AKC, BKC, MF> walk(t, tile, wave, lane, ks0, ks1);
 #ifdef DMATH_CYCLE_PROBE
     const uint64_t t_start = __builtin_amdgcn_s_memtime(), r_start = __builtin_amdgcn_s_memrealtime();
     CycleProbe probe;
-    run<BM, BN, STAGES, AKC, BKC>(walk, n_ktiles, smem, acc, probe);
-    const uint64_t t_loop_end = __builtin_amdgcn_s_memtime();
 #else
-    run<BM, BN, STAGES, AKC, BKC>(walk, n_ktiles, smem, acc);
+    NoProbe probe;
 #endif
-
+    if constexpr (MF == 16)
+        run16<BM, BN, STAGES, AKC, BKC>(walk, n_ktiles, smem, acc, probe);
+    else
+        run<BM, BN, STAGES, AKC, BKC>(walk, n_ktiles, smem, acc, probe);
 #ifdef DMATH_CYCLE_PROBE
+    const uint64_t t_loop_end = __builtin_amdgcn_s_memtime();
     auto record_probe = [&] {
         __syncthreads();
         if (tid == 0 && tile.m_glob == 0 && tile.n_glob == 0 && blockIdx.y == 0) {
@@ -136,17 +142,17 @@ __global__ __launch_bounds__(NT) void gemm_f16_kernel(GemmTables t, float alpha,
         }
     };
 #endif
-    store_tile<32, BM, BN, TC>(t, tile, split, wm * WM, wn * WN, lane, acc, alpha, beta);
+    store_tile<MF, BM, BN, TC, MF == 16>(t, tile, split, wm * WM, wn * WN, lane, acc, alpha, beta);
 #ifdef DMATH_CYCLE_PROBE
     record_probe();
 #endif
 }
 
-template <int BM, int BN, int STAGES, bool AKC, bool BKC, class TC>
+template <int BM, int BN, int STAGES, bool AKC, bool BKC, class TC, int MF>
 hipError_t launch_one(const GemmTables& t, float alpha, float beta, hipStream_t st)
 {
     constexpr int lds_bytes = STAGES * (BM + BN) * BK * 2;
-    auto kern = gemm_f16_kernel<BM, BN, STAGES, AKC, BKC, TC>;
+    auto kern = gemm_f16_kernel<BM, BN, STAGES, AKC, BKC, TC, MF>;
     static bool configured = false;
     if (!configured) {  // more than 64 KiB of LDS has to be asked for once per kernel
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -158,13 +164,13 @@ hipError_t launch_one(const GemmTables& t, float alpha, float beta, hipStream_t 
     return hipGetLastError();
 }
 
-template <int BM, int BN, int STAGES, class TC>
+template <int BM, int BN, int STAGES, class TC, int MF = 32>
 hipError_t launch_shape(const GemmTables& t, float alpha, float beta, hipStream_t st)
 {
-    if (t.a_kcontig && t.b_kcontig) return launch_one<BM, BN, STAGES, true, true, TC>(t, alpha, beta, st);
-    if (t.a_kcontig && !t.b_kcontig) return launch_one<BM, BN, STAGES, true, false, TC>(t, alpha, beta, st);
-    if (!t.a_kcontig && t.b_kcontig) return launch_one<BM, BN, STAGES, false, true, TC>(t, alpha, beta, st);
-    return launch_one<BM, BN, STAGES, false, false, TC>(t, alpha, beta, st);
+    if (t.a_kcontig && t.b_kcontig) return launch_one<BM, BN, STAGES, true, true, TC, MF>(t, alpha, beta, st);
+    if (t.a_kcontig && !t.b_kcontig) return launch_one<BM, BN, STAGES, true, false, TC, MF>(t, alpha, beta, st);
+    if (!t.a_kcontig && t.b_kcontig) return launch_one<BM, BN, STAGES, false, true, TC, MF>(t, alpha, beta, st);
+    return launch_one<BM, BN, STAGES, false, false, TC, MF>(t, alpha, beta, st);
 }
 
 // Tile shapes: 256x256 (two 64 KiB stages), 256x128 (three 48 KiB stages), 128x128 (two 32 KiB
@@ -174,6 +180,16 @@ template <class TC>
 hipError_t launch_out(const GemmPlan& p, const GemmTables& t, float alpha, float beta, hipStream_t st)
 {
     const int bm = p.info.tile_m, bn = p.info.tile_n;
+    // 256x128 and 128x128 run on 16x16x32 fragments (7 % faster on configuration 3's forward and
+    // data-gradient GEMMs, A/B on one box).  256x256 stays on 32x32x16: its 256 accumulator
+    // registers leave the 16-row pipeline's address tables no room, and the compiler spills
+    // accumulators around the last iterations.  DMATH_F16_MFMA32=1 switches the others back too
+    // (A/B measurements).
+    static const bool mf32 = std::getenv("DMATH_F16_MFMA32") != nullptr;
+    if (!mf32) {
+        if (bm == 256 && bn == 128) return launch_shape<256, 128, 3, TC, 16>(t, alpha, beta, st);
+        if (bm == 128 && bn == 128) return launch_shape<128, 128, 2, TC, 16>(t, alpha, beta, st);
+    }
     if (bm == 256 && bn == 256) return launch_shape<256, 256, 2, TC>(t, alpha, beta, st);
     if (bm == 256 && bn == 128) return launch_shape<256, 128, 3, TC>(t, alpha, beta, st);
     if (bm == 128 && bn == 128) return launch_shape<128, 128, 2, TC>(t, alpha, beta, st);

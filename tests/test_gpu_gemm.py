@@ -499,6 +499,37 @@ def test_random_shapes_grids_ops_against_oracle(ctx, oracle, seed):
             m.destroy()
 
 
+@pytest.mark.parametrize("tile", ["256x256", "256x128", "128x128"])
+@pytest.mark.parametrize("ta,tb", [(0, 1), (1, 0)])
+def test_fp16_every_k_tile_count_per_tile_shape(oracle, monkeypatch, tile, ta, tb):
+    """1 to 17 k-tiles of 64 on each tile shape of the 16x16x32 pipeline: the k-loop is unrolled
+    into differently scheduled first, steady and last iterations, and every count takes another
+    path through them (a stale accumulator register once showed only for some counts).  C is left
+    as allocated, beta = 0; small integers, bit for bit."""
+    monkeypatch.setenv("DMATH_TILE", tile)
+    r = np.random.default_rng(270)
+    c = make_context(0.5)
+    try:
+        M = N = 512
+        for n in range(1, 18):
+            K = 64 * n
+            opA = r.integers(-3, 4, (M, K)).astype(np.float16)
+            opB = r.integers(-3, 4, (K, N)).astype(np.float16)
+            A, B = stored(opA, ta), stored(opB, tb)
+            dA, dB = c.from_host(A), c.from_host(B)
+            dC = c.matrix(M, N, (1, 1), dm.F32)
+            info = dm.gemm_plan_info(c, ta, tb, dA, dB, dC)
+            assert f"{info['tile_m']}x{info['tile_n']}" == tile and info["kernel"] > 0, info
+            dm.gemm(c, ta, tb, 1.0, dA, dB, 0.0, dC)
+            got = dC.get().astype(np.float64)
+            ref = oracle.gemm(bool(ta), bool(tb), 1.0, A, B, 0.0)
+            assert np.array_equal(got, ref), (tile, n, int((got != ref).sum()))
+            for m in (dA, dB, dC):
+                m.destroy()
+    finally:
+        c.close()
+
+
 @pytest.mark.parametrize("dt,out,tile,shape", [
     (dm.F32, dm.F32, "128x64", (1300, 4128, 256)),     # 11 x 65 = 715 tiles on 512 workgroup slots
     (dm.F64, dm.F64, "128x64", (1300, 4128, 256)),
