@@ -437,6 +437,18 @@ __device__ __forceinline__ void run16(Walk& walk, int n_ktiles, char* smem,
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t wave_lds = lds0 + wave * 1024;  // where this wavefront's segments start (scalar)
+    // A wavefront tile of 128 x 128 fills the accumulator register file: the compiler then has no
+    // register to spare where differently scheduled iterations meet, and spills accumulators.  So
+    // there every iteration is the full one: loads are issued to the very end (the walk stays on
+    // the last k-tile; what is fetched again lands in stages nobody reads any more), and the
+    // last iteration reads "next" fragments it never uses.
+    constexpr bool kAlwaysFull = MT * NTL * 4 >= 256;
+    auto next_tile = [&]() __attribute__((always_inline)) {
+        if constexpr (kAlwaysFull)
+            walk.advance_or_stay();
+        else
+            walk.advance();
+    };
     const int wm = TS::wm(wave), wn = TS::wn(wave), g = lane >> 4, l16 = lane & 15;
 
     // lane addresses of the fragment reads (see OperandTile::lane_addrs); B's carry the origin of
@@ -467,7 +479,7 @@ __device__ __forceinline__ void run16(Walk& walk, int n_ktiles, char* smem,
         const char* bb = uniform_ptr(walk.bbase);
 #pragma unroll
         for (int idx = 0; idx < kPerTile; ++idx) issue_one(stage, ab, bb, idx);
-        walk.advance();
+        next_tile();
     };
 
     constexpr int kPhases = 4, kMfma = MT * NTL / 2, kReads = MT + NTL;  // per phase / per k-step
@@ -521,7 +533,7 @@ __device__ __forceinline__ void run16(Walk& walk, int n_ktiles, char* smem,
         for (int p = 0; p < kPhases; ++p) {
             const int cur = p >> 1, half = p & 1;
             if (p == kPhases - 1) {
-                if (DMA_REST) walk.advance();  // every load of tile kt+STAGES-1 has been issued
+                if (DMA_REST) next_tile();  // every load of tile kt+STAGES-1 has been issued
                 if (DMA_FIRST) {
                     ab = uniform_ptr(walk.abase);
                     bb = uniform_ptr(walk.bbase);
@@ -582,11 +594,26 @@ __device__ __forceinline__ void run16(Walk& walk, int n_ktiles, char* smem,
         }
     };
 
+    // Wherever the accumulators may be touched by anything but a matrix instruction -- the
+    // epilogue, and the copies the compiler may place between the differently unrolled
+    // iterations below -- the matrix pipeline is drained first and every accumulator is tied to
+    // a point after the drain.
+    auto settle = [&]() __attribute__((always_inline)) {
+        mfma_drain();
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NTL; ++j) pin(acc[i][j]);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    using T = std::true_type;
+    using F = std::false_type;
+
     // Prologue: tiles 0 .. STAGES-2 and the first loads of tile STAGES-1 in flight, tile 0 landed
     // and visible, its first fragments read.
     issue_all(0);
-    if (STAGES == 3 && n_ktiles > 1) issue_all(1);
-    if (n_ktiles > STAGES - 1) {
+    if (STAGES == 3 && (kAlwaysFull || n_ktiles > 1)) issue_all(1);
+    if (kAlwaysFull || n_ktiles > STAGES - 1) {
         const char* ab = uniform_ptr(walk.abase);
         const char* bb = uniform_ptr(walk.bbase);
 #pragma unroll
@@ -603,20 +630,20 @@ __device__ __forceinline__ void run16(Walk& walk, int n_ktiles, char* smem,
     for (int r = 0; r < kReads; ++r) read_frag(0, 0, r, 0);
 
     probe.prologue_done();
-    // Wherever the accumulators may be touched by anything but a matrix instruction -- the
-    // epilogue, and the copies the compiler may place between the differently unrolled
-    // iterations below -- the matrix pipeline is drained first and every accumulator is tied to
-    // a point after the drain.
-    auto settle = [&]() __attribute__((always_inline)) {
-        mfma_drain();
-#pragma unroll
-        for (int i = 0; i < MT; ++i)
-#pragma unroll
-            for (int j = 0; j < NTL; ++j) pin(acc[i][j]);
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    using T = std::true_type;
-    using F = std::false_type;
+    if (kAlwaysFull) {
+        // rounds of STAGES iterations whose stages are constants, then the n % STAGES left over
+        for (int round = n_ktiles / STAGES; round > 0; --round) {
+            iteration(std::integral_constant<int, 0>{}, T{}, T{}, T{});
+            iteration(std::integral_constant<int, 1>{}, T{}, T{}, T{});
+            if (STAGES == 3) iteration(std::integral_constant<int, 2>{}, T{}, T{}, T{});
+        }
+        const int left = n_ktiles % STAGES;
+        if (left >= 1) iteration(std::integral_constant<int, 0>{}, T{}, T{}, T{});
+        if (STAGES == 3 && left >= 2) iteration(std::integral_constant<int, 1>{}, T{}, T{}, T{});
+        wait_vmcnt<0>();  // the loads issued past the end
+        settle();
+        return;
+    }
     int kt = 0;
     // steady state: rounds of STAGES iterations whose stages are constants
     for (; kt + 2 * STAGES - 1 < n_ktiles; kt += STAGES) {

@@ -88,6 +88,19 @@ template <int BM, int BN, bool AKC, bool BKC, int MF> struct PanelWalk {
             load_panel();
         }
     }
+    // The same for a pipeline that keeps issuing loads to the end of its k-loop: on the last
+    // k-tile the walk stays, and what is then fetched again is valid memory that nobody reads.
+    __device__ __forceinline__ void advance_or_stay()
+    {
+        if (kleft > 1) {
+            --kleft;
+            abase += TA::step(pa.ld);
+            bbase += TB::step(pb.ld);
+        } else if (ks + 1 < ks_end) {
+            ++ks;
+            load_panel();
+        }
+    }
 };
 
 // MF: 32 = v_mfma_f32_32x32x16_f16 fragments (every tile shape), 16 = v_mfma_f32_16x16x32_f16
@@ -180,13 +193,11 @@ template <class TC>
 hipError_t launch_out(const GemmPlan& p, const GemmTables& t, float alpha, float beta, hipStream_t st)
 {
     const int bm = p.info.tile_m, bn = p.info.tile_n;
-    // 256x128 and 128x128 run on 16x16x32 fragments (7 % faster on configuration 3's forward and
-    // data-gradient GEMMs, A/B on one box).  256x256 stays on 32x32x16: its 256 accumulator
-    // registers leave the 16-row pipeline's address tables no room, and the compiler spills
-    // accumulators around the last iterations.  DMATH_F16_MFMA32=1 switches the others back too
-    // (A/B measurements).
+    // The three large tiles run on 16x16x32 fragments; DMATH_F16_MFMA32=1 switches them back to
+    // 32x32x16 (A/B measurements).
     static const bool mf32 = std::getenv("DMATH_F16_MFMA32") != nullptr;
     if (!mf32) {
+        if (bm == 256 && bn == 256) return launch_shape<256, 256, 2, TC, 16>(t, alpha, beta, st);
         if (bm == 256 && bn == 128) return launch_shape<256, 128, 3, TC, 16>(t, alpha, beta, st);
         if (bm == 128 && bn == 128) return launch_shape<128, 128, 2, TC, 16>(t, alpha, beta, st);
     }

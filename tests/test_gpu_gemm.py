@@ -530,6 +530,35 @@ def test_fp16_every_k_tile_count_per_tile_shape(oracle, monkeypatch, tile, ta, t
         c.close()
 
 
+@pytest.mark.parametrize("tile", ["256x256", "256x128", "128x128"])
+def test_fp16_k_segments_and_splits_per_tile_shape(oracle, monkeypatch, tile):
+    """The k-loop of the 16x16x32 pipeline over several k-segments (block boundaries of A and B
+    along k: the walk reloads its panel descriptors inside the loop) and split into parts, on
+    each tile shape, beta = 0 and 1; small integers, bit for bit."""
+    monkeypatch.setenv("DMATH_TILE", tile)
+    r = np.random.default_rng(271)
+    c = make_context(0.5)
+    try:
+        M = N = 512
+        for K, gk in ((512, 4), (512, 1), (768, 3), (1024, 8), (256, 2), (512, 2), (1280, 5)):
+            for beta in (0.0, 1.0):
+                A = r.integers(-3, 4, (M, K)).astype(np.float16)
+                B = r.integers(-3, 4, (K, N)).astype(np.float16)
+                C0 = r.integers(-3, 4, (M, N)).astype(np.float32)
+                dA, dB, dC = c.from_host(A, (1, gk)), c.from_host(B, (gk, 1)), c.from_host(C0)
+                info = dm.gemm_plan_info(c, 0, 0, dA, dB, dC)
+                assert f"{info['tile_m']}x{info['tile_n']}" == tile and info["kernel"] > 0, info
+                dm.gemm(c, 0, 0, 1.0, dA, dB, beta, dC)
+                got = dC.get().astype(np.float64)
+                ref = oracle.gemm(False, False, 1.0, oracle.BlockMatrix(A, (1, gk)), oracle.BlockMatrix(B, (gk, 1)),
+                                  beta, C0)
+                assert np.array_equal(got, ref), (tile, K, gk, beta, info["split_k"], int((got != ref).sum()))
+                for m in (dA, dB, dC):
+                    m.destroy()
+    finally:
+        c.close()
+
+
 @pytest.mark.parametrize("dt,out,tile,shape", [
     (dm.F32, dm.F32, "128x64", (1300, 4128, 256)),     # 11 x 65 = 715 tiles on 512 workgroup slots
     (dm.F64, dm.F64, "128x64", (1300, 4128, 256)),
