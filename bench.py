@@ -196,6 +196,7 @@ def main():
             for m in d.values():
                 m.destroy()
         bench_workload(synth.config1(), "cfg1", "f32")
+        bench_step(synth.config1(), "cfg1", "f32")      # its two launches issued and replayed as a recorded pipeline
         bench_step(synth.config3("f32"), "cfg3_f32out", "f16")
         bench_workload(synth.config3("f32"), "cfg3_f32out", "f16")
         bench_workload(synth.config3("f16"), "cfg3_f16out", "f16")

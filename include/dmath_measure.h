@@ -27,7 +27,8 @@ dmath_status_t dmath_cycle_probe_read(dmath_ctx_t ctx, uint64_t *out6);
 /*
  * Measurement aid (not part of the paper's method): enqueues a register-only kernel in which
  * every wavefront issues independent chains of the MFMA instruction the GEMM kernels of
- * `dtype` use, `iters` times 16 instructions per wavefront, and returns in *flops the number
+ * `dtype` use (fp16: v_mfma_f32_16x16x32_f16, 64 per iteration; fp32 and fp64: 16 per iteration),
+ * `iters` iterations per wavefront, and returns in *flops the number
  * of floating-point operations it performs.  Timing it gives the matrix-core rate the chip
  * sustains at its clocks under load, to be read beside the nominal peak.
  */

@@ -64,11 +64,13 @@ template <int BMN, bool KC, int MF = 32> struct OperandTile {
     // on the same bank, so the four rows a transposing read touches are spread by two chunk bits;
     // 128-byte rows (64 columns) alternate between two bank halves already and need one bit,
     // taken from the row pair.  Both are the same for rows 4 and 16 apart.
-    // 16-row fragments: a transposing read of 32 lanes touches k rows r .. r+3 and r+8 .. r+11 of
-    // one 16-column group, so a third chunk bit, taken from row bit 3, separates the two row groups.
+    // 16-row fragments: the four 16-lane groups of a transposing read touch k rows r .. r+3 of the
+    // four 8-row blocks of a 32-deep k-step, all in one 16-column group; a third chunk bit, the
+    // parity of row bits 3 and 4, differs between any two blocks that are 8 or 16 rows apart, so
+    // whichever two groups the LDS serves together land on different banks.
     __device__ __forceinline__ static int mswz(int row)
     {
-        if (MF == 16) return ((row & 3) << 2) | (((row >> 3) & 1) << 1);
+        if (MF == 16) return ((row & 3) << 2) | ((((row >> 3) ^ (row >> 4)) & 1) << 1);
         return BMN >= 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
     }
 
@@ -103,6 +105,14 @@ template <int BMN, bool KC, int MF = 32> struct OperandTile {
     // bytes a dense panel pointer advances per k-tile
     __device__ __forceinline__ static int64_t step(int64_t ld) { return KC ? BK * 2 : BK * 2 * ld; }
 
+    // 16-row fragments: which 8-deep block of a 32-deep k-step the 16-lane group g supplies.
+    // The instruction sums over k, so any order serves as long as both operands use the same one;
+    // blocks 1 and 2 are exchanged because a 128-bit read serves lanes of groups g and g+2 (or
+    // g and g+1 -- the counters cannot tell which) in one turn: with the natural order the two read
+    // chunks 2 apart of rows of equal parity, the same banks (counted: 40 to 50 % of the LDS
+    // cycles were conflicts); exchanged, chunks 1 or 2 apart never coincide under the row XOR.
+    __device__ __forceinline__ static constexpr int kgroup(int g) { return ((g & 1) << 1) | (g >> 1); }
+
     // Per-lane LDS byte offset (inside the operand's stage) of the fragment for k-step 0 of the
     // MF-row tile starting at mn_base.
     __device__ __forceinline__ static uint32_t frag_base(int mn_base, int lane)
@@ -111,7 +121,7 @@ template <int BMN, bool KC, int MF = 32> struct OperandTile {
         const int g = lane >> 4, i = lane & 15;
         // the 16-lane group g reads a 4 (k) x 16 (mn) patch: 32-row fragments have two column
         // groups and two k-groups of 8, 16-row fragments one column group and four k-groups
-        const int row = (MF == 32 ? 8 * (g >> 1) : 8 * g) + (i >> 2);
+        const int row = (MF == 32 ? 8 * (g >> 1) : 8 * kgroup(g)) + (i >> 2);
         const int col = mn_base + (MF == 32 ? 16 * (g & 1) : 0) + 4 * (i & 3);
         return (uint32_t)(row * (BMN * 2) + (((col >> 3) ^ mswz(row)) << 4) + (col & 7) * 2);
     }
@@ -122,7 +132,7 @@ template <int BMN, bool KC, int MF = 32> struct OperandTile {
                                                    int h, int s)
     {
         if (KC) {
-            const int chunk = (MF == 32 ? (s << 1) + h : (s << 2) + h) ^ swz(mn_row);
+            const int chunk = (MF == 32 ? (s << 1) + h : (s << 2) + kgroup(h)) ^ swz(mn_row);
             return *reinterpret_cast<const __attribute__((address_space(3))) v8h*>(tile + fb + (chunk << 4));
         }
         const lds_char* p = tile + fb + s * ((MF == 32 ? 16 : 32) * BMN * 2);
@@ -136,7 +146,7 @@ template <int BMN, bool KC, int MF = 32> struct OperandTile {
     // 16-row fragments, addressed so that a read is ONE instruction: a loop-invariant lane address
     // out of a small table plus an immediate.  f: which of the wavefront's 16-row blocks, s: which
     // 32-deep k-step; the wavefront's first row mn0 is a multiple of 64.
-    //   k unit-stride: chunk = (4s + g) ^ swz(row) = [g ^ (l&7) ^ (l>>3)] ^ [(4s) ^ (2f & 7)] (g = lane/16,
+    //   k unit-stride: chunk = (4s + g) ^ swz(row) = [g ^ (l&7) ^ (l>>3)] ^ [(4s) ^ (2f & 7)] (g = kgroup(lane/16),
     //     l = lane%16): the bracket on the right is one of eight constants, so eight lane addresses
     //     serve every fragment, the block's row offset 2048*f goes into the immediate;
     //   m/n unit-stride: the chunk XOR depends on the lane only, one lane address per block, the
@@ -148,7 +158,7 @@ template <int BMN, bool KC, int MF = 32> struct OperandTile {
 #pragma unroll
         for (int k = 0; k < kAddr; ++k) {
             if (KC)
-                x[k] = (uint32_t)((mn0 + l) * 128 + (((g ^ (l & 7) ^ (l >> 3)) ^ k) << 4));
+                x[k] = (uint32_t)((mn0 + l) * 128 + (((kgroup(g) ^ (l & 7) ^ (l >> 3)) ^ k) << 4));
             else
                 x[k] = frag_base(mn0 + 16 * k, lane);
         }

@@ -46,6 +46,19 @@ template <int BMN, bool KC> struct OperandTile {
     static constexpr int kRowsPerSeg = 64 / kChunksPerRow;
     static constexpr int kReadsPerFrag = KC ? 1 : 2;
 
+    // Chunk XOR of an m/n unit-stride tile ([k][mn], rows of 512 or 1024 bytes: every row starts on
+    // the same bank).  A 64-bit fragment read serves 32 lanes at a time, the 16 doubles of one k row
+    // and those of a row 2 or 4 further on: moving rows by 128 bytes according to the parity of row
+    // bits 1 and 2 puts any such two on different bank halves (without it the counters showed
+    // every such read taking two turns).
+    __device__ __forceinline__ static int mswz(int row) { return (((row >> 1) ^ (row >> 2)) & 1) << 3; }
+
+    // Which pair of k indices of an 8-deep group the 16-lane group g supplies.  The instruction sums
+    // over k, so any order serves as long as both operands use the same one; pairs 1 and 2 are
+    // exchanged because a 128-bit read serves lanes of two groups in one turn, and with the natural
+    // order those read chunks 2 apart of rows of equal parity: the same banks.
+    __device__ __forceinline__ static constexpr int kgroup(int g) { return ((g & 1) << 1) | (g >> 1); }
+
     // Row (k unit-stride: m/n index; otherwise: k index) inside the tile, and 16-byte chunk of
     // that row in memory, which this lane fetches with segment q (operands whose rows are gathered).
     __device__ __forceinline__ static void lane_slot(int q, int wave, int lane, int& row, int& chunk)
@@ -53,7 +66,7 @@ template <int BMN, bool KC> struct OperandTile {
         const int seg = q * 4 + wave;
         row = seg * kRowsPerSeg + lane / kChunksPerRow;
         const int cpos = lane % kChunksPerRow;
-        chunk = KC ? (cpos ^ swz(row)) : cpos;
+        chunk = KC ? (cpos ^ swz(row)) : (cpos ^ mswz(row));
     }
 
     // byte offsets (relative to the panel origin) of the chunks this lane fetches at k-tile 0
@@ -71,7 +84,7 @@ template <int BMN, bool KC> struct OperandTile {
             if (KC)
                 off[q] = (uint32_t)((((int64_t)(mn0 + min(row, len - 1))) * ld + (cpos ^ swz(row)) * 2) * 8);
             else
-                off[q] = (uint32_t)(((int64_t)row * ld + mn0 + min(cpos, (len - 1) >> 1) * 2) * 8);
+                off[q] = (uint32_t)(((int64_t)row * ld + mn0 + min(cpos ^ mswz(row), (len - 1) >> 1) * 2) * 8);
         }
     }
     __device__ __forceinline__ static int64_t step(int64_t ld) { return KC ? BK * 8 : BK * 8 * ld; }
@@ -83,10 +96,11 @@ template <int BMN, bool KC> struct OperandTile {
     {
         if (KC) {
             frag = *reinterpret_cast<const __attribute__((address_space(3))) v2d*>(
-                tile + mn * 128 + ((((u << 2) + g) ^ swz(mn)) << 4));
+                tile + mn * 128 + ((((u << 2) + kgroup(g)) ^ swz(mn)) << 4));
         } else {
+            const int row = 8 * u + 2 * kgroup(g) + part;
             frag[part] = *reinterpret_cast<const __attribute__((address_space(3))) double*>(
-                tile + ((8 * u + 2 * g + part) * BMN + mn) * 8);
+                tile + row * (BMN * 8) + (((mn >> 1) ^ mswz(row)) << 4) + (mn & 1) * 8);
         }
     }
 };

@@ -39,12 +39,13 @@ __global__ __launch_bounds__(256) void peak_f32(float* out, int iters)
 
 // The operands rotate through eight different pseudo-random fragments per lane, so that the
 // matrix cores see inputs that change from instruction to instruction as in a real GEMM
-// (constant operands draw less power and sustain a higher clock).
+// (constant operands draw less power and sustain a higher clock).  The instruction is the one
+// the large fp16 GEMM tiles use, v_mfma_f32_16x16x32_f16, sixteen independent chains.
 __global__ __launch_bounds__(256) void peak_f16(float* out, int iters)
 {
-    v16f c[4];
-    for (int i = 0; i < 4; ++i)
-        for (int r = 0; r < 16; ++r) c[i][r] = 0.f;
+    v4f c[16];
+    for (int i = 0; i < 16; ++i)
+        for (int r = 0; r < 4; ++r) c[i][r] = 0.f;
     v8h a[4], b[4];
     uint32_t seed = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
     for (int q = 0; q < 4; ++q)
@@ -58,11 +59,12 @@ __global__ __launch_bounds__(256) void peak_f16(float* out, int iters)
 #pragma unroll
         for (int u = 0; u < 4; ++u)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) c[i] = mfma_f16_32x32x16(a[(u + i) & 3], b[u], c[i]);
+            for (int i = 0; i < 16; ++i)
+                c[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[(u + i) & 3], b[(u + (i >> 2)) & 3], c[i], 0, 0, 0);
     }
     float s = 0.f;
-    for (int i = 0; i < 4; ++i)
-        for (int r = 0; r < 16; ++r) s += c[i][r];
+    for (int i = 0; i < 16; ++i)
+        for (int r = 0; r < 4; ++r) s += c[i][r];
     if (s == 12345.678f) out[0] = s;
 }
 
@@ -104,7 +106,7 @@ hipError_t launch_mfma_peak(dmath_dtype_t dt, int iters, void* scratch, hipStrea
         *flops = waves * iters * 16.0 * (2.0 * 32 * 32 * 2);
     } else if (dt == DMATH_F16) {
         peak_f16<<<blocks, threads, 0, st>>>(out, iters);
-        *flops = waves * iters * 16.0 * (2.0 * 32 * 32 * 16);
+        *flops = waves * iters * 64.0 * (2.0 * 16 * 16 * 32);
     } else {
         peak_f64<<<blocks, threads, 0, st>>>(out, iters);
         *flops = waves * iters * 16.0 * (2.0 * 16 * 16 * 4);

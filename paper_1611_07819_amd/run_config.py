@@ -1,12 +1,16 @@
 """Runs the calls of one benchmark configuration a few times and prints per-call timings.
 
-    python -m paper_1611_07819_amd.run_config <1|2|3|3h|4|5|5h> [--iters N] [--only CALL]
-        [--copy-probe]
+    python -m paper_1611_07819_amd.run_config <1|2|3|3h|4|5|5h|skinny> [--iters N] [--only CALL]
+        [--copy-probe] [--vendor-reference]
 
 Meant as the target of a profiler (`rocprofv3 ... -- python3 -m paper_1611_07819_amd.run_config 3`):
 inputs are the seeded synthetic recipes of ``synth.py``; nothing is checked here.
 ``--copy-probe`` appends three 1 GiB device-to-device copies (a kernel of known traffic that
-calibrates the HBM byte counters)."""
+calibrates the HBM byte counters).  ``skinny`` is the batch-of-64 workload of the benchmark's
+side table (fp16 64 x 4096 x 4096 and 64 x 4096 x 9216, fp32 64 x 4096 x 9216).
+``--vendor-reference`` also times the vendor GEMM library (through torch.matmul) on the same
+shapes and operand orientations: a measuring stick for what this chip gives a tuned kernel at
+these sizes, never part of the product path."""
 import argparse
 import os
 import sys
@@ -20,6 +24,7 @@ def main():
     ap.add_argument("--iters", type=int, default=20)
     ap.add_argument("--only", default=None)
     ap.add_argument("--copy-probe", action="store_true")
+    ap.add_argument("--vendor-reference", action="store_true")
     ap.add_argument("--cycle-probe", action="store_true",
                     help="print the fp16 GEMM kernel's own cycle counts (needs the probe build of the "
                          "library: python -m paper_1611_07819_amd.build --probe, then DMATH_LIBRARY=...)")
@@ -28,7 +33,20 @@ def main():
     import paper_1611_07819_amd as dm
     from paper_1611_07819_amd import synth
 
-    make = {"1": synth.config1, "2": synth.config2, "3": lambda: synth.config3("f32"),
+    import numpy as np
+
+    def skinny():
+        r = np.random.default_rng(16110781)
+        mats, calls = {}, []
+        for i, (dt, M, N, K) in enumerate((("f16", 64, 4096, 4096), ("f16", 64, 4096, 9216), ("f32", 64, 4096, 9216))):
+            npdt = np.float16 if dt == "f16" else np.float32
+            mats[f"A{i}"] = r.uniform(0, 1, (M, K)).astype(npdt)
+            mats[f"B{i}"] = r.normal(0, 0.01, (K, N)).astype(npdt)
+            mats[f"C{i}"] = np.zeros((M, N), np.float32)
+            calls.append(synth.GemmCall(f"nn_{dt}_M{M}_N{N}_K{K}", False, False, f"A{i}", f"B{i}", f"C{i}"))
+        return synth.Workload("skinny_batch64", "mixed", (1, 1), mats, calls)
+
+    make = {"skinny": skinny, "1": synth.config1, "2": synth.config2, "3": lambda: synth.config3("f32"),
             "3h": lambda: synth.config3("f16"), "4": synth.config4,
             "5": lambda: synth.config5("f32"), "5h": lambda: synth.config5("f16")}[args.config]
     w = make()
@@ -45,6 +63,12 @@ def main():
         calls.append((c.name, 2.0 * M * N * K, desc,
                       lambda c=c: dm.gemm(ctx, int(c.transA), int(c.transB), c.alpha, dev[c.a],
                                           dev[c.b], c.beta, dev[c.c])))
+    vendor = {}
+    if args.vendor_reference:
+        tdev = {k: torch.from_numpy(v).cuda() for k, v in w.mats.items()}
+        for c in w.calls:
+            a, b = tdev[c.a], tdev[c.b]
+            vendor[c.name] = (lambda a=a, b=b, c=c: torch.matmul(a.t() if c.transA else a, b.t() if c.transB else b))
     if w.conv:
         d = dm.ConvDesc(**w.conv)
         g = w.conv
@@ -69,6 +93,19 @@ def main():
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / args.iters
         print(f"{w.name} {name}: {desc}: {ms * 1e3:.1f} us  {fl / ms / 1e9:.1f} TFLOP/s", flush=True)
+        if args.vendor_reference and name in vendor:
+            vf = vendor[name]
+            for _ in range(50):
+                vf()
+            torch.cuda.synchronize()
+            e0.record(st)
+            for _ in range(args.iters):
+                vf()
+            e1.record(st)
+            torch.cuda.synchronize()
+            vms = e0.elapsed_time(e1) / args.iters
+            print(f"    vendor library (torch.matmul), same shape and orientation: {vms * 1e3:.1f} us  "
+                  f"{fl / vms / 1e9:.1f} TFLOP/s", flush=True)
         if args.cycle_probe and name.startswith(("fwd", "dW", "dX", "nn")):
             c = ctx.cycle_probe_read()
             cyc = c["prologue"] + c["loop"] + c["epilogue"]
