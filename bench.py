@@ -316,12 +316,14 @@ def main():
 
     # ---------------- MFMA-only probe: what the matrix cores sustain at their clocks under load
     sustained = {}
-    for key, code, iters in (("f32", dm.F32, 4000), ("f16", dm.F16, 8000), ("f64", dm.F64, 4000)):
-        ctx.mfma_peak_probe(code, 200)
+    for key, code, iters in (("f32", dm.F32, 4000), ("f16", dm.F16, 8000), ("f16_32x32x16", dm.F16, 8000),
+                             ("f64", dm.F64, 4000)):
+        wide = key == "f16_32x32x16"
+        ctx.mfma_peak_probe(code, 200, wide)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
-        fl = ctx.mfma_peak_probe(code, iters)
+        fl = ctx.mfma_peak_probe(code, iters, wide)
         e1.record(stream)
         torch.cuda.synchronize()
         sustained[key] = round(fl / e0.elapsed_time(e1) / 1e9, 1)

@@ -35,6 +35,14 @@ dmath_status_t dmath_cycle_probe_read(dmath_ctx_t ctx, uint64_t *out6);
 dmath_status_t dmath_mfma_peak_probe(dmath_ctx_t ctx, dmath_dtype_t dtype, int32_t iters,
                                      double *flops);
 
+/*
+ * The same for fp16 on v_mfma_f32_32x32x16_f16 (16 per iteration, the same flops per iteration):
+ * the instruction of the fp16 convolution kernels and of the 64-row GEMM tiles.  Read beside
+ * dmath_mfma_peak_probe(DMATH_F16) it shows what the smaller instruction buys at the chip's
+ * power limit.
+ */
+dmath_status_t dmath_mfma_peak_probe_f16_32x32x16(dmath_ctx_t ctx, int32_t iters, double *flops);
+
 #ifdef __cplusplus
 }
 #endif

@@ -764,19 +764,29 @@ dmath_status_t dmath_set_kernel_policy(dmath_ctx_t ctx, int32_t policy)
     });
 }
 
-dmath_status_t dmath_mfma_peak_probe(dmath_ctx_t ctx, dmath_dtype_t dtype, int32_t iters, double* flops)
+static dmath_status_t mfma_peak_probe(dmath_ctx_t ctx, dmath_dtype_t dtype, int32_t iters, double* flops, bool wide_f16)
 {
     return guarded([&]() -> dmath_status_t {
         if (!ctx || !flops || !valid_dtype(dtype) || iters <= 0) return DMATH_ERR_INVALID_ARG;
         void* scratch = ctx->pool.alloc(256);
         if (!scratch) return DMATH_ERR_OOM;
         double f = 0;
-        hipError_t e = launch_mfma_peak(dtype, iters, scratch, ctx->stream, &f);
+        hipError_t e = launch_mfma_peak(dtype, iters, scratch, ctx->stream, &f, wide_f16);
         ctx->pool.free(scratch);  // the kernel practically never writes; reuse is stream-ordered anyway
         if (e != hipSuccess) return DMATH_ERR_DEVICE;
         *flops = f;
         return DMATH_OK;
     });
+}
+
+dmath_status_t dmath_mfma_peak_probe(dmath_ctx_t ctx, dmath_dtype_t dtype, int32_t iters, double* flops)
+{
+    return mfma_peak_probe(ctx, dtype, iters, flops, false);
+}
+
+dmath_status_t dmath_mfma_peak_probe_f16_32x32x16(dmath_ctx_t ctx, int32_t iters, double* flops)
+{
+    return mfma_peak_probe(ctx, DMATH_F16, iters, flops, true);
 }
 
 dmath_status_t dmath_cycle_probe_read(dmath_ctx_t ctx, uint64_t* out6)

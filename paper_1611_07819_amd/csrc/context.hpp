@@ -235,7 +235,8 @@ int64_t conv_fast_partial_elems(int mode, const ConvGeom& g, dmath_dtype_t in_dt
 hipError_t launch_conv_fast(const ConvPlan& p, int mode, double alpha, double beta, unsigned rewrite,
                            hipStream_t st);
 bool read_cycle_probe(uint64_t* out6);  // gemm_f16.hip; false unless built with the cycle probe
-hipError_t launch_mfma_peak(dmath_dtype_t dt, int iters, void* scratch, hipStream_t st, double* flops);
+hipError_t launch_mfma_peak(dmath_dtype_t dt, int iters, void* scratch, hipStream_t st, double* flops,
+                            bool wide_f16 = false);
 // Picks kernel, tile shape and split-K; written next to the kernels whose preconditions it checks.
 struct SegView {
     int64_t M, N, K;

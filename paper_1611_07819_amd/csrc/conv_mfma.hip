@@ -64,6 +64,17 @@ struct Acc16d {
     __device__ __forceinline__ static int col(int lane) { return acc16d_col(lane); }
 };
 
+// Accumulators of the 16x16x32 fp16 MFMA: 4 registers, register r of lane l holds row
+// 4*(l/16) + r and column l%16: the four registers are four consecutive rows.
+struct Acc16q {
+    using AccT = float;
+    using Acc = v4f;
+    static constexpr int kRegs = 4, kEdge = 16;
+    static constexpr bool kRowQuads = true;
+    __device__ __forceinline__ static int row(int lane, int r) { return 4 * (lane >> 4) + r; }
+    __device__ __forceinline__ static int col(int lane) { return lane & 15; }
+};
+
 struct PipeF16 : Acc32 {
     using Elem = _Float16;
     static constexpr int BK = f16p::BK;
@@ -73,6 +84,20 @@ struct PipeF16 : Acc32 {
     __device__ __forceinline__ static void run(Walk& walk, int n_ktiles, char* smem, Acc& acc)
     {
         f16p::run<BM, BN, STAGES, AKC, BKC>(walk, n_ktiles, smem, acc);
+    }
+    static constexpr int lds_bytes(int bm, int bn, int stages) { return stages * (bm + bn) * BK * 2; }
+};
+// fp16 on 16x16x32 fragments (tiles of 128 rows and columns or more)
+struct PipeF16Q : Acc16q {
+    using Elem = _Float16;
+    static constexpr int BK = f16p::BK;
+    template <int BMN, bool KC> using Tile = f16p::OperandTile<BMN, KC, 16>;
+    template <int BM, int BN> using Shape = f16p::TileShape16<BM, BN>;
+    template <int BM, int BN, int STAGES, bool AKC, bool BKC, class Walk, class Acc>
+    __device__ __forceinline__ static void run(Walk& walk, int n_ktiles, char* smem, Acc& acc)
+    {
+        f16p::NoProbe none;
+        f16p::run16<BM, BN, STAGES, AKC, BKC>(walk, n_ktiles, smem, acc, none);
     }
     static constexpr int lds_bytes(int bm, int bn, int stages) { return stages * (bm + bn) * BK * 2; }
 };
@@ -320,6 +345,7 @@ template <class P, int BM, int BN> struct FwdWalk {
     const char *abase, *bbase, *xp;
     uint32_t aoff[TA::kInstr], boff[TB::kInstr];
     int c, wp, s_taps, cchunks, r, s, cc;
+    int ahead = 0;  // k-tiles after the current one (advance_or_stay only)
 
     // starts at k-tile kt0 of the (r, s, c) order
     __device__ __forceinline__ FwdWalk(const FastConv& p, int m0, int n0, int wave, int lane, int kt0)
@@ -354,6 +380,14 @@ template <class P, int BM, int BN> struct FwdWalk {
         }
         abase = xp + ((int64_t)(r * wp + s) * c + cc * BK) * sizeof(T);
     }
+    // for pipelines that issue loads to the end of the k-loop: stays on the last k-tile
+    __device__ __forceinline__ void advance_or_stay()
+    {
+        if (ahead > 0) {
+            --ahead;
+            advance();
+        }
+    }
 };
 
 // workgroup w of n: XCD w % 8 gets a contiguous run of the logical order
@@ -387,7 +421,7 @@ __global__ __launch_bounds__(NT) void conv_fwd_kernel(FastConv p, typename P::Ac
     const int m0 = (mn / tiles_n) * BM, n0 = (mn % tiles_n) * BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = TS::wm(wave), wn = TS::wn(wave), h = lane >> 5, lcol = P::col(lane);
+    const int wm = TS::wm(wave), wn = TS::wn(wave), lcol = P::col(lane);
 
     typename P::Acc acc[MT][NTL];
 #pragma unroll
@@ -399,8 +433,9 @@ __global__ __launch_bounds__(NT) void conv_fwd_kernel(FastConv p, typename P::Ac
 
     const int kt0 = part * p.ktiles_per_split;
     FwdWalk<P, BM, BN> walk(p, m0, n0, wave, lane, kt0);
-    P::template run<BM, BN, STAGES, true, true>(walk, partial ? min(p.ktiles_per_split, p.ktiles - kt0) : p.ktiles,
-                                                smem, acc);
+    const int n_ktiles = partial ? min(p.ktiles_per_split, p.ktiles - kt0) : p.ktiles;
+    walk.ahead = n_ktiles - 1;
+    P::template run<BM, BN, STAGES, true, true>(walk, n_ktiles, smem, acc);
 
     if (partial) {
         // partial sums [part][output channel][pixel], the pixels those of the split tiles (whole
@@ -416,11 +451,11 @@ __global__ __launch_bounds__(NT) void conv_fwd_kernel(FastConv p, typename P::Ac
                 if constexpr (P::kRowQuads) {
                     typedef AccT acc4 __attribute__((ext_vector_type(4)));
 #pragma unroll
-                    for (int q4 = 0; q4 < 4; ++q4) {
+                    for (int q4 = 0; q4 < P::kRegs / 4; ++q4) {
                         acc4 o;
 #pragma unroll
                         for (int e = 0; e < 4; ++e) o[e] = acc[i][j][q4 * 4 + e];
-                        *reinterpret_cast<acc4*>(col + 8 * q4 + 4 * h) = o;
+                        *reinterpret_cast<acc4*>(col + P::row(lane, 4 * q4)) = o;
                     }
                 } else {
 #pragma unroll
@@ -482,33 +517,36 @@ __global__ __launch_bounds__(NT) void conv_fwd_kernel(FastConv p, typename P::Ac
         return;
     }
     if constexpr (P::kRowQuads) {
-        // with the 32x32 MFMAs four consecutive registers are four consecutive pixels of one
+        // with the fp16 / fp32 MFMAs four consecutive registers are four consecutive pixels of one
         // output plane: stored together where a plane is a multiple of 4 pixels
         typedef TC out4 __attribute__((ext_vector_type(4)));
         typedef __attribute__((address_space(1))) out4 GOut4;
+        constexpr int kQuads = P::kRegs / 4;
         // the row pointers of block row i + 1 are loaded before the stores of block row i
-        auto row_pointers = [&](int i, GTC* (&rowp)[4]) {
+        auto row_pointers = [&](int i, GTC* (&rowp)[kQuads]) {
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const int m = m0 + wm * WM + i * 32 + 8 * q4 + 4 * h;
+            for (int q4 = 0; q4 < kQuads; ++q4) {
+                const int m = m0 + wm * WM + i * E + P::row(lane, 4 * q4);
                 const bool ok = m < m_end;  // ragged last tile (m_end is a multiple of 4, as sp_out is)
                 const int mm = ok ? m : 0, n_img = mm / sp_out, sp = mm - n_img * sp_out;
                 GTC* y = (GTC*)static_cast<TC*>(const_cast<void*>(p.y_rows[n_img]));
                 rowp[q4] = ok ? y + sp : nullptr;
             }
         };
-        GTC* rowp[4];
+        GTC* rowp[kQuads];
         row_pointers(0, rowp);
 #pragma unroll
         for (int i = 0; i < MT; ++i) {
-            GTC* next[4] = {nullptr, nullptr, nullptr, nullptr};
+            GTC* next[kQuads];
+#pragma unroll
+            for (int q4 = 0; q4 < kQuads; ++q4) next[q4] = nullptr;
             if (i + 1 < MT) row_pointers(i + 1, next);
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
+            for (int q4 = 0; q4 < kQuads; ++q4) {
                 GOut4* dst[NTL];
 #pragma unroll
                 for (int j = 0; j < NTL; ++j) {
-                    const int ko = n0 + wn * WN + j * 32 + lcol;
+                    const int ko = n0 + wn * WN + j * E + lcol;
                     GTC* d = (ko < p.k_real && rowp[q4]) ? rowp[q4] + (int64_t)ko * sp_out : sink;  // pad filters
                     dst[j] = reinterpret_cast<GOut4*>(d);
                 }
@@ -537,7 +575,7 @@ __global__ __launch_bounds__(NT) void conv_fwd_kernel(FastConv p, typename P::Ac
                 }
             }
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) rowp[q4] = next[q4];
+            for (int q4 = 0; q4 < kQuads; ++q4) rowp[q4] = next[q4];
         }
     }
 }
@@ -1153,7 +1191,8 @@ hipError_t launch_fwd_shape(const FastConv& geom, dmath_dtype_t out, double alph
     p.ktiles = p.g.r * p.g.s * (p.g.c / P::BK);
     p.ktiles_per_split = (p.ktiles + p.split - 1) / p.split;
     if (!wgrad_split_ok(p.ktiles, p.split) || (p.split > 1 && !p.ws)) return hipErrorInvalidValue;
-    const dmath_dtype_t in = std::is_same<P, PipeF16>::value ? DMATH_F16 : std::is_same<P, PipeF32>::value ? DMATH_F32 : DMATH_F64;
+    constexpr bool kHalf = std::is_same<typename P::Elem, _Float16>::value;
+    const dmath_dtype_t in = kHalf ? DMATH_F16 : std::is_same<P, PipeF32>::value ? DMATH_F32 : DMATH_F64;
     p.full_tiles = p.split == 1    ? tiles_m * tiles_n
                    : p.tail_only   ? (int)fwd_full_tiles(tiles_m, tiles_n, BM, BN, in)
                                    : 0;
@@ -1163,7 +1202,7 @@ hipError_t launch_fwd_shape(const FastConv& geom, dmath_dtype_t out, double alph
     static bool configured = false;  // more than 64 KiB of LDS has to be asked for once per kernel
     if (!configured) {
         hipError_t e = set_lds(conv_fwd_kernel<P, BM, BN, STAGES, Wide>, lds);
-        if (e == hipSuccess && std::is_same<P, PipeF16>::value)
+        if (e == hipSuccess && kHalf)
             e = set_lds(conv_fwd_kernel<P, BM, BN, STAGES, typename P::Elem>, lds);
         if (e != hipSuccess) return e;
         configured = true;
@@ -1196,6 +1235,14 @@ hipError_t launch_fwd(const FastConv& p, dmath_dtype_t in, int tile_m, int tile_
         if (tile_m == 128 && tile_n == 128) return launch_fwd_shape<PipeF32, 128, 128, 3>(p, out, alpha, beta, st);
         if (tile_m == 128 && tile_n == 64) return launch_fwd_shape<PipeF32, 128, 64, 3>(p, out, alpha, beta, st);
         return hipErrorInvalidValue;
+    }
+    // The tiles whose wavefront parts are multiples of 64 on both sides run on 16x16x32 fragments;
+    // DMATH_F16_MFMA32=1 switches them back to 32x32x16 (A/B measurements).
+    static const bool mf32 = std::getenv("DMATH_F16_MFMA32") != nullptr;
+    if (!mf32) {
+        if (tile_m == 224 && tile_n == 256) return launch_fwd_shape<PipeF16Q, 224, 256, 2>(p, out, alpha, beta, st);
+        if (tile_m == 256 && tile_n == 256) return launch_fwd_shape<PipeF16Q, 256, 256, 2>(p, out, alpha, beta, st);
+        if (tile_m == 256 && tile_n == 128) return launch_fwd_shape<PipeF16Q, 256, 128, 3>(p, out, alpha, beta, st);
     }
     if (tile_m == 224 && tile_n == 256) return launch_fwd_shape<PipeF16, 224, 256, 2>(p, out, alpha, beta, st);
     if (tile_m == 256 && tile_n == 256) return launch_fwd_shape<PipeF16, 256, 256, 2>(p, out, alpha, beta, st);
@@ -1233,6 +1280,9 @@ hipError_t launch_wgrad(const FastConv& p, dmath_dtype_t in, int bm, int bn, int
         if (bm == 64 && bn == 64) return launch_wgrad_shape<PipeF32, 64, 64>(p, tiles, st);
         return hipErrorInvalidValue;
     }
+    // The weight gradient stays on 32x32x16 fragments: with its walk's many per-lane offsets the
+    // compiler renames accumulators between the iterations of the 16x16x32 pipeline and reads them
+    // before the matrix instructions written as assembly have finished (found by check_isa.py).
     if (bm == 256 && bn == 128) return launch_wgrad_shape<PipeF16, 256, 128>(p, tiles, st);
     if (bm == 128 && bn == 128) return launch_wgrad_shape<PipeF16, 128, 128>(p, tiles, st);
     if (bm == 64 && bn == 128) return launch_wgrad_shape<PipeF16, 64, 128>(p, tiles, st);

@@ -417,12 +417,18 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
 // the four phases that the load schedule and the barrier are laid over: the fragments of k-step 1
 // are read during phases 0 and 1, the barrier sits before phase 3, and phase 3 reads the first
 // fragments of the next tile.
+// The four wavefronts tile BM x BN as 2 x 2, or as 1 x 4 where BM is not a multiple of 128
+// (224 rows: fourteen 16-row blocks per wavefront; k unit-stride A only, whose lane addresses do
+// not depend on how many blocks a wavefront has).
 template <int BM, int BN> struct TileShape16 {
-    static constexpr int WM = BM / 2, WN = BN / 2;  // wavefront tile
+    static constexpr int WVM = BM % 128 == 0 ? 2 : 1, WVN = 4 / WVM;
+    static constexpr int WM = BM / WVM, WN = BN / WVN;  // wavefront tile
     static constexpr int MT = WM / 16, NTL = WN / 16;
     static_assert(MT % 2 == 0, "two halves of row blocks");
-    __device__ __forceinline__ static int wm(int wave) { return wave >> 1; }
-    __device__ __forceinline__ static int wn(int wave) { return wave & 1; }
+    static_assert(WM % 64 == 0 || WVM == 1, "a wavefront's first row is a multiple of 64");
+    static_assert(WN % 64 == 0, "a wavefront's first column is a multiple of 64");
+    __device__ __forceinline__ static int wm(int wave) { return wave / WVN; }
+    __device__ __forceinline__ static int wn(int wave) { return wave % WVN; }
 };
 
 template <int BM, int BN, int STAGES, bool AKC, bool BKC, class Walk, class Probe>
@@ -435,6 +441,7 @@ __device__ __forceinline__ void run16(Walk& walk, int n_ktiles, char* smem,
     constexpr int WM = TS::WM, WN = TS::WN, MT = TS::MT, NTL = TS::NTL;
     constexpr int kPerTile = TA::kInstr + TB::kInstr;
     static_assert(STAGES == 2 || STAGES == 3, "ring of two or three stages");
+    static_assert((AKC || TS::WVM == 2) && (BKC || TS::WVN == 2), "m/n unit-stride operands: 2 x 2 wavefronts");
     // LDS: the STAGES stages of A, then those of B.  A 16x16x32 instruction takes 16 cycles, and a
     // wavefront issues one instruction every four: between two of them there is room for three
     // others.  So in the steady state the stage of every iteration is a compile-time constant
@@ -447,12 +454,12 @@ __device__ __forceinline__ void run16(Walk& walk, int n_ktiles, char* smem,
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t wave_lds = lds0 + wave * 1024;  // where this wavefront's segments start (scalar)
-    // A wavefront tile of 128 x 128 fills the accumulator register file: the compiler then has no
-    // register to spare where differently scheduled iterations meet, and spills accumulators.  So
+    // A wavefront tile of 128 x 128 (or 224 x 64) fills the accumulator register file, or nearly: the
+    // compiler then has no register to spare where differently scheduled iterations meet, and spills.  So
     // there every iteration is the full one: loads are issued to the very end (the walk stays on
     // the last k-tile; what is fetched again lands in stages nobody reads any more), and the
     // last iteration reads "next" fragments it never uses.
-    constexpr bool kAlwaysFull = MT * NTL * 4 >= 256;
+    constexpr bool kAlwaysFull = MT * NTL * 4 >= 224;
     auto next_tile = [&]() __attribute__((always_inline)) {
         if constexpr (kAlwaysFull)
             walk.advance_or_stay();

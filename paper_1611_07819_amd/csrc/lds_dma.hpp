@@ -26,12 +26,15 @@ __device__ __forceinline__ const char* uniform_ptr(const char* p)
 }
 
 // One direct global->LDS load: lane fetches 16 bytes at (sbase + voff), lands at m0 + 16*lane.
+// The compiler is told what the assembly overwrites besides memory: M0, and in the second form
+// the scalar condition code, which the add sets (a comparison whose result the compiler kept in
+// SCC across such a load skipped a whole k-loop once).
 __device__ __forceinline__ void dma16(uint32_t lds_addr, const void* sbase, uint32_t voff)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(lds_addr), "v"(voff), "s"(sbase)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 // The same with the LDS address given as a scalar base plus an offset: where the offset is a
@@ -43,7 +46,7 @@ __device__ __forceinline__ void dma16(uint32_t lds_base, int lds_off, const void
         asm volatile("s_add_i32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3"
                      :
                      : "s"(lds_base), "i"(lds_off), "v"(voff), "s"(sbase)
-                     : "memory");
+                     : "memory", "m0", "scc");
     } else {
         dma16(lds_base + (uint32_t)lds_off, sbase, voff);
     }

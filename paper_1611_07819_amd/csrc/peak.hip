@@ -68,6 +68,34 @@ __global__ __launch_bounds__(256) void peak_f16(float* out, int iters)
     if (s == 12345.678f) out[0] = s;
 }
 
+// The same on v_mfma_f32_32x32x16_f16 (the instruction of the fp16 convolution kernels and of
+// the 64-row GEMM tiles): four chains of 16 accumulator registers, the same flops per iteration.
+__global__ __launch_bounds__(256) void peak_f16_wide(float* out, int iters)
+{
+    v16f c[4];
+    for (int i = 0; i < 4; ++i)
+        for (int r = 0; r < 16; ++r) c[i][r] = 0.f;
+    v8h a[4], b[4];
+    uint32_t seed = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
+    for (int q = 0; q < 4; ++q)
+        for (int e = 0; e < 8; ++e) {
+            seed = seed * 1664525u + 1013904223u;
+            a[q][e] = (_Float16)((float)(seed >> 16) * (1.0f / 65536.0f));
+            seed = seed * 1664525u + 1013904223u;
+            b[q][e] = (_Float16)((float)(seed >> 16) * (1.0f / 65536.0f) - 0.5f);
+        }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) c[i] = mfma_f16_32x32x16(a[(u + i) & 3], b[u], c[i]);
+    }
+    float s = 0.f;
+    for (int i = 0; i < 4; ++i)
+        for (int r = 0; r < 16; ++r) s += c[i][r];
+    if (s == 12345.678f) out[0] = s;
+}
+
 __global__ __launch_bounds__(256) void peak_f64(float* out, int iters)
 {
     v4d c[8];
@@ -96,7 +124,8 @@ __global__ __launch_bounds__(256) void peak_f64(float* out, int iters)
 }  // namespace
 
 // Enqueues the micro-kernel; *flops receives the floating-point operations it performs.
-hipError_t launch_mfma_peak(dmath_dtype_t dt, int iters, void* scratch, hipStream_t st, double* flops)
+// wide_f16: fp16 on the 32x32x16 instruction instead of 16x16x32.
+hipError_t launch_mfma_peak(dmath_dtype_t dt, int iters, void* scratch, hipStream_t st, double* flops, bool wide_f16)
 {
     const int blocks = 256 * 8, threads = 256;  // 8 workgroups of 4 wavefronts per CU
     const double waves = (double)blocks * threads / 64;
@@ -104,6 +133,9 @@ hipError_t launch_mfma_peak(dmath_dtype_t dt, int iters, void* scratch, hipStrea
     if (dt == DMATH_F32) {
         peak_f32<<<blocks, threads, 0, st>>>(out, iters);
         *flops = waves * iters * 16.0 * (2.0 * 32 * 32 * 2);
+    } else if (dt == DMATH_F16 && wide_f16) {
+        peak_f16_wide<<<blocks, threads, 0, st>>>(out, iters);
+        *flops = waves * iters * 16.0 * (2.0 * 32 * 32 * 16);
     } else if (dt == DMATH_F16) {
         peak_f16<<<blocks, threads, 0, st>>>(out, iters);
         *flops = waves * iters * 64.0 * (2.0 * 16 * 16 * 32);

@@ -113,6 +113,7 @@ def load_library(build_if_missing: bool = True):
         "dmath_synchronize": [vp],
         "dmath_cycle_probe_read": [vp, P(ctypes.c_uint64)],
         "dmath_mfma_peak_probe": [vp, ctypes.c_int, i32, P(dbl)],
+        "dmath_mfma_peak_probe_f16_32x32x16": [vp, i32, P(dbl)],
         "dmath_pool_stats": [vp, P(sz), P(sz), P(sz)],
     }
     for name, args in sig.items():
@@ -174,11 +175,16 @@ class Context:
                "dmath_relayout_stats")
         return {"reused": a.value, "written": b.value, "bytes_held": c.value}
 
-    def mfma_peak_probe(self, dtype: int, iters: int) -> float:
-        """Enqueues the MFMA-only micro-kernel; returns the flops it performs."""
+    def mfma_peak_probe(self, dtype: int, iters: int, wide_f16: bool = False) -> float:
+        """Enqueues the MFMA-only micro-kernel; returns the flops it performs (wide_f16: fp16
+        on the 32x32x16 instruction instead of 16x16x32)."""
         f = ctypes.c_double()
-        _check(self._lib.dmath_mfma_peak_probe(self._h, dtype, iters, ctypes.byref(f)),
-               "dmath_mfma_peak_probe")
+        if wide_f16:
+            _check(self._lib.dmath_mfma_peak_probe_f16_32x32x16(self._h, iters, ctypes.byref(f)),
+                   "dmath_mfma_peak_probe_f16_32x32x16")
+        else:
+            _check(self._lib.dmath_mfma_peak_probe(self._h, dtype, iters, ctypes.byref(f)),
+                   "dmath_mfma_peak_probe")
         return f.value
 
     def pipeline_begin(self):

@@ -292,6 +292,37 @@ def test_forward_and_data_gradient_with_a_split_k_loop(oracle, monkeypatch, g, d
         c.close()
 
 
+@pytest.mark.parametrize("split", ["1", "3"])
+@pytest.mark.parametrize("g", [
+    dict(n=5, c=128, h=14, w=14, k=256, r=3, s=3, pad_h=1, pad_w=1),   # 18 k-tiles (parts of 6), ragged last row tile
+    dict(n=4, c=64, h=16, w=16, k=256, r=3, s=1, pad_h=1, pad_w=0),    # 3 k-tiles (parts of 1)
+    dict(n=4, c=64, h=16, w=16, k=256, r=2, s=2, pad_h=1, pad_w=1),    # 4 k-tiles, even filter (parts of 2, 2: two parts)
+    dict(n=4, c=192, h=16, w=16, k=256, r=3, s=3, pad_h=1, pad_w=1),   # 27 k-tiles
+])
+@pytest.mark.parametrize("tile", ["224x256", "256x256", "256x128", "256x64"])
+@pytest.mark.parametrize("out", [dm.F32, dm.F16])
+def test_fp16_forward_tile_shapes_and_k_tile_counts(oracle, monkeypatch, out, tile, g, split):
+    """Every fp16 tile shape of the forward pass / data gradient (16x16x32 fragments: 224x256,
+    256x256, 256x128; 32x32x16: 256x64) over k-loops of 3 to 27 k-tiles, whole and in three parts
+    (down to one k-tile per part): bit for bit on small-integer data with beta = 1."""
+    monkeypatch.setenv("DMATH_CONV_TILE", tile)
+    monkeypatch.setenv("DMATH_CONV_SPLIT", split)
+    c = make_context(1.0)
+    try:
+        grids = {"X": (g["n"], 1), "F": (2, 1), "Y": (1, 1)}
+        before = c.relayout_stats()["written"]
+        res = three_modes(c, oracle, g, dm.F16, out, 1.0, 1.0, grids, ints=True, policy=0)
+        assert c.relayout_stats()["written"] - before == 6       # every mode on the specialised kernels
+        for mode in ("fwd", "bwd_filter", "bwd_data"):
+            got, ref = res[mode]
+            if out == dm.F16 and np.abs(ref).max() > 2048:
+                assert rel_fro(got, ref) <= TOL[dm.F16], mode
+            else:
+                assert np.array_equal(got.astype(np.float64), ref), mode
+    finally:
+        c.close()
+
+
 @pytest.mark.parametrize("dt,out,tile", [(dm.F16, dm.F32, "256x64"), (dm.F32, dm.F32, "128x64"),
                                          (dm.F64, dm.F64, "128x64")])
 def test_split_of_the_tiles_after_the_last_full_round(oracle, monkeypatch, dt, out, tile):

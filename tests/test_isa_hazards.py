@@ -1,0 +1,48 @@
+"""The compiler's output for the fp16 kernels holds no read of an accumulator register right
+behind the inline-assembly matrix instruction that writes it (paper_1611_07819_amd/check_isa.py
+explains the hazard).  Compiling both sources to assembly takes about five minutes, so the
+check runs only when DMATH_CHECK_ISA=1 is set; the scanner itself is always tested on
+hand-written snippets."""
+import os
+
+import pytest
+
+from paper_1611_07819_amd import check_isa
+
+
+def _lines(text):
+    return [l.strip() for l in text.strip().split("\n")]
+
+
+def test_scanner_flags_an_early_copy_and_accepts_a_drained_one():
+    early = _lines("""
+        s_nop 0
+        v_mfma_f32_16x16x32_f16 a[60:63], v[2:5], v[38:41], a[60:63]
+        ds_read_b64_tr_b16 v[38:39], v2
+        v_accvgpr_mov_b32 a127, a63
+    """)
+    assert [l for _, l, _ in check_isa.scan_function(early)] == ["v_accvgpr_mov_b32 a127, a63"]
+    drained = early[:3] + ["s_nop 15", "s_nop 15"] + early[3:]
+    assert check_isa.scan_function(drained) == []
+    other_register = early[:3] + ["v_accvgpr_mov_b32 a127, a59"]
+    assert check_isa.scan_function(other_register) == []
+    store = early[:3] + ["global_store_dwordx4 v[0:1], a[60:63], off"]
+    assert len(check_isa.scan_function(store)) == 1
+
+
+def test_scanner_follows_a_backward_branch():
+    loop = _lines("""
+        .LBB0_1:
+        v_accvgpr_read_b32 v7, a3
+        s_nop 0
+        v_mfma_f32_16x16x32_f16 a[0:3], v[2:5], v[38:41], a[0:3]
+        s_cbranch_scc1 .LBB0_1
+    """)
+    assert [l for _, l, _ in check_isa.scan_function(loop)] == ["v_accvgpr_read_b32 v7, a3"]
+
+
+@pytest.mark.skipif(os.environ.get("DMATH_CHECK_ISA") != "1", reason="takes five minutes of compilation: set DMATH_CHECK_ISA=1")
+def test_fp16_kernels_have_no_early_accumulator_reads():
+    report, looked = check_isa.check()
+    assert looked >= 24
+    assert report == {}
