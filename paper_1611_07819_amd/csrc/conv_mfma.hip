@@ -146,37 +146,68 @@ template <class TC, class A> __device__ __forceinline__ TC to_out(A v) { return 
 // src rows: image n -> [ch][hw] elements (NCHW inside a row).  dst: [n][HP][WP][chd] with pixel
 // (y, x) of the image placed at (ph + y*sy, pw + x*sx); sy = sx = 1 except for the data gradient
 // of a strided convolution, which reads dY spread out with zeros between its pixels.  One
-// workgroup of 1024 threads moves 64 channels of one image (of up to tcl_pixels<T>() pixels of
-// it: blockIdx.y) through LDS: fully coalesced 16-byte reads of the 64 planes, 16-byte writes
-// of consecutive channels per lane.  The plane stride (pixels + pad) keeps the transposed reads
-// spread over the banks.  dst has chd >= ch channels per pixel (a multiple of 64); channels
-// ch .. chd-1 are written as zeros.
+// workgroup of 1024 threads moves 64 channels of `chunk` pixels of one image (blockIdx.y: which
+// chunk) through LDS: fully coalesced 16-byte reads of the 64 planes, 16-byte writes of
+// consecutive channels per lane.  dst has chd >= ch channels per pixel (a multiple of 64);
+// channels ch .. chd-1 are written as zeros.
+// The chunk is chosen (tcl_chunk) so that two or three workgroups share a CU: a workgroup reads
+// all its planes, waits, and then writes, so a lone workgroup per CU leaves the memory system idle
+// in one direction at a time (one chunk of 784 pixels per workgroup: 11.9 us for the 55 MB of
+// configuration 5; two chunks of 392: see the profile summary).
+// LDS banks (64 of 4 bytes): the plane stride (pixels + pad) is 8 bytes mod 32 for 16-bit and 32-bit
+// elements.  Writes: a lane's 16 bytes go out as two 8-byte halves, lanes 16 apart hit the same
+// banks, so every other group of 16 lanes writes its upper half first.  Reads: a wavefront takes
+// 16 (fp16) or 8 (fp32) pixels x half of the channel groups at a time, which puts the channel
+// groups 8 rows = 64 bytes apart on four (eight) different bank groups and the pixels of a group
+// side by side (with all eight channel groups of 8 pixels in one instruction, groups 0 and 4 met on
+// the same banks: the counters showed two turns per access).
 constexpr int kTclThreads = 1024;
-template <class T> constexpr int tcl_pixels() { return 2048 / sizeof(T); }  // 64 planes: 128 KiB of LDS
+template <class T> constexpr int tcl_max_pixels() { return 2048 / sizeof(T); }  // 64 planes: 128 KiB of LDS
 template <class T> __host__ __device__ inline int tcl_stride(int px)
 {
     // 16-bit: stride = 4 mod 16 elements; 32-bit: stride = 2 mod 8
     return sizeof(T) == 2 ? px + ((20 - px % 16) % 16) : px + ((10 - px % 8) % 8);
 }
-
-// VB: bytes per global read: 16 where a plane is a multiple of 16 bytes, 8 where of 8, else one element.
-template <class T, int VB>
-__global__ __launch_bounds__(kTclThreads) void to_channels_last_kernel(const void* const* src_rows, int ch,
-                                                                       int chd, int h, int w, int ph, int pw,
-                                                                       int sy, int sx, int hp, int wp, T* dst)
+// pixels per workgroup: whole planes where they are small or the grid fills the chip anyway,
+// otherwise the fewest parts (of a multiple of 16 pixels) that give every CU two workgroups
+template <class T> inline int tcl_chunk(int groups, int hw)
 {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+    int parts = (hw + tcl_max_pixels<T>() - 1) / tcl_max_pixels<T>();
+    while (groups * parts < 512 && hw / (parts + 1) >= 128) ++parts;
+    const int chunk = ((hw + parts - 1) / parts + 15) / 16 * 16;
+    return std::min(chunk, tcl_max_pixels<T>());
+}
+
+// One NCHW -> channels-last rewrite: what a workgroup needs to know.
+struct TclJob {
+    const void* const* src_rows;
+    void* dst;
+    int ch, chd, h, w, ph, pw, sy, sx, hp, wp;
+    int chunk;   // pixels per workgroup
+    int vb;      // bytes per global read: 16 where a plane is a multiple of 16 bytes, 8 where of 8, else one element
+    int groups;  // images x groups of 64 channels
+    int blocks;  // groups x chunks per plane (0: no such job)
+};
+
+// group: which (image, 64 channels); part: which chunk of the plane.  Every thread of the workgroup calls it.
+template <class T, int VB> __device__ __forceinline__ void tcl_body(const TclJob& j, int group, int part, char* smem)
+{
+    const void* const* src_rows = j.src_rows;
+    T* const dst = static_cast<T*>(j.dst);
+    const int ch = j.ch, chd = j.chd, h = j.h, w = j.w, ph = j.ph, pw = j.pw, sy = j.sy, sx = j.sx, hp = j.hp,
+              wp = j.wp, chunk = j.chunk;
     T* planes = reinterpret_cast<T*>(smem);  // [64][stride]
-    constexpr int VEC = VB / (int)sizeof(T), kPixels = tcl_pixels<T>();
+    constexpr int VEC = VB / (int)sizeof(T);
     constexpr int kPerLane = 16 / (int)sizeof(T), kLanesPerPixel = 64 / kPerLane;  // 16-byte writes
     const int hw = h * w;
-    const int p0 = blockIdx.y * kPixels, pixels = min(kPixels, hw - p0);  // this workgroup's pixels
-    const int stride = tcl_stride<T>(min(kPixels, hw));
+    const int p0 = part * chunk, pixels = min(chunk, hw - p0);  // this workgroup's pixels
+    const int stride = tcl_stride<T>(min(chunk, hw));
     const int chunks_c = chd / 64;
-    const int n = blockIdx.x / chunks_c, c0 = (blockIdx.x % chunks_c) * 64;
+    const int n = group / chunks_c, c0 = (group % chunks_c) * 64;
     const int planes_here = min(64, ch - c0);  // the last group of a padded channel count is short
     const T* src = static_cast<const T*>(src_rows[n]) + (int64_t)c0 * hw + p0;
     const int vec_per_plane = pixels / VEC;
+    const int swap = (threadIdx.x >> 4) & 1;  // which half of its 16 bytes this lane writes first
     for (int e = threadIdx.x; e < 64 * vec_per_plane; e += kTclThreads) {
         const int c = e / vec_per_plane, v = e - c * vec_per_plane;
         // planes past the last channel read plane 0 instead (unconditional loads) and store zeros
@@ -191,8 +222,9 @@ __global__ __launch_bounds__(kTclThreads) void to_channels_last_kernel(const voi
         const uint32_t keep = real ? ~0u : 0u;
         if (VB == 16) {
             const v4u d = *reinterpret_cast<const v4u*>(from);
-            q[0] = v2u{d[0] & keep, d[1] & keep};
-            q[1] = v2u{d[2] & keep, d[3] & keep};
+            const v2u lo = v2u{d[0] & keep, d[1] & keep}, hi = v2u{d[2] & keep, d[3] & keep};
+            q[swap] = swap ? hi : lo;
+            q[swap ^ 1] = swap ? lo : hi;
         } else {
             const v2u d = *reinterpret_cast<const v2u*>(from);
             q[0] = v2u{d[0] & keep, d[1] & keep};
@@ -201,30 +233,19 @@ __global__ __launch_bounds__(kTclThreads) void to_channels_last_kernel(const voi
     __syncthreads();
     T* out = dst + ((int64_t)n * hp * wp) * chd + c0;
     typedef T vout __attribute__((ext_vector_type(kPerLane)));
-    for (int e = threadIdx.x; e < pixels * kLanesPerPixel; e += kTclThreads) {
-        const int pix = e / kLanesPerPixel, cg = e % kLanesPerPixel;
+    // a wavefront's 64 lanes: G channel groups x 64/G pixels (G: all groups for 64-bit elements, half otherwise)
+    constexpr int G = sizeof(T) == 8 ? kLanesPerPixel : kLanesPerPixel / 2, H = kLanesPerPixel / G, PW = 64 / G;
+    const int items = (pixels + PW - 1) / PW * H * 64;
+    for (int e = threadIdx.x; e < items; e += kTclThreads) {
+        const int wi = e >> 6, l = e & 63;
+        const int pix = (wi / H) * PW + l / G, cg = (wi % H) * G + l % G;
+        if (pix >= pixels) continue;
         const int y = (p0 + pix) / w, x = (p0 + pix) - y * w;
         vout v;
 #pragma unroll
         for (int i = 0; i < kPerLane; ++i) v[i] = planes[(cg * kPerLane + i) * stride + pix];
         *reinterpret_cast<vout*>(out + ((int64_t)(y * sy + ph) * wp + (x * sx + pw)) * chd + cg * kPerLane) = v;
     }
-}
-
-// NCHW rows -> zero-bordered channels-last copy, on stream st.
-template <class T>
-static void to_channels_last(const void* const* src_rows, int n, int ch, int chd, int h, int w, int ph, int pw,
-                             int sy, int sx, int hp, int wp, T* dst, hipStream_t st)
-{
-    const int hw = h * w, lds = 64 * tcl_stride<T>(std::min(tcl_pixels<T>(), hw)) * (int)sizeof(T);
-    const dim3 grid(n * (chd / 64), (hw + tcl_pixels<T>() - 1) / tcl_pixels<T>());
-    const int plane_bytes = hw * (int)sizeof(T);
-    if (plane_bytes % 16 == 0)
-        to_channels_last_kernel<T, 16><<<grid, kTclThreads, lds, st>>>(src_rows, ch, chd, h, w, ph, pw, sy, sx, hp, wp, dst);
-    else if (plane_bytes % 8 == 0)
-        to_channels_last_kernel<T, 8><<<grid, kTclThreads, lds, st>>>(src_rows, ch, chd, h, w, ph, pw, sy, sx, hp, wp, dst);
-    else
-        to_channels_last_kernel<T, sizeof(T)><<<grid, kTclThreads, lds, st>>>(src_rows, ch, chd, h, w, ph, pw, sy, sx, hp, wp, dst);
 }
 
 // F[k][c][r][s] -> Fp[k][(r,s,cp)], cp >= c channels per tap (the pad channels written as zeros)
@@ -306,6 +327,154 @@ __global__ __launch_bounds__(256) void filter_to_rsk_rotated_tiled_kernel(const 
         const int cc = cidx / rs, q = cidx - cc * rs;
         gp[((int64_t)cc * rs + (rs - 1 - q)) * kp + k0 + row] = tile[row][col];
     }
+}
+
+// The bodies of filter_to_rsc_tiled_kernel and filter_to_rsk_rotated_tiled_kernel for one quarter
+// (256 threads, t = its thread index) of a 1024-thread workgroup; every thread of the workgroup
+// calls them (`active`: this quarter has work), the barrier inside is the workgroup's.
+template <class T>
+__device__ __forceinline__ void filter_rsc_quarter(const void* const* f_rows, int c, int cp, int rs, T* fp, int kk,
+                                                   int c0, T* tile, int t, bool active)
+{
+    const int rsp = rs | 1, nch = min(64, c - c0);
+    if (active && nch > 0) {
+        const T* src = static_cast<const T*>(f_rows[kk]) + (int64_t)c0 * rs;
+        for (int i = t; i < nch * rs; i += 256) {
+            const int ch = i / rs;
+            tile[ch * rsp + (i - ch * rs)] = src[i];
+        }
+    }
+    __syncthreads();
+    if (!active) return;
+    T* dst = fp + (int64_t)kk * rs * cp + c0;
+    for (int i = t; i < 64 * rs; i += 256) {
+        const int q = i >> 6, ch = i & 63;
+        dst[(int64_t)q * cp + ch] = ch < nch ? tile[ch * rsp + q] : (T)0.f;
+    }
+}
+
+template <class T>
+__device__ __forceinline__ void filter_rotated_quarter(const void* const* f_rows, int c, int rs, int k, int kp, T* gp,
+                                                       int col0, int k0, T* tile /* [64][65] */, int t, bool active)
+{
+    const int crs = c * rs;
+    if (active) {
+        const int col = t & 63, row0 = t >> 6;
+        const bool col_ok = col0 + col < crs;
+        const T* src[16];
+        T v[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) src[j] = static_cast<const T*>(f_rows[min(k0 + row0 + 4 * j, k - 1)]);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) v[j] = col_ok ? src[j][col0 + col] : (T)0.f;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) tile[(row0 + 4 * j) * 65 + col] = k0 + row0 + 4 * j < k ? v[j] : (T)0.f;
+    }
+    __syncthreads();
+    if (!active) return;
+    for (int i = t; i < 64 * 64; i += 256) {
+        const int col = i >> 6, row = i & 63, cidx = col0 + col;
+        if (cidx >= crs) continue;
+        const int cc = cidx / rs, q = cidx - cc * rs;
+        gp[((int64_t)cc * rs + (rs - 1 - q)) * kp + k0 + row] = tile[row * 65 + col];
+    }
+}
+
+// A filter permutation that rides along with the rewrites of the activations.
+struct FilterJob {
+    int kind;  // 0: none, 1: F -> Fp[k][(r,s,cp)], 2: F -> Gp[c][(r',s',kp)]
+    const void* const* f_rows;
+    void* out;
+    int c, cp, rs, k, kp;
+    int tiles_x;  // kind 1: groups of 64 channels; kind 2: tiles of 64 columns of [k][c*rs]
+    int tiles;    // kind 1: tiles_x x filters; kind 2: tiles_x x tiles of 64 filters
+    int blocks;   // workgroups: four tiles each
+};
+struct RelayoutJobs {
+    TclJob a, b;
+    FilterJob f;
+};
+
+// Every re-layout a convolution call needs, in one launch: the short filter permutation no longer
+// waits for (or delays) the rewrites of the activations behind a launch boundary of its own.
+// Workgroups [0, f.blocks) permute the filter, four tiles each (one per 256 threads); the next
+// a.blocks rewrite tensor a, the last b.blocks tensor b.
+template <class T> __global__ __launch_bounds__(kTclThreads) void relayout_kernel(RelayoutJobs r)
+{
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    int bid = blockIdx.x;
+    if (bid < r.f.blocks) {
+        const int quarter = threadIdx.x >> 8, t = threadIdx.x & 255, tile_idx = bid * 4 + quarter;
+        const bool active = tile_idx < r.f.tiles;
+        const int tx = active ? tile_idx % r.f.tiles_x : 0, ty = active ? tile_idx / r.f.tiles_x : 0;
+        if (r.f.kind == 1) {
+            T* tile = reinterpret_cast<T*>(smem) + quarter * 64 * (r.f.rs | 1);
+            filter_rsc_quarter<T>(r.f.f_rows, r.f.c, r.f.cp, r.f.rs, static_cast<T*>(r.f.out), ty, tx * 64, tile, t, active);
+        } else {
+            T* tile = reinterpret_cast<T*>(smem) + quarter * 64 * 65;
+            filter_rotated_quarter<T>(r.f.f_rows, r.f.c, r.f.rs, r.f.k, r.f.kp, static_cast<T*>(r.f.out), tx * 64, ty * 64,
+                                      tile, t, active);
+        }
+        return;
+    }
+    bid -= r.f.blocks;
+    const bool first = bid < r.a.blocks;
+    const TclJob& j = first ? r.a : r.b;
+    if (!first) bid -= r.a.blocks;
+    const int group = bid % j.groups, part = bid / j.groups;
+    if (j.vb == 16)
+        tcl_body<T, 16>(j, group, part, smem);
+    else if (j.vb == 8)
+        tcl_body<T, 8>(j, group, part, smem);
+    else
+        tcl_body<T, sizeof(T)>(j, group, part, smem);
+}
+
+// NCHW rows -> zero-bordered channels-last copy: the job description and the LDS it needs.
+template <class T>
+static TclJob tcl_job(const void* const* src_rows, int n, int ch, int chd, int h, int w, int ph, int pw, int sy,
+                      int sx, int hp, int wp, T* dst, int* lds)
+{
+    TclJob j{};
+    const int hw = h * w, plane_bytes = hw * (int)sizeof(T);
+    j.src_rows = src_rows; j.dst = dst;
+    j.ch = ch; j.chd = chd; j.h = h; j.w = w; j.ph = ph; j.pw = pw; j.sy = sy; j.sx = sx; j.hp = hp; j.wp = wp;
+    j.groups = n * (chd / 64);
+    j.chunk = tcl_chunk<T>(j.groups, hw);
+    j.vb = plane_bytes % 16 == 0 ? 16 : plane_bytes % 8 == 0 ? 8 : (int)sizeof(T);
+    j.blocks = j.groups * ((hw + j.chunk - 1) / j.chunk);
+    *lds = std::max(*lds, 64 * tcl_stride<T>(std::min(j.chunk, hw)) * (int)sizeof(T));
+    return j;
+}
+// The filter permutation as a job of the same launch; false: too large for that (the caller
+// launches the kernel of its own).
+template <class T>
+static bool filter_job(int kind, const void* const* f_rows, int c, int cp, int rs, int k, int kp, T* out,
+                       FilterJob* f, int* lds)
+{
+    const size_t tile_bytes = (kind == 1 ? (size_t)64 * (rs | 1) : (size_t)64 * 65) * sizeof(T);
+    if (4 * tile_bytes > 64 * 1024) return false;
+    f->kind = kind; f->f_rows = f_rows; f->out = out;
+    f->c = c; f->cp = cp; f->rs = rs; f->k = k; f->kp = kp;
+    f->tiles_x = kind == 1 ? cp / 64 : (c * rs + 63) / 64;
+    f->tiles = f->tiles_x * (kind == 1 ? k : kp / 64);
+    f->blocks = (f->tiles + 3) / 4;
+    *lds = std::max(*lds, (int)(4 * tile_bytes));
+    return true;
+}
+template <class T> static hipError_t launch_relayout(const RelayoutJobs& r, int lds, hipStream_t st)
+{
+    const int blocks = r.f.blocks + r.a.blocks + r.b.blocks;
+    if (blocks == 0) return hipSuccess;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(relayout_kernel<T>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    relayout_kernel<T><<<blocks, kTclThreads, lds, st>>>(r);
+    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1323,14 +1492,8 @@ hipError_t launch_typed(const ConvPlan& plan, int mode, double alpha, double bet
     if (!xp || !p.sink || (mode != CONV_BWD_FILTER && !fp) || (mode == CONV_BWD_FILTER && (!yt || !p.ws)))
         return hipErrorInvalidValue;  // the plan was not made for this path
 
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = set_lds(to_channels_last_kernel<T, 16>, 150 * 1024);
-        if (e == hipSuccess) e = set_lds(to_channels_last_kernel<T, 8>, 150 * 1024);
-        if (e == hipSuccess) e = set_lds(to_channels_last_kernel<T, sizeof(T)>, 150 * 1024);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    RelayoutJobs jobs{};
+    int lds = 0;
     if (mode == CONV_BWD_DATA) {
         // forward convolution (stride 1) over dY with its pixels spread out by the stride: input
         // channels k, padding r-1-pad in front, rotated filter, output channels c, output
@@ -1346,21 +1509,31 @@ hipError_t launch_typed(const ConvPlan& plan, int mode, double alpha, double bet
         q.wp = g.w + g.s - 1;
         q.y_rows = t.x_rows;
         if (rewrite & REWRITE_X)
-            to_channels_last<T>(t.y_rows, g.n, g.k, kp, g.oh, g.ow, pph, ppw, g.stride_h, g.stride_w, q.hp, q.wp, xp, st);
+            jobs.a = tcl_job<T>(t.y_rows, g.n, g.k, kp, g.oh, g.ow, pph, ppw, g.stride_h, g.stride_w, q.hp, q.wp, xp, &lds);
+        bool filter_apart = false;
         if (rewrite & REWRITE_F)
+            filter_apart = !filter_job<T>(2, t.f_rows, g.c, cp, g.r * g.s, g.k, kp, fp, &jobs.f, &lds);
+        if (hipError_t e = launch_relayout<T>(jobs, lds, st); e != hipSuccess) return e;
+        if (filter_apart)
             filter_to_rsk_rotated_tiled_kernel<T>
                 <<<dim3((g.c * g.r * g.s + 63) / 64, kp / 64), 256, 0, st>>>(t.f_rows, g.c, g.r * g.s, g.k, kp, fp);
         return launch_fwd(q, in, plan.tile_m, plan.tile_n, plan.out_dtype, alpha, beta, st);
     }
     // activations -> zero-bordered channels-last copy (borders were zeroed when the copy was allocated)
     if (rewrite & REWRITE_X)
-        to_channels_last<T>(t.x_rows, g.n, g.c, cp, g.h, g.w, g.pad_h, g.pad_w, 1, 1, p.hp, p.wp, xp, st);
+        jobs.a = tcl_job<T>(t.x_rows, g.n, g.c, cp, g.h, g.w, g.pad_h, g.pad_w, 1, 1, p.hp, p.wp, xp, &lds);
     if (mode == CONV_FWD) {
-        if (rewrite & REWRITE_F) filter_to_rsc<T>(t.f_rows, g.c, cp, g.r * g.s, g.k, fp, st);
+        bool filter_apart = false;
+        if (rewrite & REWRITE_F)
+            filter_apart = !filter_job<T>(1, t.f_rows, g.c, cp, g.r * g.s, g.k, kp, fp, &jobs.f, &lds);
+        if (hipError_t e = launch_relayout<T>(jobs, lds, st); e != hipSuccess) return e;
+        if (filter_apart) filter_to_rsc<T>(t.f_rows, g.c, cp, g.r * g.s, g.k, fp, st);
         return launch_fwd(p, in, plan.tile_m, plan.tile_n, plan.out_dtype, alpha, beta, st);
     }
     // weight gradient: dY -> channels-last [m][k], split GEMM, fixed-order reduction
-    if (rewrite & REWRITE_Y) to_channels_last<T>(t.y_rows, g.n, g.k, kp, g.oh, g.ow, 0, 0, 1, 1, g.oh, g.ow, yt, st);
+    if (rewrite & REWRITE_Y)
+        jobs.b = tcl_job<T>(t.y_rows, g.n, g.k, kp, g.oh, g.ow, 0, 0, 1, 1, g.oh, g.ow, yt, &lds);
+    if (hipError_t e = launch_relayout<T>(jobs, lds, st); e != hipSuccess) return e;
     p.ktiles = (int)wgrad_ktiles(g, in);
     p.ktiles_per_split = (p.ktiles + t.split_k - 1) / t.split_k;
     if (!wgrad_split_ok(p.ktiles, t.split_k)) return hipErrorInvalidValue;  // a part without pixels
