@@ -1451,7 +1451,8 @@ hipError_t launch_wgrad(const FastConv& p, dmath_dtype_t in, int bm, int bn, int
     }
     // The weight gradient stays on 32x32x16 fragments: with its walk's many per-lane offsets the
     // compiler renames accumulators between the iterations of the 16x16x32 pipeline and reads them
-    // before the matrix instructions written as assembly have finished (found by check_isa.py).
+    // before the matrix instructions written as assembly have finished (found by check_isa.py);
+    // with the matrix cores drained at those points it was correct and 5-7 % slower than this.
     if (bm == 256 && bn == 128) return launch_wgrad_shape<PipeF16, 256, 128>(p, tiles, st);
     if (bm == 128 && bn == 128) return launch_wgrad_shape<PipeF16, 128, 128>(p, tiles, st);
     if (bm == 64 && bn == 128) return launch_wgrad_shape<PipeF16, 64, 128>(p, tiles, st);
