@@ -7,7 +7,12 @@ renames accumulators between differently scheduled parts of a k-loop it may ther
 copy (v_accvgpr_mov / v_accvgpr_read, or a store straight from an accumulator register) right
 behind the matrix instruction that produces the value, and the copy reads the old contents.  The
 pipeline drains the matrix cores (two s_nop 15) wherever it hands the accumulators to other code;
-this check finds the copies that end up in front of such a drain.
+this check finds the copies that end up in front of such a drain.  The other direction: a matrix
+instruction must not read an accumulator register in the cycle after a vector instruction wrote it;
+the assembly statement carries a wait state (s_nop 0) for that except in the steady state of the
+k-loop, where the compiler is expected to put no copy in front of it -- the check reports any
+v_accvgpr_write / v_accvgpr_mov into a register that the very next instruction, a matrix
+instruction, accumulates into.
 
     python -m paper_1611_07819_amd.check_isa            # compiles gemm_f16.hip and conv_mfma.hip
 
@@ -59,18 +64,25 @@ def scan_function(lines):
     def walk(start, stop, written, drained_at, base):
         # written: register -> position of the matrix instruction that wrote it (same scale as base + i)
         snapshots = []
+        prev = ""
         for i in range(start, stop):
             l, pos = lines[i], base + (i - start)
             if l.endswith(":"):
                 continue
             if l.startswith("s_nop 15"):
                 drained_at = pos
+                prev = l
                 continue
             if l.startswith(MFMA):
                 dst = re.match(MFMA + r"\s+(a\[\d+:\d+\])", l)
-                for r in _regs(dst.group(1)):
+                acc = _regs(dst.group(1))
+                if re.match(r"v_accvgpr_(write|mov)_b32\s+a(\d+)", prev) and int(re.match(r"\S+\s+a(\d+)", prev).group(1)) in acc:
+                    found.append((i, prev + "  ->  " + l, 1))
+                for r in acc:
                     written[r] = pos
+                prev = l
                 continue
+            prev = l
             if l.startswith("v_mfma"):
                 continue
             ops = l.split(None, 1)[1] if " " in l else ""

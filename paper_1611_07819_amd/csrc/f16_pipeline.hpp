@@ -576,7 +576,11 @@ __device__ __forceinline__ void run16(Walk& walk, int n_ktiles, char* smem,
 #pragma unroll
             for (int m = 0; m < kMfma; ++m) {
                 const int i = half * (MT / 2) + m / NTL, j = m % NTL;
-                mfma_f16_16x16x32(acc[i][j], fa[cur][i], fb[cur][j]);
+                // the wait state in front of the instruction is needed where the compiler copies
+                // accumulators: between the differently scheduled iterations that run on a run-time
+                // stage, not in the steady state (4-5 % of its cycles; check_isa.py looks for a
+                // copy directly in front of an instruction without one)
+                mfma_f16_16x16x32<std::is_same<decltype(stage_v), int>::value>(acc[i][j], fa[cur][i], fb[cur][j]);
                 __builtin_amdgcn_sched_barrier(0);
                 // reads m*r_count/kMfma .. (m+1)*r_count/kMfma of the phase's share go into this slot
 #pragma unroll

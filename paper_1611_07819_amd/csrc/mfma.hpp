@@ -50,9 +50,14 @@ __device__ __forceinline__ v16f mfma_f16_32x32x16(v8h a, v8h b, v16f c)
 //     state in front, inside the statement, where nothing can be scheduled between;
 //   - after: code that reads an accumulator written this way has to leave the matrix pipeline
 //     time to drain first (mfma_drain() + pin()).
-__device__ __forceinline__ void mfma_f16_16x16x32(v4f& c, v8h a, v8h b)
+// WAIT = false leaves the wait state out: for code in which the compiler has been shown to put
+// no copy in front of the statement (check_isa.py looks for exactly that).
+template <bool WAIT = true> __device__ __forceinline__ void mfma_f16_16x16x32(v4f& c, v8h a, v8h b)
 {
-    asm volatile("s_nop 0\n\tv_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+    if (WAIT)
+        asm volatile("s_nop 0\n\tv_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+    else
+        asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
 }
 // More wait states than the longest matrix instruction needs before its result may be read.
 // Volatile statements keep their order, so passing every accumulator through pin() after

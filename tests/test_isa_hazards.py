@@ -30,6 +30,18 @@ def test_scanner_flags_an_early_copy_and_accepts_a_drained_one():
     assert len(check_isa.scan_function(store)) == 1
 
 
+def test_scanner_flags_a_copy_directly_in_front_of_a_matrix_instruction():
+    bare = _lines("""
+        v_accvgpr_mov_b32 a3, a67
+        v_mfma_f32_16x16x32_f16 a[0:3], v[2:5], v[38:41], a[0:3]
+    """)
+    assert len(check_isa.scan_function(bare)) == 1
+    waited = [bare[0], "s_nop 0", bare[1]]
+    assert check_isa.scan_function(waited) == []
+    elsewhere = ["v_accvgpr_mov_b32 a9, a67", bare[1]]
+    assert check_isa.scan_function(elsewhere) == []
+
+
 def test_scanner_follows_a_backward_branch():
     loop = _lines("""
         .LBB0_1:
