@@ -28,10 +28,16 @@ MEASURED_TRAFFIC_BYTES = 585430504
 def cpu_model():
     """Model string of the host CPU the oracle is timed on."""
     try:
+        seen = {}
         with open("/proc/cpuinfo") as f:
             for line in f:
-                if line.lower().startswith("model name"):
-                    return line.split(":", 1)[1].strip()
+                key, _, val = line.partition(":")
+                key = key.strip().lower()
+                if key in ("model name", "cpu family", "model") and key not in seen:
+                    seen[key] = val.strip()
+        if "model name" in seen:  # virtual machines report a generic name: family / model tell the part
+            return "%s (family %s, model %s, %d logical CPUs)" % (
+                seen["model name"], seen.get("cpu family", "?"), seen.get("model", "?"), os.cpu_count() or 0)
     except OSError:
         pass
     import platform

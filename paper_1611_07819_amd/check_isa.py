@@ -1,29 +1,32 @@
-"""Checks the compiler's output for this library's fp16 kernels against one hazard that the
-compiler cannot see: the 16x16x32 matrix instructions of the fp16 pipeline are written as inline
-assembly (their accumulators tied in place), so the compiler does not know that their results
-take several cycles to land, and the hardware does not interlock a vector instruction that reads
-an accumulator register against a matrix instruction still writing it.  Where the compiler
-renames accumulators between differently scheduled parts of a k-loop it may therefore place a
-copy (v_accvgpr_mov / v_accvgpr_read, or a store straight from an accumulator register) right
-behind the matrix instruction that produces the value, and the copy reads the old contents.  The
-pipeline drains the matrix cores (two s_nop 15) wherever it hands the accumulators to other code;
-this check finds the copies that end up in front of such a drain.  The other direction: a matrix
-instruction must not read an accumulator register in the cycle after a vector instruction wrote it;
-the assembly statement carries a wait state (s_nop 0) for that except in the steady state of the
-k-loop, where the compiler is expected to put no copy in front of it -- the check reports any
-v_accvgpr_write / v_accvgpr_mov into a register that the very next instruction, a matrix
-instruction, accumulates into.
+"""Checks the compiler's output for this library's pipelined fp16 and fp64 kernels against a
+hazard that the compiler cannot see: their matrix instructions (v_mfma_f32_16x16x32_f16,
+v_mfma_f64_16x16x4_f64) are written as inline assembly with the accumulators tied in place, so
+the compiler does not know that their results take 16 / 64 cycles to land, and the hardware does
+not interlock a vector instruction that reads an accumulator register against a matrix
+instruction still writing it.  Where the compiler renames accumulators between differently
+scheduled parts of a k-loop it may therefore place a copy (v_accvgpr_mov / v_accvgpr_read, or a
+store straight from an accumulator register) right behind the matrix instruction that produces
+the value, and the copy reads the old contents.  The pipelines drain the matrix cores (a run of
+s_nop 15) wherever they hand the accumulators to other code; this check finds the copies that
+end up in front of such a drain.  The other direction: a matrix instruction must not read an
+accumulator register in the cycle after a vector instruction wrote it; the assembly statement
+carries a wait state (s_nop 0) for that except in the steady state of the fp16 k-loop, where the
+compiler is expected to put no copy in front of it -- the check reports any v_accvgpr_write /
+v_accvgpr_mov into a register that the very next instruction, a matrix instruction, accumulates
+into.  The fp64 pipelines go further and keep their accumulators in fixed registers that the
+compiler knows nothing about (mfma.hpp): in a kernel with fp64 matrix instructions every
+instruction that names an accumulation register must be one of the three forms the pipeline
+writes itself (the matrix instruction, v_accvgpr_write_b32 aN, 0 and v_accvgpr_read_b32 vM, aN).
 
-    python -m paper_1611_07819_amd.check_isa            # compiles gemm_f16.hip and conv_mfma.hip
+    python -m paper_1611_07819_amd.check_isa     # compiles gemm_f16.hip, gemm_f64.hip, conv_mfma.hip
 
-For every kernel that contains the inline-assembly instruction it walks the assembly in program
-order (and once more across every backward branch, with the state at the branch) and reports any
-instruction other than a matrix instruction that names an accumulator register written fewer
-than WINDOW instructions earlier with no drain in between.  A 16x16x32 instruction occupies the
-matrix core for 16 cycles and a wavefront issues at most one instruction per cycle (a vector or
-matrix instruction every four), so WINDOW = 16 instructions is a safe distance.
+For every kernel that contains such an instruction it walks the assembly in program order (and
+once more across every backward branch, with the state at the branch), counting one cycle per
+instruction -- a wavefront issues no faster -- and N+1 for s_nop N, and reports any instruction
+other than a matrix instruction that names an accumulator register fewer than NEED cycles (the
+instruction's occupancy of the matrix core plus four) after the matrix instruction that wrote it.
 
-Compiling the two sources to assembly takes about five minutes, so the test that runs this check
+Compiling the sources to assembly takes several minutes, so the test that runs this check
 (tests/test_isa_hazards.py) only does so when DMATH_CHECK_ISA=1 is set; assembly files made
 before can be given as arguments instead."""
 import os
@@ -34,8 +37,8 @@ import tempfile
 
 from . import build as _build
 
-WINDOW = 16
-MFMA = "v_mfma_f32_16x16x32_f16"
+NEED = {"v_mfma_f32_16x16x32_f16": 20, "v_mfma_f64_16x16x4_f64": 68}
+LOOKAHEAD = 96  # instructions re-walked from the top of a loop with the state at its backward branch
 
 
 def compile_to_asm(src: str, out_dir: str) -> str:
@@ -57,48 +60,52 @@ def _regs(text: str):
 
 
 def scan_function(lines):
-    """lines: the instructions and labels of one kernel.  Returns [(line index, text, distance)]."""
+    """lines: the instructions and labels of one kernel.  Returns [(line index, text, cycles)]."""
     label_at = {l[:-1]: i for i, l in enumerate(lines) if l.endswith(":")}
     found = []
+    if any(l.startswith("v_mfma_f64_16x16x4_f64") for l in lines):
+        own = re.compile(r"v_mfma_f64_16x16x4_f64 |v_accvgpr_write_b32 a\d+, 0$|v_accvgpr_read_b32 v\d+, a\d+$")
+        for i, l in enumerate(lines):
+            ops = l.split(None, 1)[1] if " " in l and not l.endswith(":") else ""
+            if _regs(ops) and not own.match(l):
+                found.append((i, l + "   (accumulation register used by the compiler)", 0))
 
-    def walk(start, stop, written, drained_at, base):
-        # written: register -> position of the matrix instruction that wrote it (same scale as base + i)
+    def walk(start, stop, written, clock):
+        # written: register -> (cycle at which the matrix instruction that wrote it issued, cycles it needs)
         snapshots = []
         prev = ""
         for i in range(start, stop):
-            l, pos = lines[i], base + (i - start)
+            l = lines[i]
             if l.endswith(":"):
                 continue
-            if l.startswith("s_nop 15"):
-                drained_at = pos
-                prev = l
-                continue
-            if l.startswith(MFMA):
-                dst = re.match(MFMA + r"\s+(a\[\d+:\d+\])", l)
-                acc = _regs(dst.group(1))
+            nop = re.match(r"s_nop\s+(\d+)", l)
+            clock += int(nop.group(1)) + 1 if nop else 1
+            name = l.split()[0]
+            if name in NEED:
+                acc = _regs(re.match(r"\S+\s+(a\[\d+:\d+\])", l).group(1))
                 if re.match(r"v_accvgpr_(write|mov)_b32\s+a(\d+)", prev) and int(re.match(r"\S+\s+a(\d+)", prev).group(1)) in acc:
                     found.append((i, prev + "  ->  " + l, 1))
                 for r in acc:
-                    written[r] = pos
+                    written[r] = (clock, NEED[name])
                 prev = l
                 continue
             prev = l
-            if l.startswith("v_mfma"):
+            if name.startswith("v_mfma"):
                 continue
             ops = l.split(None, 1)[1] if " " in l else ""
             for r in _regs(ops):
                 w = written.get(r)
-                if w is not None and pos - w < WINDOW and drained_at < w:
-                    found.append((i, l, pos - w))
+                if w is not None and clock - w[0] < w[1]:
+                    found.append((i, l, clock - w[0]))
                     break
             m = re.match(r"s_c?branch\S*\s+(\S+)", l)
             if m and m.group(1) in label_at and label_at[m.group(1)] <= i:
-                snapshots.append((label_at[m.group(1)], dict(written), drained_at, pos + 1))
+                snapshots.append((label_at[m.group(1)], dict(written), clock))
         return snapshots
 
-    for target, written, drained_at, pos in walk(0, len(lines), {}, -10 ** 9, 0):
+    for target, written, clock in walk(0, len(lines), {}, 0):
         # once more from the top of each loop, as the instructions that follow the backward branch
-        walk(target, min(len(lines), target + WINDOW + 8), written, drained_at, pos)
+        walk(target, min(len(lines), target + LOOKAHEAD), written, clock)
     return sorted(set(found))
 
 
@@ -108,7 +115,7 @@ def scan_file(path: str):
     text = open(path).read()
     report, looked = {}, 0
     for name, body in re.findall(r"^(_Z\S+):[^\n]*\n(.*?)s_endpgm", text, re.S | re.M):
-        if MFMA not in body:
+        if not any(name in body for name in NEED):
             continue
         looked += 1
         lines = [l.split(";")[0].strip() for l in body.split("\n")]
@@ -119,7 +126,7 @@ def scan_file(path: str):
     return report, looked
 
 
-def check(sources=("gemm_f16.hip", "conv_mfma.hip")):
+def check(sources=("gemm_f16.hip", "gemm_f64.hip", "conv_mfma.hip")):
     total, looked = {}, 0
     with tempfile.TemporaryDirectory() as tmp:
         for src in sources:
@@ -141,6 +148,6 @@ if __name__ == "__main__":
     for name, bad in rep.items():
         print(name)
         for i, l, d in bad[:8]:
-            print(f"    line {i}: {l}   ({d} instructions after the matrix instruction that writes it)")
+            print(f"    line {i}: {l}   ({d} cycles at most after the matrix instruction that writes it)")
     print(f"{looked} kernels with inline-assembly matrix instructions checked, {len(rep)} with early accumulator reads")
     sys.exit(1 if rep else 0)

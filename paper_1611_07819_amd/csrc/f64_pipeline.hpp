@@ -112,8 +112,9 @@ template <int BMN, bool KC> struct KCheck {
 // Runs the whole k-loop of one workgroup tile (wavefronts arranged WVM x 4/WVM).  `walk` must
 // provide
 //   const char *abase, *bbase;  uint32_t aoff[BM/32], boff[BN/32];  void advance();
-// describing the k-tile that is fetched next.  acc must be zeroed by the caller.
-template <int BM, int BN, int WVM, bool AKC, bool BKC, class Walk>
+// describing the k-tile that is fetched next.  acc receives the sums (what it holds on entry is ignored).
+// NS: stages of the LDS ring (k-tiles NS-1 ahead are in flight).
+template <int BM, int BN, int WVM, bool AKC, bool BKC, int NS = STAGES, class Walk>
 __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
                                     v4d (&acc)[BM / WVM / 16][BN / (4 / WVM) / 16])
 {
@@ -130,6 +131,11 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WVN, wn = wave % WVN, h = lane >> 4, l32 = lane & 15;
+
+    static_assert(MT * NTL * 8 <= 128, "accumulators in a0 .. a127");
+    acc_f64_begin();
+#pragma unroll
+    for (int idx = 0; idx < MT * NTL; ++idx) acc_f64_zero(idx);
 
     auto issue_one = [&](uint32_t sbase, const char* ab, const char* bb, int idx) {
         if (idx < TA::kInstr)
@@ -176,11 +182,13 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
                      (r - kUnitsA) % TB::kReadsPerFrag, fb[buf][(r - kUnitsA) / TB::kReadsPerFrag]);
     };
 
-    // One iteration.  HAS_NEXT: tile kt+1 exists; HAS_DMA: tile kt+2 exists and is fetched.
-    auto iteration = [&](int stage, auto has_next, auto has_dma) {
+    // One iteration.  HAS_NEXT: tile kt+1 exists; HAS_DMA: tile kt+NS-1 exists and is fetched.
+    // The accumulators live in fixed accumulation registers (mfma.hpp) from the first iteration to
+    // the read-out after the last.
+    auto iteration = [&](int stage, auto has_next, auto has_dma) __attribute__((always_inline)) {
         constexpr bool HAS_NEXT = decltype(has_next)::value, HAS_DMA = decltype(has_dma)::value;
-        const int stage1 = stage + 1 == STAGES ? 0 : stage + 1;   // tile kt+1
-        const int stage2 = stage == 0 ? STAGES - 1 : stage - 1;   // tile kt+2 (= stage of tile kt-1)
+        const int stage1 = stage + 1 == NS ? 0 : stage + 1;   // tile kt+1
+        const int stage2 = stage == 0 ? NS - 1 : stage - 1;   // tile kt+NS-1 (= stage of tile kt-1)
         const lds_char* sa = lds + stage * kStage;
         const lds_char* sa1 = lds + stage1 * kStage;
         const uint32_t dbase = lds0 + stage2 * kStage;
@@ -192,7 +200,7 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
             const int cur = u & 1;
             if (u == kGroups - 1 && HAS_NEXT) {
                 if (HAS_DMA)
-                    wait_vmcnt<kPerTile>();
+                    wait_vmcnt<(NS - 2) * kPerTile>();  // the tiles after the next one may still be on their way
                 else
                     wait_vmcnt<0>();
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -207,7 +215,7 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
 #pragma unroll
                     for (int j = 0; j < NTL; ++j) {
                         const int m = (s * MT + i) * NTL + j;
-                        acc[i][j] = mfma_f64_16x16x4(fa[cur][i][s], fb[cur][j][s], acc[i][j]);
+                        mfma_f64_fixed(i * NTL + j, fa[cur][i][s], fb[cur][j][s]);
                         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                         for (int q = 0; q < kPerSlot; ++q) {
@@ -230,14 +238,16 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
         if (HAS_DMA) walk.advance();
     };
 
-    // Prologue: tiles 0 and 1 in flight, tile 0 landed and visible, its first fragments read.
+    // Prologue: tiles 0 .. NS-2 in flight, tile 0 landed and visible, its first fragments read.
+    static_assert(NS >= 3 && (NS - 1) * kPerTile <= 63, "ring length (the counter of outstanding loads has 6 bits)");
     issue_all(0);
-    if (n_ktiles > 1) {
-        issue_all(1);
-        wait_vmcnt<kPerTile>();
-    } else {
+#pragma unroll
+    for (int t = 1; t <= NS - 2; ++t)
+        if (n_ktiles > t) issue_all(t);
+    if (n_ktiles > NS - 2)
+        wait_vmcnt<(NS - 2) * kPerTile>();
+    else
         wait_vmcnt<0>();
-    }
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 #pragma unroll
@@ -245,15 +255,21 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
 
     int stage = 0;
     int kt = 0;
-    for (; kt + 2 < n_ktiles; ++kt) {
+    for (; kt + NS - 1 < n_ktiles; ++kt) {
         iteration(stage, std::true_type{}, std::true_type{});
-        stage = stage + 1 == STAGES ? 0 : stage + 1;
+        stage = stage + 1 == NS ? 0 : stage + 1;
     }
-    if (kt + 1 < n_ktiles) {
+    for (; kt + 1 < n_ktiles; ++kt) {
         iteration(stage, std::true_type{}, std::false_type{});
-        stage = stage + 1 == STAGES ? 0 : stage + 1;
+        stage = stage + 1 == NS ? 0 : stage + 1;
     }
     iteration(stage, std::false_type{}, std::false_type{});
+    // hand the sums to the caller: the last matrix instruction has 64 cycles to go
+    mfma_drain_f64();
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NTL; ++j) acc[i][j] = acc_f64_read(i * NTL + j);
 }
 
 }  // namespace f64p

@@ -9,6 +9,8 @@
 // aligned panel origins and leading dimensions, blocks smaller than 4 GiB.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+
 #include <type_traits>
 
 #include "context.hpp"
@@ -60,7 +62,7 @@ template <int BM, int BN, bool AKC, bool BKC> struct PanelWalk {
 };
 
 // WVM x WVN = 4: arrangement of the wavefronts over the tile.
-template <int BM, int BN, int WVM, bool AKC, bool BKC>
+template <int BM, int BN, int WVM, bool AKC, bool BKC, int NS>
 __global__ __launch_bounds__(NT) void gemm_f64_kernel(GemmTables t, double alpha, double beta)
 {
     constexpr int WVN = 4 / WVM;
@@ -87,16 +89,16 @@ __global__ __launch_bounds__(NT) void gemm_f64_kernel(GemmTables t, double alpha
     int n_ktiles = 0;
     for (int s = ks; s < ks_end; ++s) n_ktiles += t.klen[s] / BK;
     PanelWalk<BM, BN, AKC, BKC> walk(t, tile, ks, ks_end, wave, lane);
-    run<BM, BN, WVM, AKC, BKC>(walk, n_ktiles, smem, acc);
+    run<BM, BN, WVM, AKC, BKC, NS>(walk, n_ktiles, smem, acc);
 
     store_tile<16, BM, BN, double>(t, tile, split, wm * WM, wn * WN, lane, acc, alpha, beta);
 }
 
-template <int BM, int BN, int WVM, bool AKC, bool BKC>
+template <int BM, int BN, int WVM, bool AKC, bool BKC, int NS>
 hipError_t launch_one(const GemmTables& t, double alpha, double beta, hipStream_t st)
 {
-    constexpr int lds_bytes = STAGES * (BM + BN) * BK * 8;
-    auto kern = gemm_f64_kernel<BM, BN, WVM, AKC, BKC>;
+    constexpr int lds_bytes = NS * (BM + BN) * BK * 8;
+    auto kern = gemm_f64_kernel<BM, BN, WVM, AKC, BKC, NS>;
     static bool configured = false;
     if (!configured) {  // more than 64 KiB of LDS has to be asked for once per kernel
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -108,14 +110,14 @@ hipError_t launch_one(const GemmTables& t, double alpha, double beta, hipStream_
     return hipGetLastError();
 }
 
-template <int BM, int BN, int WVM>
+template <int BM, int BN, int WVM, int NS = STAGES>
 hipError_t launch_shape(const GemmTables& t, double alpha, double beta, hipStream_t st)
 {
-    if (t.a_kcontig && t.b_kcontig) return launch_one<BM, BN, WVM, true, true>(t, alpha, beta, st);
-    if (!t.a_kcontig && t.b_kcontig) return launch_one<BM, BN, WVM, false, true>(t, alpha, beta, st);
+    if (t.a_kcontig && t.b_kcontig) return launch_one<BM, BN, WVM, true, true, NS>(t, alpha, beta, st);
+    if (!t.a_kcontig && t.b_kcontig) return launch_one<BM, BN, WVM, false, true, NS>(t, alpha, beta, st);
     if constexpr (64 % (BN / 2) == 0) {  // an m/n-major B tile must fill whole 1 KiB LDS segments
-        if (t.a_kcontig) return launch_one<BM, BN, WVM, true, false>(t, alpha, beta, st);
-        return launch_one<BM, BN, WVM, false, false>(t, alpha, beta, st);
+        if (t.a_kcontig) return launch_one<BM, BN, WVM, true, false, NS>(t, alpha, beta, st);
+        return launch_one<BM, BN, WVM, false, false, NS>(t, alpha, beta, st);
     }
     return hipErrorInvalidValue;
 }
@@ -125,6 +127,11 @@ hipError_t launch_shape(const GemmTables& t, double alpha, double beta, hipStrea
 hipError_t launch_gemm_f64(const GemmPlan& p, const GemmTables& t, double alpha, double beta, hipStream_t st)
 {
     const int bm = p.info.tile_m, bn = p.info.tile_n;
+    static const int ring = std::getenv("DMATH_F64_RING") ? std::atoi(std::getenv("DMATH_F64_RING")) : 0;
+    if (bm == 128 && bn == 128 && ring == 4) return launch_shape<128, 128, 2, 4>(t, alpha, beta, st);
+    if (bm == 128 && bn == 128 && ring == 5) return launch_shape<128, 128, 2, 5>(t, alpha, beta, st);
+    if (bm == 128 && bn == 64 && ring == 6) return launch_shape<128, 64, 2, 6>(t, alpha, beta, st);
+    if (bm == 128 && bn == 64 && ring == 4) return launch_shape<128, 64, 2, 4>(t, alpha, beta, st);
     if (bm == 128 && bn == 128) return launch_shape<128, 128, 2>(t, alpha, beta, st);
     if (bm == 128 && bn == 64) return launch_shape<128, 64, 2>(t, alpha, beta, st);
     if (bm == 64 && bn == 128) return launch_shape<64, 128, 2>(t, alpha, beta, st);

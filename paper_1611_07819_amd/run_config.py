@@ -1,7 +1,7 @@
 """Runs the calls of one benchmark configuration a few times and prints per-call timings.
 
     python -m paper_1611_07819_amd.run_config <1|2|3|3h|4|5|5h|skinny> [--iters N] [--only CALL]
-        [--copy-probe] [--vendor-reference]
+        [--copy-probe] [--vendor-reference] [--warm-ms T]
 
 Meant as the target of a profiler (`rocprofv3 ... -- python3 -m paper_1611_07819_amd.run_config 3`):
 inputs are the seeded synthetic recipes of ``synth.py``; nothing is checked here.
@@ -25,6 +25,9 @@ def main():
     ap.add_argument("--only", default=None)
     ap.add_argument("--copy-probe", action="store_true")
     ap.add_argument("--vendor-reference", action="store_true")
+    ap.add_argument("--warm-ms", type=float, default=20.0,
+                    help="warm-up per call: at least three calls, and on until this much wall time has passed "
+                         "(0 for counter runs, where every dispatch is slow)")
     ap.add_argument("--cycle-probe", action="store_true",
                     help="print the fp16 GEMM kernel's own cycle counts (needs the probe build of the "
                          "library: python -m paper_1611_07819_amd.build --probe, then DMATH_LIBRARY=...)")
@@ -79,12 +82,22 @@ def main():
         dev["dX"] = ctx.matrix(dev["X"].rows, dev["X"].cols, (1, 1), dev["Y"].dtype)
         calls.append(("conv_bwd_data", fl, "",
                       lambda: dm.conv_bwd_data(ctx, d, 1.0, dev["dY"], dev["F"], 0.0, dev["dX"])))
+    import time
+
+    def warm_up(fn):
+        """At least three calls, and on until --warm-ms have passed (the clocks settle)."""
+        t0, n = time.perf_counter(), 0
+        while n < 3 or time.perf_counter() - t0 < args.warm_ms * 1e-3:
+            fn()
+            n += 1
+            if n % 8 == 0:
+                torch.cuda.synchronize()
+        torch.cuda.synchronize()
+
     for name, fl, desc, f in calls:
         if args.only and args.only != name:
             continue
-        for _ in range(3):
-            f()
-        torch.cuda.synchronize()
+        warm_up(f)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(st)
         for _ in range(args.iters):
@@ -95,9 +108,7 @@ def main():
         print(f"{w.name} {name}: {desc}: {ms * 1e3:.1f} us  {fl / ms / 1e9:.1f} TFLOP/s", flush=True)
         if args.vendor_reference and name in vendor:
             vf = vendor[name]
-            for _ in range(50):
-                vf()
-            torch.cuda.synchronize()
+            warm_up(vf)
             e0.record(st)
             for _ in range(args.iters):
                 vf()

@@ -56,5 +56,18 @@ def test_scanner_follows_a_backward_branch():
 @pytest.mark.skipif(os.environ.get("DMATH_CHECK_ISA") != "1", reason="takes five minutes of compilation: set DMATH_CHECK_ISA=1")
 def test_fp16_kernels_have_no_early_accumulator_reads():
     report, looked = check_isa.check()
-    assert looked >= 24
+    assert looked >= 36
     assert report == {}
+
+
+def test_scanner_knows_the_longer_fp64_instruction():
+    early = _lines("""
+        s_nop 0
+        v_mfma_f64_16x16x4_f64 a[16:23], v[122:123], v[126:127], a[16:23]
+        s_nop 15
+        s_nop 15
+        v_accvgpr_read_b32 v7, a23
+    """)
+    assert len(check_isa.scan_function(early)) == 1      # 32 cycles of drain are enough for fp16 only
+    drained = early[:2] + ["s_nop 15"] * 5 + early[-1:]
+    assert check_isa.scan_function(drained) == []
