@@ -9,8 +9,6 @@
 // aligned panel origins and leading dimensions, blocks smaller than 4 GiB.
 #include <hip/hip_runtime.h>
 
-#include <cstdlib>
-
 #include <type_traits>
 
 #include "context.hpp"
@@ -127,11 +125,6 @@ hipError_t launch_shape(const GemmTables& t, double alpha, double beta, hipStrea
 hipError_t launch_gemm_f64(const GemmPlan& p, const GemmTables& t, double alpha, double beta, hipStream_t st)
 {
     const int bm = p.info.tile_m, bn = p.info.tile_n;
-    static const int ring = std::getenv("DMATH_F64_RING") ? std::atoi(std::getenv("DMATH_F64_RING")) : 0;
-    if (bm == 128 && bn == 128 && ring == 4) return launch_shape<128, 128, 2, 4>(t, alpha, beta, st);
-    if (bm == 128 && bn == 128 && ring == 5) return launch_shape<128, 128, 2, 5>(t, alpha, beta, st);
-    if (bm == 128 && bn == 64 && ring == 6) return launch_shape<128, 64, 2, 6>(t, alpha, beta, st);
-    if (bm == 128 && bn == 64 && ring == 4) return launch_shape<128, 64, 2, 4>(t, alpha, beta, st);
     if (bm == 128 && bn == 128) return launch_shape<128, 128, 2>(t, alpha, beta, st);
     if (bm == 128 && bn == 64) return launch_shape<128, 64, 2>(t, alpha, beta, st);
     if (bm == 64 && bn == 128) return launch_shape<64, 128, 2>(t, alpha, beta, st);

@@ -96,11 +96,14 @@ __global__ __launch_bounds__(256) void peak_f16_wide(float* out, int iters)
     if (s == 12345.678f) out[0] = s;
 }
 
+// fp64: sixteen chains on accumulators in fixed accumulation registers, as in the pipelined
+// kernels (mfma.hpp); with the builtin the compiler moved accumulators between register files
+// around the instructions and the probe read 60 TFLOP/s where the GEMM kernel now runs at 67.
 __global__ __launch_bounds__(256) void peak_f64(float* out, int iters)
 {
-    v4d c[8];
-    for (int i = 0; i < 8; ++i)
-        for (int r = 0; r < 4; ++r) c[i][r] = 0.0;
+    acc_f64_begin();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc_f64_zero(i);
     double a[4], b[4];
     uint32_t seed = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
     for (int q = 0; q < 4; ++q) {
@@ -111,13 +114,15 @@ __global__ __launch_bounds__(256) void peak_f64(float* out, int iters)
     }
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int i = 0; i < 8; ++i) c[i] = mfma_f64_16x16x4(a[(u + i) & 3], b[(u + 2 * i) & 3], c[i]);
+        for (int i = 0; i < 16; ++i) mfma_f64_fixed(i, a[i & 3], b[(i >> 2) & 3]);
     }
+    mfma_drain_f64();
     double s = 0.0;
-    for (int i = 0; i < 8; ++i)
-        for (int r = 0; r < 4; ++r) s += c[i][r];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const v4d c = acc_f64_read(i);
+        for (int r = 0; r < 4; ++r) s += c[r];
+    }
     if (s == 12345.678) out[0] = (float)s;
 }
 
