@@ -118,7 +118,8 @@ struct ConvPlan {
     // specialised (MFMA pipeline) path: the copies it reads (owned by the context's table of re-layouts)
     Relayout* xp = nullptr;  // gathered activations, channels-last with zero border
     Relayout* fp = nullptr;  // permuted filter
-    Relayout* yt = nullptr;  // weight gradient: dY channels-last, [n*oh*ow][k]
+    Relayout* yt = nullptr;  // weight gradient: dY channels-last, [n*oh*ow][k] ...
+    const void* dy_in_place = nullptr;  // ... or dY itself (its first element) where the kernel can read it as it lies
     // 0 generic, 1 specialised (gathering MFMA kernels over re-layout copies), 2 as a block GEMM
     // (1x1, stride 1, no padding: the images are the column blocks of a k x c by c x n*h*w product)
     int32_t kernel = 0;
@@ -230,6 +231,7 @@ ConvFastLayout conv_fast_layout(int mode, const ConvGeom& g, dmath_dtype_t in_dt
 bool conv_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype);
 // A 1x1 convolution with stride 1 and no padding that is better run as a block GEMM.
 bool conv_as_gemm_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype);
+bool conv_fast_wgrad_dy_in_place(const ConvGeom& g, dmath_dtype_t in_dtype);
 int conv_fast_wgrad_split(const ConvGeom& g, dmath_dtype_t in_dtype);
 int64_t conv_fast_partial_elems(int mode, const ConvGeom& g, dmath_dtype_t in_dtype, const ConvChoice& c);
 hipError_t launch_conv_fast(const ConvPlan& p, int mode, double alpha, double beta, unsigned rewrite,

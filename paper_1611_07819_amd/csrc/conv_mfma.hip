@@ -489,6 +489,7 @@ struct FastConv {
     const void* xp;  // the copies, elements of the pipeline's input type
     const void* fp;
     const void* yt;
+    const void* y_src;  // weight gradient reading dY where it lies (NCHW, one block): its first element; else null
     void* ws;  // partial sums in the accumulation type (weight gradient: always; others: when split)
     int split, ktiles, ktiles_per_split;  // parts of the k-loop, its k-tiles in all and per part
     // forward, data gradient: tiles (in launch order) that run the whole k-loop; the tiles after
@@ -777,13 +778,27 @@ __global__ __launch_bounds__(256) void conv_fwd_reduce_kernel(FastConv p, int64_
 // ------------------------------------------------------------------------------------------
 // weight gradient
 // ------------------------------------------------------------------------------------------
-template <class P, int BM, int BN> struct WgradWalk {
+// IN_PLACE: the A' operand is dY itself.  In NCHW the pixels of one (image, filter) plane are
+// unit-stride, so dY is the k unit-stride form of A'[filter][pixel] where it lies: row `filter` of
+// a k-tile is 128 bytes of a plane, and a 16-byte chunk never straddles two images when the plane
+// is a whole number of chunks.  The k-tile's first pixel is tracked in scalars (its plane and its
+// place in it go into the base pointer); a plane holds at least one k-tile, so a lane's chunk is
+// either in that plane or in the same filter's plane of the next image: one compare and one
+// select between two fixed offsets per segment and k-tile (per-lane pixel counters with their
+// wraps cost the matrix instructions a tenth of their issue slots).
+template <class P, int BM, int BN, bool IN_PLACE = false> struct WgradWalk {
     using T = typename P::Elem;
-    using TA = typename P::template Tile<BM, false>;
+    using TA = typename P::template Tile<BM, IN_PLACE>;
     using TB = typename P::template Tile<BN, false>;
     static constexpr int BK = P::BK;
     const char *abase, *bbase;
     uint32_t aoff[TA::kInstr], boff[TB::kInstr];
+    // IN_PLACE: the lane's chunk of each A segment: its pixel inside the k-tile, its offset from the
+    // k-tile's first pixel in the same plane and in the next image's
+    int apix[IN_PLACE ? TA::kInstr : 1];
+    uint32_t aoff_here[IN_PLACE ? TA::kInstr : 1], aoff_next[IN_PLACE ? TA::kInstr : 1];
+    int sp_plane, a_first;  // pixels of a plane; the k-tile's first pixel inside its plane (uniform)
+    uint32_t a_next_image_bytes;
     // pixel (oy, ox) of its image fetched by this lane for each B segment; stepping it by one
     // k-tile moves the byte offset by sums of four constants (all arithmetic modulo 2^32: the
     // copy is smaller than 4 GiB, so the true offset is what remains)
@@ -804,10 +819,29 @@ template <class P, int BM, int BN> struct WgradWalk {
         step_bytes = d_oy * row_bytes + d_ox * col_bytes;
         wrap_x_bytes = row_bytes - ow * col_bytes;
         wrap_y_bytes = img_bytes - oh * row_bytes;
-        // A' = Yt[m][k]: dense, m/n (= k_out) unit-stride, filters m0 .. m0+BM of the tile
-        TA::offsets(p.g.k, m0_filters, BM, wave, lane, aoff);
-        astep = TA::step(p.g.k);
-        abase = reinterpret_cast<const char*>(p.yt) + (int64_t)k0_pixels * p.g.k * sizeof(T);
+        sp_plane = oh * ow;
+        a_next_image_bytes = (uint32_t)(p.g.k - 1) * (uint32_t)sp_plane * (uint32_t)sizeof(T);
+        if (IN_PLACE) {
+            astep = 0;
+            const int pn = k0_pixels / sp_plane;
+            a_first = k0_pixels - pn * sp_plane;
+            abase = reinterpret_cast<const char*>(p.y_src) +
+                    (((int64_t)pn * p.g.k + m0_filters) * sp_plane + a_first) * sizeof(T);
+#pragma unroll
+            for (int q = 0; q < TA::kInstr; ++q) {
+                int row, chunk;
+                TA::lane_slot(q, wave, lane, row, chunk);
+                apix[q] = chunk * (16 / (int)sizeof(T));
+                aoff_here[q] = (uint32_t)(((int64_t)row * sp_plane + apix[q]) * sizeof(T));
+                aoff_next[q] = aoff_here[q] + a_next_image_bytes;
+            }
+            select_a();
+        } else {
+            // A' = Yt[m][k]: dense, m/n (= k_out) unit-stride, filters m0 .. m0+BM of the tile
+            TA::offsets(p.g.k, m0_filters, BM, wave, lane, aoff);
+            astep = TA::step(p.g.k);
+            abase = reinterpret_cast<const char*>(p.yt) + (int64_t)k0_pixels * p.g.k * sizeof(T);
+        }
         // B' columns n0 .. n0+BN of (r, s, c): one tap, BN consecutive channels
         const int tap = n0_cols / c, c0 = n0_cols % c, r = tap / p.g.s, s = tap % p.g.s;
         bbase = reinterpret_cast<const char*>(p.xp) + ((int64_t)(r * wp + s) * c + c0) * sizeof(T);
@@ -823,9 +857,25 @@ template <class P, int BM, int BN> struct WgradWalk {
             boff[q] = pn * img_bytes + py[q] * row_bytes + px[q] * col_bytes + chunk * 16;
         }
     }
+    __device__ __forceinline__ void select_a()
+    {
+        const int left = sp_plane - a_first;  // pixels of the k-tile that lie in its first pixel's plane
+#pragma unroll
+        for (int q = 0; q < (IN_PLACE ? TA::kInstr : 0); ++q) aoff[q] = apix[q] < left ? aoff_here[q] : aoff_next[q];
+    }
     __device__ __forceinline__ void advance()
     {
-        abase += astep;
+        if (IN_PLACE) {
+            a_first += BK;
+            abase += BK * sizeof(T);
+            if (a_first >= sp_plane) {
+                a_first -= sp_plane;
+                abase += a_next_image_bytes;
+            }
+            select_a();
+        } else {
+            abase += astep;
+        }
 #pragma unroll
         for (int q = 0; q < TB::kInstr; ++q) {  // pixel index += BK
             px[q] += d_ox;
@@ -840,7 +890,7 @@ template <class P, int BM, int BN> struct WgradWalk {
     }
 };
 
-template <class P, int BM, int BN>
+template <class P, int BM, int BN, bool IN_PLACE>
 __global__ __launch_bounds__(NT) void conv_wgrad_kernel(FastConv p)
 {
     using TS = typename P::template Shape<BM, BN>;
@@ -866,8 +916,8 @@ __global__ __launch_bounds__(NT) void conv_wgrad_kernel(FastConv p)
 
     // the last part may be shorter; pixels past n*oh*ow (last k-tile) read zeros on both sides
     const int kt0 = split * p.ktiles_per_split;
-    WgradWalk<P, BM, BN> walk(p, kt0 * BK, m0, n0, wave, lane);
-    P::template run<BM, BN, 3, false, false>(walk, min(p.ktiles_per_split, p.ktiles - kt0), smem, acc);
+    WgradWalk<P, BM, BN, IN_PLACE> walk(p, kt0 * BK, m0, n0, wave, lane);
+    P::template run<BM, BN, 3, IN_PLACE, false>(walk, min(p.ktiles_per_split, p.ktiles - kt0), smem, acc);
 
     AccT* ws = static_cast<AccT*>(p.ws) + (int64_t)split * p.g.k * ncols;
 #pragma unroll
@@ -1013,6 +1063,20 @@ bool conv_fast_ok(int mode, const ConvGeom& g, dmath_dtype_t in_dtype)
     // the weight gradient steps its pixel index by one k-tile with three conditional wraps
     if (mode == CONV_BWD_FILTER) return pixel_tile(in_dtype) / g.ow < 3 * g.oh;
     return true;
+}
+
+// The weight gradient can read dY where it lies (no channels-last copy of it) when a plane of oh*ow
+// pixels is a whole number of 16-byte chunks, the pixels of all images are a whole number of
+// k-tiles (there are no zero rows to read past the end), no filter row is padding, a plane holds
+// at least one k-tile, and 32-bit lane offsets reach all of dY.  The caller checks that dY is one
+// block.  DMATH_CONV_DY_COPY=1 keeps the copy (experiments and tests).
+bool conv_fast_wgrad_dy_in_place(const ConvGeom& g, dmath_dtype_t in_dtype)
+{
+    static const bool keep_copy = std::getenv("DMATH_CONV_DY_COPY") != nullptr;
+    if (keep_copy) return false;
+    const int64_t eb = elem_bytes(in_dtype), pt = pixel_tile(in_dtype), sp = (int64_t)g.oh * g.ow;
+    return (sp * eb) % 16 == 0 && ((int64_t)g.n * sp) % pt == 0 && g.k % 64 == 0 && pt <= sp &&
+           (int64_t)g.n * g.k * sp * eb < (1ll << 32);
 }
 
 // A 1x1 convolution with stride 1 and no padding is, image by image, Y_n[k x hw] = F[k x c] *
@@ -1420,17 +1484,23 @@ hipError_t launch_fwd(const FastConv& p, dmath_dtype_t in, int tile_m, int tile_
     return hipErrorInvalidValue;
 }
 
-template <class P, int BM, int BN> hipError_t launch_wgrad_shape(const FastConv& p, int tiles, hipStream_t st)
+template <class P, int BM, int BN, bool IN_PLACE>
+hipError_t launch_wgrad_kernel(const FastConv& p, int tiles, hipStream_t st)
 {
     constexpr int lds = P::lds_bytes(BM, BN, 3);
     static bool configured = false;
     if (!configured) {
-        hipError_t e = set_lds(conv_wgrad_kernel<P, BM, BN>, lds);
+        hipError_t e = set_lds(conv_wgrad_kernel<P, BM, BN, IN_PLACE>, lds);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    conv_wgrad_kernel<P, BM, BN><<<tiles, NT, lds, st>>>(p);
+    conv_wgrad_kernel<P, BM, BN, IN_PLACE><<<tiles, NT, lds, st>>>(p);
     return hipGetLastError();
+}
+template <class P, int BM, int BN> hipError_t launch_wgrad_shape(const FastConv& p, int tiles, hipStream_t st)
+{
+    if (p.y_src) return launch_wgrad_kernel<P, BM, BN, true>(p, tiles, st);
+    return launch_wgrad_kernel<P, BM, BN, false>(p, tiles, st);
 }
 
 hipError_t launch_wgrad(const FastConv& p, dmath_dtype_t in, int bm, int bn, int tiles, hipStream_t st)
@@ -1486,11 +1556,12 @@ hipError_t launch_typed(const ConvPlan& plan, int mode, double alpha, double bet
     p.xp = xp;
     p.fp = fp;
     p.yt = yt;
+    p.y_src = mode == CONV_BWD_FILTER ? plan.dy_in_place : nullptr;
     p.ws = t.workspace;
     p.split = t.split_k;
     p.tail_only = plan.tail_only;
     p.sink = t.sink;
-    if (!xp || !p.sink || (mode != CONV_BWD_FILTER && !fp) || (mode == CONV_BWD_FILTER && (!yt || !p.ws)))
+    if (!xp || !p.sink || (mode != CONV_BWD_FILTER && !fp) || (mode == CONV_BWD_FILTER && ((!yt && !p.y_src) || !p.ws)))
         return hipErrorInvalidValue;  // the plan was not made for this path
 
     RelayoutJobs jobs{};
@@ -1532,7 +1603,7 @@ hipError_t launch_typed(const ConvPlan& plan, int mode, double alpha, double bet
         return launch_fwd(p, in, plan.tile_m, plan.tile_n, plan.out_dtype, alpha, beta, st);
     }
     // weight gradient: dY -> channels-last [m][k], split GEMM, fixed-order reduction
-    if (rewrite & REWRITE_Y)
+    if (!p.y_src && (rewrite & REWRITE_Y))
         jobs.b = tcl_job<T>(t.y_rows, g.n, g.k, kp, g.oh, g.ow, 0, 0, 1, 1, g.oh, g.ow, yt, &lds);
     if (hipError_t e = launch_relayout<T>(jobs, lds, st); e != hipSuccess) return e;
     p.ktiles = (int)wgrad_ktiles(g, in);

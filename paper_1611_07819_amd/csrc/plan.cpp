@@ -739,10 +739,12 @@ dmath_status_t make_conv_plan(dmath_ctx_s* ctx, int mode, const dmath_conv_desc_
                                     {g.c, g.h, g.w, g.pad_h, g.pad_w, (int32_t)lay.x_images}, (size_t)lay.x_bytes);
             if (mode == CONV_FWD)
                 plan->fp = get_relayout(ctx, F, RELAYOUT_FILTER_RSC, {g.c, g.r, g.s, g.k}, (size_t)lay.f_bytes);
+            else if (Y->rsplit.g == 1 && conv_fast_wgrad_dy_in_place(g, plan->in_dtype))
+                plan->dy_in_place = Y->block(0, 0);
             else
                 plan->yt = get_relayout(ctx, Y, RELAYOUT_CHANNELS_LAST, {g.k, g.oh, g.ow, 0, 0}, (size_t)lay.y_bytes);
         }
-        const bool ok = plan->xp && (mode == CONV_BWD_FILTER ? plan->yt != nullptr : plan->fp != nullptr);
+        const bool ok = plan->xp && (mode == CONV_BWD_FILTER ? (plan->yt || plan->dy_in_place) : plan->fp != nullptr);
         if (!ok) {
             free_conv_plan(ctx, *plan);
             return DMATH_ERR_OOM;

@@ -1,4 +1,6 @@
 """GPU parity of the implicit-GEMM convolutions against the CPU oracle, through the C ABI."""
+import os
+
 import numpy as np
 import pytest
 
@@ -182,6 +184,29 @@ def runs_as_block_gemm(g, dt):
             (g["c"] * es) % 16 == 0 and (sp + 63) // 64 * 64 * 100 <= sp * 135)
 
 
+def out_plane(g):
+    oh = (g["h"] + 2 * g.get("pad_h", 0) - g["r"]) // g.get("stride_h", 1) + 1
+    ow = (g["w"] + 2 * g.get("pad_w", 0) - g["s"]) // g.get("stride_w", 1) + 1
+    return oh, ow
+
+
+def dy_read_in_place(g, dt, y_grid=(1, 1)):
+    """The weight gradient reads dY where it lies (no channels-last copy of it): dY is one block,
+    a plane is a whole number of 16-byte chunks, all pixels a whole number of k-tiles, the filter
+    count a multiple of 64, and a plane holds at least one k-tile."""
+    es, pt = {dm.F16: (2, 64), dm.F32: (4, 32), dm.F64: (8, 16)}[dt]
+    oh, ow = out_plane(g)
+    sp = oh * ow
+    return (y_grid[0] == 1 and "DMATH_CONV_DY_COPY" not in os.environ and (sp * es) % 16 == 0 and
+            (g["n"] * sp) % pt == 0 and g["k"] % 64 == 0 and pt <= sp)
+
+
+def copies_written(g, dt, y_grid=(1, 1)):
+    """Re-layout copies the three modes write on the specialised kernels: two each, except that
+    the weight gradient may read dY in place."""
+    return 5 if dy_read_in_place(g, dt, y_grid) else 6
+
+
 FAST_GEOMS = [
     # geometries that run on the specialised kernels
     dict(n=4, c=128, h=16, w=16, k=256, r=3, s=3, pad_h=1, pad_w=1),
@@ -207,6 +232,7 @@ FAST_GEOMS = [
     dict(n=2, c=64, h=27, w=27, k=128, r=5, s=5, pad_h=2, pad_w=2),
     dict(n=5, c=120, h=9, w=11, k=120, r=3, s=2, pad_h=1, pad_w=0, stride_h=2, stride_w=1),
     dict(n=16, c=64, h=13, w=13, k=64, r=3, s=3, pad_h=1, pad_w=1),       # 43 pixel tiles in 5 uneven parts
+    dict(n=8, c=64, h=6, w=4, k=64, r=3, s=3, pad_h=1, pad_w=1),          # planes of 24 pixels: fp64 reads dY in place, a plane ends inside two k-tiles of three
     dict(n=2, c=64, h=16, w=16, k=64, r=12, s=12),                        # 144 taps: fp64 filter permute / reduction without LDS staging
     # 1x1, stride 1, no padding: block GEMMs with one column block per image (planes of 576 pixels:
     # ragged last column tile, and a k-tail per image in the weight gradient; 56 channels: a k-tail
@@ -226,16 +252,17 @@ def test_specialised_conv_whole_result(ctx, oracle, g, dt, out):
     before = ctx.relayout_stats()["written"]
     res = three_modes(ctx, oracle, g, dt, out, 1.5, -0.5, grids, policy=0)
     # every mode went through the specialised kernels: each re-laid-out its two operands
-    assert ctx.relayout_stats()["written"] - before == (0 if runs_as_block_gemm(g, dt) else 6)
+    assert ctx.relayout_stats()["written"] - before == (0 if runs_as_block_gemm(g, dt) else copies_written(g, dt))
     for mode in ("fwd", "bwd_filter", "bwd_data"):
         got, ref = res[mode]
         assert rel_fro(got, ref) <= TOL[dt], mode
     d, t = tensors(g, dt, 300, ints=True)
     t = {k: np.sign(v).astype(NP[dt]) if k != "F" else v for k, v in t.items()}   # keep sums small
     od = oracle.ConvDesc(**g)
-    grids = {"X": (g["n"], 1), "F": (2, 1), "Y": (2, 1)}
     ctx.set_kernel_policy(0)
-    for mode in ("fwd", "bwd_filter", "bwd_data"):
+    blocked, whole = {"X": (g["n"], 1), "F": (2, 1), "Y": (2, 1)}, {"X": (1, 1), "F": (1, 1), "Y": (1, 1)}
+    # the weight gradient a second time on one-block tensors, where it may read dY in place
+    for mode, grids in (("fwd", blocked), ("bwd_filter", blocked), ("bwd_data", blocked), ("bwd_filter", whole)):
         out_name = {"fwd": "Y", "bwd_filter": "F", "bwd_data": "X"}[mode]
         host = {k: (v.astype(NP[out]) if k == out_name else v) for k, v in t.items()}
         dev = {k: ctx.from_host(v, grids[k]) for k, v in host.items()}
@@ -277,7 +304,7 @@ def test_forward_and_data_gradient_with_a_split_k_loop(oracle, monkeypatch, g, d
         grids = {"X": (g["n"], 1), "F": (2, 1), "Y": (1, 1)}
         before = c.relayout_stats()["written"]
         res = three_modes(c, oracle, g, dt, out, 1.0, 1.0, grids, ints=True, policy=0)
-        assert c.relayout_stats()["written"] - before == 6       # every mode on the specialised kernels
+        assert c.relayout_stats()["written"] - before == copies_written(g, dt)   # every mode on the specialised kernels
         for mode in ("fwd", "bwd_data"):
             got, ref = res[mode]
             if out == dm.F16 and np.abs(ref).max() > 2048:
@@ -312,7 +339,7 @@ def test_fp16_forward_tile_shapes_and_k_tile_counts(oracle, monkeypatch, out, ti
         grids = {"X": (g["n"], 1), "F": (2, 1), "Y": (1, 1)}
         before = c.relayout_stats()["written"]
         res = three_modes(c, oracle, g, dm.F16, out, 1.0, 1.0, grids, ints=True, policy=0)
-        assert c.relayout_stats()["written"] - before == 6       # every mode on the specialised kernels
+        assert c.relayout_stats()["written"] - before == copies_written(g, dm.F16)   # every mode on the specialised kernels
         for mode in ("fwd", "bwd_filter", "bwd_data"):
             got, ref = res[mode]
             if out == dm.F16 and np.abs(ref).max() > 2048:
@@ -424,7 +451,7 @@ def test_specialised_conv_ragged_last_row_tile(ctx, oracle, g, dt, out):
     grids = {"X": (g["n"], 1), "F": (2, 1), "Y": (1, 1)}
     before = ctx.relayout_stats()["written"]
     res = three_modes(ctx, oracle, g, dt, out, 1.0, 1.0, grids, ints=True, policy=0)
-    assert ctx.relayout_stats()["written"] - before == 6       # every mode on the specialised kernels
+    assert ctx.relayout_stats()["written"] - before == copies_written(g, dt)   # every mode on the specialised kernels
     for mode, (got, ref) in res.items():
         if out == dm.F16 and np.abs(ref).max() > 2048:
             assert rel_fro(got, ref) <= TOL[dm.F16], mode
