@@ -13,8 +13,9 @@ accumulator register in the cycle after a vector instruction wrote it; the assem
 carries a wait state (s_nop 0) for that except in the steady state of the fp16 k-loop, where the
 compiler is expected to put no copy in front of it -- the check reports any v_accvgpr_write /
 v_accvgpr_mov into a register that the very next instruction, a matrix instruction, accumulates
-into.  The fp64 pipelines go further and keep their accumulators in fixed registers that the
-compiler knows nothing about (mfma.hpp): in a kernel with fp64 matrix instructions every
+into.  The fp64 pipelines, and the fp16 weight gradient of the convolution, go further and keep
+their accumulators in fixed registers that the compiler knows nothing about (mfma.hpp): in a
+kernel with fp64 matrix instructions, or with the comment that acc_fixed_marker() leaves, every
 instruction that names an accumulation register must be one of the three forms the pipeline
 writes itself (the matrix instruction, v_accvgpr_write_b32 aN, 0 and v_accvgpr_read_b32 vM, aN).
 
@@ -59,12 +60,17 @@ def _regs(text: str):
     return out
 
 
-def scan_function(lines):
-    """lines: the instructions and labels of one kernel.  Returns [(line index, text, cycles)]."""
+FIXED_MARKER = "dmath: fixed accumulation registers"  # comment left by acc_fixed_marker() (mfma.hpp)
+
+
+def scan_function(lines, fixed=False):
+    """lines: the instructions and labels of one kernel.  fixed: the kernel keeps its accumulators
+    in fixed registers (every fp64 kernel does).  Returns [(line index, text, cycles)]."""
     label_at = {l[:-1]: i for i, l in enumerate(lines) if l.endswith(":")}
     found = []
-    if any(l.startswith("v_mfma_f64_16x16x4_f64") for l in lines):
-        own = re.compile(r"v_mfma_f64_16x16x4_f64 |v_accvgpr_write_b32 a\d+, 0$|v_accvgpr_read_b32 v\d+, a\d+$")
+    if fixed or any(l.startswith("v_mfma_f64_16x16x4_f64") for l in lines):
+        own = re.compile(r"v_mfma_f64_16x16x4_f64 |v_mfma_f32_16x16x32_f16 a\[\d+:\d+\], v\[\d+:\d+\], v\[\d+:\d+\], a\[\d+:\d+\]$|"
+                         r"v_accvgpr_write_b32 a\d+, 0$|v_accvgpr_read_b32 v\d+, a\d+$")
         for i, l in enumerate(lines):
             ops = l.split(None, 1)[1] if " " in l and not l.endswith(":") else ""
             if _regs(ops) and not own.match(l):
@@ -120,7 +126,7 @@ def scan_file(path: str):
         looked += 1
         lines = [l.split(";")[0].strip() for l in body.split("\n")]
         lines = [l for l in lines if l and (not l.startswith(".") or re.match(r"\.LBB\w+:", l))]
-        bad = scan_function(lines)
+        bad = scan_function(lines, fixed=FIXED_MARKER in body)
         if bad:
             report[name] = bad
     return report, looked

@@ -101,6 +101,15 @@ struct PipeF16Q : Acc16q {
     }
     static constexpr int lds_bytes(int bm, int bn, int stages) { return stages * (bm + bn) * BK * 2; }
 };
+// ... with the accumulators in fixed registers (the weight gradient)
+struct PipeF16QF : PipeF16Q {
+    template <int BM, int BN, int STAGES, bool AKC, bool BKC, class Walk, class Acc>
+    __device__ __forceinline__ static void run(Walk& walk, int n_ktiles, char* smem, Acc& acc)
+    {
+        f16p::NoProbe none;
+        f16p::run16<BM, BN, STAGES, AKC, BKC, true>(walk, n_ktiles, smem, acc, none);
+    }
+};
 struct PipeF32 : Acc32 {
     using Elem = float;
     static constexpr int BK = f32p::BK;
@@ -1519,10 +1528,14 @@ hipError_t launch_wgrad(const FastConv& p, dmath_dtype_t in, int bm, int bn, int
         if (bm == 64 && bn == 64) return launch_wgrad_shape<PipeF32, 64, 64>(p, tiles, st);
         return hipErrorInvalidValue;
     }
-    // The weight gradient stays on 32x32x16 fragments: with its walk's many per-lane offsets the
-    // compiler renames accumulators between the iterations of the 16x16x32 pipeline and reads them
-    // before the matrix instructions written as assembly have finished (found by check_isa.py);
-    // with the matrix cores drained at those points it was correct and 5-7 % slower than this.
+    // Tiles of 128 columns run on 16x16x32 fragments with the accumulators in fixed registers: with
+    // tied accumulators the compiler, given this walk's many per-lane values, renamed them between
+    // the iterations and read them before the matrix instructions written as assembly had finished
+    // (found by check_isa.py); draining the matrix cores at those points was correct and slower
+    // than 32x32x16 fragments.  DMATH_F16_MFMA32=1 switches back to those (A/B measurements).
+    static const bool mf32 = std::getenv("DMATH_F16_MFMA32") != nullptr;
+    if (!mf32 && bm == 256 && bn == 128) return launch_wgrad_shape<PipeF16QF, 256, 128>(p, tiles, st);
+    if (!mf32 && bm == 128 && bn == 128) return launch_wgrad_shape<PipeF16QF, 128, 128>(p, tiles, st);
     if (bm == 256 && bn == 128) return launch_wgrad_shape<PipeF16, 256, 128>(p, tiles, st);
     if (bm == 128 && bn == 128) return launch_wgrad_shape<PipeF16, 128, 128>(p, tiles, st);
     if (bm == 64 && bn == 128) return launch_wgrad_shape<PipeF16, 64, 128>(p, tiles, st);

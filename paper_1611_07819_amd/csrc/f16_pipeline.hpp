@@ -431,7 +431,10 @@ template <int BM, int BN> struct TileShape16 {
     __device__ __forceinline__ static int wn(int wave) { return wave % WVN; }
 };
 
-template <int BM, int BN, int STAGES, bool AKC, bool BKC, class Walk, class Probe>
+// FIXED: the accumulators live in fixed accumulation registers that the compiler never sees
+// (mfma.hpp: acc_f16_zero / mfma_f16_fixed / acc_f16_read; at most 32 of them); `acc` only
+// receives the sums at the end.  For kernels in which the compiler renames tied accumulators.
+template <int BM, int BN, int STAGES, bool AKC, bool BKC, bool FIXED = false, class Walk, class Probe>
 __device__ __forceinline__ void run16(Walk& walk, int n_ktiles, char* smem,
                                       v4f (&acc)[TileShape16<BM, BN>::MT][TileShape16<BM, BN>::NTL], Probe& probe)
 {
@@ -460,6 +463,13 @@ __device__ __forceinline__ void run16(Walk& walk, int n_ktiles, char* smem,
     // the last k-tile; what is fetched again lands in stages nobody reads any more), and the
     // last iteration reads "next" fragments it never uses.
     constexpr bool kAlwaysFull = MT * NTL * 4 >= 224;
+    static_assert(!FIXED || MT * NTL <= 32, "fixed accumulators: a0 .. a127");
+    if constexpr (FIXED) {
+        acc_f64_begin();
+        acc_fixed_marker();
+#pragma unroll
+        for (int idx = 0; idx < MT * NTL; ++idx) acc_f16_zero(idx);
+    }
     auto next_tile = [&]() __attribute__((always_inline)) {
         if constexpr (kAlwaysFull)
             walk.advance_or_stay();
@@ -580,7 +590,10 @@ __device__ __forceinline__ void run16(Walk& walk, int n_ktiles, char* smem,
                 // accumulators: between the differently scheduled iterations that run on a run-time
                 // stage, not in the steady state (4-5 % of its cycles; check_isa.py looks for a
                 // copy directly in front of an instruction without one)
-                mfma_f16_16x16x32<std::is_same<decltype(stage_v), int>::value>(acc[i][j], fa[cur][i], fb[cur][j]);
+                if constexpr (FIXED)
+                    mfma_f16_fixed(i * NTL + j, fa[cur][i], fb[cur][j]);
+                else
+                    mfma_f16_16x16x32<std::is_same<decltype(stage_v), int>::value>(acc[i][j], fa[cur][i], fb[cur][j]);
                 __builtin_amdgcn_sched_barrier(0);
                 // reads m*r_count/kMfma .. (m+1)*r_count/kMfma of the phase's share go into this slot
 #pragma unroll
@@ -620,6 +633,7 @@ __device__ __forceinline__ void run16(Walk& walk, int n_ktiles, char* smem,
     // iterations below -- the matrix pipeline is drained first and every accumulator is tied to
     // a point after the drain.
     auto settle = [&]() __attribute__((always_inline)) {
+        if constexpr (FIXED) return;  // nothing but matrix instructions touches the accumulators
         mfma_drain();
 #pragma unroll
         for (int i = 0; i < MT; ++i)
@@ -688,6 +702,13 @@ __device__ __forceinline__ void run16(Walk& walk, int n_ktiles, char* smem,
     }
     iteration(stage, F{}, F{}, F{});
     settle();
+    if constexpr (FIXED) {
+        mfma_drain();
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NTL; ++j) acc[i][j] = acc_f16_read(i * NTL + j);
+    }
 }
 
 }  // namespace f16p

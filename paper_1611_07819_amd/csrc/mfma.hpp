@@ -166,4 +166,61 @@ __device__ __forceinline__ v4d acc_f64_read(int idx)
     return c;
 }
 
+// The same for the fp16 16x16x32 instruction where the compiler cannot be kept from renaming tied
+// accumulators (the convolution's weight gradient: its walk holds many per-lane values, and the
+// copies between renamed accumulators landed right behind the matrix instructions that write
+// them): accumulator idx < 32 lives in a[4*idx .. 4*idx+3].  acc_f64_begin() reserves a0 .. a127
+// for these as well; acc_fixed_marker() leaves a comment in the assembly by which check_isa.py
+// knows that in this kernel nothing but the three statements below may name an accumulation
+// register.
+#define DM_ACC4_LIST(X) \
+    X(0, 0, 1, 2, 3) X(1, 4, 5, 6, 7) X(2, 8, 9, 10, 11) X(3, 12, 13, 14, 15) \
+    X(4, 16, 17, 18, 19) X(5, 20, 21, 22, 23) X(6, 24, 25, 26, 27) X(7, 28, 29, 30, 31) \
+    X(8, 32, 33, 34, 35) X(9, 36, 37, 38, 39) X(10, 40, 41, 42, 43) X(11, 44, 45, 46, 47) \
+    X(12, 48, 49, 50, 51) X(13, 52, 53, 54, 55) X(14, 56, 57, 58, 59) X(15, 60, 61, 62, 63) \
+    X(16, 64, 65, 66, 67) X(17, 68, 69, 70, 71) X(18, 72, 73, 74, 75) X(19, 76, 77, 78, 79) \
+    X(20, 80, 81, 82, 83) X(21, 84, 85, 86, 87) X(22, 88, 89, 90, 91) X(23, 92, 93, 94, 95) \
+    X(24, 96, 97, 98, 99) X(25, 100, 101, 102, 103) X(26, 104, 105, 106, 107) X(27, 108, 109, 110, 111) \
+    X(28, 112, 113, 114, 115) X(29, 116, 117, 118, 119) X(30, 120, 121, 122, 123) X(31, 124, 125, 126, 127)
+__device__ __forceinline__ void acc_fixed_marker() { asm volatile("; dmath: fixed accumulation registers"); }
+__device__ __forceinline__ void acc_f16_zero(int idx)
+{
+    switch (idx) {
+#define X(I, R0, R1, R2, R3)                                                                                   \
+    case I:                                                                                                    \
+        asm volatile("v_accvgpr_write_b32 a" #R0 ", 0\n\tv_accvgpr_write_b32 a" #R1 ", 0\n\tv_accvgpr_write_b32 a" #R2 \
+                     ", 0\n\tv_accvgpr_write_b32 a" #R3 ", 0");                                                \
+        break;
+        DM_ACC4_LIST(X)
+#undef X
+    }
+}
+__device__ __forceinline__ void mfma_f16_fixed(int idx, v8h a, v8h b)
+{
+    switch (idx) {
+#define X(I, R0, R1, R2, R3)                                                                                    \
+    case I:                                                                                                     \
+        asm volatile("v_mfma_f32_16x16x32_f16 a[" #R0 ":" #R3 "], %0, %1, a[" #R0 ":" #R3 "]" ::"v"(a), "v"(b)); \
+        break;
+        DM_ACC4_LIST(X)
+#undef X
+    }
+}
+__device__ __forceinline__ v4f acc_f16_read(int idx)
+{
+    v4f c = {0.f, 0.f, 0.f, 0.f};
+    switch (idx) {
+#define X(I, R0, R1, R2, R3)                                                                                  \
+    case I:                                                                                                   \
+        asm volatile("v_accvgpr_read_b32 %0, a" #R0 "\n\tv_accvgpr_read_b32 %1, a" #R1 "\n\tv_accvgpr_read_b32 %2, a" #R2 \
+                     "\n\tv_accvgpr_read_b32 %3, a" #R3                                                       \
+                     : "=v"(c[0]), "=v"(c[1]), "=v"(c[2]), "=v"(c[3]));                                         \
+        break;
+        DM_ACC4_LIST(X)
+#undef X
+    }
+    return c;
+}
+#undef DM_ACC4_LIST
+
 }  // namespace dm

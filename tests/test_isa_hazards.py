@@ -71,3 +71,20 @@ def test_scanner_knows_the_longer_fp64_instruction():
     assert len(check_isa.scan_function(early)) == 1      # 32 cycles of drain are enough for fp16 only
     drained = early[:2] + ["s_nop 15"] * 5 + early[-1:]
     assert check_isa.scan_function(drained) == []
+
+
+def test_scanner_accepts_only_the_pipelines_own_forms_on_fixed_accumulators():
+    own = _lines("""
+        v_accvgpr_write_b32 a5, 0
+        s_nop 0
+        v_mfma_f32_16x16x32_f16 a[4:7], v[2:5], v[38:41], a[4:7]
+        s_nop 15
+        s_nop 15
+        v_accvgpr_read_b32 v9, a5
+    """)
+    assert check_isa.scan_function(own, fixed=True) == []
+    # a register the compiler parks in the accumulation file: fine in an ordinary kernel, not here
+    parked = own + ["v_accvgpr_write_b32 a200, v17"]
+    assert check_isa.scan_function(parked) == []
+    assert [l for _, l, _ in check_isa.scan_function(parked, fixed=True)] == \
+        ["v_accvgpr_write_b32 a200, v17   (accumulation register used by the compiler)"]
