@@ -891,10 +891,13 @@ template <class P, int BM, int BN, bool IN_PLACE = false> struct WgradWalk {
             py[q] += d_oy;
             boff[q] += step_bytes;
             if (px[q] >= ow) { px[q] -= ow; ++py[q]; boff[q] += wrap_x_bytes; }
-            // a k-tile spans at most three image boundaries (conv_fast_ok: BK / ow < 3 * oh)
+            // a k-tile spans at most three image boundaries (conv_fast_ok: BK / ow < 3 * oh); one
+            // where dY is read in place (a plane holds at least one k-tile there)
             if (py[q] >= oh) { py[q] -= oh; boff[q] += wrap_y_bytes; }
-            if (py[q] >= oh) { py[q] -= oh; boff[q] += wrap_y_bytes; }
-            if (py[q] >= oh) { py[q] -= oh; boff[q] += wrap_y_bytes; }
+            if (!IN_PLACE) {
+                if (py[q] >= oh) { py[q] -= oh; boff[q] += wrap_y_bytes; }
+                if (py[q] >= oh) { py[q] -= oh; boff[q] += wrap_y_bytes; }
+            }
         }
     }
 };
