@@ -795,7 +795,11 @@ __global__ __launch_bounds__(256) void conv_fwd_reduce_kernel(FastConv p, int64_
 // either in that plane or in the same filter's plane of the next image: one compare and one
 // select between two fixed offsets per segment and k-tile (per-lane pixel counters with their
 // wraps cost the matrix instructions a tenth of their issue slots).
-template <class P, int BM, int BN, bool IN_PLACE = false> struct WgradWalk {
+// TABLE: the byte offset of every pixel of this workgroup's k-range lies in an LDS table that the
+// workgroup filled before the k-loop (wgrad_fill_table); stepping the B rows by a k-tile is then one
+// LDS read and one add per segment instead of counters with wraps (a wavefront of the 16x16x32
+// pipeline has three issue slots per matrix instruction and this kernel fills nearly all of them).
+template <class P, int BM, int BN, bool IN_PLACE = false, bool TABLE = false> struct WgradWalk {
     using T = typename P::Elem;
     using TA = typename P::template Tile<BM, IN_PLACE>;
     using TB = typename P::template Tile<BN, false>;
@@ -811,13 +815,16 @@ template <class P, int BM, int BN, bool IN_PLACE = false> struct WgradWalk {
     // pixel (oy, ox) of its image fetched by this lane for each B segment; stepping it by one
     // k-tile moves the byte offset by sums of four constants (all arithmetic modulo 2^32: the
     // copy is smaller than 4 GiB, so the true offset is what remains)
-    int py[TB::kInstr], px[TB::kInstr];
+    int py[TABLE ? 1 : TB::kInstr], px[TABLE ? 1 : TB::kInstr];
+    typedef const __attribute__((address_space(3))) uint32_t LdsU32;
+    LdsU32* tab_lane;  // TABLE: entry of this lane's row of segment 0 in the current k-tile
+    uint32_t bchunk[TABLE ? TB::kInstr : 1];  // ... and the lane's 16-byte chunk of each segment
     int oh, ow, d_oy, d_ox;
     uint32_t step_bytes, wrap_x_bytes, wrap_y_bytes;
     int64_t astep;
 
     __device__ __forceinline__ WgradWalk(const FastConv& p, int k0_pixels, int m0_filters, int n0_cols, int wave,
-                                         int lane)
+                                         int lane, const char* table = nullptr)
     {
         const int hp = p.hp, wp = p.wp, c = p.g.c;
         oh = p.g.oh; ow = p.g.ow;
@@ -855,15 +862,37 @@ template <class P, int BM, int BN, bool IN_PLACE = false> struct WgradWalk {
         const int tap = n0_cols / c, c0 = n0_cols % c, r = tap / p.g.s, s = tap % p.g.s;
         bbase = reinterpret_cast<const char*>(p.xp) + ((int64_t)(r * wp + s) * c + c0) * sizeof(T);
         const int sp_out = oh * ow;
+        if constexpr (TABLE) {
+            // segment q holds rows q * kRowStep further on (lane_slot: 4 segments of kRowsPerSeg rows per step of q)
+            int row0, chunk0;
+            TB::lane_slot(0, wave, lane, row0, chunk0);
+            tab_lane = (LdsU32*)table + row0;
 #pragma unroll
-        for (int q = 0; q < TB::kInstr; ++q) {
-            int row, chunk;
-            TB::lane_slot(q, wave, lane, row, chunk);
-            const int m = k0_pixels + row;
-            const int pn = m / sp_out, sp = m % sp_out;
-            py[q] = sp / ow;
-            px[q] = sp % ow;
-            boff[q] = pn * img_bytes + py[q] * row_bytes + px[q] * col_bytes + chunk * 16;
+            for (int q = 0; q < TB::kInstr; ++q) {
+                int row, chunk;
+                TB::lane_slot(q, wave, lane, row, chunk);
+                bchunk[q] = chunk * 16;
+            }
+            select_b();
+        } else {
+#pragma unroll
+            for (int q = 0; q < TB::kInstr; ++q) {
+                int row, chunk;
+                TB::lane_slot(q, wave, lane, row, chunk);
+                const int m = k0_pixels + row;
+                const int pn = m / sp_out, sp = m % sp_out;
+                py[q] = sp / ow;
+                px[q] = sp % ow;
+                boff[q] = pn * img_bytes + py[q] * row_bytes + px[q] * col_bytes + chunk * 16;
+            }
+        }
+    }
+    static constexpr int kRowStep = 4 * TB::kRowsPerSeg;
+    __device__ __forceinline__ void select_b()
+    {
+        if constexpr (TABLE) {
+#pragma unroll
+            for (int q = 0; q < TB::kInstr; ++q) boff[q] = tab_lane[q * kRowStep] + bchunk[q];
         }
     }
     __device__ __forceinline__ void select_a()
@@ -885,24 +914,62 @@ template <class P, int BM, int BN, bool IN_PLACE = false> struct WgradWalk {
         } else {
             abase += astep;
         }
+        if constexpr (TABLE) {
+            tab_lane += BK;
+            select_b();
+        } else {
 #pragma unroll
-        for (int q = 0; q < TB::kInstr; ++q) {  // pixel index += BK
-            px[q] += d_ox;
-            py[q] += d_oy;
-            boff[q] += step_bytes;
-            if (px[q] >= ow) { px[q] -= ow; ++py[q]; boff[q] += wrap_x_bytes; }
-            // a k-tile spans at most three image boundaries (conv_fast_ok: BK / ow < 3 * oh); one
-            // where dY is read in place (a plane holds at least one k-tile there)
-            if (py[q] >= oh) { py[q] -= oh; boff[q] += wrap_y_bytes; }
-            if (!IN_PLACE) {
+            for (int q = 0; q < TB::kInstr; ++q) {  // pixel index += BK
+                px[q] += d_ox;
+                py[q] += d_oy;
+                boff[q] += step_bytes;
+                if (px[q] >= ow) { px[q] -= ow; ++py[q]; boff[q] += wrap_x_bytes; }
+                // a k-tile spans at most three image boundaries (conv_fast_ok: BK / ow < 3 * oh); one
+                // where dY is read in place (a plane holds at least one k-tile there)
                 if (py[q] >= oh) { py[q] -= oh; boff[q] += wrap_y_bytes; }
-                if (py[q] >= oh) { py[q] -= oh; boff[q] += wrap_y_bytes; }
+                if (!IN_PLACE) {
+                    if (py[q] >= oh) { py[q] -= oh; boff[q] += wrap_y_bytes; }
+                    if (py[q] >= oh) { py[q] -= oh; boff[q] += wrap_y_bytes; }
+                }
             }
         }
     }
 };
 
-template <class P, int BM, int BN, bool IN_PLACE>
+// table[e] = byte offset in Xp (tap (0,0), channel 0) of pixel k0_pixels + e, e < entries; the
+// `spare` entries after them (the k-tile that the walk steps onto after its last load) hold 0.
+// Each thread takes a run of consecutive pixels: one division at its start, then counters.
+template <class T>
+__device__ __forceinline__ void wgrad_fill_table(const FastConv& p, int k0_pixels, int entries, int spare, char* table)
+{
+    uint32_t* tab = reinterpret_cast<uint32_t*>(table);
+    const int oh = p.g.oh, ow = p.g.ow, sp_out = oh * ow;
+    const uint32_t col_bytes = (uint32_t)(p.g.stride_w * p.g.c * (int)sizeof(T));
+    const uint32_t row_bytes = (uint32_t)p.g.stride_h * p.wp * p.g.c * sizeof(T);
+    const uint32_t img_bytes = (uint32_t)p.hp * p.wp * p.g.c * sizeof(T);
+    const int per = (entries + NT - 1) / NT, e0 = threadIdx.x * per, e1 = min(e0 + per, entries);
+    if (e0 < e1) {
+        const int m = k0_pixels + e0, pn = m / sp_out, sp = m - pn * sp_out;
+        int py = sp / ow, px = sp - py * ow;
+        uint32_t off = pn * img_bytes + py * row_bytes + px * col_bytes;
+        for (int e = e0; e < e1; ++e) {
+            tab[e] = off;
+            off += col_bytes;
+            if (++px == ow) {
+                px = 0;
+                off += row_bytes - ow * col_bytes;
+                if (++py == oh) {
+                    py = 0;
+                    off += img_bytes - oh * row_bytes;
+                }
+            }
+        }
+    }
+    for (int e = entries + threadIdx.x; e < entries + spare; e += NT) tab[e] = 0;
+    __syncthreads();
+}
+
+template <class P, int BM, int BN, bool IN_PLACE, bool TABLE>
 __global__ __launch_bounds__(NT) void conv_wgrad_kernel(FastConv p)
 {
     using TS = typename P::template Shape<BM, BN>;
@@ -928,8 +995,11 @@ __global__ __launch_bounds__(NT) void conv_wgrad_kernel(FastConv p)
 
     // the last part may be shorter; pixels past n*oh*ow (last k-tile) read zeros on both sides
     const int kt0 = split * p.ktiles_per_split;
-    WgradWalk<P, BM, BN, IN_PLACE> walk(p, kt0 * BK, m0, n0, wave, lane);
-    P::template run<BM, BN, 3, IN_PLACE, false>(walk, min(p.ktiles_per_split, p.ktiles - kt0), smem, acc);
+    const int n_ktiles = min(p.ktiles_per_split, p.ktiles - kt0);
+    char* table = smem + P::lds_bytes(BM, BN, 3);  // TABLE: behind the pipeline's stages
+    if (TABLE) wgrad_fill_table<typename P::Elem>(p, kt0 * BK, n_ktiles * BK, BK, table);
+    WgradWalk<P, BM, BN, IN_PLACE, TABLE> walk(p, kt0 * BK, m0, n0, wave, lane, table);
+    P::template run<BM, BN, 3, IN_PLACE, false>(walk, n_ktiles, smem, acc);
 
     AccT* ws = static_cast<AccT*>(p.ws) + (int64_t)split * p.g.k * ncols;
 #pragma unroll
@@ -1496,23 +1566,33 @@ hipError_t launch_fwd(const FastConv& p, dmath_dtype_t in, int tile_m, int tile_
     return hipErrorInvalidValue;
 }
 
-template <class P, int BM, int BN, bool IN_PLACE>
+template <class P, int BM, int BN, bool IN_PLACE, bool TABLE>
 hipError_t launch_wgrad_kernel(const FastConv& p, int tiles, hipStream_t st)
 {
-    constexpr int lds = P::lds_bytes(BM, BN, 3);
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = set_lds(conv_wgrad_kernel<P, BM, BN, IN_PLACE>, lds);
+    // TABLE: one offset per pixel of a part's k-range and of one k-tile more, behind the stages
+    const int lds = P::lds_bytes(BM, BN, 3) + (TABLE ? (p.ktiles_per_split + 1) * P::BK * 4 : 0);
+    static int configured = 0;
+    if (configured < lds) {
+        hipError_t e = set_lds(conv_wgrad_kernel<P, BM, BN, IN_PLACE, TABLE>, lds);
         if (e != hipSuccess) return e;
-        configured = true;
+        configured = lds;
     }
-    conv_wgrad_kernel<P, BM, BN, IN_PLACE><<<tiles, NT, lds, st>>>(p);
+    conv_wgrad_kernel<P, BM, BN, IN_PLACE, TABLE><<<tiles, NT, lds, st>>>(p);
     return hipGetLastError();
 }
+constexpr int kLdsPerCu = 160 * 1024;
 template <class P, int BM, int BN> hipError_t launch_wgrad_shape(const FastConv& p, int tiles, hipStream_t st)
 {
-    if (p.y_src) return launch_wgrad_kernel<P, BM, BN, true>(p, tiles, st);
-    return launch_wgrad_kernel<P, BM, BN, false>(p, tiles, st);
+    // the pixel-offset table where the pipeline has few issue slots to spare (16x16x32 fragments)
+    // and the table fits beside its stages
+    if constexpr (std::is_same<P, PipeF16QF>::value) {
+        if (P::lds_bytes(BM, BN, 3) + (int64_t)(p.ktiles_per_split + 1) * P::BK * 4 <= kLdsPerCu) {
+            if (p.y_src) return launch_wgrad_kernel<P, BM, BN, true, true>(p, tiles, st);
+            return launch_wgrad_kernel<P, BM, BN, false, true>(p, tiles, st);
+        }
+    }
+    if (p.y_src) return launch_wgrad_kernel<P, BM, BN, true, false>(p, tiles, st);
+    return launch_wgrad_kernel<P, BM, BN, false, false>(p, tiles, st);
 }
 
 hipError_t launch_wgrad(const FastConv& p, dmath_dtype_t in, int bm, int bn, int tiles, hipStream_t st)

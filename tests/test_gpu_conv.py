@@ -457,3 +457,22 @@ def test_specialised_conv_ragged_last_row_tile(ctx, oracle, g, dt, out):
             assert rel_fro(got, ref) <= TOL[dm.F16], mode
         else:
             assert np.array_equal(got.astype(np.float64), ref), mode
+
+
+@pytest.mark.parametrize("y_grid", [(1, 1), (2, 1)])
+def test_fp16_weight_gradient_with_a_k_range_too_long_for_the_offset_table(oracle, monkeypatch, y_grid):
+    """The fp16 weight gradient on 256x128 tiles keeps the pixel offsets of a part's k-range in an
+    LDS table beside the pipeline's stages when they fit (up to 63 k-tiles per part); unsplit, the
+    4608 pixels of this layer are 72 k-tiles, so the kernel steps its pixel counters instead.
+    With dY read in place (one block) and through its channels-last copy (two blocks): bit for bit
+    on small-integer data."""
+    monkeypatch.setenv("DMATH_CONV_SPLIT", "1")
+    g = dict(n=8, c=128, h=24, w=24, k=256, r=3, s=3, pad_h=1, pad_w=1)
+    c = make_context(1.0)
+    try:
+        grids = {"X": (1, 1), "F": (1, 1), "Y": y_grid}
+        res = three_modes(c, oracle, g, dm.F16, dm.F32, 1.0, 1.0, grids, ints=True, policy=0)
+        got, ref = res["bwd_filter"]
+        assert np.array_equal(got.astype(np.float64), ref)
+    finally:
+        c.close()
