@@ -137,7 +137,9 @@ __global__ __launch_bounds__(NT) void gemm_f16_kernel(GemmTables t, float alpha,
     NoProbe probe;
 #endif
     if constexpr (MF == 16)
-        run16<BM, BN, STAGES, AKC, BKC>(walk, n_ktiles, smem, acc, probe);
+        // tiles with at most 32 accumulators keep them in fixed registers, out of the compiler's
+        // reach (no copies between differently scheduled iterations, hence nothing to drain for)
+        run16<BM, BN, STAGES, AKC, BKC, MT * NTL <= 32>(walk, n_ktiles, smem, acc, probe);
     else
         run<BM, BN, STAGES, AKC, BKC>(walk, n_ktiles, smem, acc, probe);
 #ifdef DMATH_CYCLE_PROBE
