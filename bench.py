@@ -22,7 +22,7 @@ PEAK_TFLOPS = {"f16": 2516.6, "f32": 157.3, "f64": 78.6}   # dense MFMA peaks of
 # two rocprofv3 --pmc runs of this program, scaled by a 1 GiB copy of known size; the runs, their
 # command lines and the commit they were made at are in profiles/gemm_f32_cfg2_hbm_traffic.txt.  A
 # counter cannot be read from inside this program, so the figure is carried here, not re-measured.
-MEASURED_TRAFFIC_BYTES = 585485435
+MEASURED_TRAFFIC_BYTES = 585415583
 
 
 def cpu_model():
