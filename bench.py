@@ -255,7 +255,18 @@ def main():
             ms, _ = time_calls([step5], 50, 3, stats=st)
             calls[f"cfg5.{name}"] = entry(ms, 3 * fl5, "f16", st)
         ctx.set_relayout_reuse(False)
-        for m in d5.values():
+        # the three calls again with fp16 results (half the bytes stored by each epilogue), as for
+        # configuration 3; inputs, kernels and re-layouts are the same
+        h5 = {"Y": ctx.matrix(d5["Y"].rows, d5["Y"].cols, (1, 1), dm.F16),
+              "dF": ctx.matrix(d5["dF"].rows, d5["dF"].cols, (1, 1), dm.F16),
+              "dX": ctx.matrix(d5["X"].rows, d5["X"].cols, (1, 1), dm.F16)}
+        for name, f in [("fwd", lambda: dm.conv_fwd(ctx, desc, 1.0, d5["X"], d5["F"], 0.0, h5["Y"])),
+                        ("bwd_filter", lambda: dm.conv_bwd_filter(ctx, desc, 1.0, d5["X"], d5["dY"], 0.0, h5["dF"])),
+                        ("bwd_data", lambda: dm.conv_bwd_data(ctx, desc, 1.0, d5["dY"], d5["F"], 0.0, h5["dX"]))]:
+            st = {}
+            ms, _ = time_calls([f], 50, 3, stats=st)
+            calls[f"cfg5_f16out.{name}"] = entry(ms, fl5, "f16", st)
+        for m in list(d5.values()) + list(h5.values()):
             m.destroy()
         # the same layer in fp32 (fp32 MFMA pipeline), per call, copies rewritten every call
         d5 = {k: ctx.from_host(v.astype(np.float32)) for k, v in w5.mats.items()}
