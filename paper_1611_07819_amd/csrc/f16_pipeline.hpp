@@ -465,7 +465,7 @@ __device__ __forceinline__ void run16(Walk& walk, int n_ktiles, char* smem,
     constexpr bool kAlwaysFull = MT * NTL * 4 >= 224;
     static_assert(!FIXED || MT * NTL <= 32, "fixed accumulators: a0 .. a127");
     if constexpr (FIXED) {
-        acc_f64_begin();
+        acc_fixed_begin();
         acc_fixed_marker();
 #pragma unroll
         for (int idx = 0; idx < MT * NTL; ++idx) acc_f16_zero(idx);

@@ -133,7 +133,7 @@ __device__ __forceinline__ void run(Walk& walk, int n_ktiles, char* smem,
     const int wm = wave / WVN, wn = wave % WVN, h = lane >> 4, l32 = lane & 15;
 
     static_assert(MT * NTL * 8 <= 128, "accumulators in a0 .. a127");
-    acc_f64_begin();
+    acc_fixed_begin();
 #pragma unroll
     for (int idx = 0; idx < MT * NTL; ++idx) acc_f64_zero(idx);
 

@@ -76,7 +76,7 @@ __device__ __forceinline__ v4d mfma_f64_16x16x4(double a, double b, v4d c)
 // part of the 8-register accumulators in VGPRs and copied them into and out of AGPRs around the
 // instruction (128 v_accvgpr_write and 128 v_accvgpr_read per k-tile of a 128x128 tile), and every
 // copy out waits for the 64-cycle instruction to finish: a third of the matrix cores' time.
-//   acc_f64_begin()    once, before anything else: tells the compiler that a0 .. a127 are taken
+//   acc_fixed_begin()  once, before anything else: tells the compiler that a0 .. a127 are taken
 //                      (so that the kernel is given them and nothing of its own is kept there)
 //   acc_f64_zero(idx)  accumulator idx = 0
 //   mfma_f64_fixed(idx, a, b)   accumulator idx += A(16x4) * B(4x16); idx must be a constant after
@@ -85,7 +85,7 @@ __device__ __forceinline__ v4d mfma_f64_16x16x4(double a, double b, v4d c)
 //                      (mfma_drain_f64: the instruction takes 64 cycles, nothing interlocks the read)
 // check_isa.py verifies on the compiler's output that nothing else touches these registers.
 #define DM_A8(n) "a" #n "0", "a" #n "1", "a" #n "2", "a" #n "3", "a" #n "4", "a" #n "5", "a" #n "6", "a" #n "7", "a" #n "8", "a" #n "9"
-__device__ __forceinline__ void acc_f64_begin()
+__device__ __forceinline__ void acc_fixed_begin()
 {
     asm volatile("" ::: "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", DM_A8(1), DM_A8(2), DM_A8(3),
                  DM_A8(4), DM_A8(5), DM_A8(6), DM_A8(7), DM_A8(8), DM_A8(9), DM_A8(10), DM_A8(11), "a120", "a121",
@@ -169,7 +169,7 @@ __device__ __forceinline__ v4d acc_f64_read(int idx)
 // The same for the fp16 16x16x32 instruction where the compiler cannot be kept from renaming tied
 // accumulators (the convolution's weight gradient: its walk holds many per-lane values, and the
 // copies between renamed accumulators landed right behind the matrix instructions that write
-// them): accumulator idx < 32 lives in a[4*idx .. 4*idx+3].  acc_f64_begin() reserves a0 .. a127
+// them): accumulator idx < 32 lives in a[4*idx .. 4*idx+3].  acc_fixed_begin() reserves a0 .. a127
 // for these as well; acc_fixed_marker() leaves a comment in the assembly by which check_isa.py
 // knows that in this kernel nothing but the three statements below may name an accumulation
 // register.

@@ -101,7 +101,7 @@ __global__ __launch_bounds__(256) void peak_f16_wide(float* out, int iters)
 // around the instructions and the probe read 60 TFLOP/s where the GEMM kernel now runs at 67.
 __global__ __launch_bounds__(256) void peak_f64(float* out, int iters)
 {
-    acc_f64_begin();
+    acc_fixed_begin();
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc_f64_zero(i);
     double a[4], b[4];
